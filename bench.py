@@ -1,0 +1,169 @@
+#!/usr/bin/env python3
+"""Decode-attention benchmark on one MI355X.
+
+A step is one pass of the whole hot path for one layer's batch: kv_append of the
+new token, then decode (split pass + merge), through the C ABI, with every input
+already resident in HBM.  The workload is the 13B-shaped MHA layer (batch 16,
+40 heads of 128, 4096 cached positions, fp16).  Steps rotate over several distinct
+layer caches so that no step starts with its KV in the last-level cache.
+
+Prints ONE JSON line: whole-job KV GB/s (algorithmic K+V bytes / wall time of the
+timed steps), the roofline of the split-pass kernel measured live with HIP events,
+and the CPU oracle timed on the host cores as a baseline.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--workload", default="mha13b_4k")
+    ap.add_argument("--layers-resident", type=int, default=8,
+                    help="distinct layer caches the steps rotate over")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def cpu_baseline(case, kv_bytes_step, positions_step):
+    """The C oracle as it stands, on the host cores, on a bounded sample of (b, h) pairs."""
+    import numpy as np
+    from oracle import c_oracle
+    cores = min(len(os.sched_getaffinity(0)), 16)
+    wl = case.wl
+    q = case.q.cpu().numpy()
+    k, v = case.k_cache.cpu().numpy(), case.v_cache.cpu().numpy()
+    sl = case.seq_lens.cpu().numpy()
+    pt = None if case.page_table is None else case.page_table.cpu().numpy()
+    pairs = wl.batch * wl.num_q_heads
+    # calibrate on a thin sample, then size the timed sample to about 15 s
+    stride = max(1, pairs // (2 * cores))
+    t = time.perf_counter()
+    n = c_oracle.decode(q, k, v, sl, case.scale, pt, pair_stride=stride, nthreads=cores)[0]
+    calib = time.perf_counter() - t
+    done = len(range(0, pairs, stride))
+    per_pair = calib / done * cores
+    want = int(min(pairs, max(cores, 15.0 / per_pair * cores)))
+    stride = max(1, pairs // want)
+    t = time.perf_counter()
+    c_oracle.decode(q, k, v, sl, case.scale, pt, pair_stride=stride, nthreads=cores)
+    dt = time.perf_counter() - t
+    done = len(range(0, pairs, stride))
+    frac = done / pairs
+    return {
+        "value": kv_bytes_step * frac / dt / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
+        "sample": "%d of %d (sequence, head) pairs (every %d-th) of the same layer, fp64 C oracle, "
+                  "%d OpenMP threads, %.1f s" % (done, pairs, stride, cores, dt),
+        "attended_tokens_per_s": positions_step * frac / dt,
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2409_04992_amd import binding as B
+    from paper_2409_04992_amd import workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    B.lib()                                   # fail loudly if the HIP library is missing
+    dev = "cuda:0"
+    wl = W.WORKLOADS[args.workload]
+    R = max(1, args.layers_resident)
+    cases = [W.make_case(wl, dev, layer=i) for i in range(R)]
+    descs = [B.kv_desc(c.k_cache, c.v_cache, c.page_table) for c in cases]
+    max_len = int(cases[0].seq_lens.max().item())
+    ws = B.alloc_workspace(wl.batch, wl.num_q_heads, wl.num_kv_heads, wl.head_dim, max_len, dev)
+    out_dtype = torch.float32 if wl.out_dtype == "f32" else torch.float16
+    out = torch.empty(wl.batch, wl.num_q_heads, wl.head_dim, dtype=out_dtype, device=dev)
+    kv_bytes = cases[0].kv_read_bytes()
+    positions = int(cases[0].seq_lens.sum().item())
+    chunk, splits = B.decode_plan(wl.batch, wl.num_q_heads, wl.num_kv_heads, wl.head_dim, max_len)
+
+    def step(i):
+        c, d = cases[i % R], descs[i % R]
+        B.kv_append(d, c.k_new, c.v_new, c.seq_lens)
+        B.decode(c.q, d, c.seq_lens, wl.num_kv_heads, c.scale, out, ws, max_len)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall / args.steps * 1e3
+    value = kv_bytes * args.steps / wall / 1e9
+
+    # Dominant kernel (the split pass) on its own, HIP events on the launch stream.
+    n_k = min(args.steps, 200)
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+          for _ in range(n_k)]
+    for i in range(n_k):
+        c, d = cases[i % R], descs[i % R]
+        ev[i][0].record()
+        B.decode_partial(c.q, d, c.seq_lens, wl.num_kv_heads, c.scale, out, ws, max_len)
+        ev[i][1].record()
+    torch.cuda.synchronize()
+    k_ms = sorted(a.elapsed_time(b) for a, b in ev)
+    k_avg_ms = sum(k_ms) / len(k_ms)
+    achieved = kv_bytes / (k_avg_ms * 1e-3) / 1e9
+
+    # Read ceiling: a plain streaming-read kernel over the same footprint.
+    sink = torch.zeros(4096, dtype=torch.int32, device=dev)
+    flat = [c.k_cache.view(-1) for c in cases]
+    rd = []
+    for i in range(3 * R):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        B.probe_read(flat[i % R], sink)
+        b.record()
+        rd.append((a, b))
+    torch.cuda.synchronize()
+    rd_ms = sorted(a.elapsed_time(b) for a, b in rd[R:])
+    ceiling = flat[0].numel() * 2 / (sum(rd_ms) / len(rd_ms) * 1e-3) / 1e9
+
+    res = {
+        "metric": "decode_attention_kv_bandwidth", "value": value, "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": wl.name, "batch": wl.batch, "num_q_heads": wl.num_q_heads,
+                   "num_kv_heads": wl.num_kv_heads, "head_dim": wl.head_dim,
+                   "seq_len": wl.seq_len, "kv_layout": "paged16" if wl.paged else "contiguous",
+                   "out_dtype": wl.out_dtype, "layers_resident": R,
+                   "step": "kv_append + decode (split pass + merge), one layer",
+                   "chunk_tokens": chunk, "num_splits": splits,
+                   "kv_bytes_per_step": kv_bytes},
+        "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBPS,
+        "attended_tokens_per_s": positions * args.steps / wall,
+        "attended_head_tokens_per_s": positions * wl.num_q_heads * args.steps / wall,
+        "read_ceiling_GBps": ceiling,
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                     "kernel": "decode split pass", "kernel_ms_avg": k_avg_ms,
+                     "kernel_ms_min": k_ms[0], "launches_timed": n_k,
+                     "algorithmic_bytes_per_launch": kv_bytes},
+    }
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(cases[0], kv_bytes, positions)
+    print(json.dumps(res), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,169 @@
+/*
+ * instattn -- decode-phase attention over a long fp16 KV cache, for one MI355X (gfx950).
+ *
+ * C ABI of the shared library built from paper_2409_04992_amd/csrc.  The operation
+ * is the one the paper moves next to the stored KV cache: per sequence and head,
+ * one new query row attends over all cached keys and values
+ * (softmax(q K^T * scale) V, Sec. II-A; matrix-vector form of the decode phase,
+ * Sec. II-B), after the new token's k and v have been stored behind the cached
+ * ones (Sec. IV-C "Batch Writing Requests", Sec. IV-D "GPU-CSD coordination": the
+ * device receives q, k, v, keeps k, v, returns the output row).
+ *
+ * General rules of every entry point
+ *   - Pointers marked "device" are HIP device pointers owned by the caller; the
+ *     library allocates no device memory, frees nothing, and keeps no pointer
+ *     after the call returns.  Pointers marked "host" are ordinary host memory.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream) and the call returns without synchronising.
+ *   - The return value is an instattn_status.  Arguments are checked on the host
+ *     before anything is launched; a rejected call launches nothing.
+ *   - Lengths live on the device and cannot be checked by the host, so kernels
+ *     clamp them: L_b is read as min(max(seq_lens[b], 0), capacity, max_seq_len).
+ *   - fp16 is IEEE binary16; all accumulation is fp32.
+ *   - Query head h reads KV head h / (num_q_heads / num_kv_heads).
+ */
+#ifndef INSTATTN_H
+#define INSTATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    INSTATTN_OK = 0,
+    INSTATTN_ERR_INVALID_ARG = 1, /* NULL pointer, non-positive size, bad stride/alignment, bad enum */
+    INSTATTN_ERR_UNSUPPORTED = 2, /* valid request outside what the kernels cover (see decode) */
+    INSTATTN_ERR_WORKSPACE = 3,   /* workspace NULL, misaligned or smaller than decode_workspace_size */
+    INSTATTN_ERR_RUNTIME = 4      /* a HIP launch failed */
+} instattn_status;
+
+typedef enum { INSTATTN_KV_CONTIGUOUS = 0, INSTATTN_KV_PAGED = 1 } instattn_kv_layout;
+typedef enum { INSTATTN_F16 = 0, INSTATTN_F32 = 1 } instattn_dtype;
+
+/*
+ * Where the cached keys and values live.  k and v have the same geometry.
+ * Strides are in fp16 elements; the head dimension is unit-stride; every stride
+ * must be a multiple of 8 elements and k, v 16-byte aligned (rows are moved with
+ * 128-bit accesses).
+ *
+ *   contiguous: element (b, hk, t, d) at  b*stride_b    + hk*stride_h + t*stride_t + d
+ *               capacity = rows available per (b, hk); page_table = NULL.
+ *   paged:      position t of sequence b is row t % page_size of pool page
+ *               p = page_table[b*max_pages_per_seq + t / page_size]; element at
+ *               p*stride_b + hk*stride_h + (t % page_size)*stride_t + d.
+ *               page_size is a power of two >= 16 (the paper's 16-token, 4 KB group of
+ *               Sec. IV-C "Token-Indexed Mapping" is page_size 16 with head_dim 128);
+ *               capacity = page_size*max_pages_per_seq.  Entries behind the last
+ *               used page are never read.  Pool ids must lie in [0, num_pages).
+ */
+typedef struct {
+    void* k;                   /* device, fp16 */
+    void* v;                   /* device, fp16 */
+    int32_t layout;            /* instattn_kv_layout */
+    int32_t page_size;         /* paged only */
+    int64_t stride_b;          /* contiguous: per sequence; paged: per pool page */
+    int64_t stride_h;          /* per KV head */
+    int64_t stride_t;          /* per position (row) */
+    int32_t capacity;          /* max positions per sequence */
+    int32_t max_pages_per_seq; /* paged only: row length of page_table */
+    int32_t num_pages;         /* paged only: pool size */
+    int32_t reserved;          /* must be 0 */
+    const int32_t* page_table; /* device [batch][max_pages_per_seq]; NULL if contiguous */
+} instattn_kv_desc;
+
+/* Library version: major*10000 + minor*100 + patch. */
+int instattn_version(void);
+
+/* Static, NUL-terminated description of a status value (host memory, never freed). */
+const char* instattn_status_string(int status);
+
+/*
+ * Store the new token's key and value (Sec. IV-C "Batch Writing Requests").
+ * For every sequence b and KV head hk, copies the head_dim fp16 values
+ * k_new[b][hk][:] and v_new[b][hk][:] bit for bit into position seq_lens[b] - 1
+ * of the cache.  seq_lens[b] is the length INCLUDING the token being stored.  A
+ * length outside [1, capacity] stores nothing for that sequence.
+ *   k_new, v_new : device, [batch][num_kv_heads][head_dim] fp16, dense, 16-byte aligned
+ *   seq_lens     : device, [batch] int32, not modified
+ * head_dim must be a multiple of 8.  One kernel launch.
+ */
+int instattn_kv_append(const instattn_kv_desc* kv, const void* k_new, const void* v_new,
+                       const int32_t* seq_lens, int batch, int num_kv_heads, int head_dim,
+                       void* stream);
+
+/*
+ * How decode cuts the sequence axis (host arithmetic only; no device access).
+ * Work is split into units of `chunk_tokens` consecutive positions so that a
+ * single long sequence still fills the chip; unit i of sequence b covers
+ * positions [i*chunk, (i+1)*chunk) cut off at L_b, and num_splits =
+ * ceil(max_seq_len / chunk).  The plan depends only on the arguments given here
+ * (and the INSTATTN_CHUNK environment variable, which forces chunk_tokens for
+ * experiments).  Either output pointer may be NULL.  host pointers.
+ */
+int instattn_decode_plan(int batch, int num_q_heads, int num_kv_heads, int head_dim,
+                         int max_seq_len, int* chunk_tokens, int* num_splits);
+
+/* Bytes of device workspace decode needs for these arguments (0 if they are invalid). */
+size_t instattn_decode_workspace_size(int batch, int num_q_heads, int num_kv_heads,
+                                      int head_dim, int max_seq_len);
+
+/*
+ * Decode attention (Sec. II-A, II-B): for every sequence b and query head h
+ *     s_t  = scale * sum_d q[b][h][d] * K[b][hk][t][d]        t = 0 .. L_b-1
+ *     out[b][h][:] = sum_t softmax(s)_t * V[b][hk][t][:]
+ *     lse[b][h]    = log sum_t exp(s_t)                         (natural log)
+ * over exactly the first L_b = seq_lens[b] positions; rows at or behind L_b are
+ * never read.  L_b <= 0 gives a zero output row and lse = -inf.
+ *   q         : device, [batch][num_q_heads][head_dim] fp16, dense, 16-byte aligned
+ *   out       : device, [batch][num_q_heads][head_dim], fp16 (round to nearest even,
+ *               once, at the end) or fp32 according to out_dtype
+ *   lse       : device, [batch][num_q_heads] fp32, or NULL
+ *   workspace : device, >= instattn_decode_workspace_size(...) bytes, 256-byte aligned;
+ *               contents on entry are ignored, contents on return are unspecified
+ *   max_seq_len : host-known upper bound of every L_b (<= capacity); it fixes the
+ *               split plan, so no device value is read back
+ * Supported: head_dim 64 or 128; num_q_heads a multiple of num_kv_heads with a
+ * ratio of 1 (vector-ALU path) or 2..16 (MFMA group path); both layouts; both
+ * output types.  Two kernel launches (partial pass, merge); the merge is skipped
+ * when the plan has a single split.
+ */
+int instattn_decode(const void* q, const instattn_kv_desc* kv, const int32_t* seq_lens,
+                    int batch, int num_q_heads, int num_kv_heads, int head_dim, float scale,
+                    void* out, int out_dtype, float* lse, void* workspace,
+                    size_t workspace_bytes, int max_seq_len, void* stream);
+
+/*
+ * The two halves of instattn_decode, callable on their own (same arguments, same
+ * checks) so that each can be timed or composed separately.  decode_partial
+ * runs the split pass: per unit an online-softmax pass over its positions,
+ * leaving a normalised partial output row and its log-sum-exp in the workspace
+ * (when the plan has one split it writes out/lse directly).  decode_merge
+ * combines the units of each (b, h) by their log-sum-exp weights into out/lse;
+ * with a single split it launches nothing.
+ */
+int instattn_decode_partial(const void* q, const instattn_kv_desc* kv, const int32_t* seq_lens,
+                            int batch, int num_q_heads, int num_kv_heads, int head_dim,
+                            float scale, void* out, int out_dtype, float* lse, void* workspace,
+                            size_t workspace_bytes, int max_seq_len, void* stream);
+int instattn_decode_merge(const int32_t* seq_lens, int batch, int num_q_heads, int num_kv_heads,
+                          int head_dim, int capacity, void* out, int out_dtype, float* lse,
+                          const void* workspace, size_t workspace_bytes, int max_seq_len,
+                          void* stream);
+
+/*
+ * Measurement aids, not part of the attention path.  probe_read streams `bytes`
+ * (a multiple of 16) from src with 128-bit loads and folds them into 4 bytes per
+ * workgroup written to sink (device, >= 16 KiB): the read ceiling a streaming
+ * kernel can reach.  probe_copy copies `bytes` from src to dst (device, disjoint):
+ * a kernel of known traffic for scaling hardware counters.
+ */
+int instattn_probe_read(const void* src, size_t bytes, void* sink, void* stream);
+int instattn_probe_copy(const void* src, void* dst, size_t bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* INSTATTN_H */

@@ -1,0 +1,199 @@
+"""ctypes binding of libinstattn.so: argument marshalling only.
+
+Same entry points as include/instattn.h, taking torch tensors (device memory and
+streams come from PyTorch; every step of the path runs in the library's HIP
+kernels).  There is no fallback: if the library has not been built, loading
+raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libinstattn.so")
+
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_RUNTIME = range(5)
+KV_CONTIGUOUS, KV_PAGED = 0, 1
+F16, F32 = 0, 1
+
+
+class KvDesc(ctypes.Structure):
+    """Mirror of instattn_kv_desc."""
+    _fields_ = [
+        ("k", ctypes.c_void_p), ("v", ctypes.c_void_p),
+        ("layout", ctypes.c_int32), ("page_size", ctypes.c_int32),
+        ("stride_b", ctypes.c_int64), ("stride_h", ctypes.c_int64), ("stride_t", ctypes.c_int64),
+        ("capacity", ctypes.c_int32), ("max_pages_per_seq", ctypes.c_int32),
+        ("num_pages", ctypes.c_int32), ("reserved", ctypes.c_int32),
+        ("page_table", ctypes.c_void_p),
+    ]
+
+
+class InstattnError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s: %s (status %d)" % (where, status_string(status), status))
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded library.  Raises if it has not been built (no fallback path)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(
+                "libinstattn.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'`")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i, sz, f = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t, ctypes.c_float
+        L.instattn_version.restype = i
+        L.instattn_version.argtypes = []
+        L.instattn_status_string.restype = ctypes.c_char_p
+        L.instattn_status_string.argtypes = [i]
+        L.instattn_kv_append.restype = i
+        L.instattn_kv_append.argtypes = [ctypes.POINTER(KvDesc), vp, vp, vp, i, i, i, vp]
+        L.instattn_decode_plan.restype = i
+        L.instattn_decode_plan.argtypes = [i, i, i, i, i, ctypes.POINTER(i), ctypes.POINTER(i)]
+        L.instattn_decode_workspace_size.restype = sz
+        L.instattn_decode_workspace_size.argtypes = [i, i, i, i, i]
+        decode_args = [vp, ctypes.POINTER(KvDesc), vp, i, i, i, i, f, vp, i, vp, vp, sz, i, vp]
+        L.instattn_decode.restype = i
+        L.instattn_decode.argtypes = decode_args
+        L.instattn_decode_partial.restype = i
+        L.instattn_decode_partial.argtypes = decode_args
+        L.instattn_decode_merge.restype = i
+        L.instattn_decode_merge.argtypes = [vp, i, i, i, i, i, vp, i, vp, vp, sz, i, vp]
+        L.instattn_probe_read.restype = i
+        L.instattn_probe_read.argtypes = [vp, sz, vp, vp]
+        L.instattn_probe_copy.restype = i
+        L.instattn_probe_copy.argtypes = [vp, vp, sz, vp]
+        _lib = L
+    return _lib
+
+
+def version() -> int:
+    return lib().instattn_version()
+
+
+def status_string(status: int) -> str:
+    return lib().instattn_status_string(int(status)).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != OK:
+        raise InstattnError(status, where)
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _p(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def kv_desc(k_cache: torch.Tensor, v_cache: torch.Tensor,
+            page_table: Optional[torch.Tensor] = None) -> KvDesc:
+    """Descriptor for [B, Hkv, capacity, D] caches or [num_pages, Hkv, page_size, D] pools."""
+    assert k_cache.dtype == torch.float16 and v_cache.dtype == torch.float16
+    assert k_cache.shape == v_cache.shape and k_cache.stride() == v_cache.stride()
+    assert k_cache.stride(3) == 1
+    d = KvDesc()
+    d.k, d.v = k_cache.data_ptr(), v_cache.data_ptr()
+    d.stride_b, d.stride_h, d.stride_t = k_cache.stride(0), k_cache.stride(1), k_cache.stride(2)
+    d.reserved = 0
+    if page_table is None:
+        d.layout = KV_CONTIGUOUS
+        d.capacity = k_cache.shape[2]
+        d.page_table = None
+    else:
+        assert page_table.dtype == torch.int32 and page_table.is_contiguous()
+        d.layout = KV_PAGED
+        d.page_size = k_cache.shape[2]
+        d.max_pages_per_seq = page_table.shape[1]
+        d.num_pages = k_cache.shape[0]
+        d.capacity = d.page_size * d.max_pages_per_seq
+        d.page_table = page_table.data_ptr()
+    return d
+
+
+def kv_append(desc: KvDesc, k_new: torch.Tensor, v_new: torch.Tensor, seq_lens: torch.Tensor,
+              stream=None) -> None:
+    B, Hkv, D = k_new.shape
+    assert k_new.is_contiguous() and v_new.is_contiguous() and seq_lens.dtype == torch.int32
+    _check(lib().instattn_kv_append(ctypes.byref(desc), _p(k_new), _p(v_new), _p(seq_lens),
+                                    B, Hkv, D, _stream(stream)), "instattn_kv_append")
+
+
+def decode_plan(batch: int, num_q_heads: int, num_kv_heads: int, head_dim: int,
+                max_seq_len: int) -> Tuple[int, int]:
+    chunk, splits = ctypes.c_int(0), ctypes.c_int(0)
+    _check(lib().instattn_decode_plan(batch, num_q_heads, num_kv_heads, head_dim, max_seq_len,
+                                      ctypes.byref(chunk), ctypes.byref(splits)),
+           "instattn_decode_plan")
+    return chunk.value, splits.value
+
+
+def decode_workspace_size(batch: int, num_q_heads: int, num_kv_heads: int, head_dim: int,
+                          max_seq_len: int) -> int:
+    return lib().instattn_decode_workspace_size(batch, num_q_heads, num_kv_heads, head_dim,
+                                                max_seq_len)
+
+
+def _decode_args(q, desc, seq_lens, num_kv_heads, scale, out, lse, workspace, max_seq_len, stream):
+    B, Hq, D = q.shape
+    assert q.dtype == torch.float16 and q.is_contiguous() and out.is_contiguous()
+    assert seq_lens.dtype == torch.int32 and out.shape == q.shape
+    assert out.dtype in (torch.float16, torch.float32)
+    assert lse is None or (lse.dtype == torch.float32 and lse.is_contiguous())
+    return (_p(q), ctypes.byref(desc), _p(seq_lens), B, Hq, num_kv_heads, D, float(scale),
+            _p(out), F16 if out.dtype == torch.float16 else F32, _p(lse), _p(workspace),
+            workspace.numel() * workspace.element_size(), int(max_seq_len), _stream(stream))
+
+
+def decode(q, desc: KvDesc, seq_lens, num_kv_heads: int, scale: float, out, workspace,
+           max_seq_len: int, lse=None, stream=None) -> None:
+    _check(lib().instattn_decode(*_decode_args(q, desc, seq_lens, num_kv_heads, scale, out, lse,
+                                               workspace, max_seq_len, stream)), "instattn_decode")
+
+
+def decode_partial(q, desc: KvDesc, seq_lens, num_kv_heads: int, scale: float, out, workspace,
+                   max_seq_len: int, lse=None, stream=None) -> None:
+    _check(lib().instattn_decode_partial(*_decode_args(q, desc, seq_lens, num_kv_heads, scale, out,
+                                                       lse, workspace, max_seq_len, stream)),
+           "instattn_decode_partial")
+
+
+def decode_merge(seq_lens, num_q_heads: int, num_kv_heads: int, capacity: int, out, workspace,
+                 max_seq_len: int, lse=None, stream=None) -> None:
+    B, Hq, D = out.shape
+    _check(lib().instattn_decode_merge(
+        _p(seq_lens), B, num_q_heads, num_kv_heads, D, int(capacity), _p(out),
+        F16 if out.dtype == torch.float16 else F32, _p(lse), _p(workspace),
+        workspace.numel() * workspace.element_size(), int(max_seq_len), _stream(stream)),
+        "instattn_decode_merge")
+
+
+def alloc_workspace(batch: int, num_q_heads: int, num_kv_heads: int, head_dim: int,
+                    max_seq_len: int, device) -> torch.Tensor:
+    n = decode_workspace_size(batch, num_q_heads, num_kv_heads, head_dim, max_seq_len)
+    if n == 0:
+        raise InstattnError(ERR_INVALID_ARG, "instattn_decode_workspace_size")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def probe_read(src: torch.Tensor, sink: torch.Tensor, stream=None) -> None:
+    _check(lib().instattn_probe_read(_p(src), src.numel() * src.element_size(), _p(sink),
+                                     _stream(stream)), "instattn_probe_read")
+
+
+def probe_copy(src: torch.Tensor, dst: torch.Tensor, stream=None) -> None:
+    _check(lib().instattn_probe_copy(_p(src), _p(dst), src.numel() * src.element_size(),
+                                     _stream(stream)), "instattn_probe_copy")

@@ -1,0 +1,276 @@
+// Host side of the C ABI: argument checks, the split plan, kernel launches.
+// Nothing here touches device memory or synchronises.
+#include "../../include/instattn.h"
+
+#include <math.h>
+#include <stdlib.h>
+
+#include "common.h"
+
+using namespace instattn;
+
+namespace {
+
+constexpr int kVersion = 100;          // 0.1.0
+constexpr int kChunkQuantum = 128;     // every kernel's block tile divides this
+constexpr int kMinChunk = 256;
+constexpr int kTargetUnits = 4096;     // work units wanted per launch (256 CUs, several blocks each)
+
+bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+bool pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
+int ilog2(int x) { int s = 0; while ((1 << s) < x) ++s; return s; }
+
+struct Plan {
+    int chunk;
+    int num_splits;
+};
+
+// Sequence split: units of `chunk` positions, enough of them to fill the chip
+// from host-known sizes alone.
+Plan make_plan(int batch, int num_q_heads, int num_kv_heads, int max_seq_len)
+{
+    const int group = num_q_heads / num_kv_heads;
+    // the MFMA path walks a KV head once for its whole query group
+    const long streams = (long)batch * (group == 1 ? num_q_heads : num_kv_heads);
+    long chunk = ((long)max_seq_len * streams + kTargetUnits - 1) / kTargetUnits;
+    if (chunk < kMinChunk) chunk = kMinChunk;
+    const char* forced = getenv("INSTATTN_CHUNK");
+    if (forced && atoi(forced) > 0) chunk = atoi(forced);
+    chunk = (chunk + kChunkQuantum - 1) / kChunkQuantum * kChunkQuantum;
+    const long whole = ((long)max_seq_len + kChunkQuantum - 1) / kChunkQuantum * kChunkQuantum;
+    if (chunk > whole) chunk = whole;
+    Plan p;
+    p.chunk = (int)chunk;
+    p.num_splits = (int)((max_seq_len + chunk - 1) / chunk);
+    return p;
+}
+
+int check_shape(int batch, int num_q_heads, int num_kv_heads, int head_dim, int max_seq_len)
+{
+    if (batch <= 0 || num_q_heads <= 0 || num_kv_heads <= 0 || head_dim <= 0 || max_seq_len <= 0)
+        return INSTATTN_ERR_INVALID_ARG;
+    if (num_q_heads % num_kv_heads != 0) return INSTATTN_ERR_INVALID_ARG;
+    if (head_dim != 64 && head_dim != 128) return INSTATTN_ERR_UNSUPPORTED;
+    if (num_q_heads / num_kv_heads > 16) return INSTATTN_ERR_UNSUPPORTED;
+    if (batch > 65535 || num_q_heads > 65535) return INSTATTN_ERR_UNSUPPORTED;  // grid y, z
+    return INSTATTN_OK;
+}
+
+int check_kv(const instattn_kv_desc* kv, int head_dim)
+{
+    if (!kv || !kv->k || !kv->v) return INSTATTN_ERR_INVALID_ARG;
+    if (!aligned16(kv->k) || !aligned16(kv->v)) return INSTATTN_ERR_INVALID_ARG;
+    if (kv->reserved != 0) return INSTATTN_ERR_INVALID_ARG;
+    if (kv->stride_b <= 0 || kv->stride_h <= 0 || kv->stride_t < head_dim)
+        return INSTATTN_ERR_INVALID_ARG;
+    if (kv->stride_b % 8 || kv->stride_h % 8 || kv->stride_t % 8) return INSTATTN_ERR_INVALID_ARG;
+    if (kv->capacity <= 0) return INSTATTN_ERR_INVALID_ARG;
+    if (kv->layout == INSTATTN_KV_CONTIGUOUS) {
+        if (kv->page_table != nullptr) return INSTATTN_ERR_INVALID_ARG;
+    } else if (kv->layout == INSTATTN_KV_PAGED) {
+        if (!kv->page_table) return INSTATTN_ERR_INVALID_ARG;
+        if (!pow2(kv->page_size) || kv->page_size < 16) return INSTATTN_ERR_INVALID_ARG;
+        if (kv->max_pages_per_seq <= 0 || kv->num_pages <= 0) return INSTATTN_ERR_INVALID_ARG;
+        if ((int64_t)kv->capacity != (int64_t)kv->page_size * kv->max_pages_per_seq)
+            return INSTATTN_ERR_INVALID_ARG;
+    } else {
+        return INSTATTN_ERR_INVALID_ARG;
+    }
+    return INSTATTN_OK;
+}
+
+KvView make_view(const instattn_kv_desc* kv)
+{
+    KvView w;
+    w.k = (const half_t*)kv->k;
+    w.v = (const half_t*)kv->v;
+    w.page_table = kv->layout == INSTATTN_KV_PAGED ? kv->page_table : nullptr;
+    w.stride_b = kv->stride_b;
+    w.stride_h = kv->stride_h;
+    w.stride_t = kv->stride_t;
+    w.capacity = kv->capacity;
+    w.page_shift = kv->layout == INSTATTN_KV_PAGED ? ilog2(kv->page_size) : 0;
+    w.page_mask = kv->layout == INSTATTN_KV_PAGED ? kv->page_size - 1 : 0;
+    w.max_pages = kv->max_pages_per_seq;
+    return w;
+}
+
+size_t workspace_bytes_for(int batch, int num_q_heads, int head_dim, const Plan& p)
+{
+    size_t units = (size_t)batch * num_q_heads * p.num_splits;
+    size_t bytes = units * (size_t)(head_dim + 1) * sizeof(float);
+    return (bytes + 255) / 256 * 256;
+}
+
+int check_out(void* out, int out_dtype, const void* workspace, size_t workspace_bytes, size_t need)
+{
+    if (!out || !aligned16(out)) return INSTATTN_ERR_INVALID_ARG;
+    if (out_dtype != INSTATTN_F16 && out_dtype != INSTATTN_F32) return INSTATTN_ERR_INVALID_ARG;
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < need)
+        return INSTATTN_ERR_WORKSPACE;
+    return INSTATTN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int instattn_version(void) { return kVersion; }
+
+const char* instattn_status_string(int status)
+{
+    switch (status) {
+        case INSTATTN_OK: return "ok";
+        case INSTATTN_ERR_INVALID_ARG: return "invalid argument";
+        case INSTATTN_ERR_UNSUPPORTED: return "unsupported configuration";
+        case INSTATTN_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case INSTATTN_ERR_RUNTIME: return "HIP launch failed";
+        default: return "unknown status";
+    }
+}
+
+int instattn_kv_append(const instattn_kv_desc* kv, const void* k_new, const void* v_new,
+                       const int32_t* seq_lens, int batch, int num_kv_heads, int head_dim,
+                       void* stream)
+{
+    if (batch <= 0 || num_kv_heads <= 0 || head_dim <= 0 || head_dim % 8) return INSTATTN_ERR_INVALID_ARG;
+    int st = check_kv(kv, head_dim);
+    if (st != INSTATTN_OK) return st;
+    if (!k_new || !v_new || !seq_lens || !aligned16(k_new) || !aligned16(v_new))
+        return INSTATTN_ERR_INVALID_ARG;
+    const KvView w = make_view(kv);
+    AppendArgs a;
+    a.k = (half_t*)kv->k;
+    a.v = (half_t*)kv->v;
+    a.page_table = w.page_table;
+    a.stride_b = w.stride_b;
+    a.stride_h = w.stride_h;
+    a.stride_t = w.stride_t;
+    a.capacity = w.capacity;
+    a.page_shift = w.page_shift;
+    a.page_mask = w.page_mask;
+    a.max_pages = w.max_pages;
+    a.k_new = (const half_t*)k_new;
+    a.v_new = (const half_t*)v_new;
+    a.seq_lens = seq_lens;
+    a.batch = batch;
+    a.num_kv_heads = num_kv_heads;
+    a.head_dim = head_dim;
+    return launch_kv_append(a, (hipStream_t)stream) == hipSuccess ? INSTATTN_OK : INSTATTN_ERR_RUNTIME;
+}
+
+int instattn_decode_plan(int batch, int num_q_heads, int num_kv_heads, int head_dim,
+                         int max_seq_len, int* chunk_tokens, int* num_splits)
+{
+    int st = check_shape(batch, num_q_heads, num_kv_heads, head_dim, max_seq_len);
+    if (st != INSTATTN_OK) return st;
+    const Plan p = make_plan(batch, num_q_heads, num_kv_heads, max_seq_len);
+    if (chunk_tokens) *chunk_tokens = p.chunk;
+    if (num_splits) *num_splits = p.num_splits;
+    return INSTATTN_OK;
+}
+
+size_t instattn_decode_workspace_size(int batch, int num_q_heads, int num_kv_heads, int head_dim,
+                                      int max_seq_len)
+{
+    if (check_shape(batch, num_q_heads, num_kv_heads, head_dim, max_seq_len) != INSTATTN_OK) return 0;
+    return workspace_bytes_for(batch, num_q_heads, head_dim,
+                               make_plan(batch, num_q_heads, num_kv_heads, max_seq_len));
+}
+
+int instattn_decode_partial(const void* q, const instattn_kv_desc* kv, const int32_t* seq_lens,
+                            int batch, int num_q_heads, int num_kv_heads, int head_dim,
+                            float scale, void* out, int out_dtype, float* lse, void* workspace,
+                            size_t workspace_bytes, int max_seq_len, void* stream)
+{
+    int st = check_shape(batch, num_q_heads, num_kv_heads, head_dim, max_seq_len);
+    if (st != INSTATTN_OK) return st;
+    st = check_kv(kv, head_dim);
+    if (st != INSTATTN_OK) return st;
+    if (!q || !aligned16(q) || !seq_lens || !isfinite(scale)) return INSTATTN_ERR_INVALID_ARG;
+    if (max_seq_len > kv->capacity) return INSTATTN_ERR_INVALID_ARG;
+    const Plan p = make_plan(batch, num_q_heads, num_kv_heads, max_seq_len);
+    st = check_out(out, out_dtype, workspace, workspace_bytes,
+                   workspace_bytes_for(batch, num_q_heads, head_dim, p));
+    if (st != INSTATTN_OK) return st;
+
+    DecodeArgs a;
+    a.q = (const half_t*)q;
+    a.kv = make_view(kv);
+    a.seq_lens = seq_lens;
+    a.num_q_heads = num_q_heads;
+    a.num_kv_heads = num_kv_heads;
+    a.chunk = p.chunk;
+    a.num_splits = p.num_splits;
+    a.max_len = max_seq_len;
+    a.scale_log2 = scale * kLog2e;
+    a.o_part = (float*)workspace;
+    a.lse_part = a.o_part + (size_t)batch * num_q_heads * p.num_splits * head_dim;
+    a.out = out;
+    a.lse = lse;
+    a.out_f32 = out_dtype == INSTATTN_F32;
+    hipError_t e = num_q_heads == num_kv_heads
+                       ? launch_decode_mha(a, batch, head_dim, (hipStream_t)stream)
+                       : launch_decode_gqa(a, batch, head_dim, (hipStream_t)stream);
+    return e == hipSuccess ? INSTATTN_OK : INSTATTN_ERR_RUNTIME;
+}
+
+int instattn_decode_merge(const int32_t* seq_lens, int batch, int num_q_heads, int num_kv_heads,
+                          int head_dim, int capacity, void* out, int out_dtype, float* lse,
+                          const void* workspace, size_t workspace_bytes, int max_seq_len,
+                          void* stream)
+{
+    int st = check_shape(batch, num_q_heads, num_kv_heads, head_dim, max_seq_len);
+    if (st != INSTATTN_OK) return st;
+    if (!seq_lens || capacity <= 0 || max_seq_len > capacity) return INSTATTN_ERR_INVALID_ARG;
+    const Plan p = make_plan(batch, num_q_heads, num_kv_heads, max_seq_len);
+    st = check_out(out, out_dtype, workspace, workspace_bytes,
+                   workspace_bytes_for(batch, num_q_heads, head_dim, p));
+    if (st != INSTATTN_OK) return st;
+    if (p.num_splits == 1) return INSTATTN_OK;   // the split pass already wrote out/lse
+
+    MergeArgs m;
+    m.seq_lens = seq_lens;
+    m.o_part = (const float*)workspace;
+    m.lse_part = m.o_part + (size_t)batch * num_q_heads * p.num_splits * head_dim;
+    m.out = out;
+    m.lse = lse;
+    m.num_q_heads = num_q_heads;
+    m.chunk = p.chunk;
+    m.num_splits = p.num_splits;
+    m.max_len = max_seq_len;
+    m.out_f32 = out_dtype == INSTATTN_F32;
+    return launch_merge(m, batch, head_dim, (hipStream_t)stream) == hipSuccess ? INSTATTN_OK
+                                                                                : INSTATTN_ERR_RUNTIME;
+}
+
+int instattn_decode(const void* q, const instattn_kv_desc* kv, const int32_t* seq_lens, int batch,
+                    int num_q_heads, int num_kv_heads, int head_dim, float scale, void* out,
+                    int out_dtype, float* lse, void* workspace, size_t workspace_bytes,
+                    int max_seq_len, void* stream)
+{
+    int st = instattn_decode_partial(q, kv, seq_lens, batch, num_q_heads, num_kv_heads, head_dim,
+                                     scale, out, out_dtype, lse, workspace, workspace_bytes,
+                                     max_seq_len, stream);
+    if (st != INSTATTN_OK) return st;
+    return instattn_decode_merge(seq_lens, batch, num_q_heads, num_kv_heads, head_dim,
+                                 kv->capacity, out, out_dtype, lse, workspace, workspace_bytes,
+                                 max_seq_len, stream);
+}
+
+int instattn_probe_read(const void* src, size_t bytes, void* sink, void* stream)
+{
+    if (!src || !sink || bytes == 0 || bytes % 16 || !aligned16(src)) return INSTATTN_ERR_INVALID_ARG;
+    return launch_probe_read(src, bytes, sink, (hipStream_t)stream) == hipSuccess ? INSTATTN_OK
+                                                                                    : INSTATTN_ERR_RUNTIME;
+}
+
+int instattn_probe_copy(const void* src, void* dst, size_t bytes, void* stream)
+{
+    if (!src || !dst || bytes == 0 || bytes % 16 || !aligned16(src) || !aligned16(dst))
+        return INSTATTN_ERR_INVALID_ARG;
+    return launch_probe_copy(src, dst, bytes, (hipStream_t)stream) == hipSuccess ? INSTATTN_OK
+                                                                                  : INSTATTN_ERR_RUNTIME;
+}
+
+}  // extern "C"

@@ -1,0 +1,140 @@
+// Shared device-side declarations of the instattn kernels (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace instattn {
+
+typedef _Float16 half_t;
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kWave = 64;
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+// Running maxima start at a large finite negative value so that a unit whose
+// positions are all masked never forms (-inf) - (-inf).
+constexpr float kNegBig = -1.0e30f;
+
+// Geometry of the cached keys/values as the kernels see it (copied from the
+// caller's descriptor after validation).
+struct KvView {
+    const half_t* k;
+    const half_t* v;
+    const int32_t* page_table;  // nullptr: contiguous
+    int64_t stride_b, stride_h, stride_t;
+    int32_t capacity;
+    int32_t page_shift;         // log2(page_size), paged only
+    int32_t page_mask;          // page_size - 1
+    int32_t max_pages;
+};
+
+// Arguments of the split pass (both the vector-ALU and the MFMA kernel).
+struct DecodeArgs {
+    const half_t* q;            // [B][Hq][D]
+    KvView kv;
+    const int32_t* seq_lens;    // [B]
+    int32_t num_q_heads, num_kv_heads;
+    int32_t chunk;              // positions per unit
+    int32_t num_splits;
+    int32_t max_len;            // min(capacity, max_seq_len)
+    float scale_log2;           // scale * log2(e)
+    float* o_part;              // [B][Hq][num_splits][D] fp32, normalised rows
+    float* lse_part;            // [B][Hq][num_splits]   fp32, log2 domain
+    void* out;                  // final rows when num_splits == 1
+    float* lse;                 // may be nullptr
+    int32_t out_f32;
+};
+
+// Arguments of the log-sum-exp merge.
+struct MergeArgs {
+    const int32_t* seq_lens;
+    const float* o_part;   // [B][Hq][num_splits][D]
+    const float* lse_part; // [B][Hq][num_splits], log2 domain
+    void* out;
+    float* lse;
+    int32_t num_q_heads, chunk, num_splits, max_len, out_f32;
+};
+
+// Arguments of the KV append.
+struct AppendArgs {
+    half_t* k;
+    half_t* v;
+    const int32_t* page_table;
+    int64_t stride_b, stride_h, stride_t;
+    int32_t capacity, page_shift, page_mask, max_pages;
+    const half_t* k_new;
+    const half_t* v_new;
+    const int32_t* seq_lens;
+    int32_t batch, num_kv_heads, head_dim;
+};
+
+// Launchers (one per kernel family); each returns hipGetLastError() of its launch.
+hipError_t launch_decode_mha(const DecodeArgs& a, int batch, int head_dim, hipStream_t stream);
+hipError_t launch_decode_gqa(const DecodeArgs& a, int batch, int head_dim, hipStream_t stream);
+hipError_t launch_merge(const MergeArgs& a, int batch, int head_dim, hipStream_t stream);
+hipError_t launch_kv_append(const AppendArgs& a, hipStream_t stream);
+hipError_t launch_probe_read(const void* src, size_t bytes, void* sink, hipStream_t stream);
+hipError_t launch_probe_copy(const void* src, void* dst, size_t bytes, hipStream_t stream);
+
+__device__ __forceinline__ int clamp_len(int L, int max_len) {
+    L = L < 0 ? 0 : L;
+    return L > max_len ? max_len : L;
+}
+
+// Element offset of row t of (sequence b, KV head hk).
+__device__ __forceinline__ int64_t row_offset(const KvView& kv, int b, int hk, int t) {
+    if (kv.page_table == nullptr)
+        return (int64_t)b * kv.stride_b + (int64_t)hk * kv.stride_h + (int64_t)t * kv.stride_t;
+    int page = kv.page_table[(int64_t)b * kv.max_pages + (t >> kv.page_shift)];
+    return (int64_t)page * kv.stride_b + (int64_t)hk * kv.stride_h +
+           (int64_t)(t & kv.page_mask) * kv.stride_t;
+}
+
+// Cross-lane exchange inside a row of 16 lanes with DPP (no LDS traffic).
+template <int Ctrl>
+__device__ __forceinline__ float dpp_f32(float x) {
+    return __builtin_bit_cast(
+        float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), Ctrl, 0xF, 0xF, true));
+}
+constexpr int kDppXor1 = 0xB1;        // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;        // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141; // lane i <-> 7-i within 8
+constexpr int kDppMirror = 0x140;     // lane i <-> 15-i within 16
+
+// Sum over groups of `Lanes` (8 or 16) adjacent lanes; every lane gets the total.
+template <int Lanes>
+__device__ __forceinline__ float group_sum(float x) {
+    x += dpp_f32<kDppXor1>(x);
+    x += dpp_f32<kDppXor2>(x);
+    x += dpp_f32<kDppHalfMirror>(x);
+    if (Lanes == 16) x += dpp_f32<kDppMirror>(x);
+    return x;
+}
+
+// fp32 dot product of 8 fp16 pairs (v_dot2_f32_f16: exact products, fp32 sums).
+// Pairs are taken with shufflevector: bit-casting a single element of a vector
+// lvalue reads element 0 with this compiler.
+__device__ __forceinline__ float dot8(half8_t a, half8_t b, float acc) {
+    acc = __builtin_amdgcn_fdot2(__builtin_shufflevector(a, a, 0, 1), __builtin_shufflevector(b, b, 0, 1), acc, false);
+    acc = __builtin_amdgcn_fdot2(__builtin_shufflevector(a, a, 2, 3), __builtin_shufflevector(b, b, 2, 3), acc, false);
+    acc = __builtin_amdgcn_fdot2(__builtin_shufflevector(a, a, 4, 5), __builtin_shufflevector(b, b, 4, 5), acc, false);
+    acc = __builtin_amdgcn_fdot2(__builtin_shufflevector(a, a, 6, 7), __builtin_shufflevector(b, b, 6, 7), acc, false);
+    return acc;
+}
+
+// Keeps the compiler from sinking the loads issued above this point down to
+// their uses: they must stay in flight across the arithmetic that follows.
+__device__ __forceinline__ void pin_order() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
+
+}  // namespace instattn

@@ -1,0 +1,152 @@
+"""C-ABI checks that need no GPU: the library loads, exports every symbol the
+header declares, and rejects bad arguments on the host before launching anything.
+Every call below is built to fail validation, so no kernel is ever launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2409_04992_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x7F0000001000          # aligned, non-NULL, never dereferenced on the host
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "instattn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(instattn_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_symbols()
+    assert {"instattn_kv_append", "instattn_decode", "instattn_decode_partial",
+            "instattn_decode_merge", "instattn_decode_plan", "instattn_decode_workspace_size",
+            "instattn_status_string", "instattn_version", "instattn_probe_read",
+            "instattn_probe_copy"} <= set(names)
+    lib = B.lib()
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_version_and_status_strings():
+    assert B.version() >= 100
+    texts = {B.status_string(s) for s in range(5)}
+    assert len(texts) == 5 and B.status_string(99) == "unknown status"
+
+
+def desc(**kw):
+    d = B.KvDesc()
+    d.k, d.v = FAKE, FAKE
+    d.layout = B.KV_CONTIGUOUS
+    d.stride_b, d.stride_h, d.stride_t = 40 * 4112 * 128, 4112 * 128, 128
+    d.capacity = 4112
+    d.reserved = 0
+    for k, v in kw.items():
+        setattr(d, k, v)
+    return d
+
+
+def paged_desc(**kw):
+    base = dict(layout=B.KV_PAGED, page_size=16, max_pages_per_seq=257, num_pages=5000,
+                capacity=16 * 257, stride_b=40 * 16 * 128, stride_h=16 * 128, stride_t=128,
+                page_table=FAKE)
+    base.update(kw)
+    return desc(**base)
+
+
+def decode_status(d, q=FAKE, seq=FAKE, batch=16, hq=40, hkv=40, dim=128, scale=0.088, out=FAKE,
+                  out_dtype=B.F16, ws=FAKE & ~255, ws_bytes=1 << 30, max_len=4097):
+    return B.lib().instattn_decode(q, ctypes.byref(d) if d is not None else None, seq, batch, hq,
+                                   hkv, dim, scale, out, out_dtype, None, ws, ws_bytes, max_len, None)
+
+
+@pytest.mark.parametrize("kw,want", [
+    (dict(q=None), B.ERR_INVALID_ARG),
+    (dict(seq=None), B.ERR_INVALID_ARG),
+    (dict(out=None), B.ERR_INVALID_ARG),
+    (dict(q=FAKE + 2), B.ERR_INVALID_ARG),
+    (dict(batch=0), B.ERR_INVALID_ARG),
+    (dict(hq=40, hkv=16), B.ERR_INVALID_ARG),          # not a multiple
+    (dict(hq=0), B.ERR_INVALID_ARG),
+    (dict(dim=96), B.ERR_UNSUPPORTED),
+    (dict(dim=256), B.ERR_UNSUPPORTED),
+    (dict(hq=64, hkv=2), B.ERR_UNSUPPORTED),           # group of 32
+    (dict(out_dtype=7), B.ERR_INVALID_ARG),
+    (dict(max_len=0), B.ERR_INVALID_ARG),
+    (dict(max_len=5000), B.ERR_INVALID_ARG),           # beyond the capacity
+    (dict(scale=float("nan")), B.ERR_INVALID_ARG),
+    (dict(ws=None), B.ERR_WORKSPACE),
+    (dict(ws=(FAKE & ~255) + 16), B.ERR_WORKSPACE),
+    (dict(ws_bytes=1024), B.ERR_WORKSPACE),
+])
+def test_decode_rejects(kw, want):
+    assert decode_status(desc(), **kw) == want
+
+
+@pytest.mark.parametrize("d", [
+    None,
+    desc(k=None), desc(v=None), desc(k=FAKE + 8),
+    desc(layout=5), desc(stride_t=64), desc(stride_t=129), desc(stride_h=0), desc(stride_b=-8),
+    desc(capacity=0), desc(reserved=1), desc(page_table=FAKE),
+    paged_desc(page_table=None), paged_desc(page_size=8), paged_desc(page_size=24),
+    paged_desc(max_pages_per_seq=0), paged_desc(num_pages=0), paged_desc(capacity=4000),
+])
+def test_bad_kv_descriptor_rejected_by_decode_and_append(d):
+    assert decode_status(d) == B.ERR_INVALID_ARG
+    ptr = ctypes.byref(d) if d is not None else None
+    assert B.lib().instattn_kv_append(ptr, FAKE, FAKE, FAKE, 16, 40, 128, None) == B.ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("args", [
+    (None, FAKE, FAKE, 16, 40, 128), (FAKE, None, FAKE, 16, 40, 128), (FAKE, FAKE, None, 16, 40, 128),
+    (FAKE + 4, FAKE, FAKE, 16, 40, 128), (FAKE, FAKE, FAKE, 0, 40, 128),
+    (FAKE, FAKE, FAKE, 16, 0, 128), (FAKE, FAKE, FAKE, 16, 40, 100),
+])
+def test_append_rejects(args):
+    k_new, v_new, seq, batch, hkv, dim = args
+    d = desc()
+    assert B.lib().instattn_kv_append(ctypes.byref(d), k_new, v_new, seq, batch, hkv, dim,
+                                      None) == B.ERR_INVALID_ARG
+
+
+def test_probe_rejects():
+    L = B.lib()
+    assert L.instattn_probe_read(None, 1024, FAKE, None) == B.ERR_INVALID_ARG
+    assert L.instattn_probe_read(FAKE, 1000, FAKE, None) == B.ERR_INVALID_ARG
+    assert L.instattn_probe_copy(FAKE, None, 1024, None) == B.ERR_INVALID_ARG
+    assert L.instattn_probe_copy(FAKE, FAKE, 0, None) == B.ERR_INVALID_ARG
+
+
+# ------------------------------------------------------------------ split plan (host arithmetic)
+@pytest.mark.parametrize("shape", [
+    (2, 4, 4, 64, 257), (16, 40, 40, 128, 4097), (8, 40, 40, 128, 32769),
+    (64, 40, 40, 128, 16385), (32, 64, 8, 128, 16385), (1, 40, 40, 128, 131072), (1, 1, 1, 64, 1),
+])
+def test_plan_covers_the_sequence_and_fills_the_chip(shape):
+    batch, hq, hkv, dim, max_len = shape
+    chunk, splits = B.decode_plan(*shape)
+    assert chunk % 128 == 0 and chunk >= 128
+    assert (splits - 1) * chunk < max_len <= splits * chunk
+    streams = batch * (hq if hq == hkv else hkv)
+    if max_len * streams >= 256 * 1024:            # enough work to want >= 1024 units
+        assert streams * splits >= 1024
+    ws = B.decode_workspace_size(*shape)
+    assert ws >= batch * hq * splits * (dim + 1) * 4 and ws % 256 == 0
+
+
+def test_plan_rejects_bad_shapes():
+    assert B.decode_workspace_size(0, 4, 4, 64, 100) == 0
+    assert B.decode_workspace_size(1, 4, 4, 80, 100) == 0
+    with pytest.raises(B.InstattnError):
+        B.decode_plan(1, 4, 3, 64, 100)
+
+
+def test_forced_chunk_env(monkeypatch):
+    monkeypatch.setenv("INSTATTN_CHUNK", "512")
+    assert B.decode_plan(16, 40, 40, 128, 4097) == (512, 9)
+    monkeypatch.setenv("INSTATTN_CHUNK", "500")      # rounded up to the tile quantum
+    assert B.decode_plan(16, 40, 40, 128, 4097) == (512, 9)
+    monkeypatch.delenv("INSTATTN_CHUNK")
+    assert B.decode_plan(16, 40, 40, 128, 4097)[0] != 512
