@@ -19,6 +19,17 @@
 //     the sequence length are never read.
 #include "common.h"
 
+// Compile-time knobs (defaults are the measured best).
+#ifndef INSTATTN_MHA_NT
+#define INSTATTN_MHA_NT 1        // 1: KV loads carry the non-temporal hint
+#endif
+#ifndef INSTATTN_MHA_WAVES
+#define INSTATTN_MHA_WAVES 4     // waves per block
+#endif
+#ifndef INSTATTN_MHA_WTILE
+#define INSTATTN_MHA_WTILE 16    // rows per wave per iteration, contiguous layout (paged: always 16)
+#endif
+
 namespace instattn {
 
 template <int U>
@@ -30,16 +41,21 @@ struct MhaTile {
 // 128-bit load at (uniform 64-bit base) + (32-bit per-lane byte offset): the form
 // the hardware addresses with a scalar base register pair and one VGPR.
 __device__ __forceinline__ u32x4 load16(const char* base, uint32_t lane_off) {
+#if INSTATTN_MHA_NT
     return __builtin_nontemporal_load((const u32x4*)(base + (uint64_t)lane_off));
+#else
+    return *(const u32x4*)(base + (uint64_t)lane_off);
+#endif
 }
 
 template <int D, bool PAGED>
-__global__ __launch_bounds__(256) void decode_mha_kernel(DecodeArgs a)
+__global__ __launch_bounds__(INSTATTN_MHA_WAVES * 64) void decode_mha_kernel(DecodeArgs a)
 {
     constexpr int LPR = D / 8;             // lanes per row
     constexpr int RPW = kWave / LPR;       // rows per wave load
-    constexpr int WAVES = 4;
-    constexpr int WTILE = 16;              // rows per wave per iteration: never straddles a page
+    constexpr int WAVES = INSTATTN_MHA_WAVES;
+    // rows per wave per iteration; 16 never straddles a page
+    constexpr int WTILE = PAGED ? 16 : INSTATTN_MHA_WTILE;
     constexpr int U = WTILE / RPW;         // loads of K (and of V) per lane per iteration
     constexpr int TILE = WAVES * WTILE;    // rows per block per iteration
     constexpr int NG = WAVES * RPW;        // independent softmax streams per block
@@ -190,9 +206,9 @@ static hipError_t launch_mha(const DecodeArgs& a, int batch, hipStream_t stream)
 {
     dim3 grid(a.num_splits, a.num_q_heads, batch);
     if (a.kv.page_table)
-        hipLaunchKernelGGL((decode_mha_kernel<D, true>), grid, dim3(256), 0, stream, a);
+        hipLaunchKernelGGL((decode_mha_kernel<D, true>), grid, dim3(INSTATTN_MHA_WAVES * 64), 0, stream, a);
     else
-        hipLaunchKernelGGL((decode_mha_kernel<D, false>), grid, dim3(256), 0, stream, a);
+        hipLaunchKernelGGL((decode_mha_kernel<D, false>), grid, dim3(INSTATTN_MHA_WAVES * 64), 0, stream, a);
     return hipGetLastError();
 }
 

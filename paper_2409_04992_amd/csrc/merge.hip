@@ -81,27 +81,34 @@ hipError_t launch_kv_append(const AppendArgs& a, hipStream_t stream)
 // ---------------------------------------------------------------------------
 // Measurement kernels: a pure streaming read and a plain copy.
 constexpr int kProbeBlocks = 4096;
+constexpr size_t kProbeSeg16 = 16384;   // 16-byte words per block segment (256 KiB)
 
+// Each block streams its own contiguous 256 KiB segments with eight 128-bit
+// loads per lane in flight -- the access shape of the attention split pass
+// without its arithmetic.
 __global__ __launch_bounds__(256) void probe_read_kernel(const u32x4* src, size_t n16, uint32_t* sink)
 {
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     uint32_t x = 0;
-    for (; i + 3 * stride < n16; i += 4 * stride) {
-        u32x4 a0 = __builtin_nontemporal_load(src + i);
-        u32x4 a1 = __builtin_nontemporal_load(src + i + stride);
-        u32x4 a2 = __builtin_nontemporal_load(src + i + 2 * stride);
-        u32x4 a3 = __builtin_nontemporal_load(src + i + 3 * stride);
-        x ^= a0.x ^ a0.y ^ a0.z ^ a0.w ^ a1.x ^ a1.y ^ a1.z ^ a1.w;
-        x ^= a2.x ^ a2.y ^ a2.z ^ a2.w ^ a3.x ^ a3.y ^ a3.z ^ a3.w;
+    const size_t nseg = (n16 + kProbeSeg16 - 1) / kProbeSeg16;
+    for (size_t seg = blockIdx.x; seg < nseg; seg += gridDim.x) {
+        const size_t lo = seg * kProbeSeg16;
+        const size_t hi = lo + kProbeSeg16 < n16 ? lo + kProbeSeg16 : n16;
+        size_t i = lo + threadIdx.x;
+        for (; i + 7 * 256 < hi; i += 8 * 256) {
+            u32x4 a[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) a[j] = __builtin_nontemporal_load(src + i + j * 256);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) x ^= a[j].x ^ a[j].y ^ a[j].z ^ a[j].w;
+        }
+        for (; i < hi; i += 256) {
+            u32x4 a0 = __builtin_nontemporal_load(src + i);
+            x ^= a0.x ^ a0.y ^ a0.z ^ a0.w;
+        }
     }
-    for (; i < n16; i += stride) {
-        u32x4 a0 = __builtin_nontemporal_load(src + i);
-        x ^= a0.x ^ a0.y ^ a0.z ^ a0.w;
-    }
-    // Fold the wave so that one store per block keeps the loads alive.
+    // Fold the wave so that one small store per wave keeps the loads alive.
     for (int s = 32; s > 0; s >>= 1) x ^= __shfl_xor(x, s);
-    if ((threadIdx.x & 63) == 0) atomicXor(&sink[blockIdx.x], x);
+    if ((threadIdx.x & 63) == 0) atomicXor(&sink[blockIdx.x % kProbeBlocks], x);
 }
 
 __global__ __launch_bounds__(256) void probe_copy_kernel(const u32x4* src, u32x4* dst, size_t n16)
@@ -113,7 +120,9 @@ __global__ __launch_bounds__(256) void probe_copy_kernel(const u32x4* src, u32x4
 
 hipError_t launch_probe_read(const void* src, size_t bytes, void* sink, hipStream_t stream)
 {
-    hipLaunchKernelGGL(probe_read_kernel, dim3(kProbeBlocks), dim3(256), 0, stream,
+    const size_t nseg = (bytes / 16 + kProbeSeg16 - 1) / kProbeSeg16;
+    const unsigned blocks = (unsigned)(nseg < 65536 ? nseg : 65536);
+    hipLaunchKernelGGL(probe_read_kernel, dim3(blocks), dim3(256), 0, stream,
                        (const u32x4*)src, bytes / 16, (uint32_t*)sink);
     return hipGetLastError();
 }
