@@ -1,0 +1,293 @@
+// Split pass of decode attention for grouped queries on the matrix cores
+// (head_dim 128, 2..16 query heads per KV head).
+//
+// Paper: Sec. II-A/II-B give the operation; the paper's engine runs one query
+// head per K/V stream.  With G query heads sharing a KV head every fp16 loaded
+// feeds G multiply-adds, which is more than the vector ALUs sustain at HBM speed,
+// while the two products become small dense contractions:
+//     S^T [16 rows x 16 heads]   = K_tile [16 x 128] . Q^T [128 x 16]
+//     O^T [128 dims x 16 heads] += V_tile^T [128 x 32] . P^T [32 x 16]
+// done with v_mfma_f32_16x16x32_f16 (heads padded to 16 with zero queries).
+//
+// Operand layouts of that instruction (lane l, g = l / 16, c = l % 16):
+//     A[i][k]: i = c, k = 8g .. 8g+7      B[k][j]: j = c, k = 8g .. 8g+7
+//     C[i][j]: j = c, i = 4g + r  (r = 0..3)
+//
+// Data movement per wave and iteration (32 rows of K and of V, 16 KB):
+//   * Global loads are 128-bit and row-contiguous: lane (g, c) reads bytes
+//     [16c, 16c+16) of row  base + 16m + 4x + g  (m = 0,1; x = 0..3), so one wave
+//     load covers four consecutive rows (1 KB).  K and V use the same offsets.
+//   * K goes through a wave-private LDS tile (row stride 272 B, conflict-free
+//     128-bit reads): the row loaded as (m, x) by lane group g is stored as LDS
+//     row 16m + 4g + x, and read back as the A operand, so that the score a lane
+//     gets in C register r of sub-tile m belongs to row 16m + 4r + g -- exactly
+//     the rows whose V it loaded.
+//   * V never touches LDS.  A lane holds 8 rows x 8 dims of V; contraction slot
+//     8g + 4m + r of the second product is defined to be "the row this lane group
+//     loaded as (m, r)", so the A operand V^T for output dims {8c + e} is an
+//     in-lane 8x8 transpose of fp16 values, and the softmax weights the lane
+//     already holds are the B operand as they are.
+//   * Softmax statistics are per head = per lane column c: the running maximum
+//     is agreed across the four lane groups with two cross-lane exchanges per
+//     tile; the running sum stays a per-lane partial until the unit ends.
+//   * Weights enter the matrix core as fp16.  When fp32 output is requested a
+//     second product with the fp16 remainder of each weight restores fp32
+//     accuracy.
+#include "common.h"
+
+namespace instattn {
+
+namespace {
+
+constexpr int kGqWaves = 4;
+constexpr int kGqWaveRows = 32;                   // rows per wave per iteration
+constexpr int kGqTile = kGqWaves * kGqWaveRows;   // rows per block per iteration
+constexpr int kGqRowBytes = 256 + 16;             // padded LDS row
+constexpr int kGqWaveLds = kGqWaveRows * kGqRowBytes;
+constexpr int kGqLds = kGqWaves * kGqWaveLds;     // 34816 B
+
+struct GqaTile {
+    u32x4 k[8];   // index 4m + x
+    u32x4 v[8];
+};
+
+__device__ __forceinline__ u32x4 gq_load16(const char* base, uint32_t lane_off) {
+    return __builtin_nontemporal_load((const u32x4*)(base + (uint64_t)lane_off));
+}
+
+__device__ __forceinline__ float xor_lanes(float x, int mask) {
+    return __shfl_xor(x, mask, 64);
+}
+
+// Orders this wave's LDS stores before its following LDS loads (and the reverse)
+// for the compiler; the hardware executes one wave's LDS operations in order.
+__device__ __forceinline__ void wave_lds_fence() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+}  // namespace
+
+template <bool PAGED, bool SPLIT_P>
+__global__ __launch_bounds__(256) void decode_gqa_kernel(DecodeArgs a)
+{
+    constexpr int D = 128;
+    const int split = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;
+    const int G = a.num_q_heads / a.num_kv_heads;
+    const int L = clamp_len(a.seq_lens[b], a.max_len);
+    const int t0 = split * a.chunk;
+    const int tid = threadIdx.x;
+    const int64_t row0 = (int64_t)b * a.num_q_heads + (int64_t)hk * G;   // first query head of the group
+
+    if (t0 >= L) {
+        if (a.num_splits == 1) {
+            for (int i = tid; i < G * D; i += 256) {
+                if (a.out_f32) ((float*)a.out)[row0 * D + i] = 0.f;
+                else ((half_t*)a.out)[row0 * D + i] = (half_t)0.f;
+            }
+            if (a.lse && tid < G) a.lse[row0 + tid] = -__builtin_inff();
+        }
+        return;
+    }
+    const int t1 = min(t0 + a.chunk, L);
+    const int last = t1 - 1;
+
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lane = tid & 63;
+    const int g = lane >> 4;
+    const int c = lane & 15;
+
+    __shared__ __align__(16) char lds[kGqLds];
+    char* my_lds = lds + wave * kGqWaveLds;
+
+    // Q^T as B operand of the first product: head c, dims 32kk + 8g .. +7.
+    half8_t qb[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+        half8_t z = {0, 0, 0, 0, 0, 0, 0, 0};
+        qb[kk] = c < G ? *(const half8_t*)(a.q + (row0 + c) * D + kk * 32 + g * 8) : z;
+    }
+
+    const char* kp = (const char*)a.kv.k;
+    const char* vp = (const char*)a.kv.v;
+    const uint32_t row_bytes = (uint32_t)a.kv.stride_t * 2u;
+    const int64_t head_off = (int64_t)hk * a.kv.stride_h;
+    const int32_t* table = PAGED ? a.kv.page_table + (int64_t)b * a.kv.max_pages : nullptr;
+
+    // First row of sub-tile m of this wave in iteration `it`, pulled back into the unit.
+    auto sub_row = [&](int it, int m) { return min(t0 + it * kGqTile + wave * kGqWaveRows + 16 * m, last); };
+    auto page_of = [&](int t) { return PAGED ? table[t >> a.kv.page_shift] : b; };
+
+    auto load_tile = [&](GqaTile& T, int it, int page0, int page1) {
+#pragma unroll
+        for (int m = 0; m < 2; ++m) {
+            const int tm = sub_row(it, m);                      // wave-uniform
+            const int in_page = PAGED ? (tm & a.kv.page_mask) : tm;
+            const int page = m == 0 ? page0 : page1;
+            const int64_t base =
+                2 * ((int64_t)page * a.kv.stride_b + head_off + (int64_t)in_page * a.kv.stride_t);
+            const int first = t0 + it * kGqTile + wave * kGqWaveRows + 16 * m + g;
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+                // rows behind the unit's end are redirected to its last row
+                const uint32_t off = (uint32_t)(min(first + 4 * x, last) - tm) * row_bytes + c * 16;
+                T.k[4 * m + x] = gq_load16(kp + base, off);
+                T.v[4 * m + x] = gq_load16(vp + base, off);
+            }
+        }
+    };
+
+    float m_run = kNegBig, l_run = 0.f;
+    float4_t acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = float4_t{0.f, 0.f, 0.f, 0.f};
+
+    auto consume = [&](const GqaTile& T, int it) {
+        // K tile -> LDS: the row loaded as (m, x) by group g becomes LDS row 16m + 4g + x.
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int lrow = 16 * (i >> 2) + 4 * g + (i & 3);
+            *(u32x4*)(my_lds + lrow * kGqRowBytes + c * 16) = T.k[i];
+        }
+        wave_lds_fence();
+        float4_t s[2];
+#pragma unroll
+        for (int m = 0; m < 2; ++m) {
+            s[m] = float4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                const half8_t ka =
+                    *(const half8_t*)(my_lds + (16 * m + c) * kGqRowBytes + kk * 64 + g * 16);
+                s[m] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka, qb[kk], s[m], 0, 0, 0);
+            }
+        }
+        wave_lds_fence();
+
+        // Scores of head c for rows first + 16m + 4r (slot 4m + r).
+        const int first = t0 + it * kGqTile + wave * kGqWaveRows + g;
+        float sc[8];
+        float mx = -__builtin_inff();
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int t = first + 16 * (i >> 2) + 4 * (i & 3);
+            sc[i] = t < t1 ? s[i >> 2][i & 3] * a.scale_log2 : -__builtin_inff();
+            mx = fmaxf(mx, sc[i]);
+        }
+        mx = fmaxf(mx, xor_lanes(mx, 16));
+        mx = fmaxf(mx, xor_lanes(mx, 32));
+        const float m_new = fmaxf(m_run, mx);
+        const float alpha = fast_exp2(m_run - m_new);
+        m_run = m_new;
+
+        half8_t p_hi, p_lo = {0, 0, 0, 0, 0, 0, 0, 0};
+        float psum = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const float p = fast_exp2(sc[i] - m_new);
+            p_hi[i] = (half_t)p;
+            if (SPLIT_P) {
+                p_lo[i] = (half_t)(p - (float)p_hi[i]);
+                psum += p;
+            } else {
+                psum += (float)p_hi[i];     // normalise by the weights actually used
+            }
+        }
+        l_run = l_run * alpha + psum;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] *= alpha;
+
+        // V^T operand for output dims 8c + e: element e of each of the 8 rows held.
+        half8_t vh[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) vh[i] = __builtin_bit_cast(half8_t, T.v[i]);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const half8_t va = {vh[0][e], vh[1][e], vh[2][e], vh[3][e],
+                                vh[4][e], vh[5][e], vh[6][e], vh[7][e]};
+            acc[e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va, p_hi, acc[e], 0, 0, 0);
+            if (SPLIT_P) acc[e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va, p_lo, acc[e], 0, 0, 0);
+        }
+    };
+
+    const int n_it = (t1 - t0 + kGqTile - 1) / kGqTile;
+    GqaTile A, B;
+    int pa0 = page_of(sub_row(0, 0)), pa1 = page_of(sub_row(0, 1));
+    int pb0 = page_of(sub_row(1, 0)), pb1 = page_of(sub_row(1, 1));
+    load_tile(A, 0, pa0, pa1);
+    for (int it = 0; it < n_it; it += 2) {
+        pa0 = page_of(sub_row(it + 2, 0));
+        pa1 = page_of(sub_row(it + 2, 1));
+        load_tile(B, it + 1, pb0, pb1);
+        pin_order();
+        consume(A, it);
+        pb0 = page_of(sub_row(it + 3, 0));
+        pb1 = page_of(sub_row(it + 3, 1));
+        load_tile(A, it + 2, pa0, pa1);
+        pin_order();
+        if (it + 1 < n_it) consume(B, it + 1);
+    }
+
+    // Unit result: combine the four waves through LDS (the K tiles are dead now).
+    l_run += xor_lanes(l_run, 16);
+    l_run += xor_lanes(l_run, 32);
+    __syncthreads();
+    float* s_o = (float*)lds;                       // [wave][G][D]
+    float* s_m = s_o + kGqWaves * G * D;            // [wave][16]
+    float* s_l = s_m + kGqWaves * 16;               // [wave][16]
+    if (c < G) {
+        float* dst = s_o + ((int64_t)wave * G + c) * D + 32 * g;
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) dst[8 * r + e] = acc[e][r];
+        if (g == 0) {
+            s_m[wave * 16 + c] = m_run;
+            s_l[wave * 16 + c] = l_run;
+        }
+    }
+    __syncthreads();
+    for (int i = tid; i < G * D; i += 256) {
+        const int head = i / D, d = i % D;
+        float M = kNegBig;
+#pragma unroll
+        for (int w = 0; w < kGqWaves; ++w) M = fmaxf(M, s_m[w * 16 + head]);
+        float lsum = 0.f, o = 0.f;
+#pragma unroll
+        for (int w = 0; w < kGqWaves; ++w) {
+            const float wgt = fast_exp2(s_m[w * 16 + head] - M);
+            lsum += wgt * s_l[w * 16 + head];
+            o += wgt * s_o[((int64_t)w * G + head) * D + d];
+        }
+        o /= lsum;
+        const float lse2 = M + fast_log2(lsum);
+        const int64_t row = row0 + head;
+        if (a.num_splits == 1) {
+            if (a.out_f32) ((float*)a.out)[row * D + d] = o;
+            else ((half_t*)a.out)[row * D + d] = (half_t)o;
+            if (a.lse && d == 0) a.lse[row] = lse2 * kLn2;
+        } else {
+            const int64_t u = row * a.num_splits + split;
+            a.o_part[u * D + d] = o;
+            if (d == 0) a.lse_part[u] = lse2;
+        }
+    }
+}
+
+// head_dim 128 only; the caller routes other shapes to the vector-ALU kernel.
+hipError_t launch_decode_gqa(const DecodeArgs& a, int batch, int head_dim, hipStream_t stream)
+{
+    if (head_dim != 128) return launch_decode_mha(a, batch, head_dim, stream);
+    dim3 grid(a.num_splits, a.num_kv_heads, batch);
+    const bool paged = a.kv.page_table != nullptr;
+    if (a.out_f32) {
+        if (paged) hipLaunchKernelGGL((decode_gqa_kernel<true, true>), grid, dim3(256), 0, stream, a);
+        else hipLaunchKernelGGL((decode_gqa_kernel<false, true>), grid, dim3(256), 0, stream, a);
+    } else {
+        if (paged) hipLaunchKernelGGL((decode_gqa_kernel<true, false>), grid, dim3(256), 0, stream, a);
+        else hipLaunchKernelGGL((decode_gqa_kernel<false, false>), grid, dim3(256), 0, stream, a);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace instattn

@@ -218,11 +218,4 @@ hipError_t launch_decode_mha(const DecodeArgs& a, int batch, int head_dim, hipSt
     return launch_mha<64>(a, batch, stream);
 }
 
-// Until the MFMA group kernel takes over, grouped queries run here too: every
-// query head walks its KV head's rows on its own.
-hipError_t launch_decode_gqa(const DecodeArgs& a, int batch, int head_dim, hipStream_t stream)
-{
-    return launch_decode_mha(a, batch, head_dim, stream);
-}
-
 }  // namespace instattn
