@@ -26,8 +26,8 @@ HBM_PEAK_GBPS = 8000.0
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=400)
-    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="mha13b_4k")
     ap.add_argument("--layers-resident", type=int, default=8,
                     help="distinct layer caches the steps rotate over")
@@ -83,22 +83,30 @@ def main():
     B.lib()                                   # fail loudly if the HIP library is missing
     dev = "cuda:0"
     wl = W.WORKLOADS[args.workload]
-    R = max(1, args.layers_resident)
+    # a multi-layer workload keeps all its layers resident and a step walks them all
+    R = wl.layers if wl.layers > 1 else max(1, args.layers_resident)
+    lps = wl.layers
     cases = [W.make_case(wl, dev, layer=i) for i in range(R)]
     descs = [B.kv_desc(c.k_cache, c.v_cache, c.page_table) for c in cases]
     max_len = int(cases[0].seq_lens.max().item())
     ws = B.alloc_workspace(wl.batch, wl.num_q_heads, wl.num_kv_heads, wl.head_dim, max_len, dev)
     out_dtype = torch.float32 if wl.out_dtype == "f32" else torch.float16
     out = torch.empty(wl.batch, wl.num_q_heads, wl.head_dim, dtype=out_dtype, device=dev)
-    kv_bytes = cases[0].kv_read_bytes()
-    positions = int(cases[0].seq_lens.sum().item())
+    kv_bytes_layer = cases[0].kv_read_bytes()
+    kv_bytes = kv_bytes_layer * lps                      # per step
+    positions = int(cases[0].seq_lens.sum().item()) * lps
     chunk, splits = B.decode_plan(wl.batch, wl.num_q_heads, wl.num_kv_heads, wl.head_dim, max_len)
 
     def step(i):
-        c, d = cases[i % R], descs[i % R]
-        B.kv_append(d, c.k_new, c.v_new, c.seq_lens)
-        B.decode(c.q, d, c.seq_lens, wl.num_kv_heads, c.scale, out, ws, max_len)
+        for j in range(lps):
+            c, d = cases[(i * lps + j) % R], descs[(i * lps + j) % R]
+            B.kv_append(d, c.k_new, c.v_new, c.seq_lens)
+            B.decode(c.q, d, c.seq_lens, wl.num_kv_heads, c.scale, out, ws, max_len)
 
+    if args.steps is None:
+        args.steps = 400 if lps == 1 else 20
+    if args.warmup is None:
+        args.warmup = 40 if lps == 1 else 2
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -122,7 +130,7 @@ def main():
     torch.cuda.synchronize()
     k_ms = sorted(a.elapsed_time(b) for a, b in ev)
     k_avg_ms = sum(k_ms) / len(k_ms)
-    achieved = kv_bytes / (k_avg_ms * 1e-3) / 1e9
+    achieved = kv_bytes_layer / (k_avg_ms * 1e-3) / 1e9
 
     # Read ceiling: a plain streaming-read kernel over the same footprint.
     sink = torch.zeros(4096, dtype=torch.int32, device=dev)
@@ -138,6 +146,21 @@ def main():
     rd_ms = sorted(a.elapsed_time(b) for a, b in rd[R:])
     ceiling = flat[0].numel() * 2 / (sum(rd_ms) / len(rd_ms) * 1e-3) / 1e9
 
+    # A plain copy of known size (256 MiB read + 256 MiB written per launch): the
+    # reference kernel for scaling the hardware traffic counters.
+    csrc = torch.empty(256 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+    cdst = torch.empty_like(csrc)
+    cp = []
+    for i in range(6):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        B.probe_copy(csrc, cdst)
+        b.record()
+        cp.append((a, b))
+    torch.cuda.synchronize()
+    cp_ms = sorted(a.elapsed_time(b) for a, b in cp[1:])
+    copy_gbps = 2 * csrc.numel() / (sum(cp_ms) / len(cp_ms) * 1e-3) / 1e9
+
     res = {
         "metric": "decode_attention_kv_bandwidth", "value": value, "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -146,22 +169,22 @@ def main():
         "config": {"workload": wl.name, "batch": wl.batch, "num_q_heads": wl.num_q_heads,
                    "num_kv_heads": wl.num_kv_heads, "head_dim": wl.head_dim,
                    "seq_len": wl.seq_len, "kv_layout": "paged16" if wl.paged else "contiguous",
-                   "out_dtype": wl.out_dtype, "layers_resident": R,
-                   "step": "kv_append + decode (split pass + merge), one layer",
+                   "out_dtype": wl.out_dtype, "layers_resident": R, "layers_per_step": lps,
+                   "step": "kv_append + decode (split pass + merge) for each layer of the step",
                    "chunk_tokens": chunk, "num_splits": splits,
                    "kv_bytes_per_step": kv_bytes},
         "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBPS,
         "attended_tokens_per_s": positions * args.steps / wall,
         "attended_head_tokens_per_s": positions * wl.num_q_heads * args.steps / wall,
-        "read_ceiling_GBps": ceiling,
+        "read_ceiling_GBps": ceiling, "copy_GBps_read_plus_write": copy_gbps,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
                      "kernel": "decode split pass", "kernel_ms_avg": k_avg_ms,
                      "kernel_ms_min": k_ms[0], "launches_timed": n_k,
-                     "algorithmic_bytes_per_launch": kv_bytes},
+                     "algorithmic_bytes_per_launch": kv_bytes_layer},
     }
     if not args.no_cpu_baseline:
-        res["cpu_baseline"] = cpu_baseline(cases[0], kv_bytes, positions)
+        res["cpu_baseline"] = cpu_baseline(cases[0], kv_bytes_layer, positions // lps)
     print(json.dumps(res), flush=True)
 
 

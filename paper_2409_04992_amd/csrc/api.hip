@@ -13,8 +13,13 @@ namespace {
 
 constexpr int kVersion = 100;          // 0.1.0
 constexpr int kChunkQuantum = 128;     // every kernel's block tile divides this
-constexpr int kMinChunk = 256;
-constexpr int kTargetUnits = 4096;     // work units wanted per launch (256 CUs, several blocks each)
+constexpr int kMinChunk = 384;
+// Work units wanted per launch and largest unit, per kernel family.  The
+// vector-ALU kernel runs 5 blocks per CU and is insensitive to the unit size, so
+// units stay small enough to balance ragged batches; the MFMA kernel runs 2
+// blocks per CU and pays more per unit, so it gets fewer, larger units.
+constexpr int kTargetUnitsMha = 4096, kMaxChunkMha = 1408;
+constexpr int kTargetUnitsGqa = 768, kMaxChunkGqa = 5504;
 
 bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 bool pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
@@ -26,17 +31,23 @@ struct Plan {
 };
 
 // Sequence split: units of `chunk` positions, enough of them to fill the chip
-// from host-known sizes alone.
+// from host-known sizes alone.  The chunk is an ODD multiple of 128 rows: units
+// that start a large power of two apart walk the same HBM channels in lockstep
+// and lose up to a fifth of the bandwidth (measured), an odd multiple staggers them.
 Plan make_plan(int batch, int num_q_heads, int num_kv_heads, int max_seq_len)
 {
     const int group = num_q_heads / num_kv_heads;
     // the MFMA path walks a KV head once for its whole query group
     const long streams = (long)batch * (group == 1 ? num_q_heads : num_kv_heads);
-    long chunk = ((long)max_seq_len * streams + kTargetUnits - 1) / kTargetUnits;
+    const long target = group == 1 ? kTargetUnitsMha : kTargetUnitsGqa;
+    const long cap = group == 1 ? kMaxChunkMha : kMaxChunkGqa;
+    long chunk = ((long)max_seq_len * streams + target - 1) / target;
     if (chunk < kMinChunk) chunk = kMinChunk;
+    if (chunk > cap) chunk = cap;
+    chunk = (chunk / kChunkQuantum | 1) * kChunkQuantum;
     const char* forced = getenv("INSTATTN_CHUNK");
-    if (forced && atoi(forced) > 0) chunk = atoi(forced);
-    chunk = (chunk + kChunkQuantum - 1) / kChunkQuantum * kChunkQuantum;
+    if (forced && atoi(forced) > 0)
+        chunk = ((long)atoi(forced) + kChunkQuantum - 1) / kChunkQuantum * kChunkQuantum;
     const long whole = ((long)max_seq_len + kChunkQuantum - 1) / kChunkQuantum * kChunkQuantum;
     if (chunk > whole) chunk = whole;
     Plan p;

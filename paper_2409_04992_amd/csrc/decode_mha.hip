@@ -30,6 +30,13 @@
 #define INSTATTN_MHA_WTILE 16    // rows per wave per iteration, contiguous layout (paged: always 16)
 #endif
 
+#ifndef INSTATTN_MHA_LDS_PAD
+#define INSTATTN_MHA_LDS_PAD 0   // extra LDS bytes per block (experiments: caps blocks per CU)
+#endif
+#ifndef INSTATTN_MHA_HEAD_FAST
+#define INSTATTN_MHA_HEAD_FAST 0 // 1: blockIdx.x walks heads, blockIdx.y walks splits
+#endif
+
 namespace instattn {
 
 template <int U>
@@ -60,13 +67,21 @@ __global__ __launch_bounds__(INSTATTN_MHA_WAVES * 64) void decode_mha_kernel(Dec
     constexpr int TILE = WAVES * WTILE;    // rows per block per iteration
     constexpr int NG = WAVES * RPW;        // independent softmax streams per block
 
+#if INSTATTN_MHA_HEAD_FAST
+    const int split = blockIdx.y, h = blockIdx.x, b = blockIdx.z;
+#else
     const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+#endif
     const int G = a.num_q_heads / a.num_kv_heads;
     const int hk = h / G;
     const int L = clamp_len(a.seq_lens[b], a.max_len);
     const int t0 = split * a.chunk;
     const int tid = threadIdx.x;
     const int64_t row = (int64_t)b * a.num_q_heads + h;
+#if INSTATTN_MHA_LDS_PAD > 0
+    __shared__ char s_pad[INSTATTN_MHA_LDS_PAD];
+    if (a.chunk < 0) s_pad[tid] = 1;   // never true; keeps the allocation
+#endif
 
     if (t0 >= L) {
         // Nothing to attend in this unit.  The merge ignores units behind L; with a
@@ -204,7 +219,11 @@ __global__ __launch_bounds__(INSTATTN_MHA_WAVES * 64) void decode_mha_kernel(Dec
 template <int D>
 static hipError_t launch_mha(const DecodeArgs& a, int batch, hipStream_t stream)
 {
+#if INSTATTN_MHA_HEAD_FAST
+    dim3 grid(a.num_q_heads, a.num_splits, batch);
+#else
     dim3 grid(a.num_splits, a.num_q_heads, batch);
+#endif
     if (a.kv.page_table)
         hipLaunchKernelGGL((decode_mha_kernel<D, true>), grid, dim3(INSTATTN_MHA_WAVES * 64), 0, stream, a);
     else

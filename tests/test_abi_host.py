@@ -130,8 +130,10 @@ def test_plan_covers_the_sequence_and_fills_the_chip(shape):
     assert chunk % 128 == 0 and chunk >= 128
     assert (splits - 1) * chunk < max_len <= splits * chunk
     streams = batch * (hq if hq == hkv else hkv)
-    if max_len * streams >= 256 * 1024:            # enough work to want >= 1024 units
-        assert streams * splits >= 1024
+    if max_len * streams >= 1024 * 1024:           # enough work to want every CU busy twice over
+        assert streams * splits >= 512
+    if chunk < max_len:                            # split: chunk is an odd multiple of 128
+        assert (chunk // 128) % 2 == 1
     ws = B.decode_workspace_size(*shape)
     assert ws >= batch * hq * splits * (dim + 1) * 4 and ws % 256 == 0
 
@@ -149,4 +151,4 @@ def test_forced_chunk_env(monkeypatch):
     monkeypatch.setenv("INSTATTN_CHUNK", "500")      # rounded up to the tile quantum
     assert B.decode_plan(16, 40, 40, 128, 4097) == (512, 9)
     monkeypatch.delenv("INSTATTN_CHUNK")
-    assert B.decode_plan(16, 40, 40, 128, 4097)[0] != 512
+    assert B.decode_plan(16, 40, 40, 128, 4097) == (640, 7)
