@@ -1,9 +1,10 @@
 #!/usr/bin/env python3
 """Decode-attention benchmark on one MI355X.
 
-A step is one pass of the whole hot path for one layer's batch: kv_append of the
-new token, then decode (split pass + merge), through the C ABI, with every input
-already resident in HBM.  The workload is the 13B-shaped MHA layer (batch 16,
+A step is one pass of the whole hot path for one layer's batch: the new token's
+k, v are appended to the cache and the query attends over it (split pass + LSE
+merge where the plan splits), through the C ABI (instattn_append_decode, or the
+two separate calls with --two-calls), with every input already resident in HBM.  The workload is the 13B-shaped MHA layer (batch 16,
 40 heads of 128, 4096 cached positions, fp16).  Steps rotate over several distinct
 layer caches so that no step starts with its KV in the last-level cache.
 
@@ -32,6 +33,8 @@ def parse():
     ap.add_argument("--layers-resident", type=int, default=8,
                     help="distinct layer caches the steps rotate over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--two-calls", action="store_true",
+                    help="step = instattn_kv_append + instattn_decode instead of instattn_append_decode")
     return ap.parse_args()
 
 
@@ -100,8 +103,12 @@ def main():
     def step(i):
         for j in range(lps):
             c, d = cases[(i * lps + j) % R], descs[(i * lps + j) % R]
-            B.kv_append(d, c.k_new, c.v_new, c.seq_lens)
-            B.decode(c.q, d, c.seq_lens, wl.num_kv_heads, c.scale, out, ws, max_len)
+            if args.two_calls:
+                B.kv_append(d, c.k_new, c.v_new, c.seq_lens)
+                B.decode(c.q, d, c.seq_lens, wl.num_kv_heads, c.scale, out, ws, max_len)
+            else:
+                B.append_decode(c.q, c.k_new, c.v_new, d, c.seq_lens, wl.num_kv_heads, c.scale,
+                                out, ws, max_len)
 
     if args.steps is None:
         args.steps = 400 if lps == 1 else 20
@@ -170,7 +177,9 @@ def main():
                    "num_kv_heads": wl.num_kv_heads, "head_dim": wl.head_dim,
                    "seq_len": wl.seq_len, "kv_layout": "paged16" if wl.paged else "contiguous",
                    "out_dtype": wl.out_dtype, "layers_resident": R, "layers_per_step": lps,
-                   "step": "kv_append + decode (split pass + merge) for each layer of the step",
+                   "step": ("kv_append; decode" if args.two_calls else "append_decode (append fused into "
+                            "the split pass)") + (", LSE merge" if splits > 1 else ", single split: no merge")
+                           + ", for each layer of the step",
                    "chunk_tokens": chunk, "num_splits": splits,
                    "kv_bytes_per_step": kv_bytes},
         "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBPS,

@@ -136,6 +136,22 @@ int instattn_decode(const void* q, const instattn_kv_desc* kv, const int32_t* se
                     size_t workspace_bytes, int max_seq_len, void* stream);
 
 /*
+ * instattn_kv_append followed by instattn_decode in one call (Sec. IV-D: q, k, v
+ * of the new token arrive together).  Same arguments, checks and results as the
+ * two calls in that order: the caches end up bit-identical and out/lse are those
+ * of instattn_decode on the updated caches.  The store of the new row is done
+ * inside the split pass by the unit that owns position seq_lens[b] - 1, which
+ * saves a kernel launch; for head_dim 64 with grouped queries, where no single
+ * unit owns a KV head's rows, the append is launched on its own first.
+ *   k_new, v_new : device, [batch][num_kv_heads][head_dim] fp16, dense, 16-byte aligned
+ */
+int instattn_append_decode(const void* q, const void* k_new, const void* v_new,
+                           const instattn_kv_desc* kv, const int32_t* seq_lens, int batch,
+                           int num_q_heads, int num_kv_heads, int head_dim, float scale, void* out,
+                           int out_dtype, float* lse, void* workspace, size_t workspace_bytes,
+                           int max_seq_len, void* stream);
+
+/*
  * The two halves of instattn_decode, callable on their own (same arguments, same
  * checks) so that each can be timed or composed separately.  decode_partial
  * runs the split pass: per unit an online-softmax pass over its positions,

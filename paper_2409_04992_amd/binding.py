@@ -66,6 +66,8 @@ def lib() -> ctypes.CDLL:
         L.instattn_decode.argtypes = decode_args
         L.instattn_decode_partial.restype = i
         L.instattn_decode_partial.argtypes = decode_args
+        L.instattn_append_decode.restype = i
+        L.instattn_append_decode.argtypes = [vp, vp, vp] + decode_args[1:]
         L.instattn_decode_merge.restype = i
         L.instattn_decode_merge.argtypes = [vp, i, i, i, i, i, vp, i, vp, vp, sz, i, vp]
         L.instattn_probe_read.restype = i
@@ -162,6 +164,15 @@ def decode(q, desc: KvDesc, seq_lens, num_kv_heads: int, scale: float, out, work
            max_seq_len: int, lse=None, stream=None) -> None:
     _check(lib().instattn_decode(*_decode_args(q, desc, seq_lens, num_kv_heads, scale, out, lse,
                                                workspace, max_seq_len, stream)), "instattn_decode")
+
+
+def append_decode(q, k_new, v_new, desc: KvDesc, seq_lens, num_kv_heads: int, scale: float, out,
+                  workspace, max_seq_len: int, lse=None, stream=None) -> None:
+    assert k_new.is_contiguous() and v_new.is_contiguous() and k_new.dtype == torch.float16
+    args = _decode_args(q, desc, seq_lens, num_kv_heads, scale, out, lse, workspace, max_seq_len,
+                        stream)
+    _check(lib().instattn_append_decode(args[0], _p(k_new), _p(v_new), *args[1:]),
+           "instattn_append_decode")
 
 
 def decode_partial(q, desc: KvDesc, seq_lens, num_kv_heads: int, scale: float, out, workspace,

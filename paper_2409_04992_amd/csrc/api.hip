@@ -20,6 +20,7 @@ constexpr int kMinChunk = 384;
 // blocks per CU and pays more per unit, so it gets fewer, larger units.
 constexpr int kTargetUnitsMha = 4096, kMaxChunkMha = 1408;
 constexpr int kTargetUnitsGqa = 768, kMaxChunkGqa = 5504;
+constexpr int kSingleSplitStreams = 512, kSingleSplitMaxLen = 8192;
 
 bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 bool pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
@@ -45,6 +46,10 @@ Plan make_plan(int batch, int num_q_heads, int num_kv_heads, int max_seq_len)
     if (chunk < kMinChunk) chunk = kMinChunk;
     if (chunk > cap) chunk = cap;
     chunk = (chunk / kChunkQuantum | 1) * kChunkQuantum;
+    // Enough short independent streams already fill the chip: one unit per stream,
+    // the split pass writes the result itself and no merge is launched.
+    if (group == 1 && streams >= kSingleSplitStreams && max_seq_len <= kSingleSplitMaxLen)
+        chunk = (long)kSingleSplitMaxLen + kChunkQuantum;   // cut down to the whole sequence below
     const char* forced = getenv("INSTATTN_CHUNK");
     if (forced && atoi(forced) > 0)
         chunk = ((long)atoi(forced) + kChunkQuantum - 1) / kChunkQuantum * kChunkQuantum;
@@ -189,10 +194,11 @@ size_t instattn_decode_workspace_size(int batch, int num_q_heads, int num_kv_hea
                                make_plan(batch, num_q_heads, num_kv_heads, max_seq_len));
 }
 
-int instattn_decode_partial(const void* q, const instattn_kv_desc* kv, const int32_t* seq_lens,
-                            int batch, int num_q_heads, int num_kv_heads, int head_dim,
-                            float scale, void* out, int out_dtype, float* lse, void* workspace,
-                            size_t workspace_bytes, int max_seq_len, void* stream)
+static int run_partial(const void* q, const void* k_new, const void* v_new, bool fused,
+                       const instattn_kv_desc* kv, const int32_t* seq_lens,
+                       int batch, int num_q_heads, int num_kv_heads, int head_dim,
+                       float scale, void* out, int out_dtype, float* lse, void* workspace,
+                       size_t workspace_bytes, int max_seq_len, void* stream)
 {
     int st = check_shape(batch, num_q_heads, num_kv_heads, head_dim, max_seq_len);
     if (st != INSTATTN_OK) return st;
@@ -200,12 +206,26 @@ int instattn_decode_partial(const void* q, const instattn_kv_desc* kv, const int
     if (st != INSTATTN_OK) return st;
     if (!q || !aligned16(q) || !seq_lens || !isfinite(scale)) return INSTATTN_ERR_INVALID_ARG;
     if (max_seq_len > kv->capacity) return INSTATTN_ERR_INVALID_ARG;
+    if (fused && (!k_new || !v_new || !aligned16(k_new) || !aligned16(v_new)))
+        return INSTATTN_ERR_INVALID_ARG;
     const Plan p = make_plan(batch, num_q_heads, num_kv_heads, max_seq_len);
     st = check_out(out, out_dtype, workspace, workspace_bytes,
                    workspace_bytes_for(batch, num_q_heads, head_dim, p));
     if (st != INSTATTN_OK) return st;
 
+    // The in-kernel append needs one block to own each (sequence, KV head): true for
+    // the vector-ALU kernel without groups and for the MFMA kernel.  Otherwise the
+    // append runs as its own launch first.
+    const bool one_owner = num_q_heads == num_kv_heads || head_dim == 128;
+    if (fused && !one_owner) {
+        st = instattn_kv_append(kv, k_new, v_new, seq_lens, batch, num_kv_heads, head_dim, stream);
+        if (st != INSTATTN_OK) return st;
+        fused = false;
+    }
+
     DecodeArgs a;
+    a.k_new = fused ? (const half_t*)k_new : nullptr;
+    a.v_new = fused ? (const half_t*)v_new : nullptr;
     a.q = (const half_t*)q;
     a.kv = make_view(kv);
     a.seq_lens = seq_lens;
@@ -224,6 +244,31 @@ int instattn_decode_partial(const void* q, const instattn_kv_desc* kv, const int
                        ? launch_decode_mha(a, batch, head_dim, (hipStream_t)stream)
                        : launch_decode_gqa(a, batch, head_dim, (hipStream_t)stream);
     return e == hipSuccess ? INSTATTN_OK : INSTATTN_ERR_RUNTIME;
+}
+
+int instattn_decode_partial(const void* q, const instattn_kv_desc* kv, const int32_t* seq_lens,
+                            int batch, int num_q_heads, int num_kv_heads, int head_dim,
+                            float scale, void* out, int out_dtype, float* lse, void* workspace,
+                            size_t workspace_bytes, int max_seq_len, void* stream)
+{
+    return run_partial(q, nullptr, nullptr, false, kv, seq_lens, batch, num_q_heads, num_kv_heads,
+                       head_dim, scale, out, out_dtype, lse, workspace, workspace_bytes, max_seq_len,
+                       stream);
+}
+
+int instattn_append_decode(const void* q, const void* k_new, const void* v_new,
+                           const instattn_kv_desc* kv, const int32_t* seq_lens, int batch,
+                           int num_q_heads, int num_kv_heads, int head_dim, float scale, void* out,
+                           int out_dtype, float* lse, void* workspace, size_t workspace_bytes,
+                           int max_seq_len, void* stream)
+{
+    int st = run_partial(q, k_new, v_new, true, kv, seq_lens, batch, num_q_heads, num_kv_heads,
+                         head_dim, scale, out, out_dtype, lse, workspace, workspace_bytes,
+                         max_seq_len, stream);
+    if (st != INSTATTN_OK) return st;
+    return instattn_decode_merge(seq_lens, batch, num_q_heads, num_kv_heads, head_dim,
+                                 kv->capacity, out, out_dtype, lse, workspace, workspace_bytes,
+                                 max_seq_len, stream);
 }
 
 int instattn_decode_merge(const int32_t* seq_lens, int batch, int num_q_heads, int num_kv_heads,

@@ -48,6 +48,10 @@ struct DecodeArgs {
     void* out;                  // final rows when num_splits == 1
     float* lse;                 // may be nullptr
     int32_t out_f32;
+    // Fused append (both nullptr otherwise): [B][Hkv][D] rows stored at position
+    // seq_lens[b] - 1 by the unit that owns that position, before it reads it.
+    const half_t* k_new;
+    const half_t* v_new;
 };
 
 // Arguments of the log-sum-exp merge.
@@ -93,6 +97,29 @@ __device__ __forceinline__ int64_t row_offset(const KvView& kv, int b, int hk, i
     int page = kv.page_table[(int64_t)b * kv.max_pages + (t >> kv.page_shift)];
     return (int64_t)page * kv.stride_b + (int64_t)hk * kv.stride_h +
            (int64_t)(t & kv.page_mask) * kv.stride_t;
+}
+
+// Fused append: the unit whose range holds position seq_lens[b] - 1 (the last
+// unit if the caller's bound was too small) copies the new K and V rows of KV
+// head hk into the cache, 16 bytes per thread, then the whole block synchronises
+// so that its own later loads of that row see the new bits.  Exactly one block per
+// (b, hk) may call this with owner == true.
+template <int D>
+__device__ __forceinline__ void fused_append(const DecodeArgs& a, int b, int hk, int split, int tid) {
+    if (a.k_new == nullptr) return;
+    const int La = a.seq_lens[b];
+    if (La < 1 || La > a.kv.capacity) return;
+    const int ta = La - 1;
+    if (split != min(ta / a.chunk, a.num_splits - 1)) return;   // block-uniform
+    constexpr int LPR = D / 8;
+    if (tid < 2 * LPR) {
+        const int c = tid % LPR;
+        const int64_t src = ((int64_t)b * a.num_kv_heads + hk) * D + c * 8;
+        const int64_t dst = row_offset(a.kv, b, hk, ta) + c * 8;
+        if (tid < LPR) *(u32x4*)(const_cast<half_t*>(a.kv.k) + dst) = *(const u32x4*)(a.k_new + src);
+        else *(u32x4*)(const_cast<half_t*>(a.kv.v) + dst) = *(const u32x4*)(a.v_new + src);
+    }
+    __syncthreads();
 }
 
 // Cross-lane exchange inside a row of 16 lanes with DPP (no LDS traffic).

@@ -73,12 +73,16 @@ template <bool PAGED, bool SPLIT_P>
 __global__ __launch_bounds__(256) void decode_gqa_kernel(DecodeArgs a)
 {
     constexpr int D = 128;
-    const int split = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;
+    // blockIdx.x walks KV heads: consecutive blocks go round-robin over the XCDs,
+    // so every XCD gets the same mix of units whatever the lengths are.
+    const int split = blockIdx.y, hk = blockIdx.x, b = blockIdx.z;
     const int G = a.num_q_heads / a.num_kv_heads;
     const int L = clamp_len(a.seq_lens[b], a.max_len);
     const int t0 = split * a.chunk;
     const int tid = threadIdx.x;
     const int64_t row0 = (int64_t)b * a.num_q_heads + (int64_t)hk * G;   // first query head of the group
+
+    fused_append<D>(a, b, hk, split, tid);
 
     if (t0 >= L) {
         if (a.num_splits == 1) {
@@ -278,7 +282,7 @@ __global__ __launch_bounds__(256) void decode_gqa_kernel(DecodeArgs a)
 hipError_t launch_decode_gqa(const DecodeArgs& a, int batch, int head_dim, hipStream_t stream)
 {
     if (head_dim != 128) return launch_decode_mha(a, batch, head_dim, stream);
-    dim3 grid(a.num_splits, a.num_kv_heads, batch);
+    dim3 grid(a.num_kv_heads, a.num_splits, batch);
     const bool paged = a.kv.page_table != nullptr;
     if (a.out_f32) {
         if (paged) hipLaunchKernelGGL((decode_gqa_kernel<true, true>), grid, dim3(256), 0, stream, a);

@@ -34,7 +34,7 @@
 #define INSTATTN_MHA_LDS_PAD 0   // extra LDS bytes per block (experiments: caps blocks per CU)
 #endif
 #ifndef INSTATTN_MHA_HEAD_FAST
-#define INSTATTN_MHA_HEAD_FAST 0 // 1: blockIdx.x walks heads, blockIdx.y walks splits
+#define INSTATTN_MHA_HEAD_FAST 1 // 1: blockIdx.x walks heads, blockIdx.y walks splits
 #endif
 
 namespace instattn {
@@ -82,6 +82,8 @@ __global__ __launch_bounds__(INSTATTN_MHA_WAVES * 64) void decode_mha_kernel(Dec
     __shared__ char s_pad[INSTATTN_MHA_LDS_PAD];
     if (a.chunk < 0) s_pad[tid] = 1;   // never true; keeps the allocation
 #endif
+
+    if (G == 1) fused_append<D>(a, b, hk, split, tid);
 
     if (t0 >= L) {
         // Nothing to attend in this unit.  The merge ignores units behind L; with a

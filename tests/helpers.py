@@ -17,8 +17,9 @@ def host(t):
     return None if t is None else t.detach().cpu().numpy()
 
 
-def gpu_step(case, out_dtype=None, append=True, want_lse=True, max_seq_len=None):
-    """append + decode through the library; returns (out, lse) torch tensors."""
+def gpu_step(case, out_dtype=None, append=True, want_lse=True, max_seq_len=None, fused=False):
+    """append + decode through the library (two calls, or the fused entry point);
+    returns (out, lse) torch tensors."""
     wl = case.wl
     dev = case.q.device
     desc = B.kv_desc(case.k_cache, case.v_cache, case.page_table)
@@ -32,9 +33,14 @@ def gpu_step(case, out_dtype=None, append=True, want_lse=True, max_seq_len=None)
     ws.fill_(0xFF)       # NaN patterns: stale workspace contents must not leak into the result
     out = torch.full((Bn, Hq, D), float("nan"), dtype=out_dtype, device=dev)
     lse = torch.full((Bn, Hq), float("nan"), dtype=torch.float32, device=dev) if want_lse else None
-    if append:
-        B.kv_append(desc, case.k_new, case.v_new, case.seq_lens)
-    B.decode(case.q, desc, case.seq_lens, wl.num_kv_heads, case.scale, out, ws, max_seq_len, lse=lse)
+    if append and fused:
+        B.append_decode(case.q, case.k_new, case.v_new, desc, case.seq_lens, wl.num_kv_heads,
+                        case.scale, out, ws, max_seq_len, lse=lse)
+    else:
+        if append:
+            B.kv_append(desc, case.k_new, case.v_new, case.seq_lens)
+        B.decode(case.q, desc, case.seq_lens, wl.num_kv_heads, case.scale, out, ws, max_seq_len,
+                 lse=lse)
     torch.cuda.synchronize()
     return out, lse
 

@@ -21,13 +21,13 @@ def small(name, **kw):
     return W.scaled_down(W.WORKLOADS[name], **kw)
 
 
-def full_check(wl, poison=True, out_dtype=None, lens=None, capacity=None):
+def full_check(wl, poison=True, out_dtype=None, lens=None, capacity=None, fused=False):
     """Whole-tensor comparison (sizes the C oracle finishes in seconds)."""
     case = W.make_case(wl, DEV, poison=poison, capacity=capacity)
     if lens is not None:
         case.seq_lens = torch.tensor(lens, dtype=torch.int32, device=DEV)
     want_out, want_lse, want_k, want_v = H.oracle_step(case)
-    out, lse = H.gpu_step(case, out_dtype=out_dtype)
+    out, lse = H.gpu_step(case, out_dtype=out_dtype, fused=fused)
     # appended caches: bit-exact everywhere (NaN poison included, so compare bit patterns)
     assert np.array_equal(H.host(case.k_cache).view(np.uint16), want_k.view(np.uint16))
     assert np.array_equal(H.host(case.v_cache).view(np.uint16), want_v.view(np.uint16))
@@ -35,18 +35,20 @@ def full_check(wl, poison=True, out_dtype=None, lens=None, capacity=None):
 
 
 # ------------------------------------------------------------------ the five configurations
-def test_config1_tiny_mha_fp32_out():
-    err = full_check(W.WORKLOADS["tiny_mha"])
+@pytest.mark.parametrize("fused", [False, True])
+def test_config1_tiny_mha_fp32_out(fused):
+    err = full_check(W.WORKLOADS["tiny_mha"], fused=fused)
     assert err < 1e-4
 
 
-def test_config2_mha13b_4k_full():
-    full_check(W.WORKLOADS["mha13b_4k"])
+@pytest.mark.parametrize("fused", [False, True])
+def test_config2_mha13b_4k_full(fused):
+    full_check(W.WORKLOADS["mha13b_4k"], fused=fused)
 
 
-def sampled_check(wl, pairs, poison, layer=0):
+def sampled_check(wl, pairs, poison, layer=0, fused=False):
     case = W.make_case(wl, DEV, layer=layer, poison=poison)
-    out, lse = H.gpu_step(case)
+    out, lse = H.gpu_step(case, fused=fused)
     rows = H.oracle_rows(case, pairs)          # caches already hold the appended row
     tol = H.TOL[out.dtype]
     worst = 0.0
@@ -60,23 +62,25 @@ def sampled_check(wl, pairs, poison, layer=0):
     return case, out, worst
 
 
-def test_config3_mha13b_32k_full_size_sampled():
+@pytest.mark.parametrize("fused", [False, True])
+def test_config3_mha13b_32k_full_size_sampled(fused):
     wl = W.WORKLOADS["mha13b_32k"]
     pairs = [(0, 0), (0, 39), (3, 17), (7, 39), (5, 1), (2, 20)]
-    case, out, _ = sampled_check(wl, pairs, poison=True)
+    case, out, _ = sampled_check(wl, pairs, poison=True, fused=fused)
     # append landed: row L-1 of sampled heads equals the new k, v bit for bit
     L = int(case.seq_lens[0])
     assert torch.equal(case.k_cache[:, :, L - 1].view(torch.int16), case.k_new.view(torch.int16))
     assert torch.equal(case.v_cache[:, :, L - 1].view(torch.int16), case.v_new.view(torch.int16))
 
 
-def test_config4_ragged_paged_full_size_sampled():
+@pytest.mark.parametrize("fused", [False, True])
+def test_config4_ragged_paged_full_size_sampled(fused):
     wl = W.WORKLOADS["ragged_paged"]
     lens = W.draw_seq_lens(wl)
     order = torch.argsort(lens)
     bs = [int(order[0]), int(order[-1]), int(order[len(order) // 2]), 0, 63]
     pairs = [(b, h) for b in bs for h in (0, 39)] + [(11, 7), (42, 23)]
-    case, out, _ = sampled_check(wl, pairs, poison=True)
+    case, out, _ = sampled_check(wl, pairs, poison=True, fused=fused)
     assert lens.min() >= 1025 and lens.max() <= 16385 and len(set(lens.tolist())) > 32
     # appended rows sit behind the page table
     for b in bs:
@@ -88,15 +92,20 @@ def test_config4_ragged_paged_full_size_sampled():
                            case.v_new[b].view(torch.int16))
 
 
-def test_config5_gqa_layer_full_shape_sampled():
+@pytest.mark.parametrize("fused", [False, True])
+def test_config5_gqa_layer_full_shape_sampled(fused):
     """One layer of the 80-layer GQA step at its real shape (2.1 GB of KV)."""
     wl = dataclasses.replace(W.WORKLOADS["gqa70b_16k"], layers=1)
     pairs = [(0, 0), (0, 7), (0, 8), (13, 31), (31, 63), (20, 40)]
-    sampled_check(wl, pairs, poison=True, layer=3)
+    case, out, _ = sampled_check(wl, pairs, poison=True, layer=3, fused=fused)
+    L = int(case.seq_lens[0])
+    assert torch.equal(case.k_cache[:, :, L - 1].view(torch.int16), case.k_new.view(torch.int16))
+    assert torch.equal(case.v_cache[:, :, L - 1].view(torch.int16), case.v_new.view(torch.int16))
 
 
-def test_config5_gqa_scaled_down_full_check():
-    full_check(small("gqa70b_16k", batch=3, seq_len=1500, layers=1))
+@pytest.mark.parametrize("fused", [False, True])
+def test_config5_gqa_scaled_down_full_check(fused):
+    full_check(small("gqa70b_16k", batch=3, seq_len=1500, layers=1), fused=fused)
 
 
 # ------------------------------------------------------------------ scaled-down recipes, whole tensors
@@ -254,3 +263,46 @@ def test_partial_then_merge_equals_decode():
     B.decode_merge(case.seq_lens, 4, 4, case.capacity, out, ws, 3001, lse=lse)
     torch.cuda.synchronize()
     assert torch.equal(out, ref) and torch.equal(lse, ref_lse)
+
+
+# ------------------------------------------------------------------ fused append + decode
+FUSED_CASES = [
+    W.Workload("f_mha", 3, 4, 4, 128, 2999, seq_len_min=5, seed=301),
+    W.Workload("f_mha64_paged", 3, 4, 4, 64, 1000, seq_len_min=5, paged=True, seed=302),
+    W.Workload("f_gqa", 2, 16, 2, 128, 6100, seq_len_min=2000, seed=303),
+    W.Workload("f_gqa_paged", 2, 8, 2, 128, 777, seq_len_min=1, paged=True, seed=304),
+    W.Workload("f_gqa64", 2, 8, 2, 64, 900, seq_len_min=100, seed=305),      # append launched on its own
+    W.Workload("f_many_short", 16, 40, 40, 128, 300, seq_len_min=1, seed=306),  # single split
+]
+
+
+@pytest.mark.parametrize("wl", FUSED_CASES, ids=[w.name for w in FUSED_CASES])
+def test_fused_call_equals_the_two_calls(wl):
+    a = W.make_case(wl, DEV, poison=True)
+    b = W.make_case(wl, DEV, poison=True)
+    assert torch.equal(a.k_cache.view(torch.int16), b.k_cache.view(torch.int16))
+    out_a, lse_a = H.gpu_step(a, fused=False)
+    out_b, lse_b = H.gpu_step(b, fused=True)
+    assert torch.equal(a.k_cache.view(torch.int16), b.k_cache.view(torch.int16))
+    assert torch.equal(a.v_cache.view(torch.int16), b.v_cache.view(torch.int16))
+    assert torch.equal(out_a, out_b) and torch.equal(lse_a, lse_b)
+    full_check(wl, fused=True)
+
+
+def test_fused_append_edge_lengths():
+    """Lengths of 0, below 0, at the capacity, beyond it and beyond max_seq_len:
+    the fused call stores exactly what kv_append stores."""
+    wl = small("mha13b_4k", batch=6, num_q_heads=2, num_kv_heads=2, seq_len=600)
+    lens = [0, -3, 608, 609, 5000, 300]
+    res = []
+    for fused in (False, True):
+        case = W.make_case(wl, DEV, poison=False)
+        assert case.capacity == 608
+        case.seq_lens = torch.tensor(lens, dtype=torch.int32, device=DEV)
+        out, lse = H.gpu_step(case, fused=fused, max_seq_len=400)
+        res.append((case, out, lse))
+    (ca, oa, la), (cb, ob, lb) = res
+    assert torch.equal(ca.k_cache.view(torch.int16), cb.k_cache.view(torch.int16))
+    assert torch.equal(ca.v_cache.view(torch.int16), cb.v_cache.view(torch.int16))
+    assert torch.equal(oa, ob) and torch.equal(la, lb)
+    assert torch.equal(cb.k_cache[2, :, 607].view(torch.int16), cb.k_new[2].view(torch.int16))
