@@ -22,6 +22,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
+# HBM bytes per launch of the split-pass kernel from rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE runs of this script, scaled by what the same counters read for the
+# 256 MiB copy kernel (FETCH_SIZE x 2.000, WRITE_SIZE x 1.000); see profiles/.
+MEASURED_TRAFFIC_BYTES = {"mha13b_4k": 1343279911, "gqa70b_16k": 2151868618}
 
 
 def parse():
@@ -187,7 +191,8 @@ def main():
         "attended_head_tokens_per_s": positions * wl.num_q_heads * args.steps / wall,
         "read_ceiling_GBps": ceiling, "copy_GBps_read_plus_write": copy_gbps,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBPS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name),
                      "kernel": "decode split pass", "kernel_ms_avg": k_avg_ms,
                      "kernel_ms_min": k_ms[0], "launches_timed": n_k,
                      "algorithmic_bytes_per_launch": kv_bytes_layer},
