@@ -42,36 +42,44 @@ def parse():
     return ap.parse_args()
 
 
-def cpu_baseline(case, kv_bytes_step, positions_step):
-    """The C oracle as it stands, on the host cores, on a bounded sample of (b, h) pairs."""
-    import numpy as np
+def cpu_baseline(cases, kv_bytes_layer, positions_layer):
+    """The C oracle as it stands, on the host cores, on a bounded sample: whole
+    layers of the same workload (every (sequence, head) pair, or every n-th pair if
+    one layer alone would take much longer than the budget), about 10-30 s of CPU
+    work in total."""
     from oracle import c_oracle
     cores = min(len(os.sched_getaffinity(0)), 16)
-    wl = case.wl
-    q = case.q.cpu().numpy()
-    k, v = case.k_cache.cpu().numpy(), case.v_cache.cpu().numpy()
-    sl = case.seq_lens.cpu().numpy()
-    pt = None if case.page_table is None else case.page_table.cpu().numpy()
+    wl = cases[0].wl
     pairs = wl.batch * wl.num_q_heads
-    # calibrate on a thin sample, then size the timed sample to about 15 s
+    budget_cpu_s = 20.0
+
+    def host(case):
+        pt = None if case.page_table is None else case.page_table.cpu().numpy()
+        return (case.q.cpu().numpy(), case.k_cache.cpu().numpy(), case.v_cache.cpu().numpy(),
+                case.seq_lens.cpu().numpy(), case.scale, pt)
+
+    # calibrate on a thin sample of the first layer
+    args0 = host(cases[0])
     stride = max(1, pairs // (2 * cores))
     t = time.perf_counter()
-    n = c_oracle.decode(q, k, v, sl, case.scale, pt, pair_stride=stride, nthreads=cores)[0]
-    calib = time.perf_counter() - t
-    done = len(range(0, pairs, stride))
-    per_pair = calib / done * cores
-    want = int(min(pairs, max(cores, 15.0 / per_pair * cores)))
-    stride = max(1, pairs // want)
-    t = time.perf_counter()
-    c_oracle.decode(q, k, v, sl, case.scale, pt, pair_stride=stride, nthreads=cores)
-    dt = time.perf_counter() - t
-    done = len(range(0, pairs, stride))
-    frac = done / pairs
+    c_oracle.decode(*args0, pair_stride=stride, nthreads=cores)
+    per_pair_cpu_s = (time.perf_counter() - t) * cores / len(range(0, pairs, stride))
+    want_pairs = budget_cpu_s / per_pair_cpu_s
+    layers = int(min(len(cases), max(1, want_pairs // pairs)))
+    stride = max(1, int(pairs // want_pairs)) if want_pairs < pairs else 1
+    done, dt = 0, 0.0
+    for i in range(layers):
+        args = args0 if i == 0 else host(cases[i])
+        t = time.perf_counter()
+        c_oracle.decode(*args, pair_stride=stride, nthreads=cores)
+        dt += time.perf_counter() - t
+        done += len(range(0, pairs, stride))
+    frac = done / pairs          # in units of one layer
     return {
-        "value": kv_bytes_step * frac / dt / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
-        "sample": "%d of %d (sequence, head) pairs (every %d-th) of the same layer, fp64 C oracle, "
-                  "%d OpenMP threads, %.1f s" % (done, pairs, stride, cores, dt),
-        "attended_tokens_per_s": positions_step * frac / dt,
+        "value": kv_bytes_layer * frac / dt / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
+        "sample": "%d (sequence, head) pairs = every %d-th pair of %d layer(s) of the same workload, "
+                  "fp64 C oracle, %d OpenMP threads, %.1f s wall" % (done, stride, layers, cores, dt),
+        "attended_tokens_per_s": positions_layer * frac / dt,
     }
 
 
@@ -198,7 +206,7 @@ def main():
                      "algorithmic_bytes_per_launch": kv_bytes_layer},
     }
     if not args.no_cpu_baseline:
-        res["cpu_baseline"] = cpu_baseline(cases[0], kv_bytes_layer, positions // lps)
+        res["cpu_baseline"] = cpu_baseline(cases, kv_bytes_layer, positions // lps)
     print(json.dumps(res), flush=True)
 
 
