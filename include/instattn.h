@@ -169,6 +169,73 @@ int instattn_decode_merge(const int32_t* seq_lens, int batch, int num_q_heads, i
                           const void* workspace, size_t workspace_bytes, int max_seq_len,
                           void* stream);
 
+/* ------------------------------------------------------------------------
+ * SparF attention (Algorithm 1): decode attention from a fraction of the cache.
+ *
+ * Per query head: keep the r components of q with the largest magnitude, score
+ * every position from those r columns of K alone (softmax with the temperature
+ * of step 4), keep the k best-scored positions, the l most recent always among
+ * them (steps 5-6), let alpha be their share of the approximate softmax (step 7),
+ * run exact softmax attention over the kept rows (step 10) and return
+ *     out = alpha * attention_over_kept_rows + (1 - alpha) * mean(V[0:L_b])   (step 11).
+ * 1/sqrt(d_h) enters through `scale` as in the dense path.  Ties in either top-k
+ * go to the lower index.  k and l are cut off at L_b, l at k.  With k >= L_b the
+ * result equals instattn_decode.  Contiguous caches only, head_dim 64 or 128.
+ *
+ * The column reads need K stored a second time, component-major (the paper's
+ * hidden-embedding-indexed copy, Sec. IV-C), and step 11 needs the running sum
+ * of V; both live in caller-owned device memory described by instattn_sparf_aux:
+ *   kt   : fp16, element (b, hk, d, t) at b*stride_b + hk*stride_h + d*stride_d + t;
+ *          strides multiples of 8, 16-byte aligned, capacity a multiple of 8
+ *   vsum : fp32 [batch][num_kv_heads][head_dim], sum of rows 0 .. L_b-1 of V
+ */
+typedef struct {
+    void* kt;
+    int64_t stride_b, stride_h, stride_d;
+    float* vsum;
+    int32_t capacity;          /* positions per (b, hk, d) row of kt */
+    int32_t reserved;          /* must be 0 */
+} instattn_sparf_aux;
+
+/*
+ * Fill aux (kt and vsum) from the rows 0 .. seq_lens[b]-1 of an existing cache:
+ * what the storage side does when the prefill phase hands over a layer's K and V
+ * (Sec. IV-D).  Rows at or behind the length are not read.  One launch.
+ */
+int instattn_sparf_build(const instattn_kv_desc* kv, const instattn_sparf_aux* aux,
+                         const int32_t* seq_lens, int batch, int num_kv_heads, int head_dim,
+                         void* stream);
+
+/*
+ * instattn_kv_append that also keeps aux current: stores k_new as entry
+ * seq_lens[b]-1 of every K column and adds v_new to vsum.  Unlike kv_append it is
+ * not idempotent (vsum is a running sum): call it once per new token.  A length
+ * outside [1, capacity] changes nothing for that sequence.  One launch.
+ */
+int instattn_sparf_append(const instattn_kv_desc* kv, const instattn_sparf_aux* aux,
+                          const void* k_new, const void* v_new, const int32_t* seq_lens,
+                          int batch, int num_kv_heads, int head_dim, void* stream);
+
+/* Bytes of device workspace instattn_sparf_decode needs (0 if the arguments are invalid). */
+size_t instattn_sparf_workspace_size(int batch, int num_q_heads, int head_dim, int max_seq_len,
+                                     int k);
+
+/*
+ * SparF decode as described above.  Arguments as for instattn_decode, plus
+ *   r, k, l   : Algorithm 1's inputs; 1 <= r <= head_dim, k >= 1, l >= 0
+ *   sel_rows  : device [batch][num_q_heads][k] int32 or NULL: receives the kept
+ *               positions of every head in ascending order (min(k, L_b) entries
+ *               are written per head)
+ *   alpha     : device [batch][num_q_heads] fp32 or NULL: receives step 7's alpha
+ * L_b <= 0 gives a zero row (alpha 0).  Three launches (column scores, selection,
+ * attention over the kept rows).
+ */
+int instattn_sparf_decode(const void* q, const instattn_kv_desc* kv, const instattn_sparf_aux* aux,
+                          const int32_t* seq_lens, int batch, int num_q_heads, int num_kv_heads,
+                          int head_dim, float scale, int r, int k, int l, void* out, int out_dtype,
+                          int32_t* sel_rows, float* alpha, void* workspace, size_t workspace_bytes,
+                          int max_seq_len, void* stream);
+
 /*
  * Measurement aids, not part of the attention path.  probe_read streams `bytes`
  * (a multiple of 16) from src with 128-bit loads and folds them into 4 bytes per

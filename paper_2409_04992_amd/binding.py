@@ -33,6 +33,16 @@ class KvDesc(ctypes.Structure):
     ]
 
 
+class SparfAux(ctypes.Structure):
+    """Mirror of instattn_sparf_aux."""
+    _fields_ = [
+        ("kt", ctypes.c_void_p),
+        ("stride_b", ctypes.c_int64), ("stride_h", ctypes.c_int64), ("stride_d", ctypes.c_int64),
+        ("vsum", ctypes.c_void_p),
+        ("capacity", ctypes.c_int32), ("reserved", ctypes.c_int32),
+    ]
+
+
 class InstattnError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
@@ -70,6 +80,16 @@ def lib() -> ctypes.CDLL:
         L.instattn_append_decode.argtypes = [vp, vp, vp] + decode_args[1:]
         L.instattn_decode_merge.restype = i
         L.instattn_decode_merge.argtypes = [vp, i, i, i, i, i, vp, i, vp, vp, sz, i, vp]
+        pk, pa = ctypes.POINTER(KvDesc), ctypes.POINTER(SparfAux)
+        L.instattn_sparf_build.restype = i
+        L.instattn_sparf_build.argtypes = [pk, pa, vp, i, i, i, vp]
+        L.instattn_sparf_append.restype = i
+        L.instattn_sparf_append.argtypes = [pk, pa, vp, vp, vp, i, i, i, vp]
+        L.instattn_sparf_workspace_size.restype = sz
+        L.instattn_sparf_workspace_size.argtypes = [i, i, i, i, i]
+        L.instattn_sparf_decode.restype = i
+        L.instattn_sparf_decode.argtypes = [vp, pk, pa, vp, i, i, i, i, f, i, i, i, vp, i, vp, vp,
+                                            vp, sz, i, vp]
         L.instattn_probe_read.restype = i
         L.instattn_probe_read.argtypes = [vp, sz, vp, vp]
         L.instattn_probe_copy.restype = i
@@ -208,3 +228,51 @@ def probe_read(src: torch.Tensor, sink: torch.Tensor, stream=None) -> None:
 def probe_copy(src: torch.Tensor, dst: torch.Tensor, stream=None) -> None:
     _check(lib().instattn_probe_copy(_p(src), _p(dst), src.numel() * src.element_size(),
                                      _stream(stream)), "instattn_probe_copy")
+
+
+# ---------------------------------------------------------------------- SparF
+def sparf_aux(kt: torch.Tensor, vsum: torch.Tensor) -> SparfAux:
+    """Descriptor for kt [B, Hkv, D, capacity] fp16 and vsum [B, Hkv, D] fp32."""
+    assert kt.dtype == torch.float16 and kt.stride(3) == 1
+    assert vsum.dtype == torch.float32 and vsum.is_contiguous()
+    a = SparfAux()
+    a.kt, a.vsum = kt.data_ptr(), vsum.data_ptr()
+    a.stride_b, a.stride_h, a.stride_d = kt.stride(0), kt.stride(1), kt.stride(2)
+    a.capacity = kt.shape[3]
+    a.reserved = 0
+    return a
+
+
+def sparf_build(desc: KvDesc, aux: SparfAux, seq_lens, num_kv_heads: int, head_dim: int,
+                stream=None) -> None:
+    _check(lib().instattn_sparf_build(ctypes.byref(desc), ctypes.byref(aux), _p(seq_lens),
+                                      seq_lens.numel(), num_kv_heads, head_dim, _stream(stream)),
+           "instattn_sparf_build")
+
+
+def sparf_append(desc: KvDesc, aux: SparfAux, k_new, v_new, seq_lens, stream=None) -> None:
+    B, Hkv, D = k_new.shape
+    assert k_new.is_contiguous() and v_new.is_contiguous()
+    _check(lib().instattn_sparf_append(ctypes.byref(desc), ctypes.byref(aux), _p(k_new), _p(v_new),
+                                       _p(seq_lens), B, Hkv, D, _stream(stream)),
+           "instattn_sparf_append")
+
+
+def sparf_workspace_size(batch: int, num_q_heads: int, head_dim: int, max_seq_len: int,
+                         k: int) -> int:
+    return lib().instattn_sparf_workspace_size(batch, num_q_heads, head_dim, max_seq_len, k)
+
+
+def sparf_decode(q, desc: KvDesc, aux: SparfAux, seq_lens, num_kv_heads: int, scale: float,
+                 r: int, k: int, l: int, out, workspace, max_seq_len: int, sel_rows=None,
+                 alpha=None, stream=None) -> None:
+    B, Hq, D = q.shape
+    assert q.dtype == torch.float16 and q.is_contiguous() and out.is_contiguous()
+    assert sel_rows is None or (sel_rows.dtype == torch.int32 and sel_rows.shape == (B, Hq, k))
+    assert alpha is None or (alpha.dtype == torch.float32 and alpha.shape == (B, Hq))
+    _check(lib().instattn_sparf_decode(
+        _p(q), ctypes.byref(desc), ctypes.byref(aux), _p(seq_lens), B, Hq, num_kv_heads, D,
+        float(scale), int(r), int(k), int(l), _p(out),
+        F16 if out.dtype == torch.float16 else F32, _p(sel_rows), _p(alpha), _p(workspace),
+        workspace.numel() * workspace.element_size(), int(max_seq_len), _stream(stream)),
+        "instattn_sparf_decode")

@@ -1,0 +1,167 @@
+// Host side of the SparF entry points: argument checks, workspace carving, launches.
+#include "../../include/instattn.h"
+
+#include <math.h>
+
+#include "sparf.h"
+
+using namespace instattn;
+
+namespace {
+
+bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+size_t up256(size_t x) { return (x + 255) / 256 * 256; }
+
+struct Carve {
+    size_t logits, stats, sel, alpha, total;
+    int lpad, nchunk;
+};
+
+Carve carve(int batch, int num_q_heads, int max_seq_len, int k)
+{
+    Carve c;
+    c.nchunk = (max_seq_len + kSparfChunk - 1) / kSparfChunk;
+    c.lpad = c.nchunk * kSparfChunk;
+    const size_t rows = (size_t)batch * num_q_heads;
+    c.logits = 0;
+    c.stats = c.logits + up256(rows * c.lpad * sizeof(float));
+    c.sel = c.stats + up256(rows * c.nchunk * 2 * sizeof(float));
+    c.alpha = c.sel + up256(rows * (size_t)k * sizeof(int32_t));
+    c.total = c.alpha + up256(rows * sizeof(float));
+    return c;
+}
+
+int check_common(const instattn_kv_desc* kv, const instattn_sparf_aux* aux, int batch, int num_kv_heads,
+                 int head_dim)
+{
+    if (batch <= 0 || num_kv_heads <= 0) return INSTATTN_ERR_INVALID_ARG;
+    if (head_dim != 64 && head_dim != 128) return head_dim > 0 ? INSTATTN_ERR_UNSUPPORTED : INSTATTN_ERR_INVALID_ARG;
+    if (!kv || !kv->k || !kv->v || !aligned16(kv->k) || !aligned16(kv->v)) return INSTATTN_ERR_INVALID_ARG;
+    if (kv->reserved != 0 || kv->capacity <= 0) return INSTATTN_ERR_INVALID_ARG;
+    if (kv->layout == INSTATTN_KV_PAGED) return INSTATTN_ERR_UNSUPPORTED;
+    if (kv->layout != INSTATTN_KV_CONTIGUOUS || kv->page_table) return INSTATTN_ERR_INVALID_ARG;
+    if (kv->stride_b <= 0 || kv->stride_h <= 0 || kv->stride_t < head_dim) return INSTATTN_ERR_INVALID_ARG;
+    if (kv->stride_b % 8 || kv->stride_h % 8 || kv->stride_t % 8) return INSTATTN_ERR_INVALID_ARG;
+    if (!aux || !aux->kt || !aux->vsum || !aligned16(aux->kt) || aux->reserved != 0)
+        return INSTATTN_ERR_INVALID_ARG;
+    if (aux->capacity <= 0 || aux->capacity % 8 || aux->stride_d < aux->capacity) return INSTATTN_ERR_INVALID_ARG;
+    if (aux->stride_b <= 0 || aux->stride_h <= 0) return INSTATTN_ERR_INVALID_ARG;
+    if (aux->stride_b % 8 || aux->stride_h % 8 || aux->stride_d % 8) return INSTATTN_ERR_INVALID_ARG;
+    return INSTATTN_OK;
+}
+
+void fill_views(SparfArgs& a, const instattn_kv_desc* kv, const instattn_sparf_aux* aux)
+{
+    a.kv.k = (const half_t*)kv->k;
+    a.kv.v = (const half_t*)kv->v;
+    a.kv.page_table = nullptr;
+    a.kv.stride_b = kv->stride_b;
+    a.kv.stride_h = kv->stride_h;
+    a.kv.stride_t = kv->stride_t;
+    a.kv.capacity = kv->capacity;
+    a.kv.page_shift = 0;
+    a.kv.page_mask = 0;
+    a.kv.max_pages = 0;
+    a.aux.kt = (half_t*)aux->kt;
+    a.aux.stride_b = aux->stride_b;
+    a.aux.stride_h = aux->stride_h;
+    a.aux.stride_d = aux->stride_d;
+    a.aux.capacity = aux->capacity;
+    a.aux.vsum = aux->vsum;
+}
+
+int status_of(hipError_t e) { return e == hipSuccess ? INSTATTN_OK : INSTATTN_ERR_RUNTIME; }
+
+}  // namespace
+
+extern "C" {
+
+int instattn_sparf_build(const instattn_kv_desc* kv, const instattn_sparf_aux* aux,
+                         const int32_t* seq_lens, int batch, int num_kv_heads, int head_dim,
+                         void* stream)
+{
+    int st = check_common(kv, aux, batch, num_kv_heads, head_dim);
+    if (st != INSTATTN_OK) return st;
+    if (!seq_lens || batch > 65535) return INSTATTN_ERR_INVALID_ARG;
+    SparfArgs a = {};
+    fill_views(a, kv, aux);
+    a.seq_lens = seq_lens;
+    a.batch = batch;
+    a.num_kv_heads = num_kv_heads;
+    a.head_dim = head_dim;
+    return status_of(launch_sparf_build(a, (hipStream_t)stream));
+}
+
+int instattn_sparf_append(const instattn_kv_desc* kv, const instattn_sparf_aux* aux,
+                          const void* k_new, const void* v_new, const int32_t* seq_lens,
+                          int batch, int num_kv_heads, int head_dim, void* stream)
+{
+    int st = check_common(kv, aux, batch, num_kv_heads, head_dim);
+    if (st != INSTATTN_OK) return st;
+    if (!seq_lens || !k_new || !v_new) return INSTATTN_ERR_INVALID_ARG;
+    SparfArgs a = {};
+    fill_views(a, kv, aux);
+    a.seq_lens = seq_lens;
+    a.batch = batch;
+    a.num_kv_heads = num_kv_heads;
+    a.head_dim = head_dim;
+    a.k_new = (const half_t*)k_new;
+    a.v_new = (const half_t*)v_new;
+    return status_of(launch_sparf_append(a, (hipStream_t)stream));
+}
+
+size_t instattn_sparf_workspace_size(int batch, int num_q_heads, int head_dim, int max_seq_len, int k)
+{
+    if (batch <= 0 || num_q_heads <= 0 || max_seq_len <= 0 || k <= 0) return 0;
+    if (head_dim != 64 && head_dim != 128) return 0;
+    return carve(batch, num_q_heads, max_seq_len, k).total;
+}
+
+int instattn_sparf_decode(const void* q, const instattn_kv_desc* kv, const instattn_sparf_aux* aux,
+                          const int32_t* seq_lens, int batch, int num_q_heads, int num_kv_heads,
+                          int head_dim, float scale, int r, int k, int l, void* out, int out_dtype,
+                          int32_t* sel_rows, float* alpha, void* workspace, size_t workspace_bytes,
+                          int max_seq_len, void* stream)
+{
+    int st = check_common(kv, aux, batch, num_kv_heads, head_dim);
+    if (st != INSTATTN_OK) return st;
+    if (num_q_heads <= 0 || num_q_heads % num_kv_heads || max_seq_len <= 0) return INSTATTN_ERR_INVALID_ARG;
+    if (batch > 65535 || num_q_heads > 65535) return INSTATTN_ERR_UNSUPPORTED;
+    if (!q || !aligned16(q) || !seq_lens || !isfinite(scale)) return INSTATTN_ERR_INVALID_ARG;
+    if (!out || !aligned16(out)) return INSTATTN_ERR_INVALID_ARG;
+    if (out_dtype != INSTATTN_F16 && out_dtype != INSTATTN_F32) return INSTATTN_ERR_INVALID_ARG;
+    if (r < 1 || r > head_dim || k < 1 || l < 0) return INSTATTN_ERR_INVALID_ARG;
+    if (max_seq_len > kv->capacity || max_seq_len > aux->capacity) return INSTATTN_ERR_INVALID_ARG;
+    const Carve c = carve(batch, num_q_heads, max_seq_len, k);
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < c.total)
+        return INSTATTN_ERR_WORKSPACE;
+
+    SparfArgs a = {};
+    fill_views(a, kv, aux);
+    a.q = (const half_t*)q;
+    a.seq_lens = seq_lens;
+    a.batch = batch;
+    a.num_q_heads = num_q_heads;
+    a.num_kv_heads = num_kv_heads;
+    a.head_dim = head_dim;
+    a.max_len = max_seq_len;
+    a.scale_log2 = scale * kLog2e;
+    a.r = r;
+    a.k = k;
+    a.l = l;
+    char* ws = (char*)workspace;
+    a.logits = (float*)(ws + c.logits);
+    a.lpad = c.lpad;
+    a.nchunk = c.nchunk;
+    a.stats = (float*)(ws + c.stats);
+    a.sel = sel_rows ? sel_rows : (int32_t*)(ws + c.sel);
+    a.alpha = alpha ? alpha : (float*)(ws + c.alpha);
+    a.out = out;
+    a.out_f32 = out_dtype == INSTATTN_F32;
+    hipStream_t s = (hipStream_t)stream;
+    if (launch_sparf_logits(a, s) != hipSuccess) return INSTATTN_ERR_RUNTIME;
+    if (launch_sparf_select(a, s) != hipSuccess) return INSTATTN_ERR_RUNTIME;
+    return status_of(launch_sparf_attend(a, s));
+}
+
+}  // extern "C"

@@ -1,0 +1,46 @@
+// Device-side declarations of the SparF (sparse decode attention) kernels.
+#pragma once
+
+#include "common.h"
+
+namespace instattn {
+
+constexpr int kSparfChunk = 2048;      // positions per block of the approximate-score pass
+constexpr int kSparfSelectThreads = 1024;
+constexpr int kSparfAttendWaves = 8;
+
+// K stored a second time, component-major (the paper's hidden-embedding-indexed
+// copy, Sec. IV-C): element (b, hk, d, t) at b*stride_b + hk*stride_h + d*stride_d + t.
+struct KtView {
+    half_t* kt;
+    int64_t stride_b, stride_h, stride_d;
+    int32_t capacity;                  // positions per (b, hk, d) row, multiple of 8
+    float* vsum;                       // [B][Hkv][D] running sum of the first L_b rows of V
+};
+
+struct SparfArgs {
+    const half_t* q;                   // [B][Hq][D]
+    KvView kv;                         // contiguous layout only
+    KtView aux;
+    const int32_t* seq_lens;
+    int32_t batch, num_q_heads, num_kv_heads, head_dim, max_len;
+    float scale_log2;
+    int32_t r, k, l;
+    float* logits;                     // [B][Hq][lpad] approximate scores, log2 domain
+    int32_t lpad, nchunk;
+    float* stats;                      // [B][Hq][nchunk][2]: block max, sum of 2^(x - max)
+    int32_t* sel;                      // [B][Hq][k] selected rows, ascending
+    float* alpha;                      // [B][Hq] selected share of the approximate softmax
+    void* out;
+    int32_t out_f32;
+    const half_t* k_new;               // append only
+    const half_t* v_new;
+};
+
+hipError_t launch_sparf_build(const SparfArgs& a, hipStream_t stream);
+hipError_t launch_sparf_append(const SparfArgs& a, hipStream_t stream);
+hipError_t launch_sparf_logits(const SparfArgs& a, hipStream_t stream);
+hipError_t launch_sparf_select(const SparfArgs& a, hipStream_t stream);
+hipError_t launch_sparf_attend(const SparfArgs& a, hipStream_t stream);
+
+}  // namespace instattn

@@ -24,7 +24,8 @@ def test_library_exports_every_declared_symbol():
     assert {"instattn_kv_append", "instattn_decode", "instattn_decode_partial",
             "instattn_decode_merge", "instattn_decode_plan", "instattn_decode_workspace_size",
             "instattn_status_string", "instattn_version", "instattn_probe_read",
-            "instattn_append_decode",
+            "instattn_append_decode", "instattn_sparf_build", "instattn_sparf_append",
+            "instattn_sparf_decode", "instattn_sparf_workspace_size",
             "instattn_probe_copy"} <= set(names)
     lib = B.lib()
     for n in names:
@@ -155,3 +156,54 @@ def test_forced_chunk_env(monkeypatch):
     assert B.decode_plan(16, 40, 40, 128, 4097) == (512, 9)
     monkeypatch.delenv("INSTATTN_CHUNK")
     assert B.decode_plan(16, 40, 40, 128, 4097) == (4224, 1)
+
+
+# ------------------------------------------------------------------ SparF entry points
+def aux_desc(**kw):
+    a = B.SparfAux()
+    a.kt, a.vsum = FAKE, FAKE
+    a.stride_b, a.stride_h, a.stride_d = 40 * 128 * 4112, 128 * 4112, 4112
+    a.capacity, a.reserved = 4112, 0
+    for k, v in kw.items():
+        setattr(a, k, v)
+    return a
+
+
+def sparf_status(d=None, a=None, q=FAKE, seq=FAKE, batch=16, hq=40, hkv=40, dim=128, scale=0.088,
+                 r=16, k=256, l=16, out=FAKE, out_dtype=B.F16, ws=FAKE & ~255, ws_bytes=1 << 30,
+                 max_len=4097):
+    d = desc() if d is None else d
+    a = aux_desc() if a is None else a
+    return B.lib().instattn_sparf_decode(q, ctypes.byref(d), ctypes.byref(a), seq, batch, hq, hkv, dim,
+                                         scale, r, k, l, out, out_dtype, None, None, ws, ws_bytes,
+                                         max_len, None)
+
+
+@pytest.mark.parametrize("kw,want", [
+    (dict(q=None), B.ERR_INVALID_ARG), (dict(seq=None), B.ERR_INVALID_ARG),
+    (dict(out=None), B.ERR_INVALID_ARG), (dict(r=0), B.ERR_INVALID_ARG),
+    (dict(r=129), B.ERR_INVALID_ARG), (dict(k=0), B.ERR_INVALID_ARG), (dict(l=-1), B.ERR_INVALID_ARG),
+    (dict(dim=96), B.ERR_UNSUPPORTED), (dict(hq=40, hkv=16), B.ERR_INVALID_ARG),
+    (dict(max_len=5000), B.ERR_INVALID_ARG), (dict(out_dtype=3), B.ERR_INVALID_ARG),
+    (dict(ws=None), B.ERR_WORKSPACE), (dict(ws_bytes=4096), B.ERR_WORKSPACE),
+    (dict(d=paged_desc()), B.ERR_UNSUPPORTED),
+    (dict(a=aux_desc(kt=None)), B.ERR_INVALID_ARG), (dict(a=aux_desc(vsum=None)), B.ERR_INVALID_ARG),
+    (dict(a=aux_desc(capacity=4100)), B.ERR_INVALID_ARG), (dict(a=aux_desc(stride_d=4000)), B.ERR_INVALID_ARG),
+    (dict(a=aux_desc(reserved=1)), B.ERR_INVALID_ARG), (dict(a=aux_desc(capacity=4000, stride_d=4000)), B.ERR_INVALID_ARG),
+])
+def test_sparf_decode_rejects(kw, want):
+    assert sparf_status(**kw) == want
+
+
+def test_sparf_build_and_append_reject():
+    L = B.lib()
+    d, a = desc(), aux_desc()
+    assert L.instattn_sparf_build(ctypes.byref(d), ctypes.byref(a), None, 16, 40, 128, None) == B.ERR_INVALID_ARG
+    assert L.instattn_sparf_build(None, ctypes.byref(a), FAKE, 16, 40, 128, None) == B.ERR_INVALID_ARG
+    assert L.instattn_sparf_build(ctypes.byref(d), None, FAKE, 16, 40, 128, None) == B.ERR_INVALID_ARG
+    assert L.instattn_sparf_append(ctypes.byref(d), ctypes.byref(a), None, FAKE, FAKE, 16, 40, 128,
+                                   None) == B.ERR_INVALID_ARG
+    assert L.instattn_sparf_append(ctypes.byref(d), ctypes.byref(a), FAKE, FAKE, FAKE, 0, 40, 128,
+                                   None) == B.ERR_INVALID_ARG
+    assert B.sparf_workspace_size(16, 40, 128, 4097, 256) >= 16 * 40 * (6144 + 256 + 1) * 4
+    assert B.sparf_workspace_size(16, 40, 100, 4097, 256) == 0

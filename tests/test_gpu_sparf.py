@@ -1,0 +1,191 @@
+"""GPU parity of the SparF path (Algorithm 1) against its fp64 oracle.
+
+The top-k of steps 1 and 6 is an integer decision taken on floating-point
+scores.  Step 1 compares exact fp16 magnitudes, so the kept components must be
+identical.  Step 6 is taken by the kernel on fp32 scores, the oracle's on fp64
+ones: the two selections may differ only in rows whose score is within the fp32
+rounding of the threshold, so the test checks that the kernel's selection is a
+valid top-k of the oracle's scores up to that rounding, and then compares the
+output with the oracle's steps 7, 10, 11 evaluated on the kernel's selection."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import decode_attention as dense
+from oracle import sparf_attention as sparf
+from paper_2409_04992_amd import binding as B
+from paper_2409_04992_amd import workloads as W
+
+import helpers as H
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+SCORE_EPS = 2e-4          # fp32 rounding of an r-term dot product of magnitude <~ 50, in natural-log units
+
+
+def setup(wl, build_lens_offset=-1):
+    """Caches with S_b valid rows, aux built for them; the step then appends row S_b."""
+    case = W.make_case(wl, DEV, poison=True)
+    Bn, Hkv, cap, D = case.k_cache.shape
+    kt = torch.full((Bn, Hkv, D, cap), float("nan"), dtype=torch.float16, device=DEV)
+    vsum = torch.full((Bn, Hkv, D), float("nan"), dtype=torch.float32, device=DEV)
+    desc, aux = B.kv_desc(case.k_cache, case.v_cache), B.sparf_aux(kt, vsum)
+    before = (case.seq_lens + build_lens_offset).contiguous()
+    B.sparf_build(desc, aux, before, Hkv, D)
+    torch.cuda.synchronize()
+    return case, desc, aux, kt, vsum, before
+
+
+def run_decode(case, desc, aux, r, k, l, out_dtype, max_len=None):
+    wl = case.wl
+    Bn, Hq, D = case.q.shape
+    max_len = max_len or max(1, int(case.seq_lens.max()))
+    ws = torch.empty(B.sparf_workspace_size(Bn, Hq, D, max_len, k), dtype=torch.uint8, device=DEV)
+    ws.fill_(0xFF)
+    out = torch.full((Bn, Hq, D), float("nan"), dtype=out_dtype, device=DEV)
+    sel = torch.full((Bn, Hq, k), -1, dtype=torch.int32, device=DEV)
+    alpha = torch.full((Bn, Hq), float("nan"), dtype=torch.float32, device=DEV)
+    B.sparf_decode(case.q, desc, aux, case.seq_lens, wl.num_kv_heads, case.scale, r, k, l, out, ws,
+                   max_len, sel_rows=sel, alpha=alpha)
+    torch.cuda.synchronize()
+    return out, sel, alpha
+
+
+def check_against_oracle(case, out, sel, alpha, r, k, l, pairs=None):
+    wl = case.wl
+    q, K, V = H.host(case.q), H.host(case.k_cache), H.host(case.v_cache)
+    lens = H.host(case.seq_lens)
+    tol = H.TOL[out.dtype]
+    Bn, Hq, D = q.shape
+    pairs = pairs or [(b, h) for b in range(Bn) for h in range(Hq)]
+    worst = 0.0
+    for b, h in pairs:
+        L = int(lens[b])
+        hk = h // wl.group
+        if L <= 0:
+            assert torch.equal(out[b, h], torch.zeros_like(out[b, h])) and float(alpha[b, h]) == 0.0
+            continue
+        res = sparf.sparf_one(q[b, h], K[b, hk, :L], V[b, hk, :L], case.scale, r, k, l)
+        keff = min(k, L)
+        got_rows = sel[b, h, :keff].cpu().numpy().astype(np.int64)
+        assert (np.diff(got_rows) > 0).all() and got_rows[0] >= 0 and got_rows[-1] < L
+        leff = min(l, keff)
+        assert set(range(L - leff, L)) <= set(got_rows)            # step 5
+        # step 6: a valid top-k of the oracle's scores up to fp32 rounding
+        want_rows = set(res["j_rows"].tolist())
+        lg = res["logits_hat"]
+        cand = np.array(sorted(want_rows - set(range(L - leff, L))))
+        if len(cand):
+            thr = lg[cand].min()
+            for t in set(got_rows.tolist()) - want_rows:
+                assert lg[t] >= thr - SCORE_EPS, (b, h, t)
+            for t in want_rows - set(got_rows.tolist()):
+                assert lg[t] <= thr + SCORE_EPS, (b, h, t)
+        # steps 7, 10, 11 on the kernel's own selection
+        want_out, want_alpha = sparf.finish_from_selection(q[b, h], K[b, hk, :L], V[b, hk, :L],
+                                                           case.scale, res["s_hat"], got_rows, res["vbar"])
+        assert abs(float(alpha[b, h]) - want_alpha) <= 2e-5
+        err = np.abs(out[b, h].double().cpu().numpy() - want_out).max()
+        worst = max(worst, err)
+        assert err <= tol, "(%d,%d): %.3e" % (b, h, err)
+    return worst
+
+
+def sparf_step(wl, r, k, l, out_dtype=torch.float32, pairs=None):
+    case, desc, aux, kt, vsum, before = setup(wl)
+    want_k, want_v = H.host(case.k_cache).copy(), H.host(case.v_cache).copy()
+    dense.kv_append(want_k, want_v, H.host(case.k_new), H.host(case.v_new), H.host(case.seq_lens))
+    B.sparf_append(desc, aux, case.k_new, case.v_new, case.seq_lens)
+    out, sel, alpha = run_decode(case, desc, aux, r, k, l, out_dtype)
+    # the append part: caches bit-exact, column copy and V sums consistent with them
+    assert np.array_equal(H.host(case.k_cache).view(np.uint16), want_k.view(np.uint16))
+    assert np.array_equal(H.host(case.v_cache).view(np.uint16), want_v.view(np.uint16))
+    lens = H.host(case.seq_lens)
+    for b in range(case.wl.batch):
+        L = int(lens[b])
+        if L < 1:
+            continue
+        assert torch.equal(kt[b, :, :, :L].view(torch.int16),
+                           case.k_cache[b, :, :L].transpose(1, 2).contiguous().view(torch.int16))
+        ref = want_v[b, :, :L].astype(np.float64).sum(axis=1)
+        np.testing.assert_allclose(vsum[b].double().cpu().numpy(), ref, rtol=0, atol=2e-3)
+    return check_against_oracle(case, out, sel, alpha, r, k, l, pairs)
+
+
+# ------------------------------------------------------------------ parity
+@pytest.mark.parametrize("r,k,l", [(16, 64, 8), (8, 128, 0), (128, 32, 4), (1, 16, 16), (32, 700, 3)])
+@pytest.mark.parametrize("out_dtype", [torch.float32, torch.float16])
+def test_sparf_mha_small(r, k, l, out_dtype):
+    wl = W.Workload("sparf_mha", 3, 4, 4, 128, 1500, seq_len_min=300, seed=401)
+    sparf_step(wl, r, k, l, out_dtype)
+
+
+@pytest.mark.parametrize("head_dim,group", [(64, 1), (64, 4), (128, 8)])
+def test_sparf_head_dims_and_groups(head_dim, group):
+    wl = W.Workload("sparf_g", 2, 2 * group, 2, head_dim, 900, seq_len_min=100, seed=402)
+    sparf_step(wl, head_dim // 8, 96, 8)
+
+
+@pytest.mark.parametrize("seq_len", [0, 1, 7, 8, 9, 63, 64, 2047, 2048, 2049, 5000])
+def test_sparf_lengths_around_vector_and_block_edges(seq_len):
+    wl = W.Workload("sparf_len", 2, 2, 2, 128, seq_len, seed=403)
+    sparf_step(wl, 16, 40, 5)
+
+
+def test_sparf_keeping_every_row_equals_dense_decode():
+    wl = W.Workload("sparf_all", 2, 4, 4, 128, 800, seq_len_min=200, seed=404)
+    case, desc, aux, kt, vsum, _ = setup(wl)
+    B.sparf_append(desc, aux, case.k_new, case.v_new, case.seq_lens)
+    out, sel, alpha = run_decode(case, desc, aux, 16, 1024, 4, torch.float32)
+    ref, _ = H.gpu_step(case, out_dtype=torch.float32, append=False)
+    assert (out - ref).abs().max() <= 1e-5
+    assert (alpha - 1).abs().max() <= 1e-5
+    for b in range(2):
+        L = int(case.seq_lens[b])
+        assert torch.equal(sel[b, :, :L].cpu(), torch.arange(L, dtype=torch.int32).expand(4, L))
+
+
+def test_sparf_empty_and_mixed_lengths():
+    wl = W.Workload("sparf_mixed", 4, 2, 2, 128, 600, seed=405)
+    case, desc, aux, kt, vsum, _ = setup(wl)
+    case.seq_lens = torch.tensor([0, 601, 1, -2], dtype=torch.int32, device=DEV)
+    B.sparf_build(desc, aux, (case.seq_lens - 1).contiguous(), 2, 128)
+    B.sparf_append(desc, aux, case.k_new, case.v_new, case.seq_lens)
+    out, sel, alpha = run_decode(case, desc, aux, 16, 50, 2, torch.float32, max_len=601)
+    check_against_oracle(case, out, sel, alpha, 16, 50, 2)
+    assert torch.equal(out[2].view(torch.int32), case.v_new[2].float().view(torch.int32))   # L = 1
+
+
+def test_sparf_13b_shape_one_eighth(monkeypatch):
+    """The 13B-shaped layer at the paper's 1/8 compression (r = 16 of 128 columns,
+    k = 256 of 4097 rows, 16 most recent kept): sampled heads against the oracle."""
+    wl = W.WORKLOADS["mha13b_4k"]
+    pairs = [(0, 0), (3, 17), (15, 39), (7, 8), (11, 21), (9, 30)]
+    sparf_step(wl, 16, 256, 16, torch.float16, pairs=pairs)
+
+
+def test_sparf_is_deterministic():
+    wl = W.Workload("sparf_det", 2, 4, 4, 128, 3000, seed=406)
+    case, desc, aux, kt, vsum, _ = setup(wl)
+    B.sparf_append(desc, aux, case.k_new, case.v_new, case.seq_lens)
+    a = run_decode(case, desc, aux, 16, 200, 8, torch.float16)
+    b = run_decode(case, desc, aux, 16, 200, 8, torch.float16)
+    assert all(torch.equal(x, y) for x, y in zip(a, b))
+
+
+def test_sparf_ties_go_to_the_lower_position():
+    """Identical keys: every score ties, so the kept rows are the first k - l and the
+    last l positions, and the output is alpha * mean(V kept) + (1 - alpha) * mean(V)."""
+    wl = W.Workload("sparf_ties", 1, 2, 2, 128, 299, seed=407)
+    case, desc, aux, kt, vsum, _ = setup(wl)
+    case.k_cache[:] = case.k_cache[:, :, :1]
+    case.k_new[:] = case.k_cache[:, :, 0]
+    B.sparf_build(desc, aux, (case.seq_lens - 1).contiguous(), 2, 128)
+    B.sparf_append(desc, aux, case.k_new, case.v_new, case.seq_lens)
+    out, sel, alpha = run_decode(case, desc, aux, 16, 40, 6, torch.float32)
+    want = torch.cat([torch.arange(34), torch.arange(294, 300)]).to(torch.int32)
+    assert torch.equal(sel[0, 0].cpu(), want) and torch.equal(sel[0, 1].cpu(), want)
+    assert (alpha - 40 / 300).abs().max() < 1e-6
+    V = case.v_cache[0, :, :300].double()
+    ref = (40 / 300) * V[:, want.long()].mean(dim=1) + (1 - 40 / 300) * V.mean(dim=1)
+    assert (out[0].double() - ref).abs().max() < 1e-5
