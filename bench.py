@@ -37,6 +37,9 @@ def parse():
     ap.add_argument("--layers-resident", type=int, default=8,
                     help="distinct layer caches the steps rotate over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sparf", default=None, metavar="r,k,l",
+                    help="time the SparF path (Algorithm 1) with these parameters instead of the "
+                         "dense path, next to the dense step on the same caches")
     ap.add_argument("--two-calls", action="store_true",
                     help="step = instattn_kv_append + instattn_decode instead of instattn_append_decode")
     return ap.parse_args()
@@ -83,12 +86,82 @@ def cpu_baseline(cases, kv_bytes_layer, positions_layer):
     }
 
 
+def bench_sparf(args):
+    """SparF step (sparf_append + sparf_decode) against the dense step on the same caches."""
+    import torch
+    from paper_2409_04992_amd import binding as B
+    from paper_2409_04992_amd import workloads as W
+    dev = "cuda:0"
+    r, k, l = (int(x) for x in args.sparf.split(","))
+    wl = W.WORKLOADS[args.workload]
+    assert not wl.paged, "the SparF path takes contiguous caches"
+    R = max(1, args.layers_resident)
+    steps = args.steps or 200
+    warmup = args.warmup or 20
+    cases = [W.make_case(wl, dev, layer=i) for i in range(R)]
+    descs = [B.kv_desc(c.k_cache, c.v_cache) for c in cases]
+    auxs, keep = [], []
+    for c, d in zip(cases, descs):
+        Bn, Hkv, cap, D = c.k_cache.shape
+        kt = torch.zeros(Bn, Hkv, D, cap, dtype=torch.float16, device=dev)
+        vsum = torch.zeros(Bn, Hkv, D, dtype=torch.float32, device=dev)
+        a = B.sparf_aux(kt, vsum)
+        B.sparf_build(d, a, (c.seq_lens - 1).contiguous(), Hkv, D)
+        auxs.append(a)
+        keep.append((kt, vsum))
+    max_len = int(cases[0].seq_lens.max().item())
+    lens = cases[0].seq_lens.cpu().tolist()
+    D, Hq = wl.head_dim, wl.num_q_heads
+    ws = torch.empty(B.sparf_workspace_size(wl.batch, Hq, D, max_len, k), dtype=torch.uint8, device=dev)
+    wsd = B.alloc_workspace(wl.batch, Hq, wl.num_kv_heads, D, max_len, dev)
+    out = torch.empty(wl.batch, Hq, D, dtype=torch.float16, device=dev)
+    dense_bytes = cases[0].kv_read_bytes()
+    sparf_bytes = sum(Hq * 2 * (r * L + 2 * min(k, L) * D) for L in lens)
+    score_bytes = sum(Hq * 4 * L * 2 for L in lens)          # fp32 scores written, then read by the selection
+
+    def sparf_step(i):
+        c, d, a = cases[i % R], descs[i % R], auxs[i % R]
+        B.sparf_append(d, a, c.k_new, c.v_new, c.seq_lens)
+        B.sparf_decode(c.q, d, a, c.seq_lens, wl.num_kv_heads, c.scale, r, k, l, out, ws, max_len)
+
+    def dense_step(i):
+        c, d = cases[i % R], descs[i % R]
+        B.append_decode(c.q, c.k_new, c.v_new, d, c.seq_lens, wl.num_kv_heads, c.scale, out, wsd, max_len)
+
+    def timed(fn):
+        for i in range(warmup):
+            fn(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            fn(i)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps
+
+    t_sparf, t_dense = timed(sparf_step), timed(dense_step)
+    res = {
+        "metric": "sparf_decode_attention_dense_equivalent_kv_bandwidth",
+        "value": dense_bytes / t_sparf / 1e9, "unit": "GB/s", "n_gpus": 1, "steps": steps,
+        "warmup": warmup, "ms_per_step": t_sparf * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "config": {"workload": wl.name, "r": r, "k": k, "l": l, "layers_resident": R,
+                   "step": "sparf_append + sparf_decode (column scores, selection, gather attention)"},
+        "dense_ms_per_step": t_dense * 1e3, "speedup_over_dense_step": t_dense / t_sparf,
+        "bytes_read_algorithm1": sparf_bytes, "bytes_read_dense": dense_bytes,
+        "compression": sparf_bytes / dense_bytes, "score_bytes_written_and_read": score_bytes,
+        "achieved_GBps_algorithm1_bytes": sparf_bytes / t_sparf / 1e9,
+    }
+    print(json.dumps(res), flush=True)
+
+
 def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
               "use --gpus 1", file=sys.stderr)
         sys.exit(2)
+    if args.sparf:
+        return bench_sparf(args)
 
     import torch
     from paper_2409_04992_amd import binding as B

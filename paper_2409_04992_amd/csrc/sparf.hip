@@ -129,7 +129,7 @@ __global__ __launch_bounds__(256) void sparf_logits_kernel(SparfArgs a)
     for (int e = 0; e < 8; ++e) x[e] = 0.f;
     if (t < L) {
         const half_t* base = a.aux.kt + (int64_t)b * a.aux.stride_b + (int64_t)hk * a.aux.stride_h + t;
-#pragma unroll 4
+#pragma unroll 8
         for (int j = 0; j < a.r; ++j) {
             const int d = s_dim[j];
             const float qd = s_q[d];
@@ -160,10 +160,11 @@ __global__ __launch_bounds__(256) void sparf_logits_kernel(SparfArgs a)
 }
 
 // ---------------------------------------------------------------------------
-// Steps 4 (normaliser) to 7.
-__global__ __launch_bounds__(kSparfSelectThreads) void sparf_select_kernel(SparfArgs a)
+// Steps 4 (normaliser) to 7.  NT threads per block: 256 for short rows (more blocks
+// per CU, cheaper barriers), 1024 for long ones.
+template <int NT>
+__global__ __launch_bounds__(NT) void sparf_select_kernel(SparfArgs a)
 {
-    constexpr int NT = kSparfSelectThreads;
     constexpr int NW = NT / 64;
     const int h = blockIdx.x, b = blockIdx.y;
     const int tid = threadIdx.x;
@@ -208,20 +209,35 @@ __global__ __launch_bounds__(kSparfSelectThreads) void sparf_select_kernel(Sparf
                 if ((key & hi_mask) == (prefix & hi_mask)) atomicAdd(&s_hist[(key >> shift) & 255u], 1u);
             }
             __syncthreads();
-            if (tid == 0) {
-                uint32_t above = 0;
-                int bin = 255;
-                for (; bin > 0; --bin) {
-                    if (above + s_hist[bin] >= remaining) break;
-                    above += s_hist[bin];
+            if (wave == 0) {
+                // lane i owns bins 4i .. 4i+3; suffix sums over the lanes find the bin
+                // that holds the remaining-th largest key
+                const uint32_t c0 = s_hist[4 * lane], c1 = s_hist[4 * lane + 1];
+                const uint32_t c2 = s_hist[4 * lane + 2], c3 = s_hist[4 * lane + 3];
+                const uint32_t mine = c0 + c1 + c2 + c3;
+                uint32_t suffix = mine;                       // inclusive, over lanes >= this one
+#pragma unroll
+                for (int d = 1; d < 64; d <<= 1) {
+                    const uint32_t o = __shfl_down(suffix, d, 64);
+                    if (lane + d < 64) suffix += o;
                 }
-                s_prefix = prefix | ((uint32_t)bin << shift);
-                s_remaining = remaining - above;
+                uint32_t above = suffix - mine;               // keys in bins above this lane's
+                if (above < remaining && remaining <= suffix) {
+                    int bin = 4 * lane + 3;
+                    const uint32_t cs[4] = {c0, c1, c2, c3};
+#pragma unroll
+                    for (int j = 3; j > 0; --j) {
+                        if (above + cs[j] >= remaining) break;
+                        above += cs[j];
+                        --bin;
+                    }
+                    s_prefix = prefix | ((uint32_t)bin << shift);
+                    s_remaining = remaining - above;
+                }
             }
             __syncthreads();
             prefix = s_prefix;
             remaining = s_remaining;
-            __syncthreads();
         }
     }
 
@@ -241,6 +257,7 @@ __global__ __launch_bounds__(kSparfSelectThreads) void sparf_select_kernel(Sparf
         if (lane == 0) s_wtot[0][wave] = (uint32_t)__popcll(eq_bal);
         __syncthreads();
         uint32_t eq_before = eq_base, eq_tile = 0;
+#pragma unroll
         for (int w = 0; w < NW; ++w) {
             const uint32_t c = s_wtot[0][w];
             if (w < wave) eq_before += c;
@@ -252,6 +269,7 @@ __global__ __launch_bounds__(kSparfSelectThreads) void sparf_select_kernel(Sparf
         if (lane == 0) s_wtot[1][wave] = (uint32_t)__popcll(tk_bal);
         __syncthreads();
         uint32_t pos = out_base, tk_tile = 0;
+#pragma unroll
         for (int w = 0; w < NW; ++w) {
             const uint32_t c = s_wtot[1][w];
             if (w < wave) pos += c;
@@ -264,12 +282,11 @@ __global__ __launch_bounds__(kSparfSelectThreads) void sparf_select_kernel(Sparf
         }
         eq_base += eq_tile;
         out_base += tk_tile;
-        __syncthreads();
     }
     // Step 5: the l most recent positions are always kept.
-    if (tid < leff) {
-        const int t = ncand + tid;
-        sel[want + tid] = t;
+    for (int i = tid; i < leff; i += NT) {
+        const int t = ncand + i;
+        sel[want + i] = t;
         mass += fast_exp2(x[t] - M);
     }
     mass = block_sum(mass, s_red);
@@ -465,8 +482,9 @@ hipError_t launch_sparf_logits(const SparfArgs& a, hipStream_t stream)
 
 hipError_t launch_sparf_select(const SparfArgs& a, hipStream_t stream)
 {
-    hipLaunchKernelGGL(sparf_select_kernel, dim3(a.num_q_heads, a.batch), dim3(kSparfSelectThreads), 0,
-                       stream, a);
+    dim3 grid(a.num_q_heads, a.batch);
+    if (a.max_len <= 8192) hipLaunchKernelGGL(sparf_select_kernel<256>, grid, dim3(256), 0, stream, a);
+    else hipLaunchKernelGGL(sparf_select_kernel<1024>, grid, dim3(1024), 0, stream, a);
     return hipGetLastError();
 }
 
