@@ -40,6 +40,8 @@ def parse():
     ap.add_argument("--sparf", default=None, metavar="r,k,l",
                     help="time the SparF path (Algorithm 1) with these parameters instead of the "
                          "dense path, next to the dense step on the same caches")
+    ap.add_argument("--kv-write", action="store_true",
+                    help="time instattn_kv_write of a whole prompt (the prefill-side bulk store)")
     ap.add_argument("--two-calls", action="store_true",
                     help="step = instattn_kv_append + instattn_decode instead of instattn_append_decode")
     return ap.parse_args()
@@ -154,6 +156,44 @@ def bench_sparf(args):
     print(json.dumps(res), flush=True)
 
 
+def bench_kv_write(args):
+    """Bulk store of seq_len prompt rows per sequence into the cache (one layer)."""
+    import torch
+    from paper_2409_04992_amd import binding as B
+    from paper_2409_04992_amd import workloads as W
+    dev = "cuda:0"
+    wl = W.WORKLOADS[args.workload]
+    steps, warmup = args.steps or 50, args.warmup or 5
+    R = 3
+    cases = [W.make_case(wl, dev, layer=i) for i in range(R)]
+    descs = [B.kv_desc(c.k_cache, c.v_cache, c.page_table) for c in cases]
+    S = wl.seq_len
+    srcs = [(torch.randn(wl.batch, wl.num_kv_heads, S, wl.head_dim, device=dev).half(),
+             torch.randn(wl.batch, wl.num_kv_heads, S, wl.head_dim, device=dev).half()) for _ in range(R)]
+    start = torch.zeros(wl.batch, dtype=torch.int32, device=dev)
+    count = (cases[0].seq_lens - 1).contiguous()
+    nbytes = int(count.sum().item()) * wl.num_kv_heads * wl.head_dim * 2 * 2
+
+    def step(i):
+        B.kv_write(descs[i % R], srcs[i % R][0], srcs[i % R][1], start, count)
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(i)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / steps
+    print(json.dumps({
+        "metric": "kv_write_bandwidth_read_plus_write", "value": 2 * nbytes / dt / 1e9, "unit": "GB/s",
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": dt * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16",
+        "data": "synthetic", "config": {"workload": wl.name, "rows_per_sequence": "seq_len",
+                                        "kv_layout": "paged16" if wl.paged else "contiguous"},
+        "bytes_stored": nbytes, "pct_of_hbm_peak": 100.0 * 2 * nbytes / dt / 1e9 / HBM_PEAK_GBPS}), flush=True)
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -162,6 +202,8 @@ def main():
         sys.exit(2)
     if args.sparf:
         return bench_sparf(args)
+    if args.kv_write:
+        return bench_kv_write(args)
 
     import torch
     from paper_2409_04992_amd import binding as B

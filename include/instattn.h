@@ -95,6 +95,20 @@ int instattn_kv_append(const instattn_kv_desc* kv, const void* k_new, const void
                        void* stream);
 
 /*
+ * Store a run of rows per sequence: the prefill side of Sec. IV-D, where a layer's
+ * K and V for all prompt tokens are handed over at once.  For every b, hk and
+ * i < min(count[b], max_new), copies k_src[b][hk][i][:] and v_src[b][hk][i][:] bit
+ * for bit into position start[b] + i; positions outside [0, capacity) are
+ * skipped.  Equivalent to calling instattn_kv_append once per row.
+ *   k_src, v_src : device, [batch][num_kv_heads][max_new][head_dim] fp16, dense, 16-byte aligned
+ *   start, count : device, [batch] int32, not modified
+ * head_dim 64 or 128.  One launch.
+ */
+int instattn_kv_write(const instattn_kv_desc* kv, const void* k_src, const void* v_src,
+                      const int32_t* start, const int32_t* count, int batch, int num_kv_heads,
+                      int head_dim, int max_new, void* stream);
+
+/*
  * How decode cuts the sequence axis (host arithmetic only; no device access).
  * Work is split into units of `chunk_tokens` consecutive positions so that a
  * single long sequence still fills the chip; unit i of sequence b covers

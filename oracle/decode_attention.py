@@ -67,6 +67,33 @@ def kv_append(k_cache, v_cache, k_new, v_new, seq_lens, page_table=None) -> None
                 v_cache[page, hk, t % ps, :] = v_new[b, hk, :]
 
 
+def kv_write(k_cache, v_cache, k_src, v_src, start, count, page_table=None) -> None:
+    """Store a run of rows per sequence (bit copy, in place): row start[b] + i of
+    every KV head receives k_src[b, :, i, :] / v_src[b, :, i, :] for i < count[b].
+
+    This is the prefill side of Sec. IV-D: a layer's K and V for all prompt tokens
+    arrive at once and are laid down behind whatever is already stored.  Rows that
+    would fall outside [0, capacity) are skipped; by definition it is what
+    kv_append does when called once per row."""
+    assert k_src.dtype == np.float16 and v_src.dtype == np.float16
+    B, Hkv, N, D = k_src.shape
+    cap = _capacity(k_cache, page_table)
+    for b in range(B):
+        for i in range(min(int(count[b]), N)):
+            t = int(start[b]) + i
+            if t < 0 or t >= cap:
+                continue
+            for hk in range(Hkv):
+                if page_table is None:
+                    k_cache[b, hk, t, :] = k_src[b, hk, i, :]
+                    v_cache[b, hk, t, :] = v_src[b, hk, i, :]
+                else:
+                    ps = k_cache.shape[2]
+                    page = int(page_table[b, t // ps])
+                    k_cache[page, hk, t % ps, :] = k_src[b, hk, i, :]
+                    v_cache[page, hk, t % ps, :] = v_src[b, hk, i, :]
+
+
 def gather_rows(cache, b: int, hk: int, L: int, page_table=None) -> np.ndarray:
     """The first L rows [L, D] (float16) of sequence b, KV head hk."""
     if page_table is None:

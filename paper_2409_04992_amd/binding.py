@@ -67,6 +67,8 @@ def lib() -> ctypes.CDLL:
         L.instattn_status_string.argtypes = [i]
         L.instattn_kv_append.restype = i
         L.instattn_kv_append.argtypes = [ctypes.POINTER(KvDesc), vp, vp, vp, i, i, i, vp]
+        L.instattn_kv_write.restype = i
+        L.instattn_kv_write.argtypes = [ctypes.POINTER(KvDesc), vp, vp, vp, vp, i, i, i, i, vp]
         L.instattn_decode_plan.restype = i
         L.instattn_decode_plan.argtypes = [i, i, i, i, i, ctypes.POINTER(i), ctypes.POINTER(i)]
         L.instattn_decode_workspace_size.restype = sz
@@ -152,6 +154,15 @@ def kv_append(desc: KvDesc, k_new: torch.Tensor, v_new: torch.Tensor, seq_lens: 
     assert k_new.is_contiguous() and v_new.is_contiguous() and seq_lens.dtype == torch.int32
     _check(lib().instattn_kv_append(ctypes.byref(desc), _p(k_new), _p(v_new), _p(seq_lens),
                                     B, Hkv, D, _stream(stream)), "instattn_kv_append")
+
+
+def kv_write(desc: KvDesc, k_src: torch.Tensor, v_src: torch.Tensor, start: torch.Tensor,
+             count: torch.Tensor, stream=None) -> None:
+    B, Hkv, N, D = k_src.shape
+    assert k_src.is_contiguous() and v_src.is_contiguous() and k_src.dtype == torch.float16
+    assert start.dtype == torch.int32 and count.dtype == torch.int32
+    _check(lib().instattn_kv_write(ctypes.byref(desc), _p(k_src), _p(v_src), _p(start), _p(count),
+                                   B, Hkv, D, N, _stream(stream)), "instattn_kv_write")
 
 
 def decode_plan(batch: int, num_q_heads: int, num_kv_heads: int, head_dim: int,

@@ -175,6 +175,30 @@ int instattn_kv_append(const instattn_kv_desc* kv, const void* k_new, const void
     return launch_kv_append(a, (hipStream_t)stream) == hipSuccess ? INSTATTN_OK : INSTATTN_ERR_RUNTIME;
 }
 
+int instattn_kv_write(const instattn_kv_desc* kv, const void* k_src, const void* v_src,
+                      const int32_t* start, const int32_t* count, int batch, int num_kv_heads,
+                      int head_dim, int max_new, void* stream)
+{
+    if (batch <= 0 || num_kv_heads <= 0 || max_new <= 0) return INSTATTN_ERR_INVALID_ARG;
+    if (head_dim != 64 && head_dim != 128) return head_dim > 0 ? INSTATTN_ERR_UNSUPPORTED : INSTATTN_ERR_INVALID_ARG;
+    if (batch > 65535 || num_kv_heads > 65535) return INSTATTN_ERR_UNSUPPORTED;
+    int st = check_kv(kv, head_dim);
+    if (st != INSTATTN_OK) return st;
+    if (!k_src || !v_src || !start || !count || !aligned16(k_src) || !aligned16(v_src))
+        return INSTATTN_ERR_INVALID_ARG;
+    WriteArgs a;
+    a.kv = make_view(kv);
+    a.k_src = (const half_t*)k_src;
+    a.v_src = (const half_t*)v_src;
+    a.start = start;
+    a.count = count;
+    a.batch = batch;
+    a.num_kv_heads = num_kv_heads;
+    a.head_dim = head_dim;
+    a.max_new = max_new;
+    return launch_kv_write(a, (hipStream_t)stream) == hipSuccess ? INSTATTN_OK : INSTATTN_ERR_RUNTIME;
+}
+
 int instattn_decode_plan(int batch, int num_q_heads, int num_kv_heads, int head_dim,
                          int max_seq_len, int* chunk_tokens, int* num_splits)
 {

@@ -77,11 +77,22 @@ struct AppendArgs {
     int32_t batch, num_kv_heads, head_dim;
 };
 
+// Arguments of the bulk KV write (prefill side): rows start[b] .. start[b]+count[b]-1.
+struct WriteArgs {
+    KvView kv;
+    const half_t* k_src;   // [B][Hkv][max_new][D]
+    const half_t* v_src;
+    const int32_t* start;
+    const int32_t* count;
+    int32_t batch, num_kv_heads, head_dim, max_new;
+};
+
 // Launchers (one per kernel family); each returns hipGetLastError() of its launch.
 hipError_t launch_decode_mha(const DecodeArgs& a, int batch, int head_dim, hipStream_t stream);
 hipError_t launch_decode_gqa(const DecodeArgs& a, int batch, int head_dim, hipStream_t stream);
 hipError_t launch_merge(const MergeArgs& a, int batch, int head_dim, hipStream_t stream);
 hipError_t launch_kv_append(const AppendArgs& a, hipStream_t stream);
+hipError_t launch_kv_write(const WriteArgs& a, hipStream_t stream);
 hipError_t launch_probe_read(const void* src, size_t bytes, void* sink, hipStream_t stream);
 hipError_t launch_probe_copy(const void* src, void* dst, size_t bytes, hipStream_t stream);
 

@@ -79,6 +79,33 @@ hipError_t launch_kv_append(const AppendArgs& a, hipStream_t stream)
 }
 
 // ---------------------------------------------------------------------------
+// Bulk KV write: one thread moves 16 bytes of K and of V; a block covers 16 rows of
+// one (sequence, KV head), i.e. one 4 KB page-sized group of each tensor.
+__global__ __launch_bounds__(256) void kv_write_kernel(WriteArgs a)
+{
+    const int cols = a.head_dim / 8;
+    const int rows_per_block = 256 / cols;
+    const int hk = blockIdx.y, b = blockIdx.z;
+    const int i = blockIdx.x * rows_per_block + threadIdx.x / cols;   // row inside the source run
+    const int c = threadIdx.x % cols;
+    if (i >= a.max_new || i >= a.count[b]) return;
+    const int t = a.start[b] + i;
+    if (t < 0 || t >= a.kv.capacity) return;
+    const int64_t src = (((int64_t)b * a.num_kv_heads + hk) * a.max_new + i) * a.head_dim + c * 8;
+    const int64_t dst = row_offset(a.kv, b, hk, t) + c * 8;
+    *(u32x4*)(const_cast<half_t*>(a.kv.k) + dst) = __builtin_nontemporal_load((const u32x4*)(a.k_src + src));
+    *(u32x4*)(const_cast<half_t*>(a.kv.v) + dst) = __builtin_nontemporal_load((const u32x4*)(a.v_src + src));
+}
+
+hipError_t launch_kv_write(const WriteArgs& a, hipStream_t stream)
+{
+    const int rows_per_block = 256 / (a.head_dim / 8);
+    dim3 grid((a.max_new + rows_per_block - 1) / rows_per_block, a.num_kv_heads, a.batch);
+    hipLaunchKernelGGL(kv_write_kernel, grid, dim3(256), 0, stream, a);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
 // Measurement kernels: a pure streaming read and a plain copy.
 constexpr int kProbeBlocks = 4096;
 constexpr size_t kProbeSeg16 = 16384;   // 16-byte words per block segment (256 KiB)

@@ -24,7 +24,7 @@ def test_library_exports_every_declared_symbol():
     assert {"instattn_kv_append", "instattn_decode", "instattn_decode_partial",
             "instattn_decode_merge", "instattn_decode_plan", "instattn_decode_workspace_size",
             "instattn_status_string", "instattn_version", "instattn_probe_read",
-            "instattn_append_decode", "instattn_sparf_build", "instattn_sparf_append",
+            "instattn_append_decode", "instattn_kv_write", "instattn_sparf_build", "instattn_sparf_append",
             "instattn_sparf_decode", "instattn_sparf_workspace_size",
             "instattn_probe_copy"} <= set(names)
     lib = B.lib()
@@ -207,3 +207,17 @@ def test_sparf_build_and_append_reject():
                                    None) == B.ERR_INVALID_ARG
     assert B.sparf_workspace_size(16, 40, 128, 4097, 256) >= 16 * 40 * (6144 + 256 + 1) * 4
     assert B.sparf_workspace_size(16, 40, 100, 4097, 256) == 0
+
+
+def test_kv_write_rejects():
+    L = B.lib()
+    d = desc()
+    ok = [ctypes.byref(d), FAKE, FAKE, FAKE, FAKE, 16, 40, 128, 512, None]
+    for idx, bad, want in [(1, None, B.ERR_INVALID_ARG), (2, None, B.ERR_INVALID_ARG),
+                           (3, None, B.ERR_INVALID_ARG), (4, None, B.ERR_INVALID_ARG),
+                           (1, FAKE + 2, B.ERR_INVALID_ARG), (5, 0, B.ERR_INVALID_ARG),
+                           (6, 0, B.ERR_INVALID_ARG), (7, 96, B.ERR_UNSUPPORTED),
+                           (8, 0, B.ERR_INVALID_ARG), (0, None, B.ERR_INVALID_ARG)]:
+        args = list(ok)
+        args[idx] = bad
+        assert L.instattn_kv_write(*args) == want, idx

@@ -395,6 +395,36 @@ def test_append_paged_lands_behind_the_page_table(impl):
     assert np.array_equal(bits(vp)[~changed], bits(v0)[~changed])
 
 
+def test_bulk_write_equals_one_append_per_row():
+    """kv_write is by definition kv_append applied row by row (checked against the
+    plain-C append too), for both layouts, with runs that start anywhere, overrun
+    the capacity or are empty."""
+    r = rng(40)
+    B, Hkv, D, N, ps = 3, 2, 8, 7, 4
+    k_src = r.integers(0, 65536, size=(B, Hkv, N, D)).astype(np.uint16).view(np.float16)
+    v_src = r.integers(0, 65536, size=(B, Hkv, N, D)).astype(np.uint16).view(np.float16)
+    start, count = np.array([0, 5, 9], np.int32), np.array([7, 0, 6], np.int32)
+    for paged in (False, True):
+        if paged:
+            K, V, table = make_paged(r, B, Hkv, D, [12, 12, 12], ps)
+        else:
+            K, V, table = f16(r.normal(size=(B, Hkv, 12, D))), f16(r.normal(size=(B, Hkv, 12, D))), None
+        for appender in (np_oracle.kv_append, c_oracle.kv_append):
+            Ka, Va, Kb, Vb = K.copy(), V.copy(), K.copy(), V.copy()
+            np_oracle.kv_write(Ka, Va, k_src, v_src, start, count, table)
+            for i in range(N):
+                lens = np.where(i < count, start + i + 1, 0).astype(np.int32)   # 0: skipped
+                appender(Kb, Vb, np.ascontiguousarray(k_src[:, :, i]), np.ascontiguousarray(v_src[:, :, i]),
+                         lens, table)
+            assert np.array_equal(bits(Ka), bits(Kb)) and np.array_equal(bits(Va), bits(Vb))
+            assert not np.array_equal(bits(Ka), bits(K))
+            # sequence 1 (count 0) untouched; sequence 2 wrote rows 9..11 only (capacity 12)
+            if not paged:
+                assert np.array_equal(bits(Ka[1]), bits(K[1]))
+                assert np.array_equal(bits(Ka[2, :, :9]), bits(K[2, :, :9]))
+                assert np.array_equal(bits(Ka[2, :, 9:12]), bits(k_src[2, :, :3]))
+
+
 def test_append_then_decode_sees_the_new_token(impl):
     """A new key far along q dominates: the output becomes the new v."""
     r = rng(27)
