@@ -241,8 +241,9 @@ size_t instattn_sparf_workspace_size(int batch, int num_q_heads, int head_dim, i
  *               positions of every head in ascending order (min(k, L_b) entries
  *               are written per head)
  *   alpha     : device [batch][num_q_heads] fp32 or NULL: receives step 7's alpha
- * L_b <= 0 gives a zero row (alpha 0).  Three launches (column scores, selection,
- * attention over the kept rows).
+ * L_b <= 0 gives a zero row (alpha 0).  One launch when max_seq_len <= 8192 (one
+ * block per query head keeps the scores in LDS), otherwise three (column scores,
+ * selection, attention over the kept rows).
  */
 int instattn_sparf_decode(const void* q, const instattn_kv_desc* kv, const instattn_sparf_aux* aux,
                           const int32_t* seq_lens, int batch, int num_q_heads, int num_kv_heads,

@@ -2,6 +2,7 @@
 #include "../../include/instattn.h"
 
 #include <math.h>
+#include <stdlib.h>
 
 #include "sparf.h"
 
@@ -25,7 +26,7 @@ Carve carve(int batch, int num_q_heads, int max_seq_len, int k)
     const size_t rows = (size_t)batch * num_q_heads;
     c.logits = 0;
     c.stats = c.logits + up256(rows * c.lpad * sizeof(float));
-    c.sel = c.stats + up256(rows * c.nchunk * 2 * sizeof(float));
+    c.sel = c.stats + up256(rows * c.nchunk * 3 * sizeof(float));
     c.alpha = c.sel + up256(rows * (size_t)k * sizeof(int32_t));
     c.total = c.alpha + up256(rows * sizeof(float));
     return c;
@@ -159,6 +160,9 @@ int instattn_sparf_decode(const void* q, const instattn_kv_desc* kv, const insta
     a.out = out;
     a.out_f32 = out_dtype == INSTATTN_F32;
     hipStream_t s = (hipStream_t)stream;
+    const char* force3 = getenv("INSTATTN_SPARF_THREE_LAUNCHES");
+    if (max_seq_len <= kSparfFusedMaxLen && !(force3 && force3[0] == '1'))
+        return status_of(launch_sparf_fused(a, s));
     if (launch_sparf_logits(a, s) != hipSuccess) return INSTATTN_ERR_RUNTIME;
     if (launch_sparf_select(a, s) != hipSuccess) return INSTATTN_ERR_RUNTIME;
     return status_of(launch_sparf_attend(a, s));

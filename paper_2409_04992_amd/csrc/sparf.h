@@ -28,7 +28,7 @@ struct SparfArgs {
     int32_t r, k, l;
     float* logits;                     // [B][Hq][lpad] approximate scores, log2 domain
     int32_t lpad, nchunk;
-    float* stats;                      // [B][Hq][nchunk][2]: block max, sum of 2^(x - max)
+    float* stats;                      // [B][Hq][nchunk][3]: block max, sum of 2^(x - max), min
     int32_t* sel;                      // [B][Hq][k] selected rows, ascending
     float* alpha;                      // [B][Hq] selected share of the approximate softmax
     void* out;
@@ -42,5 +42,8 @@ hipError_t launch_sparf_append(const SparfArgs& a, hipStream_t stream);
 hipError_t launch_sparf_logits(const SparfArgs& a, hipStream_t stream);
 hipError_t launch_sparf_select(const SparfArgs& a, hipStream_t stream);
 hipError_t launch_sparf_attend(const SparfArgs& a, hipStream_t stream);
+hipError_t launch_sparf_fused(const SparfArgs& a, hipStream_t stream);
+
+constexpr int kSparfFusedMaxLen = 8192;   // rows up to this length take the one-launch kernel
 
 }  // namespace instattn

@@ -19,10 +19,15 @@
 //   sparf_attend_kernel   steps 10-11: one block per query head gathers the
 //                         selected rows of K and V (online softmax as in the dense
 //                         vector-ALU kernel) and blends with the mean of V.
+//   sparf_fused_kernel    all of the above in one launch, one block per query head,
+//                         scores kept in LDS: used when a row has at most 8192
+//                         positions.
 //   sparf_build_kernel    builds the component-major K copy and the running sum
 //                         of V from an existing cache (prefill side).
 //   sparf_append_kernel   kv_append plus the new column entry and sum update.
 #include "sparf.h"
+
+#include <stdlib.h>
 
 namespace instattn {
 
@@ -51,6 +56,7 @@ __device__ __forceinline__ float block_max(float x, float* red) {
     for (int i = 1; i < nw; ++i) m = fmaxf(m, red[i]);
     return m;
 }
+__device__ __forceinline__ float block_min(float x, float* red) { return -block_max(-x, red); }
 __device__ __forceinline__ float block_sum(float x, float* red) {
     x = wave_sum(x);
     const int w = threadIdx.x >> 6, nw = blockDim.x >> 6;
@@ -68,259 +74,310 @@ __device__ __forceinline__ uint32_t order_key(float x) {
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-}  // namespace
-
-// ---------------------------------------------------------------------------
-// Steps 1-4 (without the normaliser).
-__global__ __launch_bounds__(256) void sparf_logits_kernel(SparfArgs a)
+// Step 1 and the temperature of step 4.  Leaves q (fp32) in s_q and the components
+// ordered by decreasing |q| (ties towards the lower index) in s_dim; returns the
+// factor that turns a column dot product into a log2-domain score.  Needs at least
+// head_dim threads and is called by the whole block; `red` holds one float per wave.
+__device__ __forceinline__ float prepare_query(const SparfArgs& a, int64_t row, float* s_q, float* s_abs,
+                                               int* s_dim, float* red)
 {
-    const int h = blockIdx.x, chunk = blockIdx.y, b = blockIdx.z;
-    const int D = a.head_dim;
-    const int G = a.num_q_heads / a.num_kv_heads;
-    const int hk = h / G;
-    const int tid = threadIdx.x;
-    const int64_t row = (int64_t)b * a.num_q_heads + h;
-    const int L = clamp_len(a.seq_lens[b], a.max_len);
-    const int t0 = chunk * kSparfChunk;
-    float* stats = a.stats + (row * a.nchunk + chunk) * 2;
-    if (t0 >= L) {
-        if (tid == 0) {
-            stats[0] = kNegBig;
-            stats[1] = 0.f;
-        }
-        return;
-    }
-
-    __shared__ float s_q[128];
-    __shared__ float s_abs[128];
-    __shared__ int s_dim[128];       // component with magnitude rank j
-    __shared__ float s_red[4];
+    const int D = a.head_dim, tid = threadIdx.x;
+    float mine = 0.f;
     if (tid < D) {
         const float qd = (float)a.q[row * D + tid];
         s_q[tid] = qd;
-        s_abs[tid] = fabsf(qd);
+        mine = fabsf(qd);
+        s_abs[tid] = mine;
     }
     __syncthreads();
-    // Step 1: rank of |q_d| (larger first, ties towards the lower index).
+    float kept = 0.f;
     if (tid < D) {
-        const float mine = s_abs[tid];
         int rank = 0;
         for (int d = 0; d < D; ++d) {
             const float o = s_abs[d];
             rank += (o > mine) || (o == mine && d < tid);
         }
         s_dim[rank] = tid;
+        if (rank < a.r) kept = mine;
     }
-    __syncthreads();
-    // Step 4 temperature: sqrt(d_h * |q_kept|_1 / |q|_1); 1/sqrt(d_h) is in `scale`.
-    float tot = 0.f, kept = 0.f;
-    for (int j = 0; j < D; ++j) {
-        const float v = s_abs[s_dim[j]];
-        tot += v;
-        if (j < a.r) kept += v;
-    }
+    // sqrt(d_h * |q_kept|_1 / |q|_1); 1/sqrt(d_h) is in `scale`
+    const float tot = block_sum(mine, red);
+    kept = block_sum(kept, red);
     const float rho = tot > 0.f ? kept / tot : 1.f;
-    const float factor = rho > 0.f ? a.scale_log2 / sqrtf(rho) : 0.f;
+    return rho > 0.f ? a.scale_log2 / sqrtf(rho) : 0.f;
+}
 
-    // Eight consecutive positions per thread, one 128-bit load per kept component.
-    const int t = t0 + tid * 8;
-    float x[8];
+// Scores of the 8 consecutive positions that start at `col0` (the address of
+// position t in column 0 of this KV head): one 128-bit load per kept column.
+__device__ __forceinline__ void column_scores8(const SparfArgs& a, const half_t* col0, const float* s_q,
+                                               const int* s_dim, float x[8])
+{
 #pragma unroll
     for (int e = 0; e < 8; ++e) x[e] = 0.f;
-    if (t < L) {
-        const half_t* base = a.aux.kt + (int64_t)b * a.aux.stride_b + (int64_t)hk * a.aux.stride_h + t;
-#pragma unroll 8
-        for (int j = 0; j < a.r; ++j) {
-            const int d = s_dim[j];
-            const float qd = s_q[d];
-            const half8_t kc = __builtin_nontemporal_load((const half8_t*)(base + (int64_t)d * a.aux.stride_d));
+#pragma unroll 16
+    for (int j = 0; j < a.r; ++j) {
+        const int d = s_dim[j];
+        const float qd = s_q[d];
+        const half8_t kc = __builtin_nontemporal_load((const half8_t*)(col0 + (int64_t)d * a.aux.stride_d));
 #pragma unroll
-            for (int e = 0; e < 8; ++e) x[e] = __builtin_fmaf(qd, (float)kc[e], x[e]);
-        }
-    }
-    float mx = kNegBig;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        x[e] = (t + e < L) ? x[e] * factor : -__builtin_inff();
-        mx = fmaxf(mx, x[e]);
-    }
-    float* dst = a.logits + row * a.lpad + t;
-    *(float4_t*)dst = float4_t{x[0], x[1], x[2], x[3]};
-    *(float4_t*)(dst + 4) = float4_t{x[4], x[5], x[6], x[7]};
-
-    const float M = block_max(mx, s_red);
-    float s = 0.f;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) s += fast_exp2(x[e] - M);
-    s = block_sum(s, s_red);
-    if (tid == 0) {
-        stats[0] = M;
-        stats[1] = s;
+        for (int e = 0; e < 8; ++e) x[e] = __builtin_fmaf(qd, (float)kc[e], x[e]);
     }
 }
 
-// ---------------------------------------------------------------------------
-// Steps 4 (normaliser) to 7.  NT threads per block: 256 for short rows (more blocks
-// per CU, cheaper barriers), 1024 for long ones.
+constexpr int kSelMembers = 512;     // members of the threshold bin ranked directly
+constexpr int kSelTiles = 32;        // tiles of NT positions compacted per round
+
+struct SelectScratch {
+    uint32_t hist[256];
+    uint32_t prefix, remaining, nmem;
+    uint32_t mem_key[kSelMembers];
+    alignas(16) uint16_t cnt_eq[kSelTiles][16];     // per tile and wave: rows with the threshold key
+    alignas(16) uint16_t cnt_take[kSelTiles][16];   // per tile and wave: rows kept
+    float red[16];
+};
+
+// From the per-wave counts of one tile (16-bit, two per word): how many precede
+// this wave, and the tile's total.
+template <int NW>
+__device__ __forceinline__ void wave_prefix(const uint16_t* cnt, int wave, uint32_t& before, uint32_t& total)
+{
+    const uint32_t* p = (const uint32_t*)cnt;
+    before = 0;
+    total = 0;
+#pragma unroll
+    for (int j = 0; j < NW / 2; ++j) {
+        const uint32_t v = p[j];
+        const uint32_t lo = v & 0xFFFFu, hi = v >> 16;
+        total += lo + hi;
+        before += (2 * j < wave ? lo : 0u) + (2 * j + 1 < wave ? hi : 0u);
+    }
+}
+
+// Executed by wave 0 after a histogram is complete: finds the bin that holds the
+// remaining-th largest entry (higher bins rank first) and leaves
+//   S.prefix = that bin,  S.remaining = entries still to take inside it.
+// Lane i owns bins 4i .. 4i+3; suffix sums over the lanes locate the bin.
+__device__ __forceinline__ void locate_bin(SelectScratch& S, uint32_t remaining, int lane)
+{
+    const uint32_t c0 = S.hist[4 * lane], c1 = S.hist[4 * lane + 1];
+    const uint32_t c2 = S.hist[4 * lane + 2], c3 = S.hist[4 * lane + 3];
+    const uint32_t mine = c0 + c1 + c2 + c3;
+    uint32_t suffix = mine;                       // inclusive, over lanes >= this one
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t o = __shfl_down(suffix, d, 64);
+        if (lane + d < 64) suffix += o;
+    }
+    uint32_t above = suffix - mine;               // entries in bins above this lane's
+    if (above < remaining && remaining <= suffix) {
+        int bin = 4 * lane + 3;
+        const uint32_t cs[4] = {c0, c1, c2, c3};
+#pragma unroll
+        for (int j = 3; j > 0; --j) {
+            if (above + cs[j] >= remaining) break;
+            above += cs[j];
+            --bin;
+        }
+        S.prefix = (uint32_t)bin;
+        S.remaining = remaining - above;
+    }
+}
+
+// Steps 5-7 for one head: x[0..L) are the log2-domain scores (LDS or global), M
+// their maximum, xmin their minimum and Z the sum of 2^(x - M).  Writes the kept
+// positions in ascending order to sel and returns alpha to every thread.
+//
+// The threshold is found exactly in two levels.  Level 1 buckets the scores
+// linearly between xmin and M into 256 bins (monotone in x, so every score in a
+// higher bin is >= every score in a lower one); scores spread evenly over these
+// bins, unlike over the exponent byte of a float.  Level 2 works on the members of
+// the one bin that holds the threshold: normally a few dozen, which are gathered
+// and ranked against each other directly; if there are more than kSelMembers
+// (e.g. all scores equal) a 4-pass radix select on order-preserving keys takes
+// over.  Either way the outcome is a threshold key and the number of rows with
+// exactly that key still to keep.  The compaction is ordered (ballot + popcount
+// with per-tile counts in LDS, three barriers per 32 tiles): ties go to the lower
+// position and the result is deterministic.
 template <int NT>
-__global__ __launch_bounds__(NT) void sparf_select_kernel(SparfArgs a)
+__device__ __forceinline__ float select_rows(const float* x, int L, int k, int l, float M, float xmin, float Z,
+                                             int32_t* sel, SelectScratch& S)
 {
     constexpr int NW = NT / 64;
-    const int h = blockIdx.x, b = blockIdx.y;
-    const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    const int64_t row = (int64_t)b * a.num_q_heads + h;
-    const int L = clamp_len(a.seq_lens[b], a.max_len);
-    if (L == 0) {
-        if (tid == 0) a.alpha[row] = 0.f;
-        return;
-    }
-    const int keff = min(a.k, L);
-    const int leff = min(a.l, keff);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int keff = min(k, L);
+    const int leff = min(l, keff);
     const int want = keff - leff;          // rows to pick among the candidates
     const int ncand = L - leff;            // candidates: positions [0, ncand)
-    const float* x = a.logits + row * a.lpad;
-    int32_t* sel = a.sel + row * a.k;
 
-    __shared__ uint32_t s_hist[256];
-    __shared__ uint32_t s_prefix, s_remaining;
-    __shared__ uint32_t s_wtot[2][NW];
-    __shared__ float s_red[NW];
+    const float binscale = M > xmin ? 255.99f / (M - xmin) : 0.f;
+    auto level1 = [&](float v) { return 255u - (uint32_t)min(255, max(0, (int)((M - v) * binscale))); };
 
-    // Normaliser of step 4 from the per-block statistics.
-    const int nc = (L + kSparfChunk - 1) / kSparfChunk;
-    const float* st = a.stats + row * a.nchunk * 2;
-    float M = kNegBig;
-    for (int c = 0; c < nc; ++c) M = fmaxf(M, st[2 * c]);
-    float Z = 0.f;
-    for (int c = 0; c < nc; ++c) Z += st[2 * c + 1] * fast_exp2(st[2 * c] - M);
-
-    // Radix select, most significant byte first: after the four passes `prefix` is
-    // the key of the want-th largest candidate and `remaining` says how many rows
-    // with exactly that key are still to be taken.
-    uint32_t prefix = 0, remaining = (uint32_t)want;
+    uint32_t bin1 = 0, prefix = 0, remaining = (uint32_t)want;
     if (want > 0) {
-        for (int shift = 24; shift >= 0; shift -= 8) {
-            if (tid < 256) s_hist[tid] = 0;
-            __syncthreads();
-            const uint32_t hi_mask = shift == 24 ? 0u : (0xFFFFFFFFu << (shift + 8));
-            for (int t = tid; t < ncand; t += NT) {
-                const uint32_t key = order_key(x[t]);
-                if ((key & hi_mask) == (prefix & hi_mask)) atomicAdd(&s_hist[(key >> shift) & 255u], 1u);
-            }
-            __syncthreads();
-            if (wave == 0) {
-                // lane i owns bins 4i .. 4i+3; suffix sums over the lanes find the bin
-                // that holds the remaining-th largest key
-                const uint32_t c0 = s_hist[4 * lane], c1 = s_hist[4 * lane + 1];
-                const uint32_t c2 = s_hist[4 * lane + 2], c3 = s_hist[4 * lane + 3];
-                const uint32_t mine = c0 + c1 + c2 + c3;
-                uint32_t suffix = mine;                       // inclusive, over lanes >= this one
+        // level 1
+        if (tid < 256) S.hist[tid] = 0;
+        if (tid == 0) S.nmem = 0;
+        __syncthreads();
+        // eight independent loads per thread before their histogram updates (the scores
+        // may live in global memory)
+        for (int t0 = tid; t0 < ncand; t0 += 8 * NT) {
+            float v[8];
 #pragma unroll
-                for (int d = 1; d < 64; d <<= 1) {
-                    const uint32_t o = __shfl_down(suffix, d, 64);
-                    if (lane + d < 64) suffix += o;
-                }
-                uint32_t above = suffix - mine;               // keys in bins above this lane's
-                if (above < remaining && remaining <= suffix) {
-                    int bin = 4 * lane + 3;
-                    const uint32_t cs[4] = {c0, c1, c2, c3};
+            for (int j = 0; j < 8; ++j) v[j] = t0 + j * NT < ncand ? x[t0 + j * NT] : M;
 #pragma unroll
-                    for (int j = 3; j > 0; --j) {
-                        if (above + cs[j] >= remaining) break;
-                        above += cs[j];
-                        --bin;
-                    }
-                    s_prefix = prefix | ((uint32_t)bin << shift);
-                    s_remaining = remaining - above;
+            for (int j = 0; j < 8; ++j)
+                if (t0 + j * NT < ncand) atomicAdd(&S.hist[level1(v[j])], 1u);
+        }
+        __syncthreads();
+        if (wave == 0) locate_bin(S, remaining, lane);
+        __syncthreads();
+        bin1 = S.prefix;
+        remaining = S.remaining;
+        // level 2: gather the members of bin1
+        for (int t0 = tid; t0 < ncand; t0 += 8 * NT) {
+            float v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = t0 + j * NT < ncand ? x[t0 + j * NT] : M;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                if (t0 + j * NT < ncand && level1(v[j]) == bin1) {
+                    const uint32_t i = atomicAdd(&S.nmem, 1u);
+                    if (i < (uint32_t)kSelMembers) S.mem_key[i] = order_key(v[j]);
                 }
             }
+        }
+        __syncthreads();
+        const uint32_t nmem = S.nmem;
+        if (nmem <= (uint32_t)kSelMembers) {
+            // rank every member against the others: the threshold key is the one with
+            // fewer than `remaining` keys above it and at least `remaining` at or above
+            for (uint32_t i = tid; i < nmem; i += NT) {
+                const uint32_t mine = S.mem_key[i];
+                uint32_t gt = 0, ge = 0;
+                for (uint32_t j = 0; j < nmem; ++j) {
+                    const uint32_t o = S.mem_key[j];
+                    gt += o > mine;
+                    ge += o >= mine;
+                }
+                if (gt < remaining && remaining <= ge) {     // same values from every such member
+                    S.prefix = mine;
+                    S.remaining = remaining - gt;
+                }
+            }
             __syncthreads();
-            prefix = s_prefix;
-            remaining = s_remaining;
+            prefix = S.prefix;
+            remaining = S.remaining;
+        } else {
+            for (int shift = 24; shift >= 0; shift -= 8) {
+                __syncthreads();
+                if (tid < 256) S.hist[tid] = 0;
+                __syncthreads();
+                const uint32_t hi_mask = shift == 24 ? 0u : (0xFFFFFFFFu << (shift + 8));
+                for (int t = tid; t < ncand; t += NT) {
+                    const float v = x[t];
+                    const uint32_t key = order_key(v);
+                    if (level1(v) == bin1 && (key & hi_mask) == (prefix & hi_mask))
+                        atomicAdd(&S.hist[(key >> shift) & 255u], 1u);
+                }
+                __syncthreads();
+                if (wave == 0) locate_bin(S, remaining, lane);
+                __syncthreads();
+                prefix |= S.prefix << shift;
+                remaining = S.remaining;
+            }
         }
     }
 
-    // Ordered compaction: rows above the threshold key, plus the first `remaining`
-    // rows with the threshold key, in ascending position.
+    // kept: everything in a bin above bin1; inside bin1 the keys above the threshold
+    // key, plus the first `remaining` rows with exactly that key
     float mass = 0.f;
     uint32_t eq_base = 0, out_base = 0;
     const uint64_t lt_mask = lane == 0 ? 0ull : (~0ull >> (64 - lane));
-    for (int t0 = 0; t0 < ncand && want > 0; t0 += NT) {
-        const int t = t0 + tid;
-        const bool valid = t < ncand;
-        const float xv = valid ? x[t] : 0.f;
-        const uint32_t key = valid ? order_key(xv) : 0u;
-        const bool gt = valid && key > prefix;
-        const bool eq = valid && key == prefix;
-        const uint64_t eq_bal = __ballot(eq);
-        if (lane == 0) s_wtot[0][wave] = (uint32_t)__popcll(eq_bal);
-        __syncthreads();
-        uint32_t eq_before = eq_base, eq_tile = 0;
+    const int ntiles = want > 0 ? (ncand + NT - 1) / NT : 0;
+    for (int T0 = 0; T0 < ntiles; T0 += kSelTiles) {
+        const int nt = min(kSelTiles, ntiles - T0);
+        uint32_t gtbits = 0, eqbits = 0, takebits = 0;
+        for (int i0 = 0; i0 < nt; i0 += 8) {
+            float v[8];
 #pragma unroll
-        for (int w = 0; w < NW; ++w) {
-            const uint32_t c = s_wtot[0][w];
-            if (w < wave) eq_before += c;
-            eq_tile += c;
-        }
-        eq_before += (uint32_t)__popcll(eq_bal & lt_mask);
-        const bool take = gt || (eq && eq_before < remaining);
-        const uint64_t tk_bal = __ballot(take);
-        if (lane == 0) s_wtot[1][wave] = (uint32_t)__popcll(tk_bal);
-        __syncthreads();
-        uint32_t pos = out_base, tk_tile = 0;
+            for (int j = 0; j < 8; ++j) {
+                const int t = (T0 + i0 + j) * NT + tid;
+                v[j] = (i0 + j < nt && t < ncand) ? x[t] : M;
+            }
 #pragma unroll
-        for (int w = 0; w < NW; ++w) {
-            const uint32_t c = s_wtot[1][w];
-            if (w < wave) pos += c;
-            tk_tile += c;
+            for (int j = 0; j < 8; ++j) {
+                const int i = i0 + j;
+                if (i < nt) {                                   // block-uniform
+                    const bool valid = (T0 + i) * NT + tid < ncand;
+                    const uint32_t b1 = level1(v[j]);
+                    const uint32_t key = order_key(v[j]);
+                    const bool gt = valid && (b1 > bin1 || (b1 == bin1 && key > prefix));
+                    const bool eq = valid && b1 == bin1 && key == prefix;
+                    gtbits |= (uint32_t)gt << i;
+                    eqbits |= (uint32_t)eq << i;
+                    const uint64_t bal = __ballot(eq);
+                    if (lane == 0) S.cnt_eq[i][wave] = (uint16_t)__popcll(bal);
+                }
+            }
         }
-        pos += (uint32_t)__popcll(tk_bal & lt_mask);
-        if (take) {
-            sel[pos] = t;
-            mass += fast_exp2(xv - M);
+        __syncthreads();
+        uint32_t eqb = eq_base;
+        for (int i = 0; i < nt; ++i) {
+            const bool eq = (eqbits >> i) & 1u;
+            const uint64_t bal = __ballot(eq);
+            uint32_t before, tile;
+            wave_prefix<NW>(S.cnt_eq[i], wave, before, tile);
+            before += eqb + (uint32_t)__popcll(bal & lt_mask);
+            const bool take = ((gtbits >> i) & 1u) || (eq && before < remaining);
+            takebits |= (uint32_t)take << i;
+            const uint64_t tb = __ballot(take);
+            if (lane == 0) S.cnt_take[i][wave] = (uint16_t)__popcll(tb);
+            eqb += tile;
         }
-        eq_base += eq_tile;
-        out_base += tk_tile;
+        eq_base = eqb;
+        __syncthreads();
+        uint32_t ob = out_base;
+        for (int i = 0; i < nt; ++i) {
+            const bool take = (takebits >> i) & 1u;
+            const uint64_t tb = __ballot(take);
+            uint32_t pos, tile;
+            wave_prefix<NW>(S.cnt_take[i], wave, pos, tile);
+            pos += ob + (uint32_t)__popcll(tb & lt_mask);
+            if (take) {
+                const int t = (T0 + i) * NT + tid;
+                sel[pos] = t;
+                mass += fast_exp2(x[t] - M);
+            }
+            ob += tile;
+        }
+        out_base = ob;
+        __syncthreads();
     }
-    // Step 5: the l most recent positions are always kept.
+    // step 5: the l most recent positions are always kept
     for (int i = tid; i < leff; i += NT) {
         const int t = ncand + i;
         sel[want + i] = t;
         mass += fast_exp2(x[t] - M);
     }
-    mass = block_sum(mass, s_red);
-    if (tid == 0) a.alpha[row] = mass / Z;     // step 7
+    return block_sum(mass, S.red) / Z;     // step 7
 }
 
-// ---------------------------------------------------------------------------
-// Steps 10-11 over the selected rows.
-template <int D>
-__global__ __launch_bounds__(kSparfAttendWaves * 64) void sparf_attend_kernel(SparfArgs a)
+// Steps 10-11 for one head over the n kept rows listed in sel, by WAVES waves:
+// 16 (or 8) lanes read a row, every row group runs its own online softmax, the
+// groups are combined in LDS, the result is blended with the mean of V.
+template <int D, int WAVES>
+__device__ __forceinline__ void attend_rows(const SparfArgs& a, int b, int h, int L, int n, const int32_t* sel,
+                                            float alpha, float (*s_acc)[D], float* s_m, float* s_l)
 {
     constexpr int LPR = D / 8;
     constexpr int RPW = kWave / LPR;
-    constexpr int WAVES = kSparfAttendWaves;
     constexpr int U = 16 / RPW;            // 16 rows per wave and iteration
     constexpr int TILE = WAVES * 16;
     constexpr int NG = WAVES * RPW;
-
-    const int h = blockIdx.x, b = blockIdx.y;
     const int G = a.num_q_heads / a.num_kv_heads;
     const int hk = h / G;
     const int tid = threadIdx.x;
     const int64_t row = (int64_t)b * a.num_q_heads + h;
-    const int L = clamp_len(a.seq_lens[b], a.max_len);
-    if (L == 0) {
-        if (tid < D) {
-            if (a.out_f32) ((float*)a.out)[row * D + tid] = 0.f;
-            else ((half_t*)a.out)[row * D + tid] = (half_t)0.f;
-        }
-        return;
-    }
-    const int n = min(a.k, L);
-    const int32_t* sel = a.sel + row * a.k;
-
     const int wave = tid >> 6, lane = tid & 63;
     const int r = lane / LPR, c = lane % LPR;
     const half8_t q8 = *(const half8_t*)(a.q + row * D + c * 8);
@@ -367,9 +424,6 @@ __global__ __launch_bounds__(kSparfAttendWaves * 64) void sparf_attend_kernel(Sp
         }
     }
 
-    __shared__ float s_acc[NG][D];
-    __shared__ float s_m[NG];
-    __shared__ float s_l[NG];
     const int g = wave * RPW + r;
 #pragma unroll
     for (int e = 0; e < 8; ++e) s_acc[g][c * 8 + e] = acc[e];
@@ -390,13 +444,183 @@ __global__ __launch_bounds__(kSparfAttendWaves * 64) void sparf_attend_kernel(Sp
             o += w * s_acc[i][tid];
         }
         o /= lsum;
-        // Step 11: alpha * (attention over the kept rows) + (1 - alpha) * mean of V.
-        const float alpha = a.alpha[row];
+        // step 11: alpha * (attention over the kept rows) + (1 - alpha) * mean of V
         const float vbar = a.aux.vsum[((int64_t)b * a.num_kv_heads + hk) * D + tid] / (float)L;
         o = alpha * o + (1.f - alpha) * vbar;
         if (a.out_f32) ((float*)a.out)[row * D + tid] = o;
         else ((half_t*)a.out)[row * D + tid] = (half_t)o;
     }
+}
+
+template <int D>
+__device__ __forceinline__ void write_zero_row(const SparfArgs& a, int64_t row)
+{
+    if ((int)threadIdx.x < D) {
+        if (a.out_f32) ((float*)a.out)[row * D + threadIdx.x] = 0.f;
+        else ((half_t*)a.out)[row * D + threadIdx.x] = (half_t)0.f;
+    }
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------
+// Steps 1-4 (without the normaliser), long rows: one block per 2048 positions.
+__global__ __launch_bounds__(256) void sparf_logits_kernel(SparfArgs a)
+{
+    const int h = blockIdx.x, chunk = blockIdx.y, b = blockIdx.z;
+    const int G = a.num_q_heads / a.num_kv_heads;
+    const int hk = h / G;
+    const int tid = threadIdx.x;
+    const int64_t row = (int64_t)b * a.num_q_heads + h;
+    const int L = clamp_len(a.seq_lens[b], a.max_len);
+    const int t0 = chunk * kSparfChunk;
+    float* stats = a.stats + (row * a.nchunk + chunk) * 3;   // max, sum of 2^(x - max), min
+    if (t0 >= L) {
+        if (tid == 0) {
+            stats[0] = kNegBig;
+            stats[1] = 0.f;
+            stats[2] = -kNegBig;
+        }
+        return;
+    }
+    __shared__ float s_q[128];
+    __shared__ float s_abs[128];
+    __shared__ int s_dim[128];
+    __shared__ float s_red[4];
+    const float factor = prepare_query(a, row, s_q, s_abs, s_dim, s_red);
+
+    const int t = t0 + tid * 8;
+    float x[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) x[e] = 0.f;
+    if (t < L)
+        column_scores8(a, a.aux.kt + (int64_t)b * a.aux.stride_b + (int64_t)hk * a.aux.stride_h + t, s_q,
+                       s_dim, x);
+    float mx = kNegBig, mn = -kNegBig;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const bool in = t + e < L;
+        x[e] = in ? x[e] * factor : -__builtin_inff();
+        mx = fmaxf(mx, x[e]);
+        if (in) mn = fminf(mn, x[e]);
+    }
+    float* dst = a.logits + row * a.lpad + t;
+    *(float4_t*)dst = float4_t{x[0], x[1], x[2], x[3]};
+    *(float4_t*)(dst + 4) = float4_t{x[4], x[5], x[6], x[7]};
+
+    const float M = block_max(mx, s_red);
+    float s = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) s += fast_exp2(x[e] - M);
+    s = block_sum(s, s_red);
+    mn = block_min(mn, s_red);
+    if (tid == 0) {
+        stats[0] = M;
+        stats[1] = s;
+        stats[2] = mn;
+    }
+}
+
+// Steps 4 (normaliser) to 7, long rows: one block per head over the stored scores.
+template <int NT>
+__global__ __launch_bounds__(NT) void sparf_select_kernel(SparfArgs a)
+{
+    const int h = blockIdx.x, b = blockIdx.y;
+    const int64_t row = (int64_t)b * a.num_q_heads + h;
+    const int L = clamp_len(a.seq_lens[b], a.max_len);
+    if (L == 0) {
+        if (threadIdx.x == 0) a.alpha[row] = 0.f;
+        return;
+    }
+    __shared__ SelectScratch S;
+    const int nc = (L + kSparfChunk - 1) / kSparfChunk;
+    const float* st = a.stats + row * a.nchunk * 3;
+    float M = kNegBig, xmin = -kNegBig;
+    for (int c = 0; c < nc; ++c) {
+        M = fmaxf(M, st[3 * c]);
+        xmin = fminf(xmin, st[3 * c + 2]);
+    }
+    float Z = 0.f;
+    for (int c = 0; c < nc; ++c) Z += st[3 * c + 1] * fast_exp2(st[3 * c] - M);
+    const float alpha = select_rows<NT>(a.logits + row * a.lpad, L, a.k, a.l, M, xmin, Z, a.sel + row * a.k, S);
+    if (threadIdx.x == 0) a.alpha[row] = alpha;
+}
+
+// Steps 10-11, long rows.
+template <int D>
+__global__ __launch_bounds__(kSparfAttendWaves * 64) void sparf_attend_kernel(SparfArgs a)
+{
+    constexpr int NG = kSparfAttendWaves * (kWave / (D / 8));
+    const int h = blockIdx.x, b = blockIdx.y;
+    const int64_t row = (int64_t)b * a.num_q_heads + h;
+    const int L = clamp_len(a.seq_lens[b], a.max_len);
+    if (L == 0) {
+        write_zero_row<D>(a, row);
+        return;
+    }
+    __shared__ float s_acc[NG][D];
+    __shared__ float s_m[NG];
+    __shared__ float s_l[NG];
+    attend_rows<D, kSparfAttendWaves>(a, b, h, L, min(a.k, L), a.sel + row * a.k, a.alpha[row], s_acc, s_m,
+                                      s_l);
+}
+
+// The whole of Algorithm 1 for one query head in one block of NT threads; the
+// scores live in dynamic LDS (one float per position, rows of at most 8192).
+template <int D, int NT>
+__global__ __launch_bounds__(NT) void sparf_fused_kernel(SparfArgs a)
+{
+    constexpr int NG = (NT / 64) * (kWave / (D / 8));
+    const int h = blockIdx.x, b = blockIdx.y;
+    const int G = a.num_q_heads / a.num_kv_heads;
+    const int hk = h / G;
+    const int tid = threadIdx.x;
+    const int64_t row = (int64_t)b * a.num_q_heads + h;
+    const int L = clamp_len(a.seq_lens[b], a.max_len);
+    if (L == 0) {
+        write_zero_row<D>(a, row);
+        if (tid == 0) a.alpha[row] = 0.f;
+        return;
+    }
+    extern __shared__ float xs[];             // scores, log2 domain
+    __shared__ float s_q[128];
+    __shared__ float s_abs[128];
+    __shared__ int s_dim[128];
+    __shared__ SelectScratch S;
+    __shared__ float s_acc[NG][D];
+    __shared__ float s_m[NG];
+    __shared__ float s_l[NG];
+
+    // steps 1-4
+    const float factor = prepare_query(a, row, s_q, s_abs, s_dim, S.red);
+    const half_t* col0 = a.aux.kt + (int64_t)b * a.aux.stride_b + (int64_t)hk * a.aux.stride_h;
+    float mx = kNegBig, mn = -kNegBig;
+    for (int t = tid * 8; t < L; t += NT * 8) {
+        float x[8];
+        column_scores8(a, col0 + t, s_q, s_dim, x);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const bool in = t + e < L;
+            x[e] = in ? x[e] * factor : -__builtin_inff();
+            mx = fmaxf(mx, x[e]);
+            if (in) mn = fminf(mn, x[e]);
+            xs[t + e] = x[e];
+        }
+    }
+    const float M = block_max(mx, S.red);
+    const float xmin = block_min(mn, S.red);
+    float zs = 0.f;
+    for (int t = tid; t < L; t += NT) zs += fast_exp2(xs[t] - M);
+    const float Z = block_sum(zs, S.red);
+
+    // steps 5-7
+    int32_t* sel = a.sel + row * a.k;
+    const float alpha = select_rows<NT>(xs, L, a.k, a.l, M, xmin, Z, sel, S);
+    if (tid == 0) a.alpha[row] = alpha;
+    __syncthreads();                          // the kept positions are read back below
+
+    // steps 10-11
+    attend_rows<D, NT / 64>(a, b, h, L, min(a.k, L), sel, alpha, s_acc, s_m, s_l);
 }
 
 // ---------------------------------------------------------------------------
@@ -485,6 +709,24 @@ hipError_t launch_sparf_select(const SparfArgs& a, hipStream_t stream)
     dim3 grid(a.num_q_heads, a.batch);
     if (a.max_len <= 8192) hipLaunchKernelGGL(sparf_select_kernel<256>, grid, dim3(256), 0, stream, a);
     else hipLaunchKernelGGL(sparf_select_kernel<1024>, grid, dim3(1024), 0, stream, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_sparf_fused(const SparfArgs& a, hipStream_t stream)
+{
+    dim3 grid(a.num_q_heads, a.batch);
+    const size_t lds = (size_t)((a.max_len + 7) / 8 * 8) * sizeof(float);
+    const char* e = getenv("INSTATTN_SPARF_NT");     // experiments: threads per block
+    const int nt = e ? atoi(e) : 256;
+    if (a.head_dim == 128) {
+        if (nt == 1024) hipLaunchKernelGGL((sparf_fused_kernel<128, 1024>), grid, dim3(1024), lds, stream, a);
+        else if (nt == 512) hipLaunchKernelGGL((sparf_fused_kernel<128, 512>), grid, dim3(512), lds, stream, a);
+        else hipLaunchKernelGGL((sparf_fused_kernel<128, 256>), grid, dim3(256), lds, stream, a);
+    } else {
+        if (nt == 1024) hipLaunchKernelGGL((sparf_fused_kernel<64, 1024>), grid, dim3(1024), lds, stream, a);
+        else if (nt == 512) hipLaunchKernelGGL((sparf_fused_kernel<64, 512>), grid, dim3(512), lds, stream, a);
+        else hipLaunchKernelGGL((sparf_fused_kernel<64, 256>), grid, dim3(256), lds, stream, a);
+    }
     return hipGetLastError();
 }
 

@@ -115,9 +115,30 @@ def sparf_step(wl, r, k, l, out_dtype=torch.float32, pairs=None):
 # ------------------------------------------------------------------ parity
 @pytest.mark.parametrize("r,k,l", [(16, 64, 8), (8, 128, 0), (128, 32, 4), (1, 16, 16), (32, 700, 3)])
 @pytest.mark.parametrize("out_dtype", [torch.float32, torch.float16])
-def test_sparf_mha_small(r, k, l, out_dtype):
+@pytest.mark.parametrize("three_launches", [False, True])
+def test_sparf_mha_small(monkeypatch, r, k, l, out_dtype, three_launches):
+    """Both forms of the path: the one-launch kernel and the three-launch pipeline
+    that long rows take (forced here through the environment)."""
+    if three_launches:
+        monkeypatch.setenv("INSTATTN_SPARF_THREE_LAUNCHES", "1")
     wl = W.Workload("sparf_mha", 3, 4, 4, 128, 1500, seq_len_min=300, seed=401)
     sparf_step(wl, r, k, l, out_dtype)
+
+
+def test_sparf_long_rows_take_the_three_launch_pipeline():
+    wl = W.Workload("sparf_long", 1, 2, 2, 128, 20000, seed=408)
+    sparf_step(wl, 16, 1300, 32, torch.float16)
+
+
+def test_sparf_one_launch_and_three_launches_agree(monkeypatch):
+    wl = W.Workload("sparf_both", 2, 4, 2, 128, 4000, seq_len_min=1000, seed=409)
+    case, desc, aux, kt, vsum, _ = setup(wl)
+    B.sparf_append(desc, aux, case.k_new, case.v_new, case.seq_lens)
+    a = run_decode(case, desc, aux, 16, 250, 16, torch.float32)
+    monkeypatch.setenv("INSTATTN_SPARF_THREE_LAUNCHES", "1")
+    b = run_decode(case, desc, aux, 16, 250, 16, torch.float32)
+    assert torch.equal(a[1], b[1])                                   # same kept rows
+    assert (a[0] - b[0]).abs().max() <= 2e-6 and (a[2] - b[2]).abs().max() <= 1e-6
 
 
 @pytest.mark.parametrize("head_dim,group", [(64, 1), (64, 4), (128, 8)])
