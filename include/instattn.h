@@ -155,8 +155,7 @@ int instattn_decode(const void* q, const instattn_kv_desc* kv, const int32_t* se
  * two calls in that order: the caches end up bit-identical and out/lse are those
  * of instattn_decode on the updated caches.  The store of the new row is done
  * inside the split pass by the unit that owns position seq_lens[b] - 1, which
- * saves a kernel launch; for head_dim 64 with grouped queries, where no single
- * unit owns a KV head's rows, the append is launched on its own first.
+ * saves a kernel launch.
  *   k_new, v_new : device, [batch][num_kv_heads][head_dim] fp16, dense, 16-byte aligned
  */
 int instattn_append_decode(const void* q, const void* k_new, const void* v_new,

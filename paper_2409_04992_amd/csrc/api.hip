@@ -237,16 +237,6 @@ static int run_partial(const void* q, const void* k_new, const void* v_new, bool
                    workspace_bytes_for(batch, num_q_heads, head_dim, p));
     if (st != INSTATTN_OK) return st;
 
-    // The in-kernel append needs one block to own each (sequence, KV head): true for
-    // the vector-ALU kernel without groups and for the MFMA kernel.  Otherwise the
-    // append runs as its own launch first.
-    const bool one_owner = num_q_heads == num_kv_heads || head_dim == 128;
-    if (fused && !one_owner) {
-        st = instattn_kv_append(kv, k_new, v_new, seq_lens, batch, num_kv_heads, head_dim, stream);
-        if (st != INSTATTN_OK) return st;
-        fused = false;
-    }
-
     DecodeArgs a;
     a.k_new = fused ? (const half_t*)k_new : nullptr;
     a.v_new = fused ? (const half_t*)v_new : nullptr;

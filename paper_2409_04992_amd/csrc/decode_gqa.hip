@@ -1,13 +1,17 @@
 // Split pass of decode attention for grouped queries on the matrix cores
-// (head_dim 128, 2..16 query heads per KV head).
+// (head_dim 64 or 128, 2..16 query heads per KV head).
 //
 // Paper: Sec. II-A/II-B give the operation; the paper's engine runs one query
 // head per K/V stream.  With G query heads sharing a KV head every fp16 loaded
 // feeds G multiply-adds, which is more than the vector ALUs sustain at HBM speed,
 // while the two products become small dense contractions:
-//     S^T [16 rows x 16 heads]   = K_tile [16 x 128] . Q^T [128 x 16]
-//     O^T [128 dims x 16 heads] += V_tile^T [128 x 32] . P^T [32 x 16]
+//     S^T [16 rows x 16 heads] = K_tile [16 x D] . Q^T [D x 16]
+//     O^T [D dims x 16 heads] += V_tile^T [D x 32] . P^T [32 x 16]
 // done with v_mfma_f32_16x16x32_f16 (heads padded to 16 with zero queries).
+// The comments below give the numbers for D = 128; for D = 64 a lane moves 8 bytes
+// of a row instead of 16 (a row is still read by 16 adjacent lanes), the first
+// product takes 2 instructions per 16 rows instead of 4 and the second 4 per 32
+// rows instead of 8.
 //
 // Operand layouts of that instruction (lane l, g = l / 16, c = l % 16):
 //     A[i][k]: i = c, k = 8g .. 8g+7      B[k][j]: j = c, k = 8g .. 8g+7
@@ -42,17 +46,28 @@ namespace {
 constexpr int kGqWaves = 4;
 constexpr int kGqWaveRows = 32;                   // rows per wave per iteration
 constexpr int kGqTile = kGqWaves * kGqWaveRows;   // rows per block per iteration
-constexpr int kGqRowBytes = 256 + 16;             // padded LDS row
-constexpr int kGqWaveLds = kGqWaveRows * kGqRowBytes;
-constexpr int kGqLds = kGqWaves * kGqWaveLds;     // 34816 B
 
-struct GqaTile {
-    u32x4 k[8];   // index 4m + x
-    u32x4 v[8];
+// Per head_dim: a lane holds EL = D/16 fp16 of a row (one 16- or 8-byte load).
+template <int D>
+struct GqTraits {
+    static constexpr int EL = D / 16;                 // fp16 per lane and row; also MFMAs of the second product
+    static constexpr int KK = D / 32;                 // MFMAs of the first product per 16 rows
+    static constexpr int kLaneBytes = 2 * EL;
+    static constexpr int kRowBytes = 2 * D + 16;      // padded LDS row: conflict-free A-operand reads
+    static constexpr int kWaveLds = kGqWaveRows * kRowBytes;
+    static constexpr int kLds = kGqWaves * kWaveLds;  // 34816 B (D = 128), 18432 B (D = 64)
+    typedef _Float16 vec_t __attribute__((ext_vector_type(EL)));
 };
 
-__device__ __forceinline__ u32x4 gq_load16(const char* base, uint32_t lane_off) {
-    return __builtin_nontemporal_load((const u32x4*)(base + (uint64_t)lane_off));
+template <int D>
+struct GqaTile {
+    typename GqTraits<D>::vec_t k[8];   // index 4m + x
+    typename GqTraits<D>::vec_t v[8];
+};
+
+template <int D>
+__device__ __forceinline__ typename GqTraits<D>::vec_t gq_load(const char* base, uint32_t lane_off) {
+    return __builtin_nontemporal_load((const typename GqTraits<D>::vec_t*)(base + (uint64_t)lane_off));
 }
 
 __device__ __forceinline__ float xor_lanes(float x, int mask) {
@@ -69,10 +84,12 @@ __device__ __forceinline__ void wave_lds_fence() {
 
 }  // namespace
 
-template <bool PAGED, bool SPLIT_P>
+template <int D, bool PAGED, bool SPLIT_P>
 __global__ __launch_bounds__(256) void decode_gqa_kernel(DecodeArgs a)
 {
-    constexpr int D = 128;
+    typedef GqTraits<D> TR;
+    typedef typename TR::vec_t vec_t;
+    constexpr int EL = TR::EL, KK = TR::KK;
     // blockIdx.x walks KV heads: consecutive blocks go round-robin over the XCDs,
     // so every XCD gets the same mix of units whatever the lengths are.
     const int split = blockIdx.y, hk = blockIdx.x, b = blockIdx.z;
@@ -102,13 +119,13 @@ __global__ __launch_bounds__(256) void decode_gqa_kernel(DecodeArgs a)
     const int g = lane >> 4;
     const int c = lane & 15;
 
-    __shared__ __align__(16) char lds[kGqLds];
-    char* my_lds = lds + wave * kGqWaveLds;
+    __shared__ __align__(16) char lds[TR::kLds];
+    char* my_lds = lds + wave * TR::kWaveLds;
 
     // Q^T as B operand of the first product: head c, dims 32kk + 8g .. +7.
-    half8_t qb[4];
+    half8_t qb[KK];
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
+    for (int kk = 0; kk < KK; ++kk) {
         half8_t z = {0, 0, 0, 0, 0, 0, 0, 0};
         qb[kk] = c < G ? *(const half8_t*)(a.q + (row0 + c) * D + kk * 32 + g * 8) : z;
     }
@@ -123,7 +140,7 @@ __global__ __launch_bounds__(256) void decode_gqa_kernel(DecodeArgs a)
     auto sub_row = [&](int it, int m) { return min(t0 + it * kGqTile + wave * kGqWaveRows + 16 * m, last); };
     auto page_of = [&](int t) { return PAGED ? table[t >> a.kv.page_shift] : b; };
 
-    auto load_tile = [&](GqaTile& T, int it, int page0, int page1) {
+    auto load_tile = [&](GqaTile<D>& T, int it, int page0, int page1) {
 #pragma unroll
         for (int m = 0; m < 2; ++m) {
             const int tm = sub_row(it, m);                      // wave-uniform
@@ -135,24 +152,24 @@ __global__ __launch_bounds__(256) void decode_gqa_kernel(DecodeArgs a)
 #pragma unroll
             for (int x = 0; x < 4; ++x) {
                 // rows behind the unit's end are redirected to its last row
-                const uint32_t off = (uint32_t)(min(first + 4 * x, last) - tm) * row_bytes + c * 16;
-                T.k[4 * m + x] = gq_load16(kp + base, off);
-                T.v[4 * m + x] = gq_load16(vp + base, off);
+                const uint32_t off = (uint32_t)(min(first + 4 * x, last) - tm) * row_bytes + c * TR::kLaneBytes;
+                T.k[4 * m + x] = gq_load<D>(kp + base, off);
+                T.v[4 * m + x] = gq_load<D>(vp + base, off);
             }
         }
     };
 
     float m_run = kNegBig, l_run = 0.f;
-    float4_t acc[8];
+    float4_t acc[EL];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) acc[e] = float4_t{0.f, 0.f, 0.f, 0.f};
+    for (int e = 0; e < EL; ++e) acc[e] = float4_t{0.f, 0.f, 0.f, 0.f};
 
-    auto consume = [&](const GqaTile& T, int it) {
+    auto consume = [&](const GqaTile<D>& T, int it) {
         // K tile -> LDS: the row loaded as (m, x) by group g becomes LDS row 16m + 4g + x.
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int lrow = 16 * (i >> 2) + 4 * g + (i & 3);
-            *(u32x4*)(my_lds + lrow * kGqRowBytes + c * 16) = T.k[i];
+            *(vec_t*)(my_lds + lrow * TR::kRowBytes + c * TR::kLaneBytes) = T.k[i];
         }
         wave_lds_fence();
         float4_t s[2];
@@ -160,9 +177,9 @@ __global__ __launch_bounds__(256) void decode_gqa_kernel(DecodeArgs a)
         for (int m = 0; m < 2; ++m) {
             s[m] = float4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
+            for (int kk = 0; kk < KK; ++kk) {
                 const half8_t ka =
-                    *(const half8_t*)(my_lds + (16 * m + c) * kGqRowBytes + kk * 64 + g * 16);
+                    *(const half8_t*)(my_lds + (16 * m + c) * TR::kRowBytes + kk * 64 + g * 16);
                 s[m] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka, qb[kk], s[m], 0, 0, 0);
             }
         }
@@ -199,23 +216,20 @@ __global__ __launch_bounds__(256) void decode_gqa_kernel(DecodeArgs a)
         }
         l_run = l_run * alpha + psum;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc[e] *= alpha;
+        for (int e = 0; e < EL; ++e) acc[e] *= alpha;
 
-        // V^T operand for output dims 8c + e: element e of each of the 8 rows held.
-        half8_t vh[8];
+        // V^T operand for output dims EL*c + e: element e of each of the 8 rows held.
 #pragma unroll
-        for (int i = 0; i < 8; ++i) vh[i] = __builtin_bit_cast(half8_t, T.v[i]);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const half8_t va = {vh[0][e], vh[1][e], vh[2][e], vh[3][e],
-                                vh[4][e], vh[5][e], vh[6][e], vh[7][e]};
+        for (int e = 0; e < EL; ++e) {
+            const half8_t va = {T.v[0][e], T.v[1][e], T.v[2][e], T.v[3][e],
+                                T.v[4][e], T.v[5][e], T.v[6][e], T.v[7][e]};
             acc[e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va, p_hi, acc[e], 0, 0, 0);
             if (SPLIT_P) acc[e] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va, p_lo, acc[e], 0, 0, 0);
         }
     };
 
     const int n_it = (t1 - t0 + kGqTile - 1) / kGqTile;
-    GqaTile A, B;
+    GqaTile<D> A, B;
     int pa0 = page_of(sub_row(0, 0)), pa1 = page_of(sub_row(0, 1));
     int pb0 = page_of(sub_row(1, 0)), pb1 = page_of(sub_row(1, 1));
     load_tile(A, 0, pa0, pa1);
@@ -240,11 +254,12 @@ __global__ __launch_bounds__(256) void decode_gqa_kernel(DecodeArgs a)
     float* s_m = s_o + kGqWaves * G * D;            // [wave][16]
     float* s_l = s_m + kGqWaves * 16;               // [wave][16]
     if (c < G) {
-        float* dst = s_o + ((int64_t)wave * G + c) * D + 32 * g;
+        // register r of product e holds output dim EL * (4g + r) + e of head c
+        float* dst = s_o + ((int64_t)wave * G + c) * D + 4 * EL * g;
 #pragma unroll
-        for (int e = 0; e < 8; ++e)
+        for (int e = 0; e < EL; ++e)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) dst[8 * r + e] = acc[e][r];
+            for (int r = 0; r < 4; ++r) dst[EL * r + e] = acc[e][r];
         if (g == 0) {
             s_m[wave * 16 + c] = m_run;
             s_l[wave * 16 + c] = l_run;
@@ -278,20 +293,24 @@ __global__ __launch_bounds__(256) void decode_gqa_kernel(DecodeArgs a)
     }
 }
 
-// head_dim 128 only; the caller routes other shapes to the vector-ALU kernel.
-hipError_t launch_decode_gqa(const DecodeArgs& a, int batch, int head_dim, hipStream_t stream)
+template <int D>
+static hipError_t launch_gqa(const DecodeArgs& a, int batch, hipStream_t stream)
 {
-    if (head_dim != 128) return launch_decode_mha(a, batch, head_dim, stream);
     dim3 grid(a.num_kv_heads, a.num_splits, batch);
     const bool paged = a.kv.page_table != nullptr;
     if (a.out_f32) {
-        if (paged) hipLaunchKernelGGL((decode_gqa_kernel<true, true>), grid, dim3(256), 0, stream, a);
-        else hipLaunchKernelGGL((decode_gqa_kernel<false, true>), grid, dim3(256), 0, stream, a);
+        if (paged) hipLaunchKernelGGL((decode_gqa_kernel<D, true, true>), grid, dim3(256), 0, stream, a);
+        else hipLaunchKernelGGL((decode_gqa_kernel<D, false, true>), grid, dim3(256), 0, stream, a);
     } else {
-        if (paged) hipLaunchKernelGGL((decode_gqa_kernel<true, false>), grid, dim3(256), 0, stream, a);
-        else hipLaunchKernelGGL((decode_gqa_kernel<false, false>), grid, dim3(256), 0, stream, a);
+        if (paged) hipLaunchKernelGGL((decode_gqa_kernel<D, true, false>), grid, dim3(256), 0, stream, a);
+        else hipLaunchKernelGGL((decode_gqa_kernel<D, false, false>), grid, dim3(256), 0, stream, a);
     }
     return hipGetLastError();
+}
+
+hipError_t launch_decode_gqa(const DecodeArgs& a, int batch, int head_dim, hipStream_t stream)
+{
+    return head_dim == 128 ? launch_gqa<128>(a, batch, stream) : launch_gqa<64>(a, batch, stream);
 }
 
 }  // namespace instattn

@@ -128,7 +128,8 @@ def test_head_dims_layouts_output_types(head_dim, paged, out_dtype):
     full_check(wl, out_dtype=out_dtype)
 
 
-@pytest.mark.parametrize("group,head_dim", [(2, 128), (4, 64), (8, 128), (8, 64), (16, 128), (5, 128)])
+@pytest.mark.parametrize("group,head_dim", [(2, 128), (4, 64), (8, 128), (8, 64), (16, 128), (5, 128),
+                                            (2, 64), (16, 64), (3, 64)])
 @pytest.mark.parametrize("paged", [False, True])
 def test_grouped_queries(group, head_dim, paged):
     wl = W.Workload("gqa", 2, 2 * group, 2, head_dim, 900, seq_len_min=100, paged=paged, seed=88)
