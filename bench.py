@@ -37,6 +37,9 @@ def parse():
     ap.add_argument("--layers-resident", type=int, default=8,
                     help="distinct layer caches the steps rotate over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--kt-page", type=int, default=None,
+                    help="with --sparf: positions per page of the component-major K copy "
+                         "(0: contiguous; default 256 for a paged workload, else 0)")
     ap.add_argument("--sparf", default=None, metavar="r,k,l",
                     help="time the SparF path (Algorithm 1) with these parameters instead of the "
                          "dense path, next to the dense step on the same caches")
@@ -96,21 +99,34 @@ def bench_sparf(args):
     dev = "cuda:0"
     r, k, l = (int(x) for x in args.sparf.split(","))
     wl = W.WORKLOADS[args.workload]
-    assert not wl.paged, "the SparF path takes contiguous caches"
+    kt_page = args.kt_page if args.kt_page is not None else (256 if wl.paged else 0)
     R = max(1, args.layers_resident)
     steps = args.steps or 200
     warmup = args.warmup or 20
     cases = [W.make_case(wl, dev, layer=i) for i in range(R)]
-    descs = [B.kv_desc(c.k_cache, c.v_cache) for c in cases]
+    descs = [B.kv_desc(c.k_cache, c.v_cache, c.page_table) for c in cases]
     auxs, keep = [], []
     for c, d in zip(cases, descs):
-        Bn, Hkv, cap, D = c.k_cache.shape
-        kt = torch.zeros(Bn, Hkv, D, cap, dtype=torch.float16, device=dev)
+        Bn, Hkv, cap, D = wl.batch, wl.num_kv_heads, c.capacity, wl.head_dim
         vsum = torch.zeros(Bn, Hkv, D, dtype=torch.float32, device=dev)
-        a = B.sparf_aux(kt, vsum)
+        if kt_page == 0:
+            kt, kt_table = torch.zeros(Bn, Hkv, D, cap, dtype=torch.float16, device=dev), None
+        else:
+            # the component-major copy in pages of its own size behind a shuffled table
+            need = [(int(L) + kt_page - 1) // kt_page for L in c.seq_lens.cpu().tolist()]
+            pool = sum(need)
+            kt = torch.zeros(pool, Hkv, D, kt_page, dtype=torch.float16, device=dev)
+            perm = torch.randperm(pool, generator=torch.Generator().manual_seed(wl.seed)).to(torch.int32)
+            kt_table = torch.full((Bn, (cap + kt_page - 1) // kt_page), -1, dtype=torch.int32)
+            at = 0
+            for b in range(Bn):
+                kt_table[b, :need[b]] = perm[at:at + need[b]]
+                at += need[b]
+            kt_table = kt_table.to(dev)
+        a = B.sparf_aux(kt, vsum, kt_table)
         B.sparf_build(d, a, (c.seq_lens - 1).contiguous(), Hkv, D)
         auxs.append(a)
-        keep.append((kt, vsum))
+        keep.append((kt, vsum, kt_table))
     max_len = int(cases[0].seq_lens.max().item())
     lens = cases[0].seq_lens.cpu().tolist()
     D, Hq = wl.head_dim, wl.num_q_heads
@@ -147,6 +163,7 @@ def bench_sparf(args):
         "warmup": warmup, "ms_per_step": t_sparf * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f16", "data": "synthetic",
         "config": {"workload": wl.name, "r": r, "k": k, "l": l, "layers_resident": R,
+                   "kt_page": kt_page,
                    "step": "sparf_append + sparf_decode (column scores, selection, gather attention)"},
         "dense_ms_per_step": t_dense * 1e3, "speedup_over_dense_step": t_dense / t_sparf,
         "bytes_read_algorithm1": sparf_bytes, "bytes_read_dense": dense_bytes,

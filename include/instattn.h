@@ -47,7 +47,8 @@ typedef enum { INSTATTN_F16 = 0, INSTATTN_F32 = 1 } instattn_dtype;
  * Where the cached keys and values live.  k and v have the same geometry.
  * Strides are in fp16 elements; the head dimension is unit-stride; every stride
  * must be a multiple of 8 elements and k, v 16-byte aligned (rows are moved with
- * 128-bit accesses).
+ * 128-bit accesses).  stride_t may not exceed 2^24 elements
+ * (INSTATTN_ERR_UNSUPPORTED beyond).
  *
  *   contiguous: element (b, hk, t, d) at  b*stride_b    + hk*stride_h + t*stride_t + d
  *               capacity = rows available per (b, hk); page_table = NULL.
@@ -193,21 +194,36 @@ int instattn_decode_merge(const int32_t* seq_lens, int batch, int num_q_heads, i
  *     out = alpha * attention_over_kept_rows + (1 - alpha) * mean(V[0:L_b])   (step 11).
  * 1/sqrt(d_h) enters through `scale` as in the dense path.  Ties in either top-k
  * go to the lower index.  k and l are cut off at L_b, l at k.  With k >= L_b the
- * result equals instattn_decode.  Contiguous caches only, head_dim 64 or 128.
+ * result equals instattn_decode.  Both cache layouts, head_dim 64 or 128.
  *
  * The column reads need K stored a second time, component-major (the paper's
  * hidden-embedding-indexed copy, Sec. IV-C), and step 11 needs the running sum
  * of V; both live in caller-owned device memory described by instattn_sparf_aux:
- *   kt   : fp16, element (b, hk, d, t) at b*stride_b + hk*stride_h + d*stride_d + t;
- *          strides multiples of 8, 16-byte aligned, capacity a multiple of 8
+ *   kt   : fp16, 16-byte aligned, strides multiples of 8.
+ *          contiguous (page_size 0, page_table NULL): element (b, hk, d, t) at
+ *            b*stride_b + hk*stride_h + d*stride_d + t; capacity (a multiple of 8)
+ *            positions per (b, hk, d) row.
+ *          paged (page_size > 0): position t of sequence b is entry t % page_size of
+ *            pool page p = page_table[b*max_pages_per_seq + t / page_size]; element
+ *            (d, t) at p*stride_b + hk*stride_h + d*stride_d + t % page_size;
+ *            capacity = page_size*max_pages_per_seq.  page_size is a power of two
+ *            >= 8 and independent of the cache's own page size: a column is read in
+ *            runs along t, so this copy wants long pages (Sec. IV-C puts the
+ *            granularity of the hidden-embedding-indexed copy at 256 to 1K tokens),
+ *            while the row-major cache is fine with 16-token pages.  Entries of
+ *            page_table behind the last used page are never read.
  *   vsum : fp32 [batch][num_kv_heads][head_dim], sum of rows 0 .. L_b-1 of V
+ * The layout of kt is independent of the layout of the cache itself.
  */
 typedef struct {
     void* kt;
     int64_t stride_b, stride_h, stride_d;
     float* vsum;
-    int32_t capacity;          /* positions per (b, hk, d) row of kt */
-    int32_t reserved;          /* must be 0 */
+    int32_t capacity;          /* max positions per sequence in kt */
+    int32_t page_size;         /* 0: contiguous kt; else positions per kt page */
+    const int32_t* page_table; /* device [batch][max_pages_per_seq]; NULL if contiguous */
+    int32_t max_pages_per_seq; /* paged only */
+    int32_t num_pages;         /* paged only: pool size */
 } instattn_sparf_aux;
 
 /*

@@ -39,7 +39,9 @@ class SparfAux(ctypes.Structure):
         ("kt", ctypes.c_void_p),
         ("stride_b", ctypes.c_int64), ("stride_h", ctypes.c_int64), ("stride_d", ctypes.c_int64),
         ("vsum", ctypes.c_void_p),
-        ("capacity", ctypes.c_int32), ("reserved", ctypes.c_int32),
+        ("capacity", ctypes.c_int32), ("page_size", ctypes.c_int32),
+        ("page_table", ctypes.c_void_p),
+        ("max_pages_per_seq", ctypes.c_int32), ("num_pages", ctypes.c_int32),
     ]
 
 
@@ -242,15 +244,23 @@ def probe_copy(src: torch.Tensor, dst: torch.Tensor, stream=None) -> None:
 
 
 # ---------------------------------------------------------------------- SparF
-def sparf_aux(kt: torch.Tensor, vsum: torch.Tensor) -> SparfAux:
-    """Descriptor for kt [B, Hkv, D, capacity] fp16 and vsum [B, Hkv, D] fp32."""
+def sparf_aux(kt: torch.Tensor, vsum: torch.Tensor, page_table: Optional[torch.Tensor] = None) -> SparfAux:
+    """Descriptor for vsum [B, Hkv, D] fp32 and kt fp16: [B, Hkv, D, capacity], or, with
+    a page table [B, max_pages] int32, a pool [num_pages, Hkv, D, page_size]."""
     assert kt.dtype == torch.float16 and kt.stride(3) == 1
     assert vsum.dtype == torch.float32 and vsum.is_contiguous()
     a = SparfAux()
     a.kt, a.vsum = kt.data_ptr(), vsum.data_ptr()
     a.stride_b, a.stride_h, a.stride_d = kt.stride(0), kt.stride(1), kt.stride(2)
-    a.capacity = kt.shape[3]
-    a.reserved = 0
+    if page_table is None:
+        a.capacity, a.page_size, a.page_table = kt.shape[3], 0, None
+        a.max_pages_per_seq = a.num_pages = 0
+    else:
+        assert page_table.dtype == torch.int32 and page_table.is_contiguous()
+        a.page_size, a.num_pages = kt.shape[3], kt.shape[0]
+        a.max_pages_per_seq = page_table.shape[1]
+        a.capacity = a.page_size * a.max_pages_per_seq
+        a.page_table = page_table.data_ptr()
     return a
 
 

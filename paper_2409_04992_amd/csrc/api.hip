@@ -6,6 +6,7 @@
 #include <stdlib.h>
 
 #include "common.h"
+#include "host_checks.h"
 
 using namespace instattn;
 
@@ -21,10 +22,6 @@ constexpr int kMinChunk = 384;
 constexpr int kTargetUnitsMha = 4096, kMaxChunkMha = 1408;
 constexpr int kTargetUnitsGqa = 768, kMaxChunkGqa = 5504;
 constexpr int kSingleSplitStreams = 512, kSingleSplitMaxLen = 8192;
-
-bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
-bool pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
-int ilog2(int x) { int s = 0; while ((1 << s) < x) ++s; return s; }
 
 struct Plan {
     int chunk;
@@ -70,45 +67,6 @@ int check_shape(int batch, int num_q_heads, int num_kv_heads, int head_dim, int 
     if (num_q_heads / num_kv_heads > 16) return INSTATTN_ERR_UNSUPPORTED;
     if (batch > 65535 || num_q_heads > 65535) return INSTATTN_ERR_UNSUPPORTED;  // grid y, z
     return INSTATTN_OK;
-}
-
-int check_kv(const instattn_kv_desc* kv, int head_dim)
-{
-    if (!kv || !kv->k || !kv->v) return INSTATTN_ERR_INVALID_ARG;
-    if (!aligned16(kv->k) || !aligned16(kv->v)) return INSTATTN_ERR_INVALID_ARG;
-    if (kv->reserved != 0) return INSTATTN_ERR_INVALID_ARG;
-    if (kv->stride_b <= 0 || kv->stride_h <= 0 || kv->stride_t < head_dim)
-        return INSTATTN_ERR_INVALID_ARG;
-    if (kv->stride_b % 8 || kv->stride_h % 8 || kv->stride_t % 8) return INSTATTN_ERR_INVALID_ARG;
-    if (kv->capacity <= 0) return INSTATTN_ERR_INVALID_ARG;
-    if (kv->layout == INSTATTN_KV_CONTIGUOUS) {
-        if (kv->page_table != nullptr) return INSTATTN_ERR_INVALID_ARG;
-    } else if (kv->layout == INSTATTN_KV_PAGED) {
-        if (!kv->page_table) return INSTATTN_ERR_INVALID_ARG;
-        if (!pow2(kv->page_size) || kv->page_size < 16) return INSTATTN_ERR_INVALID_ARG;
-        if (kv->max_pages_per_seq <= 0 || kv->num_pages <= 0) return INSTATTN_ERR_INVALID_ARG;
-        if ((int64_t)kv->capacity != (int64_t)kv->page_size * kv->max_pages_per_seq)
-            return INSTATTN_ERR_INVALID_ARG;
-    } else {
-        return INSTATTN_ERR_INVALID_ARG;
-    }
-    return INSTATTN_OK;
-}
-
-KvView make_view(const instattn_kv_desc* kv)
-{
-    KvView w;
-    w.k = (const half_t*)kv->k;
-    w.v = (const half_t*)kv->v;
-    w.page_table = kv->layout == INSTATTN_KV_PAGED ? kv->page_table : nullptr;
-    w.stride_b = kv->stride_b;
-    w.stride_h = kv->stride_h;
-    w.stride_t = kv->stride_t;
-    w.capacity = kv->capacity;
-    w.page_shift = kv->layout == INSTATTN_KV_PAGED ? ilog2(kv->page_size) : 0;
-    w.page_mask = kv->layout == INSTATTN_KV_PAGED ? kv->page_size - 1 : 0;
-    w.max_pages = kv->max_pages_per_seq;
-    return w;
 }
 
 size_t workspace_bytes_for(int batch, int num_q_heads, int head_dim, const Plan& p)

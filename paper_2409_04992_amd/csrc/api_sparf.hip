@@ -4,13 +4,13 @@
 #include <math.h>
 #include <stdlib.h>
 
+#include "host_checks.h"
 #include "sparf.h"
 
 using namespace instattn;
 
 namespace {
 
-bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 size_t up256(size_t x) { return (x + 255) / 256 * 256; }
 
 struct Carve {
@@ -37,38 +37,38 @@ int check_common(const instattn_kv_desc* kv, const instattn_sparf_aux* aux, int 
 {
     if (batch <= 0 || num_kv_heads <= 0) return INSTATTN_ERR_INVALID_ARG;
     if (head_dim != 64 && head_dim != 128) return head_dim > 0 ? INSTATTN_ERR_UNSUPPORTED : INSTATTN_ERR_INVALID_ARG;
-    if (!kv || !kv->k || !kv->v || !aligned16(kv->k) || !aligned16(kv->v)) return INSTATTN_ERR_INVALID_ARG;
-    if (kv->reserved != 0 || kv->capacity <= 0) return INSTATTN_ERR_INVALID_ARG;
-    if (kv->layout == INSTATTN_KV_PAGED) return INSTATTN_ERR_UNSUPPORTED;
-    if (kv->layout != INSTATTN_KV_CONTIGUOUS || kv->page_table) return INSTATTN_ERR_INVALID_ARG;
-    if (kv->stride_b <= 0 || kv->stride_h <= 0 || kv->stride_t < head_dim) return INSTATTN_ERR_INVALID_ARG;
-    if (kv->stride_b % 8 || kv->stride_h % 8 || kv->stride_t % 8) return INSTATTN_ERR_INVALID_ARG;
-    if (!aux || !aux->kt || !aux->vsum || !aligned16(aux->kt) || aux->reserved != 0)
-        return INSTATTN_ERR_INVALID_ARG;
-    if (aux->capacity <= 0 || aux->capacity % 8 || aux->stride_d < aux->capacity) return INSTATTN_ERR_INVALID_ARG;
+    const int st = check_kv(kv, head_dim);
+    if (st != INSTATTN_OK) return st;
+    if (!aux || !aux->kt || !aux->vsum || !aligned16(aux->kt)) return INSTATTN_ERR_INVALID_ARG;
+    if (aux->capacity <= 0 || aux->capacity % 8) return INSTATTN_ERR_INVALID_ARG;
     if (aux->stride_b <= 0 || aux->stride_h <= 0) return INSTATTN_ERR_INVALID_ARG;
     if (aux->stride_b % 8 || aux->stride_h % 8 || aux->stride_d % 8) return INSTATTN_ERR_INVALID_ARG;
+    if (aux->page_size == 0) {
+        if (aux->page_table != nullptr || aux->stride_d < aux->capacity) return INSTATTN_ERR_INVALID_ARG;
+    } else {
+        if (!pow2(aux->page_size) || aux->page_size < 8 || !aux->page_table) return INSTATTN_ERR_INVALID_ARG;
+        if (aux->max_pages_per_seq <= 0 || aux->num_pages <= 0) return INSTATTN_ERR_INVALID_ARG;
+        if (aux->stride_d < aux->page_size) return INSTATTN_ERR_INVALID_ARG;
+        if ((int64_t)aux->capacity != (int64_t)aux->page_size * aux->max_pages_per_seq)
+            return INSTATTN_ERR_INVALID_ARG;
+    }
     return INSTATTN_OK;
 }
 
 void fill_views(SparfArgs& a, const instattn_kv_desc* kv, const instattn_sparf_aux* aux)
 {
-    a.kv.k = (const half_t*)kv->k;
-    a.kv.v = (const half_t*)kv->v;
-    a.kv.page_table = nullptr;
-    a.kv.stride_b = kv->stride_b;
-    a.kv.stride_h = kv->stride_h;
-    a.kv.stride_t = kv->stride_t;
-    a.kv.capacity = kv->capacity;
-    a.kv.page_shift = 0;
-    a.kv.page_mask = 0;
-    a.kv.max_pages = 0;
+    a.kv = make_view(kv);
     a.aux.kt = (half_t*)aux->kt;
     a.aux.stride_b = aux->stride_b;
     a.aux.stride_h = aux->stride_h;
     a.aux.stride_d = aux->stride_d;
     a.aux.capacity = aux->capacity;
     a.aux.vsum = aux->vsum;
+    const bool paged = aux->page_size != 0;
+    a.aux.page_table = paged ? aux->page_table : nullptr;
+    a.aux.page_shift = paged ? ilog2(aux->page_size) : 0;
+    a.aux.page_mask = paged ? aux->page_size - 1 : 0;
+    a.aux.max_pages = paged ? aux->max_pages_per_seq : 0;
 }
 
 int status_of(hipError_t e) { return e == hipSuccess ? INSTATTN_OK : INSTATTN_ERR_RUNTIME; }

@@ -10,17 +10,29 @@ constexpr int kSparfSelectThreads = 1024;
 constexpr int kSparfAttendWaves = 8;
 
 // K stored a second time, component-major (the paper's hidden-embedding-indexed
-// copy, Sec. IV-C): element (b, hk, d, t) at b*stride_b + hk*stride_h + d*stride_d + t.
+// copy, Sec. IV-C): element (b, hk, d, t) at b*stride_b + hk*stride_h + d*stride_d + t,
+// or, paged, at page*stride_b + hk*stride_h + d*stride_d + (t & page_mask) with
+// page = page_table[b*max_pages + (t >> page_shift)].
 struct KtView {
     half_t* kt;
     int64_t stride_b, stride_h, stride_d;
-    int32_t capacity;                  // positions per (b, hk, d) row, multiple of 8
+    int32_t capacity;                  // max positions per sequence, multiple of 8
     float* vsum;                       // [B][Hkv][D] running sum of the first L_b rows of V
+    const int32_t* page_table;         // nullptr: contiguous
+    int32_t page_shift, page_mask, max_pages;
 };
+
+// Where column 0 of KV head hk holds position t; the 8 positions of an aligned
+// run of 8 are contiguous there, and column d is d*stride_d further on.
+__device__ __forceinline__ half_t* kt_col0(const KtView& v, int b, int hk, int t) {
+    if (v.page_table == nullptr) return v.kt + (int64_t)b * v.stride_b + (int64_t)hk * v.stride_h + t;
+    const int page = v.page_table[(int64_t)b * v.max_pages + (t >> v.page_shift)];
+    return v.kt + (int64_t)page * v.stride_b + (int64_t)hk * v.stride_h + (t & v.page_mask);
+}
 
 struct SparfArgs {
     const half_t* q;                   // [B][Hq][D]
-    KvView kv;                         // contiguous layout only
+    KvView kv;
     KtView aux;
     const int32_t* seq_lens;
     int32_t batch, num_q_heads, num_kv_heads, head_dim, max_len;

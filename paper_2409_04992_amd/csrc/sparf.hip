@@ -381,7 +381,6 @@ __device__ __forceinline__ void attend_rows(const SparfArgs& a, int b, int h, in
     const int wave = tid >> 6, lane = tid & 63;
     const int r = lane / LPR, c = lane % LPR;
     const half8_t q8 = *(const half8_t*)(a.q + row * D + c * 8);
-    const int64_t head_base = (int64_t)b * a.kv.stride_b + (int64_t)hk * a.kv.stride_h + c * 8;
 
     float m = kNegBig, l = 0.f;
     float acc[8];
@@ -396,7 +395,7 @@ __device__ __forceinline__ void attend_rows(const SparfArgs& a, int b, int h, in
             const int p = p0 + wave * 16 + j * RPW + r;
             ok[j] = p < n;
             const int t = sel[min(p, n - 1)];
-            const int64_t off = head_base + (int64_t)t * a.kv.stride_t;
+            const int64_t off = row_offset(a.kv, b, hk, t) + c * 8;
             kr[j] = *(const u32x4*)(a.kv.k + off);
             vr[j] = *(const u32x4*)(a.kv.v + off);
         }
@@ -493,9 +492,7 @@ __global__ __launch_bounds__(256) void sparf_logits_kernel(SparfArgs a)
     float x[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) x[e] = 0.f;
-    if (t < L)
-        column_scores8(a, a.aux.kt + (int64_t)b * a.aux.stride_b + (int64_t)hk * a.aux.stride_h + t, s_q,
-                       s_dim, x);
+    if (t < L) column_scores8(a, kt_col0(a.aux, b, hk, t), s_q, s_dim, x);
     float mx = kNegBig, mn = -kNegBig;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
@@ -593,11 +590,10 @@ __global__ __launch_bounds__(NT) void sparf_fused_kernel(SparfArgs a)
 
     // steps 1-4
     const float factor = prepare_query(a, row, s_q, s_abs, s_dim, S.red);
-    const half_t* col0 = a.aux.kt + (int64_t)b * a.aux.stride_b + (int64_t)hk * a.aux.stride_h;
     float mx = kNegBig, mn = -kNegBig;
     for (int t = tid * 8; t < L; t += NT * 8) {
         float x[8];
-        column_scores8(a, col0 + t, s_q, s_dim, x);
+        column_scores8(a, kt_col0(a.aux, b, hk, t), s_q, s_dim, x);
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const bool in = t + e < L;
@@ -624,27 +620,36 @@ __global__ __launch_bounds__(NT) void sparf_fused_kernel(SparfArgs a)
 }
 
 // ---------------------------------------------------------------------------
-// Component-major copy of K and column sums of V for rows [0, L_b).
+// Component-major copy of K and column sums of V for rows [0, L_b): one block per
+// (sequence, KV head) walks the rows in tiles of 64, transposing K through LDS.
 __global__ __launch_bounds__(256) void sparf_build_kernel(SparfArgs a)
 {
     const int hk = blockIdx.x, b = blockIdx.y;
     const int D = a.head_dim;
     const int tid = threadIdx.x;
     const int L = clamp_len(a.seq_lens[b], min(a.kv.capacity, a.aux.capacity));
-    const half_t* kb = a.kv.k + (int64_t)b * a.kv.stride_b + (int64_t)hk * a.kv.stride_h;
-    const half_t* vb = a.kv.v + (int64_t)b * a.kv.stride_b + (int64_t)hk * a.kv.stride_h;
-    half_t* ktb = a.aux.kt + (int64_t)b * a.aux.stride_b + (int64_t)hk * a.aux.stride_h;
 
     __shared__ half_t s_tile[64][128 + 2];   // +2: odd word stride for the column reads
-    const int cols8 = D / 8;
+    __shared__ float s_sum[32][128];
+    const int cols8 = D / 8;                 // 8 or 16: divides 256, so a thread keeps its columns
+    const int c8 = tid % cols8;
+    float vs[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) vs[e] = 0.f;
     for (int t0 = 0; t0 < L; t0 += 64) {
         // rows t0 .. t0+63 (rows at or behind L are not read; their slots become 0)
         for (int i = tid; i < 64 * cols8; i += 256) {
-            const int tr = i / cols8, c8 = i % cols8;
-            half8_t v = {0, 0, 0, 0, 0, 0, 0, 0};
-            if (t0 + tr < L) v = *(const half8_t*)(kb + (int64_t)(t0 + tr) * a.kv.stride_t + c8 * 8);
+            const int tr = i / cols8;
+            half8_t kr = {0, 0, 0, 0, 0, 0, 0, 0};
+            if (t0 + tr < L) {
+                const int64_t off = row_offset(a.kv, b, hk, t0 + tr) + c8 * 8;
+                kr = *(const half8_t*)(a.kv.k + off);
+                const half8_t vr = *(const half8_t*)(a.kv.v + off);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) s_tile[tr][c8 * 8 + e] = v[e];
+                for (int e = 0; e < 8; ++e) vs[e] += (float)vr[e];
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) s_tile[tr][c8 * 8 + e] = kr[e];
         }
         __syncthreads();
         for (int i = tid; i < D * 8; i += 256) {
@@ -652,13 +657,19 @@ __global__ __launch_bounds__(256) void sparf_build_kernel(SparfArgs a)
             half8_t v;
 #pragma unroll
             for (int e = 0; e < 8; ++e) v[e] = s_tile[t8 * 8 + e][d];
-            if (t0 + t8 * 8 < L) *(half8_t*)(ktb + (int64_t)d * a.aux.stride_d + t0 + t8 * 8) = v;
+            if (t0 + t8 * 8 < L)
+                *(half8_t*)(kt_col0(a.aux, b, hk, t0 + t8 * 8) + (int64_t)d * a.aux.stride_d) = v;
         }
         __syncthreads();
     }
+    // 256 / cols8 threads hold partial sums of the same 8 columns: add them in a fixed order
+    const int part = tid / cols8;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) s_sum[part][c8 * 8 + e] = vs[e];
+    __syncthreads();
     if (tid < D) {
         float s = 0.f;
-        for (int t = 0; t < L; ++t) s += (float)vb[(int64_t)t * a.kv.stride_t + tid];
+        for (int p = 0; p < 256 / cols8; ++p) s += s_sum[p][tid];
         a.aux.vsum[((int64_t)b * a.num_kv_heads + hk) * D + tid] = s;
     }
 }
@@ -677,10 +688,10 @@ __global__ __launch_bounds__(256) void sparf_append_kernel(SparfArgs a)
     if (L < 1 || L > a.kv.capacity || L > a.aux.capacity) return;
     const int t = L - 1;
     const half_t kn = a.k_new[i], vn = a.v_new[i];
-    const int64_t off = (int64_t)b * a.kv.stride_b + (int64_t)hk * a.kv.stride_h + (int64_t)t * a.kv.stride_t + d;
+    const int64_t off = row_offset(a.kv, b, hk, t) + d;
     const_cast<half_t*>(a.kv.k)[off] = kn;
     const_cast<half_t*>(a.kv.v)[off] = vn;
-    a.aux.kt[(int64_t)b * a.aux.stride_b + (int64_t)hk * a.aux.stride_h + (int64_t)d * a.aux.stride_d + t] = kn;
+    kt_col0(a.aux, b, hk, t)[(int64_t)d * a.aux.stride_d] = kn;
     a.aux.vsum[i] += (float)vn;
 }
 

@@ -163,7 +163,18 @@ def aux_desc(**kw):
     a = B.SparfAux()
     a.kt, a.vsum = FAKE, FAKE
     a.stride_b, a.stride_h, a.stride_d = 40 * 128 * 4112, 128 * 4112, 4112
-    a.capacity, a.reserved = 4112, 0
+    a.capacity, a.page_size, a.page_table = 4112, 0, None
+    for k, v in kw.items():
+        setattr(a, k, v)
+    return a
+
+
+def paged_aux_desc(**kw):
+    a = B.SparfAux()
+    a.kt, a.vsum, a.page_table = FAKE, FAKE, FAKE
+    a.stride_b, a.stride_h, a.stride_d = 40 * 128 * 256, 128 * 256, 256
+    a.page_size, a.max_pages_per_seq, a.num_pages = 256, 17, 16 * 17
+    a.capacity = 256 * 17
     for k, v in kw.items():
         setattr(a, k, v)
     return a
@@ -186,13 +197,29 @@ def sparf_status(d=None, a=None, q=FAKE, seq=FAKE, batch=16, hq=40, hkv=40, dim=
     (dict(dim=96), B.ERR_UNSUPPORTED), (dict(hq=40, hkv=16), B.ERR_INVALID_ARG),
     (dict(max_len=5000), B.ERR_INVALID_ARG), (dict(out_dtype=3), B.ERR_INVALID_ARG),
     (dict(ws=None), B.ERR_WORKSPACE), (dict(ws_bytes=4096), B.ERR_WORKSPACE),
-    (dict(d=paged_desc()), B.ERR_UNSUPPORTED),
+    (dict(d=paged_desc(page_table=None)), B.ERR_INVALID_ARG),
     (dict(a=aux_desc(kt=None)), B.ERR_INVALID_ARG), (dict(a=aux_desc(vsum=None)), B.ERR_INVALID_ARG),
     (dict(a=aux_desc(capacity=4100)), B.ERR_INVALID_ARG), (dict(a=aux_desc(stride_d=4000)), B.ERR_INVALID_ARG),
-    (dict(a=aux_desc(reserved=1)), B.ERR_INVALID_ARG), (dict(a=aux_desc(capacity=4000, stride_d=4000)), B.ERR_INVALID_ARG),
+    (dict(a=aux_desc(capacity=4000, stride_d=4000)), B.ERR_INVALID_ARG),
+    (dict(a=aux_desc(page_table=FAKE)), B.ERR_INVALID_ARG),              # table without a page size
+    (dict(a=paged_aux_desc(page_table=None)), B.ERR_INVALID_ARG),
+    (dict(a=paged_aux_desc(page_size=100)), B.ERR_INVALID_ARG),
+    (dict(a=paged_aux_desc(page_size=4)), B.ERR_INVALID_ARG),
+    (dict(a=paged_aux_desc(capacity=4096)), B.ERR_INVALID_ARG),          # != page_size * max_pages
+    (dict(a=paged_aux_desc(stride_d=128)), B.ERR_INVALID_ARG),
+    (dict(a=paged_aux_desc(num_pages=0)), B.ERR_INVALID_ARG),
+    (dict(d=desc(stride_t=(1 << 24) + 8)), B.ERR_UNSUPPORTED),
 ])
 def test_sparf_decode_rejects(kw, want):
     assert sparf_status(**kw) == want
+
+
+def test_sparf_accepts_either_layout_of_either_copy():
+    """Validation only reaches the launch when everything is in order; stop it there
+    with a workspace that is too small."""
+    for d in (desc(), paged_desc()):
+        for a in (aux_desc(), paged_aux_desc()):
+            assert sparf_status(d=d, a=a, ws_bytes=4096) == B.ERR_WORKSPACE
 
 
 def test_sparf_build_and_append_reject():

@@ -23,13 +23,56 @@ DEV = "cuda:0"
 SCORE_EPS = 2e-4          # fp32 rounding of an r-term dot product of magnitude <~ 50, in natural-log units
 
 
-def setup(wl, build_lens_offset=-1):
-    """Caches with S_b valid rows, aux built for them; the step then appends row S_b."""
+def logical(case):
+    """K and V as host arrays [B][Hkv][capacity][D] whatever the layout (positions on
+    unmapped pages read 0)."""
+    if case.page_table is None:
+        return H.host(case.k_cache).copy(), H.host(case.v_cache).copy()
+    table = case.page_table.long()
+    mapped = (table >= 0)[:, :, None, None, None]
+    res = []
+    for cache in (case.k_cache, case.v_cache):
+        g = cache[table.clamp(min=0)]                       # [B][pages][Hkv][ps][D]
+        g = torch.where(mapped, g, torch.zeros_like(g))
+        Bn, P, Hkv, ps, D = g.shape
+        res.append(g.permute(0, 2, 1, 3, 4).reshape(Bn, Hkv, P * ps, D).cpu().numpy())
+    return res
+
+
+def column_copy(kt, kt_table, b, L):
+    """[Hkv][D][L]: the component-major copy of sequence b as the kernels see it."""
+    if kt_table is None:
+        return kt[b, :, :, :L]
+    P = kt.shape[3]
+    pages = kt_table[b, :(L + P - 1) // P].long()
+    return kt[pages].permute(1, 2, 0, 3).reshape(kt.shape[1], kt.shape[2], -1)[:, :, :L]
+
+
+def setup(wl, build_lens_offset=-1, kt_page=None):
+    """Caches with S_b valid rows, aux built for them; the step then appends row S_b.
+    kt_page: positions per page of a paged component-major copy (None: contiguous)."""
     case = W.make_case(wl, DEV, poison=True)
-    Bn, Hkv, cap, D = case.k_cache.shape
-    kt = torch.full((Bn, Hkv, D, cap), float("nan"), dtype=torch.float16, device=DEV)
+    Bn, Hkv, D, cap = wl.batch, wl.num_kv_heads, wl.head_dim, case.capacity
     vsum = torch.full((Bn, Hkv, D), float("nan"), dtype=torch.float32, device=DEV)
-    desc, aux = B.kv_desc(case.k_cache, case.v_cache), B.sparf_aux(kt, vsum)
+    kt_table = None
+    if kt_page is None:
+        kt = torch.full((Bn, Hkv, D, (cap + 7) // 8 * 8), float("nan"), dtype=torch.float16, device=DEV)
+    else:
+        per_seq = (cap + kt_page - 1) // kt_page
+        lens = case.seq_lens.cpu()
+        need = [(max(int(L), 0) + kt_page - 1) // kt_page for L in lens]
+        pool = sum(need) + 2
+        kt = torch.full((pool, Hkv, D, kt_page), float("nan"), dtype=torch.float16, device=DEV)
+        perm = torch.randperm(pool, generator=torch.Generator().manual_seed(wl.seed + 5)).to(torch.int32)
+        kt_table = torch.full((Bn, per_seq), -1, dtype=torch.int32)
+        at = 0
+        for b in range(Bn):
+            kt_table[b, :need[b]] = perm[at:at + need[b]]
+            at += need[b]
+        kt_table = kt_table.to(DEV)
+    desc = B.kv_desc(case.k_cache, case.v_cache, case.page_table)
+    aux = B.sparf_aux(kt, vsum, kt_table)
+    case.kt_table = kt_table
     before = (case.seq_lens + build_lens_offset).contiguous()
     B.sparf_build(desc, aux, before, Hkv, D)
     torch.cuda.synchronize()
@@ -53,7 +96,8 @@ def run_decode(case, desc, aux, r, k, l, out_dtype, max_len=None):
 
 def check_against_oracle(case, out, sel, alpha, r, k, l, pairs=None):
     wl = case.wl
-    q, K, V = H.host(case.q), H.host(case.k_cache), H.host(case.v_cache)
+    q = H.host(case.q)
+    K, V = logical(case)
     lens = H.host(case.seq_lens)
     tol = H.TOL[out.dtype]
     Bn, Hq, D = q.shape
@@ -91,22 +135,24 @@ def check_against_oracle(case, out, sel, alpha, r, k, l, pairs=None):
     return worst
 
 
-def sparf_step(wl, r, k, l, out_dtype=torch.float32, pairs=None):
-    case, desc, aux, kt, vsum, before = setup(wl)
-    want_k, want_v = H.host(case.k_cache).copy(), H.host(case.v_cache).copy()
+def sparf_step(wl, r, k, l, out_dtype=torch.float32, pairs=None, kt_page=None):
+    case, desc, aux, kt, vsum, before = setup(wl, kt_page=kt_page)
+    want_k, want_v = logical(case)
     dense.kv_append(want_k, want_v, H.host(case.k_new), H.host(case.v_new), H.host(case.seq_lens))
     B.sparf_append(desc, aux, case.k_new, case.v_new, case.seq_lens)
     out, sel, alpha = run_decode(case, desc, aux, r, k, l, out_dtype)
     # the append part: caches bit-exact, column copy and V sums consistent with them
-    assert np.array_equal(H.host(case.k_cache).view(np.uint16), want_k.view(np.uint16))
-    assert np.array_equal(H.host(case.v_cache).view(np.uint16), want_v.view(np.uint16))
+    got_k, got_v = logical(case)
+    assert np.array_equal(got_k.view(np.uint16), want_k.view(np.uint16))
+    assert np.array_equal(got_v.view(np.uint16), want_v.view(np.uint16))
     lens = H.host(case.seq_lens)
     for b in range(case.wl.batch):
         L = int(lens[b])
         if L < 1:
             continue
-        assert torch.equal(kt[b, :, :, :L].view(torch.int16),
-                           case.k_cache[b, :, :L].transpose(1, 2).contiguous().view(torch.int16))
+        cols = column_copy(kt, case.kt_table, b, L).cpu().numpy()
+        assert np.array_equal(cols.view(np.uint16),
+                              np.ascontiguousarray(want_k[b, :, :L].transpose(0, 2, 1)).view(np.uint16))
         ref = want_v[b, :, :L].astype(np.float64).sum(axis=1)
         np.testing.assert_allclose(vsum[b].double().cpu().numpy(), ref, rtol=0, atol=2e-3)
     return check_against_oracle(case, out, sel, alpha, r, k, l, pairs)
@@ -123,6 +169,29 @@ def test_sparf_mha_small(monkeypatch, r, k, l, out_dtype, three_launches):
         monkeypatch.setenv("INSTATTN_SPARF_THREE_LAUNCHES", "1")
     wl = W.Workload("sparf_mha", 3, 4, 4, 128, 1500, seq_len_min=300, seed=401)
     sparf_step(wl, r, k, l, out_dtype)
+
+
+@pytest.mark.parametrize("kv_paged,kt_page", [(True, 256), (True, 16), (True, None), (False, 64), (True, 8)])
+@pytest.mark.parametrize("three_launches", [False, True])
+def test_sparf_paged_layouts(monkeypatch, kv_paged, kt_page, three_launches):
+    """The cache in 16-row pages and/or the component-major copy in pages of its own
+    size, each behind its own shuffled page table, in every combination."""
+    if three_launches:
+        monkeypatch.setenv("INSTATTN_SPARF_THREE_LAUNCHES", "1")
+    wl = W.Workload("sparf_paged", 3, 4, 2, 128, 1700, seq_len_min=200, paged=kv_paged, page_size=16,
+                    seed=410)
+    sparf_step(wl, 16, 120, 9, torch.float32, kt_page=kt_page)
+
+
+@pytest.mark.parametrize("seq_len", [0, 1, 15, 16, 17, 255, 256, 257, 2048])
+def test_sparf_paged_lengths_around_page_edges(seq_len):
+    wl = W.Workload("sparf_paged_len", 2, 2, 2, 64, seq_len, paged=True, page_size=16, seed=411)
+    sparf_step(wl, 8, 40, 5, torch.float16, kt_page=256)
+
+
+def test_sparf_paged_long_rows():
+    wl = W.Workload("sparf_paged_long", 1, 2, 2, 128, 20000, paged=True, page_size=16, seed=412)
+    sparf_step(wl, 16, 1300, 32, torch.float16, kt_page=1024)
 
 
 def test_sparf_long_rows_take_the_three_launch_pipeline():
