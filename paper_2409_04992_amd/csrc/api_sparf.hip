@@ -39,6 +39,9 @@ int check_common(const instattn_kv_desc* kv, const instattn_sparf_aux* aux, int 
     if (head_dim != 64 && head_dim != 128) return head_dim > 0 ? INSTATTN_ERR_UNSUPPORTED : INSTATTN_ERR_INVALID_ARG;
     const int st = check_kv(kv, head_dim);
     if (st != INSTATTN_OK) return st;
+    // the gather packs pool page and row inside the page into one 32-bit row id
+    if (kv->layout == INSTATTN_KV_PAGED && (int64_t)kv->num_pages * kv->page_size > INT32_MAX)
+        return INSTATTN_ERR_UNSUPPORTED;
     if (!aux || !aux->kt || !aux->vsum || !aligned16(aux->kt)) return INSTATTN_ERR_INVALID_ARG;
     if (aux->capacity <= 0 || aux->capacity % 8) return INSTATTN_ERR_INVALID_ARG;
     if (aux->stride_b <= 0 || aux->stride_h <= 0) return INSTATTN_ERR_INVALID_ARG;

@@ -8,6 +8,7 @@ namespace instattn {
 constexpr int kSparfChunk = 2048;      // positions per block of the approximate-score pass
 constexpr int kSparfSelectThreads = 1024;
 constexpr int kSparfAttendWaves = 8;
+constexpr int kSparfAttendIds = 4096;   // kept rows staged in LDS at a time by the attend kernel
 
 // K stored a second time, component-major (the paper's hidden-embedding-indexed
 // copy, Sec. IV-C): element (b, hk, d, t) at b*stride_b + hk*stride_h + d*stride_d + t,

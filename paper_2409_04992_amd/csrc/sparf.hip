@@ -77,7 +77,8 @@ __device__ __forceinline__ uint32_t order_key(float x) {
 // Step 1 and the temperature of step 4.  Leaves q (fp32) in s_q and the components
 // ordered by decreasing |q| (ties towards the lower index) in s_dim; returns the
 // factor that turns a column dot product into a log2-domain score.  Needs at least
-// head_dim threads and is called by the whole block; `red` holds one float per wave.
+// head_dim threads and is called by the whole block; `red` holds 32 floats and is
+// free again once every thread has passed the next barrier.
 __device__ __forceinline__ float prepare_query(const SparfArgs& a, int64_t row, float* s_q, float* s_abs,
                                                int* s_dim, float* red)
 {
@@ -100,10 +101,21 @@ __device__ __forceinline__ float prepare_query(const SparfArgs& a, int64_t row, 
         s_dim[rank] = tid;
         if (rank < a.r) kept = mine;
     }
-    // sqrt(d_h * |q_kept|_1 / |q|_1); 1/sqrt(d_h) is in `scale`
-    const float tot = block_sum(mine, red);
-    kept = block_sum(kept, red);
-    const float rho = tot > 0.f ? kept / tot : 1.f;
+    // sqrt(d_h * |q_kept|_1 / |q|_1); 1/sqrt(d_h) is in `scale`.  Both sums in one
+    // block reduction (fixed order: deterministic).
+    const float tot_w = wave_sum(mine), kept_w = wave_sum(kept);
+    const int w = tid >> 6, nw = blockDim.x >> 6;
+    if ((tid & 63) == 0) {
+        red[w] = tot_w;
+        red[16 + w] = kept_w;
+    }
+    __syncthreads();
+    float tot = 0.f, kp = 0.f;
+    for (int i = 0; i < nw; ++i) {
+        tot += red[i];
+        kp += red[16 + i];
+    }
+    const float rho = tot > 0.f ? kp / tot : 1.f;
     return rho > 0.f ? a.scale_log2 / sqrtf(rho) : 0.f;
 }
 
@@ -124,34 +136,82 @@ __device__ __forceinline__ void column_scores8(const SparfArgs& a, const half_t*
     }
 }
 
+// Column pass of a whole row by one block (steps 2-4 without the softmax): adds
+// to xs[t], t < L, the contribution of CG kept columns, the ones ranked
+// j0 .. j0+CG-1.  The columns' offsets and the q components are the same for
+// every lane and are kept in scalar registers; a thread takes 8 consecutive
+// positions per step with one 128-bit load per column, and the loads of step i+1
+// are in flight while step i is consumed.  The steps are unrolled and every load
+// is issued unconditionally (steps behind the row's end re-read its last 8
+// positions, a cache hit) so that the count of loads in flight is known at every
+// wait.  first: xs is written, not added to.
+template <int CG, int NT>
+__device__ __forceinline__ void column_pass(const SparfArgs& a, int b, int hk, int L, int j0, bool first,
+                                            float factor, const float* s_q, const int* s_dim, float* xs)
+{
+    constexpr int STEPS = kSparfFusedMaxLen / (NT * 8);
+    static_assert(STEPS * NT * 8 == kSparfFusedMaxLen && STEPS % 2 == 0, "whole, even number of steps");
+    int64_t coff[CG];
+    float qv[CG];
+#pragma unroll
+    for (int j = 0; j < CG; ++j) {
+        const int d = __builtin_amdgcn_readfirstlane(s_dim[j0 + j]);
+        coff[j] = (int64_t)d * a.aux.stride_d;
+        qv[j] = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, s_q[d] * factor)));
+    }
+    const int tid = threadIdx.x;
+    const int t_last = (L - 1) & ~7;                 // last run of 8 that holds a position
+    const half_t* p0[STEPS];
+#pragma unroll
+    for (int i = 0; i < STEPS; ++i) p0[i] = kt_col0(a.aux, b, hk, min((i * NT + tid) * 8, t_last));
+
+    half8_t A[CG], B[CG];
+    auto load = [&](half8_t (&T)[CG], const half_t* p) {
+#pragma unroll
+        for (int j = 0; j < CG; ++j) T[j] = __builtin_nontemporal_load((const half8_t*)(p + coff[j]));
+    };
+    auto consume = [&](const half8_t (&T)[CG], int i) {
+        const int t = (i * NT + tid) * 8;
+        float4_t* dst = (float4_t*)(xs + min(t, t_last));
+        const float4_t lo = dst[0], hi = dst[1];
+        float x[8];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            x[e] = first ? 0.f : lo[e];
+            x[4 + e] = first ? 0.f : hi[e];
+        }
+#pragma unroll
+        for (int j = 0; j < CG; ++j)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) x[e] = __builtin_fmaf(qv[j], (float)T[j][e], x[e]);
+        if (t <= t_last) {
+            dst[0] = float4_t{x[0], x[1], x[2], x[3]};
+            dst[1] = float4_t{x[4], x[5], x[6], x[7]};
+        }
+    };
+    load(A, p0[0]);
+#pragma unroll
+    for (int i = 0; i < STEPS; i += 2) {
+        if (i * NT * 8 >= L) break;                  // block-uniform: the row ended before this pair of steps
+        load(B, p0[i + 1]);
+        pin_order();
+        consume(A, i);
+        if (i + 2 < STEPS) load(A, p0[i + 2]);
+        pin_order();
+        consume(B, i + 1);
+    }
+}
+
 constexpr int kSelMembers = 512;     // members of the threshold bin ranked directly
-constexpr int kSelTiles = 32;        // tiles of NT positions compacted per round
+constexpr int kSelPer = 32;          // most positions per thread in one round of the compaction
 
 struct SelectScratch {
     uint32_t hist[256];
     uint32_t prefix, remaining, nmem;
     uint32_t mem_key[kSelMembers];
-    alignas(16) uint16_t cnt_eq[kSelTiles][16];     // per tile and wave: rows with the threshold key
-    alignas(16) uint16_t cnt_take[kSelTiles][16];   // per tile and wave: rows kept
-    float red[16];
+    uint32_t wave_cnt[2][16];        // per round parity and wave: rows above the threshold | rows at it << 16
+    float red[48];
 };
-
-// From the per-wave counts of one tile (16-bit, two per word): how many precede
-// this wave, and the tile's total.
-template <int NW>
-__device__ __forceinline__ void wave_prefix(const uint16_t* cnt, int wave, uint32_t& before, uint32_t& total)
-{
-    const uint32_t* p = (const uint32_t*)cnt;
-    before = 0;
-    total = 0;
-#pragma unroll
-    for (int j = 0; j < NW / 2; ++j) {
-        const uint32_t v = p[j];
-        const uint32_t lo = v & 0xFFFFu, hi = v >> 16;
-        total += lo + hi;
-        before += (2 * j < wave ? lo : 0u) + (2 * j + 1 < wave ? hi : 0u);
-    }
-}
 
 // Executed by wave 0 after a histogram is complete: finds the bin that holds the
 // remaining-th largest entry (higher bins rank first) and leaves
@@ -195,9 +255,13 @@ __device__ __forceinline__ void locate_bin(SelectScratch& S, uint32_t remaining,
 // and ranked against each other directly; if there are more than kSelMembers
 // (e.g. all scores equal) a 4-pass radix select on order-preserving keys takes
 // over.  Either way the outcome is a threshold key and the number of rows with
-// exactly that key still to keep.  The compaction is ordered (ballot + popcount
-// with per-tile counts in LDS, three barriers per 32 tiles): ties go to the lower
-// position and the result is deterministic.
+// exactly that key still to keep.  The compaction is ordered: a wave owns a run of
+// consecutive positions (lane i takes every 64th from its i-th), ranks its kept
+// rows with ballots and popcounts alone, and one barrier per round of up to 32
+// positions per thread passes the wave totals on.  The output slot of a row is
+// (rows above the threshold before it) + min(rows at the threshold before it,
+// number of those still wanted), so ties go to the lower position and the result
+// is deterministic.
 template <int NT>
 __device__ __forceinline__ float select_rows(const float* x, int L, int k, int l, float M, float xmin, float Z,
                                              int32_t* sel, SelectScratch& S)
@@ -291,67 +355,57 @@ __device__ __forceinline__ float select_rows(const float* x, int L, int k, int l
     // kept: everything in a bin above bin1; inside bin1 the keys above the threshold
     // key, plus the first `remaining` rows with exactly that key
     float mass = 0.f;
-    uint32_t eq_base = 0, out_base = 0;
     const uint64_t lt_mask = lane == 0 ? 0ull : (~0ull >> (64 - lane));
-    const int ntiles = want > 0 ? (ncand + NT - 1) / NT : 0;
-    for (int T0 = 0; T0 < ntiles; T0 += kSelTiles) {
-        const int nt = min(kSelTiles, ntiles - T0);
-        uint32_t gtbits = 0, eqbits = 0, takebits = 0;
-        for (int i0 = 0; i0 < nt; i0 += 8) {
+    const int per = min(kSelPer, ((ncand + NT - 1) / NT + 7) & ~7);   // positions per thread and round
+    uint32_t gt_base = 0, eq_base = 0;                                // kept-above / threshold rows of earlier rounds
+    int parity = 0;
+    for (int r0 = 0; want > 0 && r0 < ncand; r0 += NT * per, parity ^= 1) {
+        const int w0 = r0 + wave * 64 * per + lane;
+        uint32_t gtbits = 0, eqbits = 0, n_gt = 0, n_eq = 0;
+        for (int j0 = 0; j0 < per; j0 += 8) {
             float v[8];
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                const int t = (T0 + i0 + j) * NT + tid;
-                v[j] = (i0 + j < nt && t < ncand) ? x[t] : M;
+                const int t = w0 + (j0 + j) * 64;
+                v[j] = t < ncand ? x[t] : M;
             }
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                const int i = i0 + j;
-                if (i < nt) {                                   // block-uniform
-                    const bool valid = (T0 + i) * NT + tid < ncand;
-                    const uint32_t b1 = level1(v[j]);
-                    const uint32_t key = order_key(v[j]);
-                    const bool gt = valid && (b1 > bin1 || (b1 == bin1 && key > prefix));
-                    const bool eq = valid && b1 == bin1 && key == prefix;
-                    gtbits |= (uint32_t)gt << i;
-                    eqbits |= (uint32_t)eq << i;
-                    const uint64_t bal = __ballot(eq);
-                    if (lane == 0) S.cnt_eq[i][wave] = (uint16_t)__popcll(bal);
-                }
+                const bool valid = w0 + (j0 + j) * 64 < ncand;
+                const uint32_t b1 = level1(v[j]);
+                const uint32_t key = order_key(v[j]);
+                const bool gt = valid && (b1 > bin1 || (b1 == bin1 && key > prefix));
+                const bool eq = valid && b1 == bin1 && key == prefix;
+                gtbits |= (uint32_t)gt << (j0 + j);
+                eqbits |= (uint32_t)eq << (j0 + j);
+                n_gt += (uint32_t)__popcll(__ballot(gt));
+                n_eq += (uint32_t)__popcll(__ballot(eq));
             }
         }
+        if (lane == 0) S.wave_cnt[parity][wave] = n_gt | (n_eq << 16);   // each at most 64 * 32
         __syncthreads();
-        uint32_t eqb = eq_base;
-        for (int i = 0; i < nt; ++i) {
-            const bool eq = (eqbits >> i) & 1u;
-            const uint64_t bal = __ballot(eq);
-            uint32_t before, tile;
-            wave_prefix<NW>(S.cnt_eq[i], wave, before, tile);
-            before += eqb + (uint32_t)__popcll(bal & lt_mask);
-            const bool take = ((gtbits >> i) & 1u) || (eq && before < remaining);
-            takebits |= (uint32_t)take << i;
-            const uint64_t tb = __ballot(take);
-            if (lane == 0) S.cnt_take[i][wave] = (uint16_t)__popcll(tb);
-            eqb += tile;
+        uint32_t before = 0, total = 0;                                  // 16-bit halves: at most 1024 * 32 each
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            const uint32_t c = S.wave_cnt[parity][w];
+            total += c;
+            before += w < wave ? c : 0u;
         }
-        eq_base = eqb;
-        __syncthreads();
-        uint32_t ob = out_base;
-        for (int i = 0; i < nt; ++i) {
-            const bool take = (takebits >> i) & 1u;
-            const uint64_t tb = __ballot(take);
-            uint32_t pos, tile;
-            wave_prefix<NW>(S.cnt_take[i], wave, pos, tile);
-            pos += ob + (uint32_t)__popcll(tb & lt_mask);
-            if (take) {
-                const int t = (T0 + i) * NT + tid;
-                sel[pos] = t;
+        uint32_t gb = gt_base + (before & 0xFFFFu), eb = eq_base + (before >> 16);
+        for (int j = 0; j < per; ++j) {
+            const bool gt = (gtbits >> j) & 1u, eq = (eqbits >> j) & 1u;
+            const uint64_t bg = __ballot(gt), be = __ballot(eq);
+            const uint32_t eq_before = eb + (uint32_t)__popcll(be & lt_mask);
+            if (gt || (eq && eq_before < remaining)) {
+                const int t = w0 + j * 64;
+                sel[gb + (uint32_t)__popcll(bg & lt_mask) + min(eq_before, remaining)] = t;
                 mass += fast_exp2(x[t] - M);
             }
-            ob += tile;
+            gb += (uint32_t)__popcll(bg);
+            eb += (uint32_t)__popcll(be);
         }
-        out_base = ob;
-        __syncthreads();
+        gt_base += total & 0xFFFFu;
+        eq_base += total >> 16;
     }
     // step 5: the l most recent positions are always kept
     for (int i = tid; i < leff; i += NT) {
@@ -365,13 +419,19 @@ __device__ __forceinline__ float select_rows(const float* x, int L, int k, int l
 // Steps 10-11 for one head over the n kept rows listed in sel, by WAVES waves:
 // 16 (or 8) lanes read a row, every row group runs its own online softmax, the
 // groups are combined in LDS, the result is blended with the mean of V.
+// The kept positions are first turned into row ids in LDS (`ids`, room for
+// ids_cap of them; longer lists go through in pieces): the position itself, or,
+// for a paged cache, pool page and row inside it packed into one word, so that
+// the gather loop has no global load between the id and the row.  Two register
+// tiles: the rows of step i+1 are in flight while step i is consumed.
 template <int D, int WAVES>
 __device__ __forceinline__ void attend_rows(const SparfArgs& a, int b, int h, int L, int n, const int32_t* sel,
-                                            float alpha, float (*s_acc)[D], float* s_m, float* s_l)
+                                            float alpha, int32_t* ids, int ids_cap, float (*s_acc)[D],
+                                            float* s_m, float* s_l)
 {
     constexpr int LPR = D / 8;
     constexpr int RPW = kWave / LPR;
-    constexpr int U = 16 / RPW;            // 16 rows per wave and iteration
+    constexpr int U = 16 / RPW;            // 16 rows per wave and step
     constexpr int TILE = WAVES * 16;
     constexpr int NG = WAVES * RPW;
     const int G = a.num_q_heads / a.num_kv_heads;
@@ -381,45 +441,71 @@ __device__ __forceinline__ void attend_rows(const SparfArgs& a, int b, int h, in
     const int wave = tid >> 6, lane = tid & 63;
     const int r = lane / LPR, c = lane % LPR;
     const half8_t q8 = *(const half8_t*)(a.q + row * D + c * 8);
+    const bool paged = a.kv.page_table != nullptr;
+    const int shift = a.kv.page_shift, mask = a.kv.page_mask;
+    const int64_t base = (paged ? 0 : (int64_t)b * a.kv.stride_b) + (int64_t)hk * a.kv.stride_h + c * 8;
+    const int64_t stride_page = paged ? a.kv.stride_b : 0;
 
     float m = kNegBig, l = 0.f;
     float acc[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[e] = 0.f;
 
-    for (int p0 = 0; p0 < n; p0 += TILE) {
-        u32x4 kr[U], vr[U];
-        bool ok[U];
-#pragma unroll
-        for (int j = 0; j < U; ++j) {
-            const int p = p0 + wave * 16 + j * RPW + r;
-            ok[j] = p < n;
-            const int t = sel[min(p, n - 1)];
-            const int64_t off = row_offset(a.kv, b, hk, t) + c * 8;
-            kr[j] = *(const u32x4*)(a.kv.k + off);
-            vr[j] = *(const u32x4*)(a.kv.v + off);
+    struct Tile {
+        u32x4 k[U], v[U];
+    };
+    for (int c0 = 0; c0 < n; c0 += ids_cap) {
+        const int nc = min(ids_cap, n - c0);
+        __syncthreads();                   // whatever used this LDS before is done with it
+        for (int i = tid; i < nc; i += WAVES * 64) {
+            const int t = sel[c0 + i];
+            ids[i] = paged ? (a.kv.page_table[(int64_t)b * a.kv.max_pages + (t >> shift)] << shift) | (t & mask) : t;
         }
-        float s[U];
-        float mx = m;
+        __syncthreads();
+        auto load = [&](Tile& T, int it) {
 #pragma unroll
-        for (int j = 0; j < U; ++j) {
-            float d = dot8(__builtin_bit_cast(half8_t, kr[j]), q8, 0.f);
-            d = group_sum<LPR>(d);
-            s[j] = ok[j] ? d * a.scale_log2 : -__builtin_inff();
-            mx = fmaxf(mx, s[j]);
-        }
-        const float al = fast_exp2(m - mx);
-        m = mx;
-        l *= al;
+            for (int j = 0; j < U; ++j) {
+                const int id = ids[min(it * TILE + wave * 16 + j * RPW + r, nc - 1)];
+                const int64_t off = base + (int64_t)(paged ? id >> shift : 0) * stride_page +
+                                    (int64_t)(paged ? id & mask : id) * a.kv.stride_t;
+                T.k[j] = *(const u32x4*)(a.kv.k + off);
+                T.v[j] = *(const u32x4*)(a.kv.v + off);
+            }
+        };
+        auto consume = [&](const Tile& T, int it) {
+            float s[U];
+            float mx = m;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc[e] *= al;
+            for (int j = 0; j < U; ++j) {
+                float d = dot8(__builtin_bit_cast(half8_t, T.k[j]), q8, 0.f);
+                d = group_sum<LPR>(d);
+                s[j] = it * TILE + wave * 16 + j * RPW + r < nc ? d * a.scale_log2 : -__builtin_inff();
+                mx = fmaxf(mx, s[j]);
+            }
+            const float al = fast_exp2(m - mx);
+            m = mx;
+            l *= al;
 #pragma unroll
-        for (int j = 0; j < U; ++j) {
-            const float p = fast_exp2(s[j] - mx);
-            l += p;
-            const half8_t vh = __builtin_bit_cast(half8_t, vr[j]);
+            for (int e = 0; e < 8; ++e) acc[e] *= al;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) acc[e] = __builtin_fmaf((float)vh[e], p, acc[e]);
+            for (int j = 0; j < U; ++j) {
+                const float p = fast_exp2(s[j] - mx);
+                l += p;
+                const half8_t vh = __builtin_bit_cast(half8_t, T.v[j]);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[e] = __builtin_fmaf((float)vh[e], p, acc[e]);
+            }
+        };
+        const int n_it = (nc + TILE - 1) / TILE;
+        Tile A, B;
+        load(A, 0);
+        for (int it = 0; it < n_it; it += 2) {
+            load(B, it + 1);
+            pin_order();
+            consume(A, it);
+            load(A, it + 2);
+            pin_order();
+            if (it + 1 < n_it) consume(B, it + 1);
         }
     }
 
@@ -485,7 +571,7 @@ __global__ __launch_bounds__(256) void sparf_logits_kernel(SparfArgs a)
     __shared__ float s_q[128];
     __shared__ float s_abs[128];
     __shared__ int s_dim[128];
-    __shared__ float s_red[4];
+    __shared__ float s_red[32];
     const float factor = prepare_query(a, row, s_q, s_abs, s_dim, s_red);
 
     const int t = t0 + tid * 8;
@@ -558,14 +644,15 @@ __global__ __launch_bounds__(kSparfAttendWaves * 64) void sparf_attend_kernel(Sp
     __shared__ float s_acc[NG][D];
     __shared__ float s_m[NG];
     __shared__ float s_l[NG];
-    attend_rows<D, kSparfAttendWaves>(a, b, h, L, min(a.k, L), a.sel + row * a.k, a.alpha[row], s_acc, s_m,
-                                      s_l);
+    __shared__ int32_t s_ids[kSparfAttendIds];
+    attend_rows<D, kSparfAttendWaves>(a, b, h, L, min(a.k, L), a.sel + row * a.k, a.alpha[row], s_ids,
+                                      kSparfAttendIds, s_acc, s_m, s_l);
 }
 
 // The whole of Algorithm 1 for one query head in one block of NT threads; the
 // scores live in dynamic LDS (one float per position, rows of at most 8192).
 template <int D, int NT>
-__global__ __launch_bounds__(NT) void sparf_fused_kernel(SparfArgs a)
+__global__ __launch_bounds__(NT, 3) void sparf_fused_kernel(SparfArgs a)
 {
     constexpr int NG = (NT / 64) * (kWave / (D / 8));
     const int h = blockIdx.x, b = blockIdx.y;
@@ -573,13 +660,7 @@ __global__ __launch_bounds__(NT) void sparf_fused_kernel(SparfArgs a)
     const int hk = h / G;
     const int tid = threadIdx.x;
     const int64_t row = (int64_t)b * a.num_q_heads + h;
-    const int L = clamp_len(a.seq_lens[b], a.max_len);
-    if (L == 0) {
-        write_zero_row<D>(a, row);
-        if (tid == 0) a.alpha[row] = 0.f;
-        return;
-    }
-    extern __shared__ float xs[];             // scores, log2 domain
+    extern __shared__ __align__(16) float xs[];   // scores, log2 domain
     __shared__ float s_q[128];
     __shared__ float s_abs[128];
     __shared__ int s_dim[128];
@@ -588,35 +669,78 @@ __global__ __launch_bounds__(NT) void sparf_fused_kernel(SparfArgs a)
     __shared__ float s_m[NG];
     __shared__ float s_l[NG];
 
-    // steps 1-4
+    // steps 1-4; the length is not needed before the column pass, so its load and
+    // the load of q are in flight together
+    const int L_raw = a.seq_lens[b];
     const float factor = prepare_query(a, row, s_q, s_abs, s_dim, S.red);
+    const int L = clamp_len(L_raw, a.max_len);
+    if (L == 0) {
+        write_zero_row<D>(a, row);
+        if (tid == 0) a.alpha[row] = 0.f;
+        return;
+    }
+    // kept columns in groups of 16, then 8, 4, 2, 1
+    {
+        int j0 = 0;
+        for (; j0 + 16 <= a.r; j0 += 16) column_pass<16, NT>(a, b, hk, L, j0, j0 == 0, factor, s_q, s_dim, xs);
+        if (a.r - j0 >= 8) { column_pass<8, NT>(a, b, hk, L, j0, j0 == 0, factor, s_q, s_dim, xs); j0 += 8; }
+        if (a.r - j0 >= 4) { column_pass<4, NT>(a, b, hk, L, j0, j0 == 0, factor, s_q, s_dim, xs); j0 += 4; }
+        if (a.r - j0 >= 2) { column_pass<2, NT>(a, b, hk, L, j0, j0 == 0, factor, s_q, s_dim, xs); j0 += 2; }
+        if (a.r - j0 >= 1) column_pass<1, NT>(a, b, hk, L, j0, j0 == 0, factor, s_q, s_dim, xs);
+    }
+    // Softmax statistics of step 4.  A thread reads back only what it wrote itself (no
+    // barrier needed yet): its own max, min and sum of 2^(x - own max), then one block
+    // reduction for all three.
     float mx = kNegBig, mn = -kNegBig;
     for (int t = tid * 8; t < L; t += NT * 8) {
-        float x[8];
-        column_scores8(a, kt_col0(a.aux, b, hk, t), s_q, s_dim, x);
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            const bool in = t + e < L;
-            x[e] = in ? x[e] * factor : -__builtin_inff();
-            mx = fmaxf(mx, x[e]);
-            if (in) mn = fminf(mn, x[e]);
-            xs[t + e] = x[e];
+            if (t + e < L) {
+                const float x = xs[t + e];
+                mx = fmaxf(mx, x);
+                mn = fminf(mn, x);
+            }
         }
     }
-    const float M = block_max(mx, S.red);
-    const float xmin = block_min(mn, S.red);
     float zs = 0.f;
-    for (int t = tid; t < L; t += NT) zs += fast_exp2(xs[t] - M);
-    const float Z = block_sum(zs, S.red);
+    for (int t = tid * 8; t < L; t += NT * 8) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            if (t + e < L) zs += fast_exp2(xs[t + e] - mx);
+    }
+    float M, xmin, Z;
+    {
+        const float mw = wave_max(mx);
+        const float zw = wave_sum(zs * fast_exp2(mx - mw));
+        const float nw_min = -wave_max(-mn);
+        const int w = tid >> 6;
+        __syncthreads();                       // S.red is free (prepare_query's readers are done)
+        if ((tid & 63) == 0) {
+            S.red[w] = mw;
+            S.red[16 + w] = zw;
+            S.red[32 + w] = nw_min;
+        }
+        __syncthreads();
+        M = kNegBig;
+        xmin = -kNegBig;
+#pragma unroll
+        for (int i = 0; i < NT / 64; ++i) {
+            M = fmaxf(M, S.red[i]);
+            xmin = fminf(xmin, S.red[32 + i]);
+        }
+        Z = 0.f;
+#pragma unroll
+        for (int i = 0; i < NT / 64; ++i) Z += S.red[16 + i] * fast_exp2(S.red[i] - M);
+    }
 
     // steps 5-7
     int32_t* sel = a.sel + row * a.k;
     const float alpha = select_rows<NT>(xs, L, a.k, a.l, M, xmin, Z, sel, S);
     if (tid == 0) a.alpha[row] = alpha;
-    __syncthreads();                          // the kept positions are read back below
 
-    // steps 10-11
-    attend_rows<D, NT / 64>(a, b, h, L, min(a.k, L), sel, alpha, s_acc, s_m, s_l);
+    // steps 10-11; the scores are dead, their LDS takes the row ids (the barrier
+    // in front of that also makes the kept positions visible to the whole block)
+    attend_rows<D, NT / 64>(a, b, h, L, min(a.k, L), sel, alpha, (int32_t*)xs, (L + 7) & ~7, s_acc, s_m, s_l);
 }
 
 // ---------------------------------------------------------------------------
@@ -727,17 +851,8 @@ hipError_t launch_sparf_fused(const SparfArgs& a, hipStream_t stream)
 {
     dim3 grid(a.num_q_heads, a.batch);
     const size_t lds = (size_t)((a.max_len + 7) / 8 * 8) * sizeof(float);
-    const char* e = getenv("INSTATTN_SPARF_NT");     // experiments: threads per block
-    const int nt = e ? atoi(e) : 256;
-    if (a.head_dim == 128) {
-        if (nt == 1024) hipLaunchKernelGGL((sparf_fused_kernel<128, 1024>), grid, dim3(1024), lds, stream, a);
-        else if (nt == 512) hipLaunchKernelGGL((sparf_fused_kernel<128, 512>), grid, dim3(512), lds, stream, a);
-        else hipLaunchKernelGGL((sparf_fused_kernel<128, 256>), grid, dim3(256), lds, stream, a);
-    } else {
-        if (nt == 1024) hipLaunchKernelGGL((sparf_fused_kernel<64, 1024>), grid, dim3(1024), lds, stream, a);
-        else if (nt == 512) hipLaunchKernelGGL((sparf_fused_kernel<64, 512>), grid, dim3(512), lds, stream, a);
-        else hipLaunchKernelGGL((sparf_fused_kernel<64, 256>), grid, dim3(256), lds, stream, a);
-    }
+    if (a.head_dim == 128) hipLaunchKernelGGL((sparf_fused_kernel<128, 256>), grid, dim3(256), lds, stream, a);
+    else hipLaunchKernelGGL((sparf_fused_kernel<64, 256>), grid, dim3(256), lds, stream, a);
     return hipGetLastError();
 }
 
