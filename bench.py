@@ -139,8 +139,12 @@ def bench_sparf(args):
 
     def sparf_step(i):
         c, d, a = cases[i % R], descs[i % R], auxs[i % R]
-        B.sparf_append(d, a, c.k_new, c.v_new, c.seq_lens)
-        B.sparf_decode(c.q, d, a, c.seq_lens, wl.num_kv_heads, c.scale, r, k, l, out, ws, max_len)
+        if args.two_calls:
+            B.sparf_append(d, a, c.k_new, c.v_new, c.seq_lens)
+            B.sparf_decode(c.q, d, a, c.seq_lens, wl.num_kv_heads, c.scale, r, k, l, out, ws, max_len)
+        else:
+            B.sparf_append_decode(c.q, c.k_new, c.v_new, d, a, c.seq_lens, wl.num_kv_heads, c.scale,
+                                  r, k, l, out, ws, max_len)
 
     def dense_step(i):
         c, d = cases[i % R], descs[i % R]
@@ -164,7 +168,8 @@ def bench_sparf(args):
         "vs_baseline": None, "dtype": "f16", "data": "synthetic",
         "config": {"workload": wl.name, "r": r, "k": k, "l": l, "layers_resident": R,
                    "kt_page": kt_page,
-                   "step": "sparf_append + sparf_decode (column scores, selection, gather attention)"},
+                   "step": ("sparf_append + sparf_decode" if args.two_calls else "sparf_append_decode") +
+                           " (column scores, selection, gather attention)"},
         "dense_ms_per_step": t_dense * 1e3, "speedup_over_dense_step": t_dense / t_sparf,
         "bytes_read_algorithm1": sparf_bytes, "bytes_read_dense": dense_bytes,
         "compression": sparf_bytes / dense_bytes, "score_bytes_written_and_read": score_bytes,

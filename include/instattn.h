@@ -267,6 +267,22 @@ int instattn_sparf_decode(const void* q, const instattn_kv_desc* kv, const insta
                           int max_seq_len, void* stream);
 
 /*
+ * instattn_sparf_append followed by instattn_sparf_decode, as the storage side sees
+ * a decode step (the new token's q, k, v arrive together, Sec. IV-D): same results
+ * in the cache, in aux and in out/sel_rows/alpha as the two calls in that order.
+ * When max_seq_len <= 8192 and every KV head has one query head, the one launch of
+ * the decode stores the new token itself; otherwise the append is a launch of its
+ * own in front.  Like instattn_sparf_append it must be called once per new token.
+ *   k_new, v_new : device, [batch][num_kv_heads][head_dim] fp16, dense
+ */
+int instattn_sparf_append_decode(const void* q, const void* k_new, const void* v_new,
+                                 const instattn_kv_desc* kv, const instattn_sparf_aux* aux,
+                                 const int32_t* seq_lens, int batch, int num_q_heads, int num_kv_heads,
+                                 int head_dim, float scale, int r, int k, int l, void* out, int out_dtype,
+                                 int32_t* sel_rows, float* alpha, void* workspace, size_t workspace_bytes,
+                                 int max_seq_len, void* stream);
+
+/*
  * Measurement aids, not part of the attention path.  probe_read streams `bytes`
  * (a multiple of 16) from src with 128-bit loads and folds them into 4 bytes per
  * workgroup written to sink (device, >= 16 KiB): the read ceiling a streaming

@@ -91,6 +91,9 @@ def lib() -> ctypes.CDLL:
         L.instattn_sparf_append.argtypes = [pk, pa, vp, vp, vp, i, i, i, vp]
         L.instattn_sparf_workspace_size.restype = sz
         L.instattn_sparf_workspace_size.argtypes = [i, i, i, i, i]
+        L.instattn_sparf_append_decode.restype = i
+        L.instattn_sparf_append_decode.argtypes = [vp, vp, vp, pk, pa, vp, i, i, i, i, f, i, i, i, vp, i, vp, vp,
+                                                   vp, sz, i, vp]
         L.instattn_sparf_decode.restype = i
         L.instattn_sparf_decode.argtypes = [vp, pk, pa, vp, i, i, i, i, f, i, i, i, vp, i, vp, vp,
                                             vp, sz, i, vp]
@@ -297,3 +300,20 @@ def sparf_decode(q, desc: KvDesc, aux: SparfAux, seq_lens, num_kv_heads: int, sc
         F16 if out.dtype == torch.float16 else F32, _p(sel_rows), _p(alpha), _p(workspace),
         workspace.numel() * workspace.element_size(), int(max_seq_len), _stream(stream)),
         "instattn_sparf_decode")
+
+
+def sparf_append_decode(q, k_new, v_new, desc: KvDesc, aux: SparfAux, seq_lens, num_kv_heads: int,
+                        scale: float, r: int, k: int, l: int, out, workspace, max_seq_len: int,
+                        sel_rows=None, alpha=None, stream=None) -> None:
+    B, Hq, D = q.shape
+    assert q.dtype == torch.float16 and q.is_contiguous() and out.is_contiguous()
+    assert k_new.dtype == torch.float16 and k_new.is_contiguous() and k_new.shape == (B, num_kv_heads, D)
+    assert v_new.dtype == torch.float16 and v_new.is_contiguous() and v_new.shape == (B, num_kv_heads, D)
+    assert sel_rows is None or (sel_rows.dtype == torch.int32 and sel_rows.shape == (B, Hq, k))
+    assert alpha is None or (alpha.dtype == torch.float32 and alpha.shape == (B, Hq))
+    _check(lib().instattn_sparf_append_decode(
+        _p(q), _p(k_new), _p(v_new), ctypes.byref(desc), ctypes.byref(aux), _p(seq_lens), B, Hq,
+        num_kv_heads, D, float(scale), int(r), int(k), int(l), _p(out),
+        F16 if out.dtype == torch.float16 else F32, _p(sel_rows), _p(alpha), _p(workspace),
+        workspace.numel() * workspace.element_size(), int(max_seq_len), _stream(stream)),
+        "instattn_sparf_append_decode")

@@ -121,17 +121,22 @@ size_t instattn_sparf_workspace_size(int batch, int num_q_heads, int head_dim, i
     return carve(batch, num_q_heads, max_seq_len, k).total;
 }
 
-int instattn_sparf_decode(const void* q, const instattn_kv_desc* kv, const instattn_sparf_aux* aux,
-                          const int32_t* seq_lens, int batch, int num_q_heads, int num_kv_heads,
-                          int head_dim, float scale, int r, int k, int l, void* out, int out_dtype,
-                          int32_t* sel_rows, float* alpha, void* workspace, size_t workspace_bytes,
-                          int max_seq_len, void* stream)
+}  // extern "C"
+
+namespace {
+
+int run_sparf_decode(const void* q, const void* k_new, const void* v_new, bool append,
+                     const instattn_kv_desc* kv, const instattn_sparf_aux* aux, const int32_t* seq_lens,
+                     int batch, int num_q_heads, int num_kv_heads, int head_dim, float scale, int r, int k,
+                     int l, void* out, int out_dtype, int32_t* sel_rows, float* alpha, void* workspace,
+                     size_t workspace_bytes, int max_seq_len, void* stream)
 {
     int st = check_common(kv, aux, batch, num_kv_heads, head_dim);
     if (st != INSTATTN_OK) return st;
     if (num_q_heads <= 0 || num_q_heads % num_kv_heads || max_seq_len <= 0) return INSTATTN_ERR_INVALID_ARG;
     if (batch > 65535 || num_q_heads > 65535) return INSTATTN_ERR_UNSUPPORTED;
     if (!q || !aligned16(q) || !seq_lens || !isfinite(scale)) return INSTATTN_ERR_INVALID_ARG;
+    if (append && (!k_new || !v_new)) return INSTATTN_ERR_INVALID_ARG;
     if (!out || !aligned16(out)) return INSTATTN_ERR_INVALID_ARG;
     if (out_dtype != INSTATTN_F16 && out_dtype != INSTATTN_F32) return INSTATTN_ERR_INVALID_ARG;
     if (r < 1 || r > head_dim || k < 1 || l < 0) return INSTATTN_ERR_INVALID_ARG;
@@ -162,13 +167,48 @@ int instattn_sparf_decode(const void* q, const instattn_kv_desc* kv, const insta
     a.alpha = alpha ? alpha : (float*)(ws + c.alpha);
     a.out = out;
     a.out_f32 = out_dtype == INSTATTN_F32;
+    a.k_new = append ? (const half_t*)k_new : nullptr;
+    a.v_new = append ? (const half_t*)v_new : nullptr;
     hipStream_t s = (hipStream_t)stream;
     const char* force3 = getenv("INSTATTN_SPARF_THREE_LAUNCHES");
-    if (max_seq_len <= kSparfFusedMaxLen && !(force3 && force3[0] == '1'))
-        return status_of(launch_sparf_fused(a, s));
+    const bool one_launch = max_seq_len <= kSparfFusedMaxLen && !(force3 && force3[0] == '1');
+    // The one-launch kernel stores the new token itself when its block is the only
+    // reader of what it stores; otherwise the append is a launch of its own.
+    if (append && !(one_launch && num_q_heads == num_kv_heads)) {
+        if (launch_sparf_append(a, s) != hipSuccess) return INSTATTN_ERR_RUNTIME;
+        a.k_new = a.v_new = nullptr;
+    }
+    if (one_launch) return status_of(launch_sparf_fused(a, s));
     if (launch_sparf_logits(a, s) != hipSuccess) return INSTATTN_ERR_RUNTIME;
     if (launch_sparf_select(a, s) != hipSuccess) return INSTATTN_ERR_RUNTIME;
     return status_of(launch_sparf_attend(a, s));
+}
+
+}  // namespace
+
+extern "C" {
+
+int instattn_sparf_decode(const void* q, const instattn_kv_desc* kv, const instattn_sparf_aux* aux,
+                          const int32_t* seq_lens, int batch, int num_q_heads, int num_kv_heads,
+                          int head_dim, float scale, int r, int k, int l, void* out, int out_dtype,
+                          int32_t* sel_rows, float* alpha, void* workspace, size_t workspace_bytes,
+                          int max_seq_len, void* stream)
+{
+    return run_sparf_decode(q, nullptr, nullptr, false, kv, aux, seq_lens, batch, num_q_heads, num_kv_heads,
+                            head_dim, scale, r, k, l, out, out_dtype, sel_rows, alpha, workspace,
+                            workspace_bytes, max_seq_len, stream);
+}
+
+int instattn_sparf_append_decode(const void* q, const void* k_new, const void* v_new,
+                                 const instattn_kv_desc* kv, const instattn_sparf_aux* aux,
+                                 const int32_t* seq_lens, int batch, int num_q_heads, int num_kv_heads,
+                                 int head_dim, float scale, int r, int k, int l, void* out, int out_dtype,
+                                 int32_t* sel_rows, float* alpha, void* workspace, size_t workspace_bytes,
+                                 int max_seq_len, void* stream)
+{
+    return run_sparf_decode(q, k_new, v_new, true, kv, aux, seq_lens, batch, num_q_heads, num_kv_heads,
+                            head_dim, scale, r, k, l, out, out_dtype, sel_rows, alpha, workspace,
+                            workspace_bytes, max_seq_len, stream);
 }
 
 }  // extern "C"

@@ -46,7 +46,7 @@ struct SparfArgs {
     float* alpha;                      // [B][Hq] selected share of the approximate softmax
     void* out;
     int32_t out_f32;
-    const half_t* k_new;               // append only
+    const half_t* k_new;               // append, or decode with the append fused in
     const half_t* v_new;
 };
 

@@ -24,7 +24,9 @@
 //                         positions.
 //   sparf_build_kernel    builds the component-major K copy and the running sum
 //                         of V from an existing cache (prefill side).
-//   sparf_append_kernel   kv_append plus the new column entry and sum update.
+//   sparf_append_kernel   kv_append plus the new column entry and sum update (the
+//                         one-launch kernel does this itself when asked to and
+//                         every KV head has a single query head).
 #include "sparf.h"
 
 #include <stdlib.h>
@@ -243,25 +245,107 @@ __device__ __forceinline__ void locate_bin(SelectScratch& S, uint32_t remaining,
     }
 }
 
+// Level-1 bucket of a score: linear between the row's minimum and maximum,
+// monotone in the score, so every score in a higher bucket is >= every score in a
+// lower one.
+struct Level1 {
+    float M, binscale;
+    __device__ __forceinline__ Level1(float M_, float xmin) : M(M_), binscale(M_ > xmin ? 255.99f / (M_ - xmin) : 0.f) {}
+    __device__ __forceinline__ uint32_t operator()(float v) const {
+        return 255u - (uint32_t)min(255, max(0, (int)((M - v) * binscale)));
+    }
+};
+
+// The threshold of the top-`want` candidates, exactly, in two levels.  Level 1
+// buckets the scores into 256 bins (scores spread evenly over these, unlike over
+// the exponent byte of a float).  Level 2 works on the members of the one bin that
+// holds the threshold: normally a few dozen, which are gathered and ranked against
+// each other directly; if there are more than kSelMembers (e.g. all scores equal)
+// a 4-pass radix select on order-preserving keys takes over.  The outcome: the
+// kept candidates are those in a bin above bin1, those in bin1 with a key above
+// `prefix`, and the first `remaining` (in position order) with exactly that key.
+// for_each(f) calls f(score) for every candidate of the calling thread; it is
+// called several times and must visit the same candidates each time.
+template <int NT, class ForEach>
+__device__ __forceinline__ void find_threshold(ForEach&& for_each, int want, const Level1& level1,
+                                               SelectScratch& S, uint32_t& bin1, uint32_t& prefix,
+                                               uint32_t& remaining)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    bin1 = 0;
+    prefix = 0;
+    remaining = (uint32_t)want;
+    if (want <= 0) return;
+    // level 1
+    if (tid < 256) S.hist[tid] = 0;
+    if (tid == 0) S.nmem = 0;
+    __syncthreads();
+    for_each([&](float v) { atomicAdd(&S.hist[level1(v)], 1u); });
+    __syncthreads();
+    if (wave == 0) locate_bin(S, remaining, lane);
+    __syncthreads();
+    bin1 = S.prefix;
+    remaining = S.remaining;
+    // level 2: gather the members of bin1
+    const uint32_t b1 = bin1;
+    for_each([&](float v) {
+        if (level1(v) == b1) {
+            const uint32_t i = atomicAdd(&S.nmem, 1u);
+            if (i < (uint32_t)kSelMembers) S.mem_key[i] = order_key(v);
+        }
+    });
+    __syncthreads();
+    const uint32_t nmem = S.nmem;
+    if (nmem <= (uint32_t)kSelMembers) {
+        // rank every member against the others: the threshold key is the one with
+        // fewer than `remaining` keys above it and at least `remaining` at or above
+        for (uint32_t i = tid; i < nmem; i += NT) {
+            const uint32_t mine = S.mem_key[i];
+            uint32_t gt = 0, ge = 0;
+            for (uint32_t j = 0; j < nmem; ++j) {
+                const uint32_t o = S.mem_key[j];
+                gt += o > mine;
+                ge += o >= mine;
+            }
+            if (gt < remaining && remaining <= ge) {     // same values from every such member
+                S.prefix = mine;
+                S.remaining = remaining - gt;
+            }
+        }
+        __syncthreads();
+        prefix = S.prefix;
+        remaining = S.remaining;
+    } else {
+        for (int shift = 24; shift >= 0; shift -= 8) {
+            __syncthreads();
+            if (tid < 256) S.hist[tid] = 0;
+            __syncthreads();
+            const uint32_t hi_mask = shift == 24 ? 0u : (0xFFFFFFFFu << (shift + 8));
+            const uint32_t pfx = prefix;
+            for_each([&](float v) {
+                const uint32_t key = order_key(v);
+                if (level1(v) == b1 && (key & hi_mask) == (pfx & hi_mask))
+                    atomicAdd(&S.hist[(key >> shift) & 255u], 1u);
+            });
+            __syncthreads();
+            if (wave == 0) locate_bin(S, remaining, lane);
+            __syncthreads();
+            prefix |= S.prefix << shift;
+            remaining = S.remaining;
+        }
+    }
+}
+
 // Steps 5-7 for one head: x[0..L) are the log2-domain scores (LDS or global), M
 // their maximum, xmin their minimum and Z the sum of 2^(x - M).  Writes the kept
 // positions in ascending order to sel and returns alpha to every thread.
 //
-// The threshold is found exactly in two levels.  Level 1 buckets the scores
-// linearly between xmin and M into 256 bins (monotone in x, so every score in a
-// higher bin is >= every score in a lower one); scores spread evenly over these
-// bins, unlike over the exponent byte of a float.  Level 2 works on the members of
-// the one bin that holds the threshold: normally a few dozen, which are gathered
-// and ranked against each other directly; if there are more than kSelMembers
-// (e.g. all scores equal) a 4-pass radix select on order-preserving keys takes
-// over.  Either way the outcome is a threshold key and the number of rows with
-// exactly that key still to keep.  The compaction is ordered: a wave owns a run of
-// consecutive positions (lane i takes every 64th from its i-th), ranks its kept
-// rows with ballots and popcounts alone, and one barrier per round of up to 32
-// positions per thread passes the wave totals on.  The output slot of a row is
-// (rows above the threshold before it) + min(rows at the threshold before it,
-// number of those still wanted), so ties go to the lower position and the result
-// is deterministic.
+// The compaction is ordered: a wave owns a run of consecutive positions (lane i
+// takes every 64th from its i-th), ranks its kept rows with ballots and popcounts
+// alone, and one barrier per round of up to 32 positions per thread passes the
+// wave totals on.  The output slot of a row is (rows above the threshold before
+// it) + min(rows at the threshold before it, number of those still wanted), so
+// ties go to the lower position and the result is deterministic.
 template <int NT>
 __device__ __forceinline__ float select_rows(const float* x, int L, int k, int l, float M, float xmin, float Z,
                                              int32_t* sel, SelectScratch& S)
@@ -272,88 +356,24 @@ __device__ __forceinline__ float select_rows(const float* x, int L, int k, int l
     const int leff = min(l, keff);
     const int want = keff - leff;          // rows to pick among the candidates
     const int ncand = L - leff;            // candidates: positions [0, ncand)
+    const Level1 level1(M, xmin);
 
-    const float binscale = M > xmin ? 255.99f / (M - xmin) : 0.f;
-    auto level1 = [&](float v) { return 255u - (uint32_t)min(255, max(0, (int)((M - v) * binscale))); };
+    uint32_t bin1, prefix, remaining;
+    // eight independent loads per thread before they are used (the scores may live in
+    // global memory)
+    find_threshold<NT>(
+        [&](auto&& f) {
+            for (int t0 = tid; t0 < ncand; t0 += 8 * NT) {
+                float v[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) v[j] = t0 + j * NT < ncand ? x[t0 + j * NT] : M;
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    if (t0 + j * NT < ncand) f(v[j]);
+            }
+        },
+        want, level1, S, bin1, prefix, remaining);
 
-    uint32_t bin1 = 0, prefix = 0, remaining = (uint32_t)want;
-    if (want > 0) {
-        // level 1
-        if (tid < 256) S.hist[tid] = 0;
-        if (tid == 0) S.nmem = 0;
-        __syncthreads();
-        // eight independent loads per thread before their histogram updates (the scores
-        // may live in global memory)
-        for (int t0 = tid; t0 < ncand; t0 += 8 * NT) {
-            float v[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) v[j] = t0 + j * NT < ncand ? x[t0 + j * NT] : M;
-#pragma unroll
-            for (int j = 0; j < 8; ++j)
-                if (t0 + j * NT < ncand) atomicAdd(&S.hist[level1(v[j])], 1u);
-        }
-        __syncthreads();
-        if (wave == 0) locate_bin(S, remaining, lane);
-        __syncthreads();
-        bin1 = S.prefix;
-        remaining = S.remaining;
-        // level 2: gather the members of bin1
-        for (int t0 = tid; t0 < ncand; t0 += 8 * NT) {
-            float v[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) v[j] = t0 + j * NT < ncand ? x[t0 + j * NT] : M;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                if (t0 + j * NT < ncand && level1(v[j]) == bin1) {
-                    const uint32_t i = atomicAdd(&S.nmem, 1u);
-                    if (i < (uint32_t)kSelMembers) S.mem_key[i] = order_key(v[j]);
-                }
-            }
-        }
-        __syncthreads();
-        const uint32_t nmem = S.nmem;
-        if (nmem <= (uint32_t)kSelMembers) {
-            // rank every member against the others: the threshold key is the one with
-            // fewer than `remaining` keys above it and at least `remaining` at or above
-            for (uint32_t i = tid; i < nmem; i += NT) {
-                const uint32_t mine = S.mem_key[i];
-                uint32_t gt = 0, ge = 0;
-                for (uint32_t j = 0; j < nmem; ++j) {
-                    const uint32_t o = S.mem_key[j];
-                    gt += o > mine;
-                    ge += o >= mine;
-                }
-                if (gt < remaining && remaining <= ge) {     // same values from every such member
-                    S.prefix = mine;
-                    S.remaining = remaining - gt;
-                }
-            }
-            __syncthreads();
-            prefix = S.prefix;
-            remaining = S.remaining;
-        } else {
-            for (int shift = 24; shift >= 0; shift -= 8) {
-                __syncthreads();
-                if (tid < 256) S.hist[tid] = 0;
-                __syncthreads();
-                const uint32_t hi_mask = shift == 24 ? 0u : (0xFFFFFFFFu << (shift + 8));
-                for (int t = tid; t < ncand; t += NT) {
-                    const float v = x[t];
-                    const uint32_t key = order_key(v);
-                    if (level1(v) == bin1 && (key & hi_mask) == (prefix & hi_mask))
-                        atomicAdd(&S.hist[(key >> shift) & 255u], 1u);
-                }
-                __syncthreads();
-                if (wave == 0) locate_bin(S, remaining, lane);
-                __syncthreads();
-                prefix |= S.prefix << shift;
-                remaining = S.remaining;
-            }
-        }
-    }
-
-    // kept: everything in a bin above bin1; inside bin1 the keys above the threshold
-    // key, plus the first `remaining` rows with exactly that key
     float mass = 0.f;
     const uint64_t lt_mask = lane == 0 ? 0ull : (~0ull >> (64 - lane));
     const int per = min(kSelPer, ((ncand + NT - 1) / NT + 7) & ~7);   // positions per thread and round
@@ -412,6 +432,103 @@ __device__ __forceinline__ float select_rows(const float* x, int L, int k, int l
         const int t = ncand + i;
         sel[want + i] = t;
         mass += fast_exp2(x[t] - M);
+    }
+    return block_sum(mass, S.red) / Z;     // step 7
+}
+
+// The same for a row of at most STEPS * NT * 8 positions whose scores the threads
+// hold in registers: xr[i][e] is the score of position (i * NT + tid) * 8 + e (what
+// the column pass gave this thread); xs holds the same scores in LDS.  Position
+// order is (i, wave, lane, e): a shuffle scan over the lanes of a wave per step i,
+// the wave totals per step through LDS, one barrier.
+template <int NT, int STEPS>
+__device__ __forceinline__ float select_rows_reg(const float (&xr)[STEPS][8], const float* xs, int L, int k,
+                                                 int l, float M, float xmin, float Z, int32_t* sel,
+                                                 SelectScratch& S)
+{
+    constexpr int NW = NT / 64;
+    static_assert(STEPS * NW <= 32 && STEPS * 8 <= 32, "counts and flag words");
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int keff = min(k, L);
+    const int leff = min(l, keff);
+    const int want = keff - leff;
+    const int ncand = L - leff;
+    const Level1 level1(M, xmin);
+
+    uint32_t bin1, prefix, remaining;
+    find_threshold<NT>(
+        [&](auto&& f) {
+#pragma unroll
+            for (int i = 0; i < STEPS; ++i) {
+                if (i * NT * 8 < ncand) {                      // block-uniform
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if ((i * NT + tid) * 8 + e < ncand) f(xr[i][e]);
+                }
+            }
+        },
+        want, level1, S, bin1, prefix, remaining);
+
+    float mass = 0.f;
+    if (want > 0) {
+        uint32_t gtbits = 0, eqbits = 0;                       // bit 8i + e
+        uint32_t excl[STEPS];                                  // kept before this lane in its wave, per step
+        uint32_t* step_cnt = &S.wave_cnt[0][0];                // [STEPS][NW]
+#pragma unroll
+        for (int i = 0; i < STEPS; ++i) {
+            uint32_t c = 0;
+            if (i * NT * 8 < ncand) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const bool valid = (i * NT + tid) * 8 + e < ncand;
+                    const uint32_t b1 = level1(xr[i][e]);
+                    const uint32_t key = order_key(xr[i][e]);
+                    const bool gt = valid && (b1 > bin1 || (b1 == bin1 && key > prefix));
+                    const bool eq = valid && b1 == bin1 && key == prefix;
+                    gtbits |= (uint32_t)gt << (8 * i + e);
+                    eqbits |= (uint32_t)eq << (8 * i + e);
+                    c += (uint32_t)gt + ((uint32_t)eq << 16);
+                }
+            }
+            uint32_t incl = c;                                 // 16-bit halves: at most 512 each
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                const uint32_t o = __shfl_up(incl, d, 64);
+                if (lane >= d) incl += o;
+            }
+            excl[i] = incl - c;
+            if (lane == 63) step_cnt[i * NW + wave] = incl;
+        }
+        __syncthreads();
+        uint32_t run = 0;                                      // halves: at most 8192 each
+#pragma unroll
+        for (int i = 0; i < STEPS; ++i) {
+            uint32_t mine = 0;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) {
+                mine = w == wave ? run : mine;
+                run += step_cnt[i * NW + w];
+            }
+            uint32_t gb = (mine + excl[i]) & 0xFFFFu, eb = (mine + excl[i]) >> 16;
+            if (((gtbits | eqbits) >> (8 * i)) & 0xFFu) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const bool gt = (gtbits >> (8 * i + e)) & 1u, eq = (eqbits >> (8 * i + e)) & 1u;
+                    if (gt || (eq && eb < remaining)) {
+                        sel[gb + min(eb, remaining)] = (i * NT + tid) * 8 + e;
+                        mass += fast_exp2(xr[i][e] - M);
+                    }
+                    gb += (uint32_t)gt;
+                    eb += (uint32_t)eq;
+                }
+            }
+        }
+    }
+    // step 5: the l most recent positions are always kept
+    for (int i = tid; i < leff; i += NT) {
+        const int t = ncand + i;
+        sel[want + i] = t;
+        mass += fast_exp2(xs[t] - M);
     }
     return block_sum(mass, S.red) / Z;     // step 7
 }
@@ -535,6 +652,21 @@ __device__ __forceinline__ void attend_rows(const SparfArgs& a, int b, int h, in
         if (a.out_f32) ((float*)a.out)[row * D + tid] = o;
         else ((half_t*)a.out)[row * D + tid] = (half_t)o;
     }
+}
+
+// Component d of the new token of (sequence b, KV head hk) goes into the cache row,
+// the column copy and the V sum; L is the length including that token.
+__device__ __forceinline__ void append_component(const SparfArgs& a, int b, int hk, int d, int L)
+{
+    if (L < 1 || L > a.kv.capacity || L > a.aux.capacity) return;
+    const int t = L - 1;
+    const int64_t i = ((int64_t)b * a.num_kv_heads + hk) * a.head_dim + d;
+    const half_t kn = a.k_new[i], vn = a.v_new[i];
+    const int64_t off = row_offset(a.kv, b, hk, t) + d;
+    const_cast<half_t*>(a.kv.k)[off] = kn;
+    const_cast<half_t*>(a.kv.v)[off] = vn;
+    kt_col0(a.aux, b, hk, t)[(int64_t)d * a.aux.stride_d] = kn;
+    a.aux.vsum[i] += (float)vn;
 }
 
 template <int D>
@@ -672,6 +804,10 @@ __global__ __launch_bounds__(NT, 3) void sparf_fused_kernel(SparfArgs a)
     // steps 1-4; the length is not needed before the column pass, so its load and
     // the load of q are in flight together
     const int L_raw = a.seq_lens[b];
+    // Fused append (one query head per KV head only: this block is the only reader
+    // of the row, the column entries and the sum it writes).  The barriers inside
+    // prepare_query order these stores before the block's later loads.
+    if (a.k_new != nullptr && tid < D) append_component(a, b, hk, tid, L_raw);
     const float factor = prepare_query(a, row, s_q, s_abs, s_dim, S.red);
     const int L = clamp_len(L_raw, a.max_len);
     if (L == 0) {
@@ -688,26 +824,41 @@ __global__ __launch_bounds__(NT, 3) void sparf_fused_kernel(SparfArgs a)
         if (a.r - j0 >= 2) { column_pass<2, NT>(a, b, hk, L, j0, j0 == 0, factor, s_q, s_dim, xs); j0 += 2; }
         if (a.r - j0 >= 1) column_pass<1, NT>(a, b, hk, L, j0, j0 == 0, factor, s_q, s_dim, xs);
     }
-    // Softmax statistics of step 4.  A thread reads back only what it wrote itself (no
-    // barrier needed yet): its own max, min and sum of 2^(x - own max), then one block
-    // reduction for all three.
-    float mx = kNegBig, mn = -kNegBig;
-    for (int t = tid * 8; t < L; t += NT * 8) {
+    // A thread takes back the scores it wrote itself (no barrier needed) and keeps them
+    // in registers for the rest of steps 4-7.
+    constexpr int STEPS = kSparfFusedMaxLen / (NT * 8);
+    float xr[STEPS][8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            if (t + e < L) {
-                const float x = xs[t + e];
-                mx = fmaxf(mx, x);
-                mn = fminf(mn, x);
-            }
+    for (int i = 0; i < STEPS; ++i) {
+        const int t = (i * NT + tid) * 8;
+        float4_t lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};
+        if (t < L) {
+            lo = *(const float4_t*)(xs + t);
+            hi = *(const float4_t*)(xs + t + 4);
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            xr[i][e] = lo[e];
+            xr[i][4 + e] = hi[e];
         }
     }
-    float zs = 0.f;
-    for (int t = tid * 8; t < L; t += NT * 8) {
+    // Softmax statistics of step 4: own max, min and sum of 2^(x - own max), then one
+    // block reduction for all three.
+    float mx = kNegBig, mn = -kNegBig;
+#pragma unroll
+    for (int i = 0; i < STEPS; ++i)
 #pragma unroll
         for (int e = 0; e < 8; ++e)
-            if (t + e < L) zs += fast_exp2(xs[t + e] - mx);
-    }
+            if ((i * NT + tid) * 8 + e < L) {
+                mx = fmaxf(mx, xr[i][e]);
+                mn = fminf(mn, xr[i][e]);
+            }
+    float zs = 0.f;
+#pragma unroll
+    for (int i = 0; i < STEPS; ++i)
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            if ((i * NT + tid) * 8 + e < L) zs += fast_exp2(xr[i][e] - mx);
     float M, xmin, Z;
     {
         const float mw = wave_max(mx);
@@ -735,7 +886,7 @@ __global__ __launch_bounds__(NT, 3) void sparf_fused_kernel(SparfArgs a)
 
     // steps 5-7
     int32_t* sel = a.sel + row * a.k;
-    const float alpha = select_rows<NT>(xs, L, a.k, a.l, M, xmin, Z, sel, S);
+    const float alpha = select_rows_reg<NT, STEPS>(xr, xs, L, a.k, a.l, M, xmin, Z, sel, S);
     if (tid == 0) a.alpha[row] = alpha;
 
     // steps 10-11; the scores are dead, their LDS takes the row ids (the barrier
@@ -808,15 +959,7 @@ __global__ __launch_bounds__(256) void sparf_append_kernel(SparfArgs a)
     const int d = (int)(i % D);
     const int hk = (int)((i / D) % a.num_kv_heads);
     const int b = (int)(i / ((int64_t)D * a.num_kv_heads));
-    const int L = a.seq_lens[b];
-    if (L < 1 || L > a.kv.capacity || L > a.aux.capacity) return;
-    const int t = L - 1;
-    const half_t kn = a.k_new[i], vn = a.v_new[i];
-    const int64_t off = row_offset(a.kv, b, hk, t) + d;
-    const_cast<half_t*>(a.kv.k)[off] = kn;
-    const_cast<half_t*>(a.kv.v)[off] = vn;
-    kt_col0(a.aux, b, hk, t)[(int64_t)d * a.aux.stride_d] = kn;
-    a.aux.vsum[i] += (float)vn;
+    append_component(a, b, hk, d, a.seq_lens[b]);
 }
 
 // ---------------------------------------------------------------------------

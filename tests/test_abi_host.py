@@ -25,7 +25,7 @@ def test_library_exports_every_declared_symbol():
             "instattn_decode_merge", "instattn_decode_plan", "instattn_decode_workspace_size",
             "instattn_status_string", "instattn_version", "instattn_probe_read",
             "instattn_append_decode", "instattn_kv_write", "instattn_sparf_build", "instattn_sparf_append",
-            "instattn_sparf_decode", "instattn_sparf_workspace_size",
+            "instattn_sparf_decode", "instattn_sparf_workspace_size", "instattn_sparf_append_decode",
             "instattn_probe_copy"} <= set(names)
     lib = B.lib()
     for n in names:
@@ -220,6 +220,20 @@ def test_sparf_accepts_either_layout_of_either_copy():
     for d in (desc(), paged_desc()):
         for a in (aux_desc(), paged_aux_desc()):
             assert sparf_status(d=d, a=a, ws_bytes=4096) == B.ERR_WORKSPACE
+
+
+def test_sparf_append_decode_rejects():
+    L = B.lib()
+    d, a = desc(), aux_desc()
+    args = [FAKE, FAKE, FAKE, ctypes.byref(d), ctypes.byref(a), FAKE, 16, 40, 40, 128, 0.088, 16, 256, 16,
+            FAKE, B.F16, None, None, FAKE & ~255, 1 << 30, 4097, None]
+    for i in (0, 1, 2, 5, 14):
+        bad = list(args)
+        bad[i] = None
+        assert L.instattn_sparf_append_decode(*bad) == B.ERR_INVALID_ARG, i
+    bad = list(args)
+    bad[19] = 4096
+    assert L.instattn_sparf_append_decode(*bad) == B.ERR_WORKSPACE
 
 
 def test_sparf_build_and_append_reject():

@@ -79,7 +79,7 @@ def setup(wl, build_lens_offset=-1, kt_page=None):
     return case, desc, aux, kt, vsum, before
 
 
-def run_decode(case, desc, aux, r, k, l, out_dtype, max_len=None):
+def run_decode(case, desc, aux, r, k, l, out_dtype, max_len=None, fused_append=False):
     wl = case.wl
     Bn, Hq, D = case.q.shape
     max_len = max_len or max(1, int(case.seq_lens.max()))
@@ -88,8 +88,12 @@ def run_decode(case, desc, aux, r, k, l, out_dtype, max_len=None):
     out = torch.full((Bn, Hq, D), float("nan"), dtype=out_dtype, device=DEV)
     sel = torch.full((Bn, Hq, k), -1, dtype=torch.int32, device=DEV)
     alpha = torch.full((Bn, Hq), float("nan"), dtype=torch.float32, device=DEV)
-    B.sparf_decode(case.q, desc, aux, case.seq_lens, wl.num_kv_heads, case.scale, r, k, l, out, ws,
-                   max_len, sel_rows=sel, alpha=alpha)
+    if fused_append:
+        B.sparf_append_decode(case.q, case.k_new, case.v_new, desc, aux, case.seq_lens, wl.num_kv_heads,
+                              case.scale, r, k, l, out, ws, max_len, sel_rows=sel, alpha=alpha)
+    else:
+        B.sparf_decode(case.q, desc, aux, case.seq_lens, wl.num_kv_heads, case.scale, r, k, l, out, ws,
+                       max_len, sel_rows=sel, alpha=alpha)
     torch.cuda.synchronize()
     return out, sel, alpha
 
@@ -135,12 +139,13 @@ def check_against_oracle(case, out, sel, alpha, r, k, l, pairs=None):
     return worst
 
 
-def sparf_step(wl, r, k, l, out_dtype=torch.float32, pairs=None, kt_page=None):
+def sparf_step(wl, r, k, l, out_dtype=torch.float32, pairs=None, kt_page=None, fused_append=False):
     case, desc, aux, kt, vsum, before = setup(wl, kt_page=kt_page)
     want_k, want_v = logical(case)
     dense.kv_append(want_k, want_v, H.host(case.k_new), H.host(case.v_new), H.host(case.seq_lens))
-    B.sparf_append(desc, aux, case.k_new, case.v_new, case.seq_lens)
-    out, sel, alpha = run_decode(case, desc, aux, r, k, l, out_dtype)
+    if not fused_append:
+        B.sparf_append(desc, aux, case.k_new, case.v_new, case.seq_lens)
+    out, sel, alpha = run_decode(case, desc, aux, r, k, l, out_dtype, fused_append=fused_append)
     # the append part: caches bit-exact, column copy and V sums consistent with them
     got_k, got_v = logical(case)
     assert np.array_equal(got_k.view(np.uint16), want_k.view(np.uint16))
@@ -192,6 +197,38 @@ def test_sparf_paged_lengths_around_page_edges(seq_len):
 def test_sparf_paged_long_rows():
     wl = W.Workload("sparf_paged_long", 1, 2, 2, 128, 20000, paged=True, page_size=16, seed=412)
     sparf_step(wl, 16, 1300, 32, torch.float16, kt_page=1024)
+
+
+@pytest.mark.parametrize("shape", ["mha", "mha64", "gqa", "paged", "long", "three"])
+def test_sparf_append_decode_in_one_call(monkeypatch, shape):
+    """The fused entry point against the oracle, in every form it takes: the new token
+    stored by the one-launch kernel itself (one query head per KV head), or by a launch
+    of its own in front (grouped queries, long rows, the three-launch pipeline)."""
+    if shape == "three":
+        monkeypatch.setenv("INSTATTN_SPARF_THREE_LAUNCHES", "1")
+    wl = {
+        "mha": W.Workload("sparf_f1", 3, 4, 4, 128, 1500, seq_len_min=300, seed=420),
+        "mha64": W.Workload("sparf_f2", 2, 4, 4, 64, 700, seq_len_min=1, seed=421),
+        "gqa": W.Workload("sparf_f3", 2, 8, 2, 128, 900, seq_len_min=100, seed=422),
+        "paged": W.Workload("sparf_f4", 3, 4, 4, 128, 1700, seq_len_min=200, paged=True, page_size=16, seed=423),
+        "long": W.Workload("sparf_f5", 1, 2, 2, 128, 9000, seed=424),
+        "three": W.Workload("sparf_f6", 2, 4, 4, 128, 1000, seq_len_min=300, seed=425),
+    }[shape]
+    sparf_step(wl, 16, 100, 7, torch.float32, kt_page=256 if shape == "paged" else None, fused_append=True)
+
+
+def test_sparf_append_decode_equals_the_two_calls():
+    wl = W.Workload("sparf_f7", 4, 4, 4, 128, 2500, seq_len_min=0, seed=426)
+    res = []
+    for fused in (False, True):
+        case, desc, aux, kt, vsum, _ = setup(wl)
+        if not fused:
+            B.sparf_append(desc, aux, case.k_new, case.v_new, case.seq_lens)
+        out = run_decode(case, desc, aux, 16, 150, 8, torch.float32, fused_append=fused)
+        res.append(out + (kt.clone(), vsum.clone(), case.k_cache.clone(), case.v_cache.clone()))
+    for x, y in zip(*res):
+        assert torch.equal(x.view(torch.int32) if x.dtype == torch.float32 else x.view(torch.int16),
+                           y.view(torch.int32) if y.dtype == torch.float32 else y.view(torch.int16))
 
 
 def test_sparf_long_rows_take_the_three_launch_pipeline():
