@@ -264,11 +264,10 @@ struct Level1 {
 // a 4-pass radix select on order-preserving keys takes over.  The outcome: the
 // kept candidates are those in a bin above bin1, those in bin1 with a key above
 // `prefix`, and the first `remaining` (in position order) with exactly that key.
-// for_each(f) calls f(score) for every candidate of the calling thread; it is
-// called several times and must visit the same candidates each time.
+// for_each(f) calls f(score, its level-1 bin) for every candidate of the calling
+// thread; it is called several times and must visit the same candidates each time.
 template <int NT, class ForEach>
-__device__ __forceinline__ void find_threshold(ForEach&& for_each, int want, const Level1& level1,
-                                               SelectScratch& S, uint32_t& bin1, uint32_t& prefix,
+__device__ __forceinline__ void find_threshold(ForEach&& for_each, int want, SelectScratch& S, uint32_t& bin1, uint32_t& prefix,
                                                uint32_t& remaining)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -280,7 +279,7 @@ __device__ __forceinline__ void find_threshold(ForEach&& for_each, int want, con
     if (tid < 256) S.hist[tid] = 0;
     if (tid == 0) S.nmem = 0;
     __syncthreads();
-    for_each([&](float v) { atomicAdd(&S.hist[level1(v)], 1u); });
+    for_each([&](float, uint32_t bin) { atomicAdd(&S.hist[bin], 1u); });
     __syncthreads();
     if (wave == 0) locate_bin(S, remaining, lane);
     __syncthreads();
@@ -288,8 +287,8 @@ __device__ __forceinline__ void find_threshold(ForEach&& for_each, int want, con
     remaining = S.remaining;
     // level 2: gather the members of bin1
     const uint32_t b1 = bin1;
-    for_each([&](float v) {
-        if (level1(v) == b1) {
+    for_each([&](float v, uint32_t bin) {
+        if (bin == b1) {
             const uint32_t i = atomicAdd(&S.nmem, 1u);
             if (i < (uint32_t)kSelMembers) S.mem_key[i] = order_key(v);
         }
@@ -322,9 +321,9 @@ __device__ __forceinline__ void find_threshold(ForEach&& for_each, int want, con
             __syncthreads();
             const uint32_t hi_mask = shift == 24 ? 0u : (0xFFFFFFFFu << (shift + 8));
             const uint32_t pfx = prefix;
-            for_each([&](float v) {
+            for_each([&](float v, uint32_t bin) {
                 const uint32_t key = order_key(v);
-                if (level1(v) == b1 && (key & hi_mask) == (pfx & hi_mask))
+                if (bin == b1 && (key & hi_mask) == (pfx & hi_mask))
                     atomicAdd(&S.hist[(key >> shift) & 255u], 1u);
             });
             __syncthreads();
@@ -369,10 +368,10 @@ __device__ __forceinline__ float select_rows(const float* x, int L, int k, int l
                 for (int j = 0; j < 8; ++j) v[j] = t0 + j * NT < ncand ? x[t0 + j * NT] : M;
 #pragma unroll
                 for (int j = 0; j < 8; ++j)
-                    if (t0 + j * NT < ncand) f(v[j]);
+                    if (t0 + j * NT < ncand) f(v[j], level1(v[j]));
             }
         },
-        want, level1, S, bin1, prefix, remaining);
+        want, S, bin1, prefix, remaining);
 
     float mass = 0.f;
     const uint64_t lt_mask = lane == 0 ? 0ull : (~0ull >> (64 - lane));
@@ -455,19 +454,31 @@ __device__ __forceinline__ float select_rows_reg(const float (&xr)[STEPS][8], co
     const int ncand = L - leff;
     const Level1 level1(M, xmin);
 
+    // level-1 bins of the own scores, one byte each, computed once
+    uint32_t bins[STEPS][2];
+#pragma unroll
+    for (int i = 0; i < STEPS; ++i) {
+        bins[i][0] = bins[i][1] = 0;
+        if (want > 0 && i * NT * 8 < ncand) {                  // block-uniform
+#pragma unroll
+            for (int e = 0; e < 8; ++e) bins[i][e >> 2] |= level1(xr[i][e]) << (8 * (e & 3));
+        }
+    }
+    auto bin_of = [&](int i, int e) { return (bins[i][e >> 2] >> (8 * (e & 3))) & 255u; };
+
     uint32_t bin1, prefix, remaining;
     find_threshold<NT>(
         [&](auto&& f) {
 #pragma unroll
             for (int i = 0; i < STEPS; ++i) {
-                if (i * NT * 8 < ncand) {                      // block-uniform
+                if (i * NT * 8 < ncand) {
 #pragma unroll
                     for (int e = 0; e < 8; ++e)
-                        if ((i * NT + tid) * 8 + e < ncand) f(xr[i][e]);
+                        if ((i * NT + tid) * 8 + e < ncand) f(xr[i][e], bin_of(i, e));
                 }
             }
         },
-        want, level1, S, bin1, prefix, remaining);
+        want, S, bin1, prefix, remaining);
 
     float mass = 0.f;
     if (want > 0) {
@@ -481,7 +492,7 @@ __device__ __forceinline__ float select_rows_reg(const float (&xr)[STEPS][8], co
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     const bool valid = (i * NT + tid) * 8 + e < ncand;
-                    const uint32_t b1 = level1(xr[i][e]);
+                    const uint32_t b1 = bin_of(i, e);
                     const uint32_t key = order_key(xr[i][e]);
                     const bool gt = valid && (b1 > bin1 || (b1 == bin1 && key > prefix));
                     const bool eq = valid && b1 == bin1 && key == prefix;
@@ -509,17 +520,19 @@ __device__ __forceinline__ float select_rows_reg(const float (&xr)[STEPS][8], co
                 mine = w == wave ? run : mine;
                 run += step_cnt[i * NW + w];
             }
-            uint32_t gb = (mine + excl[i]) & 0xFFFFu, eb = (mine + excl[i]) >> 16;
-            if (((gtbits | eqbits) >> (8 * i)) & 0xFFu) {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const bool gt = (gtbits >> (8 * i + e)) & 1u, eq = (eqbits >> (8 * i + e)) & 1u;
-                    if (gt || (eq && eb < remaining)) {
-                        sel[gb + min(eb, remaining)] = (i * NT + tid) * 8 + e;
-                        mass += fast_exp2(xr[i][e] - M);
-                    }
-                    gb += (uint32_t)gt;
-                    eb += (uint32_t)eq;
+            const uint32_t gb = (mine + excl[i]) & 0xFFFFu, eb = (mine + excl[i]) >> 16;
+            // the few flagged slots of this lane, in position order
+            const uint32_t g8 = (gtbits >> (8 * i)) & 0xFFu, e8 = (eqbits >> (8 * i)) & 0xFFu;
+            uint32_t todo = g8 | e8;
+            while (todo) {
+                const int e = __builtin_ctz(todo);
+                todo &= todo - 1;
+                const uint32_t below = (1u << e) - 1u;
+                const uint32_t eq_before = eb + (uint32_t)__popc(e8 & below);
+                if (((g8 >> e) & 1u) || eq_before < remaining) {
+                    const int t = (i * NT + tid) * 8 + e;
+                    sel[gb + (uint32_t)__popc(g8 & below) + min(eq_before, remaining)] = t;
+                    mass += fast_exp2(xs[t] - M);
                 }
             }
         }
@@ -846,19 +859,25 @@ __global__ __launch_bounds__(NT, 3) void sparf_fused_kernel(SparfArgs a)
     // block reduction for all three.
     float mx = kNegBig, mn = -kNegBig;
 #pragma unroll
-    for (int i = 0; i < STEPS; ++i)
+    for (int i = 0; i < STEPS; ++i) {
+        if (i * NT * 8 < L) {                                  // block-uniform
 #pragma unroll
-        for (int e = 0; e < 8; ++e)
-            if ((i * NT + tid) * 8 + e < L) {
-                mx = fmaxf(mx, xr[i][e]);
-                mn = fminf(mn, xr[i][e]);
-            }
+            for (int e = 0; e < 8; ++e)
+                if ((i * NT + tid) * 8 + e < L) {
+                    mx = fmaxf(mx, xr[i][e]);
+                    mn = fminf(mn, xr[i][e]);
+                }
+        }
+    }
     float zs = 0.f;
 #pragma unroll
-    for (int i = 0; i < STEPS; ++i)
+    for (int i = 0; i < STEPS; ++i) {
+        if (i * NT * 8 < L) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e)
-            if ((i * NT + tid) * 8 + e < L) zs += fast_exp2(xr[i][e] - mx);
+            for (int e = 0; e < 8; ++e)
+                if ((i * NT + tid) * 8 + e < L) zs += fast_exp2(xr[i][e] - mx);
+        }
+    }
     float M, xmin, Z;
     {
         const float mw = wave_max(mx);
