@@ -14,11 +14,11 @@ namespace {
 size_t up256(size_t x) { return (x + 255) / 256 * 256; }
 
 struct Carve {
-    size_t logits, stats, sel, alpha, total;
+    size_t logits, stats, sel, alpha, part, total;
     int lpad, nchunk;
 };
 
-Carve carve(int batch, int num_q_heads, int max_seq_len, int k)
+Carve carve(int batch, int num_q_heads, int head_dim, int max_seq_len, int k)
 {
     Carve c;
     c.nchunk = (max_seq_len + kSparfChunk - 1) / kSparfChunk;
@@ -28,7 +28,8 @@ Carve carve(int batch, int num_q_heads, int max_seq_len, int k)
     c.stats = c.logits + up256(rows * c.lpad * sizeof(float));
     c.sel = c.stats + up256(rows * c.nchunk * 3 * sizeof(float));
     c.alpha = c.sel + up256(rows * (size_t)k * sizeof(int32_t));
-    c.total = c.alpha + up256(rows * sizeof(float));
+    c.part = c.alpha + up256(rows * sizeof(float));
+    c.total = c.part + up256(rows * kSparfMaxSlices * (size_t)(head_dim + 2) * sizeof(float));
     return c;
 }
 
@@ -118,7 +119,7 @@ size_t instattn_sparf_workspace_size(int batch, int num_q_heads, int head_dim, i
 {
     if (batch <= 0 || num_q_heads <= 0 || max_seq_len <= 0 || k <= 0) return 0;
     if (head_dim != 64 && head_dim != 128) return 0;
-    return carve(batch, num_q_heads, max_seq_len, k).total;
+    return carve(batch, num_q_heads, head_dim, max_seq_len, k).total;
 }
 
 }  // extern "C"
@@ -141,7 +142,7 @@ int run_sparf_decode(const void* q, const void* k_new, const void* v_new, bool a
     if (out_dtype != INSTATTN_F16 && out_dtype != INSTATTN_F32) return INSTATTN_ERR_INVALID_ARG;
     if (r < 1 || r > head_dim || k < 1 || l < 0) return INSTATTN_ERR_INVALID_ARG;
     if (max_seq_len > kv->capacity || max_seq_len > aux->capacity) return INSTATTN_ERR_INVALID_ARG;
-    const Carve c = carve(batch, num_q_heads, max_seq_len, k);
+    const Carve c = carve(batch, num_q_heads, head_dim, max_seq_len, k);
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < c.total)
         return INSTATTN_ERR_WORKSPACE;
 
@@ -165,6 +166,17 @@ int run_sparf_decode(const void* q, const void* k_new, const void* v_new, bool a
     a.stats = (float*)(ws + c.stats);
     a.sel = sel_rows ? sel_rows : (int32_t*)(ws + c.sel);
     a.alpha = alpha ? alpha : (float*)(ws + c.alpha);
+    a.part = (float*)(ws + c.part);
+    // Slices of a head's kept rows for the attend kernel: enough blocks to fill the
+    // chip when there are few heads, none smaller than 256 rows.
+    {
+        const int64_t heads = (int64_t)batch * num_q_heads;
+        int ns = (int)((1024 + heads - 1) / heads);
+        ns = ns < k / 256 ? ns : k / 256;
+        ns = ns < 1 ? 1 : (ns > kSparfMaxSlices ? kSparfMaxSlices : ns);
+        a.nslices = ns;
+        a.slice_rows = ((k + ns - 1) / ns + 15) / 16 * 16;
+    }
     a.out = out;
     a.out_f32 = out_dtype == INSTATTN_F32;
     a.k_new = append ? (const half_t*)k_new : nullptr;

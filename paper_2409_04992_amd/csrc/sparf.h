@@ -5,9 +5,10 @@
 
 namespace instattn {
 
-constexpr int kSparfChunk = 2048;      // positions per block of the approximate-score pass
+constexpr int kSparfChunk = 8192;      // positions per block of the approximate-score pass
 constexpr int kSparfSelectThreads = 1024;
 constexpr int kSparfAttendWaves = 8;
+constexpr int kSparfMaxSlices = 8;      // most slices the attend kernel cuts a head's kept rows into
 constexpr int kSparfAttendIds = 4096;   // kept rows staged in LDS at a time by the attend kernel
 
 // K stored a second time, component-major (the paper's hidden-embedding-indexed
@@ -44,6 +45,8 @@ struct SparfArgs {
     float* stats;                      // [B][Hq][nchunk][3]: block max, sum of 2^(x - max), min
     int32_t* sel;                      // [B][Hq][k] selected rows, ascending
     float* alpha;                      // [B][Hq] selected share of the approximate softmax
+    float* part;                       // [B][Hq][nslices][D + 2] shares of the attend kernel's slices
+    int32_t nslices, slice_rows;       // slices per head and kept rows per slice (multiple of 16)
     void* out;
     int32_t out_f32;
     const half_t* k_new;               // append, or decode with the append fused in

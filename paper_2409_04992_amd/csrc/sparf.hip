@@ -10,15 +10,17 @@
 //
 // Kernels, in launch order:
 //   sparf_logits_kernel   steps 1-4 up to the softmax normaliser: one block per
-//                         2048 positions of one query head; reads the component-
+//                         8192 positions of one query head; reads the component-
 //                         major K copy, writes fp32 scores (log2 domain) and the
-//                         block's max / sum.
+//                         block's max / sum / min.
 //   sparf_select_kernel   steps 4 (normaliser), 5-7: one block per query head; an
-//                         exact radix select over the scores, ordered compaction
+//                         exact two-level selection over the scores (held in
+//                         registers for rows up to 32768), ordered compaction
 //                         (ties towards the lower position), alpha.
-//   sparf_attend_kernel   steps 10-11: one block per query head gathers the
-//                         selected rows of K and V (online softmax as in the dense
-//                         vector-ALU kernel) and blends with the mean of V.
+//   sparf_attend_kernel   steps 10-11: one block per query head (or per slice of its
+//                         kept rows, then sparf_merge_kernel combines the slices)
+//                         gathers the selected rows of K and V (online softmax as in
+//                         the dense vector-ALU kernel) and blends with the mean of V.
 //   sparf_fused_kernel    all of the above in one launch, one block per query head,
 //                         scores kept in LDS: used when a row has at most 8192
 //                         positions.
@@ -30,6 +32,8 @@
 #include "sparf.h"
 
 #include <stdlib.h>
+
+#include <type_traits>
 
 namespace instattn {
 
@@ -121,26 +125,9 @@ __device__ __forceinline__ float prepare_query(const SparfArgs& a, int64_t row, 
     return rho > 0.f ? a.scale_log2 / sqrtf(rho) : 0.f;
 }
 
-// Scores of the 8 consecutive positions that start at `col0` (the address of
-// position t in column 0 of this KV head): one 128-bit load per kept column.
-__device__ __forceinline__ void column_scores8(const SparfArgs& a, const half_t* col0, const float* s_q,
-                                               const int* s_dim, float x[8])
-{
-#pragma unroll
-    for (int e = 0; e < 8; ++e) x[e] = 0.f;
-#pragma unroll 16
-    for (int j = 0; j < a.r; ++j) {
-        const int d = s_dim[j];
-        const float qd = s_q[d];
-        const half8_t kc = __builtin_nontemporal_load((const half8_t*)(col0 + (int64_t)d * a.aux.stride_d));
-#pragma unroll
-        for (int e = 0; e < 8; ++e) x[e] = __builtin_fmaf(qd, (float)kc[e], x[e]);
-    }
-}
-
 // Column pass of a whole row by one block (steps 2-4 without the softmax): adds
 // to xs[t], t < L, the contribution of CG kept columns, the ones ranked
-// j0 .. j0+CG-1.  The columns' offsets and the q components are the same for
+// j0 .. j0+CG-1, for the L positions that start at t_base (a multiple of 8).  The columns' offsets and the q components are the same for
 // every lane and are kept in scalar registers; a thread takes 8 consecutive
 // positions per step with one 128-bit load per column, and the loads of step i+1
 // are in flight while step i is consumed.  The steps are unrolled and every load
@@ -148,8 +135,9 @@ __device__ __forceinline__ void column_scores8(const SparfArgs& a, const half_t*
 // positions, a cache hit) so that the count of loads in flight is known at every
 // wait.  first: xs is written, not added to.
 template <int CG, int NT>
-__device__ __forceinline__ void column_pass(const SparfArgs& a, int b, int hk, int L, int j0, bool first,
-                                            float factor, const float* s_q, const int* s_dim, float* xs)
+__device__ __forceinline__ void column_pass(const SparfArgs& a, int b, int hk, int t_base, int L, int j0,
+                                            bool first, float factor, const float* s_q, const int* s_dim,
+                                            float* xs)
 {
     constexpr int STEPS = kSparfFusedMaxLen / (NT * 8);
     static_assert(STEPS * NT * 8 == kSparfFusedMaxLen && STEPS % 2 == 0, "whole, even number of steps");
@@ -165,7 +153,7 @@ __device__ __forceinline__ void column_pass(const SparfArgs& a, int b, int hk, i
     const int t_last = (L - 1) & ~7;                 // last run of 8 that holds a position
     const half_t* p0[STEPS];
 #pragma unroll
-    for (int i = 0; i < STEPS; ++i) p0[i] = kt_col0(a.aux, b, hk, min((i * NT + tid) * 8, t_last));
+    for (int i = 0; i < STEPS; ++i) p0[i] = kt_col0(a.aux, b, hk, t_base + min((i * NT + tid) * 8, t_last));
 
     half8_t A[CG], B[CG];
     auto load = [&](half8_t (&T)[CG], const half_t* p) {
@@ -211,7 +199,7 @@ struct SelectScratch {
     uint32_t hist[256];
     uint32_t prefix, remaining, nmem;
     uint32_t mem_key[kSelMembers];
-    uint32_t wave_cnt[2][16];        // per round parity and wave: rows above the threshold | rows at it << 16
+    uint32_t wave_cnt[8][16];        // per round parity (or step) and wave: rows above the threshold | rows at it << 16
     float red[48];
 };
 
@@ -243,6 +231,105 @@ __device__ __forceinline__ void locate_bin(SelectScratch& S, uint32_t remaining,
         S.prefix = (uint32_t)bin;
         S.remaining = remaining - above;
     }
+}
+
+// All kept columns of one stretch of at most kSparfFusedMaxLen positions, in groups
+// of 16, then 8, 4, 2, 1 columns.
+template <int NT>
+__device__ __forceinline__ void column_passes(const SparfArgs& a, int b, int hk, int t_base, int L, float factor,
+                                              const float* s_q, const int* s_dim, float* xs)
+{
+    int j0 = 0;
+    for (; j0 + 16 <= a.r; j0 += 16) column_pass<16, NT>(a, b, hk, t_base, L, j0, j0 == 0, factor, s_q, s_dim, xs);
+    if (a.r - j0 >= 8) {
+        column_pass<8, NT>(a, b, hk, t_base, L, j0, j0 == 0, factor, s_q, s_dim, xs);
+        j0 += 8;
+    }
+    if (a.r - j0 >= 4) {
+        column_pass<4, NT>(a, b, hk, t_base, L, j0, j0 == 0, factor, s_q, s_dim, xs);
+        j0 += 4;
+    }
+    if (a.r - j0 >= 2) {
+        column_pass<2, NT>(a, b, hk, t_base, L, j0, j0 == 0, factor, s_q, s_dim, xs);
+        j0 += 2;
+    }
+    if (a.r - j0 >= 1) column_pass<1, NT>(a, b, hk, t_base, L, j0, j0 == 0, factor, s_q, s_dim, xs);
+}
+
+// The scores of positions (i * NT + tid) * 8 + e, e < 8, of a row of L scores at x
+// (what the column pass gave this thread, so no barrier is needed to read them back
+// from LDS); 0 where the run of 8 starts at or behind L.
+template <int NT, int STEPS>
+__device__ __forceinline__ void own_scores(const float* x, int L, float (&xr)[STEPS][8])
+{
+    const int tid = threadIdx.x;
+#pragma unroll
+    for (int i = 0; i < STEPS; ++i) {
+        const int t = (i * NT + tid) * 8;
+        float4_t lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};
+        if (t < L) {
+            lo = *(const float4_t*)(x + t);
+            hi = *(const float4_t*)(x + t + 4);
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            xr[i][e] = lo[e];
+            xr[i][4 + e] = hi[e];
+        }
+    }
+}
+
+// Softmax statistics of step 4 over the first L positions of such a register
+// tile: maximum, minimum and sum of 2^(x - maximum), to every thread.  Own max,
+// min and sum first, then one block reduction for all three (fixed order).  red
+// holds 48 floats.
+template <int NT, int STEPS>
+__device__ __forceinline__ void block_stats(const float (&xr)[STEPS][8], int L, float* red, float& M, float& xmin,
+                                            float& Z)
+{
+    const int tid = threadIdx.x;
+    float mx = kNegBig, mn = -kNegBig;
+#pragma unroll
+    for (int i = 0; i < STEPS; ++i) {
+        if (i * NT * 8 < L) {                                  // block-uniform
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if ((i * NT + tid) * 8 + e < L) {
+                    mx = fmaxf(mx, xr[i][e]);
+                    mn = fminf(mn, xr[i][e]);
+                }
+        }
+    }
+    float zs = 0.f;
+#pragma unroll
+    for (int i = 0; i < STEPS; ++i) {
+        if (i * NT * 8 < L) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if ((i * NT + tid) * 8 + e < L) zs += fast_exp2(xr[i][e] - mx);
+        }
+    }
+    const float mw = wave_max(mx);
+    const float zw = wave_sum(zs * fast_exp2(mx - mw));
+    const float nw_min = -wave_max(-mn);
+    const int w = tid >> 6;
+    __syncthreads();                       // red is free (earlier readers are done)
+    if ((tid & 63) == 0) {
+        red[w] = mw;
+        red[16 + w] = zw;
+        red[32 + w] = nw_min;
+    }
+    __syncthreads();
+    M = kNegBig;
+    xmin = -kNegBig;
+#pragma unroll
+    for (int i = 0; i < NT / 64; ++i) {
+        M = fmaxf(M, red[i]);
+        xmin = fminf(xmin, red[32 + i]);
+    }
+    Z = 0.f;
+#pragma unroll
+    for (int i = 0; i < NT / 64; ++i) Z += red[16 + i] * fast_exp2(red[i] - M);
 }
 
 // Level-1 bucket of a score: linear between the row's minimum and maximum,
@@ -446,7 +533,8 @@ __device__ __forceinline__ float select_rows_reg(const float (&xr)[STEPS][8], co
                                                  SelectScratch& S)
 {
     constexpr int NW = NT / 64;
-    static_assert(STEPS * NW <= 32 && STEPS * 8 <= 32, "counts and flag words");
+    static_assert(STEPS * NW <= 128 && STEPS * 8 <= 64, "counts and flag words");
+    typedef typename std::conditional<(STEPS > 4), uint64_t, uint32_t>::type bits_t;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int keff = min(k, L);
     const int leff = min(l, keff);
@@ -454,17 +542,24 @@ __device__ __forceinline__ float select_rows_reg(const float (&xr)[STEPS][8], co
     const int ncand = L - leff;
     const Level1 level1(M, xmin);
 
-    // level-1 bins of the own scores, one byte each, computed once
-    uint32_t bins[STEPS][2];
+    // level-1 bins of the own scores, one byte each, computed once (where the register
+    // budget allows: 1024 threads with 64 scores each recompute them instead)
+    constexpr bool kCacheBins = STEPS <= 4;
+    uint32_t bins[kCacheBins ? STEPS : 1][2];
+    if constexpr (kCacheBins) {
 #pragma unroll
-    for (int i = 0; i < STEPS; ++i) {
-        bins[i][0] = bins[i][1] = 0;
-        if (want > 0 && i * NT * 8 < ncand) {                  // block-uniform
+        for (int i = 0; i < STEPS; ++i) {
+            bins[i][0] = bins[i][1] = 0;
+            if (want > 0 && i * NT * 8 < ncand) {              // block-uniform
 #pragma unroll
-            for (int e = 0; e < 8; ++e) bins[i][e >> 2] |= level1(xr[i][e]) << (8 * (e & 3));
+                for (int e = 0; e < 8; ++e) bins[i][e >> 2] |= level1(xr[i][e]) << (8 * (e & 3));
+            }
         }
     }
-    auto bin_of = [&](int i, int e) { return (bins[i][e >> 2] >> (8 * (e & 3))) & 255u; };
+    auto bin_of = [&](int i, int e) -> uint32_t {
+        if constexpr (kCacheBins) return (bins[i][e >> 2] >> (8 * (e & 3))) & 255u;
+        else return level1(xr[i][e]);
+    };
 
     uint32_t bin1, prefix, remaining;
     find_threshold<NT>(
@@ -482,7 +577,7 @@ __device__ __forceinline__ float select_rows_reg(const float (&xr)[STEPS][8], co
 
     float mass = 0.f;
     if (want > 0) {
-        uint32_t gtbits = 0, eqbits = 0;                       // bit 8i + e
+        bits_t gtbits = 0, eqbits = 0;                         // bit 8i + e
         uint32_t excl[STEPS];                                  // kept before this lane in its wave, per step
         uint32_t* step_cnt = &S.wave_cnt[0][0];                // [STEPS][NW]
 #pragma unroll
@@ -496,12 +591,12 @@ __device__ __forceinline__ float select_rows_reg(const float (&xr)[STEPS][8], co
                     const uint32_t key = order_key(xr[i][e]);
                     const bool gt = valid && (b1 > bin1 || (b1 == bin1 && key > prefix));
                     const bool eq = valid && b1 == bin1 && key == prefix;
-                    gtbits |= (uint32_t)gt << (8 * i + e);
-                    eqbits |= (uint32_t)eq << (8 * i + e);
+                    gtbits |= (bits_t)gt << (8 * i + e);
+                    eqbits |= (bits_t)eq << (8 * i + e);
                     c += (uint32_t)gt + ((uint32_t)eq << 16);
                 }
             }
-            uint32_t incl = c;                                 // 16-bit halves: at most 512 each
+            uint32_t incl = c;                                 // 16-bit halves: at most 512 each (65535 in all)
 #pragma unroll
             for (int d = 1; d < 64; d <<= 1) {
                 const uint32_t o = __shfl_up(incl, d, 64);
@@ -522,7 +617,7 @@ __device__ __forceinline__ float select_rows_reg(const float (&xr)[STEPS][8], co
             }
             const uint32_t gb = (mine + excl[i]) & 0xFFFFu, eb = (mine + excl[i]) >> 16;
             // the few flagged slots of this lane, in position order
-            const uint32_t g8 = (gtbits >> (8 * i)) & 0xFFu, e8 = (eqbits >> (8 * i)) & 0xFFu;
+            const uint32_t g8 = (uint32_t)(gtbits >> (8 * i)) & 0xFFu, e8 = (uint32_t)(eqbits >> (8 * i)) & 0xFFu;
             uint32_t todo = g8 | e8;
             while (todo) {
                 const int e = __builtin_ctz(todo);
@@ -554,10 +649,15 @@ __device__ __forceinline__ float select_rows_reg(const float (&xr)[STEPS][8], co
 // for a paged cache, pool page and row inside it packed into one word, so that
 // the gather loop has no global load between the id and the row.  Two register
 // tiles: the rows of step i+1 are in flight while step i is consumed.
+//
+// The block handles entries [p_begin, p_end) of the list.  part == nullptr: that is
+// the whole list and the block writes the output row.  Otherwise it writes its
+// share as D unnormalised sums, their reference maximum and the sum of weights
+// (D + 2 floats at part) for sparf_merge_kernel.
 template <int D, int WAVES>
-__device__ __forceinline__ void attend_rows(const SparfArgs& a, int b, int h, int L, int n, const int32_t* sel,
-                                            float alpha, int32_t* ids, int ids_cap, float (*s_acc)[D],
-                                            float* s_m, float* s_l)
+__device__ __forceinline__ void attend_rows(const SparfArgs& a, int b, int h, int L, int p_begin, int p_end,
+                                            const int32_t* sel, float alpha, float* part, int32_t* ids,
+                                            int ids_cap, float (*s_acc)[D], float* s_m, float* s_l)
 {
     constexpr int LPR = D / 8;
     constexpr int RPW = kWave / LPR;
@@ -584,8 +684,8 @@ __device__ __forceinline__ void attend_rows(const SparfArgs& a, int b, int h, in
     struct Tile {
         u32x4 k[U], v[U];
     };
-    for (int c0 = 0; c0 < n; c0 += ids_cap) {
-        const int nc = min(ids_cap, n - c0);
+    for (int c0 = p_begin; c0 < p_end; c0 += ids_cap) {
+        const int nc = min(ids_cap, p_end - c0);
         __syncthreads();                   // whatever used this LDS before is done with it
         for (int i = tid; i < nc; i += WAVES * 64) {
             const int t = sel[c0 + i];
@@ -658,6 +758,14 @@ __device__ __forceinline__ void attend_rows(const SparfArgs& a, int b, int h, in
             lsum += w * s_l[i];
             o += w * s_acc[i][tid];
         }
+        if (part != nullptr) {
+            part[tid] = o;
+            if (tid == 0) {
+                part[D] = M;
+                part[D + 1] = lsum;
+            }
+            return;
+        }
         o /= lsum;
         // step 11: alpha * (attention over the kept rows) + (1 - alpha) * mean of V
         const float vbar = a.aux.vsum[((int64_t)b * a.num_kv_heads + hk) * D + tid] / (float)L;
@@ -694,9 +802,13 @@ __device__ __forceinline__ void write_zero_row(const SparfArgs& a, int64_t row)
 }  // namespace
 
 // ---------------------------------------------------------------------------
-// Steps 1-4 (without the normaliser), long rows: one block per 2048 positions.
-__global__ __launch_bounds__(256) void sparf_logits_kernel(SparfArgs a)
+// Steps 1-4 (without the normaliser), long rows: one block per stretch of 8192
+// positions of one head, the same column pass as the one-launch kernel; the
+// scores go to the workspace together with the stretch's max / sum / min.
+__global__ __launch_bounds__(256, 3) void sparf_logits_kernel(SparfArgs a)
 {
+    constexpr int NT = 256, STEPS = kSparfChunk / (NT * 8);
+    static_assert(kSparfChunk == kSparfFusedMaxLen, "the column pass covers one stretch");
     const int h = blockIdx.x, chunk = blockIdx.y, b = blockIdx.z;
     const int G = a.num_q_heads / a.num_kv_heads;
     const int hk = h / G;
@@ -713,44 +825,39 @@ __global__ __launch_bounds__(256) void sparf_logits_kernel(SparfArgs a)
         }
         return;
     }
+    __shared__ __align__(16) float xs[kSparfChunk];
     __shared__ float s_q[128];
     __shared__ float s_abs[128];
     __shared__ int s_dim[128];
-    __shared__ float s_red[32];
+    __shared__ float s_red[48];
     const float factor = prepare_query(a, row, s_q, s_abs, s_dim, s_red);
-
-    const int t = t0 + tid * 8;
-    float x[8];
+    const int Lc = min(L - t0, kSparfChunk);
+    column_passes<NT>(a, b, hk, t0, Lc, factor, s_q, s_dim, xs);
+    float xr[STEPS][8];
+    own_scores<NT, STEPS>(xs, Lc, xr);
+    float* dst = a.logits + row * a.lpad + t0;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) x[e] = 0.f;
-    if (t < L) column_scores8(a, kt_col0(a.aux, b, hk, t), s_q, s_dim, x);
-    float mx = kNegBig, mn = -kNegBig;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const bool in = t + e < L;
-        x[e] = in ? x[e] * factor : -__builtin_inff();
-        mx = fmaxf(mx, x[e]);
-        if (in) mn = fminf(mn, x[e]);
+    for (int i = 0; i < STEPS; ++i) {
+        const int t = (i * NT + tid) * 8;
+        if (t < Lc) {
+            *(float4_t*)(dst + t) = float4_t{xr[i][0], xr[i][1], xr[i][2], xr[i][3]};
+            *(float4_t*)(dst + t + 4) = float4_t{xr[i][4], xr[i][5], xr[i][6], xr[i][7]};
+        }
     }
-    float* dst = a.logits + row * a.lpad + t;
-    *(float4_t*)dst = float4_t{x[0], x[1], x[2], x[3]};
-    *(float4_t*)(dst + 4) = float4_t{x[4], x[5], x[6], x[7]};
-
-    const float M = block_max(mx, s_red);
-    float s = 0.f;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) s += fast_exp2(x[e] - M);
-    s = block_sum(s, s_red);
-    mn = block_min(mn, s_red);
+    float M, xmin, Z;
+    block_stats<NT, STEPS>(xr, Lc, s_red, M, xmin, Z);
     if (tid == 0) {
         stats[0] = M;
-        stats[1] = s;
-        stats[2] = mn;
+        stats[1] = Z;
+        stats[2] = xmin;
     }
 }
 
 // Steps 4 (normaliser) to 7, long rows: one block per head over the stored scores.
-template <int NT>
+// STEPS > 0: the row has at most NT * 8 * STEPS positions, every thread reads its
+// scores once and keeps them in registers; STEPS == 0: the selection passes over
+// the workspace.
+template <int NT, int STEPS>
 __global__ __launch_bounds__(NT) void sparf_select_kernel(SparfArgs a)
 {
     const int h = blockIdx.x, b = blockIdx.y;
@@ -761,37 +868,89 @@ __global__ __launch_bounds__(NT) void sparf_select_kernel(SparfArgs a)
         return;
     }
     __shared__ SelectScratch S;
-    const int nc = (L + kSparfChunk - 1) / kSparfChunk;
-    const float* st = a.stats + row * a.nchunk * 3;
-    float M = kNegBig, xmin = -kNegBig;
-    for (int c = 0; c < nc; ++c) {
-        M = fmaxf(M, st[3 * c]);
-        xmin = fminf(xmin, st[3 * c + 2]);
+    const float* x = a.logits + row * a.lpad;
+    float alpha;
+    if constexpr (STEPS > 0) {
+        float xr[STEPS][8];
+        own_scores<NT, STEPS>(x, L, xr);   // in flight while the stretch statistics are combined
+        const int nc = (L + kSparfChunk - 1) / kSparfChunk;
+        const float* st = a.stats + row * a.nchunk * 3;
+        float M = kNegBig, xmin = -kNegBig;
+        for (int c = 0; c < nc; ++c) {
+            M = fmaxf(M, st[3 * c]);
+            xmin = fminf(xmin, st[3 * c + 2]);
+        }
+        float Z = 0.f;
+        for (int c = 0; c < nc; ++c) Z += st[3 * c + 1] * fast_exp2(st[3 * c] - M);
+        alpha = select_rows_reg<NT, STEPS>(xr, x, L, a.k, a.l, M, xmin, Z, a.sel + row * a.k, S);
+    } else {
+        const int nc = (L + kSparfChunk - 1) / kSparfChunk;
+        const float* st = a.stats + row * a.nchunk * 3;
+        float M = kNegBig, xmin = -kNegBig;
+        for (int c = 0; c < nc; ++c) {
+            M = fmaxf(M, st[3 * c]);
+            xmin = fminf(xmin, st[3 * c + 2]);
+        }
+        float Z = 0.f;
+        for (int c = 0; c < nc; ++c) Z += st[3 * c + 1] * fast_exp2(st[3 * c] - M);
+        alpha = select_rows<NT>(x, L, a.k, a.l, M, xmin, Z, a.sel + row * a.k, S);
     }
-    float Z = 0.f;
-    for (int c = 0; c < nc; ++c) Z += st[3 * c + 1] * fast_exp2(st[3 * c] - M);
-    const float alpha = select_rows<NT>(a.logits + row * a.lpad, L, a.k, a.l, M, xmin, Z, a.sel + row * a.k, S);
     if (threadIdx.x == 0) a.alpha[row] = alpha;
 }
 
-// Steps 10-11, long rows.
+// Steps 10-11, long rows: one block per query head and slice of its kept rows.
+// With one slice the block writes the output row; with more, each writes its
+// share and sparf_merge_kernel finishes (few heads with many kept rows would
+// otherwise leave most of the chip idle).
 template <int D>
 __global__ __launch_bounds__(kSparfAttendWaves * 64) void sparf_attend_kernel(SparfArgs a)
 {
     constexpr int NG = kSparfAttendWaves * (kWave / (D / 8));
-    const int h = blockIdx.x, b = blockIdx.y;
+    const int h = blockIdx.x, slice = blockIdx.y, b = blockIdx.z;
     const int64_t row = (int64_t)b * a.num_q_heads + h;
     const int L = clamp_len(a.seq_lens[b], a.max_len);
     if (L == 0) {
-        write_zero_row<D>(a, row);
+        if (a.nslices == 1) write_zero_row<D>(a, row);     // else the merge writes it
         return;
     }
     __shared__ float s_acc[NG][D];
     __shared__ float s_m[NG];
     __shared__ float s_l[NG];
     __shared__ int32_t s_ids[kSparfAttendIds];
-    attend_rows<D, kSparfAttendWaves>(a, b, h, L, min(a.k, L), a.sel + row * a.k, a.alpha[row], s_ids,
+    const int n = min(a.k, L);
+    const int p_begin = min(slice * a.slice_rows, n), p_end = min(p_begin + a.slice_rows, n);
+    float* part = a.nslices == 1 ? nullptr : a.part + (row * a.nslices + slice) * (D + 2);
+    attend_rows<D, kSparfAttendWaves>(a, b, h, L, p_begin, p_end, a.sel + row * a.k, a.alpha[row], part, s_ids,
                                       kSparfAttendIds, s_acc, s_m, s_l);
+}
+
+// Combines the slices of a head (steps 10-11 finished): one thread per output dim.
+template <int D>
+__global__ __launch_bounds__(D) void sparf_merge_kernel(SparfArgs a)
+{
+    const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+    const int64_t row = (int64_t)b * a.num_q_heads + h;
+    const int L = clamp_len(a.seq_lens[b], a.max_len);
+    if (L == 0) {
+        write_zero_row<D>(a, row);
+        return;
+    }
+    const float* part = a.part + row * a.nslices * (D + 2);
+    float M = kNegBig;
+    for (int s = 0; s < a.nslices; ++s) M = fmaxf(M, part[s * (D + 2) + D]);
+    float lsum = 0.f, o = 0.f;
+    for (int s = 0; s < a.nslices; ++s) {
+        const float w = fast_exp2(part[s * (D + 2) + D] - M);
+        lsum += w * part[s * (D + 2) + D + 1];
+        o += w * part[s * (D + 2) + tid];
+    }
+    o /= lsum;
+    const int hk = h / (a.num_q_heads / a.num_kv_heads);
+    const float alpha = a.alpha[row];
+    const float vbar = a.aux.vsum[((int64_t)b * a.num_kv_heads + hk) * D + tid] / (float)L;
+    o = alpha * o + (1.f - alpha) * vbar;
+    if (a.out_f32) ((float*)a.out)[row * D + tid] = o;
+    else ((half_t*)a.out)[row * D + tid] = (half_t)o;
 }
 
 // The whole of Algorithm 1 for one query head in one block of NT threads; the
@@ -828,80 +987,13 @@ __global__ __launch_bounds__(NT, 3) void sparf_fused_kernel(SparfArgs a)
         if (tid == 0) a.alpha[row] = 0.f;
         return;
     }
-    // kept columns in groups of 16, then 8, 4, 2, 1
-    {
-        int j0 = 0;
-        for (; j0 + 16 <= a.r; j0 += 16) column_pass<16, NT>(a, b, hk, L, j0, j0 == 0, factor, s_q, s_dim, xs);
-        if (a.r - j0 >= 8) { column_pass<8, NT>(a, b, hk, L, j0, j0 == 0, factor, s_q, s_dim, xs); j0 += 8; }
-        if (a.r - j0 >= 4) { column_pass<4, NT>(a, b, hk, L, j0, j0 == 0, factor, s_q, s_dim, xs); j0 += 4; }
-        if (a.r - j0 >= 2) { column_pass<2, NT>(a, b, hk, L, j0, j0 == 0, factor, s_q, s_dim, xs); j0 += 2; }
-        if (a.r - j0 >= 1) column_pass<1, NT>(a, b, hk, L, j0, j0 == 0, factor, s_q, s_dim, xs);
-    }
-    // A thread takes back the scores it wrote itself (no barrier needed) and keeps them
-    // in registers for the rest of steps 4-7.
+    column_passes<NT>(a, b, hk, 0, L, factor, s_q, s_dim, xs);
+    // the thread's own scores stay in registers for the rest of steps 4-7
     constexpr int STEPS = kSparfFusedMaxLen / (NT * 8);
     float xr[STEPS][8];
-#pragma unroll
-    for (int i = 0; i < STEPS; ++i) {
-        const int t = (i * NT + tid) * 8;
-        float4_t lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};
-        if (t < L) {
-            lo = *(const float4_t*)(xs + t);
-            hi = *(const float4_t*)(xs + t + 4);
-        }
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            xr[i][e] = lo[e];
-            xr[i][4 + e] = hi[e];
-        }
-    }
-    // Softmax statistics of step 4: own max, min and sum of 2^(x - own max), then one
-    // block reduction for all three.
-    float mx = kNegBig, mn = -kNegBig;
-#pragma unroll
-    for (int i = 0; i < STEPS; ++i) {
-        if (i * NT * 8 < L) {                                  // block-uniform
-#pragma unroll
-            for (int e = 0; e < 8; ++e)
-                if ((i * NT + tid) * 8 + e < L) {
-                    mx = fmaxf(mx, xr[i][e]);
-                    mn = fminf(mn, xr[i][e]);
-                }
-        }
-    }
-    float zs = 0.f;
-#pragma unroll
-    for (int i = 0; i < STEPS; ++i) {
-        if (i * NT * 8 < L) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e)
-                if ((i * NT + tid) * 8 + e < L) zs += fast_exp2(xr[i][e] - mx);
-        }
-    }
+    own_scores<NT, STEPS>(xs, L, xr);
     float M, xmin, Z;
-    {
-        const float mw = wave_max(mx);
-        const float zw = wave_sum(zs * fast_exp2(mx - mw));
-        const float nw_min = -wave_max(-mn);
-        const int w = tid >> 6;
-        __syncthreads();                       // S.red is free (prepare_query's readers are done)
-        if ((tid & 63) == 0) {
-            S.red[w] = mw;
-            S.red[16 + w] = zw;
-            S.red[32 + w] = nw_min;
-        }
-        __syncthreads();
-        M = kNegBig;
-        xmin = -kNegBig;
-#pragma unroll
-        for (int i = 0; i < NT / 64; ++i) {
-            M = fmaxf(M, S.red[i]);
-            xmin = fminf(xmin, S.red[32 + i]);
-        }
-        Z = 0.f;
-#pragma unroll
-        for (int i = 0; i < NT / 64; ++i) Z += S.red[16 + i] * fast_exp2(S.red[i] - M);
-    }
+    block_stats<NT, STEPS>(xr, L, S.red, M, xmin, Z);
 
     // steps 5-7
     int32_t* sel = a.sel + row * a.k;
@@ -910,7 +1002,8 @@ __global__ __launch_bounds__(NT, 3) void sparf_fused_kernel(SparfArgs a)
 
     // steps 10-11; the scores are dead, their LDS takes the row ids (the barrier
     // in front of that also makes the kept positions visible to the whole block)
-    attend_rows<D, NT / 64>(a, b, h, L, min(a.k, L), sel, alpha, (int32_t*)xs, (L + 7) & ~7, s_acc, s_m, s_l);
+    attend_rows<D, NT / 64>(a, b, h, L, 0, min(a.k, L), sel, alpha, nullptr, (int32_t*)xs, (L + 7) & ~7, s_acc,
+                            s_m, s_l);
 }
 
 // ---------------------------------------------------------------------------
@@ -1004,8 +1097,12 @@ hipError_t launch_sparf_logits(const SparfArgs& a, hipStream_t stream)
 hipError_t launch_sparf_select(const SparfArgs& a, hipStream_t stream)
 {
     dim3 grid(a.num_q_heads, a.batch);
-    if (a.max_len <= 8192) hipLaunchKernelGGL(sparf_select_kernel<256>, grid, dim3(256), 0, stream, a);
-    else hipLaunchKernelGGL(sparf_select_kernel<1024>, grid, dim3(1024), 0, stream, a);
+    if (a.max_len <= 256 * 32) hipLaunchKernelGGL((sparf_select_kernel<256, 4>), grid, dim3(256), 0, stream, a);
+    else if (a.max_len <= 1024 * 32)
+        hipLaunchKernelGGL((sparf_select_kernel<1024, 4>), grid, dim3(1024), 0, stream, a);
+    else if (a.max_len < 1024 * 64)        // the packed 16-bit counts hold at most 65535
+        hipLaunchKernelGGL((sparf_select_kernel<1024, 8>), grid, dim3(1024), 0, stream, a);
+    else hipLaunchKernelGGL((sparf_select_kernel<1024, 0>), grid, dim3(1024), 0, stream, a);
     return hipGetLastError();
 }
 
@@ -1020,9 +1117,15 @@ hipError_t launch_sparf_fused(const SparfArgs& a, hipStream_t stream)
 
 hipError_t launch_sparf_attend(const SparfArgs& a, hipStream_t stream)
 {
-    dim3 grid(a.num_q_heads, a.batch), block(kSparfAttendWaves * 64);
+    dim3 grid(a.num_q_heads, a.nslices, a.batch), block(kSparfAttendWaves * 64);
     if (a.head_dim == 128) hipLaunchKernelGGL(sparf_attend_kernel<128>, grid, block, 0, stream, a);
     else hipLaunchKernelGGL(sparf_attend_kernel<64>, grid, block, 0, stream, a);
+    if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
+    if (a.nslices > 1) {
+        dim3 mgrid(a.num_q_heads, a.batch);
+        if (a.head_dim == 128) hipLaunchKernelGGL(sparf_merge_kernel<128>, mgrid, dim3(128), 0, stream, a);
+        else hipLaunchKernelGGL(sparf_merge_kernel<64>, mgrid, dim3(64), 0, stream, a);
+    }
     return hipGetLastError();
 }
 

@@ -231,9 +231,20 @@ def test_sparf_append_decode_equals_the_two_calls():
                            y.view(torch.int32) if y.dtype == torch.float32 else y.view(torch.int16))
 
 
-def test_sparf_long_rows_take_the_three_launch_pipeline():
-    wl = W.Workload("sparf_long", 1, 2, 2, 128, 20000, seed=408)
-    sparf_step(wl, 16, 1300, 32, torch.float16)
+@pytest.mark.parametrize("seq_len,k", [(20000, 1300), (8192, 100), (32767, 3000), (32768, 600), (40000, 2500),
+                                       (65534, 700), (70000, 4400)])
+def test_sparf_long_rows_take_the_three_launch_pipeline(seq_len, k):
+    """Rows behind the one-launch limit: the selection keeps the scores in registers up
+    to 32768 and up to 65535 positions and passes over the workspace beyond; the
+    attend kernel cuts the kept rows of a head into up to 8 slices."""
+    wl = W.Workload("sparf_long", 1, 2, 2, 128, seq_len, seed=408)
+    sparf_step(wl, 16, k, 32, torch.float16)
+
+
+def test_sparf_long_rows_many_heads_no_slices():
+    wl = W.Workload("sparf_long_many", 26, 40, 40, 64, 9000, seq_len_min=100, seed=413)
+    pairs = [(0, 0), (25, 39), (13, 7), (5, 20)]
+    sparf_step(wl, 8, 300, 4, torch.float16, pairs=pairs)
 
 
 def test_sparf_one_launch_and_three_launches_agree(monkeypatch):
