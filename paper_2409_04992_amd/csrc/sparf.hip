@@ -869,32 +869,27 @@ __global__ __launch_bounds__(NT) void sparf_select_kernel(SparfArgs a)
     }
     __shared__ SelectScratch S;
     const float* x = a.logits + row * a.lpad;
-    float alpha;
-    if constexpr (STEPS > 0) {
-        float xr[STEPS][8];
-        own_scores<NT, STEPS>(x, L, xr);   // in flight while the stretch statistics are combined
-        const int nc = (L + kSparfChunk - 1) / kSparfChunk;
-        const float* st = a.stats + row * a.nchunk * 3;
-        float M = kNegBig, xmin = -kNegBig;
-        for (int c = 0; c < nc; ++c) {
-            M = fmaxf(M, st[3 * c]);
-            xmin = fminf(xmin, st[3 * c + 2]);
-        }
-        float Z = 0.f;
-        for (int c = 0; c < nc; ++c) Z += st[3 * c + 1] * fast_exp2(st[3 * c] - M);
-        alpha = select_rows_reg<NT, STEPS>(xr, x, L, a.k, a.l, M, xmin, Z, a.sel + row * a.k, S);
-    } else {
-        const int nc = (L + kSparfChunk - 1) / kSparfChunk;
-        const float* st = a.stats + row * a.nchunk * 3;
-        float M = kNegBig, xmin = -kNegBig;
-        for (int c = 0; c < nc; ++c) {
-            M = fmaxf(M, st[3 * c]);
-            xmin = fminf(xmin, st[3 * c + 2]);
-        }
-        float Z = 0.f;
-        for (int c = 0; c < nc; ++c) Z += st[3 * c + 1] * fast_exp2(st[3 * c] - M);
-        alpha = select_rows<NT>(x, L, a.k, a.l, M, xmin, Z, a.sel + row * a.k, S);
+    float xr[STEPS > 0 ? STEPS : 1][8];
+    if constexpr (STEPS > 0) own_scores<NT, STEPS>(x, L, xr);   // in flight while the statistics are combined
+    // max / sum / min of the row from those of its stretches: lane c takes stretch c,
+    // every wave gets the same values
+    const int nc = (L + kSparfChunk - 1) / kSparfChunk;
+    const float* st = a.stats + row * a.nchunk * 3;
+    const int lane = threadIdx.x & 63;
+    float M = kNegBig, xmin = -kNegBig, Z = 0.f;
+    for (int c0 = 0; c0 < nc; c0 += 64) {
+        const bool in = c0 + lane < nc;
+        const float mc = in ? st[3 * (c0 + lane)] : kNegBig;
+        const float zc = in ? st[3 * (c0 + lane) + 1] : 0.f;
+        const float nc_min = in ? st[3 * (c0 + lane) + 2] : -kNegBig;
+        const float Mn = fmaxf(M, wave_max(mc));
+        Z = Z * fast_exp2(M - Mn) + wave_sum(zc * fast_exp2(mc - Mn));
+        M = Mn;
+        xmin = fminf(xmin, -wave_max(-nc_min));
     }
+    float alpha;
+    if constexpr (STEPS > 0) alpha = select_rows_reg<NT, STEPS>(xr, x, L, a.k, a.l, M, xmin, Z, a.sel + row * a.k, S);
+    else alpha = select_rows<NT>(x, L, a.k, a.l, M, xmin, Z, a.sel + row * a.k, S);
     if (threadIdx.x == 0) a.alpha[row] = alpha;
 }
 
@@ -1097,12 +1092,20 @@ hipError_t launch_sparf_logits(const SparfArgs& a, hipStream_t stream)
 hipError_t launch_sparf_select(const SparfArgs& a, hipStream_t stream)
 {
     dim3 grid(a.num_q_heads, a.batch);
-    if (a.max_len <= 256 * 32) hipLaunchKernelGGL((sparf_select_kernel<256, 4>), grid, dim3(256), 0, stream, a);
-    else if (a.max_len <= 1024 * 32)
-        hipLaunchKernelGGL((sparf_select_kernel<1024, 4>), grid, dim3(1024), 0, stream, a);
-    else if (a.max_len < 1024 * 64)        // the packed 16-bit counts hold at most 65535
-        hipLaunchKernelGGL((sparf_select_kernel<1024, 8>), grid, dim3(1024), 0, stream, a);
-    else hipLaunchKernelGGL((sparf_select_kernel<1024, 0>), grid, dim3(1024), 0, stream, a);
+    // Smallest block whose threads hold the row in registers, 32 or 40 scores each
+    // (sequence lengths like to sit just behind a power of two), 64 as the last
+    // resort: small blocks share a compute unit and overlap each other's barriers.
+#define INSTATTN_SELECT(NT, STEPS) \
+    hipLaunchKernelGGL((sparf_select_kernel<NT, STEPS>), grid, dim3(NT), 0, stream, a)
+    if (a.max_len <= 256 * 32) INSTATTN_SELECT(256, 4);
+    else if (a.max_len <= 256 * 40) INSTATTN_SELECT(256, 5);
+    else if (a.max_len <= 512 * 32) INSTATTN_SELECT(512, 4);
+    else if (a.max_len <= 512 * 40) INSTATTN_SELECT(512, 5);
+    else if (a.max_len <= 1024 * 32) INSTATTN_SELECT(1024, 4);
+    else if (a.max_len <= 1024 * 40) INSTATTN_SELECT(1024, 5);
+    else if (a.max_len < 1024 * 64) INSTATTN_SELECT(1024, 8);   // the packed 16-bit counts hold at most 65535
+    else INSTATTN_SELECT(1024, 0);
+#undef INSTATTN_SELECT
     return hipGetLastError();
 }
 
