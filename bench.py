@@ -25,7 +25,7 @@ HBM_PEAK_GBPS = 8000.0
 # HBM bytes per launch of the split-pass kernel from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE runs of this script, scaled by what the same counters read for the
 # 256 MiB copy kernel (FETCH_SIZE x 2.000, WRITE_SIZE x 1.000); see profiles/.
-MEASURED_TRAFFIC_BYTES = {"mha13b_4k": 1343279911, "gqa70b_16k": 2151868618}
+MEASURED_TRAFFIC_BYTES = {"mha13b_4k": 1343282056, "gqa70b_16k": 2151879940}
 
 
 def parse():
@@ -45,6 +45,9 @@ def parse():
                          "dense path, next to the dense step on the same caches")
     ap.add_argument("--kv-write", action="store_true",
                     help="time instattn_kv_write of a whole prompt (the prefill-side bulk store)")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay the step's launches from a captured HIP graph instead of launching them "
+                         "one by one (dense path)")
     ap.add_argument("--two-calls", action="store_true",
                     help="step = instattn_kv_append + instattn_decode instead of instattn_append_decode")
     return ap.parse_args()
@@ -263,12 +266,33 @@ def main():
         args.steps = 400 if lps == 1 else 20
     if args.warmup is None:
         args.warmup = 40 if lps == 1 else 2
-    for i in range(args.warmup):
-        step(i)
+    if args.graph:
+        # One graph holds as many consecutive steps as it takes to come back to the first
+        # resident layer cache; the timed loop replays it.
+        per_graph = max(1, R // lps)
+        args.steps = max(per_graph, args.steps // per_graph * per_graph)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step(0)                                    # warm everything the capture touches
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for i in range(per_graph):
+                step(i)
+
+        def run(n_steps):
+            for _ in range(n_steps // per_graph):
+                graph.replay()
+    else:
+        def run(n_steps):
+            for i in range(n_steps):
+                step(i)
+    run(args.warmup if not args.graph else max(1, args.warmup // max(1, R // lps)) * max(1, R // lps))
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i)
+    run(args.steps)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall / args.steps * 1e3
@@ -328,7 +352,8 @@ def main():
                    "out_dtype": wl.out_dtype, "layers_resident": R, "layers_per_step": lps,
                    "step": ("kv_append; decode" if args.two_calls else "append_decode (append fused into "
                             "the split pass)") + (", LSE merge" if splits > 1 else ", single split: no merge")
-                           + ", for each layer of the step",
+                           + ", for each layer of the step"
+                           + ("; launches replayed from a HIP graph" if args.graph else ""),
                    "chunk_tokens": chunk, "num_splits": splits,
                    "kv_bytes_per_step": kv_bytes},
         "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBPS,

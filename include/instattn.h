@@ -258,7 +258,10 @@ size_t instattn_sparf_workspace_size(int batch, int num_q_heads, int head_dim, i
  *   alpha     : device [batch][num_q_heads] fp32 or NULL: receives step 7's alpha
  * L_b <= 0 gives a zero row (alpha 0).  One launch when max_seq_len <= 8192 (one
  * block per query head keeps the scores in LDS), otherwise three (column scores,
- * selection, attention over the kept rows).
+ * selection, attention over the kept rows) or four (few heads with many kept rows:
+ * the kept rows of a head are cut into slices and a last launch combines them).
+ * A paged cache is limited to num_pages*page_size < 2^31 rows here
+ * (INSTATTN_ERR_UNSUPPORTED beyond).
  */
 int instattn_sparf_decode(const void* q, const instattn_kv_desc* kv, const instattn_sparf_aux* aux,
                           const int32_t* seq_lens, int batch, int num_q_heads, int num_kv_heads,

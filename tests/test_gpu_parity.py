@@ -365,3 +365,51 @@ def test_prefill_write_then_decode():
     want_out, want_lse, _, _ = H.oracle_step(case)
     out, lse = H.gpu_step(case, fused=True)
     H.assert_close(out, lse, want_out, want_lse, "prefill+decode")
+
+
+# ------------------------------------------------------------------ HIP graph replay
+@pytest.mark.parametrize("shape", ["mha_splits", "gqa_paged"])
+def test_step_replayed_from_a_hip_graph(shape):
+    """The launches of a step (split pass with the append fused in, merge) recorded into a
+    HIP graph: every replay, with eager work and synchronisation in between, gives the
+    oracle's result and bit for bit the eager one."""
+    if shape == "mha_splits":
+        wl = W.Workload("graph_mha", 2, 4, 4, 128, 3000, seq_len_min=500, seed=501)
+    else:
+        wl = W.Workload("graph_gqa", 2, 8, 2, 128, 2000, seq_len_min=300, paged=True, page_size=16, seed=502)
+    case = W.make_case(wl, DEV, poison=True)
+    other = W.make_case(W.Workload("graph_other", 1, 4, 4, 64, 700, seed=503), DEV)
+    want_out, want_lse, want_k, want_v = H.oracle_step(case)
+    desc = B.kv_desc(case.k_cache, case.v_cache, case.page_table)
+    max_len = int(case.seq_lens.max())
+    Bn, Hq, D = case.q.shape
+    ws = B.alloc_workspace(Bn, Hq, wl.num_kv_heads, D, max_len, DEV)
+    out = torch.empty(Bn, Hq, D, dtype=torch.float16, device=DEV)
+    lse = torch.empty(Bn, Hq, dtype=torch.float32, device=DEV)
+
+    def step():
+        B.append_decode(case.q, case.k_new, case.v_new, desc, case.seq_lens, wl.num_kv_heads, case.scale,
+                        out, ws, max_len, lse=lse)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    eager_out, eager_lse = out.clone(), lse.clone()
+    H.assert_close(eager_out, eager_lse, want_out, want_lse, "eager")
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for rep in range(3):
+        out.fill_(float("nan"))
+        lse.fill_(float("nan"))
+        ws.fill_(0xFF)
+        H.gpu_step(other)                      # unrelated eager work between the replays
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), eager_out.view(torch.int16)), rep
+        assert torch.equal(lse.view(torch.int32), eager_lse.view(torch.int32)), rep
+    assert np.array_equal(H.host(case.k_cache).view(np.uint16), want_k.view(np.uint16))
+    assert np.array_equal(H.host(case.v_cache).view(np.uint16), want_v.view(np.uint16))
