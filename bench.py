@@ -359,6 +359,8 @@ def main():
         "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBPS,
         "attended_tokens_per_s": positions * args.steps / wall,
         "attended_head_tokens_per_s": positions * wl.num_q_heads * args.steps / wall,
+        # a step that walks every layer produces one token per sequence (attention only)
+        "decode_tokens_per_s_attention_only": wl.batch * args.steps / wall if lps > 1 else None,
         "read_ceiling_GBps": ceiling, "copy_GBps_read_plus_write": copy_gbps,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS,
