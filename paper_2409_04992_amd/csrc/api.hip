@@ -18,9 +18,11 @@ constexpr int kMinChunk = 384;
 // Work units wanted per launch and largest unit, per kernel family.  The
 // vector-ALU kernel runs 5 blocks per CU and is insensitive to the unit size, so
 // units stay small enough to balance ragged batches; the MFMA kernel runs 2
-// blocks per CU and pays more per unit, so it gets fewer, larger units.
+// blocks per CU and pays more per unit (prologue, cross-wave epilogue), so it gets
+// fewer, larger units: about three per four compute units measured best from
+// 16 x 16K down to 128 x 1K rows in all.
 constexpr int kTargetUnitsMha = 4096, kMaxChunkMha = 1408;
-constexpr int kTargetUnitsGqa = 768, kMaxChunkGqa = 5504;
+constexpr int kTargetUnitsGqa = 192, kMaxChunkGqa = 5504;
 constexpr int kSingleSplitStreams = 512, kSingleSplitMaxLen = 8192;
 
 struct Plan {
