@@ -98,10 +98,24 @@ def run_decode(case, desc, aux, r, k, l, out_dtype, max_len=None, fused_append=F
     return out, sel, alpha
 
 
-def check_against_oracle(case, out, sel, alpha, r, k, l, pairs=None):
+def device_rows(case, b, hk, L):
+    """Rows [0, L) of K and V of one (sequence, KV head), gathered on the device: for
+    caches too large to copy to the host whole."""
+    if case.page_table is None:
+        return case.k_cache[b, hk, :L].cpu().numpy(), case.v_cache[b, hk, :L].cpu().numpy()
+    ps = case.k_cache.shape[2]
+    pages = case.page_table[b, :(L + ps - 1) // ps].long()
+    D = case.k_cache.shape[3]
+    return (case.k_cache[pages, hk].reshape(-1, D)[:L].cpu().numpy(),
+            case.v_cache[pages, hk].reshape(-1, D)[:L].cpu().numpy())
+
+
+def check_against_oracle(case, out, sel, alpha, r, k, l, pairs=None, rows_of=None):
     wl = case.wl
     q = H.host(case.q)
-    K, V = logical(case)
+    if rows_of is None:
+        K, V = logical(case)
+        rows_of = lambda b, hk, L: (K[b, hk, :L], V[b, hk, :L])
     lens = H.host(case.seq_lens)
     tol = H.TOL[out.dtype]
     Bn, Hq, D = q.shape
@@ -113,7 +127,8 @@ def check_against_oracle(case, out, sel, alpha, r, k, l, pairs=None):
         if L <= 0:
             assert torch.equal(out[b, h], torch.zeros_like(out[b, h])) and float(alpha[b, h]) == 0.0
             continue
-        res = sparf.sparf_one(q[b, h], K[b, hk, :L], V[b, hk, :L], case.scale, r, k, l)
+        Kr, Vr = rows_of(b, hk, L)
+        res = sparf.sparf_one(q[b, h], Kr, Vr, case.scale, r, k, l)
         keff = min(k, L)
         got_rows = sel[b, h, :keff].cpu().numpy().astype(np.int64)
         assert (np.diff(got_rows) > 0).all() and got_rows[0] >= 0 and got_rows[-1] < L
@@ -130,8 +145,8 @@ def check_against_oracle(case, out, sel, alpha, r, k, l, pairs=None):
             for t in want_rows - set(got_rows.tolist()):
                 assert lg[t] <= thr + SCORE_EPS, (b, h, t)
         # steps 7, 10, 11 on the kernel's own selection
-        want_out, want_alpha = sparf.finish_from_selection(q[b, h], K[b, hk, :L], V[b, hk, :L],
-                                                           case.scale, res["s_hat"], got_rows, res["vbar"])
+        want_out, want_alpha = sparf.finish_from_selection(q[b, h], Kr, Vr, case.scale, res["s_hat"],
+                                                           got_rows, res["vbar"])
         assert abs(float(alpha[b, h]) - want_alpha) <= 2e-5
         err = np.abs(out[b, h].double().cpu().numpy() - want_out).max()
         worst = max(worst, err)
@@ -300,6 +315,42 @@ def test_sparf_13b_shape_one_eighth(monkeypatch):
     wl = W.WORKLOADS["mha13b_4k"]
     pairs = [(0, 0), (3, 17), (15, 39), (7, 8), (11, 21), (9, 30)]
     sparf_step(wl, 16, 256, 16, torch.float16, pairs=pairs)
+
+
+def sampled_full_size_step(wl, r, k, l, pairs, kt_page=None):
+    """A whole layer of a bench workload through instattn_sparf_append_decode (the call
+    bench.py times); sampled heads against the oracle, their rows gathered on the device."""
+    case, desc, aux, kt, vsum, _ = setup(wl, kt_page=kt_page)
+    out, sel, alpha = run_decode(case, desc, aux, r, k, l, torch.float16, fused_append=True)
+    lens = H.host(case.seq_lens)
+    for b, h in pairs:
+        hk, L = h // wl.group, int(lens[b])
+        Kr, Vr = device_rows(case, b, hk, L)
+        # the appended row, the column copy and the V sum of this (sequence, KV head)
+        assert np.array_equal(Kr[L - 1].view(np.uint16), H.host(case.k_new[b, hk]).view(np.uint16))
+        assert np.array_equal(Vr[L - 1].view(np.uint16), H.host(case.v_new[b, hk]).view(np.uint16))
+        cols = column_copy(kt, case.kt_table, b, L)[hk].cpu().numpy()
+        assert np.array_equal(cols.view(np.uint16), np.ascontiguousarray(Kr.T).view(np.uint16))
+        np.testing.assert_allclose(vsum[b, hk].double().cpu().numpy(), Vr.astype(np.float64).sum(axis=0),
+                                   rtol=0, atol=4e-2)
+    return check_against_oracle(case, out, sel, alpha, r, k, l, pairs,
+                                rows_of=lambda b, hk, L: device_rows(case, b, hk, L))
+
+
+def test_sparf_32k_shape_full_size_samples():
+    """8 x 40 heads x 32K: the long-row pipeline at the size bench.py times it."""
+    pairs = [(0, 0), (7, 39), (3, 17), (5, 8)]
+    sampled_full_size_step(W.WORKLOADS["mha13b_32k"], 16, 2048, 16, pairs)
+
+
+def test_sparf_ragged_paged_full_size_samples():
+    """64 ragged sequences of 1K-16K tokens, cache in 16-token pages, column copy in
+    256-token pages: the launch configuration of bench.py --workload ragged_paged --sparf."""
+    wl = W.WORKLOADS["ragged_paged"]
+    lens = W.draw_seq_lens(wl, "cpu")
+    order = torch.argsort(lens)
+    pairs = [(int(order[0]), 3), (int(order[-1]), 39), (int(order[len(order) // 2]), 20), (5, 11)]
+    sampled_full_size_step(wl, 16, 1024, 16, pairs, kt_page=256)
 
 
 def test_sparf_is_deterministic():
