@@ -33,7 +33,8 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="mha13b_4k")
+    ap.add_argument("--workload", default="mha13b_4k",
+                    help="one of the named configurations, or custom:{json fields of Workload} for sweeps")
     ap.add_argument("--layers-resident", type=int, default=8,
                     help="distinct layer caches the steps rotate over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -101,7 +102,7 @@ def bench_sparf(args):
     from paper_2409_04992_amd import workloads as W
     dev = "cuda:0"
     r, k, l = (int(x) for x in args.sparf.split(","))
-    wl = W.WORKLOADS[args.workload]
+    wl = W.get_workload(args.workload)
     kt_page = args.kt_page if args.kt_page is not None else (256 if wl.paged else 0)
     R = max(1, args.layers_resident)
     steps = args.steps or 200
@@ -187,7 +188,7 @@ def bench_kv_write(args):
     from paper_2409_04992_amd import binding as B
     from paper_2409_04992_amd import workloads as W
     dev = "cuda:0"
-    wl = W.WORKLOADS[args.workload]
+    wl = W.get_workload(args.workload)
     steps, warmup = args.steps or 50, args.warmup or 5
     R = 3
     cases = [W.make_case(wl, dev, layer=i) for i in range(R)]
@@ -237,7 +238,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     B.lib()                                   # fail loudly if the HIP library is missing
     dev = "cuda:0"
-    wl = W.WORKLOADS[args.workload]
+    wl = W.get_workload(args.workload)
     # a multi-layer workload keeps all its layers resident and a step walks them all
     R = wl.layers if wl.layers > 1 else max(1, args.layers_resident)
     lps = wl.layers

@@ -35,6 +35,14 @@
 
 #include <type_traits>
 
+// Compile-time knobs of the one-launch kernel (defaults are the measured best).
+#ifndef INSTATTN_SPARF_CGMAX
+#define INSTATTN_SPARF_CGMAX 8       // most kept columns loaded per step of the column pass (16: -5..-14 %)
+#endif
+#ifndef INSTATTN_SPARF_WAVES_PER_SIMD
+#define INSTATTN_SPARF_WAVES_PER_SIMD 4   // register budget: blocks of 4 waves resident per compute unit
+#endif
+
 namespace instattn {
 
 namespace {
@@ -234,26 +242,25 @@ __device__ __forceinline__ void locate_bin(SelectScratch& S, uint32_t remaining,
 }
 
 // All kept columns of one stretch of at most kSparfFusedMaxLen positions, in groups
-// of 16, then 8, 4, 2, 1 columns.
+// of INSTATTN_SPARF_CGMAX columns, then halves of that down to one.
+template <int CG, int NT>
+__device__ __forceinline__ void column_groups(const SparfArgs& a, int b, int hk, int t_base, int L, float factor,
+                                              const float* s_q, const int* s_dim, float* xs, int& j0)
+{
+    if constexpr (CG <= INSTATTN_SPARF_CGMAX)
+        for (; a.r - j0 >= CG; j0 += CG) column_pass<CG, NT>(a, b, hk, t_base, L, j0, j0 == 0, factor, s_q, s_dim, xs);
+}
+
 template <int NT>
 __device__ __forceinline__ void column_passes(const SparfArgs& a, int b, int hk, int t_base, int L, float factor,
                                               const float* s_q, const int* s_dim, float* xs)
 {
     int j0 = 0;
-    for (; j0 + 16 <= a.r; j0 += 16) column_pass<16, NT>(a, b, hk, t_base, L, j0, j0 == 0, factor, s_q, s_dim, xs);
-    if (a.r - j0 >= 8) {
-        column_pass<8, NT>(a, b, hk, t_base, L, j0, j0 == 0, factor, s_q, s_dim, xs);
-        j0 += 8;
-    }
-    if (a.r - j0 >= 4) {
-        column_pass<4, NT>(a, b, hk, t_base, L, j0, j0 == 0, factor, s_q, s_dim, xs);
-        j0 += 4;
-    }
-    if (a.r - j0 >= 2) {
-        column_pass<2, NT>(a, b, hk, t_base, L, j0, j0 == 0, factor, s_q, s_dim, xs);
-        j0 += 2;
-    }
-    if (a.r - j0 >= 1) column_pass<1, NT>(a, b, hk, t_base, L, j0, j0 == 0, factor, s_q, s_dim, xs);
+    column_groups<16, NT>(a, b, hk, t_base, L, factor, s_q, s_dim, xs, j0);
+    column_groups<8, NT>(a, b, hk, t_base, L, factor, s_q, s_dim, xs, j0);
+    column_groups<4, NT>(a, b, hk, t_base, L, factor, s_q, s_dim, xs, j0);
+    column_groups<2, NT>(a, b, hk, t_base, L, factor, s_q, s_dim, xs, j0);
+    column_groups<1, NT>(a, b, hk, t_base, L, factor, s_q, s_dim, xs, j0);
 }
 
 // The scores of positions (i * NT + tid) * 8 + e, e < 8, of a row of L scores at x
@@ -654,10 +661,15 @@ __device__ __forceinline__ float select_rows_reg(const float (&xr)[STEPS][8], co
 // the whole list and the block writes the output row.  Otherwise it writes its
 // share as D unnormalised sums, their reference maximum and the sum of weights
 // (D + 2 floats at part) for sparf_merge_kernel.
+//
+// fresh: the new token of this step is not in the cache yet (the one-launch kernel
+// stores it when everything else is done): its row, position t_new, comes from
+// k_new / v_new, and v_new is added to the V sum here.
 template <int D, int WAVES>
 __device__ __forceinline__ void attend_rows(const SparfArgs& a, int b, int h, int L, int p_begin, int p_end,
                                             const int32_t* sel, float alpha, float* part, int32_t* ids,
-                                            int ids_cap, float (*s_acc)[D], float* s_m, float* s_l)
+                                            int ids_cap, float (*s_acc)[D], float* s_m, float* s_l,
+                                            bool fresh = false, int t_new = -1)
 {
     constexpr int LPR = D / 8;
     constexpr int RPW = kWave / LPR;
@@ -675,6 +687,8 @@ __device__ __forceinline__ void attend_rows(const SparfArgs& a, int b, int h, in
     const int shift = a.kv.page_shift, mask = a.kv.page_mask;
     const int64_t base = (paged ? 0 : (int64_t)b * a.kv.stride_b) + (int64_t)hk * a.kv.stride_h + c * 8;
     const int64_t stride_page = paged ? a.kv.stride_b : 0;
+    const int64_t new_off = ((int64_t)b * a.num_kv_heads + hk) * D + c * 8;
+    if (!fresh) t_new = -1;
 
     float m = kNegBig, l = 0.f;
     float acc[8];
@@ -689,17 +703,21 @@ __device__ __forceinline__ void attend_rows(const SparfArgs& a, int b, int h, in
         __syncthreads();                   // whatever used this LDS before is done with it
         for (int i = tid; i < nc; i += WAVES * 64) {
             const int t = sel[c0 + i];
-            ids[i] = paged ? (a.kv.page_table[(int64_t)b * a.kv.max_pages + (t >> shift)] << shift) | (t & mask) : t;
+            if (t == t_new) ids[i] = -1;
+            else
+                ids[i] =
+                    paged ? (a.kv.page_table[(int64_t)b * a.kv.max_pages + (t >> shift)] << shift) | (t & mask) : t;
         }
         __syncthreads();
         auto load = [&](Tile& T, int it) {
 #pragma unroll
             for (int j = 0; j < U; ++j) {
-                const int id = ids[min(it * TILE + wave * 16 + j * RPW + r, nc - 1)];
+                const int raw = ids[min(it * TILE + wave * 16 + j * RPW + r, nc - 1)];
+                const int id = max(raw, 0);
                 const int64_t off = base + (int64_t)(paged ? id >> shift : 0) * stride_page +
                                     (int64_t)(paged ? id & mask : id) * a.kv.stride_t;
-                T.k[j] = *(const u32x4*)(a.kv.k + off);
-                T.v[j] = *(const u32x4*)(a.kv.v + off);
+                T.k[j] = *(const u32x4*)(raw < 0 ? a.k_new + new_off : a.kv.k + off);
+                T.v[j] = *(const u32x4*)(raw < 0 ? a.v_new + new_off : a.kv.v + off);
             }
         };
         auto consume = [&](const Tile& T, int it) {
@@ -768,7 +786,10 @@ __device__ __forceinline__ void attend_rows(const SparfArgs& a, int b, int h, in
         }
         o /= lsum;
         // step 11: alpha * (attention over the kept rows) + (1 - alpha) * mean of V
-        const float vbar = a.aux.vsum[((int64_t)b * a.num_kv_heads + hk) * D + tid] / (float)L;
+        const int64_t vi = ((int64_t)b * a.num_kv_heads + hk) * D + tid;
+        float vs = a.aux.vsum[vi];
+        if (fresh) vs += (float)a.v_new[vi];
+        const float vbar = vs / (float)L;
         o = alpha * o + (1.f - alpha) * vbar;
         if (a.out_f32) ((float*)a.out)[row * D + tid] = o;
         else ((half_t*)a.out)[row * D + tid] = (half_t)o;
@@ -805,7 +826,7 @@ __device__ __forceinline__ void write_zero_row(const SparfArgs& a, int64_t row)
 // Steps 1-4 (without the normaliser), long rows: one block per stretch of 8192
 // positions of one head, the same column pass as the one-launch kernel; the
 // scores go to the workspace together with the stretch's max / sum / min.
-__global__ __launch_bounds__(256, 3) void sparf_logits_kernel(SparfArgs a)
+__global__ __launch_bounds__(256, INSTATTN_SPARF_WAVES_PER_SIMD) void sparf_logits_kernel(SparfArgs a)
 {
     constexpr int NT = 256, STEPS = kSparfChunk / (NT * 8);
     static_assert(kSparfChunk == kSparfFusedMaxLen, "the column pass covers one stretch");
@@ -951,7 +972,7 @@ __global__ __launch_bounds__(D) void sparf_merge_kernel(SparfArgs a)
 // The whole of Algorithm 1 for one query head in one block of NT threads; the
 // scores live in dynamic LDS (one float per position, rows of at most 8192).
 template <int D, int NT>
-__global__ __launch_bounds__(NT, 3) void sparf_fused_kernel(SparfArgs a)
+__global__ __launch_bounds__(NT, INSTATTN_SPARF_WAVES_PER_SIMD) void sparf_fused_kernel(SparfArgs a)
 {
     constexpr int NG = (NT / 64) * (kWave / (D / 8));
     const int h = blockIdx.x, b = blockIdx.y;
@@ -972,9 +993,11 @@ __global__ __launch_bounds__(NT, 3) void sparf_fused_kernel(SparfArgs a)
     // the load of q are in flight together
     const int L_raw = a.seq_lens[b];
     // Fused append (one query head per KV head only: this block is the only reader
-    // of the row, the column entries and the sum it writes).  The barriers inside
-    // prepare_query order these stores before the block's later loads.
-    if (a.k_new != nullptr && tid < D) append_component(a, b, hk, tid, L_raw);
+    // of the row, the column entries and the sum of this KV head).  The new token is
+    // stored when everything else is done, so that nothing waits for those scattered
+    // stores; until then its score and its row are taken from k_new / v_new.
+    const bool fresh = a.k_new != nullptr && L_raw >= 1 && L_raw <= a.kv.capacity && L_raw <= a.aux.capacity;
+    const int t_new = L_raw - 1;
     const float factor = prepare_query(a, row, s_q, s_abs, s_dim, S.red);
     const int L = clamp_len(L_raw, a.max_len);
     if (L == 0) {
@@ -983,6 +1006,17 @@ __global__ __launch_bounds__(NT, 3) void sparf_fused_kernel(SparfArgs a)
         return;
     }
     column_passes<NT>(a, b, hk, 0, L, factor, s_q, s_dim, xs);
+    if (fresh && t_new < L && tid == ((t_new >> 3) % NT)) {
+        // the score of the new position, from k_new, by the thread that owns it and with
+        // the arithmetic of the column pass
+        const half_t* kn = a.k_new + ((int64_t)b * a.num_kv_heads + hk) * D;
+        float x = 0.f;
+        for (int j = 0; j < a.r; ++j) {
+            const int d = s_dim[j];
+            x = __builtin_fmaf(s_q[d] * factor, (float)kn[d], x);
+        }
+        xs[t_new] = x;
+    }
     // the thread's own scores stay in registers for the rest of steps 4-7
     constexpr int STEPS = kSparfFusedMaxLen / (NT * 8);
     float xr[STEPS][8];
@@ -998,7 +1032,8 @@ __global__ __launch_bounds__(NT, 3) void sparf_fused_kernel(SparfArgs a)
     // steps 10-11; the scores are dead, their LDS takes the row ids (the barrier
     // in front of that also makes the kept positions visible to the whole block)
     attend_rows<D, NT / 64>(a, b, h, L, 0, min(a.k, L), sel, alpha, nullptr, (int32_t*)xs, (L + 7) & ~7, s_acc,
-                            s_m, s_l);
+                            s_m, s_l, fresh, t_new);
+    if (fresh && tid < D) append_component(a, b, hk, tid, L_raw);
 }
 
 // ---------------------------------------------------------------------------

@@ -58,6 +58,14 @@ WORKLOADS = {
 }
 
 
+def get_workload(spec: str) -> Workload:
+    """A named configuration, or "custom:{json}" with Workload's fields (for sweeps)."""
+    if spec.startswith("custom:"):
+        import json
+        return Workload(**json.loads(spec[7:]))
+    return WORKLOADS[spec]
+
+
 @dataclasses.dataclass
 class Case:
     wl: Workload
