@@ -47,15 +47,22 @@ namespace instattn {
 
 namespace {
 
+// Wave-wide reductions: four DPP steps inside each row of 16 lanes, then the four
+// row results through scalar registers (no LDS crossbar traffic).  Every lane gets
+// the result; the order of the operations is fixed.
+__device__ __forceinline__ float lane_value(float x, int lane) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), lane));
+}
 __device__ __forceinline__ float wave_max(float x) {
-#pragma unroll
-    for (int s = 32; s > 0; s >>= 1) x = fmaxf(x, __shfl_xor(x, s, 64));
-    return x;
+    x = fmaxf(x, dpp_f32<kDppXor1>(x));
+    x = fmaxf(x, dpp_f32<kDppXor2>(x));
+    x = fmaxf(x, dpp_f32<kDppHalfMirror>(x));
+    x = fmaxf(x, dpp_f32<kDppMirror>(x));
+    return fmaxf(fmaxf(lane_value(x, 0), lane_value(x, 16)), fmaxf(lane_value(x, 32), lane_value(x, 48)));
 }
 __device__ __forceinline__ float wave_sum(float x) {
-#pragma unroll
-    for (int s = 32; s > 0; s >>= 1) x += __shfl_xor(x, s, 64);
-    return x;
+    x = group_sum<16>(x);
+    return (lane_value(x, 0) + lane_value(x, 16)) + (lane_value(x, 32) + lane_value(x, 48));
 }
 
 // Block-wide reductions through a small LDS array (one slot per wave); every
@@ -97,20 +104,29 @@ __device__ __forceinline__ float prepare_query(const SparfArgs& a, int64_t row, 
                                                int* s_dim, float* red)
 {
     const int D = a.head_dim, tid = threadIdx.x;
+    uint32_t* s_key = (uint32_t*)s_abs;     // 16-byte aligned by its callers
     float mine = 0.f;
+    uint32_t key = 0;
     if (tid < D) {
-        const float qd = (float)a.q[row * D + tid];
+        const half_t qh = a.q[row * D + tid];
+        const float qd = (float)qh;
         s_q[tid] = qd;
         mine = fabsf(qd);
-        s_abs[tid] = mine;
+        // one integer per component that orders them as step 1 wants: by magnitude (the
+        // fp16 bit pattern without its sign is monotone in it), ties to the lower index
+        key = ((uint32_t)(__builtin_bit_cast(uint16_t, qh) & 0x7FFFu) << 8) | (uint32_t)(255 - tid);
+        s_key[tid] = key;
     }
     __syncthreads();
     float kept = 0.f;
     if (tid < D) {
+        // rank = number of keys above this one (keys are distinct); 128-bit LDS reads
+        const u32x4* k4 = (const u32x4*)s_key;
         int rank = 0;
-        for (int d = 0; d < D; ++d) {
-            const float o = s_abs[d];
-            rank += (o > mine) || (o == mine && d < tid);
+#pragma unroll 8
+        for (int i = 0; i < D / 4; ++i) {
+            const u32x4 o = k4[i];
+            rank += (int)(o.x > key) + (int)(o.y > key) + (int)(o.z > key) + (int)(o.w > key);
         }
         s_dim[rank] = tid;
         if (rank < a.r) kept = mine;
@@ -848,7 +864,7 @@ __global__ __launch_bounds__(256, INSTATTN_SPARF_WAVES_PER_SIMD) void sparf_logi
     }
     __shared__ __align__(16) float xs[kSparfChunk];
     __shared__ float s_q[128];
-    __shared__ float s_abs[128];
+    __shared__ __align__(16) float s_abs[128];
     __shared__ int s_dim[128];
     __shared__ float s_red[48];
     const float factor = prepare_query(a, row, s_q, s_abs, s_dim, s_red);
@@ -982,7 +998,7 @@ __global__ __launch_bounds__(NT, INSTATTN_SPARF_WAVES_PER_SIMD) void sparf_fused
     const int64_t row = (int64_t)b * a.num_q_heads + h;
     extern __shared__ __align__(16) float xs[];   // scores, log2 domain
     __shared__ float s_q[128];
-    __shared__ float s_abs[128];
+    __shared__ __align__(16) float s_abs[128];
     __shared__ int s_dim[128];
     __shared__ SelectScratch S;
     __shared__ float s_acc[NG][D];
