@@ -17,7 +17,7 @@ R^{S x d_h}; r, k, l in N; m, n are the page sizes of the two-step loads):
   10  s   <- softmax( q . K^T_[j,:] / sqrt(d_h) )
   11  out <- alpha * s . V_[j,:] + (1 - alpha) * v-bar
 
-Readings where the listing is garbled or silent (stated in the design doc too):
+Readings where the listing is garbled or silent:
   * step 1 writes its index range as 1..S; it ranges over the d_h components of q.
   * step 5 is printed as "1 if i > S", which would leave l unused; it is read as
     i > S - l (1-based), i.e. the l most recent positions always rank first
