@@ -276,7 +276,7 @@ int instattn_sparf_decode(const void* q, const instattn_kv_desc* kv, const insta
  * When max_seq_len <= 8192 and every KV head has one query head, the one launch of
  * the decode stores the new token itself; otherwise the append is a launch of its
  * own in front.  Like instattn_sparf_append it must be called once per new token.
- *   k_new, v_new : device, [batch][num_kv_heads][head_dim] fp16, dense
+ *   k_new, v_new : device, [batch][num_kv_heads][head_dim] fp16, dense, 16-byte aligned
  */
 int instattn_sparf_append_decode(const void* q, const void* k_new, const void* v_new,
                                  const instattn_kv_desc* kv, const instattn_sparf_aux* aux,

@@ -137,7 +137,7 @@ int run_sparf_decode(const void* q, const void* k_new, const void* v_new, bool a
     if (num_q_heads <= 0 || num_q_heads % num_kv_heads || max_seq_len <= 0) return INSTATTN_ERR_INVALID_ARG;
     if (batch > 65535 || num_q_heads > 65535) return INSTATTN_ERR_UNSUPPORTED;
     if (!q || !aligned16(q) || !seq_lens || !isfinite(scale)) return INSTATTN_ERR_INVALID_ARG;
-    if (append && (!k_new || !v_new)) return INSTATTN_ERR_INVALID_ARG;
+    if (append && (!k_new || !v_new || !aligned16(k_new) || !aligned16(v_new))) return INSTATTN_ERR_INVALID_ARG;
     if (!out || !aligned16(out)) return INSTATTN_ERR_INVALID_ARG;
     if (out_dtype != INSTATTN_F16 && out_dtype != INSTATTN_F32) return INSTATTN_ERR_INVALID_ARG;
     if (r < 1 || r > head_dim || k < 1 || l < 0) return INSTATTN_ERR_INVALID_ARG;

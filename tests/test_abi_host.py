@@ -234,6 +234,10 @@ def test_sparf_append_decode_rejects():
     bad = list(args)
     bad[19] = 4096
     assert L.instattn_sparf_append_decode(*bad) == B.ERR_WORKSPACE
+    for i in (1, 2):                             # new rows are read with 128-bit loads
+        bad = list(args)
+        bad[i] = FAKE + 2
+        assert L.instattn_sparf_append_decode(*bad) == B.ERR_INVALID_ARG, i
 
 
 def test_sparf_build_and_append_reject():
