@@ -171,11 +171,12 @@ int run_sparf_decode(const void* q, const void* k_new, const void* v_new, bool a
     // chip when there are few heads, none smaller than 256 rows.
     {
         const int64_t heads = (int64_t)batch * num_q_heads;
+        const int kept = k < max_seq_len ? k : max_seq_len;      // no head keeps more rows than it has
         int ns = (int)((1024 + heads - 1) / heads);
-        ns = ns < k / 256 ? ns : k / 256;
+        ns = ns < kept / 256 ? ns : kept / 256;
         ns = ns < 1 ? 1 : (ns > kSparfMaxSlices ? kSparfMaxSlices : ns);
         a.nslices = ns;
-        a.slice_rows = ((k + ns - 1) / ns + 15) / 16 * 16;
+        a.slice_rows = ((kept + ns - 1) / ns + 15) / 16 * 16;
     }
     a.out = out;
     a.out_f32 = out_dtype == INSTATTN_F32;

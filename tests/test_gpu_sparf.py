@@ -247,7 +247,7 @@ def test_sparf_append_decode_equals_the_two_calls():
 
 
 @pytest.mark.parametrize("seq_len,k", [(20000, 1300), (8192, 100), (32767, 3000), (32768, 600), (40000, 2500),
-                                       (65534, 700), (70000, 4400)])
+                                       (65534, 700), (70000, 4400), (9000, 20000)])
 def test_sparf_long_rows_take_the_three_launch_pipeline(seq_len, k):
     """Rows behind the one-launch limit: the selection keeps the scores in registers up
     to 32768 and up to 65535 positions and passes over the workspace beyond; the
