@@ -217,7 +217,6 @@ __device__ __forceinline__ void column_pass(const SparfArgs& a, int b, int hk, i
 }
 
 constexpr int kSelMembers = 512;     // members of the threshold bin ranked directly
-constexpr int kSelPer = 32;          // most positions per thread in one round of the compaction
 
 struct SelectScratch {
     uint32_t hist[256];
@@ -445,22 +444,93 @@ __device__ __forceinline__ void find_threshold(ForEach&& for_each, int want, Sel
     }
 }
 
-// Steps 5-7 for one head: x[0..L) are the log2-domain scores (LDS or global), M
-// their maximum, xmin their minimum and Z the sum of 2^(x - M).  Writes the kept
-// positions in ascending order to sel and returns alpha to every thread.
-//
-// The compaction is ordered: a wave owns a run of consecutive positions (lane i
-// takes every 64th from its i-th), ranks its kept rows with ballots and popcounts
-// alone, and one barrier per round of up to 32 positions per thread passes the
-// wave totals on.  The output slot of a row is (rows above the threshold before
-// it) + min(rows at the threshold before it, number of those still wanted), so
-// ties go to the lower position and the result is deterministic.
+// Ordered compaction of one register tile: xr[i][e] is the score of position
+// t_off + (i * NT + tid) * 8 + e, candidates are the positions below ncand.  Writes
+// the kept positions of the tile to their slots of sel and adds their softmax mass.
+// Position order is (i, wave, lane, e): a shuffle scan over the lanes of a wave per
+// step i, the wave totals per step through LDS (step_cnt, STEPS * NT / 64 words),
+// one barrier.  The output slot of a row is (rows above the threshold before it) +
+// min(rows at the threshold before it, number of those still wanted), so ties go
+// to the lower position and the result is deterministic.  gt_base / eq_base count
+// the rows above / at the threshold in earlier tiles and are advanced.
+template <int NT, int STEPS, class BinOf>
+__device__ __forceinline__ void compact_tile(const float (&xr)[STEPS][8], BinOf&& bin_of, int t_off, int ncand,
+                                             uint32_t bin1, uint32_t prefix, uint32_t remaining,
+                                             uint32_t& gt_base, uint32_t& eq_base, uint32_t* step_cnt,
+                                             const float* x, float M, int32_t* sel, float& mass)
+{
+    constexpr int NW = NT / 64;
+    typedef typename std::conditional<(STEPS > 4), uint64_t, uint32_t>::type bits_t;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    bits_t gtbits = 0, eqbits = 0;                         // bit 8i + e
+    uint32_t excl[STEPS];                                  // kept before this lane in its wave, per step
+#pragma unroll
+    for (int i = 0; i < STEPS; ++i) {
+        uint32_t c = 0;
+        if (t_off + i * NT * 8 < ncand) {                  // block-uniform
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const bool valid = t_off + (i * NT + tid) * 8 + e < ncand;
+                const uint32_t b1 = bin_of(i, e);
+                const uint32_t key = order_key(xr[i][e]);
+                const bool gt = valid && (b1 > bin1 || (b1 == bin1 && key > prefix));
+                const bool eq = valid && b1 == bin1 && key == prefix;
+                gtbits |= (bits_t)gt << (8 * i + e);
+                eqbits |= (bits_t)eq << (8 * i + e);
+                c += (uint32_t)gt + ((uint32_t)eq << 16);
+            }
+        }
+        uint32_t incl = c;                                 // 16-bit halves: at most 512 each
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const uint32_t o = __shfl_up(incl, d, 64);
+            if (lane >= d) incl += o;
+        }
+        excl[i] = incl - c;
+        if (lane == 63) step_cnt[i * NW + wave] = incl;
+    }
+    __syncthreads();
+    uint32_t run = 0;                                      // halves: at most 65535 each in a tile
+#pragma unroll
+    for (int i = 0; i < STEPS; ++i) {
+        uint32_t mine = 0;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            mine = w == wave ? run : mine;
+            run += step_cnt[i * NW + w];
+        }
+        const uint32_t gb = gt_base + ((mine + excl[i]) & 0xFFFFu), eb = eq_base + ((mine + excl[i]) >> 16);
+        // the few flagged slots of this lane, in position order
+        const uint32_t g8 = (uint32_t)(gtbits >> (8 * i)) & 0xFFu, e8 = (uint32_t)(eqbits >> (8 * i)) & 0xFFu;
+        uint32_t todo = g8 | e8;
+        while (todo) {
+            const int e = __builtin_ctz(todo);
+            todo &= todo - 1;
+            const uint32_t below = (1u << e) - 1u;
+            const uint32_t eq_before = eb + (uint32_t)__popc(e8 & below);
+            if (((g8 >> e) & 1u) || eq_before < remaining) {
+                const int t = t_off + (i * NT + tid) * 8 + e;
+                sel[gb + (uint32_t)__popc(g8 & below) + min(eq_before, remaining)] = t;
+                mass += fast_exp2(x[t] - M);
+            }
+        }
+    }
+    gt_base += run & 0xFFFFu;
+    eq_base += run >> 16;
+}
+
+// Steps 5-7 for one head of any length: x[0..L) are the log2-domain scores in
+// global memory, M their maximum, xmin their minimum and Z the sum of 2^(x - M).
+// Writes the kept positions in ascending order to sel and returns alpha to every
+// thread.  The row goes through register tiles of NT * 32 positions (two 128-bit
+// loads per thread and step, all of a tile in flight at once): twice for the
+// threshold, once for the compaction.
 template <int NT>
 __device__ __forceinline__ float select_rows(const float* x, int L, int k, int l, float M, float xmin, float Z,
                                              int32_t* sel, SelectScratch& S)
 {
-    constexpr int NW = NT / 64;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    constexpr int STEPS = 4, TILE = NT * 8 * STEPS;
+    const int tid = threadIdx.x;
     const int keff = min(k, L);
     const int leff = min(l, keff);
     const int want = keff - leff;          // rows to pick among the candidates
@@ -468,73 +538,29 @@ __device__ __forceinline__ float select_rows(const float* x, int L, int k, int l
     const Level1 level1(M, xmin);
 
     uint32_t bin1, prefix, remaining;
-    // eight independent loads per thread before they are used (the scores may live in
-    // global memory)
     find_threshold<NT>(
         [&](auto&& f) {
-            for (int t0 = tid; t0 < ncand; t0 += 8 * NT) {
-                float v[8];
+            for (int t_off = 0; t_off < ncand; t_off += TILE) {
+                float xr[STEPS][8];
+                own_scores<NT, STEPS>(x + t_off, ncand - t_off, xr);
 #pragma unroll
-                for (int j = 0; j < 8; ++j) v[j] = t0 + j * NT < ncand ? x[t0 + j * NT] : M;
+                for (int i = 0; i < STEPS; ++i)
 #pragma unroll
-                for (int j = 0; j < 8; ++j)
-                    if (t0 + j * NT < ncand) f(v[j], level1(v[j]));
+                    for (int e = 0; e < 8; ++e)
+                        if (t_off + (i * NT + tid) * 8 + e < ncand) f(xr[i][e], level1(xr[i][e]));
             }
         },
         want, S, bin1, prefix, remaining);
 
     float mass = 0.f;
-    const uint64_t lt_mask = lane == 0 ? 0ull : (~0ull >> (64 - lane));
-    const int per = min(kSelPer, ((ncand + NT - 1) / NT + 7) & ~7);   // positions per thread and round
-    uint32_t gt_base = 0, eq_base = 0;                                // kept-above / threshold rows of earlier rounds
+    uint32_t gt_base = 0, eq_base = 0;
     int parity = 0;
-    for (int r0 = 0; want > 0 && r0 < ncand; r0 += NT * per, parity ^= 1) {
-        const int w0 = r0 + wave * 64 * per + lane;
-        uint32_t gtbits = 0, eqbits = 0, n_gt = 0, n_eq = 0;
-        for (int j0 = 0; j0 < per; j0 += 8) {
-            float v[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int t = w0 + (j0 + j) * 64;
-                v[j] = t < ncand ? x[t] : M;
-            }
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const bool valid = w0 + (j0 + j) * 64 < ncand;
-                const uint32_t b1 = level1(v[j]);
-                const uint32_t key = order_key(v[j]);
-                const bool gt = valid && (b1 > bin1 || (b1 == bin1 && key > prefix));
-                const bool eq = valid && b1 == bin1 && key == prefix;
-                gtbits |= (uint32_t)gt << (j0 + j);
-                eqbits |= (uint32_t)eq << (j0 + j);
-                n_gt += (uint32_t)__popcll(__ballot(gt));
-                n_eq += (uint32_t)__popcll(__ballot(eq));
-            }
-        }
-        if (lane == 0) S.wave_cnt[parity][wave] = n_gt | (n_eq << 16);   // each at most 64 * 32
-        __syncthreads();
-        uint32_t before = 0, total = 0;                                  // 16-bit halves: at most 1024 * 32 each
-#pragma unroll
-        for (int w = 0; w < NW; ++w) {
-            const uint32_t c = S.wave_cnt[parity][w];
-            total += c;
-            before += w < wave ? c : 0u;
-        }
-        uint32_t gb = gt_base + (before & 0xFFFFu), eb = eq_base + (before >> 16);
-        for (int j = 0; j < per; ++j) {
-            const bool gt = (gtbits >> j) & 1u, eq = (eqbits >> j) & 1u;
-            const uint64_t bg = __ballot(gt), be = __ballot(eq);
-            const uint32_t eq_before = eb + (uint32_t)__popcll(be & lt_mask);
-            if (gt || (eq && eq_before < remaining)) {
-                const int t = w0 + j * 64;
-                sel[gb + (uint32_t)__popcll(bg & lt_mask) + min(eq_before, remaining)] = t;
-                mass += fast_exp2(x[t] - M);
-            }
-            gb += (uint32_t)__popcll(bg);
-            eb += (uint32_t)__popcll(be);
-        }
-        gt_base += total & 0xFFFFu;
-        eq_base += total >> 16;
+    for (int t_off = 0; want > 0 && t_off < ncand; t_off += TILE, parity ^= 1) {
+        float xr[STEPS][8];
+        own_scores<NT, STEPS>(x + t_off, ncand - t_off, xr);
+        compact_tile<NT, STEPS>(
+            xr, [&](int i, int e) { return level1(xr[i][e]); }, t_off, ncand, bin1, prefix, remaining, gt_base,
+            eq_base, &S.wave_cnt[parity * 4][0], x, M, sel, mass);
     }
     // step 5: the l most recent positions are always kept
     for (int i = tid; i < leff; i += NT) {
@@ -546,19 +572,15 @@ __device__ __forceinline__ float select_rows(const float* x, int L, int k, int l
 }
 
 // The same for a row of at most STEPS * NT * 8 positions whose scores the threads
-// hold in registers: xr[i][e] is the score of position (i * NT + tid) * 8 + e (what
-// the column pass gave this thread); xs holds the same scores in LDS.  Position
-// order is (i, wave, lane, e): a shuffle scan over the lanes of a wave per step i,
-// the wave totals per step through LDS, one barrier.
+// hold in registers already: xr[i][e] is the score of position (i * NT + tid) * 8 + e
+// (what the column pass gave this thread); xs holds the same scores in memory.
 template <int NT, int STEPS>
 __device__ __forceinline__ float select_rows_reg(const float (&xr)[STEPS][8], const float* xs, int L, int k,
                                                  int l, float M, float xmin, float Z, int32_t* sel,
                                                  SelectScratch& S)
 {
-    constexpr int NW = NT / 64;
-    static_assert(STEPS * NW <= 128 && STEPS * 8 <= 64, "counts and flag words");
-    typedef typename std::conditional<(STEPS > 4), uint64_t, uint32_t>::type bits_t;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    static_assert(STEPS * (NT / 64) <= 128 && STEPS * 8 <= 64, "counts and flag words");
+    const int tid = threadIdx.x;
     const int keff = min(k, L);
     const int leff = min(l, keff);
     const int want = keff - leff;
@@ -566,7 +588,7 @@ __device__ __forceinline__ float select_rows_reg(const float (&xr)[STEPS][8], co
     const Level1 level1(M, xmin);
 
     // level-1 bins of the own scores, one byte each, computed once (where the register
-    // budget allows: 1024 threads with 64 scores each recompute them instead)
+    // budget allows: with 40 or 64 scores per thread they are recomputed instead)
     constexpr bool kCacheBins = STEPS <= 4;
     uint32_t bins[kCacheBins ? STEPS : 1][2];
     if constexpr (kCacheBins) {
@@ -600,60 +622,9 @@ __device__ __forceinline__ float select_rows_reg(const float (&xr)[STEPS][8], co
 
     float mass = 0.f;
     if (want > 0) {
-        bits_t gtbits = 0, eqbits = 0;                         // bit 8i + e
-        uint32_t excl[STEPS];                                  // kept before this lane in its wave, per step
-        uint32_t* step_cnt = &S.wave_cnt[0][0];                // [STEPS][NW]
-#pragma unroll
-        for (int i = 0; i < STEPS; ++i) {
-            uint32_t c = 0;
-            if (i * NT * 8 < ncand) {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const bool valid = (i * NT + tid) * 8 + e < ncand;
-                    const uint32_t b1 = bin_of(i, e);
-                    const uint32_t key = order_key(xr[i][e]);
-                    const bool gt = valid && (b1 > bin1 || (b1 == bin1 && key > prefix));
-                    const bool eq = valid && b1 == bin1 && key == prefix;
-                    gtbits |= (bits_t)gt << (8 * i + e);
-                    eqbits |= (bits_t)eq << (8 * i + e);
-                    c += (uint32_t)gt + ((uint32_t)eq << 16);
-                }
-            }
-            uint32_t incl = c;                                 // 16-bit halves: at most 512 each (65535 in all)
-#pragma unroll
-            for (int d = 1; d < 64; d <<= 1) {
-                const uint32_t o = __shfl_up(incl, d, 64);
-                if (lane >= d) incl += o;
-            }
-            excl[i] = incl - c;
-            if (lane == 63) step_cnt[i * NW + wave] = incl;
-        }
-        __syncthreads();
-        uint32_t run = 0;                                      // halves: at most 8192 each
-#pragma unroll
-        for (int i = 0; i < STEPS; ++i) {
-            uint32_t mine = 0;
-#pragma unroll
-            for (int w = 0; w < NW; ++w) {
-                mine = w == wave ? run : mine;
-                run += step_cnt[i * NW + w];
-            }
-            const uint32_t gb = (mine + excl[i]) & 0xFFFFu, eb = (mine + excl[i]) >> 16;
-            // the few flagged slots of this lane, in position order
-            const uint32_t g8 = (uint32_t)(gtbits >> (8 * i)) & 0xFFu, e8 = (uint32_t)(eqbits >> (8 * i)) & 0xFFu;
-            uint32_t todo = g8 | e8;
-            while (todo) {
-                const int e = __builtin_ctz(todo);
-                todo &= todo - 1;
-                const uint32_t below = (1u << e) - 1u;
-                const uint32_t eq_before = eb + (uint32_t)__popc(e8 & below);
-                if (((g8 >> e) & 1u) || eq_before < remaining) {
-                    const int t = (i * NT + tid) * 8 + e;
-                    sel[gb + (uint32_t)__popc(g8 & below) + min(eq_before, remaining)] = t;
-                    mass += fast_exp2(xs[t] - M);
-                }
-            }
-        }
+        uint32_t gt_base = 0, eq_base = 0;
+        compact_tile<NT, STEPS>(xr, bin_of, 0, ncand, bin1, prefix, remaining, gt_base, eq_base, &S.wave_cnt[0][0],
+                                xs, M, sel, mass);
     }
     // step 5: the l most recent positions are always kept
     for (int i = tid; i < leff; i += NT) {
