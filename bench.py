@@ -76,16 +76,19 @@ def cpu_baseline(cases, kv_bytes_layer, positions_layer):
     t = time.perf_counter()
     c_oracle.decode(*args0, pair_stride=stride, nthreads=cores)
     per_pair_cpu_s = (time.perf_counter() - t) * cores / len(range(0, pairs, stride))
-    want_pairs = budget_cpu_s / per_pair_cpu_s
-    layers = int(min(len(cases), max(1, want_pairs // pairs)))
+    # every n-th pair only if one whole layer would take much longer than the budget;
+    # then whole layers until about 12 s of CPU work are done (the thin calibration
+    # sample overestimates, so the clock decides, not the estimate)
+    want_pairs = 1.5 * budget_cpu_s / per_pair_cpu_s
     stride = max(1, int(pairs // want_pairs)) if want_pairs < pairs else 1
-    done, dt = 0, 0.0
-    for i in range(layers):
-        args = args0 if i == 0 else host(cases[i])
+    done, dt, layers = 0, 0.0, 0
+    while layers < len(cases) and dt * cores < 12.0:
+        args = args0 if layers == 0 else host(cases[layers])
         t = time.perf_counter()
         c_oracle.decode(*args, pair_stride=stride, nthreads=cores)
         dt += time.perf_counter() - t
         done += len(range(0, pairs, stride))
+        layers += 1
     frac = done / pairs          # in units of one layer
     return {
         "value": kv_bytes_layer * frac / dt / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
