@@ -367,6 +367,28 @@ def test_prefill_write_then_decode():
     H.assert_close(out, lse, want_out, want_lse, "prefill+decode")
 
 
+# ------------------------------------------------------------------ seeded draw of shapes
+def _drawn_configs(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(n):
+        D = int(rng.choice([64, 128]))
+        G = int(rng.choice([1, 1, 2, 3, 4, 8, 16]))
+        Hkv = int(rng.choice([1, 2, 5]))
+        S = int(rng.integers(0, 9000)) if i % 4 == 3 else int(rng.integers(0, 2500))
+        Bn = int(rng.integers(1, 4))
+        out.append((i, Bn, D, G, Hkv, S, bool(rng.integers(0, 2)), bool(rng.integers(0, 2)), bool(rng.integers(0, 2))))
+    return out
+
+
+@pytest.mark.parametrize("cfg", _drawn_configs(24, 20240918), ids=lambda c: "cfg%d" % c[0])
+def test_drawn_configurations(cfg):
+    i, Bn, D, G, Hkv, S, paged, f32, fused = cfg
+    wl = W.Workload("drawn%d" % i, Bn, G * Hkv, Hkv, D, S, seq_len_min=S // 4, paged=paged, page_size=16,
+                    seed=700 + i)
+    full_check(wl, out_dtype=torch.float32 if f32 else torch.float16, fused=fused)
+
+
 # ------------------------------------------------------------------ HIP graph replay
 @pytest.mark.parametrize("shape", ["mha_splits", "gqa_paged"])
 def test_step_replayed_from_a_hip_graph(shape):

@@ -353,6 +353,35 @@ def test_sparf_ragged_paged_full_size_samples():
     sampled_full_size_step(wl, 16, 1024, 16, pairs, kt_page=256)
 
 
+def _drawn_configs(n, seed):
+    """Seeded draw of shapes and parameters across everything the entry points accept."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(n):
+        D = int(rng.choice([64, 128]))
+        G = int(rng.choice([1, 1, 2, 4, 8]))
+        Hkv = int(rng.choice([1, 2, 3]))
+        long_row = i % 5 == 4
+        S = int(rng.integers(8200, 13000)) if long_row else int(rng.integers(0, 3000))
+        paged = bool(rng.integers(0, 2))
+        kt_page = [None, 8, 64, 256][int(rng.integers(0, 4))]
+        r = int(rng.integers(1, D + 1)) if i % 3 == 0 else int(rng.choice([D // 16, D // 8, D // 4]))
+        k = int(rng.integers(1, 2 * S + 3))
+        l = int(rng.integers(0, 41))
+        f16 = bool(rng.integers(0, 2))
+        fused = bool(rng.integers(0, 2))
+        out.append((i, D, G, Hkv, S, paged, kt_page, r, k, l, f16, fused))
+    return out
+
+
+@pytest.mark.parametrize("cfg", _drawn_configs(20, 20240917), ids=lambda c: "cfg%d" % c[0])
+def test_sparf_drawn_configurations(cfg):
+    i, D, G, Hkv, S, paged, kt_page, r, k, l, f16, fused = cfg
+    wl = W.Workload("sparf_drawn%d" % i, 2, G * Hkv, Hkv, D, S, seq_len_min=max(0, S // 3), paged=paged,
+                    page_size=16, seed=600 + i)
+    sparf_step(wl, r, k, l, torch.float16 if f16 else torch.float32, kt_page=kt_page, fused_append=fused)
+
+
 def test_sparf_is_deterministic():
     wl = W.Workload("sparf_det", 2, 4, 4, 128, 3000, seed=406)
     case, desc, aux, kt, vsum, _ = setup(wl)
