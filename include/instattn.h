@@ -229,7 +229,7 @@ typedef struct {
 /*
  * Fill aux (kt and vsum) from the rows 0 .. seq_lens[b]-1 of an existing cache:
  * what the storage side does when the prefill phase hands over a layer's K and V
- * (Sec. IV-D).  Rows at or behind the length are not read.  One launch.
+ * (Sec. IV-D).  Rows at or behind the length are not read.  Two launches.
  */
 int instattn_sparf_build(const instattn_kv_desc* kv, const instattn_sparf_aux* aux,
                          const int32_t* seq_lens, int batch, int num_kv_heads, int head_dim,

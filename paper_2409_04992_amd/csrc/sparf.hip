@@ -24,8 +24,8 @@
 //   sparf_fused_kernel    all of the above in one launch, one block per query head,
 //                         scores kept in LDS: used when a row has at most 8192
 //                         positions.
-//   sparf_build_kernel    builds the component-major K copy and the running sum
-//                         of V from an existing cache (prefill side).
+//   sparf_build_kernel,   build the component-major K copy and the running sum of V
+//   sparf_vsum_kernel     from an existing cache (prefill side).
 //   sparf_append_kernel   kv_append plus the new column entry and sum update (the
 //                         one-launch kernel does this itself when asked to and
 //                         every KV head has a single query head).
@@ -1024,56 +1024,91 @@ __global__ __launch_bounds__(NT, INSTATTN_SPARF_WAVES_PER_SIMD) void sparf_fused
 }
 
 // ---------------------------------------------------------------------------
-// Component-major copy of K and column sums of V for rows [0, L_b): one block per
-// (sequence, KV head) walks the rows in tiles of 64, transposing K through LDS.
+// Component-major copy of K for rows [0, L_b): one block per stretch of 512 rows of
+// one (sequence, KV head).  A thread loads an 8 x 8 block (8 rows, 16 bytes each),
+// transposes it in registers, and the 16-byte pieces (8 positions of one component)
+// change hands through LDS so that adjacent lanes store adjacent pieces of a column:
+// every LDS access is 128 bits wide.  Slots are swizzled by the column group, so the
+// lanes of a store hit different banks.
+constexpr int kBuildRows = 512;
+
+template <int D>
 __global__ __launch_bounds__(256) void sparf_build_kernel(SparfArgs a)
+{
+    constexpr int COLS8 = D / 8;                 // 16-byte pieces per row
+    constexpr int RUNS = 256 / COLS8;            // runs of 8 rows per tile: one 8 x 8 block per thread
+    constexpr int TILE = 8 * RUNS;               // 128 rows (D = 128) or 256 (D = 64)
+    const int hk = blockIdx.x, b = blockIdx.z;
+    const int tid = threadIdx.x;
+    const int L = clamp_len(a.seq_lens[b], min(a.kv.capacity, a.aux.capacity));
+    const int t_begin = blockIdx.y * kBuildRows, t_end = min(t_begin + kBuildRows, L);
+    if (t_begin >= L) return;
+
+    __shared__ u32x4 s_piece[D][RUNS];           // [component][run of 8 positions, swizzled]
+    const int c8 = tid % COLS8, run = tid / COLS8;
+    for (int t0 = t_begin; t0 < t_end; t0 += TILE) {
+        // rows t0 + 8 run .. + 7 (rows at or behind L are not read; their slots become 0)
+        half8_t rows[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int t = t0 + run * 8 + j;
+            const half8_t z = {0, 0, 0, 0, 0, 0, 0, 0};
+            rows[j] = t < L ? *(const half8_t*)(a.kv.k + row_offset(a.kv, b, hk, t) + c8 * 8) : z;
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const half8_t col = {rows[0][e], rows[1][e], rows[2][e], rows[3][e],
+                                 rows[4][e], rows[5][e], rows[6][e], rows[7][e]};
+            s_piece[c8 * 8 + e][run ^ (c8 % RUNS)] = __builtin_bit_cast(u32x4, col);
+        }
+        __syncthreads();
+        for (int i = tid; i < D * RUNS; i += 256) {
+            const int d = i / RUNS, r8 = i % RUNS;
+            const int t = t0 + r8 * 8;
+            if (t < L)
+                *(u32x4*)(kt_col0(a.aux, b, hk, t) + (int64_t)d * a.aux.stride_d) = s_piece[d][r8 ^ ((d / 8) % RUNS)];
+        }
+        __syncthreads();
+    }
+}
+
+// Column sums of V over rows [0, L_b): one block of 1024 threads per (sequence, KV
+// head); D / 8 adjacent threads read a row, the 1024 / (D / 8) row groups take every
+// such-th row with four loads in flight and are added in a fixed order.
+__global__ __launch_bounds__(1024) void sparf_vsum_kernel(SparfArgs a)
 {
     const int hk = blockIdx.x, b = blockIdx.y;
     const int D = a.head_dim;
     const int tid = threadIdx.x;
     const int L = clamp_len(a.seq_lens[b], min(a.kv.capacity, a.aux.capacity));
-
-    __shared__ half_t s_tile[64][128 + 2];   // +2: odd word stride for the column reads
-    __shared__ float s_sum[32][128];
-    const int cols8 = D / 8;                 // 8 or 16: divides 256, so a thread keeps its columns
-    const int c8 = tid % cols8;
+    const int cols8 = D / 8;                 // 8 or 16
+    const int c8 = tid % cols8, part = tid / cols8, parts = 1024 / cols8;
+    __shared__ float s_sum[8192];            // [row group][column]: 64 x 128 or 128 x 64
     float vs[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) vs[e] = 0.f;
-    for (int t0 = 0; t0 < L; t0 += 64) {
-        // rows t0 .. t0+63 (rows at or behind L are not read; their slots become 0)
-        for (int i = tid; i < 64 * cols8; i += 256) {
-            const int tr = i / cols8;
-            half8_t kr = {0, 0, 0, 0, 0, 0, 0, 0};
-            if (t0 + tr < L) {
-                const int64_t off = row_offset(a.kv, b, hk, t0 + tr) + c8 * 8;
-                kr = *(const half8_t*)(a.kv.k + off);
-                const half8_t vr = *(const half8_t*)(a.kv.v + off);
+    int t = part;
+    for (; t + 3 * parts < L; t += 4 * parts) {
+        half8_t vr[4];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) vs[e] += (float)vr[e];
-            }
+        for (int j = 0; j < 4; ++j)
+            vr[j] = *(const half8_t*)(a.kv.v + row_offset(a.kv, b, hk, t + j * parts) + c8 * 8);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) s_tile[tr][c8 * 8 + e] = kr[e];
-        }
-        __syncthreads();
-        for (int i = tid; i < D * 8; i += 256) {
-            const int d = i / 8, t8 = i % 8;
-            half8_t v;
+        for (int j = 0; j < 4; ++j)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] = s_tile[t8 * 8 + e][d];
-            if (t0 + t8 * 8 < L)
-                *(half8_t*)(kt_col0(a.aux, b, hk, t0 + t8 * 8) + (int64_t)d * a.aux.stride_d) = v;
-        }
-        __syncthreads();
+            for (int e = 0; e < 8; ++e) vs[e] += (float)vr[j][e];
     }
-    // 256 / cols8 threads hold partial sums of the same 8 columns: add them in a fixed order
-    const int part = tid / cols8;
+    for (; t < L; t += parts) {
+        const half8_t vr = *(const half8_t*)(a.kv.v + row_offset(a.kv, b, hk, t) + c8 * 8);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) s_sum[part][c8 * 8 + e] = vs[e];
+        for (int e = 0; e < 8; ++e) vs[e] += (float)vr[e];
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) s_sum[part * D + c8 * 8 + e] = vs[e];
     __syncthreads();
     if (tid < D) {
         float s = 0.f;
-        for (int p = 0; p < 256 / cols8; ++p) s += s_sum[p][tid];
+        for (int p = 0; p < parts; ++p) s += s_sum[p * D + tid];
         a.aux.vsum[((int64_t)b * a.num_kv_heads + hk) * D + tid] = s;
     }
 }
@@ -1094,7 +1129,12 @@ __global__ __launch_bounds__(256) void sparf_append_kernel(SparfArgs a)
 // ---------------------------------------------------------------------------
 hipError_t launch_sparf_build(const SparfArgs& a, hipStream_t stream)
 {
-    hipLaunchKernelGGL(sparf_build_kernel, dim3(a.num_kv_heads, a.batch), dim3(256), 0, stream, a);
+    const int rows = a.kv.capacity < a.aux.capacity ? a.kv.capacity : a.aux.capacity;
+    dim3 grid(a.num_kv_heads, (rows + kBuildRows - 1) / kBuildRows, a.batch);
+    if (a.head_dim == 128) hipLaunchKernelGGL(sparf_build_kernel<128>, grid, dim3(256), 0, stream, a);
+    else hipLaunchKernelGGL(sparf_build_kernel<64>, grid, dim3(256), 0, stream, a);
+    if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
+    hipLaunchKernelGGL(sparf_vsum_kernel, dim3(a.num_kv_heads, a.batch), dim3(1024), 0, stream, a);
     return hipGetLastError();
 }
 
