@@ -14,7 +14,7 @@ namespace {
 size_t up256(size_t x) { return (x + 255) / 256 * 256; }
 
 struct Carve {
-    size_t logits, stats, sel, alpha, part, total;
+    size_t logits, stats, sel, alpha, part, hist, gt1, counters, state, members, mass_part, total;
     int lpad, nchunk;
 };
 
@@ -29,7 +29,15 @@ Carve carve(int batch, int num_q_heads, int head_dim, int max_seq_len, int k)
     c.sel = c.stats + up256(rows * c.nchunk * 3 * sizeof(float));
     c.alpha = c.sel + up256(rows * (size_t)k * sizeof(int32_t));
     c.part = c.alpha + up256(rows * sizeof(float));
-    c.total = c.part + up256(rows * kSparfMaxSlices * (size_t)(head_dim + 2) * sizeof(float));
+    c.hist = c.part + up256(rows * kSparfMaxSlices * (size_t)(head_dim + 2) * sizeof(float));
+    // the distributed selection's state exists only where long rows can take it
+    const size_t lr = max_seq_len > kSparfFusedMaxLen ? rows : 0;
+    c.gt1 = c.hist + up256(lr * c.nchunk * 256 * sizeof(uint32_t));
+    c.counters = c.gt1 + up256(lr * c.nchunk * sizeof(uint32_t));
+    c.state = c.counters + up256(lr * 2 * sizeof(uint32_t));
+    c.members = c.state + up256(lr * 2 * sizeof(uint32_t));
+    c.mass_part = c.members + up256(lr * kSparfMemberCap * 2 * sizeof(uint32_t));
+    c.total = c.mass_part + up256(lr * c.nchunk * sizeof(float));
     return c;
 }
 
@@ -167,6 +175,18 @@ int run_sparf_decode(const void* q, const void* k_new, const void* v_new, bool a
     a.sel = sel_rows ? sel_rows : (int32_t*)(ws + c.sel);
     a.alpha = alpha ? alpha : (float*)(ws + c.alpha);
     a.part = (float*)(ws + c.part);
+    a.hist = (uint32_t*)(ws + c.hist);
+    a.gt1 = (uint32_t*)(ws + c.gt1);
+    a.counters = (uint32_t*)(ws + c.counters);
+    a.state = (uint32_t*)(ws + c.state);
+    a.members = (uint32_t*)(ws + c.members);
+    a.mass_part = (float*)(ws + c.mass_part);
+    // One block per head selects well when there are heads enough to fill the chip;
+    // few heads with long rows spread each head's selection over its stretches.
+    {
+        const char* e = getenv("INSTATTN_SPARF_DISTRIBUTED");
+        a.distributed = e ? (e[0] == '1') : ((int64_t)batch * num_q_heads <= 512 && max_seq_len > 2 * kSparfChunk);
+    }
     // Slices of a head's kept rows for the attend kernel: enough blocks to fill the
     // chip when there are few heads, none smaller than 256 rows.
     {

@@ -8,6 +8,7 @@ namespace instattn {
 constexpr int kSparfChunk = 8192;      // positions per block of the approximate-score pass
 constexpr int kSparfSelectThreads = 1024;
 constexpr int kSparfAttendWaves = 8;
+constexpr int kSparfMemberCap = 1024;  // members of the threshold bin the distributed selection ranks directly
 constexpr int kSparfMaxSlices = 8;      // most slices the attend kernel cuts a head's kept rows into
 constexpr int kSparfAttendIds = 4096;   // kept rows staged in LDS at a time by the attend kernel
 
@@ -47,6 +48,14 @@ struct SparfArgs {
     float* alpha;                      // [B][Hq] selected share of the approximate softmax
     float* part;                       // [B][Hq][nslices][D + 2] shares of the attend kernel's slices
     int32_t nslices, slice_rows;       // slices per head and kept rows per slice (multiple of 16)
+    // selection of a head spread over one block per stretch (few heads, long rows)
+    int32_t distributed;
+    uint32_t* hist;                    // [B][Hq][nchunk][256] level-1 histogram of every stretch
+    uint32_t* gt1;                     // [B][Hq][nchunk] scores of the stretch in bins above the threshold bin
+    uint32_t* counters;                // [B][Hq][2]: members gathered, stretches compacted
+    uint32_t* state;                   // [B][Hq][2]: threshold bin, rows still wanted inside it
+    uint32_t* members;                 // [B][Hq][kSparfMemberCap][2]: key and stretch of the bin's members
+    float* mass_part;                  // [B][Hq][nchunk] softmax mass kept per stretch
     void* out;
     int32_t out_f32;
     const half_t* k_new;               // append, or decode with the append fused in

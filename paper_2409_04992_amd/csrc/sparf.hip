@@ -861,6 +861,28 @@ __global__ __launch_bounds__(256, INSTATTN_SPARF_WAVES_PER_SIMD) void sparf_logi
     }
 }
 
+// Maximum, minimum and sum of 2^(x - maximum) of a row from those of its stretches:
+// lane c takes stretch c, every wave (and every block) gets the same values.
+__device__ __forceinline__ void row_stats(const SparfArgs& a, int64_t row, int L, float& M, float& xmin, float& Z)
+{
+    const int nc = (L + kSparfChunk - 1) / kSparfChunk;
+    const float* st = a.stats + row * a.nchunk * 3;
+    const int lane = threadIdx.x & 63;
+    M = kNegBig;
+    xmin = -kNegBig;
+    Z = 0.f;
+    for (int c0 = 0; c0 < nc; c0 += 64) {
+        const bool in = c0 + lane < nc;
+        const float mc = in ? st[3 * (c0 + lane)] : kNegBig;
+        const float zc = in ? st[3 * (c0 + lane) + 1] : 0.f;
+        const float nc_min = in ? st[3 * (c0 + lane) + 2] : -kNegBig;
+        const float Mn = fmaxf(M, wave_max(mc));
+        Z = Z * fast_exp2(M - Mn) + wave_sum(zc * fast_exp2(mc - Mn));
+        M = Mn;
+        xmin = fminf(xmin, -wave_max(-nc_min));
+    }
+}
+
 // Steps 4 (normaliser) to 7, long rows: one block per head over the stored scores.
 // STEPS > 0: the row has at most NT * 8 * STEPS positions, every thread reads its
 // scores once and keeps them in registers; STEPS == 0: the selection passes over
@@ -879,26 +901,227 @@ __global__ __launch_bounds__(NT) void sparf_select_kernel(SparfArgs a)
     const float* x = a.logits + row * a.lpad;
     float xr[STEPS > 0 ? STEPS : 1][8];
     if constexpr (STEPS > 0) own_scores<NT, STEPS>(x, L, xr);   // in flight while the statistics are combined
-    // max / sum / min of the row from those of its stretches: lane c takes stretch c,
-    // every wave gets the same values
-    const int nc = (L + kSparfChunk - 1) / kSparfChunk;
-    const float* st = a.stats + row * a.nchunk * 3;
-    const int lane = threadIdx.x & 63;
-    float M = kNegBig, xmin = -kNegBig, Z = 0.f;
-    for (int c0 = 0; c0 < nc; c0 += 64) {
-        const bool in = c0 + lane < nc;
-        const float mc = in ? st[3 * (c0 + lane)] : kNegBig;
-        const float zc = in ? st[3 * (c0 + lane) + 1] : 0.f;
-        const float nc_min = in ? st[3 * (c0 + lane) + 2] : -kNegBig;
-        const float Mn = fmaxf(M, wave_max(mc));
-        Z = Z * fast_exp2(M - Mn) + wave_sum(zc * fast_exp2(mc - Mn));
-        M = Mn;
-        xmin = fminf(xmin, -wave_max(-nc_min));
-    }
+    float M, xmin, Z;
+    row_stats(a, row, L, M, xmin, Z);
     float alpha;
     if constexpr (STEPS > 0) alpha = select_rows_reg<NT, STEPS>(xr, x, L, a.k, a.l, M, xmin, Z, a.sel + row * a.k, S);
     else alpha = select_rows<NT>(x, L, a.k, a.l, M, xmin, Z, a.sel + row * a.k, S);
     if (threadIdx.x == 0) a.alpha[row] = alpha;
+}
+
+// ---------------------------------------------------------------------------
+// Steps 4 (normaliser) to 7 for few heads with long rows: the selection of a head
+// is spread over one block of 256 threads per stretch of 8192 scores (held in
+// registers), in three launches that pass small integers through the workspace:
+//   sparf_hist_kernel     level-1 histogram of every stretch;
+//   sparf_members_kernel  every block adds the histograms up and finds the threshold
+//                         bin (same result in all of them), then gathers its members
+//                         of that bin into the head's list and counts its scores in
+//                         higher bins;
+//   sparf_compact_kernel  every block ranks the members (same threshold key in all
+//                         of them), derives how many kept rows lie in front of its
+//                         stretch, compacts it and leaves its share of the kept
+//                         softmax mass; the block that finishes last adds the shares
+//                         up in stretch order and writes alpha.
+// The kept rows are those of the one-block selection.  If the threshold bin holds
+// more than kSparfMemberCap scores (many equal scores), the block of stretch 0 runs
+// the one-block selection over the whole row instead.
+struct StretchView {
+    int L, want, leff, ncand, t0, ncc;     // ncc: stretches that hold candidates
+};
+
+__device__ __forceinline__ StretchView stretch_view(const SparfArgs& a, int b, int chunk)
+{
+    StretchView v;
+    v.L = clamp_len(a.seq_lens[b], a.max_len);
+    const int keff = min(a.k, v.L);
+    v.leff = min(a.l, keff);
+    v.want = keff - v.leff;
+    v.ncand = v.L - v.leff;
+    v.t0 = chunk * kSparfChunk;
+    v.ncc = (v.ncand + kSparfChunk - 1) / kSparfChunk;
+    return v;
+}
+
+__global__ __launch_bounds__(256) void sparf_hist_kernel(SparfArgs a)
+{
+    constexpr int NT = 256, STEPS = kSparfChunk / (NT * 8);
+    const int h = blockIdx.x, chunk = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
+    const int64_t row = (int64_t)b * a.num_q_heads + h;
+    const StretchView v = stretch_view(a, b, chunk);
+    if (chunk == 0 && tid < 2) a.counters[row * 2 + tid] = 0;
+    if (v.want <= 0 || v.t0 >= v.ncand) return;
+    float xr[STEPS][8];
+    own_scores<NT, STEPS>(a.logits + row * a.lpad + v.t0, v.ncand - v.t0, xr);
+    float M, xmin, Z;
+    row_stats(a, row, v.L, M, xmin, Z);
+    const Level1 level1(M, xmin);
+    __shared__ uint32_t s_hist[256];
+    s_hist[tid] = 0;
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < STEPS; ++i)
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            if (v.t0 + (i * NT + tid) * 8 + e < v.ncand) atomicAdd(&s_hist[level1(xr[i][e])], 1u);
+    __syncthreads();
+    a.hist[(row * a.nchunk + chunk) * 256 + tid] = s_hist[tid];
+}
+
+__global__ __launch_bounds__(256) void sparf_members_kernel(SparfArgs a)
+{
+    constexpr int NT = 256, STEPS = kSparfChunk / (NT * 8);
+    const int h = blockIdx.x, chunk = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
+    const int64_t row = (int64_t)b * a.num_q_heads + h;
+    const StretchView v = stretch_view(a, b, chunk);
+    if (v.want <= 0 || v.t0 >= v.ncand) return;
+    float xr[STEPS][8];
+    own_scores<NT, STEPS>(a.logits + row * a.lpad + v.t0, v.ncand - v.t0, xr);
+    float M, xmin, Z;
+    row_stats(a, row, v.L, M, xmin, Z);
+    const Level1 level1(M, xmin);
+
+    __shared__ SelectScratch S;
+    __shared__ uint32_t s_keys[kSparfMemberCap];
+    __shared__ uint32_t s_n, s_above, s_base;
+    uint32_t total = 0;
+    for (int c = 0; c < v.ncc; ++c) total += a.hist[(row * a.nchunk + c) * 256 + tid];
+    S.hist[tid] = total;
+    if (tid == 0) s_n = s_above = 0;
+    __syncthreads();
+    if (tid < 64) locate_bin(S, (uint32_t)v.want, tid);
+    __syncthreads();
+    const uint32_t bin1 = S.prefix;
+    if (chunk == 0 && tid == 0) {
+        a.state[row * 2] = bin1;
+        a.state[row * 2 + 1] = S.remaining;
+    }
+    uint32_t above = 0;
+#pragma unroll
+    for (int i = 0; i < STEPS; ++i)
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            if (v.t0 + (i * NT + tid) * 8 + e < v.ncand) {
+                const uint32_t bin = level1(xr[i][e]);
+                above += bin > bin1;
+                if (bin == bin1) {
+                    const uint32_t j = atomicAdd(&s_n, 1u);
+                    if (j < (uint32_t)kSparfMemberCap) s_keys[j] = order_key(xr[i][e]);
+                }
+            }
+    if (above) atomicAdd(&s_above, above);
+    __syncthreads();
+    const uint32_t n = s_n;
+    if (tid == 0) {
+        a.gt1[row * a.nchunk + chunk] = s_above;
+        s_base = atomicAdd(&a.counters[row * 2], n);       // more than the cap in all: the list is not used
+    }
+    __syncthreads();
+    const uint32_t base = s_base;
+    for (uint32_t j = tid; j < n && j < (uint32_t)kSparfMemberCap; j += NT) {
+        if (base + j < (uint32_t)kSparfMemberCap) {
+            uint32_t* m = a.members + (row * kSparfMemberCap + base + j) * 2;
+            m[0] = s_keys[j];
+            m[1] = (uint32_t)chunk;
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void sparf_compact_kernel(SparfArgs a)
+{
+    constexpr int NT = 256, STEPS = kSparfChunk / (NT * 8);
+    const int h = blockIdx.x, chunk = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
+    const int64_t row = (int64_t)b * a.num_q_heads + h;
+    const StretchView v = stretch_view(a, b, chunk);
+    if (v.L == 0) {
+        if (chunk == 0 && tid == 0) a.alpha[row] = 0.f;
+        return;
+    }
+    __shared__ SelectScratch S;
+    const float* x = a.logits + row * a.lpad;
+    int32_t* sel = a.sel + row * a.k;
+    float M, xmin, Z;
+    row_stats(a, row, v.L, M, xmin, Z);
+    const uint32_t nmem = v.want > 0 ? a.counters[row * 2] : 0u;
+    if (v.want <= 0 || nmem > (uint32_t)kSparfMemberCap) {
+        // nothing to pick among the candidates, or too many scores in the threshold bin:
+        // the block of stretch 0 does the whole row the one-block way
+        if (chunk == 0) {
+            const float alpha = select_rows<NT>(x, v.L, a.k, a.l, M, xmin, Z, sel, S);
+            if (tid == 0) a.alpha[row] = alpha;
+        }
+        return;
+    }
+    if (v.t0 >= v.ncand) return;
+    float xr[STEPS][8];
+    own_scores<NT, STEPS>(x + v.t0, v.ncand - v.t0, xr);
+    const Level1 level1(M, xmin);
+    const uint32_t bin1 = a.state[row * 2], rem1 = a.state[row * 2 + 1];
+
+    // the members of the threshold bin: rank them against each other (the threshold key
+    // has fewer than rem1 keys above it and at least rem1 at or above)
+    __shared__ uint32_t s_mkey[kSparfMemberCap];
+    __shared__ uint16_t s_mchunk[kSparfMemberCap];
+    __shared__ uint32_t s_gtb, s_eqb;
+    for (uint32_t i = tid; i < nmem; i += NT) {
+        const uint32_t* m = a.members + (row * kSparfMemberCap + i) * 2;
+        s_mkey[i] = m[0];
+        s_mchunk[i] = (uint16_t)m[1];
+    }
+    if (tid == 0) s_gtb = s_eqb = 0;
+    __syncthreads();
+    for (uint32_t i = tid; i < nmem; i += NT) {
+        const uint32_t mine = s_mkey[i];
+        uint32_t gt = 0, ge = 0;
+        for (uint32_t j = 0; j < nmem; ++j) {
+            const uint32_t o = s_mkey[j];
+            gt += o > mine;
+            ge += o >= mine;
+        }
+        if (gt < rem1 && rem1 <= ge) {                  // same values from every such member
+            S.prefix = mine;
+            S.remaining = rem1 - gt;
+        }
+    }
+    __syncthreads();
+    const uint32_t thr = S.prefix, rem_eq = S.remaining;
+    // kept rows in front of this stretch: scores in higher bins and members above the
+    // threshold key of earlier stretches; rows at the threshold key likewise
+    for (uint32_t i = tid; i < nmem; i += NT) {
+        if ((int)s_mchunk[i] < chunk) {
+            if (s_mkey[i] > thr) atomicAdd(&s_gtb, 1u);
+            else if (s_mkey[i] == thr) atomicAdd(&s_eqb, 1u);
+        }
+    }
+    __syncthreads();
+    uint32_t gt_base = s_gtb, eq_base = s_eqb;
+    for (int c = 0; c < chunk; ++c) gt_base += a.gt1[row * a.nchunk + c];
+
+    float mass = 0.f;
+    compact_tile<NT, STEPS>(
+        xr, [&](int i, int e) { return level1(xr[i][e]); }, v.t0, v.ncand, bin1, thr, rem_eq, gt_base, eq_base,
+        &S.wave_cnt[0][0], x, M, sel, mass);
+    if (chunk == 0) {
+        // step 5: the l most recent positions are always kept
+        for (int i = tid; i < v.leff; i += NT) {
+            const int t = v.ncand + i;
+            sel[v.want + i] = t;
+            mass += fast_exp2(x[t] - M);
+        }
+    }
+    mass = block_sum(mass, S.red);
+    if (tid == 0) {
+        // step 7: the block that finishes last adds the shares up in stretch order
+        a.mass_part[row * a.nchunk + chunk] = mass;
+        __threadfence();
+        if (atomicAdd(&a.counters[row * 2 + 1], 1u) == (uint32_t)v.ncc - 1u) {
+            __threadfence();
+            float kept = 0.f;
+            for (int c = 0; c < v.ncc; ++c)
+                kept += __hip_atomic_load(&a.mass_part[row * a.nchunk + c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            a.alpha[row] = kept / Z;
+        }
+    }
 }
 
 // Steps 10-11, long rows: one block per query head and slice of its kept rows.
@@ -1153,6 +1376,13 @@ hipError_t launch_sparf_logits(const SparfArgs& a, hipStream_t stream)
 
 hipError_t launch_sparf_select(const SparfArgs& a, hipStream_t stream)
 {
+    if (a.distributed) {
+        dim3 dgrid(a.num_q_heads, a.nchunk, a.batch);
+        hipLaunchKernelGGL(sparf_hist_kernel, dgrid, dim3(256), 0, stream, a);
+        hipLaunchKernelGGL(sparf_members_kernel, dgrid, dim3(256), 0, stream, a);
+        hipLaunchKernelGGL(sparf_compact_kernel, dgrid, dim3(256), 0, stream, a);
+        return hipGetLastError();
+    }
     dim3 grid(a.num_q_heads, a.batch);
     // Smallest block whose threads hold the row in registers, 32 or 40 scores each
     // (sequence lengths like to sit just behind a power of two), 64 as the last

@@ -248,12 +248,65 @@ def test_sparf_append_decode_equals_the_two_calls():
 
 @pytest.mark.parametrize("seq_len,k", [(20000, 1300), (8192, 100), (32767, 3000), (32768, 600), (40000, 2500),
                                        (65534, 700), (70000, 4400), (9000, 20000)])
-def test_sparf_long_rows_take_the_three_launch_pipeline(seq_len, k):
-    """Rows behind the one-launch limit: the selection keeps the scores in registers up
-    to 32768 and up to 65535 positions and passes over the workspace beyond; the
-    attend kernel cuts the kept rows of a head into up to 8 slices."""
+@pytest.mark.parametrize("distributed", ["0", "1"])
+def test_sparf_long_rows_take_the_three_launch_pipeline(monkeypatch, seq_len, k, distributed):
+    """Rows behind the one-launch limit.  One block per head: the selection keeps the
+    scores in registers up to 32768 and up to 65535 positions and passes over the
+    workspace beyond.  Distributed: one block per stretch of 8192 scores, three
+    launches.  The attend kernel cuts the kept rows of a head into up to 8 slices."""
+    monkeypatch.setenv("INSTATTN_SPARF_DISTRIBUTED", distributed)
     wl = W.Workload("sparf_long", 1, 2, 2, 128, seq_len, seed=408)
     sparf_step(wl, 16, k, 32, torch.float16)
+
+
+def test_sparf_distributed_selection_equals_one_block_per_head(monkeypatch):
+    """Same kept rows bit for bit, alpha and out up to the order of the mass sum; ragged
+    lengths so that heads use different numbers of stretches; repeated (the gathered
+    members arrive in any order)."""
+    wl = W.Workload("sparf_dist", 3, 4, 2, 128, 40000, seq_len_min=8300, paged=True, page_size=16, seed=414)
+    case, desc, aux, kt, vsum, _ = setup(wl, kt_page=256)
+    B.sparf_append(desc, aux, case.k_new, case.v_new, case.seq_lens)
+    monkeypatch.setenv("INSTATTN_SPARF_DISTRIBUTED", "0")
+    ref = run_decode(case, desc, aux, 16, 3000, 16, torch.float32)
+    monkeypatch.setenv("INSTATTN_SPARF_DISTRIBUTED", "1")
+    first = None
+    for rep in range(3):
+        got = run_decode(case, desc, aux, 16, 3000, 16, torch.float32)
+        assert torch.equal(got[1], ref[1])
+        assert (got[0] - ref[0]).abs().max() <= 2e-6 and (got[2] - ref[2]).abs().max() <= 1e-6
+        first = first or got
+        assert all(torch.equal(x, y) for x, y in zip(got, first))       # deterministic
+
+
+@pytest.mark.parametrize("distributed", ["0", "1"])
+def test_sparf_long_rows_of_equal_scores(monkeypatch, distributed):
+    """Identical keys on a long row: every score ties, the threshold bin holds the whole
+    row (more than the distributed selection ranks directly: it falls back to the block
+    of stretch 0).  Kept: the first k - l and the last l positions."""
+    monkeypatch.setenv("INSTATTN_SPARF_DISTRIBUTED", distributed)
+    wl = W.Workload("sparf_long_ties", 1, 2, 2, 128, 19999, seed=415)
+    case, desc, aux, kt, vsum, _ = setup(wl)
+    case.k_cache[:] = case.k_cache[:, :, :1]
+    case.k_new[:] = case.k_cache[:, :, 0]
+    B.sparf_build(desc, aux, (case.seq_lens - 1).contiguous(), 2, 128)
+    B.sparf_append(desc, aux, case.k_new, case.v_new, case.seq_lens)
+    out, sel, alpha = run_decode(case, desc, aux, 16, 1000, 10, torch.float32)
+    want = torch.cat([torch.arange(990), torch.arange(19990, 20000)]).to(torch.int32)
+    assert torch.equal(sel[0, 0].cpu(), want) and torch.equal(sel[0, 1].cpu(), want)
+    assert (alpha - 1000 / 20000).abs().max() < 1e-6
+
+
+def test_sparf_distributed_edge_lengths(monkeypatch):
+    """Lengths around the stretch edges, k below l, k above the length, an empty row."""
+    monkeypatch.setenv("INSTATTN_SPARF_DISTRIBUTED", "1")
+    wl = W.Workload("sparf_dist_edges", 6, 2, 2, 64, 16500, seed=416)
+    case, desc, aux, kt, vsum, _ = setup(wl)
+    case.seq_lens = torch.tensor([8193, 16384, 16385, 0, 9000, 16500], dtype=torch.int32, device=DEV)
+    B.sparf_build(desc, aux, (case.seq_lens - 1).clamp(min=0).contiguous(), 2, 64)
+    B.sparf_append(desc, aux, case.k_new, case.v_new, case.seq_lens)
+    for k, l in [(300, 8), (5, 9), (20000, 3), (8200, 0)]:
+        out, sel, alpha = run_decode(case, desc, aux, 8, k, l, torch.float32, max_len=16500)
+        check_against_oracle(case, out, sel, alpha, 8, k, l)
 
 
 def test_sparf_long_rows_many_heads_no_slices():
