@@ -181,11 +181,16 @@ int run_sparf_decode(const void* q, const void* k_new, const void* v_new, bool a
     a.state = (uint32_t*)(ws + c.state);
     a.members = (uint32_t*)(ws + c.members);
     a.mass_part = (float*)(ws + c.mass_part);
-    // One block per head selects well when there are heads enough to fill the chip;
-    // few heads with long rows spread each head's selection over its stretches.
+    // One block per head selects well when there are heads enough to fill the chip or
+    // the rows are short; few heads with long rows spread each head's selection over
+    // its stretches (three launches).  Measured: one block takes about max_len / 1100
+    // us per round of 256 heads, the distributed form 24 us + 0.015 us per block.
     {
+        const int64_t heads = (int64_t)batch * num_q_heads;
+        const double one_block = max_seq_len / 1100.0 * (double)((heads + 255) / 256);
+        const double spread = 24.0 + 0.015 * (double)heads * c.nchunk;
         const char* e = getenv("INSTATTN_SPARF_DISTRIBUTED");
-        a.distributed = e ? (e[0] == '1') : ((int64_t)batch * num_q_heads <= 512 && max_seq_len > 2 * kSparfChunk);
+        a.distributed = e ? (e[0] == '1') : (max_seq_len > 2 * kSparfChunk && heads <= 512 && spread < one_block);
     }
     // Slices of a head's kept rows for the attend kernel: enough blocks to fill the
     // chip when there are few heads, none smaller than 256 rows.

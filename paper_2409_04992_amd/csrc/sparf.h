@@ -52,7 +52,7 @@ struct SparfArgs {
     int32_t distributed;
     uint32_t* hist;                    // [B][Hq][nchunk][256] level-1 histogram of every stretch
     uint32_t* gt1;                     // [B][Hq][nchunk] scores of the stretch in bins above the threshold bin
-    uint32_t* counters;                // [B][Hq][2]: members gathered, stretches compacted
+    uint32_t* counters;                // [B][Hq][2]: members gathered, spare
     uint32_t* state;                   // [B][Hq][2]: threshold bin, rows still wanted inside it
     uint32_t* members;                 // [B][Hq][kSparfMemberCap][2]: key and stretch of the bin's members
     float* mass_part;                  // [B][Hq][nchunk] softmax mass kept per stretch

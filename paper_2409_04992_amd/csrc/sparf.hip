@@ -17,6 +17,9 @@
 //                         exact two-level selection over the scores (held in
 //                         registers for rows up to 32768), ordered compaction
 //                         (ties towards the lower position), alpha.
+//   sparf_hist_kernel,    the same selection for few heads with long rows, one block
+//   sparf_members_kernel, per stretch of 8192 scores in three launches (described
+//   sparf_compact_kernel  with the kernels).
 //   sparf_attend_kernel   steps 10-11: one block per query head (or per slice of its
 //                         kept rows, then sparf_merge_kernel combines the slices)
 //                         gathers the selected rows of K and V (online softmax as in
@@ -220,8 +223,9 @@ constexpr int kSelMembers = 512;     // members of the threshold bin ranked dire
 
 struct SelectScratch {
     uint32_t hist[256];
-    uint32_t prefix, remaining, nmem;
-    uint32_t mem_key[kSelMembers];
+    uint32_t prefix, remaining, nmem, nsub;
+    alignas(16) uint32_t mem_key[kSelMembers];
+    alignas(16) uint32_t mem_key2[kSelMembers];
     uint32_t wave_cnt[8][16];        // per round parity (or step) and wave: rows above the threshold | rows at it << 16
     float red[48];
 };
@@ -363,7 +367,83 @@ struct Level1 {
     __device__ __forceinline__ uint32_t operator()(float v) const {
         return 255u - (uint32_t)min(255, max(0, (int)((M - v) * binscale)));
     }
+    // 256 finer buckets inside a level-1 bucket, monotone in the score like the bucket
+    __device__ __forceinline__ uint32_t sub(float v) const {
+        const float t = (M - v) * binscale;
+        const float f = t - (float)min(255, max(0, (int)t));
+        return 255u - (uint32_t)min(255, max(0, (int)(f * 256.f)));
+    }
 };
+
+// Inverse of order_key.
+__device__ __forceinline__ float key_score(uint32_t key) {
+    return __builtin_bit_cast(float, (key & 0x80000000u) ? (key & 0x7FFFFFFFu) : ~key);
+}
+
+// Ranks the n keys at `keys` (LDS, 16-byte aligned, room for n rounded up to 4)
+// against each other: the threshold key is the one with fewer than `remaining` keys
+// above it and at least `remaining` at or above.  The tail of the last vector must
+// hold 0, a key no finite score has.  Leaves the key in S.prefix and the number of
+// rows with exactly that key still wanted in S.remaining.
+template <int NT>
+__device__ __forceinline__ void rank_directly(const uint32_t* keys, uint32_t n, uint32_t remaining,
+                                              SelectScratch& S)
+{
+    const int tid = threadIdx.x;
+    const u32x4* k4 = (const u32x4*)keys;
+    const uint32_t n4 = (n + 3) / 4;
+    for (uint32_t i = tid; i < n; i += NT) {
+        const uint32_t mine = keys[i];
+        uint32_t gt = 0, ge = 0;
+#pragma unroll 4
+        for (uint32_t j = 0; j < n4; ++j) {
+            const u32x4 o = k4[j];
+            gt += (uint32_t)(o.x > mine) + (uint32_t)(o.y > mine) + (uint32_t)(o.z > mine) + (uint32_t)(o.w > mine);
+            ge += (uint32_t)(o.x >= mine) + (uint32_t)(o.y >= mine) + (uint32_t)(o.z >= mine) + (uint32_t)(o.w >= mine);
+        }
+        if (gt < remaining && remaining <= ge) {         // same values from every such member
+            S.prefix = mine;
+            S.remaining = remaining - gt;
+        }
+    }
+}
+
+// The threshold key among the n members of the threshold bin (keys, n <= cap; keys2:
+// scratch of the same size; both 16-byte aligned LDS).  A handful is ranked
+// directly; more go through 256 finer buckets first (linear in n instead of
+// quadratic: the members of a long row's bin run into the hundreds) and only the
+// members of the one finer bucket that holds the threshold are ranked.  Called by
+// the whole block, synchronised on entry; the results are in S.prefix and
+// S.remaining after the caller's next barrier.
+template <int NT>
+__device__ __forceinline__ void rank_members(uint32_t* keys, uint32_t* keys2, uint32_t n, uint32_t cap,
+                                             uint32_t remaining, const Level1& level1, SelectScratch& S)
+{
+    const int tid = threadIdx.x;
+    if (n <= 64u) {
+        if (tid < 3 && n + tid < cap) keys[n + tid] = 0;
+        __syncthreads();
+        rank_directly<NT>(keys, n, remaining, S);
+        return;
+    }
+    if (tid < 256) S.hist[tid] = 0;
+    if (tid == 0) S.nsub = 0;
+    __syncthreads();
+    for (uint32_t i = tid; i < n; i += NT) atomicAdd(&S.hist[level1.sub(key_score(keys[i]))], 1u);
+    __syncthreads();
+    if (tid < 64) locate_bin(S, remaining, tid);
+    __syncthreads();
+    const uint32_t bucket = S.prefix, rem2 = S.remaining;
+    for (uint32_t i = tid; i < n; i += NT) {
+        const uint32_t key = keys[i];
+        if (level1.sub(key_score(key)) == bucket) keys2[atomicAdd(&S.nsub, 1u)] = key;
+    }
+    __syncthreads();                                   // also: everyone has read bucket and rem2
+    const uint32_t m = S.nsub;
+    if (tid < 3 && m + tid < cap) keys2[m + tid] = 0;
+    __syncthreads();
+    rank_directly<NT>(keys2, m, rem2, S);
+}
 
 // The threshold of the top-`want` candidates, exactly, in two levels.  Level 1
 // buckets the scores into 256 bins (scores spread evenly over these, unlike over
@@ -376,7 +456,8 @@ struct Level1 {
 // for_each(f) calls f(score, its level-1 bin) for every candidate of the calling
 // thread; it is called several times and must visit the same candidates each time.
 template <int NT, class ForEach>
-__device__ __forceinline__ void find_threshold(ForEach&& for_each, int want, SelectScratch& S, uint32_t& bin1, uint32_t& prefix,
+__device__ __forceinline__ void find_threshold(ForEach&& for_each, int want, const Level1& level1,
+                                               SelectScratch& S, uint32_t& bin1, uint32_t& prefix,
                                                uint32_t& remaining)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -405,21 +486,7 @@ __device__ __forceinline__ void find_threshold(ForEach&& for_each, int want, Sel
     __syncthreads();
     const uint32_t nmem = S.nmem;
     if (nmem <= (uint32_t)kSelMembers) {
-        // rank every member against the others: the threshold key is the one with
-        // fewer than `remaining` keys above it and at least `remaining` at or above
-        for (uint32_t i = tid; i < nmem; i += NT) {
-            const uint32_t mine = S.mem_key[i];
-            uint32_t gt = 0, ge = 0;
-            for (uint32_t j = 0; j < nmem; ++j) {
-                const uint32_t o = S.mem_key[j];
-                gt += o > mine;
-                ge += o >= mine;
-            }
-            if (gt < remaining && remaining <= ge) {     // same values from every such member
-                S.prefix = mine;
-                S.remaining = remaining - gt;
-            }
-        }
+        rank_members<NT>(S.mem_key, S.mem_key2, nmem, (uint32_t)kSelMembers, remaining, level1, S);
         __syncthreads();
         prefix = S.prefix;
         remaining = S.remaining;
@@ -457,11 +524,13 @@ template <int NT, int STEPS, class BinOf>
 __device__ __forceinline__ void compact_tile(const float (&xr)[STEPS][8], BinOf&& bin_of, int t_off, int ncand,
                                              uint32_t bin1, uint32_t prefix, uint32_t remaining,
                                              uint32_t& gt_base, uint32_t& eq_base, uint32_t* step_cnt,
-                                             const float* x, float M, int32_t* sel, float& mass)
+                                             float M, int32_t* sel, float& mass)
 {
     constexpr int NW = NT / 64;
     typedef typename std::conditional<(STEPS > 4), uint64_t, uint32_t>::type bits_t;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // the score whose key is the threshold key (inverse of order_key)
+    const float mass_at_key = fast_exp2(key_score(prefix) - M);
     bits_t gtbits = 0, eqbits = 0;                         // bit 8i + e
     uint32_t excl[STEPS];                                  // kept before this lane in its wave, per step
 #pragma unroll
@@ -478,6 +547,7 @@ __device__ __forceinline__ void compact_tile(const float (&xr)[STEPS][8], BinOf&
                 gtbits |= (bits_t)gt << (8 * i + e);
                 eqbits |= (bits_t)eq << (8 * i + e);
                 c += (uint32_t)gt + ((uint32_t)eq << 16);
+                if (gt) mass += fast_exp2(xr[i][e] - M);   // here, where the score is at hand in a register
             }
         }
         uint32_t incl = c;                                 // 16-bit halves: at most 512 each
@@ -508,10 +578,10 @@ __device__ __forceinline__ void compact_tile(const float (&xr)[STEPS][8], BinOf&
             todo &= todo - 1;
             const uint32_t below = (1u << e) - 1u;
             const uint32_t eq_before = eb + (uint32_t)__popc(e8 & below);
-            if (((g8 >> e) & 1u) || eq_before < remaining) {
-                const int t = t_off + (i * NT + tid) * 8 + e;
-                sel[gb + (uint32_t)__popc(g8 & below) + min(eq_before, remaining)] = t;
-                mass += fast_exp2(x[t] - M);
+            const bool above = (g8 >> e) & 1u;
+            if (above || eq_before < remaining) {
+                sel[gb + (uint32_t)__popc(g8 & below) + min(eq_before, remaining)] = t_off + (i * NT + tid) * 8 + e;
+                if (!above) mass += mass_at_key;           // rows at the threshold key share one score
             }
         }
     }
@@ -550,7 +620,7 @@ __device__ __forceinline__ float select_rows(const float* x, int L, int k, int l
                         if (t_off + (i * NT + tid) * 8 + e < ncand) f(xr[i][e], level1(xr[i][e]));
             }
         },
-        want, S, bin1, prefix, remaining);
+        want, level1, S, bin1, prefix, remaining);
 
     float mass = 0.f;
     uint32_t gt_base = 0, eq_base = 0;
@@ -560,7 +630,7 @@ __device__ __forceinline__ float select_rows(const float* x, int L, int k, int l
         own_scores<NT, STEPS>(x + t_off, ncand - t_off, xr);
         compact_tile<NT, STEPS>(
             xr, [&](int i, int e) { return level1(xr[i][e]); }, t_off, ncand, bin1, prefix, remaining, gt_base,
-            eq_base, &S.wave_cnt[parity * 4][0], x, M, sel, mass);
+            eq_base, &S.wave_cnt[parity * 4][0], M, sel, mass);
     }
     // step 5: the l most recent positions are always kept
     for (int i = tid; i < leff; i += NT) {
@@ -618,13 +688,13 @@ __device__ __forceinline__ float select_rows_reg(const float (&xr)[STEPS][8], co
                 }
             }
         },
-        want, S, bin1, prefix, remaining);
+        want, level1, S, bin1, prefix, remaining);
 
     float mass = 0.f;
     if (want > 0) {
         uint32_t gt_base = 0, eq_base = 0;
         compact_tile<NT, STEPS>(xr, bin_of, 0, ncand, bin1, prefix, remaining, gt_base, eq_base, &S.wave_cnt[0][0],
-                                xs, M, sel, mass);
+                                M, sel, mass);
     }
     // step 5: the l most recent positions are always kept
     for (int i = tid; i < leff; i += NT) {
@@ -921,8 +991,10 @@ __global__ __launch_bounds__(NT) void sparf_select_kernel(SparfArgs a)
 //   sparf_compact_kernel  every block ranks the members (same threshold key in all
 //                         of them), derives how many kept rows lie in front of its
 //                         stretch, compacts it and leaves its share of the kept
-//                         softmax mass; the block that finishes last adds the shares
-//                         up in stretch order and writes alpha.
+//                         softmax mass; the attend kernel adds the shares up in
+//                         stretch order (alpha).  Nothing crosses blocks inside a
+//                         launch except one integer atomic per block: fences between
+//                         the chip's L2 caches cost more than a launch.
 // The kept rows are those of the one-block selection.  If the threshold bin holds
 // more than kSparfMemberCap scores (many equal scores), the block of stretch 0 runs
 // the one-block selection over the whole row instead.
@@ -985,7 +1057,13 @@ __global__ __launch_bounds__(256) void sparf_members_kernel(SparfArgs a)
     __shared__ uint32_t s_keys[kSparfMemberCap];
     __shared__ uint32_t s_n, s_above, s_base;
     uint32_t total = 0;
-    for (int c = 0; c < v.ncc; ++c) total += a.hist[(row * a.nchunk + c) * 256 + tid];
+    const uint32_t* hp = a.hist + row * a.nchunk * 256 + tid;
+    int c = 0;
+    for (; c + 4 <= v.ncc; c += 4) {
+        const uint32_t h0 = hp[c * 256], h1 = hp[(c + 1) * 256], h2 = hp[(c + 2) * 256], h3 = hp[(c + 3) * 256];
+        total += (h0 + h1) + (h2 + h3);
+    }
+    for (; c < v.ncc; ++c) total += hp[c * 256];
     S.hist[tid] = total;
     if (tid == 0) s_n = s_above = 0;
     __syncthreads();
@@ -1009,7 +1087,8 @@ __global__ __launch_bounds__(256) void sparf_members_kernel(SparfArgs a)
                     if (j < (uint32_t)kSparfMemberCap) s_keys[j] = order_key(xr[i][e]);
                 }
             }
-    if (above) atomicAdd(&s_above, above);
+    above = (uint32_t)wave_sum((float)above);              // at most 32 per lane: exact in fp32
+    if ((tid & 63) == 0) atomicAdd(&s_above, above);
     __syncthreads();
     const uint32_t n = s_n;
     if (tid == 0) {
@@ -1033,8 +1112,9 @@ __global__ __launch_bounds__(256) void sparf_compact_kernel(SparfArgs a)
     const int h = blockIdx.x, chunk = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
     const int64_t row = (int64_t)b * a.num_q_heads + h;
     const StretchView v = stretch_view(a, b, chunk);
+    float* share = a.mass_part + row * a.nchunk;           // kept softmax mass per stretch; alpha = sum / Z
     if (v.L == 0) {
-        if (chunk == 0 && tid == 0) a.alpha[row] = 0.f;
+        if (tid == 0) share[chunk] = 0.f;
         return;
     }
     __shared__ SelectScratch S;
@@ -1048,11 +1128,16 @@ __global__ __launch_bounds__(256) void sparf_compact_kernel(SparfArgs a)
         // the block of stretch 0 does the whole row the one-block way
         if (chunk == 0) {
             const float alpha = select_rows<NT>(x, v.L, a.k, a.l, M, xmin, Z, sel, S);
-            if (tid == 0) a.alpha[row] = alpha;
+            if (tid == 0) share[0] = alpha * Z;
+        } else if (tid == 0) {
+            share[chunk] = 0.f;
         }
         return;
     }
-    if (v.t0 >= v.ncand) return;
+    if (v.t0 >= v.ncand) {
+        if (tid == 0) share[chunk] = 0.f;
+        return;
+    }
     float xr[STEPS][8];
     own_scores<NT, STEPS>(x + v.t0, v.ncand - v.t0, xr);
     const Level1 level1(M, xmin);
@@ -1060,7 +1145,8 @@ __global__ __launch_bounds__(256) void sparf_compact_kernel(SparfArgs a)
 
     // the members of the threshold bin: rank them against each other (the threshold key
     // has fewer than rem1 keys above it and at least rem1 at or above)
-    __shared__ uint32_t s_mkey[kSparfMemberCap];
+    __shared__ __align__(16) uint32_t s_mkey[kSparfMemberCap];
+    __shared__ __align__(16) uint32_t s_mkey2[kSparfMemberCap];
     __shared__ uint16_t s_mchunk[kSparfMemberCap];
     __shared__ uint32_t s_gtb, s_eqb;
     for (uint32_t i = tid; i < nmem; i += NT) {
@@ -1070,37 +1156,36 @@ __global__ __launch_bounds__(256) void sparf_compact_kernel(SparfArgs a)
     }
     if (tid == 0) s_gtb = s_eqb = 0;
     __syncthreads();
-    for (uint32_t i = tid; i < nmem; i += NT) {
-        const uint32_t mine = s_mkey[i];
-        uint32_t gt = 0, ge = 0;
-        for (uint32_t j = 0; j < nmem; ++j) {
-            const uint32_t o = s_mkey[j];
-            gt += o > mine;
-            ge += o >= mine;
-        }
-        if (gt < rem1 && rem1 <= ge) {                  // same values from every such member
-            S.prefix = mine;
-            S.remaining = rem1 - gt;
-        }
-    }
+    rank_members<NT>(s_mkey, s_mkey2, nmem, (uint32_t)kSparfMemberCap, rem1, level1, S);
     __syncthreads();
     const uint32_t thr = S.prefix, rem_eq = S.remaining;
     // kept rows in front of this stretch: scores in higher bins and members above the
     // threshold key of earlier stretches; rows at the threshold key likewise
+    // (every thread counts its share, one LDS atomic per wave; all loads in flight at once)
+    uint32_t gtb = 0, eqb = 0;
     for (uint32_t i = tid; i < nmem; i += NT) {
         if ((int)s_mchunk[i] < chunk) {
-            if (s_mkey[i] > thr) atomicAdd(&s_gtb, 1u);
-            else if (s_mkey[i] == thr) atomicAdd(&s_eqb, 1u);
+            gtb += s_mkey[i] > thr;
+            eqb += s_mkey[i] == thr;
         }
+    }
+    for (int c = tid; c < chunk; c += NT) gtb += a.gt1[row * a.nchunk + c];
+#pragma unroll
+    for (int sft = 32; sft > 0; sft >>= 1) {
+        gtb += __shfl_xor(gtb, sft, 64);
+        eqb += __shfl_xor(eqb, sft, 64);
+    }
+    if ((tid & 63) == 0) {
+        atomicAdd(&s_gtb, gtb);
+        atomicAdd(&s_eqb, eqb);
     }
     __syncthreads();
     uint32_t gt_base = s_gtb, eq_base = s_eqb;
-    for (int c = 0; c < chunk; ++c) gt_base += a.gt1[row * a.nchunk + c];
 
     float mass = 0.f;
     compact_tile<NT, STEPS>(
         xr, [&](int i, int e) { return level1(xr[i][e]); }, v.t0, v.ncand, bin1, thr, rem_eq, gt_base, eq_base,
-        &S.wave_cnt[0][0], x, M, sel, mass);
+        &S.wave_cnt[0][0], M, sel, mass);
     if (chunk == 0) {
         // step 5: the l most recent positions are always kept
         for (int i = tid; i < v.leff; i += NT) {
@@ -1110,18 +1195,17 @@ __global__ __launch_bounds__(256) void sparf_compact_kernel(SparfArgs a)
         }
     }
     mass = block_sum(mass, S.red);
-    if (tid == 0) {
-        // step 7: the block that finishes last adds the shares up in stretch order
-        a.mass_part[row * a.nchunk + chunk] = mass;
-        __threadfence();
-        if (atomicAdd(&a.counters[row * 2 + 1], 1u) == (uint32_t)v.ncc - 1u) {
-            __threadfence();
-            float kept = 0.f;
-            for (int c = 0; c < v.ncc; ++c)
-                kept += __hip_atomic_load(&a.mass_part[row * a.nchunk + c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            a.alpha[row] = kept / Z;
-        }
-    }
+    if (tid == 0) share[chunk] = mass;                      // step 7 is finished by the attend kernel
+}
+
+// Step 7 after the distributed selection: the stretches' shares in stretch order.
+__device__ __forceinline__ float distributed_alpha(const SparfArgs& a, int64_t row, int L)
+{
+    float M, xmin, Z;
+    row_stats(a, row, L, M, xmin, Z);
+    float kept = 0.f;
+    for (int c = 0; c < a.nchunk; ++c) kept += a.mass_part[row * a.nchunk + c];
+    return kept / Z;
 }
 
 // Steps 10-11, long rows: one block per query head and slice of its kept rows.
@@ -1137,6 +1221,7 @@ __global__ __launch_bounds__(kSparfAttendWaves * 64) void sparf_attend_kernel(Sp
     const int L = clamp_len(a.seq_lens[b], a.max_len);
     if (L == 0) {
         if (a.nslices == 1) write_zero_row<D>(a, row);     // else the merge writes it
+        if (a.distributed && slice == 0 && threadIdx.x == 0) a.alpha[row] = 0.f;
         return;
     }
     __shared__ float s_acc[NG][D];
@@ -1146,7 +1231,14 @@ __global__ __launch_bounds__(kSparfAttendWaves * 64) void sparf_attend_kernel(Sp
     const int n = min(a.k, L);
     const int p_begin = min(slice * a.slice_rows, n), p_end = min(p_begin + a.slice_rows, n);
     float* part = a.nslices == 1 ? nullptr : a.part + (row * a.nslices + slice) * (D + 2);
-    attend_rows<D, kSparfAttendWaves>(a, b, h, L, p_begin, p_end, a.sel + row * a.k, a.alpha[row], part, s_ids,
+    float alpha;
+    if (a.distributed) {
+        alpha = distributed_alpha(a, row, L);
+        if (slice == 0 && threadIdx.x == 0) a.alpha[row] = alpha;
+    } else {
+        alpha = a.alpha[row];
+    }
+    attend_rows<D, kSparfAttendWaves>(a, b, h, L, p_begin, p_end, a.sel + row * a.k, alpha, part, s_ids,
                                       kSparfAttendIds, s_acc, s_m, s_l);
 }
 
