@@ -887,47 +887,55 @@ __global__ __launch_bounds__(256, INSTATTN_SPARF_WAVES_PER_SIMD) void sparf_logi
 {
     constexpr int NT = 256, STEPS = kSparfChunk / (NT * 8);
     static_assert(kSparfChunk == kSparfFusedMaxLen, "the column pass covers one stretch");
-    const int h = blockIdx.x, chunk = blockIdx.y, b = blockIdx.z;
+    const int h = blockIdx.x, b = blockIdx.z;
     const int G = a.num_q_heads / a.num_kv_heads;
     const int hk = h / G;
     const int tid = threadIdx.x;
     const int64_t row = (int64_t)b * a.num_q_heads + h;
     const int L = clamp_len(a.seq_lens[b], a.max_len);
-    const int t0 = chunk * kSparfChunk;
-    float* stats = a.stats + (row * a.nchunk + chunk) * 3;   // max, sum of 2^(x - max), min
-    if (t0 >= L) {
-        if (tid == 0) {
-            stats[0] = kNegBig;
-            stats[1] = 0.f;
-            stats[2] = -kNegBig;
-        }
-        return;
-    }
     __shared__ __align__(16) float xs[kSparfChunk];
     __shared__ float s_q[128];
     __shared__ __align__(16) float s_abs[128];
     __shared__ int s_dim[128];
     __shared__ float s_red[48];
-    const float factor = prepare_query(a, row, s_q, s_abs, s_dim, s_red);
-    const int Lc = min(L - t0, kSparfChunk);
-    column_passes<NT>(a, b, hk, t0, Lc, factor, s_q, s_dim, xs);
-    float xr[STEPS][8];
-    own_scores<NT, STEPS>(xs, Lc, xr);
-    float* dst = a.logits + row * a.lpad + t0;
-#pragma unroll
-    for (int i = 0; i < STEPS; ++i) {
-        const int t = (i * NT + tid) * 8;
-        if (t < Lc) {
-            *(float4_t*)(dst + t) = float4_t{xr[i][0], xr[i][1], xr[i][2], xr[i][3]};
-            *(float4_t*)(dst + t + 4) = float4_t{xr[i][4], xr[i][5], xr[i][6], xr[i][7]};
+    float factor = 0.f;
+    bool prepared = false;
+    // a block takes every gridDim.y-th stretch of its head and ranks the query once
+    for (int chunk = blockIdx.y; chunk < a.nchunk; chunk += gridDim.y) {
+        const int t0 = chunk * kSparfChunk;
+        float* stats = a.stats + (row * a.nchunk + chunk) * 3;   // max, sum of 2^(x - max), min
+        if (t0 >= L) {
+            if (tid == 0) {
+                stats[0] = kNegBig;
+                stats[1] = 0.f;
+                stats[2] = -kNegBig;
+            }
+            continue;
         }
-    }
-    float M, xmin, Z;
-    block_stats<NT, STEPS>(xr, Lc, s_red, M, xmin, Z);
-    if (tid == 0) {
-        stats[0] = M;
-        stats[1] = Z;
-        stats[2] = xmin;
+        if (!prepared) {                                        // block-uniform
+            factor = prepare_query(a, row, s_q, s_abs, s_dim, s_red);
+            prepared = true;
+        }
+        const int Lc = min(L - t0, kSparfChunk);
+        column_passes<NT>(a, b, hk, t0, Lc, factor, s_q, s_dim, xs);
+        float xr[STEPS][8];
+        own_scores<NT, STEPS>(xs, Lc, xr);
+        float* dst = a.logits + row * a.lpad + t0;
+#pragma unroll
+        for (int i = 0; i < STEPS; ++i) {
+            const int t = (i * NT + tid) * 8;
+            if (t < Lc) {
+                *(float4_t*)(dst + t) = float4_t{xr[i][0], xr[i][1], xr[i][2], xr[i][3]};
+                *(float4_t*)(dst + t + 4) = float4_t{xr[i][4], xr[i][5], xr[i][6], xr[i][7]};
+            }
+        }
+        float M, xmin, Z;
+        block_stats<NT, STEPS>(xr, Lc, s_red, M, xmin, Z);
+        if (tid == 0) {
+            stats[0] = M;
+            stats[1] = Z;
+            stats[2] = xmin;
+        }
     }
 }
 
@@ -1462,7 +1470,12 @@ hipError_t launch_sparf_append(const SparfArgs& a, hipStream_t stream)
 
 hipError_t launch_sparf_logits(const SparfArgs& a, hipStream_t stream)
 {
-    hipLaunchKernelGGL(sparf_logits_kernel, dim3(a.num_q_heads, a.nchunk, a.batch), dim3(256), 0, stream, a);
+    // about 1024 blocks (four per compute unit) at most: a block walks several stretches of
+    // its head when there are more, and ranks the query once for all of them
+    const int64_t heads = (int64_t)a.num_q_heads * a.batch;
+    int per_head = (int)(1024 / heads);
+    per_head = per_head < 1 ? 1 : (per_head > a.nchunk ? a.nchunk : per_head);
+    hipLaunchKernelGGL(sparf_logits_kernel, dim3(a.num_q_heads, per_head, a.batch), dim3(256), 0, stream, a);
     return hipGetLastError();
 }
 
