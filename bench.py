@@ -181,8 +181,48 @@ def bench_sparf(args):
         "bytes_read_algorithm1": sparf_bytes, "bytes_read_dense": dense_bytes,
         "compression": sparf_bytes / dense_bytes, "score_bytes_written_and_read": score_bytes,
         "achieved_GBps_algorithm1_bytes": sparf_bytes / t_sparf / 1e9,
+        # the whole step (one or several launches) against the bytes Algorithm 1 must read
+        "roofline": {"bound": "hbm", "achieved": sparf_bytes / t_sparf / 1e9, "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": sparf_bytes / t_sparf / 1e9 / HBM_PEAK_GBPS, "traffic": None,
+                     "kernel": "whole SparF step", "algorithmic_bytes_per_launch": sparf_bytes},
     }
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = sparf_cpu_baseline(cases, r, k, l)
     print(json.dumps(res), flush=True)
+
+
+def sparf_cpu_baseline(cases, r, k, l, budget_s=10.0):
+    """The fp64 numpy oracle of Algorithm 1 as it stands, one (sequence, head) pair after
+    the other on one core, over the resident layers in order until about 10 s of CPU
+    work are done (a pair's rows are gathered on the device and copied over, outside
+    the clock)."""
+    from oracle import sparf_attention as sparf_oracle
+    wl = cases[0].wl
+    done, bytes_done, dt = 0, 0, 0.0
+    for case in cases:
+        lens = case.seq_lens.cpu().numpy()
+        ps = case.k_cache.shape[2]
+        for b in range(wl.batch):
+            for h in range(wl.num_q_heads):
+                if dt >= budget_s:
+                    break
+                hk, L = h // wl.group, int(lens[b])
+                if case.page_table is None:
+                    K, V = case.k_cache[b, hk, :L], case.v_cache[b, hk, :L]
+                else:
+                    pages = case.page_table[b, :(L + ps - 1) // ps].long()
+                    K = case.k_cache[pages, hk].reshape(-1, wl.head_dim)[:L]
+                    V = case.v_cache[pages, hk].reshape(-1, wl.head_dim)[:L]
+                q, K, V = case.q[b, h].cpu().numpy(), K.cpu().numpy(), V.cpu().numpy()
+                t = time.perf_counter()
+                sparf_oracle.sparf_one(q, K, V, case.scale, r, k, l)
+                dt += time.perf_counter() - t
+                done += 1
+                bytes_done += 2 * L * wl.head_dim * 2 // wl.group     # this head's share of the dense K + V bytes
+    return {"value": bytes_done / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": "%d (sequence, head) pairs of the same workload's layers in order, fp64 numpy "
+                      "oracle of Algorithm 1, 1 thread, %.1f s; value in dense-equivalent KV bytes like the "
+                      "metric" % (done, dt)}
 
 
 def bench_kv_write(args):
