@@ -773,8 +773,8 @@ __device__ __forceinline__ void attend_rows(const SparfArgs& a, int b, int h, in
                 const int id = max(raw, 0);
                 const int64_t off = base + (int64_t)(paged ? id >> shift : 0) * stride_page +
                                     (int64_t)(paged ? id & mask : id) * a.kv.stride_t;
-                T.k[j] = *(const u32x4*)(raw < 0 ? a.k_new + new_off : a.kv.k + off);
-                T.v[j] = *(const u32x4*)(raw < 0 ? a.v_new + new_off : a.kv.v + off);
+                T.k[j] = __builtin_nontemporal_load((const u32x4*)(raw < 0 ? a.k_new + new_off : a.kv.k + off));
+                T.v[j] = __builtin_nontemporal_load((const u32x4*)(raw < 0 ? a.v_new + new_off : a.kv.v + off));
             }
         };
         auto consume = [&](const Tile& T, int it) {
