@@ -135,7 +135,9 @@ def test_plan_covers_the_sequence_and_fills_the_chip(shape):
     if max_len * streams >= 1024 * 1024:           # enough work to want every CU busy twice over
         assert streams * splits >= 512
     if hq == hkv and streams >= 512 and max_len <= 8192:
-        assert splits == 1                         # enough short streams: no merge pass
+        # enough short streams: whole sequences, or the fewest equal splits that fill every
+        # block slot of the chip (no merge pass from 1280 streams on)
+        assert splits == max(1, -(-1280 // streams)) or chunk == 384
     if chunk < max_len:                            # split: chunk is an odd multiple of 128
         assert (chunk // 128) % 2 == 1
     ws = B.decode_workspace_size(*shape)
@@ -155,7 +157,8 @@ def test_forced_chunk_env(monkeypatch):
     monkeypatch.setenv("INSTATTN_CHUNK", "500")      # rounded up to the tile quantum
     assert B.decode_plan(16, 40, 40, 128, 4097) == (512, 9)
     monkeypatch.delenv("INSTATTN_CHUNK")
-    assert B.decode_plan(16, 40, 40, 128, 4097) == (4224, 1)
+    assert B.decode_plan(16, 40, 40, 128, 4097) == (2176, 2)      # 640 streams in two halves
+    assert B.decode_plan(32, 40, 40, 128, 4097) == (4224, 1)      # 1280 streams fill the chip: one unit each
 
 
 # ------------------------------------------------------------------ SparF entry points
