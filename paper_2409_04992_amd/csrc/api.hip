@@ -54,6 +54,17 @@ Plan make_plan(int batch, int num_q_heads, int num_kv_heads, int max_seq_len)
         const long n = (kResidentUnits + streams - 1) / streams;       // 1 from 1280 streams on
         chunk = ((((long)max_seq_len + n - 1) / n + kChunkQuantum - 1) / kChunkQuantum | 1) * kChunkQuantum;
     }
+    // The MFMA kernel holds two blocks per compute unit.  With a stream or more per
+    // compute unit and short sequences, whole sequences are the best units when they
+    // come out even over the 256 compute units (256 or 512 streams: 84.5 % of peak
+    // against 79 % in two splits, and no merge); otherwise equal splits, three units or
+    // more per compute unit, dilute the uneven last round (384 streams of 8K rows in
+    // halves: 82 % against 78 % at the longest allowed unit).
+    if (group > 1 && streams >= 256 && max_seq_len <= kSingleSplitMaxLen) {
+        const long n = streams % 256 == 0 ? 1 : (3 * 256 + streams - 1) / streams;
+        chunk = ((((long)max_seq_len + n - 1) / n + kChunkQuantum - 1) / kChunkQuantum | 1) * kChunkQuantum;
+        if (chunk < kMinChunk) chunk = kMinChunk;
+    }
     const char* forced = getenv("INSTATTN_CHUNK");
     if (forced && atoi(forced) > 0)
         chunk = ((long)atoi(forced) + kChunkQuantum - 1) / kChunkQuantum * kChunkQuantum;
