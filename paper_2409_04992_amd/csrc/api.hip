@@ -216,6 +216,13 @@ static int run_partial(const void* q, const void* k_new, const void* v_new, bool
     DecodeArgs a;
     a.k_new = fused ? (const half_t*)k_new : nullptr;
     a.v_new = fused ? (const half_t*)v_new : nullptr;
+    // Streams whose strides walk the HBM channels in step (a contiguous cache of 2064
+    // rows per head does) lose a tenth to a half of the bandwidth; starting every unit
+    // at its own tile undoes most of that and costs about 1 % elsewhere: off by default.
+    {
+        const char* e = getenv("INSTATTN_ROTATE");
+        a.rotate = e && e[0] == '1';
+    }
     a.q = (const half_t*)q;
     a.kv = make_view(kv);
     a.seq_lens = seq_lens;

@@ -52,6 +52,9 @@ struct DecodeArgs {
     // seq_lens[b] - 1 by the unit that owns that position, before it reads it.
     const half_t* k_new;
     const half_t* v_new;
+    // 1: every unit starts its walk over its rows at a tile of its own (and wraps
+    // round) instead of at its first row.
+    int32_t rotate;
 };
 
 // Arguments of the log-sum-exp merge.

@@ -85,7 +85,7 @@ __device__ __forceinline__ void wave_lds_fence() {
 }  // namespace
 
 template <int D, bool PAGED, bool SPLIT_P>
-__global__ __launch_bounds__(256) void decode_gqa_kernel(DecodeArgs a)
+__global__ __launch_bounds__(256, 2) void decode_gqa_kernel(DecodeArgs a)
 {
     typedef GqTraits<D> TR;
     typedef typename TR::vec_t vec_t;
@@ -136,8 +136,16 @@ __global__ __launch_bounds__(256) void decode_gqa_kernel(DecodeArgs a)
     const int64_t head_off = (int64_t)hk * a.kv.stride_h;
     const int32_t* table = PAGED ? a.kv.page_table + (int64_t)b * a.kv.max_pages : nullptr;
 
+    const int n_it = (t1 - t0 + kGqTile - 1) / kGqTile;
+    // Tile visited in iteration `it`: in order, or (a.rotate) from a start of the unit's
+    // own and round; iterations behind the end stay behind it.
+    const int rot =
+        a.rotate ? (int)((((uint32_t)(b * a.num_kv_heads + hk) * 0x9E3779B1u) >> 16) % (uint32_t)n_it) : 0;
+    auto tile_of = [&](int it) { return it < n_it ? (it + rot < n_it ? it + rot : it + rot - n_it) : it; };
     // First row of sub-tile m of this wave in iteration `it`, pulled back into the unit.
-    auto sub_row = [&](int it, int m) { return min(t0 + it * kGqTile + wave * kGqWaveRows + 16 * m, last); };
+    auto sub_row = [&](int it, int m) {
+        return min(t0 + tile_of(it) * kGqTile + wave * kGqWaveRows + 16 * m, last);
+    };
     auto page_of = [&](int t) { return PAGED ? table[t >> a.kv.page_shift] : b; };
 
     auto load_tile = [&](GqaTile<D>& T, int it, int page0, int page1) {
@@ -148,7 +156,7 @@ __global__ __launch_bounds__(256) void decode_gqa_kernel(DecodeArgs a)
             const int page = m == 0 ? page0 : page1;
             const int64_t base =
                 2 * ((int64_t)page * a.kv.stride_b + head_off + (int64_t)in_page * a.kv.stride_t);
-            const int first = t0 + it * kGqTile + wave * kGqWaveRows + 16 * m + g;
+            const int first = t0 + tile_of(it) * kGqTile + wave * kGqWaveRows + 16 * m + g;
 #pragma unroll
             for (int x = 0; x < 4; ++x) {
                 // rows behind the unit's end are redirected to its last row
@@ -186,7 +194,7 @@ __global__ __launch_bounds__(256) void decode_gqa_kernel(DecodeArgs a)
         wave_lds_fence();
 
         // Scores of head c for rows first + 16m + 4r (slot 4m + r).
-        const int first = t0 + it * kGqTile + wave * kGqWaveRows + g;
+        const int first = t0 + tile_of(it) * kGqTile + wave * kGqWaveRows + g;
         float sc[8];
         float mx = -__builtin_inff();
 #pragma unroll
@@ -228,7 +236,6 @@ __global__ __launch_bounds__(256) void decode_gqa_kernel(DecodeArgs a)
         }
     };
 
-    const int n_it = (t1 - t0 + kGqTile - 1) / kGqTile;
     GqaTile<D> A, B;
     int pa0 = page_of(sub_row(0, 0)), pa1 = page_of(sub_row(0, 1));
     int pb0 = page_of(sub_row(1, 0)), pb1 = page_of(sub_row(1, 1));

@@ -112,8 +112,13 @@ __global__ __launch_bounds__(INSTATTN_MHA_WAVES * 64) void decode_mha_kernel(Dec
     const int64_t head_off = (int64_t)hk * a.kv.stride_h;
     const int32_t* table = PAGED ? a.kv.page_table + (int64_t)b * a.kv.max_pages : nullptr;
 
+    const int n_it = (t1 - t0 + TILE - 1) / TILE;
+    // Tile visited in iteration `it`: in order, or (a.rotate) from a start of the unit's
+    // own and round; iterations behind the end stay behind it.
+    const int rot = a.rotate ? (int)((((uint32_t)row * 0x9E3779B1u) >> 16) % (uint32_t)n_it) : 0;
+    auto tile_of = [&](int it) { return it < n_it ? (it + rot < n_it ? it + rot : it + rot - n_it) : it; };
     // First row this wave touches in iteration `it`, pulled back into the unit.
-    auto wave_row = [&](int it) { return min(t0 + it * TILE + wave * WTILE, last); };
+    auto wave_row = [&](int it) { return min(t0 + tile_of(it) * TILE + wave * WTILE, last); };
     // Pool page (paged) of that row; fetched one iteration ahead of its use.
     auto page_of = [&](int tw) { return PAGED ? table[tw >> a.kv.page_shift] : b; };
 
@@ -122,7 +127,7 @@ __global__ __launch_bounds__(INSTATTN_MHA_WAVES * 64) void decode_mha_kernel(Dec
         const int in_page = PAGED ? (tw & a.kv.page_mask) : tw;
         const int64_t tile_off =
             2 * ((int64_t)page * a.kv.stride_b + head_off + (int64_t)in_page * a.kv.stride_t);
-        const int first = t0 + it * TILE + wave * WTILE + r;  // this lane's row for j = 0
+        const int first = t0 + tile_of(it) * TILE + wave * WTILE + r;  // this lane's row for j = 0
 #pragma unroll
         for (int j = 0; j < U; ++j) {
             // rows behind the unit's end are redirected to its last row
@@ -138,7 +143,7 @@ __global__ __launch_bounds__(INSTATTN_MHA_WAVES * 64) void decode_mha_kernel(Dec
     for (int e = 0; e < 8; ++e) acc[e] = 0.f;
 
     auto consume = [&](const MhaTile<U>& T, int it) {
-        const int first = t0 + it * TILE + wave * WTILE + r;
+        const int first = t0 + tile_of(it) * TILE + wave * WTILE + r;
         float s[U];
         float mx = m;
 #pragma unroll
@@ -165,7 +170,6 @@ __global__ __launch_bounds__(INSTATTN_MHA_WAVES * 64) void decode_mha_kernel(Dec
 
     // Two register tiles: tile i+1 is in flight while tile i is consumed; the page
     // id of tile i+2 is in flight behind it.
-    const int n_it = (t1 - t0 + TILE - 1) / TILE;
     MhaTile<U> A, B;
     int page_a = page_of(wave_row(0));
     int page_b = page_of(wave_row(1));

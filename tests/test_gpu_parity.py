@@ -389,6 +389,22 @@ def test_drawn_configurations(cfg):
     full_check(wl, out_dtype=torch.float32 if f32 else torch.float16, fused=fused)
 
 
+@pytest.mark.parametrize("cfg", _drawn_configs(12, 20240919), ids=lambda c: "cfg%d" % c[0])
+def test_drawn_configurations_with_rotated_walks(monkeypatch, cfg):
+    """INSTATTN_ROTATE=1: every unit starts at a tile of its own and wraps round (the
+    remedy for cache strides that walk the HBM channels in step); same results."""
+    monkeypatch.setenv("INSTATTN_ROTATE", "1")
+    i, Bn, D, G, Hkv, S, paged, f32, fused = cfg
+    wl = W.Workload("rot%d" % i, Bn, G * Hkv, Hkv, D, S, seq_len_min=S // 4, paged=paged, page_size=16,
+                    seed=800 + i)
+    full_check(wl, out_dtype=torch.float32 if f32 else torch.float16, fused=fused)
+
+
+def test_rotated_walk_on_the_13b_shape(monkeypatch):
+    monkeypatch.setenv("INSTATTN_ROTATE", "1")
+    full_check(W.WORKLOADS["mha13b_4k"], fused=True)
+
+
 # ------------------------------------------------------------------ HIP graph replay
 @pytest.mark.parametrize("shape", ["mha_splits", "gqa_paged"])
 def test_step_replayed_from_a_hip_graph(shape):
