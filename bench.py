@@ -41,6 +41,9 @@ def parse():
     ap.add_argument("--kt-page", type=int, default=None,
                     help="with --sparf: positions per page of the component-major K copy "
                          "(0: contiguous; default 256 for a paged workload, else 0)")
+    ap.add_argument("--kt-capacity", type=int, default=None,
+                    help="with --sparf and a contiguous component-major copy: positions it is allocated "
+                         "for (multiple of 8; default: the cache's capacity)")
     ap.add_argument("--sparf", default=None, metavar="r,k,l",
                     help="time the SparF path (Algorithm 1) with these parameters instead of the "
                          "dense path, next to the dense step on the same caches")
@@ -117,7 +120,7 @@ def bench_sparf(args):
         Bn, Hkv, cap, D = wl.batch, wl.num_kv_heads, c.capacity, wl.head_dim
         vsum = torch.zeros(Bn, Hkv, D, dtype=torch.float32, device=dev)
         if kt_page == 0:
-            kt, kt_table = torch.zeros(Bn, Hkv, D, cap, dtype=torch.float16, device=dev), None
+            kt, kt_table = torch.zeros(Bn, Hkv, D, max(cap, args.kt_capacity or 0), dtype=torch.float16, device=dev), None
         else:
             # the component-major copy in pages of its own size behind a shuffled table
             need = [(int(L) + kt_page - 1) // kt_page for L in c.seq_lens.cpu().tolist()]

@@ -15,7 +15,7 @@ size_t up256(size_t x) { return (x + 255) / 256 * 256; }
 
 struct Carve {
     size_t logits, stats, sel, alpha, part, hist, gt1, counters, state, members, mass_part, total;
-    int lpad, nchunk;
+    int lpad, nchunk, nstat;
 };
 
 Carve carve(int batch, int num_q_heads, int head_dim, int max_seq_len, int k)
@@ -23,10 +23,11 @@ Carve carve(int batch, int num_q_heads, int head_dim, int max_seq_len, int k)
     Carve c;
     c.nchunk = (max_seq_len + kSparfChunk - 1) / kSparfChunk;
     c.lpad = c.nchunk * kSparfChunk;
+    c.nstat = c.lpad / kSparfStatRun;
     const size_t rows = (size_t)batch * num_q_heads;
     c.logits = 0;
     c.stats = c.logits + up256(rows * c.lpad * sizeof(float));
-    c.sel = c.stats + up256(rows * c.nchunk * 3 * sizeof(float));
+    c.sel = c.stats + up256(rows * c.nstat * 3 * sizeof(float));
     c.alpha = c.sel + up256(rows * (size_t)k * sizeof(int32_t));
     c.part = c.alpha + up256(rows * sizeof(float));
     c.hist = c.part + up256(rows * kSparfMaxSlices * (size_t)(head_dim + 2) * sizeof(float));
@@ -171,6 +172,7 @@ int run_sparf_decode(const void* q, const void* k_new, const void* v_new, bool a
     a.logits = (float*)(ws + c.logits);
     a.lpad = c.lpad;
     a.nchunk = c.nchunk;
+    a.nstat = c.nstat;
     a.stats = (float*)(ws + c.stats);
     a.sel = sel_rows ? sel_rows : (int32_t*)(ws + c.sel);
     a.alpha = alpha ? alpha : (float*)(ws + c.alpha);

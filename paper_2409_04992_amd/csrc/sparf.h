@@ -6,6 +6,7 @@
 namespace instattn {
 
 constexpr int kSparfChunk = 8192;      // positions per block of the approximate-score pass
+constexpr int kSparfStatRun = 512;     // scores per entry of the score statistics (a wave's share of a unit)
 constexpr int kSparfSelectThreads = 1024;
 constexpr int kSparfAttendWaves = 8;
 constexpr int kSparfMemberCap = 1024;  // members of the threshold bin the distributed selection ranks directly
@@ -42,8 +43,8 @@ struct SparfArgs {
     float scale_log2;
     int32_t r, k, l;
     float* logits;                     // [B][Hq][lpad] approximate scores, log2 domain
-    int32_t lpad, nchunk;
-    float* stats;                      // [B][Hq][nchunk][3]: block max, sum of 2^(x - max), min
+    int32_t lpad, nchunk, nstat;       // padded row, its stretches of kSparfChunk, its runs of kSparfStatRun
+    float* stats;                      // [B][Hq][nstat][3]: a run's max, sum of 2^(x - max), min
     int32_t* sel;                      // [B][Hq][k] selected rows, ascending
     float* alpha;                      // [B][Hq] selected share of the approximate softmax
     float* part;                       // [B][Hq][nslices][D + 2] shares of the attend kernel's slices

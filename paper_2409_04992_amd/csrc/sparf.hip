@@ -880,71 +880,196 @@ __device__ __forceinline__ void write_zero_row(const SparfArgs& a, int64_t row)
 }  // namespace
 
 // ---------------------------------------------------------------------------
-// Steps 1-4 (without the normaliser), long rows: one block per stretch of 8192
-// positions of one head, the same column pass as the one-launch kernel; the
-// scores go to the workspace together with the stretch's max / sum / min.
+// Steps 1-4 (without the normaliser), long rows.  A block of 256 threads ranks the
+// query once and walks units of 2048 positions of its head, every gridDim.y-th one;
+// a thread owns 8 consecutive positions of a unit and adds up the kept columns in
+// rank order, 8 columns per step (the same sums, in the same order, as the column
+// pass of the one-launch kernel).  The steps of all its units form one sequence:
+// the loads of step i+1 are in flight while step i is consumed, across units, and
+// every step issues its 8 loads unconditionally (a last group of fewer than 8
+// columns repeats the last column, steps behind the row's end re-read its last 8
+// positions) so that the count of loads in flight is known at every wait.  The
+// columns of a step and their q components come out of two registers by lane index
+// (lane j holds the component ranked j): no LDS, no barrier after the query ranking.
+// Scores go to the workspace; every wave leaves the max / sum of 2^(x - max) / min
+// of its 512 positions.
+#ifndef INSTATTN_SPARF_LOGITS_CG
+// Columns per step; with 4 or 2 a thread takes 2 or 4 runs of 8 positions, 2048 apart,
+// of each (fewer address streams per block, same bytes in flight: measured the same).
+#define INSTATTN_SPARF_LOGITS_CG 8
+#endif
+template <bool PAGED>
 __global__ __launch_bounds__(256, INSTATTN_SPARF_WAVES_PER_SIMD) void sparf_logits_kernel(SparfArgs a)
 {
-    constexpr int NT = 256, STEPS = kSparfChunk / (NT * 8);
-    static_assert(kSparfChunk == kSparfFusedMaxLen, "the column pass covers one stretch");
+    constexpr int NT = 256, CG = INSTATTN_SPARF_LOGITS_CG, NV = 8 / CG, SPAN = NT * 8, UNIT = SPAN * NV;
+    static_assert(SPAN == 4 * kSparfStatRun, "one statistics entry per wave and span");
     const int h = blockIdx.x, b = blockIdx.z;
     const int G = a.num_q_heads / a.num_kv_heads;
     const int hk = h / G;
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int64_t row = (int64_t)b * a.num_q_heads + h;
     const int L = clamp_len(a.seq_lens[b], a.max_len);
-    __shared__ __align__(16) float xs[kSparfChunk];
+    const int nunits = (L + UNIT - 1) / UNIT;
+    if ((int)blockIdx.y >= nunits) return;                    // block-uniform, before any barrier
     __shared__ float s_q[128];
     __shared__ __align__(16) float s_abs[128];
     __shared__ int s_dim[128];
     __shared__ float s_red[48];
-    float factor = 0.f;
-    bool prepared = false;
-    // a block takes every gridDim.y-th stretch of its head and ranks the query once
-    for (int chunk = blockIdx.y; chunk < a.nchunk; chunk += gridDim.y) {
-        const int t0 = chunk * kSparfChunk;
-        float* stats = a.stats + (row * a.nchunk + chunk) * 3;   // max, sum of 2^(x - max), min
-        if (t0 >= L) {
-            if (tid == 0) {
-                stats[0] = kNegBig;
-                stats[1] = 0.f;
-                stats[2] = -kNegBig;
-            }
-            continue;
+    const float factor = prepare_query(a, row, s_q, s_abs, s_dim, s_red);
+
+    // lane j: component ranked j (and 64 + j) and its q times the factor
+    const int D = a.head_dim;
+    const int dim_lo = s_dim[lane];
+    const int dim_hi = 64 + lane < D ? s_dim[64 + lane] : 0;
+    const int qw_lo = __builtin_bit_cast(int, s_q[dim_lo] * factor);
+    const int qw_hi = __builtin_bit_cast(int, s_q[dim_hi] * factor);
+
+    const int ng = (a.r + CG - 1) / CG;                       // steps per unit
+    const int stride = gridDim.y;
+    const int t_last = (L - 1) & ~7;                          // last run of 8 that holds a position
+    struct Step {
+        int u, g;                                             // unit, column group
+    };
+    auto advance = [&](Step& s) {
+        if (++s.g == ng) {
+            s.g = 0;
+            s.u += stride;
         }
-        if (!prepared) {                                        // block-uniform
-            factor = prepare_query(a, row, s_q, s_abs, s_dim, s_red);
-            prepared = true;
-        }
-        const int Lc = min(L - t0, kSparfChunk);
-        column_passes<NT>(a, b, hk, t0, Lc, factor, s_q, s_dim, xs);
-        float xr[STEPS][8];
-        own_scores<NT, STEPS>(xs, Lc, xr);
-        float* dst = a.logits + row * a.lpad + t0;
+    };
+    // This thread's v-th run of 8 positions in a unit, pulled back into the row.
+    auto run_of = [&](const Step& s, int v) { return min(s.u * UNIT + v * SPAN + tid * 8, t_last); };
+    // Where column 0 holds such a run: the page of the component-major copy (paged
+    // form) is looked up one step before it is needed.
+    struct Pages {
+        int p[NV];
+    };
+    auto pages_of = [&](const Step& s) {
+        Pages pg;
 #pragma unroll
-        for (int i = 0; i < STEPS; ++i) {
-            const int t = (i * NT + tid) * 8;
-            if (t < Lc) {
-                *(float4_t*)(dst + t) = float4_t{xr[i][0], xr[i][1], xr[i][2], xr[i][3]};
-                *(float4_t*)(dst + t + 4) = float4_t{xr[i][4], xr[i][5], xr[i][6], xr[i][7]};
+        for (int v = 0; v < NV; ++v) {
+            if constexpr (!PAGED) pg.p[v] = b;
+            else pg.p[v] = a.aux.page_table[(int64_t)b * a.aux.max_pages + (run_of(s, v) >> a.aux.page_shift)];
+        }
+        return pg;
+    };
+    auto ptr = [&](const Step& s, int v, int page) {
+        const int t = run_of(s, v);
+        return a.aux.kt + (int64_t)page * a.aux.stride_b + (int64_t)hk * a.aux.stride_h + (PAGED ? (t & a.aux.page_mask) : t);
+    };
+    // columns (as offsets) and q components of a step, wave-uniform
+    auto setup = [&](const Step& s, int64_t (&coff)[CG], float (&qv)[CG]) {
+        const int c0 = s.g * CG;
+        const int dsel = c0 < 64 ? dim_lo : dim_hi;           // a group never straddles 64
+        const int qsel = c0 < 64 ? qw_lo : qw_hi;
+#pragma unroll
+        for (int j = 0; j < CG; ++j) {
+            const int rk = min(c0 + j, a.r - 1) & 63;
+            coff[j] = (int64_t)__builtin_amdgcn_readlane(dsel, rk) * a.aux.stride_d;
+            qv[j] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(qsel, rk));
+        }
+    };
+    auto load = [&](half8_t (&T)[NV][CG], const Step& s, const Pages& pg, const int64_t (&coff)[CG]) {
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            const half_t* p = ptr(s, v, pg.p[v]);
+#pragma unroll
+            for (int j = 0; j < CG; ++j) T[v][j] = __builtin_nontemporal_load((const half8_t*)(p + coff[j]));
+        }
+    };
+
+    float x[NV][8];
+    auto finish = [&](int u) {
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            const int t = u * UNIT + v * SPAN + tid * 8;
+            if (t < L) {
+                float* dst = a.logits + row * a.lpad + t;
+                *(float4_t*)dst = float4_t{x[v][0], x[v][1], x[v][2], x[v][3]};
+                *(float4_t*)(dst + 4) = float4_t{x[v][4], x[v][5], x[v][6], x[v][7]};
+            }
+            const int t_w = u * UNIT + v * SPAN + wave * kSparfStatRun;
+            if (t_w < L) {                                    // wave-uniform
+                float mx = kNegBig, mn = -kNegBig;
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (t + e < L) {
+                        mx = fmaxf(mx, x[v][e]);
+                        mn = fminf(mn, x[v][e]);
+                    }
+                float zs = 0.f;
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (t + e < L) zs += fast_exp2(x[v][e] - mx);
+                const float mw = wave_max(mx);
+                const float zw = wave_sum(zs * fast_exp2(mx - mw));
+                const float nw_min = -wave_max(-mn);
+                if (lane == 0) {
+                    float* st = a.stats + (row * a.nstat + t_w / kSparfStatRun) * 3;
+                    st[0] = mw;
+                    st[1] = zw;
+                    st[2] = nw_min;
+                }
             }
         }
-        float M, xmin, Z;
-        block_stats<NT, STEPS>(xr, Lc, s_red, M, xmin, Z);
-        if (tid == 0) {
-            stats[0] = M;
-            stats[1] = Z;
-            stats[2] = xmin;
+    };
+    auto consume = [&](const half8_t (&T)[NV][CG], const float (&qv)[CG], const Step& s) {
+        if (s.g == 0) {
+#pragma unroll
+            for (int v = 0; v < NV; ++v)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) x[v][e] = 0.f;
         }
+        const int cnt = a.r - s.g * CG;                       // columns of this group (CG or more: all)
+#pragma unroll
+        for (int j = 0; j < CG; ++j)
+            if (cnt >= CG || j < cnt) {
+#pragma unroll
+                for (int v = 0; v < NV; ++v)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) x[v][e] = __builtin_fmaf(qv[j], (float)T[v][j][e], x[v][e]);
+            }
+        if (s.g == ng - 1) finish(s.u);
+    };
+
+    const int n = (nunits - (int)blockIdx.y + stride - 1) / stride * ng;   // this block's steps
+    Step sa{(int)blockIdx.y, 0};                              // step whose columns go to A next
+    Step sb = sa;                                             // ... to B next
+    advance(sb);
+    Pages page_a = pages_of(sa), page_b = pages_of(sb);
+    half8_t A[NV][CG], B[NV][CG];
+    int64_t coff[CG];
+    float qa[CG], qb[CG];
+    setup(sa, coff, qa);
+    load(A, sa, page_a, coff);
+    for (int i = 0; i < n; i += 2) {
+        const Step ca = sa, cb = sb;                          // the steps consumed in this round
+        setup(sb, coff, qb);
+        const Step la = sb;
+        advance(sa);
+        advance(sa);
+        const Pages next_a = pages_of(sa);                    // in flight behind B's loads
+        load(B, la, page_b, coff);
+        pin_order();
+        consume(A, qa, ca);
+        setup(sa, coff, qa);
+        advance(sb);
+        advance(sb);
+        page_b = pages_of(sb);
+        page_a = next_a;
+        load(A, sa, page_a, coff);
+        pin_order();
+        if (i + 1 < n) consume(B, qb, cb);
     }
 }
 
-// Maximum, minimum and sum of 2^(x - maximum) of a row from those of its stretches:
-// lane c takes stretch c, every wave (and every block) gets the same values.
+// Maximum, minimum and sum of 2^(x - maximum) of a row from those of its runs of
+// 512 scores: lane c takes run c (then 64 + c ...), every wave (and every block)
+// gets the same values.
 __device__ __forceinline__ void row_stats(const SparfArgs& a, int64_t row, int L, float& M, float& xmin, float& Z)
 {
-    const int nc = (L + kSparfChunk - 1) / kSparfChunk;
-    const float* st = a.stats + row * a.nchunk * 3;
+    const int nc = (L + kSparfStatRun - 1) / kSparfStatRun;
+    const float* st = a.stats + row * a.nstat * 3;
     const int lane = threadIdx.x & 63;
     M = kNegBig;
     xmin = -kNegBig;
@@ -1472,10 +1597,16 @@ hipError_t launch_sparf_logits(const SparfArgs& a, hipStream_t stream)
 {
     // about 1024 blocks (four per compute unit) at most: a block walks several stretches of
     // its head when there are more, and ranks the query once for all of them
+    // about as many blocks as are resident at once (5 per compute unit), so that each
+    // ranks its query once and then streams
     const int64_t heads = (int64_t)a.num_q_heads * a.batch;
-    int per_head = (int)(1024 / heads);
-    per_head = per_head < 1 ? 1 : (per_head > a.nchunk ? a.nchunk : per_head);
-    hipLaunchKernelGGL(sparf_logits_kernel, dim3(a.num_q_heads, per_head, a.batch), dim3(256), 0, stream, a);
+    const int unit = 2048 * (8 / INSTATTN_SPARF_LOGITS_CG);
+    const int nunits = (a.max_len + unit - 1) / unit;
+    int per_head = (int)(1280 / heads);
+    per_head = per_head < 1 ? 1 : (per_head > nunits ? nunits : per_head);
+    const dim3 grid(a.num_q_heads, per_head, a.batch);
+    if (a.aux.page_table) hipLaunchKernelGGL(sparf_logits_kernel<true>, grid, dim3(256), 0, stream, a);
+    else hipLaunchKernelGGL(sparf_logits_kernel<false>, grid, dim3(256), 0, stream, a);
     return hipGetLastError();
 }
 
