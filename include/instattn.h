@@ -257,10 +257,12 @@ size_t instattn_sparf_workspace_size(int batch, int num_q_heads, int head_dim, i
  *               are written per head)
  *   alpha     : device [batch][num_q_heads] fp32 or NULL: receives step 7's alpha
  * L_b <= 0 gives a zero row (alpha 0).  One launch when max_seq_len <= 8192 (one
- * block per query head keeps the scores in LDS), otherwise three to six: column
- * scores, selection (one launch with a block per head, or three with a block per
- * 8192 scores when there are few heads with long rows), attention over the kept
- * rows (plus a launch that combines the slices when a head's kept rows are cut up).
+ * block per query head keeps the scores in LDS), otherwise two to six: column
+ * scores; then either one launch in which a block per head selects and gathers
+ * (many heads, rows below 65536), or selection (one launch with a block per head,
+ * or three with a block per 8192 scores when there are few heads with long rows),
+ * attention over the kept rows, and a launch that combines the slices when a
+ * head's kept rows are cut up.
  * A paged cache is limited to num_pages*page_size < 2^31 rows here
  * (INSTATTN_ERR_UNSUPPORTED beyond).
  */

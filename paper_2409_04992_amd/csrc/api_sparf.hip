@@ -220,6 +220,10 @@ int run_sparf_decode(const void* q, const void* k_new, const void* v_new, bool a
     }
     if (one_launch) return status_of(launch_sparf_fused(a, s));
     if (launch_sparf_logits(a, s) != hipSuccess) return INSTATTN_ERR_RUNTIME;
+    // One block per head and no slices: that block also gathers the rows it kept.
+    const char* split = getenv("INSTATTN_SPARF_SPLIT_TAIL");
+    if (!a.distributed && a.nslices == 1 && max_seq_len < kSparfTailMaxLen && !(split && split[0] == '1'))
+        return status_of(launch_sparf_select_attend(a, s));
     if (launch_sparf_select(a, s) != hipSuccess) return INSTATTN_ERR_RUNTIME;
     return status_of(launch_sparf_attend(a, s));
 }

@@ -68,8 +68,10 @@ hipError_t launch_sparf_append(const SparfArgs& a, hipStream_t stream);
 hipError_t launch_sparf_logits(const SparfArgs& a, hipStream_t stream);
 hipError_t launch_sparf_select(const SparfArgs& a, hipStream_t stream);
 hipError_t launch_sparf_attend(const SparfArgs& a, hipStream_t stream);
+hipError_t launch_sparf_select_attend(const SparfArgs& a, hipStream_t stream);
 hipError_t launch_sparf_fused(const SparfArgs& a, hipStream_t stream);
 
 constexpr int kSparfFusedMaxLen = 8192;   // rows up to this length take the one-launch kernel
+constexpr int kSparfTailMaxLen = 65536;   // rows below this length can be selected and gathered by one block
 
 }  // namespace instattn

@@ -1472,6 +1472,42 @@ __global__ __launch_bounds__(NT, INSTATTN_SPARF_WAVES_PER_SIMD) void sparf_fused
 }
 
 // ---------------------------------------------------------------------------
+// Steps 4 (normaliser) to 11, long rows, one block per head: the selection of
+// sparf_select_kernel on register-resident scores, then the same block gathers the
+// rows it kept.  With many heads the blocks drift apart, and the latency-bound
+// selection of some overlaps the memory-bound gather of others.
+template <int D, int NT, int STEPS>
+__global__ __launch_bounds__(NT) void sparf_select_attend_kernel(SparfArgs a)
+{
+    static_assert(STEPS > 0, "scores in registers");
+    constexpr int NG = (NT / 64) * (kWave / (D / 8));
+    const int h = blockIdx.x, b = blockIdx.y;
+    const int64_t row = (int64_t)b * a.num_q_heads + h;
+    const int L = clamp_len(a.seq_lens[b], a.max_len);
+    if (L == 0) {
+        write_zero_row<D>(a, row);
+        if (threadIdx.x == 0) a.alpha[row] = 0.f;
+        return;
+    }
+    __shared__ SelectScratch S;
+    __shared__ float s_acc[NG][D];
+    __shared__ float s_m[NG];
+    __shared__ float s_l[NG];
+    __shared__ int32_t s_ids[kSparfAttendIds];
+    const float* x = a.logits + row * a.lpad;
+    float xr[STEPS][8];
+    own_scores<NT, STEPS>(x, L, xr);                          // in flight while the statistics are combined
+    float M, xmin, Z;
+    row_stats(a, row, L, M, xmin, Z);
+    int32_t* sel = a.sel + row * a.k;
+    const float alpha = select_rows_reg<NT, STEPS>(xr, x, L, a.k, a.l, M, xmin, Z, sel, S);
+    if (threadIdx.x == 0) a.alpha[row] = alpha;
+    // the barrier in front of the row ids also makes the kept positions visible to the block
+    attend_rows<D, NT / 64>(a, b, h, L, 0, min(a.k, L), sel, alpha, nullptr, s_ids, kSparfAttendIds, s_acc, s_m,
+                            s_l);
+}
+
+// ---------------------------------------------------------------------------
 // Component-major copy of K for rows [0, L_b): one block per stretch of 512 rows of
 // one (sequence, KV head).  A thread loads an 8 x 8 block (8 rows, 16 bytes each),
 // transposes it in registers, and the 16-byte pieces (8 positions of one component)
@@ -1634,6 +1670,32 @@ hipError_t launch_sparf_select(const SparfArgs& a, hipStream_t stream)
     else if (a.max_len < 1024 * 64) INSTATTN_SELECT(1024, 8);   // the packed 16-bit counts hold at most 65535
     else INSTATTN_SELECT(1024, 0);
 #undef INSTATTN_SELECT
+    return hipGetLastError();
+}
+
+template <int D>
+static void launch_select_attend(const SparfArgs& a, hipStream_t stream)
+{
+    dim3 grid(a.num_q_heads, a.batch);
+    // block sizes as in launch_sparf_select
+#define INSTATTN_TAIL(NT, STEPS) \
+    hipLaunchKernelGGL((sparf_select_attend_kernel<D, NT, STEPS>), grid, dim3(NT), 0, stream, a)
+    if (a.max_len <= 256 * 32) INSTATTN_TAIL(256, 4);
+    else if (a.max_len <= 256 * 40) INSTATTN_TAIL(256, 5);
+    else if (a.max_len <= 512 * 32) INSTATTN_TAIL(512, 4);
+    else if (a.max_len <= 512 * 40) INSTATTN_TAIL(512, 5);
+    else if (a.max_len <= 1024 * 32) INSTATTN_TAIL(1024, 4);
+    else if (a.max_len <= 1024 * 40) INSTATTN_TAIL(1024, 5);
+    else INSTATTN_TAIL(1024, 8);
+#undef INSTATTN_TAIL
+}
+
+// Selection and gather of a head in one block; rows shorter than kSparfTailMaxLen,
+// kept rows not sliced.
+hipError_t launch_sparf_select_attend(const SparfArgs& a, hipStream_t stream)
+{
+    if (a.head_dim == 128) launch_select_attend<128>(a, stream);
+    else launch_select_attend<64>(a, stream);
     return hipGetLastError();
 }
 

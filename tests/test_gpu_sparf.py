@@ -259,6 +259,33 @@ def test_sparf_long_rows_take_the_three_launch_pipeline(monkeypatch, seq_len, k,
     sparf_step(wl, 16, k, 32, torch.float16)
 
 
+@pytest.mark.parametrize("seq_len,k,head_dim", [(8192, 100, 128), (10000, 450, 64), (16000, 400, 128),
+                                                (20000, 511, 128), (32767, 500, 64), (40000, 300, 128),
+                                                (65534, 200, 128), (65534, 480, 64)])
+@pytest.mark.parametrize("split_tail", ["0", "1"])
+def test_sparf_long_rows_selected_and_gathered_by_one_block(monkeypatch, seq_len, k, head_dim, split_tail):
+    """Few kept rows per head (no slices), one block per head: that block selects and
+    then gathers (two launches in all), or, forced here, the selection and the gather
+    stay kernels of their own.  Every block size of the selection."""
+    monkeypatch.setenv("INSTATTN_SPARF_DISTRIBUTED", "0")
+    monkeypatch.setenv("INSTATTN_SPARF_SPLIT_TAIL", split_tail)
+    wl = W.Workload("sparf_tail", 2, 3, 3, head_dim, seq_len, seq_len_min=seq_len // 2, seed=414)
+    sparf_step(wl, head_dim // 8, k, 16, torch.float16)
+
+
+def test_sparf_one_block_tail_equals_the_two_kernels(monkeypatch):
+    wl = W.Workload("sparf_tail_eq", 3, 4, 2, 128, 12000, seq_len_min=0, paged=True, page_size=16, seed=415)
+    case, desc, aux, kt, vsum, _ = setup(wl, kt_page=256)
+    B.sparf_append(desc, aux, case.k_new, case.v_new, case.seq_lens)
+    monkeypatch.setenv("INSTATTN_SPARF_DISTRIBUTED", "0")
+    monkeypatch.setenv("INSTATTN_SPARF_SPLIT_TAIL", "1")
+    a = run_decode(case, desc, aux, 16, 300, 16, torch.float32)
+    monkeypatch.setenv("INSTATTN_SPARF_SPLIT_TAIL", "0")
+    b = run_decode(case, desc, aux, 16, 300, 16, torch.float32)
+    assert torch.equal(a[1], b[1]) and torch.equal(a[2], b[2])       # same kept rows, same alpha
+    assert (a[0] - b[0]).abs().max() <= 2e-6
+
+
 def test_sparf_distributed_selection_equals_one_block_per_head(monkeypatch):
     """Same kept rows bit for bit, alpha and out up to the order of the mass sum; ragged
     lengths so that heads use different numbers of stretches; repeated (the gathered
