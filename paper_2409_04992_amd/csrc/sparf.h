@@ -7,7 +7,6 @@ namespace instattn {
 
 constexpr int kSparfChunk = 8192;      // positions per block of the approximate-score pass
 constexpr int kSparfStatRun = 512;     // scores per entry of the score statistics (a wave's share of a unit)
-constexpr int kSparfSelectThreads = 1024;
 constexpr int kSparfAttendWaves = 8;
 constexpr int kSparfMemberCap = 1024;  // members of the threshold bin the distributed selection ranks directly
 constexpr int kSparfMaxSlices = 8;      // most slices the attend kernel cuts a head's kept rows into
