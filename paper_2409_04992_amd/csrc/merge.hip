@@ -198,7 +198,8 @@ __global__ __launch_bounds__(256) void probe_copy_kernel(const u32x4* src, u32x4
 hipError_t launch_probe_read(const void* src, size_t bytes, void* sink, hipStream_t stream)
 {
     const size_t nseg = (bytes / 16 + kProbeSeg16 - 1) / kProbeSeg16;
-    const unsigned blocks = (unsigned)(nseg < 65536 ? nseg : 65536);
+    // as many blocks as are resident at once (5 per compute unit); each walks its segments
+    const unsigned blocks = (unsigned)(nseg < 1280 ? nseg : 1280);
     hipLaunchKernelGGL(probe_read_kernel, dim3(blocks), dim3(256), 0, stream,
                        (const u32x4*)src, bytes / 16, (uint32_t*)sink);
     return hipGetLastError();
