@@ -256,8 +256,9 @@ size_t instattn_sparf_workspace_size(int batch, int num_q_heads, int head_dim, i
  *               positions of every head in ascending order (min(k, L_b) entries
  *               are written per head)
  *   alpha     : device [batch][num_q_heads] fp32 or NULL: receives step 7's alpha
- * L_b <= 0 gives a zero row (alpha 0).  One launch when max_seq_len <= 8192 (one
- * block per query head keeps the scores in LDS), otherwise two to six: column
+ * L_b <= 0 gives a zero row (alpha 0).  One launch when max_seq_len <= 8192, or
+ * <= 18432 with at least 128 (sequence, query head) pairs (one block per query head
+ * keeps the scores in LDS), otherwise two to six: column
  * scores; then either one launch in which a block per head selects and gathers
  * (many heads, rows below 65536), or selection (one launch with a block per head,
  * or three with a block per 8192 scores when there are few heads with long rows),
@@ -276,8 +277,8 @@ int instattn_sparf_decode(const void* q, const instattn_kv_desc* kv, const insta
  * instattn_sparf_append followed by instattn_sparf_decode, as the storage side sees
  * a decode step (the new token's q, k, v arrive together, Sec. IV-D): same results
  * in the cache, in aux and in out/sel_rows/alpha as the two calls in that order.
- * When max_seq_len <= 8192 and every KV head has one query head, the one launch of
- * the decode stores the new token itself; otherwise the append is a launch of its
+ * When the decode is one launch (see above) and every KV head has one query head,
+ * that launch stores the new token itself; otherwise the append is a launch of its
  * own in front.  Like instattn_sparf_append it must be called once per new token.
  *   k_new, v_new : device, [batch][num_kv_heads][head_dim] fp16, dense, 16-byte aligned
  */

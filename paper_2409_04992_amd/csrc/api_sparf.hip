@@ -211,7 +211,14 @@ int run_sparf_decode(const void* q, const void* k_new, const void* v_new, bool a
     a.v_new = append ? (const half_t*)v_new : nullptr;
     hipStream_t s = (hipStream_t)stream;
     const char* force3 = getenv("INSTATTN_SPARF_THREE_LAUNCHES");
-    const bool one_launch = max_seq_len <= kSparfFusedMaxLen && !(force3 && force3[0] == '1');
+    // Rows behind the 256-thread form's limit take the one-launch kernel's 512-thread form
+    // when there are heads enough for one block each (measured at 16K rows: 160 heads
+    // 52 us against the pipeline's 63, 40 heads 44 against 40; INSTATTN_SPARF_WIDE forces
+    // either way).
+    const char* wide_env = getenv("INSTATTN_SPARF_WIDE");
+    const bool wide = max_seq_len > kSparfFusedMaxLen && max_seq_len <= kSparfFusedWideMaxLen &&
+                      (wide_env ? wide_env[0] == '1' : (int64_t)batch * num_q_heads >= 128);
+    const bool one_launch = (max_seq_len <= kSparfFusedMaxLen || wide) && !(force3 && force3[0] == '1');
     // The one-launch kernel stores the new token itself when its block is the only
     // reader of what it stores; otherwise the append is a launch of its own.
     if (append && !(one_launch && num_q_heads == num_kv_heads)) {

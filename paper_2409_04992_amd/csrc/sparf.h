@@ -70,7 +70,22 @@ hipError_t launch_sparf_attend(const SparfArgs& a, hipStream_t stream);
 hipError_t launch_sparf_select_attend(const SparfArgs& a, hipStream_t stream);
 hipError_t launch_sparf_fused(const SparfArgs& a, hipStream_t stream);
 
-constexpr int kSparfFusedMaxLen = 8192;   // rows up to this length take the one-launch kernel
+constexpr int kSparfFusedMaxLen = 8192;   // rows up to this length take the one-launch kernel with 256 threads
+// ... and up to this length its form with 512 threads, when there are heads enough to
+// fill the chip with one block each (two blocks of 72 KB of LDS + 8 KB fit a compute unit)
+constexpr int kSparfFusedWideMaxLen = 18432;
+
+// Floats at the end of the one-launch kernel's dynamic LDS that take the partial
+// sums of the gather (NG row groups of D sums, a maximum and a weight each) ...
+__host__ __device__ constexpr int sparf_fused_acc_floats(int ng, int d) { return ng * d + 2 * ng; }
+// ... and the size of that LDS: one score per position, and never less than those
+// sums plus room for 1024 row ids.
+__host__ __device__ constexpr int sparf_fused_lds_floats(int max_len, int ng, int d)
+{
+    const int scores = (max_len + 7) / 8 * 8;
+    const int least = sparf_fused_acc_floats(ng, d) + 1024;
+    return scores > least ? scores : least;
+}
 constexpr int kSparfTailMaxLen = 65536;   // rows below this length can be selected and gathered by one block
 
 }  // namespace instattn

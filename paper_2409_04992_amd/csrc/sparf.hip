@@ -161,13 +161,12 @@ __device__ __forceinline__ float prepare_query(const SparfArgs& a, int64_t row, 
 // is issued unconditionally (steps behind the row's end re-read its last 8
 // positions, a cache hit) so that the count of loads in flight is known at every
 // wait.  first: xs is written, not added to.
-template <int CG, int NT>
+template <int CG, int NT, int STEPS>
 __device__ __forceinline__ void column_pass(const SparfArgs& a, int b, int hk, int t_base, int L, int j0,
                                             bool first, float factor, const float* s_q, const int* s_dim,
                                             float* xs)
 {
-    constexpr int STEPS = kSparfFusedMaxLen / (NT * 8);
-    static_assert(STEPS * NT * 8 == kSparfFusedMaxLen && STEPS % 2 == 0, "whole, even number of steps");
+
     int64_t coff[CG];
     float qv[CG];
 #pragma unroll
@@ -210,12 +209,12 @@ __device__ __forceinline__ void column_pass(const SparfArgs& a, int b, int hk, i
 #pragma unroll
     for (int i = 0; i < STEPS; i += 2) {
         if (i * NT * 8 >= L) break;                  // block-uniform: the row ended before this pair of steps
-        load(B, p0[i + 1]);
+        if (i + 1 < STEPS) load(B, p0[i + 1]);
         pin_order();
         consume(A, i);
         if (i + 2 < STEPS) load(A, p0[i + 2]);
         pin_order();
-        consume(B, i + 1);
+        if (i + 1 < STEPS) consume(B, i + 1);
     }
 }
 
@@ -260,26 +259,27 @@ __device__ __forceinline__ void locate_bin(SelectScratch& S, uint32_t remaining,
     }
 }
 
-// All kept columns of one stretch of at most kSparfFusedMaxLen positions, in groups
+// All kept columns of one stretch of at most STEPS * NT * 8 positions, in groups
 // of INSTATTN_SPARF_CGMAX columns, then halves of that down to one.
-template <int CG, int NT>
+template <int CG, int NT, int STEPS>
 __device__ __forceinline__ void column_groups(const SparfArgs& a, int b, int hk, int t_base, int L, float factor,
                                               const float* s_q, const int* s_dim, float* xs, int& j0)
 {
     if constexpr (CG <= INSTATTN_SPARF_CGMAX)
-        for (; a.r - j0 >= CG; j0 += CG) column_pass<CG, NT>(a, b, hk, t_base, L, j0, j0 == 0, factor, s_q, s_dim, xs);
+        for (; a.r - j0 >= CG; j0 += CG)
+            column_pass<CG, NT, STEPS>(a, b, hk, t_base, L, j0, j0 == 0, factor, s_q, s_dim, xs);
 }
 
-template <int NT>
+template <int NT, int STEPS>
 __device__ __forceinline__ void column_passes(const SparfArgs& a, int b, int hk, int t_base, int L, float factor,
                                               const float* s_q, const int* s_dim, float* xs)
 {
     int j0 = 0;
-    column_groups<16, NT>(a, b, hk, t_base, L, factor, s_q, s_dim, xs, j0);
-    column_groups<8, NT>(a, b, hk, t_base, L, factor, s_q, s_dim, xs, j0);
-    column_groups<4, NT>(a, b, hk, t_base, L, factor, s_q, s_dim, xs, j0);
-    column_groups<2, NT>(a, b, hk, t_base, L, factor, s_q, s_dim, xs, j0);
-    column_groups<1, NT>(a, b, hk, t_base, L, factor, s_q, s_dim, xs, j0);
+    column_groups<16, NT, STEPS>(a, b, hk, t_base, L, factor, s_q, s_dim, xs, j0);
+    column_groups<8, NT, STEPS>(a, b, hk, t_base, L, factor, s_q, s_dim, xs, j0);
+    column_groups<4, NT, STEPS>(a, b, hk, t_base, L, factor, s_q, s_dim, xs, j0);
+    column_groups<2, NT, STEPS>(a, b, hk, t_base, L, factor, s_q, s_dim, xs, j0);
+    column_groups<1, NT, STEPS>(a, b, hk, t_base, L, factor, s_q, s_dim, xs, j0);
 }
 
 // The scores of positions (i * NT + tid) * 8 + e, e < 8, of a row of L scores at x
@@ -824,10 +824,10 @@ __device__ __forceinline__ void attend_rows(const SparfArgs& a, int b, int h, in
     __syncthreads();
     if (tid < D) {
         float M = kNegBig;
-#pragma unroll
+#pragma unroll 8
         for (int i = 0; i < NG; ++i) M = fmaxf(M, s_m[i]);
         float lsum = 0.f, o = 0.f;
-#pragma unroll
+#pragma unroll 8
         for (int i = 0; i < NG; ++i) {
             const float w = fast_exp2(s_m[i] - M);
             lsum += w * s_l[i];
@@ -1405,8 +1405,12 @@ __global__ __launch_bounds__(D) void sparf_merge_kernel(SparfArgs a)
 }
 
 // The whole of Algorithm 1 for one query head in one block of NT threads; the
-// scores live in dynamic LDS (one float per position, rows of at most 8192).
-template <int D, int NT>
+// scores live in dynamic LDS (one float per position, rows of at most
+// STEPS * NT * 8 positions).  Two forms: 256 threads for rows up to 8192 (four blocks
+// per compute unit) and 512 threads for rows up to kSparfFusedWideMaxLen (two blocks
+// per compute unit: 72 KB of LDS each).  Once the scores are dead the same LDS holds
+// the row ids of the gather and, at its end, the partial sums of its waves.
+template <int D, int NT, int STEPS>
 __global__ __launch_bounds__(NT, INSTATTN_SPARF_WAVES_PER_SIMD) void sparf_fused_kernel(SparfArgs a)
 {
     constexpr int NG = (NT / 64) * (kWave / (D / 8));
@@ -1420,9 +1424,12 @@ __global__ __launch_bounds__(NT, INSTATTN_SPARF_WAVES_PER_SIMD) void sparf_fused
     __shared__ __align__(16) float s_abs[128];
     __shared__ int s_dim[128];
     __shared__ SelectScratch S;
-    __shared__ float s_acc[NG][D];
-    __shared__ float s_m[NG];
-    __shared__ float s_l[NG];
+    // the gather's partial sums sit at the end of the dynamic LDS, its row ids in front
+    const int lds_floats = sparf_fused_lds_floats(a.max_len, NG, D);
+    const int ids_cap = lds_floats - sparf_fused_acc_floats(NG, D);
+    float(*s_acc)[D] = (float(*)[D])(xs + ids_cap);
+    float* s_m = xs + ids_cap + NG * D;
+    float* s_l = s_m + NG;
 
     // steps 1-4; the length is not needed before the column pass, so its load and
     // the load of q are in flight together
@@ -1440,7 +1447,7 @@ __global__ __launch_bounds__(NT, INSTATTN_SPARF_WAVES_PER_SIMD) void sparf_fused
         if (tid == 0) a.alpha[row] = 0.f;
         return;
     }
-    column_passes<NT>(a, b, hk, 0, L, factor, s_q, s_dim, xs);
+    column_passes<NT, STEPS>(a, b, hk, 0, L, factor, s_q, s_dim, xs);
     if (fresh && t_new < L && tid == ((t_new >> 3) % NT)) {
         // the score of the new position, from k_new, by the thread that owns it and with
         // the arithmetic of the column pass
@@ -1453,7 +1460,6 @@ __global__ __launch_bounds__(NT, INSTATTN_SPARF_WAVES_PER_SIMD) void sparf_fused
         xs[t_new] = x;
     }
     // the thread's own scores stay in registers for the rest of steps 4-7
-    constexpr int STEPS = kSparfFusedMaxLen / (NT * 8);
     float xr[STEPS][8];
     own_scores<NT, STEPS>(xs, L, xr);
     float M, xmin, Z;
@@ -1466,8 +1472,8 @@ __global__ __launch_bounds__(NT, INSTATTN_SPARF_WAVES_PER_SIMD) void sparf_fused
 
     // steps 10-11; the scores are dead, their LDS takes the row ids (the barrier
     // in front of that also makes the kept positions visible to the whole block)
-    attend_rows<D, NT / 64>(a, b, h, L, 0, min(a.k, L), sel, alpha, nullptr, (int32_t*)xs, (L + 7) & ~7, s_acc,
-                            s_m, s_l, fresh, t_new);
+    attend_rows<D, NT / 64>(a, b, h, L, 0, min(a.k, L), sel, alpha, nullptr, (int32_t*)xs, ids_cap, s_acc, s_m, s_l,
+                            fresh, t_new);
     if (fresh && tid < D) append_component(a, b, hk, tid, L_raw);
 }
 
@@ -1699,13 +1705,26 @@ hipError_t launch_sparf_select_attend(const SparfArgs& a, hipStream_t stream)
     return hipGetLastError();
 }
 
+template <int D, int NT, int STEPS>
+static hipError_t launch_fused(const SparfArgs& a, hipStream_t stream)
+{
+    constexpr int NG = (NT / 64) * (kWave / (D / 8));
+    const size_t lds = (size_t)sparf_fused_lds_floats(a.max_len, NG, D) * sizeof(float);
+    auto kernel = sparf_fused_kernel<D, NT, STEPS>;
+    if (lds > 48 * 1024) {
+        // more dynamic LDS than a launch gets by default
+        const hipError_t e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(kernel, dim3(a.num_q_heads, a.batch), dim3(NT), lds, stream, a);
+    return hipGetLastError();
+}
+
 hipError_t launch_sparf_fused(const SparfArgs& a, hipStream_t stream)
 {
-    dim3 grid(a.num_q_heads, a.batch);
-    const size_t lds = (size_t)((a.max_len + 7) / 8 * 8) * sizeof(float);
-    if (a.head_dim == 128) hipLaunchKernelGGL((sparf_fused_kernel<128, 256>), grid, dim3(256), lds, stream, a);
-    else hipLaunchKernelGGL((sparf_fused_kernel<64, 256>), grid, dim3(256), lds, stream, a);
-    return hipGetLastError();
+    if (a.max_len <= kSparfFusedMaxLen)
+        return a.head_dim == 128 ? launch_fused<128, 256, 4>(a, stream) : launch_fused<64, 256, 4>(a, stream);
+    return a.head_dim == 128 ? launch_fused<128, 512, 5>(a, stream) : launch_fused<64, 512, 5>(a, stream);
 }
 
 hipError_t launch_sparf_attend(const SparfArgs& a, hipStream_t stream)

@@ -286,6 +286,33 @@ def test_sparf_one_block_tail_equals_the_two_kernels(monkeypatch):
     assert (a[0] - b[0]).abs().max() <= 2e-6
 
 
+@pytest.mark.parametrize("seq_len,k,head_dim,paged,fused", [
+    (8192, 300, 128, False, True), (8200, 600, 64, True, False), (12000, 13000, 128, True, True),
+    (16384, 1024, 128, False, True), (16385, 1, 64, False, True), (18431, 2000, 128, True, False),
+    (18430, 5000, 64, False, True)])
+def test_sparf_one_launch_kernel_of_512_threads(monkeypatch, seq_len, k, head_dim, paged, fused):
+    """Rows between 8193 and 18432 positions in the one-launch kernel's wide form (forced
+    here: with few heads the host would pick the pipeline), with and without the append
+    inside it, up to the longest row it takes; kept rows beyond the room for row ids in
+    LDS go through in pieces."""
+    monkeypatch.setenv("INSTATTN_SPARF_WIDE", "1")
+    wl = W.Workload("sparf_wide", 2, 3, 3, head_dim, seq_len, seq_len_min=seq_len - 9000, paged=paged,
+                    page_size=16, seed=416)
+    sparf_step(wl, head_dim // 8, k, 16, torch.float32, kt_page=256 if paged else None, fused_append=fused)
+
+
+def test_sparf_wide_one_launch_equals_the_pipeline(monkeypatch):
+    wl = W.Workload("sparf_wide_eq", 2, 4, 2, 128, 15000, seq_len_min=9000, seed=417)
+    case, desc, aux, kt, vsum, _ = setup(wl)
+    B.sparf_append(desc, aux, case.k_new, case.v_new, case.seq_lens)
+    monkeypatch.setenv("INSTATTN_SPARF_WIDE", "1")
+    a = run_decode(case, desc, aux, 16, 900, 16, torch.float32)
+    monkeypatch.setenv("INSTATTN_SPARF_WIDE", "0")
+    b = run_decode(case, desc, aux, 16, 900, 16, torch.float32)
+    assert torch.equal(a[1], b[1])                                   # same kept rows
+    assert (a[0] - b[0]).abs().max() <= 2e-6 and (a[2] - b[2]).abs().max() <= 1e-6
+
+
 def test_sparf_distributed_selection_equals_one_block_per_head(monkeypatch):
     """Same kept rows bit for bit, alpha and out up to the order of the mass sum; ragged
     lengths so that heads use different numbers of stretches; repeated (the gathered
@@ -336,7 +363,12 @@ def test_sparf_distributed_edge_lengths(monkeypatch):
         check_against_oracle(case, out, sel, alpha, 8, k, l)
 
 
-def test_sparf_long_rows_many_heads_no_slices():
+@pytest.mark.parametrize("wide", ["0", "1"])
+def test_sparf_long_rows_many_heads_no_slices(monkeypatch, wide):
+    """1040 heads of up to 9001 positions: the pipeline (score pass, then one block per
+    head that selects and gathers), or the one-launch kernel's 512-thread form (the
+    host's choice for this shape)."""
+    monkeypatch.setenv("INSTATTN_SPARF_WIDE", wide)
     wl = W.Workload("sparf_long_many", 26, 40, 40, 64, 9000, seq_len_min=100, seed=413)
     pairs = [(0, 0), (25, 39), (13, 7), (5, 20)]
     sparf_step(wl, 8, 300, 4, torch.float16, pairs=pairs)
