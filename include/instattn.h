@@ -245,6 +245,23 @@ int instattn_sparf_append(const instattn_kv_desc* kv, const instattn_sparf_aux* 
                           const void* k_new, const void* v_new, const int32_t* seq_lens,
                           int batch, int num_kv_heads, int head_dim, void* stream);
 
+/*
+ * Which kernels instattn_sparf_decode (with_append = 0) or
+ * instattn_sparf_append_decode (with_append = 1) launches for these sizes: host
+ * arithmetic only, no device access (the choices are the implementation's, not
+ * the paper's; they depend on the arguments and on the INSTATTN_SPARF_*
+ * environment switches that force a form for tests).  plan: host, 6 int32:
+ *   [0] kernel launches in all
+ *   [1] threads per block of the one-launch kernel (256 or 512), 0 if the row is
+ *       too long for it and the pipeline runs
+ *   [2] 1 if the decode's launch stores the new token itself
+ *   [3] pipeline only: 1 = one block per head selects, 2 = one block per 8192 scores
+ *   [4] pipeline only: 1 if the block that selects also gathers the kept rows
+ *   [5] slices a head's kept rows are gathered in
+ */
+int instattn_sparf_plan(int batch, int num_q_heads, int num_kv_heads, int head_dim, int max_seq_len,
+                        int k, int with_append, int32_t* plan);
+
 /* Bytes of device workspace instattn_sparf_decode needs (0 if the arguments are invalid). */
 size_t instattn_sparf_workspace_size(int batch, int num_q_heads, int head_dim, int max_seq_len,
                                      int k);

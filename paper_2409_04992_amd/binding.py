@@ -89,6 +89,8 @@ def lib() -> ctypes.CDLL:
         L.instattn_sparf_build.argtypes = [pk, pa, vp, i, i, i, vp]
         L.instattn_sparf_append.restype = i
         L.instattn_sparf_append.argtypes = [pk, pa, vp, vp, vp, i, i, i, vp]
+        L.instattn_sparf_plan.restype = i
+        L.instattn_sparf_plan.argtypes = [i, i, i, i, i, i, i, ctypes.POINTER(ctypes.c_int32)]
         L.instattn_sparf_workspace_size.restype = sz
         L.instattn_sparf_workspace_size.argtypes = [i, i, i, i, i]
         L.instattn_sparf_append_decode.restype = i
@@ -280,6 +282,16 @@ def sparf_append(desc: KvDesc, aux: SparfAux, k_new, v_new, seq_lens, stream=Non
     _check(lib().instattn_sparf_append(ctypes.byref(desc), ctypes.byref(aux), _p(k_new), _p(v_new),
                                        _p(seq_lens), B, Hkv, D, _stream(stream)),
            "instattn_sparf_append")
+
+
+def sparf_plan(batch: int, num_q_heads: int, num_kv_heads: int, head_dim: int, max_seq_len: int,
+               k: int, with_append: bool = False) -> dict:
+    """What a SparF decode of these sizes launches (host arithmetic only)."""
+    out = (ctypes.c_int32 * 6)()
+    _check(lib().instattn_sparf_plan(batch, num_q_heads, num_kv_heads, head_dim, max_seq_len, k,
+                                     int(with_append), out), "instattn_sparf_plan")
+    return {"launches": out[0], "one_launch_threads": out[1], "append_fused": bool(out[2]),
+            "selection": out[3], "select_and_gather": bool(out[4]), "slices": out[5]}
 
 
 def sparf_workspace_size(batch: int, num_q_heads: int, head_dim: int, max_seq_len: int,

@@ -42,6 +42,66 @@ Carve carve(int batch, int num_q_heads, int head_dim, int max_seq_len, int k)
     return c;
 }
 
+// Which kernels a decode of these sizes launches: host arithmetic only.
+struct SparfPlan {
+    bool one_launch;      // sparf_fused_kernel does everything
+    bool wide;            // ... in its 512-thread form
+    bool append_fused;    // the decode's launch stores the new token itself
+    bool distributed;     // selection spread over one block per stretch (three launches)
+    bool fused_tail;      // one block per head selects and gathers
+    int nslices, slice_rows;
+    int launches;
+};
+
+SparfPlan plan_sparf(int batch, int num_q_heads, int num_kv_heads, int max_seq_len, int k, bool append)
+{
+    SparfPlan p = {};
+    const int64_t heads = (int64_t)batch * num_q_heads;
+    const int nchunk = (max_seq_len + kSparfChunk - 1) / kSparfChunk;
+    // One block per head selects well when there are heads enough to fill the chip or
+    // the rows are short; few heads with long rows spread each head's selection over
+    // its stretches (three launches).  Measured: one block takes about max_len / 1100
+    // us per round of 256 heads, the distributed form 24 us + 0.015 us per block.
+    {
+        const double one_block = max_seq_len / 1100.0 * (double)((heads + 255) / 256);
+        const double spread = 24.0 + 0.015 * (double)heads * nchunk;
+        const char* e = getenv("INSTATTN_SPARF_DISTRIBUTED");
+        p.distributed = e ? (e[0] == '1') : (max_seq_len > 2 * kSparfChunk && heads <= 512 && spread < one_block);
+    }
+    // Slices of a head's kept rows for the attend kernel: enough blocks to fill the
+    // chip when there are few heads, none smaller than 256 rows.
+    {
+        const int kept = k < max_seq_len ? k : max_seq_len;      // no head keeps more rows than it has
+        int ns = (int)((1024 + heads - 1) / heads);
+        ns = ns < kept / 256 ? ns : kept / 256;
+        ns = ns < 1 ? 1 : (ns > kSparfMaxSlices ? kSparfMaxSlices : ns);
+        p.nslices = ns;
+        p.slice_rows = ((kept + ns - 1) / ns + 15) / 16 * 16;
+    }
+    const char* force3 = getenv("INSTATTN_SPARF_THREE_LAUNCHES");
+    // Rows behind the 256-thread form's limit take the one-launch kernel's 512-thread form
+    // when there are heads enough for one block each (measured at 16K rows: 160 heads
+    // 52 us against the pipeline's 63, 40 heads 44 against 40; INSTATTN_SPARF_WIDE forces
+    // either way).
+    const char* wide_env = getenv("INSTATTN_SPARF_WIDE");
+    p.wide = max_seq_len > kSparfFusedMaxLen && max_seq_len <= kSparfFusedWideMaxLen &&
+             (wide_env ? wide_env[0] == '1' : heads >= 128);
+    p.one_launch = (max_seq_len <= kSparfFusedMaxLen || p.wide) && !(force3 && force3[0] == '1');
+    if (!p.one_launch) p.wide = false;
+    // The one-launch kernel stores the new token itself when its block is the only
+    // reader of what it stores; otherwise the append is a launch of its own.
+    p.append_fused = append && p.one_launch && num_q_heads == num_kv_heads;
+    // One block per head and no slices: that block also gathers the rows it kept.
+    const char* split = getenv("INSTATTN_SPARF_SPLIT_TAIL");
+    p.fused_tail = !p.one_launch && !p.distributed && p.nslices == 1 && max_seq_len < kSparfTailMaxLen &&
+                   !(split && split[0] == '1');
+    p.launches = (append && !p.append_fused) ? 1 : 0;
+    if (p.one_launch) p.launches += 1;
+    else if (p.fused_tail) p.launches += 2;
+    else p.launches += 1 + (p.distributed ? 3 : 1) + 1 + (p.nslices > 1 ? 1 : 0);
+    return p;
+}
+
 int check_common(const instattn_kv_desc* kv, const instattn_sparf_aux* aux, int batch, int num_kv_heads,
                  int head_dim)
 {
@@ -124,6 +184,23 @@ int instattn_sparf_append(const instattn_kv_desc* kv, const instattn_sparf_aux* 
     return status_of(launch_sparf_append(a, (hipStream_t)stream));
 }
 
+int instattn_sparf_plan(int batch, int num_q_heads, int num_kv_heads, int head_dim, int max_seq_len, int k,
+                        int with_append, int32_t* plan)
+{
+    if (!plan || batch <= 0 || num_q_heads <= 0 || num_kv_heads <= 0 || num_q_heads % num_kv_heads ||
+        max_seq_len <= 0 || k <= 0)
+        return INSTATTN_ERR_INVALID_ARG;
+    if (head_dim != 64 && head_dim != 128) return head_dim > 0 ? INSTATTN_ERR_UNSUPPORTED : INSTATTN_ERR_INVALID_ARG;
+    const SparfPlan p = plan_sparf(batch, num_q_heads, num_kv_heads, max_seq_len, k, with_append != 0);
+    plan[0] = p.launches;
+    plan[1] = p.one_launch ? (p.wide ? 512 : 256) : 0;
+    plan[2] = p.append_fused;
+    plan[3] = p.one_launch ? 0 : (p.distributed ? 2 : 1);
+    plan[4] = p.fused_tail;
+    plan[5] = p.one_launch || p.fused_tail ? 1 : p.nslices;
+    return INSTATTN_OK;
+}
+
 size_t instattn_sparf_workspace_size(int batch, int num_q_heads, int head_dim, int max_seq_len, int k)
 {
     if (batch <= 0 || num_q_heads <= 0 || max_seq_len <= 0 || k <= 0) return 0;
@@ -183,54 +260,22 @@ int run_sparf_decode(const void* q, const void* k_new, const void* v_new, bool a
     a.state = (uint32_t*)(ws + c.state);
     a.members = (uint32_t*)(ws + c.members);
     a.mass_part = (float*)(ws + c.mass_part);
-    // One block per head selects well when there are heads enough to fill the chip or
-    // the rows are short; few heads with long rows spread each head's selection over
-    // its stretches (three launches).  Measured: one block takes about max_len / 1100
-    // us per round of 256 heads, the distributed form 24 us + 0.015 us per block.
-    {
-        const int64_t heads = (int64_t)batch * num_q_heads;
-        const double one_block = max_seq_len / 1100.0 * (double)((heads + 255) / 256);
-        const double spread = 24.0 + 0.015 * (double)heads * c.nchunk;
-        const char* e = getenv("INSTATTN_SPARF_DISTRIBUTED");
-        a.distributed = e ? (e[0] == '1') : (max_seq_len > 2 * kSparfChunk && heads <= 512 && spread < one_block);
-    }
-    // Slices of a head's kept rows for the attend kernel: enough blocks to fill the
-    // chip when there are few heads, none smaller than 256 rows.
-    {
-        const int64_t heads = (int64_t)batch * num_q_heads;
-        const int kept = k < max_seq_len ? k : max_seq_len;      // no head keeps more rows than it has
-        int ns = (int)((1024 + heads - 1) / heads);
-        ns = ns < kept / 256 ? ns : kept / 256;
-        ns = ns < 1 ? 1 : (ns > kSparfMaxSlices ? kSparfMaxSlices : ns);
-        a.nslices = ns;
-        a.slice_rows = ((kept + ns - 1) / ns + 15) / 16 * 16;
-    }
+    const SparfPlan plan = plan_sparf(batch, num_q_heads, num_kv_heads, max_seq_len, k, append);
+    a.distributed = plan.distributed;
+    a.nslices = plan.nslices;
+    a.slice_rows = plan.slice_rows;
     a.out = out;
     a.out_f32 = out_dtype == INSTATTN_F32;
     a.k_new = append ? (const half_t*)k_new : nullptr;
     a.v_new = append ? (const half_t*)v_new : nullptr;
     hipStream_t s = (hipStream_t)stream;
-    const char* force3 = getenv("INSTATTN_SPARF_THREE_LAUNCHES");
-    // Rows behind the 256-thread form's limit take the one-launch kernel's 512-thread form
-    // when there are heads enough for one block each (measured at 16K rows: 160 heads
-    // 52 us against the pipeline's 63, 40 heads 44 against 40; INSTATTN_SPARF_WIDE forces
-    // either way).
-    const char* wide_env = getenv("INSTATTN_SPARF_WIDE");
-    const bool wide = max_seq_len > kSparfFusedMaxLen && max_seq_len <= kSparfFusedWideMaxLen &&
-                      (wide_env ? wide_env[0] == '1' : (int64_t)batch * num_q_heads >= 128);
-    const bool one_launch = (max_seq_len <= kSparfFusedMaxLen || wide) && !(force3 && force3[0] == '1');
-    // The one-launch kernel stores the new token itself when its block is the only
-    // reader of what it stores; otherwise the append is a launch of its own.
-    if (append && !(one_launch && num_q_heads == num_kv_heads)) {
+    if (append && !plan.append_fused) {
         if (launch_sparf_append(a, s) != hipSuccess) return INSTATTN_ERR_RUNTIME;
         a.k_new = a.v_new = nullptr;
     }
-    if (one_launch) return status_of(launch_sparf_fused(a, s));
+    if (plan.one_launch) return status_of(launch_sparf_fused(a, s));
     if (launch_sparf_logits(a, s) != hipSuccess) return INSTATTN_ERR_RUNTIME;
-    // One block per head and no slices: that block also gathers the rows it kept.
-    const char* split = getenv("INSTATTN_SPARF_SPLIT_TAIL");
-    if (!a.distributed && a.nslices == 1 && max_seq_len < kSparfTailMaxLen && !(split && split[0] == '1'))
-        return status_of(launch_sparf_select_attend(a, s));
+    if (plan.fused_tail) return status_of(launch_sparf_select_attend(a, s));
     if (launch_sparf_select(a, s) != hipSuccess) return INSTATTN_ERR_RUNTIME;
     return status_of(launch_sparf_attend(a, s));
 }

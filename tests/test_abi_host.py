@@ -26,6 +26,7 @@ def test_library_exports_every_declared_symbol():
             "instattn_status_string", "instattn_version", "instattn_probe_read",
             "instattn_append_decode", "instattn_kv_write", "instattn_sparf_build", "instattn_sparf_append",
             "instattn_sparf_decode", "instattn_sparf_workspace_size", "instattn_sparf_append_decode",
+            "instattn_sparf_plan",
             "instattn_probe_copy"} <= set(names)
     lib = B.lib()
     for n in names:
@@ -269,3 +270,86 @@ def test_kv_write_rejects():
         args = list(ok)
         args[idx] = bad
         assert L.instattn_kv_write(*args) == want, idx
+
+
+# ------------------------------------------------------------------ what a SparF decode launches
+SPARF_ENV = ("INSTATTN_SPARF_THREE_LAUNCHES", "INSTATTN_SPARF_WIDE", "INSTATTN_SPARF_SPLIT_TAIL",
+             "INSTATTN_SPARF_DISTRIBUTED")
+
+
+@pytest.fixture
+def no_sparf_env(monkeypatch):
+    for name in SPARF_ENV:
+        monkeypatch.delenv(name, raising=False)
+    return monkeypatch
+
+
+def test_sparf_plan_of_the_measured_shapes(no_sparf_env):
+    # 16 x 40 heads x 4K: everything in one launch of 256 threads per head, append included
+    p = B.sparf_plan(16, 40, 40, 128, 4097, 256, with_append=True)
+    assert p == {"launches": 1, "one_launch_threads": 256, "append_fused": True, "selection": 0,
+                 "select_and_gather": False, "slices": 1}
+    # grouped queries: another head reads what the block would store, so the append stays a launch
+    p = B.sparf_plan(4, 32, 8, 128, 4097, 256, with_append=True)
+    assert p["launches"] == 2 and not p["append_fused"] and p["one_launch_threads"] == 256
+    # 64 ragged sequences up to 16K: the 512-thread form
+    p = B.sparf_plan(64, 40, 40, 128, 16385, 1024, with_append=True)
+    assert p["launches"] == 1 and p["one_launch_threads"] == 512 and p["append_fused"]
+    # 8 x 40 heads x 32K: score pass, selection spread over the stretches, sliced gather, merge
+    p = B.sparf_plan(8, 40, 40, 128, 32769, 2048, with_append=True)
+    assert p == {"launches": 7, "one_launch_threads": 0, "append_fused": False, "selection": 2,
+                 "select_and_gather": False, "slices": 4}
+    # 1 x 40 heads x 128K
+    p = B.sparf_plan(1, 40, 40, 128, 131073, 8192)
+    assert p["selection"] == 2 and p["slices"] == 8 and p["launches"] == 6
+
+
+def test_sparf_plan_limits_of_the_one_launch_kernel(no_sparf_env):
+    assert B.sparf_plan(1, 1, 1, 64, 8192, 10)["one_launch_threads"] == 256        # any number of heads
+    assert B.sparf_plan(1, 1, 1, 64, 8193, 10)["one_launch_threads"] == 0          # few heads: pipeline
+    assert B.sparf_plan(4, 32, 32, 64, 8193, 10)["one_launch_threads"] == 512      # 128 heads
+    assert B.sparf_plan(127, 1, 1, 64, 8193, 10)["one_launch_threads"] == 0
+    assert B.sparf_plan(4, 32, 32, 64, 18432, 10)["one_launch_threads"] == 512
+    assert B.sparf_plan(4, 32, 32, 64, 18433, 10)["one_launch_threads"] == 0
+
+
+def test_sparf_plan_pipeline_tail(no_sparf_env):
+    # many heads, rows too long for one launch, few kept rows: one block per head selects and gathers
+    p = B.sparf_plan(32, 40, 40, 128, 20000, 1000)
+    assert p == {"launches": 2, "one_launch_threads": 0, "append_fused": False, "selection": 1,
+                 "select_and_gather": True, "slices": 1}
+    # ... not behind 65535 positions, where the selection passes over memory
+    p = B.sparf_plan(32, 40, 40, 128, 70000, 1000)
+    assert not p["select_and_gather"] and p["launches"] == 3
+    # few heads with many kept rows: the gather is sliced, never more than 8 ways, never below 256 rows
+    assert B.sparf_plan(1, 8, 8, 128, 20000, 20000)["slices"] == 8
+    assert B.sparf_plan(1, 8, 8, 128, 20000, 600)["slices"] == 2
+    assert B.sparf_plan(1, 8, 8, 128, 20000, 255)["slices"] == 1
+
+
+def test_sparf_plan_environment_switches(no_sparf_env):
+    m = no_sparf_env
+    m.setenv("INSTATTN_SPARF_THREE_LAUNCHES", "1")
+    p = B.sparf_plan(16, 40, 40, 128, 4097, 256, with_append=True)
+    assert p["one_launch_threads"] == 0 and not p["append_fused"] and p["launches"] == 3
+    m.setenv("INSTATTN_SPARF_SPLIT_TAIL", "1")
+    assert B.sparf_plan(16, 40, 40, 128, 4097, 256)["launches"] == 3
+    m.delenv("INSTATTN_SPARF_THREE_LAUNCHES")
+    m.setenv("INSTATTN_SPARF_WIDE", "1")
+    assert B.sparf_plan(1, 2, 2, 128, 9000, 100)["one_launch_threads"] == 512
+    m.setenv("INSTATTN_SPARF_WIDE", "0")
+    assert B.sparf_plan(64, 40, 40, 128, 16385, 1024)["one_launch_threads"] == 0
+    m.setenv("INSTATTN_SPARF_DISTRIBUTED", "1")
+    assert B.sparf_plan(64, 40, 40, 128, 16385, 1024)["selection"] == 2
+    m.setenv("INSTATTN_SPARF_DISTRIBUTED", "0")
+    assert B.sparf_plan(1, 40, 40, 128, 131073, 8192)["selection"] == 1
+
+
+def test_sparf_plan_rejects():
+    for args in [(0, 4, 4, 128, 100, 10), (1, 4, 3, 128, 100, 10), (1, 4, 4, 128, 0, 10), (1, 4, 4, 128, 100, 0)]:
+        with pytest.raises(B.InstattnError) as e:
+            B.sparf_plan(*args)
+        assert e.value.status == B.ERR_INVALID_ARG
+    with pytest.raises(B.InstattnError) as e:
+        B.sparf_plan(1, 4, 4, 96, 100, 10)
+    assert e.value.status == B.ERR_UNSUPPORTED
