@@ -274,7 +274,7 @@ size_t instattn_sparf_workspace_size(int batch, int num_q_heads, int head_dim, i
  *               are written per head)
  *   alpha     : device [batch][num_q_heads] fp32 or NULL: receives step 7's alpha
  * L_b <= 0 gives a zero row (alpha 0).  One launch when max_seq_len <= 8192, or
- * <= 18432 with at least 128 (sequence, query head) pairs (one block per query head
+ * <= 18432 with at least 80 (sequence, query head) pairs (one block per query head
  * keeps the scores in LDS), otherwise two to six: column
  * scores; then either one launch in which a block per head selects and gathers
  * (many heads, rows below 65536), or selection (one launch with a block per head,

@@ -81,11 +81,11 @@ SparfPlan plan_sparf(int batch, int num_q_heads, int num_kv_heads, int max_seq_l
     const char* force3 = getenv("INSTATTN_SPARF_THREE_LAUNCHES");
     // Rows behind the 256-thread form's limit take the one-launch kernel's 512-thread form
     // when there are heads enough for one block each (measured at 16K rows: 160 heads
-    // 52 us against the pipeline's 63, 40 heads 44 against 40; INSTATTN_SPARF_WIDE forces
-    // either way).
+    // 52 us against the pipeline's 63, 120 heads 48 against 55, 80 heads 46 against 48,
+    // 40 heads 44 against 40; INSTATTN_SPARF_WIDE forces either way).
     const char* wide_env = getenv("INSTATTN_SPARF_WIDE");
     p.wide = max_seq_len > kSparfFusedMaxLen && max_seq_len <= kSparfFusedWideMaxLen &&
-             (wide_env ? wide_env[0] == '1' : heads >= 128);
+             (wide_env ? wide_env[0] == '1' : heads >= 80);
     p.one_launch = (max_seq_len <= kSparfFusedMaxLen || p.wide) && !(force3 && force3[0] == '1');
     if (!p.one_launch) p.wide = false;
     // The one-launch kernel stores the new token itself when its block is the only
@@ -264,6 +264,7 @@ int run_sparf_decode(const void* q, const void* k_new, const void* v_new, bool a
     a.distributed = plan.distributed;
     a.nslices = plan.nslices;
     a.slice_rows = plan.slice_rows;
+    a.wide = plan.wide;
     a.out = out;
     a.out_f32 = out_dtype == INSTATTN_F32;
     a.k_new = append ? (const half_t*)k_new : nullptr;

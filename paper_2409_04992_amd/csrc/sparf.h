@@ -48,6 +48,7 @@ struct SparfArgs {
     float* alpha;                      // [B][Hq] selected share of the approximate softmax
     float* part;                       // [B][Hq][nslices][D + 2] shares of the attend kernel's slices
     int32_t nslices, slice_rows;       // slices per head and kept rows per slice (multiple of 16)
+    int32_t wide;                      // one-launch kernel: 512 threads per head instead of 256
     // selection of a head spread over one block per stretch (few heads, long rows)
     int32_t distributed;
     uint32_t* hist;                    // [B][Hq][nchunk][256] level-1 histogram of every stretch

@@ -1722,7 +1722,7 @@ static hipError_t launch_fused(const SparfArgs& a, hipStream_t stream)
 
 hipError_t launch_sparf_fused(const SparfArgs& a, hipStream_t stream)
 {
-    if (a.max_len <= kSparfFusedMaxLen)
+    if (a.max_len <= kSparfFusedMaxLen && !a.wide)
         return a.head_dim == 128 ? launch_fused<128, 256, 4>(a, stream) : launch_fused<64, 256, 4>(a, stream);
     return a.head_dim == 128 ? launch_fused<128, 512, 5>(a, stream) : launch_fused<64, 512, 5>(a, stream);
 }

@@ -307,8 +307,8 @@ def test_sparf_plan_of_the_measured_shapes(no_sparf_env):
 def test_sparf_plan_limits_of_the_one_launch_kernel(no_sparf_env):
     assert B.sparf_plan(1, 1, 1, 64, 8192, 10)["one_launch_threads"] == 256        # any number of heads
     assert B.sparf_plan(1, 1, 1, 64, 8193, 10)["one_launch_threads"] == 0          # few heads: pipeline
-    assert B.sparf_plan(4, 32, 32, 64, 8193, 10)["one_launch_threads"] == 512      # 128 heads
-    assert B.sparf_plan(127, 1, 1, 64, 8193, 10)["one_launch_threads"] == 0
+    assert B.sparf_plan(4, 20, 20, 64, 8193, 10)["one_launch_threads"] == 512      # 80 heads
+    assert B.sparf_plan(79, 1, 1, 64, 8193, 10)["one_launch_threads"] == 0
     assert B.sparf_plan(4, 32, 32, 64, 18432, 10)["one_launch_threads"] == 512
     assert B.sparf_plan(4, 32, 32, 64, 18433, 10)["one_launch_threads"] == 0
 
