@@ -252,8 +252,8 @@ int instattn_sparf_append(const instattn_kv_desc* kv, const instattn_sparf_aux* 
  * the paper's; they depend on the arguments and on the INSTATTN_SPARF_*
  * environment switches that force a form for tests).  plan: host, 6 int32:
  *   [0] kernel launches in all
- *   [1] threads per block of the one-launch kernel (256 or 512), 0 if the row is
- *       too long for it and the pipeline runs
+ *   [1] threads per block of the one-launch kernel (256, 512 or 1024), 0 if the
+ *       pipeline runs instead
  *   [2] 1 if the decode's launch stores the new token itself
  *   [3] pipeline only: 1 = one block per head selects, 2 = one block per 8192 scores
  *   [4] pipeline only: 1 if the block that selects also gathers the kept rows
@@ -274,8 +274,9 @@ size_t instattn_sparf_workspace_size(int batch, int num_q_heads, int head_dim, i
  *               are written per head)
  *   alpha     : device [batch][num_q_heads] fp32 or NULL: receives step 7's alpha
  * L_b <= 0 gives a zero row (alpha 0).  One launch when max_seq_len <= 8192, or
- * <= 18432 with at least 80 (sequence, query head) pairs (one block per query head
- * keeps the scores in LDS), otherwise two to six: column
+ * <= 18432 with at least 80 (sequence, query head) pairs, or <= 36864 with 96 to
+ * 256 of them (one block per query head keeps the scores in LDS; 256, 512 or 1024
+ * threads), otherwise two to six: column
  * scores; then either one launch in which a block per head selects and gathers
  * (many heads, rows below 65536), or selection (one launch with a block per head,
  * or three with a block per 8192 scores when there are few heads with long rows),

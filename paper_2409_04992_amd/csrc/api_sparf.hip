@@ -45,7 +45,7 @@ Carve carve(int batch, int num_q_heads, int head_dim, int max_seq_len, int k)
 // Which kernels a decode of these sizes launches: host arithmetic only.
 struct SparfPlan {
     bool one_launch;      // sparf_fused_kernel does everything
-    bool wide;            // ... in its 512-thread form
+    int fused_threads;    // ... with this many threads per head (0: the pipeline runs)
     bool append_fused;    // the decode's launch stores the new token itself
     bool distributed;     // selection spread over one block per stretch (three launches)
     bool fused_tail;      // one block per head selects and gathers
@@ -80,14 +80,22 @@ SparfPlan plan_sparf(int batch, int num_q_heads, int num_kv_heads, int max_seq_l
     }
     const char* force3 = getenv("INSTATTN_SPARF_THREE_LAUNCHES");
     // Rows behind the 256-thread form's limit take the one-launch kernel's 512-thread form
-    // when there are heads enough for one block each (measured at 16K rows: 160 heads
+    // (up to 18432 positions; up to 36864 one of 1024 threads) when there are heads enough for
+    // one block each (measured at 16K rows: 160 heads
     // 52 us against the pipeline's 63, 120 heads 48 against 55, 80 heads 46 against 48,
     // 40 heads 44 against 40; INSTATTN_SPARF_WIDE forces either way).
     const char* wide_env = getenv("INSTATTN_SPARF_WIDE");
-    p.wide = max_seq_len > kSparfFusedMaxLen && max_seq_len <= kSparfFusedWideMaxLen &&
-             (wide_env ? wide_env[0] == '1' : heads >= 80);
-    p.one_launch = (max_seq_len <= kSparfFusedMaxLen || p.wide) && !(force3 && force3[0] == '1');
-    if (!p.one_launch) p.wide = false;
+    const bool force_wide = wide_env && wide_env[0] == '1', forbid_wide = wide_env && wide_env[0] == '0';
+    p.fused_threads = 0;
+    if (max_seq_len <= kSparfFusedMaxLen) p.fused_threads = 256;
+    else if (max_seq_len <= kSparfFusedWideMaxLen && !forbid_wide && (force_wide || heads >= 80)) p.fused_threads = 512;
+    else if (max_seq_len > kSparfFusedWideMaxLen && max_seq_len <= kSparfFusedWidestMaxLen && !forbid_wide &&
+             (force_wide || (heads >= 96 && heads <= 256)))
+        p.fused_threads = 1024;   // one block per compute unit: pays when the heads fit in one round of those
+                                  // (measured at 32K rows: 160 heads 94 us against the pipeline's 108;
+                                  // 320 and 640 heads level; 40 heads 74 against 56)
+    if (force3 && force3[0] == '1') p.fused_threads = 0;
+    p.one_launch = p.fused_threads != 0;
     // The one-launch kernel stores the new token itself when its block is the only
     // reader of what it stores; otherwise the append is a launch of its own.
     p.append_fused = append && p.one_launch && num_q_heads == num_kv_heads;
@@ -193,7 +201,7 @@ int instattn_sparf_plan(int batch, int num_q_heads, int num_kv_heads, int head_d
     if (head_dim != 64 && head_dim != 128) return head_dim > 0 ? INSTATTN_ERR_UNSUPPORTED : INSTATTN_ERR_INVALID_ARG;
     const SparfPlan p = plan_sparf(batch, num_q_heads, num_kv_heads, max_seq_len, k, with_append != 0);
     plan[0] = p.launches;
-    plan[1] = p.one_launch ? (p.wide ? 512 : 256) : 0;
+    plan[1] = p.fused_threads;
     plan[2] = p.append_fused;
     plan[3] = p.one_launch ? 0 : (p.distributed ? 2 : 1);
     plan[4] = p.fused_tail;
@@ -264,7 +272,7 @@ int run_sparf_decode(const void* q, const void* k_new, const void* v_new, bool a
     a.distributed = plan.distributed;
     a.nslices = plan.nslices;
     a.slice_rows = plan.slice_rows;
-    a.wide = plan.wide;
+    a.fused_threads = plan.fused_threads;
     a.out = out;
     a.out_f32 = out_dtype == INSTATTN_F32;
     a.k_new = append ? (const half_t*)k_new : nullptr;

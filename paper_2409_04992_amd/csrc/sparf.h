@@ -48,7 +48,7 @@ struct SparfArgs {
     float* alpha;                      // [B][Hq] selected share of the approximate softmax
     float* part;                       // [B][Hq][nslices][D + 2] shares of the attend kernel's slices
     int32_t nslices, slice_rows;       // slices per head and kept rows per slice (multiple of 16)
-    int32_t wide;                      // one-launch kernel: 512 threads per head instead of 256
+    int32_t fused_threads;             // one-launch kernel: threads per head (256, 512 or 1024)
     // selection of a head spread over one block per stretch (few heads, long rows)
     int32_t distributed;
     uint32_t* hist;                    // [B][Hq][nchunk][256] level-1 histogram of every stretch
@@ -75,6 +75,8 @@ constexpr int kSparfFusedMaxLen = 8192;   // rows up to this length take the one
 // ... and up to this length its form with 512 threads, when there are heads enough to
 // fill the chip with one block each (two blocks of 72 KB of LDS + 8 KB fit a compute unit)
 constexpr int kSparfFusedWideMaxLen = 18432;
+// ... and up to this length its form with 1024 threads (one block of 144 KB + 8 KB per compute unit)
+constexpr int kSparfFusedWidestMaxLen = 36864;
 
 // Floats at the end of the one-launch kernel's dynamic LDS that take the partial
 // sums of the gather (NG row groups of D sums, a maximum and a weight each) ...

@@ -1406,9 +1406,10 @@ __global__ __launch_bounds__(D) void sparf_merge_kernel(SparfArgs a)
 
 // The whole of Algorithm 1 for one query head in one block of NT threads; the
 // scores live in dynamic LDS (one float per position, rows of at most
-// STEPS * NT * 8 positions).  Two forms: 256 threads for rows up to 8192 (four blocks
-// per compute unit) and 512 threads for rows up to kSparfFusedWideMaxLen (two blocks
-// per compute unit: 72 KB of LDS each).  Once the scores are dead the same LDS holds
+// STEPS * NT * 8 positions).  Three forms: 256 threads for rows up to 8192 (four blocks
+// per compute unit), 512 threads for rows up to kSparfFusedWideMaxLen (two blocks per
+// compute unit: 72 KB of LDS each) and 1024 threads up to kSparfFusedWidestMaxLen (one
+// block: 144 KB).  Once the scores are dead the same LDS holds
 // the row ids of the gather and, at its end, the partial sums of its waves.
 template <int D, int NT, int STEPS>
 __global__ __launch_bounds__(NT, INSTATTN_SPARF_WAVES_PER_SIMD) void sparf_fused_kernel(SparfArgs a)
@@ -1722,9 +1723,11 @@ static hipError_t launch_fused(const SparfArgs& a, hipStream_t stream)
 
 hipError_t launch_sparf_fused(const SparfArgs& a, hipStream_t stream)
 {
-    if (a.max_len <= kSparfFusedMaxLen && !a.wide)
+    if (a.fused_threads == 256)
         return a.head_dim == 128 ? launch_fused<128, 256, 4>(a, stream) : launch_fused<64, 256, 4>(a, stream);
-    return a.head_dim == 128 ? launch_fused<128, 512, 5>(a, stream) : launch_fused<64, 512, 5>(a, stream);
+    if (a.fused_threads == 512)
+        return a.head_dim == 128 ? launch_fused<128, 512, 5>(a, stream) : launch_fused<64, 512, 5>(a, stream);
+    return a.head_dim == 128 ? launch_fused<128, 1024, 5>(a, stream) : launch_fused<64, 1024, 5>(a, stream);
 }
 
 hipError_t launch_sparf_attend(const SparfArgs& a, hipStream_t stream)

@@ -289,12 +289,14 @@ def test_sparf_one_block_tail_equals_the_two_kernels(monkeypatch):
 @pytest.mark.parametrize("seq_len,k,head_dim,paged,fused", [
     (8192, 300, 128, False, True), (8200, 600, 64, True, False), (12000, 13000, 128, True, True),
     (16384, 1024, 128, False, True), (16385, 1, 64, False, True), (18431, 2000, 128, True, False),
-    (18430, 5000, 64, False, True)])
-def test_sparf_one_launch_kernel_of_512_threads(monkeypatch, seq_len, k, head_dim, paged, fused):
-    """Rows between 8193 and 18432 positions in the one-launch kernel's wide form (forced
-    here: with few heads the host would pick the pipeline), with and without the append
-    inside it, up to the longest row it takes; kept rows beyond the room for row ids in
-    LDS go through in pieces."""
+    (18430, 5000, 64, False, True),
+    (18432, 700, 128, False, True), (25000, 26000, 64, True, True), (32768, 2048, 128, False, True),
+    (36863, 100, 128, True, False), (36862, 30000, 64, False, True)])
+def test_sparf_one_launch_kernel_of_512_and_1024_threads(monkeypatch, seq_len, k, head_dim, paged, fused):
+    """Rows between 8193 and 18432 positions in the one-launch kernel's form of 512
+    threads, up to 36864 positions in that of 1024 (forced here: with few heads the host
+    would pick the pipeline), with and without the append inside it, up to the longest row
+    each takes; kept rows beyond the room for row ids in LDS go through in pieces."""
     monkeypatch.setenv("INSTATTN_SPARF_WIDE", "1")
     wl = W.Workload("sparf_wide", 2, 3, 3, head_dim, seq_len, seq_len_min=seq_len - 9000, paged=paged,
                     page_size=16, seed=416)
