@@ -8,14 +8,22 @@
 // is already an efficient access, so the loads are exact: only selected columns
 // and selected rows are read.
 //
-// Kernels, in launch order:
-//   sparf_logits_kernel   steps 1-4 up to the softmax normaliser: one block per
-//                         8192 positions of one query head; reads the component-
-//                         major K copy, writes fp32 scores (log2 domain) and the
-//                         block's max / sum / min.
+// Kernels (the device functions they are made of are in sparf_score.h, steps 1-4;
+// sparf_select.h, steps 5-7; sparf_gather.h, steps 10-11):
+//   sparf_fused_kernel    the whole algorithm in one launch, one block per query
+//                         head, scores kept in LDS: 256 threads for rows of at most
+//                         8192 positions, 512 up to 18432, 1024 up to 36864.
+// Longer rows (or too few heads for the wider forms):
+//   sparf_logits_kernel   steps 1-4 up to the softmax normaliser: blocks walk units
+//                         of 2048 positions of one query head; reads the component-
+//                         major K copy, writes fp32 scores (log2 domain) and every
+//                         wave's max / sum / min.
+//   sparf_select_attend_kernel  steps 4 (normaliser) to 11: one block per query head
+//                         selects (scores in registers) and gathers the rows it
+//                         kept; taken when the kept rows of a head are not sliced.
 //   sparf_select_kernel   steps 4 (normaliser), 5-7: one block per query head; an
 //                         exact two-level selection over the scores (held in
-//                         registers for rows up to 32768), ordered compaction
+//                         registers for rows below 65536), ordered compaction
 //                         (ties towards the lower position), alpha.
 //   sparf_hist_kernel,    the same selection for few heads with long rows, one block
 //   sparf_members_kernel, per stretch of 8192 scores in three launches (described
@@ -24,860 +32,24 @@
 //                         kept rows, then sparf_merge_kernel combines the slices)
 //                         gathers the selected rows of K and V (online softmax as in
 //                         the dense vector-ALU kernel) and blends with the mean of V.
-//   sparf_fused_kernel    all of the above in one launch, one block per query head,
-//                         scores kept in LDS: used when a row has at most 8192
-//                         positions.
+// Set-up and append:
 //   sparf_build_kernel,   build the component-major K copy and the running sum of V
 //   sparf_vsum_kernel     from an existing cache (prefill side).
 //   sparf_append_kernel   kv_append plus the new column entry and sum update (the
 //                         one-launch kernel does this itself when asked to and
 //                         every KV head has a single query head).
-#include "sparf.h"
-
 #include <stdlib.h>
 
-#include <type_traits>
+#include "sparf.h"
+#include "sparf_gather.h"
+#include "sparf_score.h"
+#include "sparf_select.h"
 
-// Compile-time knobs of the one-launch kernel (defaults are the measured best).
-#ifndef INSTATTN_SPARF_CGMAX
-#define INSTATTN_SPARF_CGMAX 8       // most kept columns loaded per step of the column pass (16: -5..-14 %)
-#endif
 #ifndef INSTATTN_SPARF_WAVES_PER_SIMD
 #define INSTATTN_SPARF_WAVES_PER_SIMD 4   // register budget: blocks of 4 waves resident per compute unit
 #endif
 
 namespace instattn {
-
-namespace {
-
-// Wave-wide reductions: four DPP steps inside each row of 16 lanes, then the four
-// row results through scalar registers (no LDS crossbar traffic).  Every lane gets
-// the result; the order of the operations is fixed.
-__device__ __forceinline__ float lane_value(float x, int lane) {
-    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), lane));
-}
-__device__ __forceinline__ float wave_max(float x) {
-    x = fmaxf(x, dpp_f32<kDppXor1>(x));
-    x = fmaxf(x, dpp_f32<kDppXor2>(x));
-    x = fmaxf(x, dpp_f32<kDppHalfMirror>(x));
-    x = fmaxf(x, dpp_f32<kDppMirror>(x));
-    return fmaxf(fmaxf(lane_value(x, 0), lane_value(x, 16)), fmaxf(lane_value(x, 32), lane_value(x, 48)));
-}
-__device__ __forceinline__ float wave_sum(float x) {
-    x = group_sum<16>(x);
-    return (lane_value(x, 0) + lane_value(x, 16)) + (lane_value(x, 32) + lane_value(x, 48));
-}
-
-// Block-wide reductions through a small LDS array (one slot per wave); every
-// thread gets the result.  `red` must hold blockDim.x / 64 floats.
-__device__ __forceinline__ float block_max(float x, float* red) {
-    x = wave_max(x);
-    const int w = threadIdx.x >> 6, nw = blockDim.x >> 6;
-    __syncthreads();
-    if ((threadIdx.x & 63) == 0) red[w] = x;
-    __syncthreads();
-    float m = red[0];
-    for (int i = 1; i < nw; ++i) m = fmaxf(m, red[i]);
-    return m;
-}
-__device__ __forceinline__ float block_min(float x, float* red) { return -block_max(-x, red); }
-__device__ __forceinline__ float block_sum(float x, float* red) {
-    x = wave_sum(x);
-    const int w = threadIdx.x >> 6, nw = blockDim.x >> 6;
-    __syncthreads();
-    if ((threadIdx.x & 63) == 0) red[w] = x;
-    __syncthreads();
-    float s = 0.f;
-    for (int i = 0; i < nw; ++i) s += red[i];   // fixed order: deterministic
-    return s;
-}
-
-// Monotone map from float to unsigned: a < b  <=>  key(a) < key(b).
-__device__ __forceinline__ uint32_t order_key(float x) {
-    const uint32_t u = __builtin_bit_cast(uint32_t, x);
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-
-// Step 1 and the temperature of step 4.  Leaves q (fp32) in s_q and the components
-// ordered by decreasing |q| (ties towards the lower index) in s_dim; returns the
-// factor that turns a column dot product into a log2-domain score.  Needs at least
-// head_dim threads and is called by the whole block; `red` holds 32 floats and is
-// free again once every thread has passed the next barrier.
-__device__ __forceinline__ float prepare_query(const SparfArgs& a, int64_t row, float* s_q, float* s_abs,
-                                               int* s_dim, float* red)
-{
-    const int D = a.head_dim, tid = threadIdx.x;
-    uint32_t* s_key = (uint32_t*)s_abs;     // 16-byte aligned by its callers
-    float mine = 0.f;
-    uint32_t key = 0;
-    if (tid < D) {
-        const half_t qh = a.q[row * D + tid];
-        const float qd = (float)qh;
-        s_q[tid] = qd;
-        mine = fabsf(qd);
-        // one integer per component that orders them as step 1 wants: by magnitude (the
-        // fp16 bit pattern without its sign is monotone in it), ties to the lower index
-        key = ((uint32_t)(__builtin_bit_cast(uint16_t, qh) & 0x7FFFu) << 8) | (uint32_t)(255 - tid);
-        s_key[tid] = key;
-    }
-    __syncthreads();
-    float kept = 0.f;
-    if (tid < D) {
-        // rank = number of keys above this one (keys are distinct); 128-bit LDS reads
-        const u32x4* k4 = (const u32x4*)s_key;
-        int rank = 0;
-#pragma unroll 8
-        for (int i = 0; i < D / 4; ++i) {
-            const u32x4 o = k4[i];
-            rank += (int)(o.x > key) + (int)(o.y > key) + (int)(o.z > key) + (int)(o.w > key);
-        }
-        s_dim[rank] = tid;
-        if (rank < a.r) kept = mine;
-    }
-    // sqrt(d_h * |q_kept|_1 / |q|_1); 1/sqrt(d_h) is in `scale`.  Both sums in one
-    // block reduction (fixed order: deterministic).
-    const float tot_w = wave_sum(mine), kept_w = wave_sum(kept);
-    const int w = tid >> 6, nw = blockDim.x >> 6;
-    if ((tid & 63) == 0) {
-        red[w] = tot_w;
-        red[16 + w] = kept_w;
-    }
-    __syncthreads();
-    float tot = 0.f, kp = 0.f;
-    for (int i = 0; i < nw; ++i) {
-        tot += red[i];
-        kp += red[16 + i];
-    }
-    const float rho = tot > 0.f ? kp / tot : 1.f;
-    return rho > 0.f ? a.scale_log2 / sqrtf(rho) : 0.f;
-}
-
-// Column pass of a whole row by one block (steps 2-4 without the softmax): adds
-// to xs[t], t < L, the contribution of CG kept columns, the ones ranked
-// j0 .. j0+CG-1, for the L positions that start at t_base (a multiple of 8).  The columns' offsets and the q components are the same for
-// every lane and are kept in scalar registers; a thread takes 8 consecutive
-// positions per step with one 128-bit load per column, and the loads of step i+1
-// are in flight while step i is consumed.  The steps are unrolled and every load
-// is issued unconditionally (steps behind the row's end re-read its last 8
-// positions, a cache hit) so that the count of loads in flight is known at every
-// wait.  first: xs is written, not added to.
-template <int CG, int NT, int STEPS>
-__device__ __forceinline__ void column_pass(const SparfArgs& a, int b, int hk, int t_base, int L, int j0,
-                                            bool first, float factor, const float* s_q, const int* s_dim,
-                                            float* xs)
-{
-
-    int64_t coff[CG];
-    float qv[CG];
-#pragma unroll
-    for (int j = 0; j < CG; ++j) {
-        const int d = __builtin_amdgcn_readfirstlane(s_dim[j0 + j]);
-        coff[j] = (int64_t)d * a.aux.stride_d;
-        qv[j] = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, s_q[d] * factor)));
-    }
-    const int tid = threadIdx.x;
-    const int t_last = (L - 1) & ~7;                 // last run of 8 that holds a position
-    const half_t* p0[STEPS];
-#pragma unroll
-    for (int i = 0; i < STEPS; ++i) p0[i] = kt_col0(a.aux, b, hk, t_base + min((i * NT + tid) * 8, t_last));
-
-    half8_t A[CG], B[CG];
-    auto load = [&](half8_t (&T)[CG], const half_t* p) {
-#pragma unroll
-        for (int j = 0; j < CG; ++j) T[j] = __builtin_nontemporal_load((const half8_t*)(p + coff[j]));
-    };
-    auto consume = [&](const half8_t (&T)[CG], int i) {
-        const int t = (i * NT + tid) * 8;
-        float4_t* dst = (float4_t*)(xs + min(t, t_last));
-        const float4_t lo = dst[0], hi = dst[1];
-        float x[8];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            x[e] = first ? 0.f : lo[e];
-            x[4 + e] = first ? 0.f : hi[e];
-        }
-#pragma unroll
-        for (int j = 0; j < CG; ++j)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) x[e] = __builtin_fmaf(qv[j], (float)T[j][e], x[e]);
-        if (t <= t_last) {
-            dst[0] = float4_t{x[0], x[1], x[2], x[3]};
-            dst[1] = float4_t{x[4], x[5], x[6], x[7]};
-        }
-    };
-    load(A, p0[0]);
-#pragma unroll
-    for (int i = 0; i < STEPS; i += 2) {
-        if (i * NT * 8 >= L) break;                  // block-uniform: the row ended before this pair of steps
-        if (i + 1 < STEPS) load(B, p0[i + 1]);
-        pin_order();
-        consume(A, i);
-        if (i + 2 < STEPS) load(A, p0[i + 2]);
-        pin_order();
-        if (i + 1 < STEPS) consume(B, i + 1);
-    }
-}
-
-constexpr int kSelMembers = 512;     // members of the threshold bin ranked directly
-
-struct SelectScratch {
-    uint32_t hist[256];
-    uint32_t prefix, remaining, nmem, nsub;
-    alignas(16) uint32_t mem_key[kSelMembers];
-    alignas(16) uint32_t mem_key2[kSelMembers];
-    uint32_t wave_cnt[8][16];        // per round parity (or step) and wave: rows above the threshold | rows at it << 16
-    float red[48];
-};
-
-// Executed by wave 0 after a histogram is complete: finds the bin that holds the
-// remaining-th largest entry (higher bins rank first) and leaves
-//   S.prefix = that bin,  S.remaining = entries still to take inside it.
-// Lane i owns bins 4i .. 4i+3; suffix sums over the lanes locate the bin.
-__device__ __forceinline__ void locate_bin(SelectScratch& S, uint32_t remaining, int lane)
-{
-    const uint32_t c0 = S.hist[4 * lane], c1 = S.hist[4 * lane + 1];
-    const uint32_t c2 = S.hist[4 * lane + 2], c3 = S.hist[4 * lane + 3];
-    const uint32_t mine = c0 + c1 + c2 + c3;
-    uint32_t suffix = mine;                       // inclusive, over lanes >= this one
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const uint32_t o = __shfl_down(suffix, d, 64);
-        if (lane + d < 64) suffix += o;
-    }
-    uint32_t above = suffix - mine;               // entries in bins above this lane's
-    if (above < remaining && remaining <= suffix) {
-        int bin = 4 * lane + 3;
-        const uint32_t cs[4] = {c0, c1, c2, c3};
-#pragma unroll
-        for (int j = 3; j > 0; --j) {
-            if (above + cs[j] >= remaining) break;
-            above += cs[j];
-            --bin;
-        }
-        S.prefix = (uint32_t)bin;
-        S.remaining = remaining - above;
-    }
-}
-
-// All kept columns of one stretch of at most STEPS * NT * 8 positions, in groups
-// of INSTATTN_SPARF_CGMAX columns, then halves of that down to one.
-template <int CG, int NT, int STEPS>
-__device__ __forceinline__ void column_groups(const SparfArgs& a, int b, int hk, int t_base, int L, float factor,
-                                              const float* s_q, const int* s_dim, float* xs, int& j0)
-{
-    if constexpr (CG <= INSTATTN_SPARF_CGMAX)
-        for (; a.r - j0 >= CG; j0 += CG)
-            column_pass<CG, NT, STEPS>(a, b, hk, t_base, L, j0, j0 == 0, factor, s_q, s_dim, xs);
-}
-
-template <int NT, int STEPS>
-__device__ __forceinline__ void column_passes(const SparfArgs& a, int b, int hk, int t_base, int L, float factor,
-                                              const float* s_q, const int* s_dim, float* xs)
-{
-    int j0 = 0;
-    column_groups<16, NT, STEPS>(a, b, hk, t_base, L, factor, s_q, s_dim, xs, j0);
-    column_groups<8, NT, STEPS>(a, b, hk, t_base, L, factor, s_q, s_dim, xs, j0);
-    column_groups<4, NT, STEPS>(a, b, hk, t_base, L, factor, s_q, s_dim, xs, j0);
-    column_groups<2, NT, STEPS>(a, b, hk, t_base, L, factor, s_q, s_dim, xs, j0);
-    column_groups<1, NT, STEPS>(a, b, hk, t_base, L, factor, s_q, s_dim, xs, j0);
-}
-
-// The scores of positions (i * NT + tid) * 8 + e, e < 8, of a row of L scores at x
-// (what the column pass gave this thread, so no barrier is needed to read them back
-// from LDS); 0 where the run of 8 starts at or behind L.
-template <int NT, int STEPS>
-__device__ __forceinline__ void own_scores(const float* x, int L, float (&xr)[STEPS][8])
-{
-    const int tid = threadIdx.x;
-#pragma unroll
-    for (int i = 0; i < STEPS; ++i) {
-        const int t = (i * NT + tid) * 8;
-        float4_t lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};
-        if (t < L) {
-            lo = *(const float4_t*)(x + t);
-            hi = *(const float4_t*)(x + t + 4);
-        }
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            xr[i][e] = lo[e];
-            xr[i][4 + e] = hi[e];
-        }
-    }
-}
-
-// Softmax statistics of step 4 over the first L positions of such a register
-// tile: maximum, minimum and sum of 2^(x - maximum), to every thread.  Own max,
-// min and sum first, then one block reduction for all three (fixed order).  red
-// holds 48 floats.
-template <int NT, int STEPS>
-__device__ __forceinline__ void block_stats(const float (&xr)[STEPS][8], int L, float* red, float& M, float& xmin,
-                                            float& Z)
-{
-    const int tid = threadIdx.x;
-    float mx = kNegBig, mn = -kNegBig;
-#pragma unroll
-    for (int i = 0; i < STEPS; ++i) {
-        if (i * NT * 8 < L) {                                  // block-uniform
-#pragma unroll
-            for (int e = 0; e < 8; ++e)
-                if ((i * NT + tid) * 8 + e < L) {
-                    mx = fmaxf(mx, xr[i][e]);
-                    mn = fminf(mn, xr[i][e]);
-                }
-        }
-    }
-    float zs = 0.f;
-#pragma unroll
-    for (int i = 0; i < STEPS; ++i) {
-        if (i * NT * 8 < L) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e)
-                if ((i * NT + tid) * 8 + e < L) zs += fast_exp2(xr[i][e] - mx);
-        }
-    }
-    const float mw = wave_max(mx);
-    const float zw = wave_sum(zs * fast_exp2(mx - mw));
-    const float nw_min = -wave_max(-mn);
-    const int w = tid >> 6;
-    __syncthreads();                       // red is free (earlier readers are done)
-    if ((tid & 63) == 0) {
-        red[w] = mw;
-        red[16 + w] = zw;
-        red[32 + w] = nw_min;
-    }
-    __syncthreads();
-    M = kNegBig;
-    xmin = -kNegBig;
-#pragma unroll
-    for (int i = 0; i < NT / 64; ++i) {
-        M = fmaxf(M, red[i]);
-        xmin = fminf(xmin, red[32 + i]);
-    }
-    Z = 0.f;
-#pragma unroll
-    for (int i = 0; i < NT / 64; ++i) Z += red[16 + i] * fast_exp2(red[i] - M);
-}
-
-// Level-1 bucket of a score: linear between the row's minimum and maximum,
-// monotone in the score, so every score in a higher bucket is >= every score in a
-// lower one.
-struct Level1 {
-    float M, binscale;
-    __device__ __forceinline__ Level1(float M_, float xmin) : M(M_), binscale(M_ > xmin ? 255.99f / (M_ - xmin) : 0.f) {}
-    __device__ __forceinline__ uint32_t operator()(float v) const {
-        return 255u - (uint32_t)min(255, max(0, (int)((M - v) * binscale)));
-    }
-    // 256 finer buckets inside a level-1 bucket, monotone in the score like the bucket
-    __device__ __forceinline__ uint32_t sub(float v) const {
-        const float t = (M - v) * binscale;
-        const float f = t - (float)min(255, max(0, (int)t));
-        return 255u - (uint32_t)min(255, max(0, (int)(f * 256.f)));
-    }
-};
-
-// Inverse of order_key.
-__device__ __forceinline__ float key_score(uint32_t key) {
-    return __builtin_bit_cast(float, (key & 0x80000000u) ? (key & 0x7FFFFFFFu) : ~key);
-}
-
-// Ranks the n keys at `keys` (LDS, 16-byte aligned, room for n rounded up to 4)
-// against each other: the threshold key is the one with fewer than `remaining` keys
-// above it and at least `remaining` at or above.  The tail of the last vector must
-// hold 0, a key no finite score has.  Leaves the key in S.prefix and the number of
-// rows with exactly that key still wanted in S.remaining.
-template <int NT>
-__device__ __forceinline__ void rank_directly(const uint32_t* keys, uint32_t n, uint32_t remaining,
-                                              SelectScratch& S)
-{
-    const int tid = threadIdx.x;
-    const u32x4* k4 = (const u32x4*)keys;
-    const uint32_t n4 = (n + 3) / 4;
-    for (uint32_t i = tid; i < n; i += NT) {
-        const uint32_t mine = keys[i];
-        uint32_t gt = 0, ge = 0;
-#pragma unroll 4
-        for (uint32_t j = 0; j < n4; ++j) {
-            const u32x4 o = k4[j];
-            gt += (uint32_t)(o.x > mine) + (uint32_t)(o.y > mine) + (uint32_t)(o.z > mine) + (uint32_t)(o.w > mine);
-            ge += (uint32_t)(o.x >= mine) + (uint32_t)(o.y >= mine) + (uint32_t)(o.z >= mine) + (uint32_t)(o.w >= mine);
-        }
-        if (gt < remaining && remaining <= ge) {         // same values from every such member
-            S.prefix = mine;
-            S.remaining = remaining - gt;
-        }
-    }
-}
-
-// The threshold key among the n members of the threshold bin (keys, n <= cap; keys2:
-// scratch of the same size; both 16-byte aligned LDS).  A handful is ranked
-// directly; more go through 256 finer buckets first (linear in n instead of
-// quadratic: the members of a long row's bin run into the hundreds) and only the
-// members of the one finer bucket that holds the threshold are ranked.  Called by
-// the whole block, synchronised on entry; the results are in S.prefix and
-// S.remaining after the caller's next barrier.
-template <int NT>
-__device__ __forceinline__ void rank_members(uint32_t* keys, uint32_t* keys2, uint32_t n, uint32_t cap,
-                                             uint32_t remaining, const Level1& level1, SelectScratch& S)
-{
-    const int tid = threadIdx.x;
-    if (n <= 64u) {
-        if (tid < 3 && n + tid < cap) keys[n + tid] = 0;
-        __syncthreads();
-        rank_directly<NT>(keys, n, remaining, S);
-        return;
-    }
-    if (tid < 256) S.hist[tid] = 0;
-    if (tid == 0) S.nsub = 0;
-    __syncthreads();
-    for (uint32_t i = tid; i < n; i += NT) atomicAdd(&S.hist[level1.sub(key_score(keys[i]))], 1u);
-    __syncthreads();
-    if (tid < 64) locate_bin(S, remaining, tid);
-    __syncthreads();
-    const uint32_t bucket = S.prefix, rem2 = S.remaining;
-    for (uint32_t i = tid; i < n; i += NT) {
-        const uint32_t key = keys[i];
-        if (level1.sub(key_score(key)) == bucket) keys2[atomicAdd(&S.nsub, 1u)] = key;
-    }
-    __syncthreads();                                   // also: everyone has read bucket and rem2
-    const uint32_t m = S.nsub;
-    if (tid < 3 && m + tid < cap) keys2[m + tid] = 0;
-    __syncthreads();
-    rank_directly<NT>(keys2, m, rem2, S);
-}
-
-// The threshold of the top-`want` candidates, exactly, in two levels.  Level 1
-// buckets the scores into 256 bins (scores spread evenly over these, unlike over
-// the exponent byte of a float).  Level 2 works on the members of the one bin that
-// holds the threshold: normally a few dozen, which are gathered and ranked against
-// each other directly; if there are more than kSelMembers (e.g. all scores equal)
-// a 4-pass radix select on order-preserving keys takes over.  The outcome: the
-// kept candidates are those in a bin above bin1, those in bin1 with a key above
-// `prefix`, and the first `remaining` (in position order) with exactly that key.
-// for_each(f) calls f(score, its level-1 bin) for every candidate of the calling
-// thread; it is called several times and must visit the same candidates each time.
-template <int NT, class ForEach>
-__device__ __forceinline__ void find_threshold(ForEach&& for_each, int want, const Level1& level1,
-                                               SelectScratch& S, uint32_t& bin1, uint32_t& prefix,
-                                               uint32_t& remaining)
-{
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    bin1 = 0;
-    prefix = 0;
-    remaining = (uint32_t)want;
-    if (want <= 0) return;
-    // level 1
-    if (tid < 256) S.hist[tid] = 0;
-    if (tid == 0) S.nmem = 0;
-    __syncthreads();
-    for_each([&](float, uint32_t bin) { atomicAdd(&S.hist[bin], 1u); });
-    __syncthreads();
-    if (wave == 0) locate_bin(S, remaining, lane);
-    __syncthreads();
-    bin1 = S.prefix;
-    remaining = S.remaining;
-    // level 2: gather the members of bin1
-    const uint32_t b1 = bin1;
-    for_each([&](float v, uint32_t bin) {
-        if (bin == b1) {
-            const uint32_t i = atomicAdd(&S.nmem, 1u);
-            if (i < (uint32_t)kSelMembers) S.mem_key[i] = order_key(v);
-        }
-    });
-    __syncthreads();
-    const uint32_t nmem = S.nmem;
-    if (nmem <= (uint32_t)kSelMembers) {
-        rank_members<NT>(S.mem_key, S.mem_key2, nmem, (uint32_t)kSelMembers, remaining, level1, S);
-        __syncthreads();
-        prefix = S.prefix;
-        remaining = S.remaining;
-    } else {
-        for (int shift = 24; shift >= 0; shift -= 8) {
-            __syncthreads();
-            if (tid < 256) S.hist[tid] = 0;
-            __syncthreads();
-            const uint32_t hi_mask = shift == 24 ? 0u : (0xFFFFFFFFu << (shift + 8));
-            const uint32_t pfx = prefix;
-            for_each([&](float v, uint32_t bin) {
-                const uint32_t key = order_key(v);
-                if (bin == b1 && (key & hi_mask) == (pfx & hi_mask))
-                    atomicAdd(&S.hist[(key >> shift) & 255u], 1u);
-            });
-            __syncthreads();
-            if (wave == 0) locate_bin(S, remaining, lane);
-            __syncthreads();
-            prefix |= S.prefix << shift;
-            remaining = S.remaining;
-        }
-    }
-}
-
-// Ordered compaction of one register tile: xr[i][e] is the score of position
-// t_off + (i * NT + tid) * 8 + e, candidates are the positions below ncand.  Writes
-// the kept positions of the tile to their slots of sel and adds their softmax mass.
-// Position order is (i, wave, lane, e): a shuffle scan over the lanes of a wave per
-// step i, the wave totals per step through LDS (step_cnt, STEPS * NT / 64 words),
-// one barrier.  The output slot of a row is (rows above the threshold before it) +
-// min(rows at the threshold before it, number of those still wanted), so ties go
-// to the lower position and the result is deterministic.  gt_base / eq_base count
-// the rows above / at the threshold in earlier tiles and are advanced.
-template <int NT, int STEPS, class BinOf>
-__device__ __forceinline__ void compact_tile(const float (&xr)[STEPS][8], BinOf&& bin_of, int t_off, int ncand,
-                                             uint32_t bin1, uint32_t prefix, uint32_t remaining,
-                                             uint32_t& gt_base, uint32_t& eq_base, uint32_t* step_cnt,
-                                             float M, int32_t* sel, float& mass)
-{
-    constexpr int NW = NT / 64;
-    typedef typename std::conditional<(STEPS > 4), uint64_t, uint32_t>::type bits_t;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    // the score whose key is the threshold key (inverse of order_key)
-    const float mass_at_key = fast_exp2(key_score(prefix) - M);
-    bits_t gtbits = 0, eqbits = 0;                         // bit 8i + e
-    uint32_t excl[STEPS];                                  // kept before this lane in its wave, per step
-#pragma unroll
-    for (int i = 0; i < STEPS; ++i) {
-        uint32_t c = 0;
-        if (t_off + i * NT * 8 < ncand) {                  // block-uniform
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const bool valid = t_off + (i * NT + tid) * 8 + e < ncand;
-                const uint32_t b1 = bin_of(i, e);
-                const uint32_t key = order_key(xr[i][e]);
-                const bool gt = valid && (b1 > bin1 || (b1 == bin1 && key > prefix));
-                const bool eq = valid && b1 == bin1 && key == prefix;
-                gtbits |= (bits_t)gt << (8 * i + e);
-                eqbits |= (bits_t)eq << (8 * i + e);
-                c += (uint32_t)gt + ((uint32_t)eq << 16);
-                if (gt) mass += fast_exp2(xr[i][e] - M);   // here, where the score is at hand in a register
-            }
-        }
-        uint32_t incl = c;                                 // 16-bit halves: at most 512 each
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const uint32_t o = __shfl_up(incl, d, 64);
-            if (lane >= d) incl += o;
-        }
-        excl[i] = incl - c;
-        if (lane == 63) step_cnt[i * NW + wave] = incl;
-    }
-    __syncthreads();
-    uint32_t run = 0;                                      // halves: at most 65535 each in a tile
-#pragma unroll
-    for (int i = 0; i < STEPS; ++i) {
-        uint32_t mine = 0;
-#pragma unroll
-        for (int w = 0; w < NW; ++w) {
-            mine = w == wave ? run : mine;
-            run += step_cnt[i * NW + w];
-        }
-        const uint32_t gb = gt_base + ((mine + excl[i]) & 0xFFFFu), eb = eq_base + ((mine + excl[i]) >> 16);
-        // the few flagged slots of this lane, in position order
-        const uint32_t g8 = (uint32_t)(gtbits >> (8 * i)) & 0xFFu, e8 = (uint32_t)(eqbits >> (8 * i)) & 0xFFu;
-        uint32_t todo = g8 | e8;
-        while (todo) {
-            const int e = __builtin_ctz(todo);
-            todo &= todo - 1;
-            const uint32_t below = (1u << e) - 1u;
-            const uint32_t eq_before = eb + (uint32_t)__popc(e8 & below);
-            const bool above = (g8 >> e) & 1u;
-            if (above || eq_before < remaining) {
-                sel[gb + (uint32_t)__popc(g8 & below) + min(eq_before, remaining)] = t_off + (i * NT + tid) * 8 + e;
-                if (!above) mass += mass_at_key;           // rows at the threshold key share one score
-            }
-        }
-    }
-    gt_base += run & 0xFFFFu;
-    eq_base += run >> 16;
-}
-
-// Steps 5-7 for one head of any length: x[0..L) are the log2-domain scores in
-// global memory, M their maximum, xmin their minimum and Z the sum of 2^(x - M).
-// Writes the kept positions in ascending order to sel and returns alpha to every
-// thread.  The row goes through register tiles of NT * 32 positions (two 128-bit
-// loads per thread and step, all of a tile in flight at once): twice for the
-// threshold, once for the compaction.
-template <int NT>
-__device__ __forceinline__ float select_rows(const float* x, int L, int k, int l, float M, float xmin, float Z,
-                                             int32_t* sel, SelectScratch& S)
-{
-    constexpr int STEPS = 4, TILE = NT * 8 * STEPS;
-    const int tid = threadIdx.x;
-    const int keff = min(k, L);
-    const int leff = min(l, keff);
-    const int want = keff - leff;          // rows to pick among the candidates
-    const int ncand = L - leff;            // candidates: positions [0, ncand)
-    const Level1 level1(M, xmin);
-
-    uint32_t bin1, prefix, remaining;
-    find_threshold<NT>(
-        [&](auto&& f) {
-            for (int t_off = 0; t_off < ncand; t_off += TILE) {
-                float xr[STEPS][8];
-                own_scores<NT, STEPS>(x + t_off, ncand - t_off, xr);
-#pragma unroll
-                for (int i = 0; i < STEPS; ++i)
-#pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        if (t_off + (i * NT + tid) * 8 + e < ncand) f(xr[i][e], level1(xr[i][e]));
-            }
-        },
-        want, level1, S, bin1, prefix, remaining);
-
-    float mass = 0.f;
-    uint32_t gt_base = 0, eq_base = 0;
-    int parity = 0;
-    for (int t_off = 0; want > 0 && t_off < ncand; t_off += TILE, parity ^= 1) {
-        float xr[STEPS][8];
-        own_scores<NT, STEPS>(x + t_off, ncand - t_off, xr);
-        compact_tile<NT, STEPS>(
-            xr, [&](int i, int e) { return level1(xr[i][e]); }, t_off, ncand, bin1, prefix, remaining, gt_base,
-            eq_base, &S.wave_cnt[parity * 4][0], M, sel, mass);
-    }
-    // step 5: the l most recent positions are always kept
-    for (int i = tid; i < leff; i += NT) {
-        const int t = ncand + i;
-        sel[want + i] = t;
-        mass += fast_exp2(x[t] - M);
-    }
-    return block_sum(mass, S.red) / Z;     // step 7
-}
-
-// The same for a row of at most STEPS * NT * 8 positions whose scores the threads
-// hold in registers already: xr[i][e] is the score of position (i * NT + tid) * 8 + e
-// (what the column pass gave this thread); xs holds the same scores in memory.
-template <int NT, int STEPS>
-__device__ __forceinline__ float select_rows_reg(const float (&xr)[STEPS][8], const float* xs, int L, int k,
-                                                 int l, float M, float xmin, float Z, int32_t* sel,
-                                                 SelectScratch& S)
-{
-    static_assert(STEPS * (NT / 64) <= 128 && STEPS * 8 <= 64, "counts and flag words");
-    const int tid = threadIdx.x;
-    const int keff = min(k, L);
-    const int leff = min(l, keff);
-    const int want = keff - leff;
-    const int ncand = L - leff;
-    const Level1 level1(M, xmin);
-
-    // level-1 bins of the own scores, one byte each, computed once (where the register
-    // budget allows: with 40 or 64 scores per thread they are recomputed instead)
-    constexpr bool kCacheBins = STEPS <= 4;
-    uint32_t bins[kCacheBins ? STEPS : 1][2];
-    if constexpr (kCacheBins) {
-#pragma unroll
-        for (int i = 0; i < STEPS; ++i) {
-            bins[i][0] = bins[i][1] = 0;
-            if (want > 0 && i * NT * 8 < ncand) {              // block-uniform
-#pragma unroll
-                for (int e = 0; e < 8; ++e) bins[i][e >> 2] |= level1(xr[i][e]) << (8 * (e & 3));
-            }
-        }
-    }
-    auto bin_of = [&](int i, int e) -> uint32_t {
-        if constexpr (kCacheBins) return (bins[i][e >> 2] >> (8 * (e & 3))) & 255u;
-        else return level1(xr[i][e]);
-    };
-
-    uint32_t bin1, prefix, remaining;
-    find_threshold<NT>(
-        [&](auto&& f) {
-#pragma unroll
-            for (int i = 0; i < STEPS; ++i) {
-                if (i * NT * 8 < ncand) {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        if ((i * NT + tid) * 8 + e < ncand) f(xr[i][e], bin_of(i, e));
-                }
-            }
-        },
-        want, level1, S, bin1, prefix, remaining);
-
-    float mass = 0.f;
-    if (want > 0) {
-        uint32_t gt_base = 0, eq_base = 0;
-        compact_tile<NT, STEPS>(xr, bin_of, 0, ncand, bin1, prefix, remaining, gt_base, eq_base, &S.wave_cnt[0][0],
-                                M, sel, mass);
-    }
-    // step 5: the l most recent positions are always kept
-    for (int i = tid; i < leff; i += NT) {
-        const int t = ncand + i;
-        sel[want + i] = t;
-        mass += fast_exp2(xs[t] - M);
-    }
-    return block_sum(mass, S.red) / Z;     // step 7
-}
-
-// Steps 10-11 for one head over the n kept rows listed in sel, by WAVES waves:
-// 16 (or 8) lanes read a row, every row group runs its own online softmax, the
-// groups are combined in LDS, the result is blended with the mean of V.
-// The kept positions are first turned into row ids in LDS (`ids`, room for
-// ids_cap of them; longer lists go through in pieces): the position itself, or,
-// for a paged cache, pool page and row inside it packed into one word, so that
-// the gather loop has no global load between the id and the row.  Two register
-// tiles: the rows of step i+1 are in flight while step i is consumed.
-//
-// The block handles entries [p_begin, p_end) of the list.  part == nullptr: that is
-// the whole list and the block writes the output row.  Otherwise it writes its
-// share as D unnormalised sums, their reference maximum and the sum of weights
-// (D + 2 floats at part) for sparf_merge_kernel.
-//
-// fresh: the new token of this step is not in the cache yet (the one-launch kernel
-// stores it when everything else is done): its row, position t_new, comes from
-// k_new / v_new, and v_new is added to the V sum here.
-template <int D, int WAVES>
-__device__ __forceinline__ void attend_rows(const SparfArgs& a, int b, int h, int L, int p_begin, int p_end,
-                                            const int32_t* sel, float alpha, float* part, int32_t* ids,
-                                            int ids_cap, float (*s_acc)[D], float* s_m, float* s_l,
-                                            bool fresh = false, int t_new = -1)
-{
-    constexpr int LPR = D / 8;
-    constexpr int RPW = kWave / LPR;
-    constexpr int U = 16 / RPW;            // 16 rows per wave and step
-    constexpr int TILE = WAVES * 16;
-    constexpr int NG = WAVES * RPW;
-    const int G = a.num_q_heads / a.num_kv_heads;
-    const int hk = h / G;
-    const int tid = threadIdx.x;
-    const int64_t row = (int64_t)b * a.num_q_heads + h;
-    const int wave = tid >> 6, lane = tid & 63;
-    const int r = lane / LPR, c = lane % LPR;
-    const half8_t q8 = *(const half8_t*)(a.q + row * D + c * 8);
-    const bool paged = a.kv.page_table != nullptr;
-    const int shift = a.kv.page_shift, mask = a.kv.page_mask;
-    const int64_t base = (paged ? 0 : (int64_t)b * a.kv.stride_b) + (int64_t)hk * a.kv.stride_h + c * 8;
-    const int64_t stride_page = paged ? a.kv.stride_b : 0;
-    const int64_t new_off = ((int64_t)b * a.num_kv_heads + hk) * D + c * 8;
-    if (!fresh) t_new = -1;
-
-    float m = kNegBig, l = 0.f;
-    float acc[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) acc[e] = 0.f;
-
-    struct Tile {
-        u32x4 k[U], v[U];
-    };
-    for (int c0 = p_begin; c0 < p_end; c0 += ids_cap) {
-        const int nc = min(ids_cap, p_end - c0);
-        __syncthreads();                   // whatever used this LDS before is done with it
-        for (int i = tid; i < nc; i += WAVES * 64) {
-            const int t = sel[c0 + i];
-            if (t == t_new) ids[i] = -1;
-            else
-                ids[i] =
-                    paged ? (a.kv.page_table[(int64_t)b * a.kv.max_pages + (t >> shift)] << shift) | (t & mask) : t;
-        }
-        __syncthreads();
-        auto load = [&](Tile& T, int it) {
-#pragma unroll
-            for (int j = 0; j < U; ++j) {
-                const int raw = ids[min(it * TILE + wave * 16 + j * RPW + r, nc - 1)];
-                const int id = max(raw, 0);
-                const int64_t off = base + (int64_t)(paged ? id >> shift : 0) * stride_page +
-                                    (int64_t)(paged ? id & mask : id) * a.kv.stride_t;
-                T.k[j] = __builtin_nontemporal_load((const u32x4*)(raw < 0 ? a.k_new + new_off : a.kv.k + off));
-                T.v[j] = __builtin_nontemporal_load((const u32x4*)(raw < 0 ? a.v_new + new_off : a.kv.v + off));
-            }
-        };
-        auto consume = [&](const Tile& T, int it) {
-            float s[U];
-            float mx = m;
-#pragma unroll
-            for (int j = 0; j < U; ++j) {
-                float d = dot8(__builtin_bit_cast(half8_t, T.k[j]), q8, 0.f);
-                d = group_sum<LPR>(d);
-                s[j] = it * TILE + wave * 16 + j * RPW + r < nc ? d * a.scale_log2 : -__builtin_inff();
-                mx = fmaxf(mx, s[j]);
-            }
-            const float al = fast_exp2(m - mx);
-            m = mx;
-            l *= al;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) acc[e] *= al;
-#pragma unroll
-            for (int j = 0; j < U; ++j) {
-                const float p = fast_exp2(s[j] - mx);
-                l += p;
-                const half8_t vh = __builtin_bit_cast(half8_t, T.v[j]);
-#pragma unroll
-                for (int e = 0; e < 8; ++e) acc[e] = __builtin_fmaf((float)vh[e], p, acc[e]);
-            }
-        };
-        const int n_it = (nc + TILE - 1) / TILE;
-        Tile A, B;
-        load(A, 0);
-        for (int it = 0; it < n_it; it += 2) {
-            load(B, it + 1);
-            pin_order();
-            consume(A, it);
-            load(A, it + 2);
-            pin_order();
-            if (it + 1 < n_it) consume(B, it + 1);
-        }
-    }
-
-    const int g = wave * RPW + r;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) s_acc[g][c * 8 + e] = acc[e];
-    if (c == 0) {
-        s_m[g] = m;
-        s_l[g] = l;
-    }
-    __syncthreads();
-    if (tid < D) {
-        float M = kNegBig;
-#pragma unroll 8
-        for (int i = 0; i < NG; ++i) M = fmaxf(M, s_m[i]);
-        float lsum = 0.f, o = 0.f;
-#pragma unroll 8
-        for (int i = 0; i < NG; ++i) {
-            const float w = fast_exp2(s_m[i] - M);
-            lsum += w * s_l[i];
-            o += w * s_acc[i][tid];
-        }
-        if (part != nullptr) {
-            part[tid] = o;
-            if (tid == 0) {
-                part[D] = M;
-                part[D + 1] = lsum;
-            }
-            return;
-        }
-        o /= lsum;
-        // step 11: alpha * (attention over the kept rows) + (1 - alpha) * mean of V
-        const int64_t vi = ((int64_t)b * a.num_kv_heads + hk) * D + tid;
-        float vs = a.aux.vsum[vi];
-        if (fresh) vs += (float)a.v_new[vi];
-        const float vbar = vs / (float)L;
-        o = alpha * o + (1.f - alpha) * vbar;
-        if (a.out_f32) ((float*)a.out)[row * D + tid] = o;
-        else ((half_t*)a.out)[row * D + tid] = (half_t)o;
-    }
-}
-
-// Component d of the new token of (sequence b, KV head hk) goes into the cache row,
-// the column copy and the V sum; L is the length including that token.
-__device__ __forceinline__ void append_component(const SparfArgs& a, int b, int hk, int d, int L)
-{
-    if (L < 1 || L > a.kv.capacity || L > a.aux.capacity) return;
-    const int t = L - 1;
-    const int64_t i = ((int64_t)b * a.num_kv_heads + hk) * a.head_dim + d;
-    const half_t kn = a.k_new[i], vn = a.v_new[i];
-    const int64_t off = row_offset(a.kv, b, hk, t) + d;
-    const_cast<half_t*>(a.kv.k)[off] = kn;
-    const_cast<half_t*>(a.kv.v)[off] = vn;
-    kt_col0(a.aux, b, hk, t)[(int64_t)d * a.aux.stride_d] = kn;
-    a.aux.vsum[i] += (float)vn;
-}
-
-template <int D>
-__device__ __forceinline__ void write_zero_row(const SparfArgs& a, int64_t row)
-{
-    if ((int)threadIdx.x < D) {
-        if (a.out_f32) ((float*)a.out)[row * D + threadIdx.x] = 0.f;
-        else ((half_t*)a.out)[row * D + threadIdx.x] = (half_t)0.f;
-    }
-}
-
-}  // namespace
 
 // ---------------------------------------------------------------------------
 // Steps 1-4 (without the normaliser), long rows.  A block of 256 threads ranks the
