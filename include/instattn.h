@@ -282,8 +282,8 @@ size_t instattn_sparf_workspace_size(int batch, int num_q_heads, int head_dim, i
  * or three with a block per 8192 scores when there are few heads with long rows),
  * attention over the kept rows, and a launch that combines the slices when a
  * head's kept rows are cut up.
- * A paged cache is limited to num_pages*page_size < 2^31 rows here
- * (INSTATTN_ERR_UNSUPPORTED beyond).
+ * A paged cache is limited to num_pages*page_size < 2^31 rows here, max_seq_len to
+ * 2^30 (INSTATTN_ERR_UNSUPPORTED beyond).
  */
 int instattn_sparf_decode(const void* q, const instattn_kv_desc* kv, const instattn_sparf_aux* aux,
                           const int32_t* seq_lens, int batch, int num_q_heads, int num_kv_heads,

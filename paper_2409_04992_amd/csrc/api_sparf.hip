@@ -80,10 +80,10 @@ SparfPlan plan_sparf(int batch, int num_q_heads, int num_kv_heads, int max_seq_l
     }
     const char* force3 = getenv("INSTATTN_SPARF_THREE_LAUNCHES");
     // Rows behind the 256-thread form's limit take the one-launch kernel's 512-thread form
-    // (up to 18432 positions; up to 36864 one of 1024 threads) when there are heads enough for
-    // one block each (measured at 16K rows: 160 heads
-    // 52 us against the pipeline's 63, 120 heads 48 against 55, 80 heads 46 against 48,
-    // 40 heads 44 against 40; INSTATTN_SPARF_WIDE forces either way).
+    // (up to 18432 positions; up to 36864 one of 1024 threads) when there are heads enough
+    // for one block each.  Measured at 16K rows: 160 heads 52 us against the pipeline's 63,
+    // 120 heads 48 against 55, 80 heads 46 against 48, 40 heads 44 against 40.
+    // INSTATTN_SPARF_WIDE forces either way.
     const char* wide_env = getenv("INSTATTN_SPARF_WIDE");
     const bool force_wide = wide_env && wide_env[0] == '1', forbid_wide = wide_env && wide_env[0] == '0';
     p.fused_threads = 0;
@@ -198,6 +198,7 @@ int instattn_sparf_plan(int batch, int num_q_heads, int num_kv_heads, int head_d
     if (!plan || batch <= 0 || num_q_heads <= 0 || num_kv_heads <= 0 || num_q_heads % num_kv_heads ||
         max_seq_len <= 0 || k <= 0)
         return INSTATTN_ERR_INVALID_ARG;
+    if (max_seq_len > kSparfMaxSeqLen) return INSTATTN_ERR_UNSUPPORTED;
     if (head_dim != 64 && head_dim != 128) return head_dim > 0 ? INSTATTN_ERR_UNSUPPORTED : INSTATTN_ERR_INVALID_ARG;
     const SparfPlan p = plan_sparf(batch, num_q_heads, num_kv_heads, max_seq_len, k, with_append != 0);
     plan[0] = p.launches;
@@ -211,7 +212,7 @@ int instattn_sparf_plan(int batch, int num_q_heads, int num_kv_heads, int head_d
 
 size_t instattn_sparf_workspace_size(int batch, int num_q_heads, int head_dim, int max_seq_len, int k)
 {
-    if (batch <= 0 || num_q_heads <= 0 || max_seq_len <= 0 || k <= 0) return 0;
+    if (batch <= 0 || num_q_heads <= 0 || max_seq_len <= 0 || max_seq_len > kSparfMaxSeqLen || k <= 0) return 0;
     if (head_dim != 64 && head_dim != 128) return 0;
     return carve(batch, num_q_heads, head_dim, max_seq_len, k).total;
 }
@@ -236,6 +237,7 @@ int run_sparf_decode(const void* q, const void* k_new, const void* v_new, bool a
     if (out_dtype != INSTATTN_F16 && out_dtype != INSTATTN_F32) return INSTATTN_ERR_INVALID_ARG;
     if (r < 1 || r > head_dim || k < 1 || l < 0) return INSTATTN_ERR_INVALID_ARG;
     if (max_seq_len > kv->capacity || max_seq_len > aux->capacity) return INSTATTN_ERR_INVALID_ARG;
+    if (max_seq_len > kSparfMaxSeqLen) return INSTATTN_ERR_UNSUPPORTED;
     const Carve c = carve(batch, num_q_heads, head_dim, max_seq_len, k);
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < c.total)
         return INSTATTN_ERR_WORKSPACE;

@@ -355,6 +355,9 @@ def test_sparf_plan_rejects():
         with pytest.raises(B.InstattnError) as e:
             B.sparf_plan(*args)
         assert e.value.status == B.ERR_INVALID_ARG
-    with pytest.raises(B.InstattnError) as e:
-        B.sparf_plan(1, 4, 4, 96, 100, 10)
-    assert e.value.status == B.ERR_UNSUPPORTED
+    for args in [(1, 4, 4, 96, 100, 10), (1, 4, 4, 128, (1 << 30) + 1, 10)]:
+        with pytest.raises(B.InstattnError) as e:
+            B.sparf_plan(*args)
+        assert e.value.status == B.ERR_UNSUPPORTED
+    assert B.sparf_workspace_size(1, 4, 128, (1 << 30) + 1, 10) == 0
+    assert B.sparf_workspace_size(1, 4, 128, 1 << 30, 10) > (1 << 30) * 4 * 4
