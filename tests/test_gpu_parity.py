@@ -103,6 +103,20 @@ def test_config5_gqa_layer_full_shape_sampled(fused):
     assert torch.equal(case.v_cache[:, :, L - 1].view(torch.int16), case.v_new.view(torch.int16))
 
 
+@pytest.mark.parametrize("shape", ["mha_1m", "gqa_512k_paged", "mha64_600k"])
+def test_one_very_long_sequence(shape):
+    """A single sequence far beyond the measured configurations: hundreds of units per
+    head (the merge takes its form for many units), page tables of tens of thousands of
+    entries, row offsets of hundreds of MB."""
+    wl = {
+        "mha_1m": W.Workload("long_mha", 1, 2, 2, 128, 1 << 20, seed=431),
+        "gqa_512k_paged": W.Workload("long_gqa", 1, 8, 1, 128, (1 << 19) + 77, paged=True, page_size=16, seed=432),
+        "mha64_600k": W.Workload("long_mha64", 2, 1, 1, 64, 600_000, seq_len_min=400_000, out_dtype="f32", seed=433),
+    }[shape]
+    pairs = [(0, 0), (wl.batch - 1, wl.num_q_heads - 1)]
+    sampled_check(wl, pairs, poison=True, fused=True)
+
+
 @pytest.mark.parametrize("fused", [False, True])
 def test_config5_gqa_scaled_down_full_check(fused):
     full_check(small("gqa70b_16k", batch=3, seq_len=1500, layers=1), fused=fused)
