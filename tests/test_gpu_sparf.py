@@ -315,6 +315,16 @@ def test_sparf_wide_one_launch_equals_the_pipeline(monkeypatch):
     assert (a[0] - b[0]).abs().max() <= 2e-6 and (a[2] - b[2]).abs().max() <= 1e-6
 
 
+@pytest.mark.parametrize("distributed", ["0", "1"])
+def test_sparf_one_very_long_sequence(monkeypatch, distributed):
+    """A million positions per head, 65536 kept: 128 stretches per head in the
+    distributed selection, the pass-over-memory selection in the one-block form, eight
+    slices of 8192 kept rows each."""
+    monkeypatch.setenv("INSTATTN_SPARF_DISTRIBUTED", distributed)
+    wl = W.Workload("sparf_1m", 1, 2, 2, 128, 1 << 20, seed=418)
+    sparf_step(wl, 16, 1 << 16, 16, torch.float16)
+
+
 def test_sparf_distributed_selection_equals_one_block_per_head(monkeypatch):
     """Same kept rows bit for bit, alpha and out up to the order of the mass sum; ragged
     lengths so that heads use different numbers of stretches; repeated (the gathered
