@@ -13,9 +13,19 @@ namespace {
 
 size_t up256(size_t x) { return (x + 255) / 256 * 256; }
 
+// Room in the distributed selection's list of threshold-bin members: with 256 level-1
+// bins a row of L evenly spread scores puts about L / 200 of them into the bin (5000 at
+// a million positions), so the list grows with the row.
+int member_cap_for(int max_seq_len)
+{
+    int cap = kSparfMemberCap;
+    while (cap < max_seq_len / 64 && cap < 65536) cap *= 2;
+    return cap;
+}
+
 struct Carve {
-    size_t logits, stats, sel, alpha, part, hist, gt1, counters, state, members, mass_part, total;
-    int lpad, nchunk, nstat;
+    size_t logits, stats, sel, alpha, part, hist, gt1, counters, state, members, mass_part, rowstat, total;
+    int lpad, nchunk, nstat, member_cap;
 };
 
 Carve carve(int batch, int num_q_heads, int head_dim, int max_seq_len, int k)
@@ -24,6 +34,7 @@ Carve carve(int batch, int num_q_heads, int head_dim, int max_seq_len, int k)
     c.nchunk = (max_seq_len + kSparfChunk - 1) / kSparfChunk;
     c.lpad = c.nchunk * kSparfChunk;
     c.nstat = c.lpad / kSparfStatRun;
+    c.member_cap = member_cap_for(max_seq_len);
     const size_t rows = (size_t)batch * num_q_heads;
     c.logits = 0;
     c.stats = c.logits + up256(rows * c.lpad * sizeof(float));
@@ -37,8 +48,9 @@ Carve carve(int batch, int num_q_heads, int head_dim, int max_seq_len, int k)
     c.counters = c.gt1 + up256(lr * c.nchunk * sizeof(uint32_t));
     c.state = c.counters + up256(lr * 2 * sizeof(uint32_t));
     c.members = c.state + up256(lr * 2 * sizeof(uint32_t));
-    c.mass_part = c.members + up256(lr * kSparfMemberCap * 2 * sizeof(uint32_t));
-    c.total = c.mass_part + up256(lr * c.nchunk * sizeof(float));
+    c.mass_part = c.members + up256(lr * c.member_cap * 2 * sizeof(uint32_t));
+    c.rowstat = c.mass_part + up256(lr * c.nchunk * sizeof(float));
+    c.total = c.rowstat + up256(lr * 4 * sizeof(float));
     return c;
 }
 
@@ -269,7 +281,10 @@ int run_sparf_decode(const void* q, const void* k_new, const void* v_new, bool a
     a.counters = (uint32_t*)(ws + c.counters);
     a.state = (uint32_t*)(ws + c.state);
     a.members = (uint32_t*)(ws + c.members);
+    a.member_cap = c.member_cap;
+    a.nparts = c.nchunk < kSparfHistParts ? c.nchunk : kSparfHistParts;
     a.mass_part = (float*)(ws + c.mass_part);
+    a.rowstat = (float*)(ws + c.rowstat);
     const SparfPlan plan = plan_sparf(batch, num_q_heads, num_kv_heads, max_seq_len, k, append);
     a.distributed = plan.distributed;
     a.nslices = plan.nslices;

@@ -9,7 +9,8 @@ constexpr int kSparfChunk = 8192;      // positions per block of the approximate
 constexpr int kSparfMaxSeqLen = 1 << 30;  // longest row accepted (the padded row length stays an int32)
 constexpr int kSparfStatRun = 512;     // scores per entry of the score statistics (a wave's share of a unit)
 constexpr int kSparfAttendWaves = 8;
-constexpr int kSparfMemberCap = 1024;  // members of the threshold bin the distributed selection ranks directly
+constexpr int kSparfMemberCap = 1024;  // members of the threshold bin the distributed selection ranks through LDS
+constexpr int kSparfHistParts = 32;    // most level-1 histograms kept per row by the distributed selection
 constexpr int kSparfMaxSlices = 8;      // most slices the attend kernel cuts a head's kept rows into
 constexpr int kSparfAttendIds = 4096;   // kept rows staged in LDS at a time by the attend kernel
 
@@ -52,12 +53,15 @@ struct SparfArgs {
     int32_t fused_threads;             // one-launch kernel: threads per head (256, 512 or 1024)
     // selection of a head spread over one block per stretch (few heads, long rows)
     int32_t distributed;
-    uint32_t* hist;                    // [B][Hq][nchunk][256] level-1 histogram of every stretch
+    uint32_t* hist;                    // [B][Hq][nparts][256] level-1 histograms: part p covers stretches p, p + nparts, ...
+    int32_t nparts;                    // min(nchunk, kSparfHistParts)
     uint32_t* gt1;                     // [B][Hq][nchunk] scores of the stretch in bins above the threshold bin
     uint32_t* counters;                // [B][Hq][2]: members gathered, spare
     uint32_t* state;                   // [B][Hq][2]: threshold bin, rows still wanted inside it
-    uint32_t* members;                 // [B][Hq][kSparfMemberCap][2]: key and stretch of the bin's members
+    uint32_t* members;                 // [B][Hq][member_cap][2]: key and stretch of the bin's members
+    int32_t member_cap;                // room in that list: kSparfMemberCap, more for very long rows
     float* mass_part;                  // [B][Hq][nchunk] softmax mass kept per stretch
+    float* rowstat;                    // [B][Hq][4]: a row's max, min and sum of 2^(x - max), folded by sparf_hist_kernel
     void* out;
     int32_t out_f32;
     const half_t* k_new;               // append, or decode with the append fused in

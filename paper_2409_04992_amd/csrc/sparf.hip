@@ -236,26 +236,25 @@ __global__ __launch_bounds__(256, INSTATTN_SPARF_WAVES_PER_SIMD) void sparf_logi
 }
 
 // Maximum, minimum and sum of 2^(x - maximum) of a row from those of its runs of
-// 512 scores: lane c takes run c (then 64 + c ...), every wave (and every block)
-// gets the same values.
+// 512 scores: lane c folds runs c, 64 + c, ... in that order (independent loads, no
+// cross-lane traffic inside the loop), then the 64 lanes are combined once.  The
+// order is fixed; every wave (and every block) gets the same values.
 __device__ __forceinline__ void row_stats(const SparfArgs& a, int64_t row, int L, float& M, float& xmin, float& Z)
 {
     const int nc = (L + kSparfStatRun - 1) / kSparfStatRun;
     const float* st = a.stats + row * a.nstat * 3;
     const int lane = threadIdx.x & 63;
-    M = kNegBig;
-    xmin = -kNegBig;
-    Z = 0.f;
-    for (int c0 = 0; c0 < nc; c0 += 64) {
-        const bool in = c0 + lane < nc;
-        const float mc = in ? st[3 * (c0 + lane)] : kNegBig;
-        const float zc = in ? st[3 * (c0 + lane) + 1] : 0.f;
-        const float nc_min = in ? st[3 * (c0 + lane) + 2] : -kNegBig;
-        const float Mn = fmaxf(M, wave_max(mc));
-        Z = Z * fast_exp2(M - Mn) + wave_sum(zc * fast_exp2(mc - Mn));
-        M = Mn;
-        xmin = fminf(xmin, -wave_max(-nc_min));
+    float m = kNegBig, mn = -kNegBig, z = 0.f;
+    for (int c = lane; c < nc; c += 64) {
+        const float mc = st[3 * c], zc = st[3 * c + 1], nc_min = st[3 * c + 2];
+        const float m2 = fmaxf(m, mc);
+        z = z * fast_exp2(m - m2) + zc * fast_exp2(mc - m2);
+        m = m2;
+        mn = fminf(mn, nc_min);
     }
+    M = wave_max(m);
+    Z = wave_sum(z * fast_exp2(m - M));
+    xmin = -wave_max(-mn);
 }
 
 // Steps 4 (normaliser) to 7, long rows: one block per head over the stored scores.
@@ -323,26 +322,39 @@ __device__ __forceinline__ StretchView stretch_view(const SparfArgs& a, int b, i
 __global__ __launch_bounds__(256) void sparf_hist_kernel(SparfArgs a)
 {
     constexpr int NT = 256, STEPS = kSparfChunk / (NT * 8);
-    const int h = blockIdx.x, chunk = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
+    const int h = blockIdx.x, part = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
     const int64_t row = (int64_t)b * a.num_q_heads + h;
-    const StretchView v = stretch_view(a, b, chunk);
-    if (chunk == 0 && tid < 2) a.counters[row * 2 + tid] = 0;
-    if (v.want <= 0 || v.t0 >= v.ncand) return;
-    float xr[STEPS][8];
-    own_scores<NT, STEPS>(a.logits + row * a.lpad + v.t0, v.ncand - v.t0, xr);
+    const StretchView v = stretch_view(a, b, part);
+    if (part == 0 && tid < 2) a.counters[row * 2 + tid] = 0;
+    const bool idle = v.want <= 0 || v.t0 >= v.ncand;      // no stretch with candidates for this block
+    if (v.L == 0 || (idle && part != 0)) return;
     float M, xmin, Z;
     row_stats(a, row, v.L, M, xmin, Z);
+    // the row's statistics, folded once, for the launches behind this one
+    if (part == 0 && tid == 0) {
+        float* rs = a.rowstat + row * 4;
+        rs[0] = M;
+        rs[1] = xmin;
+        rs[2] = Z;
+    }
+    if (idle) return;
     const Level1 level1(M, xmin);
     __shared__ uint32_t s_hist[256];
     s_hist[tid] = 0;
     __syncthreads();
+    // this block's stretches: every nparts-th one (a very long row has more stretches than
+    // histograms are kept for it)
+    for (int t0 = v.t0; t0 < v.ncand; t0 += a.nparts * kSparfChunk) {
+        float xr[STEPS][8];
+        own_scores<NT, STEPS>(a.logits + row * a.lpad + t0, v.ncand - t0, xr);
 #pragma unroll
-    for (int i = 0; i < STEPS; ++i)
+        for (int i = 0; i < STEPS; ++i)
 #pragma unroll
-        for (int e = 0; e < 8; ++e)
-            if (v.t0 + (i * NT + tid) * 8 + e < v.ncand) atomicAdd(&s_hist[level1(xr[i][e])], 1u);
+            for (int e = 0; e < 8; ++e)
+                if (t0 + (i * NT + tid) * 8 + e < v.ncand) atomicAdd(&s_hist[level1(xr[i][e])], 1u);
+    }
     __syncthreads();
-    a.hist[(row * a.nchunk + chunk) * 256 + tid] = s_hist[tid];
+    a.hist[(row * a.nparts + part) * 256 + tid] = s_hist[tid];
 }
 
 __global__ __launch_bounds__(256) void sparf_members_kernel(SparfArgs a)
@@ -354,21 +366,21 @@ __global__ __launch_bounds__(256) void sparf_members_kernel(SparfArgs a)
     if (v.want <= 0 || v.t0 >= v.ncand) return;
     float xr[STEPS][8];
     own_scores<NT, STEPS>(a.logits + row * a.lpad + v.t0, v.ncand - v.t0, xr);
-    float M, xmin, Z;
-    row_stats(a, row, v.L, M, xmin, Z);
+    const float M = a.rowstat[row * 4], xmin = a.rowstat[row * 4 + 1];
     const Level1 level1(M, xmin);
 
     __shared__ SelectScratch S;
     __shared__ uint32_t s_keys[kSparfMemberCap];
     __shared__ uint32_t s_n, s_above, s_base;
     uint32_t total = 0;
-    const uint32_t* hp = a.hist + row * a.nchunk * 256 + tid;
+    const uint32_t* hp = a.hist + row * a.nparts * 256 + tid;
+    const int np = min(a.nparts, v.ncc);                   // histograms that were written
     int c = 0;
-    for (; c + 4 <= v.ncc; c += 4) {
+    for (; c + 4 <= np; c += 4) {
         const uint32_t h0 = hp[c * 256], h1 = hp[(c + 1) * 256], h2 = hp[(c + 2) * 256], h3 = hp[(c + 3) * 256];
         total += (h0 + h1) + (h2 + h3);
     }
-    for (; c < v.ncc; ++c) total += hp[c * 256];
+    for (; c < np; ++c) total += hp[c * 256];
     S.hist[tid] = total;
     if (tid == 0) s_n = s_above = 0;
     __syncthreads();
@@ -399,12 +411,14 @@ __global__ __launch_bounds__(256) void sparf_members_kernel(SparfArgs a)
     if (tid == 0) {
         a.gt1[row * a.nchunk + chunk] = s_above;
         s_base = atomicAdd(&a.counters[row * 2], n);       // more than the cap in all: the list is not used
+        // more members in this stretch alone than are staged here: the list is not used either
+        if (n > (uint32_t)kSparfMemberCap) atomicOr(&a.counters[row * 2 + 1], 1u);
     }
     __syncthreads();
-    const uint32_t base = s_base;
+    const uint32_t base = s_base, cap = (uint32_t)a.member_cap;
     for (uint32_t j = tid; j < n && j < (uint32_t)kSparfMemberCap; j += NT) {
-        if (base + j < (uint32_t)kSparfMemberCap) {
-            uint32_t* m = a.members + (row * kSparfMemberCap + base + j) * 2;
+        if (base + j < cap) {
+            uint32_t* m = a.members + ((uint64_t)row * cap + base + j) * 2;
             m[0] = s_keys[j];
             m[1] = (uint32_t)chunk;
         }
@@ -425,10 +439,47 @@ __global__ __launch_bounds__(256) void sparf_compact_kernel(SparfArgs a)
     __shared__ SelectScratch S;
     const float* x = a.logits + row * a.lpad;
     int32_t* sel = a.sel + row * a.k;
-    float M, xmin, Z;
-    row_stats(a, row, v.L, M, xmin, Z);
+    const float M = a.rowstat[row * 4], xmin = a.rowstat[row * 4 + 1], Z = a.rowstat[row * 4 + 2];
     const uint32_t nmem = v.want > 0 ? a.counters[row * 2] : 0u;
-    if (v.want <= 0 || nmem > (uint32_t)kSparfMemberCap) {
+    const uint32_t cap = (uint32_t)a.member_cap;
+    const uint32_t* mem = a.members + (uint64_t)row * cap * 2;     // key, stretch
+    // The members of the threshold bin are ranked against each other: the threshold key
+    // has fewer than rem1 keys above it and at least rem1 at or above.  Up to
+    // kSparfMemberCap of them go through LDS; longer lists (rows of hundreds of thousands
+    // of positions) are ranked from the workspace: 256 finer buckets over the whole list,
+    // then the members of the one bucket that holds the threshold directly.
+    __shared__ __align__(16) uint32_t s_mkey[kSparfMemberCap];
+    __shared__ __align__(16) uint32_t s_mkey2[kSparfMemberCap];
+    __shared__ uint16_t s_mchunk[kSparfMemberCap];
+    __shared__ uint32_t s_gtb, s_eqb;
+    const Level1 level1(M, xmin);
+    const uint32_t rem1 = v.want > 0 ? a.state[row * 2 + 1] : 0u;
+    bool one_block = v.want <= 0 || nmem > cap || a.counters[row * 2 + 1] != 0;
+    const bool long_list = !one_block && nmem > (uint32_t)kSparfMemberCap;
+    uint32_t rem2 = 0, nsub = 0;
+    if (long_list) {
+        // every block of the head takes the same decisions from the same list
+        S.hist[tid] = 0;
+        if (tid == 0) S.nsub = 0;
+        __syncthreads();
+        for (uint32_t i = tid; i < nmem; i += NT) atomicAdd(&S.hist[level1.sub(key_score(mem[2 * i]))], 1u);
+        __syncthreads();
+        if (tid < 64) locate_bin(S, rem1, tid);
+        __syncthreads();
+        const uint32_t bucket = S.prefix;
+        rem2 = S.remaining;
+        for (uint32_t i = tid; i < nmem; i += NT) {
+            const uint32_t key = mem[2 * i];
+            if (level1.sub(key_score(key)) == bucket) {
+                const uint32_t j = atomicAdd(&S.nsub, 1u);
+                if (j < (uint32_t)kSparfMemberCap) s_mkey2[j] = key;
+            }
+        }
+        __syncthreads();
+        nsub = S.nsub;
+        if (nsub > (uint32_t)kSparfMemberCap) one_block = true;     // that many near-equal scores
+    }
+    if (one_block) {
         // nothing to pick among the candidates, or too many scores in the threshold bin:
         // the block of stretch 0 does the whole row the one-block way
         if (chunk == 0) {
@@ -445,33 +496,43 @@ __global__ __launch_bounds__(256) void sparf_compact_kernel(SparfArgs a)
     }
     float xr[STEPS][8];
     own_scores<NT, STEPS>(x + v.t0, v.ncand - v.t0, xr);
-    const Level1 level1(M, xmin);
-    const uint32_t bin1 = a.state[row * 2], rem1 = a.state[row * 2 + 1];
+    const uint32_t bin1 = a.state[row * 2];
 
-    // the members of the threshold bin: rank them against each other (the threshold key
-    // has fewer than rem1 keys above it and at least rem1 at or above)
-    __shared__ __align__(16) uint32_t s_mkey[kSparfMemberCap];
-    __shared__ __align__(16) uint32_t s_mkey2[kSparfMemberCap];
-    __shared__ uint16_t s_mchunk[kSparfMemberCap];
-    __shared__ uint32_t s_gtb, s_eqb;
-    for (uint32_t i = tid; i < nmem; i += NT) {
-        const uint32_t* m = a.members + (row * kSparfMemberCap + i) * 2;
-        s_mkey[i] = m[0];
-        s_mchunk[i] = (uint16_t)m[1];
-    }
     if (tid == 0) s_gtb = s_eqb = 0;
-    __syncthreads();
-    rank_members<NT>(s_mkey, s_mkey2, nmem, (uint32_t)kSparfMemberCap, rem1, level1, S);
-    __syncthreads();
-    const uint32_t thr = S.prefix, rem_eq = S.remaining;
+    uint32_t thr, rem_eq;
     // kept rows in front of this stretch: scores in higher bins and members above the
     // threshold key of earlier stretches; rows at the threshold key likewise
     // (every thread counts its share, one LDS atomic per wave; all loads in flight at once)
     uint32_t gtb = 0, eqb = 0;
-    for (uint32_t i = tid; i < nmem; i += NT) {
-        if ((int)s_mchunk[i] < chunk) {
-            gtb += s_mkey[i] > thr;
-            eqb += s_mkey[i] == thr;
+    if (long_list) {
+        if (tid < 3 && nsub + tid < (uint32_t)kSparfMemberCap) s_mkey2[nsub + tid] = 0;
+        __syncthreads();
+        rank_directly<NT>(s_mkey2, nsub, rem2, S);
+        __syncthreads();
+        thr = S.prefix;
+        rem_eq = S.remaining;
+        for (uint32_t i = tid; i < nmem; i += NT) {
+            const uint32_t key = mem[2 * i];
+            if ((int)mem[2 * i + 1] < chunk) {
+                gtb += key > thr;
+                eqb += key == thr;
+            }
+        }
+    } else {
+        for (uint32_t i = tid; i < nmem; i += NT) {
+            s_mkey[i] = mem[2 * i];
+            s_mchunk[i] = (uint16_t)mem[2 * i + 1];
+        }
+        __syncthreads();
+        rank_members<NT>(s_mkey, s_mkey2, nmem, (uint32_t)kSparfMemberCap, rem1, level1, S);
+        __syncthreads();
+        thr = S.prefix;
+        rem_eq = S.remaining;
+        for (uint32_t i = tid; i < nmem; i += NT) {
+            if ((int)s_mchunk[i] < chunk) {
+                gtb += s_mkey[i] > thr;
+                eqb += s_mkey[i] == thr;
+            }
         }
     }
     for (int c = tid; c < chunk; c += NT) gtb += a.gt1[row * a.nchunk + c];
@@ -506,8 +567,7 @@ __global__ __launch_bounds__(256) void sparf_compact_kernel(SparfArgs a)
 // Step 7 after the distributed selection: the stretches' shares in stretch order.
 __device__ __forceinline__ float distributed_alpha(const SparfArgs& a, int64_t row, int L)
 {
-    float M, xmin, Z;
-    row_stats(a, row, L, M, xmin, Z);
+    const float Z = a.rowstat[row * 4 + 2];
     float kept = 0.f;
     for (int c = 0; c < a.nchunk; ++c) kept += a.mass_part[row * a.nchunk + c];
     return kept / Z;
@@ -829,7 +889,7 @@ hipError_t launch_sparf_select(const SparfArgs& a, hipStream_t stream)
 {
     if (a.distributed) {
         dim3 dgrid(a.num_q_heads, a.nchunk, a.batch);
-        hipLaunchKernelGGL(sparf_hist_kernel, dgrid, dim3(256), 0, stream, a);
+        hipLaunchKernelGGL(sparf_hist_kernel, dim3(a.num_q_heads, a.nparts, a.batch), dim3(256), 0, stream, a);
         hipLaunchKernelGGL(sparf_members_kernel, dgrid, dim3(256), 0, stream, a);
         hipLaunchKernelGGL(sparf_compact_kernel, dgrid, dim3(256), 0, stream, a);
         return hipGetLastError();

@@ -362,6 +362,33 @@ def test_sparf_long_rows_of_equal_scores(monkeypatch, distributed):
     assert (alpha - 1000 / 20000).abs().max() < 1e-6
 
 
+@pytest.mark.parametrize("seq_len,k", [(300_000, 20_000), (524_288, 1000)])
+def test_sparf_distributed_long_member_lists(monkeypatch, seq_len, k):
+    """Rows so long that the threshold bin holds more scores than go through LDS: the
+    list is ranked from the workspace (finer buckets, then the one bucket directly)."""
+    monkeypatch.setenv("INSTATTN_SPARF_DISTRIBUTED", "1")
+    wl = W.Workload("sparf_long_list", 1, 2, 1, 128, seq_len, seed=419)
+    sparf_step(wl, 16, k, 16, torch.float32)
+
+
+def test_sparf_distributed_long_list_of_near_ties(monkeypatch):
+    """A long row whose keys repeat 61 distinct rows: a few dozen distinct scores, each
+    thousands of times.  The list of the threshold bin is long and its finer bucket still
+    holds more than can be ranked directly: the block of stretch 0 selects the whole row.
+    Ties go to the lower position either way."""
+    monkeypatch.setenv("INSTATTN_SPARF_DISTRIBUTED", "1")
+    wl = W.Workload("sparf_near_ties", 1, 2, 2, 128, 280_000, seed=420)
+    case, desc, aux, kt, vsum, _ = setup(wl)
+    L = int(case.seq_lens[0])
+    idx = torch.randint(0, 61, (L,), device=DEV, generator=torch.Generator(device=DEV).manual_seed(5))
+    case.k_cache[:, :, :L] = case.k_cache[:, :, :61][:, :, idx]
+    case.k_new[:] = case.k_cache[:, :, L - 1]
+    B.sparf_build(desc, aux, (case.seq_lens - 1).contiguous(), 2, 128)
+    B.sparf_append(desc, aux, case.k_new, case.v_new, case.seq_lens)
+    out, sel, alpha = run_decode(case, desc, aux, 16, 30_000, 16, torch.float32)
+    check_against_oracle(case, out, sel, alpha, 16, 30_000, 16)
+
+
 def test_sparf_distributed_edge_lengths(monkeypatch):
     """Lengths around the stretch edges, k below l, k above the length, an empty row."""
     monkeypatch.setenv("INSTATTN_SPARF_DISTRIBUTED", "1")
