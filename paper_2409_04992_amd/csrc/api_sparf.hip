@@ -73,12 +73,14 @@ SparfPlan plan_sparf(int batch, int num_q_heads, int num_kv_heads, int max_seq_l
     // One block per head selects well when there are heads enough to fill the chip or
     // the rows are short; few heads with long rows spread each head's selection over
     // its stretches (three launches).  Measured: one block takes about max_len / 1100
-    // us per round of 256 heads, the distributed form 24 us + 0.015 us per block.
+    // us per round of 256 heads, the distributed form 24 us + 0.015 us per block.  With
+    // many heads the two come close (640 heads x 128K: 1.31 ms against 1.48 ms for the
+    // step; 2560 heads x 32K: 1.30 against 1.28), so there the estimate must win clearly.
     {
         const double one_block = max_seq_len / 1100.0 * (double)((heads + 255) / 256);
-        const double spread = 24.0 + 0.015 * (double)heads * nchunk;
+        const double spread = (24.0 + 0.015 * (double)heads * nchunk) * (heads <= 512 ? 1.0 : 1.3);
         const char* e = getenv("INSTATTN_SPARF_DISTRIBUTED");
-        p.distributed = e ? (e[0] == '1') : (max_seq_len > 2 * kSparfChunk && heads <= 512 && spread < one_block);
+        p.distributed = e ? (e[0] == '1') : (max_seq_len > 2 * kSparfChunk && spread < one_block);
     }
     // Slices of a head's kept rows for the attend kernel: enough blocks to fill the
     // chip when there are few heads, none smaller than 256 rows.

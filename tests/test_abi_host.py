@@ -302,6 +302,9 @@ def test_sparf_plan_of_the_measured_shapes(no_sparf_env):
     # 1 x 40 heads x 128K
     p = B.sparf_plan(1, 40, 40, 128, 131073, 8192)
     assert p["selection"] == 2 and p["slices"] == 8 and p["launches"] == 6
+    # many heads: spread when the estimate wins clearly (16 x 40 x 128K), else one block per head
+    assert B.sparf_plan(16, 40, 40, 128, 131073, 8192)["selection"] == 2
+    assert B.sparf_plan(16, 40, 40, 128, 32769, 2048)["selection"] == 1
 
 
 def test_sparf_plan_limits_of_the_one_launch_kernel(no_sparf_env):
@@ -323,9 +326,14 @@ def test_sparf_plan_pipeline_tail(no_sparf_env):
     p = B.sparf_plan(32, 40, 40, 128, 20000, 1000)
     assert p == {"launches": 2, "one_launch_threads": 0, "append_fused": False, "selection": 1,
                  "select_and_gather": True, "slices": 1}
-    # ... not behind 65535 positions, where the selection passes over memory
+    # ... not behind 65535 positions, where the one-block selection passes over memory (and the
+    # host prefers the spread form: 5 launches)
     p = B.sparf_plan(32, 40, 40, 128, 70000, 1000)
-    assert not p["select_and_gather"] and p["launches"] == 3
+    assert not p["select_and_gather"] and p["selection"] == 2 and p["launches"] == 5
+    no_sparf_env.setenv("INSTATTN_SPARF_DISTRIBUTED", "0")
+    p = B.sparf_plan(32, 40, 40, 128, 70000, 1000)
+    assert not p["select_and_gather"] and p["selection"] == 1 and p["launches"] == 3
+    no_sparf_env.delenv("INSTATTN_SPARF_DISTRIBUTED")
     # few heads with many kept rows: the gather is sliced, never more than 8 ways, never below 256 rows
     assert B.sparf_plan(1, 8, 8, 128, 20000, 20000)["slices"] == 8
     assert B.sparf_plan(1, 8, 8, 128, 20000, 600)["slices"] == 2
