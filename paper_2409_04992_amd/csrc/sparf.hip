@@ -795,36 +795,43 @@ __global__ __launch_bounds__(256) void sparf_build_kernel(SparfArgs a)
     }
 }
 
-// Column sums of V over rows [0, L_b): one block of 1024 threads per (sequence, KV
-// head); D / 8 adjacent threads read a row, the 1024 / (D / 8) row groups take every
-// such-th row with four loads in flight and are added in a fixed order.
-__global__ __launch_bounds__(1024) void sparf_vsum_kernel(SparfArgs a)
+// Column sums of V over rows [0, L_b): one block of 512 threads per (sequence, KV
+// head); D / 8 adjacent threads read a row, each of the 512 / (D / 8) row groups takes
+// runs of 8 consecutive rows (one page lookup per run, eight loads in flight); the
+// groups' sums are added in a fixed order.
+constexpr int kVsumThreads = 512;
+
+__global__ __launch_bounds__(kVsumThreads) void sparf_vsum_kernel(SparfArgs a)
 {
+    constexpr int NT = kVsumThreads, U = 8;
     const int hk = blockIdx.x, b = blockIdx.y;
     const int D = a.head_dim;
     const int tid = threadIdx.x;
     const int L = clamp_len(a.seq_lens[b], min(a.kv.capacity, a.aux.capacity));
     const int cols8 = D / 8;                 // 8 or 16
-    const int c8 = tid % cols8, part = tid / cols8, parts = 1024 / cols8;
-    __shared__ float s_sum[8192];            // [row group][column]: 64 x 128 or 128 x 64
+    const int c8 = tid % cols8, part = tid / cols8, parts = NT / cols8;
+    __shared__ float s_sum[NT * 8];          // [row group][column]: 32 x 128 or 64 x 64
     float vs[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) vs[e] = 0.f;
-    int t = part;
-    for (; t + 3 * parts < L; t += 4 * parts) {
-        half8_t vr[4];
+    for (int t = part * U; t < L; t += parts * U) {
+        // rows t .. t + 7 lie in one page (pages hold a multiple of 8 rows, t is a multiple of 8)
+        const half_t* p = a.kv.v + row_offset(a.kv, b, hk, t) + c8 * 8;
+        if (t + U <= L) {
+            half8_t vr[U];
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            vr[j] = *(const half8_t*)(a.kv.v + row_offset(a.kv, b, hk, t + j * parts) + c8 * 8);
+            for (int j = 0; j < U; ++j) vr[j] = __builtin_nontemporal_load((const half8_t*)(p + (int64_t)j * a.kv.stride_t));
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < U; ++j)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) vs[e] += (float)vr[j][e];
-    }
-    for (; t < L; t += parts) {
-        const half8_t vr = *(const half8_t*)(a.kv.v + row_offset(a.kv, b, hk, t) + c8 * 8);
+                for (int e = 0; e < 8; ++e) vs[e] += (float)vr[j][e];
+        } else {
+            for (int j = 0; t + j < L; ++j) {
+                const half8_t vr = *(const half8_t*)(p + (int64_t)j * a.kv.stride_t);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) vs[e] += (float)vr[e];
+                for (int e = 0; e < 8; ++e) vs[e] += (float)vr[e];
+            }
+        }
     }
 #pragma unroll
     for (int e = 0; e < 8; ++e) s_sum[part * D + c8 * 8 + e] = vs[e];
@@ -857,7 +864,7 @@ hipError_t launch_sparf_build(const SparfArgs& a, hipStream_t stream)
     if (a.head_dim == 128) hipLaunchKernelGGL(sparf_build_kernel<128>, grid, dim3(256), 0, stream, a);
     else hipLaunchKernelGGL(sparf_build_kernel<64>, grid, dim3(256), 0, stream, a);
     if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
-    hipLaunchKernelGGL(sparf_vsum_kernel, dim3(a.num_kv_heads, a.batch), dim3(1024), 0, stream, a);
+    hipLaunchKernelGGL(sparf_vsum_kernel, dim3(a.num_kv_heads, a.batch), dim3(kVsumThreads), 0, stream, a);
     return hipGetLastError();
 }
 
