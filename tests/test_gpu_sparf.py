@@ -558,3 +558,58 @@ def test_sparf_ties_go_to_the_lower_position():
     V = case.v_cache[0, :, :300].double()
     ref = (40 / 300) * V[:, want.long()].mean(dim=1) + (1 - 40 / 300) * V.mean(dim=1)
     assert (out[0].double() - ref).abs().max() < 1e-5
+
+
+# ------------------------------------------------------------------ HIP graph replay
+@pytest.mark.parametrize("form", ["one_launch", "one_launch_512", "pipeline_tail", "pipeline_distributed"])
+def test_sparf_decode_replayed_from_a_hip_graph(monkeypatch, form):
+    """The launches of a SparF decode recorded into a HIP graph, in each form the host can
+    pick: every replay — workspace overwritten and unrelated eager work in between —
+    gives the oracle's result and bit for bit the eager one (nothing in the path
+    allocates, synchronises or depends on what the workspace held before)."""
+    seq_len, k = {"one_launch": (3000, 200), "one_launch_512": (12000, 700), "pipeline_tail": (12000, 200),
+                  "pipeline_distributed": (20000, 1500)}[form]
+    monkeypatch.setenv("INSTATTN_SPARF_WIDE", "1" if form == "one_launch_512" else "0")
+    monkeypatch.setenv("INSTATTN_SPARF_DISTRIBUTED", "1" if form == "pipeline_distributed" else "0")
+    wl = W.Workload("sparf_graph", 2, 3, 3, 128, seq_len, seq_len_min=seq_len // 2, paged=True, page_size=16,
+                    seed=440)
+    case, desc, aux, kt, vsum, _ = setup(wl, kt_page=256)
+    B.sparf_append(desc, aux, case.k_new, case.v_new, case.seq_lens)
+    r, l = 16, 16
+    Bn, Hq, D = case.q.shape
+    max_len = int(case.seq_lens.max())
+    ws = torch.empty(B.sparf_workspace_size(Bn, Hq, D, max_len, k), dtype=torch.uint8, device=DEV)
+    out = torch.empty(Bn, Hq, D, dtype=torch.float32, device=DEV)
+    sel = torch.empty(Bn, Hq, k, dtype=torch.int32, device=DEV)
+    alpha = torch.empty(Bn, Hq, dtype=torch.float32, device=DEV)
+
+    def step():
+        B.sparf_decode(case.q, desc, aux, case.seq_lens, wl.num_kv_heads, case.scale, r, k, l, out, ws,
+                       max_len, sel_rows=sel, alpha=alpha)
+
+    def scrub():
+        ws.fill_(0xFF)
+        out.fill_(float("nan"))
+        sel.fill_(-1)
+        alpha.fill_(float("nan"))
+
+    scrub()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    eager = (out.clone(), sel.clone(), alpha.clone())
+    check_against_oracle(case, *eager, r, k, l)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    other = W.make_case(W.Workload("sparf_graph_other", 1, 4, 4, 64, 700, seed=441), DEV)
+    for rep in range(3):
+        scrub()
+        H.gpu_step(other)                      # unrelated eager work between the replays
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int32), eager[0].view(torch.int32)), rep
+        assert torch.equal(sel, eager[1]) and torch.equal(alpha.view(torch.int32), eager[2].view(torch.int32)), rep
