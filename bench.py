@@ -25,7 +25,8 @@ HBM_PEAK_GBPS = 8000.0
 # HBM bytes per launch of the split-pass kernel from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE runs of this script, scaled by what the same counters read for the
 # 256 MiB copy kernel (FETCH_SIZE x 2.000, WRITE_SIZE x 1.000); see profiles/.
-MEASURED_TRAFFIC_BYTES = {"mha13b_4k": 1343968477, "gqa70b_16k": 2151829591}
+MEASURED_TRAFFIC_BYTES = {"mha13b_4k": 1343956394, "mha13b_32k": 5374752137, "ragged_paged": 11332726858,
+                          "gqa70b_16k": 2151816763}
 
 
 def parse():
