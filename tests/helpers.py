@@ -10,6 +10,10 @@ from paper_2409_04992_amd import binding as B
 
 TOL = {torch.float16: 2e-3, torch.float32: 1e-4}   # max-abs, attention output
 LSE_TOL = 2e-4                                     # absolute, natural-log lse (fp32 path)
+# Grouped queries with fp16 output: the MFMA kernel sums the fp16-rounded weights it feeds
+# to the matrix core (the row is then an exact softmax of slightly perturbed scores), so
+# the sum carries up to 2^-11 = 4.9e-4 relative error and the lse as much absolute error.
+LSE_TOL_F16_WEIGHTS = 6e-4
 ORACLE_THREADS = 16
 
 
@@ -82,7 +86,11 @@ def oracle_rows(case, pairs, appended=True):
     return res
 
 
-def assert_close(out, lse, want_out, want_lse, what=""):
+def lse_tol(group, out_dtype):
+    return LSE_TOL_F16_WEIGHTS if group > 1 and out_dtype == torch.float16 else LSE_TOL
+
+
+def assert_close(out, lse, want_out, want_lse, what="", lse_tol=LSE_TOL):
     got = out.detach().cpu().double().numpy()
     tol = TOL[out.dtype]
     mask = ~np.isnan(want_out)
@@ -97,5 +105,5 @@ def assert_close(out, lse, want_out, want_lse, what=""):
         fin = ml & ~inf
         if fin.any():
             lerr = np.abs(gl[fin] - want_lse[fin]) / (1.0 + np.abs(want_lse[fin]) * 0.01)
-            assert lerr.max() <= LSE_TOL, "%s: lse err %.3e" % (what, lerr.max())
+            assert lerr.max() <= lse_tol, "%s: lse err %.3e" % (what, lerr.max())
     return err
