@@ -42,8 +42,9 @@ Carve carve(int batch, int num_q_heads, int head_dim, int max_seq_len, int k)
     c.alpha = c.sel + up256(rows * (size_t)k * sizeof(int32_t));
     c.part = c.alpha + up256(rows * sizeof(float));
     c.hist = c.part + up256(rows * kSparfMaxSlices * (size_t)(head_dim + 2) * sizeof(float));
-    // the distributed selection's state exists only where long rows can take it
-    const size_t lr = max_seq_len > kSparfFusedMaxLen ? rows : 0;
+    // the distributed selection's state (small next to the scores; any row length may be
+    // sent that way through the environment switches)
+    const size_t lr = rows;
     c.gt1 = c.hist + up256(lr * c.nchunk * 256 * sizeof(uint32_t));
     c.counters = c.gt1 + up256(lr * c.nchunk * sizeof(uint32_t));
     c.state = c.counters + up256(lr * 2 * sizeof(uint32_t));

@@ -33,8 +33,11 @@ def gpu_step(case, out_dtype=None, append=True, want_lse=True, max_seq_len=None,
         max_seq_len = min(int(case.seq_lens.max().item()), case.capacity)
         max_seq_len = max(max_seq_len, 1)
     Bn, Hq, D = case.q.shape
-    ws = B.alloc_workspace(Bn, Hq, wl.num_kv_heads, D, max_seq_len, dev)
-    ws.fill_(0xFF)       # NaN patterns: stale workspace contents must not leak into the result
+    # the workspace as sized by the library plus a guard band that must stay untouched
+    size, guard = B.decode_workspace_size(Bn, Hq, wl.num_kv_heads, D, max_seq_len), 1 << 20
+    buf = torch.empty(size + guard, dtype=torch.uint8, device=dev)
+    buf.fill_(0xFF)      # NaN patterns: stale workspace contents must not leak into the result
+    ws = buf[:size]
     out = torch.full((Bn, Hq, D), float("nan"), dtype=out_dtype, device=dev)
     lse = torch.full((Bn, Hq), float("nan"), dtype=torch.float32, device=dev) if want_lse else None
     if append and fused:
@@ -46,6 +49,7 @@ def gpu_step(case, out_dtype=None, append=True, want_lse=True, max_seq_len=None,
         B.decode(case.q, desc, case.seq_lens, wl.num_kv_heads, case.scale, out, ws, max_seq_len,
                  lse=lse)
     torch.cuda.synchronize()
+    assert bool((buf[size:] == 0xFF).all()), "write behind the workspace"
     return out, lse
 
 

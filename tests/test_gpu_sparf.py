@@ -83,8 +83,11 @@ def run_decode(case, desc, aux, r, k, l, out_dtype, max_len=None, fused_append=F
     wl = case.wl
     Bn, Hq, D = case.q.shape
     max_len = max_len or max(1, int(case.seq_lens.max()))
-    ws = torch.empty(B.sparf_workspace_size(Bn, Hq, D, max_len, k), dtype=torch.uint8, device=DEV)
-    ws.fill_(0xFF)
+    # the workspace as sized by the library, a guard band behind it that must stay untouched
+    size, guard = B.sparf_workspace_size(Bn, Hq, D, max_len, k), 1 << 20
+    buf = torch.empty(size + guard, dtype=torch.uint8, device=DEV)
+    buf.fill_(0xFF)
+    ws = buf[:size]
     out = torch.full((Bn, Hq, D), float("nan"), dtype=out_dtype, device=DEV)
     sel = torch.full((Bn, Hq, k), -1, dtype=torch.int32, device=DEV)
     alpha = torch.full((Bn, Hq), float("nan"), dtype=torch.float32, device=DEV)
@@ -95,6 +98,7 @@ def run_decode(case, desc, aux, r, k, l, out_dtype, max_len=None, fused_append=F
         B.sparf_decode(case.q, desc, aux, case.seq_lens, wl.num_kv_heads, case.scale, r, k, l, out, ws,
                        max_len, sel_rows=sel, alpha=alpha)
     torch.cuda.synchronize()
+    assert bool((buf[size:] == 0xFF).all()), "write behind the workspace"
     return out, sel, alpha
 
 
@@ -323,6 +327,23 @@ def test_sparf_one_very_long_sequence(monkeypatch, distributed):
     monkeypatch.setenv("INSTATTN_SPARF_DISTRIBUTED", distributed)
     wl = W.Workload("sparf_1m", 1, 2, 2, 128, 1 << 20, seed=418)
     sparf_step(wl, 16, 1 << 16, 16, torch.float16)
+
+
+@pytest.mark.parametrize("shape", ["short_mha", "short_gqa_fused"])
+def test_sparf_short_rows_forced_through_the_distributed_selection(monkeypatch, shape):
+    """Rows the one-launch kernel would take, sent through the pipeline with the
+    selection spread over stretches (one stretch here): every switch combination must
+    stay inside the workspace the library asked for (checked behind every decode of
+    these tests by a guard band)."""
+    monkeypatch.setenv("INSTATTN_SPARF_THREE_LAUNCHES", "1")
+    monkeypatch.setenv("INSTATTN_SPARF_DISTRIBUTED", "1")
+    if shape == "short_mha":
+        wl = W.Workload("sparf_short_dist", 3, 4, 4, 128, 1500, seq_len_min=300, seed=442)
+        sparf_step(wl, 16, 100, 7, torch.float32)
+    else:
+        wl = W.Workload("sparf_short_dist_gqa", 2, 4, 2, 64, 5212, seq_len_min=596, paged=True, page_size=16,
+                        seed=443)
+        sparf_step(wl, 4, 4929, 24, torch.float16, kt_page=256, fused_append=True)
 
 
 def test_sparf_distributed_selection_equals_one_block_per_head(monkeypatch):
