@@ -554,6 +554,42 @@ def test_sparf_drawn_configurations(cfg):
     sparf_step(wl, r, k, l, torch.float16 if f16 else torch.float32, kt_page=kt_page, fused_append=fused)
 
 
+def _drawn_forms(n, seed):
+    """Seeded draw of shapes up to 40K positions together with a setting of every switch
+    that forces a form of the decode (None: the host's own choice)."""
+    rng = np.random.default_rng(seed)
+    names = ("INSTATTN_SPARF_WIDE", "INSTATTN_SPARF_DISTRIBUTED", "INSTATTN_SPARF_SPLIT_TAIL",
+             "INSTATTN_SPARF_THREE_LAUNCHES")
+    out = []
+    for i in range(n):
+        D = int(rng.choice([64, 128]))
+        G = int(rng.choice([1, 1, 2, 4]))
+        Hkv = int(rng.choice([1, 2, 3]))
+        top = int(rng.choice([3000, 8192, 13000, 18432, 30000, 40000]))
+        S = int(rng.integers(top // 2, top))
+        kt_page = [None, 8, 64, 256, 1024][int(rng.integers(0, 5))]
+        r = int(rng.choice([D // 16, D // 8, D // 4]))
+        k = int(rng.integers(1, 2 * S + 3)) if i % 3 == 0 else max(1, S // int(rng.choice([8, 16, 32])))
+        env = {}
+        for name in names:
+            v = int(rng.integers(0, 3))
+            if v < 2 and not (name == "INSTATTN_SPARF_THREE_LAUNCHES" and v == 0):
+                env[name] = str(v)
+        out.append((i, D, G, Hkv, S, bool(rng.integers(0, 2)), kt_page, r, k, int(rng.integers(0, 41)),
+                    bool(rng.integers(0, 2)), bool(rng.integers(0, 2)), env))
+    return out
+
+
+@pytest.mark.parametrize("cfg", _drawn_forms(30, 20240920), ids=lambda c: "cfg%d" % c[0])
+def test_sparf_drawn_configurations_in_forced_forms(monkeypatch, cfg):
+    i, D, G, Hkv, S, paged, kt_page, r, k, l, f16, fused, env = cfg
+    for name, value in env.items():
+        monkeypatch.setenv(name, value)
+    wl = W.Workload("sparf_form%d" % i, 2, G * Hkv, Hkv, D, S, seq_len_min=int(S * 0.4), paged=paged,
+                    page_size=16, seed=700 + i)
+    sparf_step(wl, r, k, l, torch.float16 if f16 else torch.float32, kt_page=kt_page, fused_append=fused)
+
+
 def test_sparf_is_deterministic():
     wl = W.Workload("sparf_det", 2, 4, 4, 128, 3000, seed=406)
     case, desc, aux, kt, vsum, _ = setup(wl)
