@@ -283,7 +283,10 @@ size_t instattn_sparf_workspace_size(int batch, int num_q_heads, int head_dim, i
  * attention over the kept rows, and a launch that combines the slices when a
  * head's kept rows are cut up.
  * A paged cache is limited to num_pages*page_size < 2^31 rows here, max_seq_len to
- * 2^30 (INSTATTN_ERR_UNSUPPORTED beyond).
+ * 2^30 (INSTATTN_ERR_UNSUPPORTED beyond).  max_seq_len must bound every L_b: a longer
+ * sequence is cut off at max_seq_len as everywhere (memory-safe), but aux.vsum still
+ * holds the sum of all its rows, so the mean of V that step 11 blends in is then not
+ * the mean of the rows attended.
  */
 int instattn_sparf_decode(const void* q, const instattn_kv_desc* kv, const instattn_sparf_aux* aux,
                           const int32_t* seq_lens, int batch, int num_q_heads, int num_kv_heads,
