@@ -952,9 +952,15 @@ static hipError_t launch_fused(const SparfArgs& a, hipStream_t stream)
     const size_t lds = (size_t)sparf_fused_lds_floats(a.max_len, NG, D) * sizeof(float);
     auto kernel = sparf_fused_kernel<D, NT, STEPS>;
     if (lds > 48 * 1024) {
-        // more dynamic LDS than a launch gets by default
-        const hipError_t e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
+        // more dynamic LDS than a launch gets by default: raise this kernel's limit to the
+        // largest it can ask for, once
+        static bool raised = false;
+        if (!raised) {
+            constexpr int most = kSparfFusedWidestMaxLen * (int)sizeof(float);
+            const hipError_t e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, most);
+            if (e != hipSuccess) return e;
+            raised = true;
+        }
     }
     hipLaunchKernelGGL(kernel, dim3(a.num_q_heads, a.batch), dim3(NT), lds, stream, a);
     return hipGetLastError();
