@@ -369,3 +369,46 @@ def test_sparf_plan_rejects():
         assert e.value.status == B.ERR_UNSUPPORTED
     assert B.sparf_workspace_size(1, 4, 128, (1 << 30) + 1, 10) == 0
     assert B.sparf_workspace_size(1, 4, 128, 1 << 30, 10) > (1 << 30) * 4 * 4
+
+
+# ------------------------------------------------------------------ the header as plain C
+def test_header_is_plain_c_and_links_against_the_library(tmp_path):
+    """include/instattn.h compiles as C99 with every warning on, and a C program that
+    uses it links against the library and runs its host-only entry points."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    src = tmp_path / "use_header.c"
+    src.write_text(r'''
+#include <stdio.h>
+#include "instattn.h"
+int main(void) {
+    int chunk = 0, splits = 0;
+    int32_t plan[6];
+    instattn_kv_desc kv = {0};
+    instattn_sparf_aux aux = {0};
+    (void)kv; (void)aux;
+    if (instattn_version() < 100) return 1;
+    if (instattn_decode_plan(16, 40, 40, 128, 4097, &chunk, &splits) != INSTATTN_OK) return 2;
+    if (instattn_sparf_plan(16, 40, 40, 128, 4097, 256, 1, plan) != INSTATTN_OK) return 3;
+    if (instattn_decode(NULL, NULL, NULL, 1, 1, 1, 128, 1.0f, NULL, INSTATTN_F16, NULL, NULL, 0, 1, NULL)
+        != INSTATTN_ERR_INVALID_ARG) return 4;
+    printf("%d %d %d %s\n", chunk, splits, plan[0], instattn_status_string(INSTATTN_ERR_WORKSPACE));
+    return 0;
+}
+''')
+    exe = tmp_path / "use_header"
+    lib_dir = os.path.dirname(B.LIB_PATH)
+    B.lib()                                    # raises if the library is not built
+    subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                    str(src), "-o", str(exe), "-L", lib_dir, "-l:libinstattn.so", "-Wl,-rpath," + lib_dir],
+                   check=True)
+    env = dict(os.environ)
+    for name in list(env):
+        if name.startswith("INSTATTN_"):
+            del env[name]
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True, env=env).stdout.split(None, 3)
+    assert (int(out[0]), int(out[1]), int(out[2])) == (2176, 2, 1)
+    assert out[3].strip() == "workspace missing, misaligned or too small"
