@@ -412,3 +412,28 @@ int main(void) {
     out = subprocess.run([str(exe)], check=True, capture_output=True, text=True, env=env).stdout.split(None, 3)
     assert (int(out[0]), int(out[1]), int(out[2])) == (2176, 2, 1)
     assert out[3].strip() == "workspace missing, misaligned or too small"
+
+
+# ------------------------------------------------------------------ bench.py's command line
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2", "--steps", "1"],
+                       capture_output=True, text=True)
+    assert r.returncode != 0 and "one GPU only" in r.stderr and r.stdout.strip() == ""
+
+
+def test_smoke_and_bench_fail_loudly_without_a_gpu():
+    """No CPU fallback anywhere on the product path: without a GPU the smoke run and the
+    bench raise instead of computing something else."""
+    import subprocess
+    import sys
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--steps", "1", "--warmup", "0",
+                        "--no-cpu-baseline"], capture_output=True, text=True)
+    assert r.returncode != 0 and r.stdout.strip() == ""
+    r = subprocess.run([sys.executable, "-c", "import __graft_entry__ as g; g.smoke()"], cwd=ROOT,
+                       capture_output=True, text=True)
+    assert r.returncode != 0
