@@ -40,6 +40,8 @@
 //                         every KV head has a single query head).
 #include <stdlib.h>
 
+#include <atomic>
+
 #include "sparf.h"
 #include "sparf_gather.h"
 #include "sparf_score.h"
@@ -954,12 +956,12 @@ static hipError_t launch_fused(const SparfArgs& a, hipStream_t stream)
     if (lds > 48 * 1024) {
         // more dynamic LDS than a launch gets by default: raise this kernel's limit to the
         // largest it can ask for, once
-        static bool raised = false;
-        if (!raised) {
+        static std::atomic<bool> raised{false};       // two host threads may both raise it: harmless
+        if (!raised.load(std::memory_order_acquire)) {
             constexpr int most = kSparfFusedWidestMaxLen * (int)sizeof(float);
             const hipError_t e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, most);
             if (e != hipSuccess) return e;
-            raised = true;
+            raised.store(true, std::memory_order_release);
         }
     }
     hipLaunchKernelGGL(kernel, dim3(a.num_q_heads, a.batch), dim3(NT), lds, stream, a);
