@@ -94,10 +94,17 @@ def cpu_baseline(cases, kv_bytes_layer, positions_layer):
         done += len(range(0, pairs, stride))
         layers += 1
     frac = done / pairs          # in units of one layer
+    # the same oracle on one core, on a sixteenth of the pairs of the first layer
+    stride1 = max(16, stride * 16)
+    t = time.perf_counter()
+    c_oracle.decode(*args0, pair_stride=stride1, nthreads=1)
+    dt1 = time.perf_counter() - t
+    single = kv_bytes_layer * len(range(0, pairs, stride1)) / pairs / dt1 / 1e9
     return {
         "value": kv_bytes_layer * frac / dt / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
         "sample": "%d (sequence, head) pairs = every %d-th pair of %d layer(s) of the same workload, "
                   "fp64 C oracle, %d OpenMP threads, %.1f s wall" % (done, stride, layers, cores, dt),
+        "single_core_value": single,
         "attended_tokens_per_s": positions_layer * frac / dt,
     }
 
