@@ -749,27 +749,35 @@ __global__ __launch_bounds__(NT) void sparf_select_attend_kernel(SparfArgs a)
 }
 
 // ---------------------------------------------------------------------------
-// Component-major copy of K for rows [0, L_b): one block per stretch of 512 rows of
-// one (sequence, KV head).  A thread loads an 8 x 8 block (8 rows, 16 bytes each),
+// Component-major copy of K for rows [0, L_b): one block per stretch of 512 rows and
+// group of 32 components of one (sequence, KV head).  A thread loads an 8 x 8 block (8 rows, 16 bytes each),
 // transposes it in registers, and the 16-byte pieces (8 positions of one component)
 // change hands through LDS so that adjacent lanes store adjacent pieces of a column:
 // every LDS access is 128 bits wide.  Slots are swizzled by the column group, so the
 // lanes of a store hit different banks.
 constexpr int kBuildRows = 512;
 
+#ifndef INSTATTN_SPARF_BUILD_COLS
+#define INSTATTN_SPARF_BUILD_COLS 32             // components per block of the copy (128: -11 %, 64: -3 %)
+#endif
 template <int D>
 __global__ __launch_bounds__(256) void sparf_build_kernel(SparfArgs a)
 {
-    constexpr int COLS8 = D / 8;                 // 16-byte pieces per row
+    // A block copies DP of the D components of a stretch: fewer components per block mean
+    // more rows per tile, so longer contiguous runs of every column it writes.
+    constexpr int DP = D < INSTATTN_SPARF_BUILD_COLS ? D : INSTATTN_SPARF_BUILD_COLS;
+    constexpr int CS = D / DP;                   // blocks that share a row
+    constexpr int COLS8 = DP / 8;                // 16-byte pieces of a row this block reads
     constexpr int RUNS = 256 / COLS8;            // runs of 8 rows per tile: one 8 x 8 block per thread
-    constexpr int TILE = 8 * RUNS;               // 128 rows (D = 128) or 256 (D = 64)
-    const int hk = blockIdx.x, b = blockIdx.z;
+    constexpr int TILE = 8 * RUNS;               // rows per tile
+    static_assert(kBuildRows % TILE == 0, "a stretch is a whole number of tiles");
+    const int hk = blockIdx.x / CS, d0 = (blockIdx.x % CS) * DP, b = blockIdx.z;
     const int tid = threadIdx.x;
     const int L = clamp_len(a.seq_lens[b], min(a.kv.capacity, a.aux.capacity));
     const int t_begin = blockIdx.y * kBuildRows, t_end = min(t_begin + kBuildRows, L);
     if (t_begin >= L) return;
 
-    __shared__ u32x4 s_piece[D][RUNS];           // [component][run of 8 positions, swizzled]
+    __shared__ u32x4 s_piece[DP][RUNS];          // [component][run of 8 positions, swizzled]
     const int c8 = tid % COLS8, run = tid / COLS8;
     for (int t0 = t_begin; t0 < t_end; t0 += TILE) {
         // rows t0 + 8 run .. + 7 (rows at or behind L are not read; their slots become 0)
@@ -778,7 +786,7 @@ __global__ __launch_bounds__(256) void sparf_build_kernel(SparfArgs a)
         for (int j = 0; j < 8; ++j) {
             const int t = t0 + run * 8 + j;
             const half8_t z = {0, 0, 0, 0, 0, 0, 0, 0};
-            rows[j] = t < L ? *(const half8_t*)(a.kv.k + row_offset(a.kv, b, hk, t) + c8 * 8) : z;
+            rows[j] = t < L ? *(const half8_t*)(a.kv.k + row_offset(a.kv, b, hk, t) + d0 + c8 * 8) : z;
         }
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
@@ -787,11 +795,12 @@ __global__ __launch_bounds__(256) void sparf_build_kernel(SparfArgs a)
             s_piece[c8 * 8 + e][run ^ (c8 % RUNS)] = __builtin_bit_cast(u32x4, col);
         }
         __syncthreads();
-        for (int i = tid; i < D * RUNS; i += 256) {
+        for (int i = tid; i < DP * RUNS; i += 256) {
             const int d = i / RUNS, r8 = i % RUNS;
             const int t = t0 + r8 * 8;
             if (t < L)
-                *(u32x4*)(kt_col0(a.aux, b, hk, t) + (int64_t)d * a.aux.stride_d) = s_piece[d][r8 ^ ((d / 8) % RUNS)];
+                *(u32x4*)(kt_col0(a.aux, b, hk, t) + (int64_t)(d0 + d) * a.aux.stride_d) =
+                    s_piece[d][r8 ^ ((d / 8) % RUNS)];
         }
         __syncthreads();
     }
@@ -862,7 +871,8 @@ __global__ __launch_bounds__(256) void sparf_append_kernel(SparfArgs a)
 hipError_t launch_sparf_build(const SparfArgs& a, hipStream_t stream)
 {
     const int rows = a.kv.capacity < a.aux.capacity ? a.kv.capacity : a.aux.capacity;
-    dim3 grid(a.num_kv_heads, (rows + kBuildRows - 1) / kBuildRows, a.batch);
+    const int cols = a.head_dim < INSTATTN_SPARF_BUILD_COLS ? a.head_dim : INSTATTN_SPARF_BUILD_COLS;
+    dim3 grid(a.num_kv_heads * (a.head_dim / cols), (rows + kBuildRows - 1) / kBuildRows, a.batch);
     if (a.head_dim == 128) hipLaunchKernelGGL(sparf_build_kernel<128>, grid, dim3(256), 0, stream, a);
     else hipLaunchKernelGGL(sparf_build_kernel<64>, grid, dim3(256), 0, stream, a);
     if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
