@@ -760,12 +760,12 @@ constexpr int kBuildRows = 512;
 #ifndef INSTATTN_SPARF_BUILD_COLS
 #define INSTATTN_SPARF_BUILD_COLS 32             // components per block of the copy (128: -11 %, 64: -3 %)
 #endif
-template <int D>
+// A block copies DP of the D components of a stretch: fewer components per block mean
+// more rows per tile, so longer contiguous runs of every column it writes (DP = 32: 1 KB).
+// A copy in short pages cannot take runs that long; there whole rows (DP = D) read better.
+template <int D, int DP>
 __global__ __launch_bounds__(256) void sparf_build_kernel(SparfArgs a)
 {
-    // A block copies DP of the D components of a stretch: fewer components per block mean
-    // more rows per tile, so longer contiguous runs of every column it writes.
-    constexpr int DP = D < INSTATTN_SPARF_BUILD_COLS ? D : INSTATTN_SPARF_BUILD_COLS;
     constexpr int CS = D / DP;                   // blocks that share a row
     constexpr int COLS8 = DP / 8;                // 16-byte pieces of a row this block reads
     constexpr int RUNS = 256 / COLS8;            // runs of 8 rows per tile: one 8 x 8 block per thread
@@ -871,10 +871,18 @@ __global__ __launch_bounds__(256) void sparf_append_kernel(SparfArgs a)
 hipError_t launch_sparf_build(const SparfArgs& a, hipStream_t stream)
 {
     const int rows = a.kv.capacity < a.aux.capacity ? a.kv.capacity : a.aux.capacity;
-    const int cols = a.head_dim < INSTATTN_SPARF_BUILD_COLS ? a.head_dim : INSTATTN_SPARF_BUILD_COLS;
+    // components per block: few where the copy can be written in long runs
+    const bool long_runs = a.aux.page_table == nullptr || (a.aux.page_mask + 1) >= kBuildRows;
+    const int cols = long_runs && a.head_dim > INSTATTN_SPARF_BUILD_COLS ? INSTATTN_SPARF_BUILD_COLS : a.head_dim;
     dim3 grid(a.num_kv_heads * (a.head_dim / cols), (rows + kBuildRows - 1) / kBuildRows, a.batch);
-    if (a.head_dim == 128) hipLaunchKernelGGL(sparf_build_kernel<128>, grid, dim3(256), 0, stream, a);
-    else hipLaunchKernelGGL(sparf_build_kernel<64>, grid, dim3(256), 0, stream, a);
+    constexpr int kFew = INSTATTN_SPARF_BUILD_COLS;
+    if (a.head_dim == 128) {
+        if (cols == kFew) hipLaunchKernelGGL((sparf_build_kernel<128, kFew>), grid, dim3(256), 0, stream, a);
+        else hipLaunchKernelGGL((sparf_build_kernel<128, 128>), grid, dim3(256), 0, stream, a);
+    } else {
+        if (cols == kFew) hipLaunchKernelGGL((sparf_build_kernel<64, kFew>), grid, dim3(256), 0, stream, a);
+        else hipLaunchKernelGGL((sparf_build_kernel<64, 64>), grid, dim3(256), 0, stream, a);
+    }
     if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
     hipLaunchKernelGGL(sparf_vsum_kernel, dim3(a.num_kv_heads, a.batch), dim3(kVsumThreads), 0, stream, a);
     return hipGetLastError();
