@@ -227,13 +227,27 @@ typedef struct {
 } instattn_sparf_aux;
 
 /*
+ * Bytes of device scratch with which instattn_sparf_build spreads the sum of V of
+ * one (sequence, KV head) over several blocks: worth it when there are few such
+ * pairs with long rows (0: there are pairs enough, or the arguments are invalid).
+ */
+size_t instattn_sparf_build_workspace_size(int batch, int num_kv_heads, int head_dim);
+
+/*
  * Fill aux (kt and vsum) from the rows 0 .. seq_lens[b]-1 of an existing cache:
  * what the storage side does when the prefill phase hands over a layer's K and V
- * (Sec. IV-D).  Rows at or behind the length are not read.  Two launches.
+ * (Sec. IV-D).  Rows at or behind the length are not read.
+ *   workspace : device scratch of at least instattn_sparf_build_workspace_size
+ *               bytes, 256-byte aligned, or NULL (then one block sums the V rows of
+ *               a pair: same result to fp32 rounding, slow for few pairs with long
+ *               rows); a non-NULL workspace that is too small is
+ *               INSTATTN_ERR_WORKSPACE.  Contents on entry are ignored.
+ * Two launches, three with the workspace in use.  The sums are taken in a fixed
+ * order: the same inputs give the same bits.
  */
 int instattn_sparf_build(const instattn_kv_desc* kv, const instattn_sparf_aux* aux,
                          const int32_t* seq_lens, int batch, int num_kv_heads, int head_dim,
-                         void* stream);
+                         void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * instattn_kv_append that also keeps aux current: stores k_new as entry

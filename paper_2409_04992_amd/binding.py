@@ -86,7 +86,9 @@ def lib() -> ctypes.CDLL:
         L.instattn_decode_merge.argtypes = [vp, i, i, i, i, i, vp, i, vp, vp, sz, i, vp]
         pk, pa = ctypes.POINTER(KvDesc), ctypes.POINTER(SparfAux)
         L.instattn_sparf_build.restype = i
-        L.instattn_sparf_build.argtypes = [pk, pa, vp, i, i, i, vp]
+        L.instattn_sparf_build.argtypes = [pk, pa, vp, i, i, i, vp, sz, vp]
+        L.instattn_sparf_build_workspace_size.restype = sz
+        L.instattn_sparf_build_workspace_size.argtypes = [i, i, i]
         L.instattn_sparf_append.restype = i
         L.instattn_sparf_append.argtypes = [pk, pa, vp, vp, vp, i, i, i, vp]
         L.instattn_sparf_plan.restype = i
@@ -269,10 +271,21 @@ def sparf_aux(kt: torch.Tensor, vsum: torch.Tensor, page_table: Optional[torch.T
     return a
 
 
+def sparf_build_workspace_size(batch: int, num_kv_heads: int, head_dim: int) -> int:
+    return lib().instattn_sparf_build_workspace_size(batch, num_kv_heads, head_dim)
+
+
 def sparf_build(desc: KvDesc, aux: SparfAux, seq_lens, num_kv_heads: int, head_dim: int,
-                stream=None) -> None:
+                stream=None, workspace="auto") -> None:
+    """workspace: a uint8 device tensor, None (one block sums the V rows of a pair), or
+    "auto": a scratch tensor of the size the library asks for, allocated here."""
+    if isinstance(workspace, str):
+        n = sparf_build_workspace_size(seq_lens.numel(), num_kv_heads, head_dim)
+        workspace = torch.empty(n, dtype=torch.uint8, device=seq_lens.device) if n else None
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().instattn_sparf_build(ctypes.byref(desc), ctypes.byref(aux), _p(seq_lens),
-                                      seq_lens.numel(), num_kv_heads, head_dim, _stream(stream)),
+                                      seq_lens.numel(), num_kv_heads, head_dim, _p(workspace), nbytes,
+                                      _stream(stream)),
            "instattn_sparf_build")
 
 

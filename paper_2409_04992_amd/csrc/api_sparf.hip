@@ -55,6 +55,17 @@ Carve carve(int batch, int num_q_heads, int head_dim, int max_seq_len, int k)
     return c;
 }
 
+// Blocks over which the set-up spreads the V sum of one (sequence, KV head): about a
+// thousand blocks in all, at most 64 per pair (one block per pair reads at 60-250 GB/s:
+// 8 pairs of a million rows took 4.6 ms).
+int vsum_parts_for(int batch, int num_kv_heads)
+{
+    const int64_t pairs = (int64_t)batch * num_kv_heads;
+    if (pairs >= 512) return 1;
+    const int64_t parts = (1024 + pairs - 1) / pairs;
+    return (int)(parts > 64 ? 64 : parts);
+}
+
 // Which kernels a decode of these sizes launches: host arithmetic only.
 struct SparfPlan {
     bool one_launch;      // sparf_fused_kernel does everything
@@ -173,9 +184,17 @@ int status_of(hipError_t e) { return e == hipSuccess ? INSTATTN_OK : INSTATTN_ER
 
 extern "C" {
 
+size_t instattn_sparf_build_workspace_size(int batch, int num_kv_heads, int head_dim)
+{
+    if (batch <= 0 || num_kv_heads <= 0 || (head_dim != 64 && head_dim != 128)) return 0;
+    const int parts = vsum_parts_for(batch, num_kv_heads);
+    if (parts == 1) return 0;
+    return up256((size_t)batch * num_kv_heads * parts * head_dim * sizeof(float));
+}
+
 int instattn_sparf_build(const instattn_kv_desc* kv, const instattn_sparf_aux* aux,
                          const int32_t* seq_lens, int batch, int num_kv_heads, int head_dim,
-                         void* stream)
+                         void* workspace, size_t workspace_bytes, void* stream)
 {
     int st = check_common(kv, aux, batch, num_kv_heads, head_dim);
     if (st != INSTATTN_OK) return st;
@@ -186,6 +205,14 @@ int instattn_sparf_build(const instattn_kv_desc* kv, const instattn_sparf_aux* a
     a.batch = batch;
     a.num_kv_heads = num_kv_heads;
     a.head_dim = head_dim;
+    const size_t need = instattn_sparf_build_workspace_size(batch, num_kv_heads, head_dim);
+    if (workspace != nullptr && need > 0) {
+        if (((uintptr_t)workspace & 255) || workspace_bytes < need) return INSTATTN_ERR_WORKSPACE;
+        const int rows = kv->capacity < aux->capacity ? kv->capacity : aux->capacity;
+        a.vsum_part = (float*)workspace;
+        a.vsum_parts = vsum_parts_for(batch, num_kv_heads);
+        a.vsum_rows = ((rows + a.vsum_parts - 1) / a.vsum_parts + 63) / 64 * 64;
+    }
     return status_of(launch_sparf_build(a, (hipStream_t)stream));
 }
 

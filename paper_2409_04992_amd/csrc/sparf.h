@@ -62,6 +62,9 @@ struct SparfArgs {
     int32_t member_cap;                // room in that list: kSparfMemberCap, more for very long rows
     float* mass_part;                  // [B][Hq][nchunk] softmax mass kept per stretch
     float* rowstat;                    // [B][Hq][4]: a row's max, min and sum of 2^(x - max), folded by sparf_hist_kernel
+    // set-up: the V sum of a (sequence, KV head) spread over vsum_parts blocks of vsum_rows rows each
+    float* vsum_part;                  // [B][Hkv][vsum_parts][D] or nullptr (one block per pair)
+    int32_t vsum_parts, vsum_rows;
     void* out;
     int32_t out_f32;
     const half_t* k_new;               // append, or decode with the append fused in

@@ -815,17 +815,20 @@ constexpr int kVsumThreads = 512;
 __global__ __launch_bounds__(kVsumThreads) void sparf_vsum_kernel(SparfArgs a)
 {
     constexpr int NT = kVsumThreads, U = 8;
-    const int hk = blockIdx.x, b = blockIdx.y;
+    const int hk = blockIdx.x, b = blockIdx.y, part_of_pair = blockIdx.z;
     const int D = a.head_dim;
     const int tid = threadIdx.x;
-    const int L = clamp_len(a.seq_lens[b], min(a.kv.capacity, a.aux.capacity));
+    // this block's rows: all of the pair's, or its share when the sum is spread over blocks
+    const int L_all = clamp_len(a.seq_lens[b], min(a.kv.capacity, a.aux.capacity));
+    const int t_first = part_of_pair * a.vsum_rows;          // a multiple of 8
+    const int L = a.vsum_part ? min(L_all, t_first + a.vsum_rows) : L_all;
     const int cols8 = D / 8;                 // 8 or 16
     const int c8 = tid % cols8, part = tid / cols8, parts = NT / cols8;
     __shared__ float s_sum[NT * 8];          // [row group][column]: 32 x 128 or 64 x 64
     float vs[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) vs[e] = 0.f;
-    for (int t = part * U; t < L; t += parts * U) {
+    for (int t = t_first + part * U; t < L; t += parts * U) {
         // rows t .. t + 7 lie in one page (pages hold a multiple of 8 rows, t is a multiple of 8)
         const half_t* p = a.kv.v + row_offset(a.kv, b, hk, t) + c8 * 8;
         if (t + U <= L) {
@@ -850,8 +853,22 @@ __global__ __launch_bounds__(kVsumThreads) void sparf_vsum_kernel(SparfArgs a)
     if (tid < D) {
         float s = 0.f;
         for (int p = 0; p < parts; ++p) s += s_sum[p * D + tid];
-        a.aux.vsum[((int64_t)b * a.num_kv_heads + hk) * D + tid] = s;
+        const int64_t pair = (int64_t)b * a.num_kv_heads + hk;
+        if (a.vsum_part) a.vsum_part[(pair * a.vsum_parts + part_of_pair) * D + tid] = s;
+        else a.aux.vsum[pair * D + tid] = s;
     }
+}
+
+// The blocks' shares of a pair's V sum, added in block order.
+__global__ __launch_bounds__(128) void sparf_vsum_fold_kernel(SparfArgs a)
+{
+    const int hk = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+    if (tid >= a.head_dim) return;
+    const int64_t pair = (int64_t)b * a.num_kv_heads + hk;
+    const float* p = a.vsum_part + pair * a.vsum_parts * a.head_dim + tid;
+    float s = 0.f;
+    for (int i = 0; i < a.vsum_parts; ++i) s += p[(int64_t)i * a.head_dim];
+    a.aux.vsum[pair * a.head_dim + tid] = s;
 }
 
 // kv_append plus the new entry of every K column and the update of the V sum.
@@ -884,7 +901,9 @@ hipError_t launch_sparf_build(const SparfArgs& a, hipStream_t stream)
         else hipLaunchKernelGGL((sparf_build_kernel<64, 64>), grid, dim3(256), 0, stream, a);
     }
     if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
-    hipLaunchKernelGGL(sparf_vsum_kernel, dim3(a.num_kv_heads, a.batch), dim3(kVsumThreads), 0, stream, a);
+    const int parts = a.vsum_part ? a.vsum_parts : 1;
+    hipLaunchKernelGGL(sparf_vsum_kernel, dim3(a.num_kv_heads, a.batch, parts), dim3(kVsumThreads), 0, stream, a);
+    if (a.vsum_part) hipLaunchKernelGGL(sparf_vsum_fold_kernel, dim3(a.num_kv_heads, a.batch), dim3(128), 0, stream, a);
     return hipGetLastError();
 }
 

@@ -25,6 +25,7 @@ def test_library_exports_every_declared_symbol():
             "instattn_decode_merge", "instattn_decode_plan", "instattn_decode_workspace_size",
             "instattn_status_string", "instattn_version", "instattn_probe_read",
             "instattn_append_decode", "instattn_kv_write", "instattn_sparf_build", "instattn_sparf_append",
+            "instattn_sparf_build_workspace_size",
             "instattn_sparf_decode", "instattn_sparf_workspace_size", "instattn_sparf_append_decode",
             "instattn_sparf_plan",
             "instattn_probe_copy"} <= set(names)
@@ -247,9 +248,19 @@ def test_sparf_append_decode_rejects():
 def test_sparf_build_and_append_reject():
     L = B.lib()
     d, a = desc(), aux_desc()
-    assert L.instattn_sparf_build(ctypes.byref(d), ctypes.byref(a), None, 16, 40, 128, None) == B.ERR_INVALID_ARG
-    assert L.instattn_sparf_build(None, ctypes.byref(a), FAKE, 16, 40, 128, None) == B.ERR_INVALID_ARG
-    assert L.instattn_sparf_build(ctypes.byref(d), None, FAKE, 16, 40, 128, None) == B.ERR_INVALID_ARG
+    assert L.instattn_sparf_build(ctypes.byref(d), ctypes.byref(a), None, 16, 40, 128, None, 0, None) == B.ERR_INVALID_ARG
+    assert L.instattn_sparf_build(None, ctypes.byref(a), FAKE, 16, 40, 128, None, 0, None) == B.ERR_INVALID_ARG
+    assert L.instattn_sparf_build(ctypes.byref(d), None, FAKE, 16, 40, 128, None, 0, None) == B.ERR_INVALID_ARG
+    # scratch for the V sum: none wanted with 640 pairs; with 8 pairs 64 blocks each, and a
+    # scratch that is given must be large enough and aligned
+    assert B.sparf_build_workspace_size(16, 40, 128) == 0
+    assert B.sparf_build_workspace_size(1, 8, 128) == 8 * 64 * 128 * 4
+    assert B.sparf_build_workspace_size(1, 40, 64) == 40 * 26 * 64 * 4
+    assert B.sparf_build_workspace_size(0, 8, 128) == 0 and B.sparf_build_workspace_size(1, 8, 96) == 0
+    small = ctypes.c_void_p(0x100000)
+    assert L.instattn_sparf_build(ctypes.byref(d), ctypes.byref(a), FAKE, 1, 8, 128, small, 1000, None) == B.ERR_WORKSPACE
+    assert L.instattn_sparf_build(ctypes.byref(d), ctypes.byref(a), FAKE, 1, 8, 128, ctypes.c_void_p(0x100010),
+                                  1 << 20, None) == B.ERR_WORKSPACE
     assert L.instattn_sparf_append(ctypes.byref(d), ctypes.byref(a), None, FAKE, FAKE, 16, 40, 128,
                                    None) == B.ERR_INVALID_ARG
     assert L.instattn_sparf_append(ctypes.byref(d), ctypes.byref(a), FAKE, FAKE, FAKE, 0, 40, 128,

@@ -346,6 +346,44 @@ def test_sparf_short_rows_forced_through_the_distributed_selection(monkeypatch, 
         sparf_step(wl, 4, 4929, 24, torch.float16, kt_page=256, fused_append=True)
 
 
+@pytest.mark.parametrize("shape", ["mha_paged", "one_pair_long", "d64_ragged"])
+def test_sparf_build_with_and_without_scratch(shape):
+    """instattn_sparf_build with the scratch it asks for (the V sum of a pair spread over
+    blocks and folded in block order) and without (one block per pair): the same column
+    copy bit for bit, the same sums to fp32 rounding, each form deterministic; a guard
+    band behind the scratch stays untouched."""
+    wl = {"mha_paged": W.Workload("sparf_bws1", 2, 3, 3, 128, 20000, seq_len_min=300, paged=True, page_size=16,
+                                  seed=444),
+          "one_pair_long": W.Workload("sparf_bws2", 1, 1, 1, 128, 300_000, seed=445),
+          "d64_ragged": W.Workload("sparf_bws3", 5, 2, 2, 64, 9000, seq_len_min=0, seed=446)}[shape]
+    case, desc, aux, kt, vsum, lens = setup(wl, kt_page=256 if wl.paged else None)
+    Hkv, D = wl.num_kv_heads, wl.head_dim
+    size = B.sparf_build_workspace_size(wl.batch, Hkv, D)
+    assert size > 0
+    runs = []
+    for use_scratch in (True, False, True, False):
+        kt.fill_(float("nan"))
+        vsum.fill_(float("nan"))
+        buf = torch.empty(size + 4096, dtype=torch.uint8, device=DEV)
+        buf.fill_(0xFF)
+        B.sparf_build(desc, aux, lens, Hkv, D, workspace=buf[:size] if use_scratch else None)
+        torch.cuda.synchronize()
+        assert bool((buf[size:] == 0xFF).all())
+        runs.append((kt.clone(), vsum.clone()))
+    for kt_i, _ in runs[1:]:
+        assert torch.equal(kt_i.view(torch.int16), runs[0][0].view(torch.int16))
+    assert torch.equal(runs[0][1].view(torch.int32), runs[2][1].view(torch.int32))      # deterministic
+    assert torch.equal(runs[1][1].view(torch.int32), runs[3][1].view(torch.int32))
+    # against the fp64 sum of the rows
+    K, V = logical(case)
+    for b in range(wl.batch):
+        n = int(lens[b])
+        want = V[b, :, :n].astype(np.float64).sum(axis=1) if n > 0 else np.zeros((Hkv, D))
+        for _, vs in runs[:2]:
+            got = vs[b].double().cpu().numpy()
+            assert np.abs(got - want).max() <= 1e-5 * max(1.0, np.abs(V[b, :, :max(n, 1)]).astype(np.float64).sum(axis=1).max())
+
+
 def test_sparf_distributed_selection_equals_one_block_per_head(monkeypatch):
     """Same kept rows bit for bit, alpha and out up to the order of the mass sum; ragged
     lengths so that heads use different numbers of stretches; repeated (the gathered
