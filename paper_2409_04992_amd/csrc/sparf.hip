@@ -807,9 +807,11 @@ __global__ __launch_bounds__(256) void sparf_build_kernel(SparfArgs a)
 }
 
 // Column sums of V over rows [0, L_b): one block of 512 threads per (sequence, KV
-// head); D / 8 adjacent threads read a row, each of the 512 / (D / 8) row groups takes
-// runs of 8 consecutive rows (one page lookup per run, eight loads in flight); the
-// groups' sums are added in a fixed order.
+// head), or, with scratch from the caller, several blocks per pair that take
+// vsum_rows rows each and leave their shares for sparf_vsum_fold_kernel; D / 8
+// adjacent threads read a row, each of the 512 / (D / 8) row groups takes runs of 8
+// consecutive rows (one page lookup per run, eight loads in flight); the groups'
+// sums are added in a fixed order.
 constexpr int kVsumThreads = 512;
 
 __global__ __launch_bounds__(kVsumThreads) void sparf_vsum_kernel(SparfArgs a)
