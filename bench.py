@@ -27,6 +27,10 @@ HBM_PEAK_GBPS = 8000.0
 # 256 MiB copy kernel (FETCH_SIZE x 2.000, WRITE_SIZE x 1.000); see profiles/.
 MEASURED_TRAFFIC_BYTES = {"mha13b_4k": 1343956394, "mha13b_32k": 5374752137, "ragged_paged": 11332726858,
                           "gqa70b_16k": 2151816763}
+# The same for all launches of a SparF step (fetched + written), keyed by workload and r,k,l.
+SPARF_MEASURED_TRAFFIC_BYTES = {("mha13b_4k", "16,256,16"): 172842965 + 4116608,
+                                ("mha13b_32k", "16,2048,16"): 820439829 + 48992165,
+                                ("ragged_paged", "16,1024,16"): 2077318752 + 24337616}
 
 
 def parse():
@@ -194,7 +198,8 @@ def bench_sparf(args):
         "achieved_GBps_algorithm1_bytes": sparf_bytes / t_sparf / 1e9,
         # the whole step (one or several launches) against the bytes Algorithm 1 must read
         "roofline": {"bound": "hbm", "achieved": sparf_bytes / t_sparf / 1e9, "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": sparf_bytes / t_sparf / 1e9 / HBM_PEAK_GBPS, "traffic": None,
+                     "unit": "GB/s", "frac": sparf_bytes / t_sparf / 1e9 / HBM_PEAK_GBPS,
+                     "traffic": SPARF_MEASURED_TRAFFIC_BYTES.get((wl.name, args.sparf)) if kt_page == (256 if wl.paged else 0) else None,
                      "kernel": "whole SparF step", "algorithmic_bytes_per_launch": sparf_bytes},
     }
     if not args.no_cpu_baseline:
