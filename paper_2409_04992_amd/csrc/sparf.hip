@@ -994,13 +994,19 @@ static hipError_t launch_fused(const SparfArgs& a, hipStream_t stream)
     auto kernel = sparf_fused_kernel<D, NT, STEPS>;
     if (lds > 48 * 1024) {
         // more dynamic LDS than a launch gets by default: raise this kernel's limit to the
-        // largest it can ask for, once
-        static std::atomic<bool> raised{false};       // two host threads may both raise it: harmless
-        if (!raised.load(std::memory_order_acquire)) {
+        // largest it can ask for, once per device (the attribute belongs to the device's copy
+        // of the kernel)
+        constexpr int kDevices = 64;
+        static std::atomic<bool> raised[kDevices];    // zero-initialised; two host threads may both raise it: harmless
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        const bool tracked = dev >= 0 && dev < kDevices;
+        if (!tracked || !raised[dev].load(std::memory_order_acquire)) {
             constexpr int most = kSparfFusedWidestMaxLen * (int)sizeof(float);
-            const hipError_t e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, most);
+            e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, most);
             if (e != hipSuccess) return e;
-            raised.store(true, std::memory_order_release);
+            if (tracked) raised[dev].store(true, std::memory_order_release);
         }
     }
     hipLaunchKernelGGL(kernel, dim3(a.num_q_heads, a.batch), dim3(NT), lds, stream, a);

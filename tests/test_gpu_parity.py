@@ -103,6 +103,42 @@ def test_config5_gqa_layer_full_shape_sampled(fused):
     assert torch.equal(case.v_cache[:, :, L - 1].view(torch.int16), case.v_new.view(torch.int16))
 
 
+def test_config5_all_80_layers_resident():
+    """The 80-layer step as the bench runs it: every layer's cache resident (172 GB), one
+    shared length array and workspace, the fused call per layer on one stream.  Every
+    layer is checked: its appended rows bit for bit, and the output rows of two
+    (sequence, head) pairs, a different couple per layer, against the oracle."""
+    wl = W.WORKLOADS["gqa70b_16k"]
+    assert wl.layers == 80
+    torch.cuda.empty_cache()
+    cases = [W.make_case(wl, DEV, layer=i, poison=True) for i in range(wl.layers)]
+    lens = cases[0].seq_lens
+    max_len = int(lens.max().item())
+    ws = B.alloc_workspace(wl.batch, wl.num_q_heads, wl.num_kv_heads, wl.head_dim, max_len, DEV)
+    outs = torch.full((wl.layers, wl.batch, wl.num_q_heads, wl.head_dim), float("nan"),
+                      dtype=torch.float16, device=DEV)
+    lses = torch.full((wl.layers, wl.batch, wl.num_q_heads), float("nan"), dtype=torch.float32, device=DEV)
+    for i, c in enumerate(cases):
+        assert torch.equal(c.seq_lens, lens)
+        B.append_decode(c.q, c.k_new, c.v_new, B.kv_desc(c.k_cache, c.v_cache, None), lens,
+                        wl.num_kv_heads, c.scale, outs[i], ws, max_len, lse=lses[i])
+    torch.cuda.synchronize()
+    assert torch.isfinite(outs.float()).all() and torch.isfinite(lses).all()
+    tol, ltol = H.TOL[torch.float16], H.lse_tol(wl.group, torch.float16)
+    for i, c in enumerate(cases):
+        L = int(lens[0])
+        assert torch.equal(c.k_cache[:, :, L - 1].view(torch.int16), c.k_new.view(torch.int16)), i
+        assert torch.equal(c.v_cache[:, :, L - 1].view(torch.int16), c.v_new.view(torch.int16)), i
+        pairs = [((7 * i + 3) % wl.batch, (13 * i + 5) % wl.num_q_heads),
+                 ((11 * i) % wl.batch, (29 * i + 63) % wl.num_q_heads)]
+        for (b, h), (want, want_lse) in H.oracle_rows(c, pairs).items():
+            err = np.abs(outs[i, b, h].double().cpu().numpy() - want).max()
+            assert err <= tol, "layer %d (b=%d,h=%d): %.3e" % (i, b, h, err)
+            assert abs(float(lses[i, b, h]) - want_lse) <= ltol * (1 + 0.01 * abs(want_lse)), (i, b, h)
+    del cases, outs, lses, ws
+    torch.cuda.empty_cache()
+
+
 @pytest.mark.parametrize("shape", ["mha_1m", "gqa_512k_paged", "mha64_600k"])
 def test_one_very_long_sequence(shape):
     """A single sequence far beyond the measured configurations: hundreds of units per
