@@ -154,6 +154,7 @@ def kv_desc(k_cache: torch.Tensor, v_cache: torch.Tensor,
         d.num_pages = k_cache.shape[0]
         d.capacity = d.page_size * d.max_pages_per_seq
         d.page_table = page_table.data_ptr()
+    d.tensors = (k_cache, v_cache, page_table)   # the struct holds bare addresses: keep their owners alive with it
     return d
 
 
@@ -268,6 +269,7 @@ def sparf_aux(kt: torch.Tensor, vsum: torch.Tensor, page_table: Optional[torch.T
         a.max_pages_per_seq = page_table.shape[1]
         a.capacity = a.page_size * a.max_pages_per_seq
         a.page_table = page_table.data_ptr()
+    a.tensors = (kt, vsum, page_table)           # keeps the owners of the addresses alive with the struct
     return a
 
 

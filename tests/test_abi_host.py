@@ -448,3 +448,28 @@ def test_smoke_and_bench_fail_loudly_without_a_gpu():
     r = subprocess.run([sys.executable, "-c", "import __graft_entry__ as g; g.smoke()"], cwd=ROOT,
                        capture_output=True, text=True)
     assert r.returncode != 0
+
+
+def test_descriptors_keep_their_tensors_alive():
+    """The C structs hold bare addresses; the binding's objects must own what they point
+    at, or a caller that drops its tensors hands the kernels freed memory."""
+    import gc
+    import weakref
+
+    import torch
+    k = torch.zeros(2, 1, 16, 64, dtype=torch.float16)
+    v = torch.zeros_like(k)
+    table = torch.zeros(1, 2, dtype=torch.int32)
+    kt = torch.zeros(1, 1, 64, 32, dtype=torch.float16)
+    vsum = torch.zeros(1, 1, 64, dtype=torch.float32)
+    desc, aux = B.kv_desc(k, v, table), B.sparf_aux(kt, vsum)
+    refs = [weakref.ref(t) for t in (k, v, table, kt, vsum)]
+    addr = (k.data_ptr(), v.data_ptr(), table.data_ptr(), kt.data_ptr(), vsum.data_ptr())
+    del k, v, table, kt, vsum
+    gc.collect()
+    assert all(r() is not None for r in refs)
+    assert (desc.k, desc.v, desc.page_table, aux.kt) == addr[:4]
+    assert ctypes.cast(aux.vsum, ctypes.c_void_p).value == addr[4]
+    del desc, aux
+    gc.collect()
+    assert all(r() is None for r in refs)

@@ -628,6 +628,53 @@ def test_sparf_drawn_configurations_in_forced_forms(monkeypatch, cfg):
     sparf_step(wl, r, k, l, torch.float16 if f16 else torch.float32, kt_page=kt_page, fused_append=fused)
 
 
+def test_calls_on_two_streams_at_once_do_not_disturb_each_other(monkeypatch):
+    """The library keeps no state between calls: a dense decode and a SparF decode of long
+    rows (six launches), each on a stream and a workspace of its own, issued alternately so
+    that they overlap on the GPU, give the bits they give one after the other."""
+    monkeypatch.setenv("INSTATTN_SPARF_DISTRIBUTED", "1")
+    wl_s = W.Workload("two_streams_sparf", 1, 4, 4, 128, 40000, seed=811)
+    wl_d = W.Workload("two_streams_dense", 3, 16, 2, 128, 9000, seq_len_min=3000, seed=812)
+    case, desc, aux, _, _, _ = setup(wl_s)
+    B.sparf_append(desc, aux, case.k_new, case.v_new, case.seq_lens)
+    r, k, l = 16, 2500, 16
+    want_out, want_sel, want_alpha = run_decode(case, desc, aux, r, k, l, torch.float16)
+    dcase = W.make_case(wl_d, DEV, poison=True)
+    ddesc = B.kv_desc(dcase.k_cache, dcase.v_cache, dcase.page_table)
+    B.kv_append(ddesc, dcase.k_new, dcase.v_new, dcase.seq_lens)
+    dmax = int(dcase.seq_lens.max())
+    dws = B.alloc_workspace(wl_d.batch, wl_d.num_q_heads, wl_d.num_kv_heads, 128, dmax, DEV)
+    dout = torch.empty(wl_d.batch, wl_d.num_q_heads, 128, dtype=torch.float16, device=DEV)
+    B.decode(dcase.q, ddesc, dcase.seq_lens, wl_d.num_kv_heads, dcase.scale, dout, dws, dmax)
+    torch.cuda.synchronize()
+    want_dense = dout.clone()
+    assert torch.isfinite(want_out.float()).all(), torch.isfinite(want_out.float()).all(dim=2).tolist()
+    assert torch.isfinite(want_dense.float()).all(), torch.isfinite(want_dense.float()).all(dim=2).tolist()
+
+    smax = int(case.seq_lens.max())
+    sws = torch.empty(B.sparf_workspace_size(1, 4, 128, smax, k), dtype=torch.uint8, device=DEV)
+    reps = 6
+    souts = torch.full((reps, 1, 4, 128), float("nan"), dtype=torch.float16, device=DEV)
+    ssels = torch.full((reps, 1, 4, k), -1, dtype=torch.int32, device=DEV)
+    salphas = torch.full((reps, 1, 4), float("nan"), dtype=torch.float32, device=DEV)
+    douts = torch.full((reps,) + tuple(dout.shape), float("nan"), dtype=torch.float16, device=DEV)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    for s_ in (s1, s2):
+        s_.wait_stream(torch.cuda.current_stream())
+    for i in range(reps):
+        with torch.cuda.stream(s1):
+            B.sparf_decode(case.q, desc, aux, case.seq_lens, wl_s.num_kv_heads, case.scale, r, k, l,
+                           souts[i], sws, smax, sel_rows=ssels[i], alpha=salphas[i])
+        with torch.cuda.stream(s2):
+            B.decode(dcase.q, ddesc, dcase.seq_lens, wl_d.num_kv_heads, dcase.scale, douts[i], dws, dmax)
+    torch.cuda.synchronize()
+    for i in range(reps):
+        assert torch.equal(souts[i].view(torch.int16), want_out.view(torch.int16)), i
+        assert torch.equal(ssels[i], want_sel), i
+        assert torch.equal(salphas[i].view(torch.int32), want_alpha.view(torch.int32)), i
+        assert torch.equal(douts[i].view(torch.int16), want_dense.view(torch.int16)), i
+
+
 def test_sparf_is_deterministic():
     wl = W.Workload("sparf_det", 2, 4, 4, 128, 3000, seed=406)
     case, desc, aux, kt, vsum, _ = setup(wl)
