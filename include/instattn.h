@@ -58,7 +58,10 @@ typedef enum { INSTATTN_F16 = 0, INSTATTN_F32 = 1 } instattn_dtype;
  *               page_size is a power of two >= 16 (the paper's 16-token, 4 KB group of
  *               Sec. IV-C "Token-Indexed Mapping" is page_size 16 with head_dim 128);
  *               capacity = page_size*max_pages_per_seq.  Entries behind the last
- *               used page are never read.  Pool ids must lie in [0, num_pages).
+ *               used page are never read.  Pool ids must lie in [0, num_pages); the
+ *               table is device data the host cannot check, so the kernels read an id
+ *               outside that range as the pool's last page: such a table costs a
+ *               meaningless result, never an access outside the pool.
  */
 typedef struct {
     void* k;                   /* device, fp16 */
@@ -211,7 +214,8 @@ int instattn_decode_merge(const int32_t* seq_lens, int batch, int num_q_heads, i
  *            runs along t, so this copy wants long pages (Sec. IV-C puts the
  *            granularity of the hidden-embedding-indexed copy at 256 to 1K tokens),
  *            while the row-major cache is fine with 16-token pages.  Entries of
- *            page_table behind the last used page are never read.
+ *            page_table behind the last used page are never read; ids outside
+ *            [0, num_pages) are read as the pool's last page, as for the cache's own table.
  *   vsum : fp32 [batch][num_kv_heads][head_dim], sum of rows 0 .. L_b-1 of V
  * The layout of kt is independent of the layout of the cache itself.
  */

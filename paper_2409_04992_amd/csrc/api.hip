@@ -142,6 +142,7 @@ int instattn_kv_append(const instattn_kv_desc* kv, const void* k_new, const void
     a.page_shift = w.page_shift;
     a.page_mask = w.page_mask;
     a.max_pages = w.max_pages;
+    a.last_page = w.last_page;
     a.k_new = (const half_t*)k_new;
     a.v_new = (const half_t*)v_new;
     a.seq_lens = seq_lens;

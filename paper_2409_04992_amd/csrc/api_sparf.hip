@@ -176,6 +176,7 @@ void fill_views(SparfArgs& a, const instattn_kv_desc* kv, const instattn_sparf_a
     a.aux.page_shift = paged ? ilog2(aux->page_size) : 0;
     a.aux.page_mask = paged ? aux->page_size - 1 : 0;
     a.aux.max_pages = paged ? aux->max_pages_per_seq : 0;
+    a.aux.last_page = paged ? aux->num_pages - 1 : 0;
 }
 
 int status_of(hipError_t e) { return e == hipSuccess ? INSTATTN_OK : INSTATTN_ERR_RUNTIME; }

@@ -31,6 +31,7 @@ struct KvView {
     int32_t page_shift;         // log2(page_size), paged only
     int32_t page_mask;          // page_size - 1
     int32_t max_pages;
+    int32_t last_page;          // num_pages - 1, paged only
 };
 
 // Arguments of the split pass (both the vector-ALU and the MFMA kernel).
@@ -73,7 +74,7 @@ struct AppendArgs {
     half_t* v;
     const int32_t* page_table;
     int64_t stride_b, stride_h, stride_t;
-    int32_t capacity, page_shift, page_mask, max_pages;
+    int32_t capacity, page_shift, page_mask, max_pages, last_page;
     const half_t* k_new;
     const half_t* v_new;
     const int32_t* seq_lens;
@@ -104,11 +105,26 @@ __device__ __forceinline__ int clamp_len(int L, int max_len) {
     return L > max_len ? max_len : L;
 }
 
+// A page id as read from a page table: the table lives on the device and cannot be
+// checked by the host, so an entry outside [0, num_pages) (a caller's mistake) is read as
+// the pool's last page and costs a wrong result, never an access outside the pool.
+__device__ __forceinline__ int pool_page(int id, int last_page) {
+    return (int)min((uint32_t)id, (uint32_t)last_page);     // one unsigned minimum: a negative id goes to the last page
+}
+
+// The same for the split passes, which fetch a wave's page id with a vector load and keep
+// the address arithmetic behind it on the vector ALU: the minimum is taken there too.
+__device__ __forceinline__ int pool_page_valu(int id, int last_page) {
+    int r;
+    asm("v_min_u32 %0, %1, %2" : "=v"(r) : "s"(last_page), "v"(id));
+    return r;
+}
+
 // Element offset of row t of (sequence b, KV head hk).
 __device__ __forceinline__ int64_t row_offset(const KvView& kv, int b, int hk, int t) {
     if (kv.page_table == nullptr)
         return (int64_t)b * kv.stride_b + (int64_t)hk * kv.stride_h + (int64_t)t * kv.stride_t;
-    int page = kv.page_table[(int64_t)b * kv.max_pages + (t >> kv.page_shift)];
+    const int page = pool_page(kv.page_table[(int64_t)b * kv.max_pages + (t >> kv.page_shift)], kv.last_page);
     return (int64_t)page * kv.stride_b + (int64_t)hk * kv.stride_h +
            (int64_t)(t & kv.page_mask) * kv.stride_t;
 }

@@ -153,7 +153,7 @@ __global__ __launch_bounds__(256, 2) void decode_gqa_kernel(DecodeArgs a)
         for (int m = 0; m < 2; ++m) {
             const int tm = sub_row(it, m);                      // wave-uniform
             const int in_page = PAGED ? (tm & a.kv.page_mask) : tm;
-            const int page = m == 0 ? page0 : page1;
+            const int page = PAGED ? pool_page_valu(m == 0 ? page0 : page1, a.kv.last_page) : b;
             const int64_t base =
                 2 * ((int64_t)page * a.kv.stride_b + head_off + (int64_t)in_page * a.kv.stride_t);
             const int first = t0 + tile_of(it) * kGqTile + wave * kGqWaveRows + 16 * m + g;

@@ -125,6 +125,7 @@ __global__ __launch_bounds__(INSTATTN_MHA_WAVES * 64) void decode_mha_kernel(Dec
     auto load_tile = [&](MhaTile<U>& T, int it, int page) {
         const int tw = wave_row(it);                         // wave-uniform
         const int in_page = PAGED ? (tw & a.kv.page_mask) : tw;
+        if constexpr (PAGED) page = pool_page_valu(page, a.kv.last_page);   // here, not at the fetch: the id stays in flight until now
         const int64_t tile_off =
             2 * ((int64_t)page * a.kv.stride_b + head_off + (int64_t)in_page * a.kv.stride_t);
         const int first = t0 + tile_of(it) * TILE + wave * WTILE + r;  // this lane's row for j = 0

@@ -54,6 +54,7 @@ inline KvView make_view(const instattn_kv_desc* kv)
     w.page_shift = kv->layout == INSTATTN_KV_PAGED ? ilog2(kv->page_size) : 0;
     w.page_mask = kv->layout == INSTATTN_KV_PAGED ? kv->page_size - 1 : 0;
     w.max_pages = kv->max_pages_per_seq;
+    w.last_page = kv->layout == INSTATTN_KV_PAGED ? kv->num_pages - 1 : 0;
     return w;
 }
 

@@ -111,7 +111,7 @@ __global__ __launch_bounds__(256) void kv_append_kernel(AppendArgs a)
     if (a.page_table == nullptr) {
         off = (int64_t)b * a.stride_b + (int64_t)t * a.stride_t;
     } else {
-        const int page = a.page_table[(int64_t)b * a.max_pages + (t >> a.page_shift)];
+        const int page = pool_page(a.page_table[(int64_t)b * a.max_pages + (t >> a.page_shift)], a.last_page);
         off = (int64_t)page * a.stride_b + (int64_t)(t & a.page_mask) * a.stride_t;
     }
     off += (int64_t)hk * a.stride_h + c * 8;

@@ -24,14 +24,14 @@ struct KtView {
     int32_t capacity;                  // max positions per sequence, multiple of 8
     float* vsum;                       // [B][Hkv][D] running sum of the first L_b rows of V
     const int32_t* page_table;         // nullptr: contiguous
-    int32_t page_shift, page_mask, max_pages;
+    int32_t page_shift, page_mask, max_pages, last_page;
 };
 
 // Where column 0 of KV head hk holds position t; the 8 positions of an aligned
 // run of 8 are contiguous there, and column d is d*stride_d further on.
 __device__ __forceinline__ half_t* kt_col0(const KtView& v, int b, int hk, int t) {
     if (v.page_table == nullptr) return v.kt + (int64_t)b * v.stride_b + (int64_t)hk * v.stride_h + t;
-    const int page = v.page_table[(int64_t)b * v.max_pages + (t >> v.page_shift)];
+    const int page = pool_page(v.page_table[(int64_t)b * v.max_pages + (t >> v.page_shift)], v.last_page);
     return v.kt + (int64_t)page * v.stride_b + (int64_t)hk * v.stride_h + (t & v.page_mask);
 }
 

@@ -129,6 +129,7 @@ __global__ __launch_bounds__(256, INSTATTN_SPARF_WAVES_PER_SIMD) void sparf_logi
     };
     auto ptr = [&](const Step& s, int v, int page) {
         const int t = run_of(s, v);
+        if constexpr (PAGED) page = pool_page(page, a.aux.last_page);   // at the use: the id was fetched a step ahead
         return a.aux.kt + (int64_t)page * a.aux.stride_b + (int64_t)hk * a.aux.stride_h + (PAGED ? (t & a.aux.page_mask) : t);
     };
     // columns (as offsets) and q components of a step, wave-uniform

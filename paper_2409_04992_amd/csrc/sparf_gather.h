@@ -67,7 +67,7 @@ __device__ __forceinline__ void attend_rows(const SparfArgs& a, int b, int h, in
             if (t == t_new) ids[i] = -1;
             else
                 ids[i] =
-                    paged ? (a.kv.page_table[(int64_t)b * a.kv.max_pages + (t >> shift)] << shift) | (t & mask) : t;
+                    paged ? (pool_page(a.kv.page_table[(int64_t)b * a.kv.max_pages + (t >> shift)], a.kv.last_page) << shift) | (t & mask) : t;
         }
         __syncthreads();
         auto load = [&](Tile& T, int it) {

@@ -224,6 +224,45 @@ def test_lengths_beyond_max_seq_len_are_clamped():
     assert torch.equal(out, ref)
 
 
+def _spoil(table, row, used, num_pages, seed):
+    """Entries of the used part of one sequence's page-table row set to ids outside the pool."""
+    idx = torch.randperm(used, generator=torch.Generator().manual_seed(seed))[:7].to(table.device)
+    table[row, idx[:3]] = -1
+    table[row, idx[3:5]] = 2**31 - 1
+    table[row, idx[5:]] = num_pages + 5
+    table[row, used - 1] = -7                       # the page the new token goes to
+
+
+@pytest.mark.parametrize("group", [1, 4])
+def test_page_ids_outside_the_pool_are_pulled_into_it(group):
+    """A page table is device data the host cannot check: ids outside [0, num_pages) are
+    replaced by the pool's last page in the kernels, so the step stays inside the pool and gives
+    exactly what it gives for the table with those ids replaced; sequences with sound rows are untouched."""
+    wl = W.Workload("bad_pages", 6, 4 * group, 4, 128, 3000, seq_len_min=1000, paged=True, seed=77)
+    runs = {}
+    for kind in ("sound", "bad", "clamped"):
+        case = W.make_case(wl, DEV, poison=False)
+        num_pages = case.k_cache.shape[0]
+        if kind == "sound":
+            # the spoilt ids land on the pool's first and last page: their owners see the new token's row
+            hit = ((case.page_table == 0) | (case.page_table == num_pages - 1)).any(dim=1).tolist()
+        if kind != "sound":
+            _spoil(case.page_table, 1, (int(case.seq_lens[1]) + 15) // 16, num_pages, 5)
+        if kind == "clamped":
+            case.page_table[(case.page_table < 0) | (case.page_table >= num_pages)] = num_pages - 1
+        for fused in (False, True):
+            out, lse = H.gpu_step(case, fused=fused)   # the second step stores the same row again
+            runs[kind, fused] = (out, lse, case.k_cache.clone(), case.v_cache.clone())
+    for fused in (False, True):
+        for x, y in zip(runs["bad", fused], runs["clamped", fused]):
+            assert torch.equal(x.view(torch.int16) if x.dtype == torch.float16 else x.view(torch.int32),
+                               y.view(torch.int16) if y.dtype == torch.float16 else y.view(torch.int32))
+        others = [b for b in range(wl.batch) if b != 1 and not hit[b]]
+        assert len(others) >= 3
+        for b in others:
+            assert torch.equal(runs["bad", fused][0][b].view(torch.int16), runs["sound", fused][0][b].view(torch.int16))
+
+
 def test_strided_cache_views():
     """Caches that are slices of larger tensors: strides larger than the dense ones."""
     wl = small("mha13b_4k", batch=2, num_q_heads=3, num_kv_heads=3, seq_len=333)

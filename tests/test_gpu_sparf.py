@@ -675,6 +675,32 @@ def test_calls_on_two_streams_at_once_do_not_disturb_each_other(monkeypatch):
         assert torch.equal(douts[i].view(torch.int16), want_dense.view(torch.int16)), i
 
 
+@pytest.mark.parametrize("seq_len,k", [(3000, 200), (20000, 1500)])
+def test_sparf_page_ids_outside_the_pools_are_pulled_into_them(seq_len, k):
+    """Both page tables are device data: ids outside their pools are replaced by the
+    pool's last page in the kernels (one-launch form and pipeline), and the step gives what it gives
+    for tables with those ids replaced."""
+    wl = W.Workload("sparf_bad_pages", 2, 3, 3, 128, seq_len, seq_len_min=seq_len // 2, paged=True, seed=913)
+    res = {}
+    for kind in ("bad", "clamped"):
+        case, desc, aux, kt, vsum, _ = setup(wl, kt_page=64)
+        L = int(case.seq_lens[1])
+        for table, page, pool in ((case.page_table, 16, case.k_cache.shape[0]), (case.kt_table, 64, kt.shape[0])):
+            used = (L + page - 1) // page
+            idx = torch.randperm(used, generator=torch.Generator().manual_seed(3))[:6].to(DEV)
+            table[1, idx[:2]] = -1
+            table[1, idx[2:4]] = 2**31 - 1
+            table[1, idx[4:]] = pool + 9
+            table[1, used - 1] = -3
+            if kind == "clamped":
+                table[(table < 0) | (table >= pool)] = pool - 1
+        out, sel, alpha = run_decode(case, desc, aux, 16, k, 16, torch.float16, fused_append=True)
+        res[kind] = (out.view(torch.int16), sel, alpha.view(torch.int32), case.k_cache.view(torch.int16).clone(),
+                     case.v_cache.view(torch.int16).clone(), kt.view(torch.int16).clone(), vsum.view(torch.int32).clone())
+    for x, y in zip(res["bad"], res["clamped"]):
+        assert torch.equal(x, y)
+
+
 def test_sparf_is_deterministic():
     wl = W.Workload("sparf_det", 2, 4, 4, 128, 3000, seed=406)
     case, desc, aux, kt, vsum, _ = setup(wl)
