@@ -554,7 +554,7 @@ __global__ __launch_bounds__(256) void sparf_compact_kernel(SparfArgs a)
     float mass = 0.f;
     compact_tile<NT, STEPS>(
         xr, [&](int i, int e) { return level1(xr[i][e]); }, v.t0, v.ncand, bin1, thr, rem_eq, gt_base, eq_base,
-        &S.wave_cnt[0][0], M, sel, mass);
+        &S.wave_cnt[0][0], M, sel, (uint32_t)v.want, mass);
     if (chunk == 0) {
         // step 5: the l most recent positions are always kept
         for (int i = tid; i < v.leff; i += NT) {

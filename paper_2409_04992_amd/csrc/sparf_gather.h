@@ -63,7 +63,7 @@ __device__ __forceinline__ void attend_rows(const SparfArgs& a, int b, int h, in
         const int nc = min(ids_cap, p_end - c0);
         __syncthreads();                   // whatever used this LDS before is done with it
         for (int i = tid; i < nc; i += WAVES * 64) {
-            const int t = sel[c0 + i];
+            const int t = min(max(sel[c0 + i], 0), L - 1);   // a kept position, whatever the list holds
             if (t == t_new) ids[i] = -1;
             else
                 ids[i] =

@@ -218,7 +218,7 @@ template <int NT, int STEPS, class BinOf>
 __device__ __forceinline__ void compact_tile(const float (&xr)[STEPS][8], BinOf&& bin_of, int t_off, int ncand,
                                              uint32_t bin1, uint32_t prefix, uint32_t remaining,
                                              uint32_t& gt_base, uint32_t& eq_base, uint32_t* step_cnt,
-                                             float M, int32_t* sel, float& mass)
+                                             float M, int32_t* sel, uint32_t room, float& mass)
 {
     constexpr int NW = NT / 64;
     typedef typename std::conditional<(STEPS > 4), uint64_t, uint32_t>::type bits_t;
@@ -274,7 +274,11 @@ __device__ __forceinline__ void compact_tile(const float (&xr)[STEPS][8], BinOf&
             const uint32_t eq_before = eb + (uint32_t)__popc(e8 & below);
             const bool above = (g8 >> e) & 1u;
             if (above || eq_before < remaining) {
-                sel[gb + (uint32_t)__popc(g8 & below) + min(eq_before, remaining)] = t_off + (i * NT + tid) * 8 + e;
+                // slot < room whenever the counts behind the threshold agree with these predicates,
+                // which they do by construction; the test keeps a disagreement (scores that are
+                // not numbers) from ever becoming a store behind the list
+                const uint32_t slot = gb + (uint32_t)__popc(g8 & below) + min(eq_before, remaining);
+                if (slot < room) sel[slot] = t_off + (i * NT + tid) * 8 + e;
                 if (!above) mass += mass_at_key;           // rows at the threshold key share one score
             }
         }
@@ -324,7 +328,7 @@ __device__ __forceinline__ float select_rows(const float* x, int L, int k, int l
         own_scores<NT, STEPS>(x + t_off, ncand - t_off, xr);
         compact_tile<NT, STEPS>(
             xr, [&](int i, int e) { return level1(xr[i][e]); }, t_off, ncand, bin1, prefix, remaining, gt_base,
-            eq_base, &S.wave_cnt[parity * 4][0], M, sel, mass);
+            eq_base, &S.wave_cnt[parity * 4][0], M, sel, (uint32_t)want, mass);
     }
     // step 5: the l most recent positions are always kept
     for (int i = tid; i < leff; i += NT) {
@@ -388,7 +392,7 @@ __device__ __forceinline__ float select_rows_reg(const float (&xr)[STEPS][8], co
     if (want > 0) {
         uint32_t gt_base = 0, eq_base = 0;
         compact_tile<NT, STEPS>(xr, bin_of, 0, ncand, bin1, prefix, remaining, gt_base, eq_base, &S.wave_cnt[0][0],
-                                M, sel, mass);
+                                M, sel, (uint32_t)want, mass);
     }
     // step 5: the l most recent positions are always kept
     for (int i = tid; i < leff; i += NT) {

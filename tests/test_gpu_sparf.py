@@ -701,6 +701,42 @@ def test_sparf_page_ids_outside_the_pools_are_pulled_into_them(seq_len, k):
         assert torch.equal(x, y)
 
 
+@pytest.mark.parametrize("seq_len,k,distributed", [(3000, 200, None), (20000, 1500, "0"), (20000, 1500, "1"),
+                                                   (70000, 3000, "0"), (70000, 3000, "1")])
+def test_sparf_scores_that_are_not_numbers_stay_inside_their_head(monkeypatch, seq_len, k, distributed):
+    """NaN and infinities in K, V or q make scores the selection cannot order sensibly.
+    Every address that depends on a score is bounded all the same: nothing is written
+    outside the outputs (guard band, untouched neighbours), the kept positions of the
+    spoilt heads lie in the row, and the other heads give the bits of the clean run."""
+    if distributed is not None:
+        monkeypatch.setenv("INSTATTN_SPARF_DISTRIBUTED", distributed)
+    wl = W.Workload("sparf_nonfinite", 2, 4, 4, 128, seq_len, seq_len_min=seq_len - 100, seed=977)
+    res = {}
+    for kind in ("clean", "spoilt"):
+        case, desc, aux, kt, vsum, _ = setup(wl)
+        if kind == "spoilt":
+            L0 = int(case.seq_lens[0])
+            rows = torch.randperm(L0 - 1, generator=torch.Generator().manual_seed(9))[:60].to(DEV)
+            vals = torch.tensor([float("nan"), float("inf"), -float("inf")], dtype=torch.float16, device=DEV)
+            # head 0 of sequence 0: spoilt keys (both copies) and values; head 1: spoilt query
+            case.k_cache[0, 0, rows, ::7] = vals[torch.arange(60, device=DEV) % 3, None]
+            kt[0, 0, :, rows] = case.k_cache[0, 0, rows].t()
+            case.v_cache[0, 0, rows[:5], 3] = float("nan")
+            case.q[0, 1, 5] = float("nan")
+            case.q[0, 1, 77] = float("inf")
+        out, sel, alpha = run_decode(case, desc, aux, 16, k, 16, torch.float16, fused_append=True)
+        res[kind] = (out, sel, alpha, case.seq_lens.clone())
+    out, sel, alpha, lens = res["spoilt"]
+    for h in (0, 1):
+        L0 = int(lens[0])
+        assert int(sel[0, h, :min(k, L0)].min()) >= 0 and int(sel[0, h, :min(k, L0)].max()) < L0
+    clean_out, clean_sel, clean_alpha, _ = res["clean"]
+    for b, h in [(0, 2), (0, 3), (1, 0), (1, 1), (1, 2), (1, 3)]:
+        assert torch.equal(out[b, h].view(torch.int16), clean_out[b, h].view(torch.int16)), (b, h)
+        assert torch.equal(sel[b, h], clean_sel[b, h]), (b, h)
+        assert torch.equal(alpha[b, h].view(torch.int32), clean_alpha[b, h].view(torch.int32)), (b, h)
+
+
 def test_sparf_is_deterministic():
     wl = W.Workload("sparf_det", 2, 4, 4, 128, 3000, seed=406)
     case, desc, aux, kt, vsum, _ = setup(wl)
