@@ -19,7 +19,10 @@
  *     before anything is launched; a rejected call launches nothing.
  *   - Lengths live on the device and cannot be checked by the host, so kernels
  *     clamp them: L_b is read as min(max(seq_lens[b], 0), capacity, max_seq_len).
- *   - fp16 is IEEE binary16; all accumulation is fp32.
+ *   - fp16 is IEEE binary16; all accumulation is fp32.  NaN and infinities in q, K or V
+ *     spread through the arithmetic into the output rows that read them (under SparF the
+ *     kept positions of such a head are then arbitrary positions of its row); no address
+ *     computed from them leaves the caller's buffers.
  *   - Query head h reads KV head h / (num_q_heads / num_kv_heads).
  */
 #ifndef INSTATTN_H
