@@ -275,7 +275,7 @@ int instattn_sparf_append(const instattn_kv_desc* kv, const instattn_sparf_aux* 
  *   [0] kernel launches in all
  *   [1] threads per block of the one-launch kernel (256, 512 or 1024), 0 if the
  *       pipeline runs instead
- *   [2] 1 if the decode's launch stores the new token itself
+ *   [2] 1 if the decode's first launch stores the new token itself
  *   [3] pipeline only: 1 = one block per head selects, 2 = one block per 8192 scores
  *   [4] pipeline only: 1 if the block that selects also gathers the kept rows
  *   [5] slices a head's kept rows are gathered in
@@ -319,9 +319,9 @@ int instattn_sparf_decode(const void* q, const instattn_kv_desc* kv, const insta
  * instattn_sparf_append followed by instattn_sparf_decode, as the storage side sees
  * a decode step (the new token's q, k, v arrive together, Sec. IV-D): same results
  * in the cache, in aux and in out/sel_rows/alpha as the two calls in that order.
- * When the decode is one launch (see above) and every KV head has one query head,
- * that launch stores the new token itself; otherwise the append is a launch of its
- * own in front.  Like instattn_sparf_append it must be called once per new token.
+ * When every KV head has one query head the decode's first launch (the one-launch
+ * kernel, or the column-score pass) stores the new token itself; otherwise the
+ * append is a launch of its own in front.  Like instattn_sparf_append it must be called once per new token.
  *   k_new, v_new : device, [batch][num_kv_heads][head_dim] fp16, dense, 16-byte aligned
  */
 int instattn_sparf_append_decode(const void* q, const void* k_new, const void* v_new,

@@ -122,9 +122,11 @@ SparfPlan plan_sparf(int batch, int num_q_heads, int num_kv_heads, int max_seq_l
                                   // 320 and 640 heads level; 40 heads 74 against 56)
     if (force3 && force3[0] == '1') p.fused_threads = 0;
     p.one_launch = p.fused_threads != 0;
-    // The one-launch kernel stores the new token itself when its block is the only
-    // reader of what it stores; otherwise the append is a launch of its own.
-    p.append_fused = append && p.one_launch && num_q_heads == num_kv_heads;
+    // The decode's first launch (the one-launch kernel, or the pipeline's score pass) stores
+    // the new token itself when one block is the only reader of what it stores during that
+    // launch, which takes one query head per KV head; otherwise the append is a launch of
+    // its own.
+    p.append_fused = append && num_q_heads == num_kv_heads;
     // One block per head and no slices: that block also gathers the rows it kept.
     const char* split = getenv("INSTATTN_SPARF_SPLIT_TAIL");
     p.fused_tail = !p.one_launch && !p.distributed && p.nslices == 1 && max_seq_len < kSparfTailMaxLen &&
@@ -332,6 +334,7 @@ int run_sparf_decode(const void* q, const void* k_new, const void* v_new, bool a
     }
     if (plan.one_launch) return status_of(launch_sparf_fused(a, s));
     if (launch_sparf_logits(a, s) != hipSuccess) return INSTATTN_ERR_RUNTIME;
+    a.k_new = a.v_new = nullptr;                  // stored by now, one way or the other
     if (plan.fused_tail) return status_of(launch_sparf_select_attend(a, s));
     if (launch_sparf_select(a, s) != hipSuccess) return INSTATTN_ERR_RUNTIME;
     return status_of(launch_sparf_attend(a, s));

@@ -83,9 +83,25 @@ __global__ __launch_bounds__(256, INSTATTN_SPARF_WAVES_PER_SIMD) void sparf_logi
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int64_t row = (int64_t)b * a.num_q_heads + h;
-    const int L = clamp_len(a.seq_lens[b], a.max_len);
+    const int L_raw = a.seq_lens[b];
+    const int L = clamp_len(L_raw, a.max_len);
     const int nunits = (L + UNIT - 1) / UNIT;
-    if ((int)blockIdx.y >= nunits) return;                    // block-uniform, before any barrier
+    const int stride = gridDim.y;
+    if (a.k_new != nullptr) {
+        // Fused append (one query head per KV head only).  The new token's column entries
+        // are read by one block of the head alone, the one that walks the unit of position
+        // L_raw - 1: that block stores the token (row, column entries, sum) before its first
+        // load and synchronises, so that its own loads see the new bits; the launches behind
+        // this one see them anyway.  A position behind the attended range is read by nobody:
+        // the head's first block stores it.
+        const int t_new = L_raw - 1;
+        const int owner = t_new >= 0 && t_new < L ? (t_new / UNIT) % stride : 0;
+        if ((int)blockIdx.y == owner) {                       // block-uniform
+            if (tid < a.head_dim) append_component(a, b, hk, tid, L_raw);
+            __syncthreads();
+        }
+    }
+    if ((int)blockIdx.y >= nunits) return;                    // block-uniform
     __shared__ float s_q[128];
     __shared__ __align__(16) float s_abs[128];
     __shared__ int s_dim[128];
@@ -100,7 +116,6 @@ __global__ __launch_bounds__(256, INSTATTN_SPARF_WAVES_PER_SIMD) void sparf_logi
     const int qw_hi = __builtin_bit_cast(int, s_q[dim_hi] * factor);
 
     const int ng = (a.r + CG - 1) / CG;                       // steps per unit
-    const int stride = gridDim.y;
     const int t_last = (L - 1) & ~7;                          // last run of 8 that holds a position
     struct Step {
         int u, g;                                             // unit, column group

@@ -306,10 +306,14 @@ def test_sparf_plan_of_the_measured_shapes(no_sparf_env):
     # 64 ragged sequences up to 16K: the 512-thread form
     p = B.sparf_plan(64, 40, 40, 128, 16385, 1024, with_append=True)
     assert p["launches"] == 1 and p["one_launch_threads"] == 512 and p["append_fused"]
-    # 8 x 40 heads x 32K: score pass, selection spread over the stretches, sliced gather, merge
+    # 8 x 40 heads x 32K: score pass (which stores the new token), selection spread over the
+    # stretches, sliced gather, merge
     p = B.sparf_plan(8, 40, 40, 128, 32769, 2048, with_append=True)
-    assert p == {"launches": 7, "one_launch_threads": 0, "append_fused": False, "selection": 2,
+    assert p == {"launches": 6, "one_launch_threads": 0, "append_fused": True, "selection": 2,
                  "select_and_gather": False, "slices": 4}
+    # the same with grouped queries: the append is a launch of its own
+    p = B.sparf_plan(8, 40, 8, 128, 32769, 2048, with_append=True)
+    assert p["launches"] == 7 and not p["append_fused"]
     # 1 x 40 heads x 128K
     p = B.sparf_plan(1, 40, 40, 128, 131073, 8192)
     assert p["selection"] == 2 and p["slices"] == 8 and p["launches"] == 6
@@ -355,6 +359,8 @@ def test_sparf_plan_environment_switches(no_sparf_env):
     m = no_sparf_env
     m.setenv("INSTATTN_SPARF_THREE_LAUNCHES", "1")
     p = B.sparf_plan(16, 40, 40, 128, 4097, 256, with_append=True)
+    assert p["one_launch_threads"] == 0 and p["append_fused"] and p["launches"] == 2
+    p = B.sparf_plan(16, 40, 8, 128, 4097, 256, with_append=True)
     assert p["one_launch_threads"] == 0 and not p["append_fused"] and p["launches"] == 3
     m.setenv("INSTATTN_SPARF_SPLIT_TAIL", "1")
     assert B.sparf_plan(16, 40, 40, 128, 4097, 256)["launches"] == 3
