@@ -147,8 +147,9 @@ size_t instattn_decode_workspace_size(int batch, int num_q_heads, int num_kv_hea
  *   max_seq_len : host-known upper bound of every L_b (<= capacity); it fixes the
  *               split plan, so no device value is read back
  * Supported: head_dim 64 or 128; num_q_heads a multiple of num_kv_heads with a
- * ratio of 1 (vector-ALU path) or 2..16 (MFMA group path); both layouts; both
- * output types.  Two kernel launches (partial pass, merge); the merge is skipped
+ * ratio of 1 (vector-ALU path) or more (MFMA group path: up to 16 query heads of a
+ * group share one pass over their KV head; a larger group, as in multi-query
+ * models, takes one pass per 16 of its heads); both layouts; both output types.  Two kernel launches (partial pass, merge); the merge is skipped
  * when the plan has a single split.
  */
 int instattn_decode(const void* q, const instattn_kv_desc* kv, const int32_t* seq_lens,
@@ -162,7 +163,7 @@ int instattn_decode(const void* q, const instattn_kv_desc* kv, const int32_t* se
  * two calls in that order: the caches end up bit-identical and out/lse are those
  * of instattn_decode on the updated caches.  The store of the new row is done
  * inside the split pass by the unit that owns position seq_lens[b] - 1, which
- * saves a kernel launch.
+ * saves a kernel launch (groups of more than 16 query heads: a launch of its own).
  *   k_new, v_new : device, [batch][num_kv_heads][head_dim] fp16, dense, 16-byte aligned
  */
 int instattn_append_decode(const void* q, const void* k_new, const void* v_new,

@@ -82,7 +82,6 @@ int check_shape(int batch, int num_q_heads, int num_kv_heads, int head_dim, int 
         return INSTATTN_ERR_INVALID_ARG;
     if (num_q_heads % num_kv_heads != 0) return INSTATTN_ERR_INVALID_ARG;
     if (head_dim != 64 && head_dim != 128) return INSTATTN_ERR_UNSUPPORTED;
-    if (num_q_heads / num_kv_heads > 16) return INSTATTN_ERR_UNSUPPORTED;
     if (batch > 65535 || num_q_heads > 65535) return INSTATTN_ERR_UNSUPPORTED;  // grid y, z
     return INSTATTN_OK;
 }
@@ -214,7 +213,17 @@ static int run_partial(const void* q, const void* k_new, const void* v_new, bool
                    workspace_bytes_for(batch, num_q_heads, head_dim, p));
     if (st != INSTATTN_OK) return st;
 
+    // The split pass stores the new token itself where one block per KV head and unit reads
+    // it; a group of more than 16 query heads is shared out over several blocks, so there the
+    // store is a launch of its own in front.
+    const int group = num_q_heads / num_kv_heads;
+    if (fused && group > 16) {
+        st = instattn_kv_append(kv, k_new, v_new, seq_lens, batch, num_kv_heads, head_dim, stream);
+        if (st != INSTATTN_OK) return st;
+        fused = false;
+    }
     DecodeArgs a;
+    a.group_blocks = (group + 15) / 16;
     a.k_new = fused ? (const half_t*)k_new : nullptr;
     a.v_new = fused ? (const half_t*)v_new : nullptr;
     // Streams whose strides walk the HBM channels in step (a contiguous cache of 2064

@@ -56,6 +56,9 @@ struct DecodeArgs {
     // 1: every unit starts its walk over its rows at a tile of its own (and wraps
     // round) instead of at its first row.
     int32_t rotate;
+    // MFMA kernel: blocks per KV head and unit; each takes up to 16 of the group's
+    // query heads (1 for groups of at most 16).
+    int32_t group_blocks;
 };
 
 // Arguments of the log-sum-exp merge.

@@ -92,12 +92,16 @@ __global__ __launch_bounds__(256, 2) void decode_gqa_kernel(DecodeArgs a)
     constexpr int EL = TR::EL, KK = TR::KK;
     // blockIdx.x walks KV heads: consecutive blocks go round-robin over the XCDs,
     // so every XCD gets the same mix of units whatever the lengths are.
-    const int split = blockIdx.y, hk = blockIdx.x, b = blockIdx.z;
-    const int G = a.num_q_heads / a.num_kv_heads;
+    // A group of more than 16 query heads is shared out over group_blocks blocks, 16 heads
+    // each (the last one the rest): every one of them streams the KV head again.
+    const int split = blockIdx.y, b = blockIdx.z;
+    const int hk = (int)blockIdx.x / a.group_blocks, sub = (int)blockIdx.x - hk * a.group_blocks;
+    const int group = a.num_q_heads / a.num_kv_heads;
+    const int G = min(16, group - 16 * sub);                 // query heads of this block
     const int L = clamp_len(a.seq_lens[b], a.max_len);
     const int t0 = split * a.chunk;
     const int tid = threadIdx.x;
-    const int64_t row0 = (int64_t)b * a.num_q_heads + (int64_t)hk * G;   // first query head of the group
+    const int64_t row0 = (int64_t)b * a.num_q_heads + (int64_t)hk * group + 16 * sub;   // first query head of the block
 
     fused_append<D>(a, b, hk, split, tid);
 
@@ -303,7 +307,7 @@ __global__ __launch_bounds__(256, 2) void decode_gqa_kernel(DecodeArgs a)
 template <int D>
 static hipError_t launch_gqa(const DecodeArgs& a, int batch, hipStream_t stream)
 {
-    dim3 grid(a.num_kv_heads, a.num_splits, batch);
+    dim3 grid(a.num_kv_heads * a.group_blocks, a.num_splits, batch);
     const bool paged = a.kv.page_table != nullptr;
     if (a.out_f32) {
         if (paged) hipLaunchKernelGGL((decode_gqa_kernel<D, true, true>), grid, dim3(256), 0, stream, a);

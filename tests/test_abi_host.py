@@ -76,7 +76,6 @@ def decode_status(d, q=FAKE, seq=FAKE, batch=16, hq=40, hkv=40, dim=128, scale=0
     (dict(hq=0), B.ERR_INVALID_ARG),
     (dict(dim=96), B.ERR_UNSUPPORTED),
     (dict(dim=256), B.ERR_UNSUPPORTED),
-    (dict(hq=64, hkv=2), B.ERR_UNSUPPORTED),           # group of 32
     (dict(out_dtype=7), B.ERR_INVALID_ARG),
     (dict(max_len=0), B.ERR_INVALID_ARG),
     (dict(max_len=5000), B.ERR_INVALID_ARG),           # beyond the capacity

@@ -186,6 +186,17 @@ def test_grouped_queries(group, head_dim, paged):
     full_check(wl, out_dtype=torch.float32 if group == 8 else torch.float16)
 
 
+@pytest.mark.parametrize("group,head_dim", [(17, 128), (32, 128), (40, 64), (64, 128), (71, 64)])
+@pytest.mark.parametrize("paged", [False, True])
+@pytest.mark.parametrize("fused", [False, True])
+def test_groups_of_more_than_16_query_heads(group, head_dim, paged, fused):
+    """Multi-query shapes: a group beyond the 16 rows of a matrix-core tile is shared out over
+    several blocks per KV head, 16 heads each and the rest (17 = 16 + 1, 71 = 4 x 16 + 7);
+    the fused call stores the new token in a launch of its own then."""
+    wl = W.Workload("mqa", 2, 2 * group, 2, head_dim, 2500, seq_len_min=300, paged=paged, seed=89)
+    full_check(wl, out_dtype=torch.float32 if group % 2 else torch.float16, fused=fused)
+
+
 def test_empty_and_mixed_lengths():
     wl = small("mha13b_4k", batch=5, num_q_heads=2, num_kv_heads=2, seq_len=600)
     case = W.make_case(wl, DEV, poison=False)
