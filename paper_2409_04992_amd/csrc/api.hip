@@ -3,6 +3,7 @@
 #include "../../include/instattn.h"
 
 #include <math.h>
+#include <limits.h>
 #include <stdlib.h>
 
 #include "common.h"
@@ -224,6 +225,11 @@ static int run_partial(const void* q, const void* k_new, const void* v_new, bool
     }
     DecodeArgs a;
     a.group_blocks = (group + 15) / 16;
+    a.units = 0;
+    // such a group runs on a one-dimensional grid of units x blocks per unit
+    if (a.group_blocks > 1 &&
+        ((int64_t)batch * num_kv_heads * p.num_splits + 8) * a.group_blocks > (int64_t)INT32_MAX)
+        return INSTATTN_ERR_UNSUPPORTED;
     a.k_new = fused ? (const half_t*)k_new : nullptr;
     a.v_new = fused ? (const half_t*)v_new : nullptr;
     // Streams whose strides walk the HBM channels in step (a contiguous cache of 2064

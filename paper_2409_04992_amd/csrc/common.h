@@ -59,6 +59,7 @@ struct DecodeArgs {
     // MFMA kernel: blocks per KV head and unit; each takes up to 16 of the group's
     // query heads (1 for groups of at most 16).
     int32_t group_blocks;
+    int32_t units;              // with group_blocks > 1: KV heads x splits x sequences (the grid is one-dimensional then)
 };
 
 // Arguments of the log-sum-exp merge.

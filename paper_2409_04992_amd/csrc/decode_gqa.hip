@@ -94,8 +94,20 @@ __global__ __launch_bounds__(256, 2) void decode_gqa_kernel(DecodeArgs a)
     // so every XCD gets the same mix of units whatever the lengths are.
     // A group of more than 16 query heads is shared out over group_blocks blocks, 16 heads
     // each (the last one the rest): every one of them streams the KV head again.
-    const int split = blockIdx.y, b = blockIdx.z;
-    const int hk = (int)blockIdx.x / a.group_blocks, sub = (int)blockIdx.x - hk * a.group_blocks;
+    // Those blocks of a unit are 8 apart in a one-dimensional grid: same XCD, dispatched
+    // together, so that the passes behind the first find the rows in that XCD's L2.
+    int split = blockIdx.y, b = blockIdx.z, hk = blockIdx.x, sub = 0;
+    if (a.group_blocks > 1) {
+        const int span = 8 * a.group_blocks;
+        const int chunk = (int)blockIdx.x / span, within = (int)blockIdx.x - chunk * span;
+        sub = within >> 3;
+        const int u = chunk * 8 + (within & 7);              // unit: KV head fastest, then split, then sequence
+        if (u >= a.units) return;                            // block-uniform: the grid is rounded up
+        hk = u % a.num_kv_heads;
+        const int rest = u / a.num_kv_heads;
+        split = rest % a.num_splits;
+        b = rest / a.num_splits;
+    }
     const int group = a.num_q_heads / a.num_kv_heads;
     const int G = min(16, group - 16 * sub);                 // query heads of this block
     const int L = clamp_len(a.seq_lens[b], a.max_len);
@@ -305,9 +317,14 @@ __global__ __launch_bounds__(256, 2) void decode_gqa_kernel(DecodeArgs a)
 }
 
 template <int D>
-static hipError_t launch_gqa(const DecodeArgs& a, int batch, hipStream_t stream)
+static hipError_t launch_gqa(const DecodeArgs& args, int batch, hipStream_t stream)
 {
-    dim3 grid(a.num_kv_heads * a.group_blocks, a.num_splits, batch);
+    DecodeArgs a = args;
+    dim3 grid(a.num_kv_heads, a.num_splits, batch);
+    if (a.group_blocks > 1) {
+        a.units = a.num_kv_heads * a.num_splits * batch;
+        grid = dim3((unsigned)((a.units + 7) / 8 * 8 * a.group_blocks), 1, 1);
+    }
     const bool paged = a.kv.page_table != nullptr;
     if (a.out_f32) {
         if (paged) hipLaunchKernelGGL((decode_gqa_kernel<D, true, true>), grid, dim3(256), 0, stream, a);
