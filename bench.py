@@ -26,7 +26,7 @@ HBM_PEAK_GBPS = 8000.0
 # WRITE_SIZE runs of this script, scaled by what the same counters read for the
 # 256 MiB copy kernel (FETCH_SIZE x 2.000, WRITE_SIZE x 1.000); see profiles/.
 MEASURED_TRAFFIC_BYTES = {"mha13b_4k": 1343993230, "mha13b_32k": 5374823655, "ragged_paged": 11332819755,
-                          "gqa70b_16k": 2151825181}
+                          "gqa70b_16k": 2151831655}
 # The same for all launches of a SparF step (fetched + written), keyed by workload and r,k,l.
 SPARF_MEASURED_TRAFFIC_BYTES = {("mha13b_4k", "16,256,16"): 172801109 + 4116672,
                                 ("mha13b_32k", "16,2048,16"): 820750144 + 48992272,

@@ -65,9 +65,14 @@ struct GqaTile {
     typename GqTraits<D>::vec_t v[8];
 };
 
-template <int D>
+// One lane's share of a row.  A row that one block alone reads carries the non-temporal
+// hint (measured +10 %); KEEP: several blocks of the XCD read it (a group of more than
+// 16 query heads), so it should stay in the L2 for the ones behind the first.
+template <int D, bool KEEP>
 __device__ __forceinline__ typename GqTraits<D>::vec_t gq_load(const char* base, uint32_t lane_off) {
-    return __builtin_nontemporal_load((const typename GqTraits<D>::vec_t*)(base + (uint64_t)lane_off));
+    typedef typename GqTraits<D>::vec_t vec_t;
+    if constexpr (KEEP) return *(const vec_t*)(base + (uint64_t)lane_off);
+    else return __builtin_nontemporal_load((const vec_t*)(base + (uint64_t)lane_off));
 }
 
 __device__ __forceinline__ float xor_lanes(float x, int mask) {
@@ -84,7 +89,7 @@ __device__ __forceinline__ void wave_lds_fence() {
 
 }  // namespace
 
-template <int D, bool PAGED, bool SPLIT_P>
+template <int D, bool PAGED, bool SPLIT_P, bool KEEP>
 __global__ __launch_bounds__(256, 2) void decode_gqa_kernel(DecodeArgs a)
 {
     typedef GqTraits<D> TR;
@@ -177,8 +182,8 @@ __global__ __launch_bounds__(256, 2) void decode_gqa_kernel(DecodeArgs a)
             for (int x = 0; x < 4; ++x) {
                 // rows behind the unit's end are redirected to its last row
                 const uint32_t off = (uint32_t)(min(first + 4 * x, last) - tm) * row_bytes + c * TR::kLaneBytes;
-                T.k[4 * m + x] = gq_load<D>(kp + base, off);
-                T.v[4 * m + x] = gq_load<D>(vp + base, off);
+                T.k[4 * m + x] = gq_load<D, KEEP>(kp + base, off);
+                T.v[4 * m + x] = gq_load<D, KEEP>(vp + base, off);
             }
         }
     };
@@ -325,14 +330,16 @@ static hipError_t launch_gqa(const DecodeArgs& args, int batch, hipStream_t stre
         a.units = a.num_kv_heads * a.num_splits * batch;
         grid = dim3((unsigned)((a.units + 7) / 8 * 8 * a.group_blocks), 1, 1);
     }
-    const bool paged = a.kv.page_table != nullptr;
-    if (a.out_f32) {
-        if (paged) hipLaunchKernelGGL((decode_gqa_kernel<D, true, true>), grid, dim3(256), 0, stream, a);
-        else hipLaunchKernelGGL((decode_gqa_kernel<D, false, true>), grid, dim3(256), 0, stream, a);
+    const bool paged = a.kv.page_table != nullptr, keep = a.group_blocks > 1;
+#define INSTATTN_GQA(P, S, K) hipLaunchKernelGGL((decode_gqa_kernel<D, P, S, K>), grid, dim3(256), 0, stream, a)
+    if (keep) {
+        if (a.out_f32) { if (paged) INSTATTN_GQA(true, true, true); else INSTATTN_GQA(false, true, true); }
+        else { if (paged) INSTATTN_GQA(true, false, true); else INSTATTN_GQA(false, false, true); }
     } else {
-        if (paged) hipLaunchKernelGGL((decode_gqa_kernel<D, true, false>), grid, dim3(256), 0, stream, a);
-        else hipLaunchKernelGGL((decode_gqa_kernel<D, false, false>), grid, dim3(256), 0, stream, a);
+        if (a.out_f32) { if (paged) INSTATTN_GQA(true, true, false); else INSTATTN_GQA(false, true, false); }
+        else { if (paged) INSTATTN_GQA(true, false, false); else INSTATTN_GQA(false, false, false); }
     }
+#undef INSTATTN_GQA
     return hipGetLastError();
 }
 
