@@ -37,6 +37,7 @@ class Workload:
     head_scale: bool = False     # per-KV-head std drawn from U[0.5, 2] for K and V
     layers: int = 1
     seed: int = 0
+    kv_adjacent: bool = False    # paged: one pool [num_pages][Hkv][2][page][D], a (page, head)'s K and V blocks adjacent
 
     @property
     def group(self) -> int:
@@ -152,8 +153,12 @@ def make_case(wl: Workload, device="cpu", layer: int = 0, poison: bool = False,
         spare = 3
         num_pages = sum(need) + spare
         cap = ps * max_pages
-        k_cache = _randn_f16((num_pages, Hkv, ps, D), g, dev)
-        v_cache = _randn_f16((num_pages, Hkv, ps, D), g, dev)
+        if wl.kv_adjacent:
+            pool = _randn_f16((num_pages, Hkv, 2, ps, D), g, dev)
+            k_cache, v_cache = pool[:, :, 0], pool[:, :, 1]     # same strides, bases 4 KB apart
+        else:
+            k_cache = _randn_f16((num_pages, Hkv, ps, D), g, dev)
+            v_cache = _randn_f16((num_pages, Hkv, ps, D), g, dev)
         gp = _gen("cpu", wl.seed * 7 + 3)
         perm = torch.randperm(num_pages, generator=gp).to(torch.int32)
         table = torch.full((B, max_pages), -1, dtype=torch.int32)

@@ -274,6 +274,19 @@ def test_page_ids_outside_the_pool_are_pulled_into_it(group):
             assert torch.equal(runs["bad", fused][0][b].view(torch.int16), runs["sound", fused][0][b].view(torch.int16))
 
 
+@pytest.mark.parametrize("group,head_dim", [(1, 128), (1, 64), (8, 128), (4, 64)])
+@pytest.mark.parametrize("fused", [False, True])
+def test_paged_pool_with_k_and_v_of_a_page_adjacent(group, head_dim, fused):
+    """One pool [num_pages][Hkv][2][16][D]: K and V of a (page, head) are one contiguous 8 KB
+    piece; the descriptor expresses it through the strides and two bases."""
+    wl = W.Workload("kv_adjacent", 3, 2 * group, 2, head_dim, 2500, seq_len_min=200, paged=True,
+                    kv_adjacent=True, seed=91)
+    case = W.make_case(wl, DEV)
+    assert case.k_cache.stride() == case.v_cache.stride() and not case.k_cache.is_contiguous()
+    assert case.v_cache.data_ptr() - case.k_cache.data_ptr() == 16 * head_dim * 2
+    full_check(wl, fused=fused)
+
+
 def test_strided_cache_views():
     """Caches that are slices of larger tensors: strides larger than the dense ones."""
     wl = small("mha13b_4k", batch=2, num_q_heads=3, num_kv_heads=3, seq_len=333)

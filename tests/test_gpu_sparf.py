@@ -737,6 +737,13 @@ def test_sparf_scores_that_are_not_numbers_stay_inside_their_head(monkeypatch, s
         assert torch.equal(alpha[b, h].view(torch.int32), clean_alpha[b, h].view(torch.int32)), (b, h)
 
 
+@pytest.mark.parametrize("seq_len,k", [(3000, 200), (20000, 1200)])
+def test_sparf_paged_pool_with_k_and_v_of_a_page_adjacent(seq_len, k):
+    wl = W.Workload("sparf_kv_adjacent", 2, 3, 3, 128, seq_len, seq_len_min=seq_len // 2, paged=True,
+                    kv_adjacent=True, seed=914)
+    sparf_step(wl, 16, k, 16, torch.float16, kt_page=256, fused_append=True)
+
+
 def test_sparf_is_deterministic():
     wl = W.Workload("sparf_det", 2, 4, 4, 128, 3000, seed=406)
     case, desc, aux, kt, vsum, _ = setup(wl)
