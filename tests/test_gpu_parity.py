@@ -423,11 +423,11 @@ def test_fused_append_edge_lengths():
 
 
 # ------------------------------------------------------------------ bulk KV write (prefill side)
-@pytest.mark.parametrize("paged", [False, True])
+@pytest.mark.parametrize("paged", [False, True, "adjacent"])
 @pytest.mark.parametrize("head_dim", [64, 128])
 def test_kv_write_bit_exact_against_the_oracle(paged, head_dim):
     from oracle import decode_attention as oracle
-    wl = W.Workload("kvw", 5, 3, 3, head_dim, 200, paged=paged, seed=501)
+    wl = W.Workload("kvw", 5, 3, 3, head_dim, 200, paged=bool(paged), kv_adjacent=paged == "adjacent", seed=501)
     case = W.make_case(wl, DEV, poison=False)
     g = torch.Generator().manual_seed(7)
     N = 150
