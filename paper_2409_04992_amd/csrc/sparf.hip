@@ -36,8 +36,9 @@
 //   sparf_build_kernel,   build the component-major K copy and the running sum of V
 //   sparf_vsum_kernel     from an existing cache (prefill side).
 //   sparf_append_kernel   kv_append plus the new column entry and sum update (the
-//                         one-launch kernel does this itself when asked to and
-//                         every KV head has a single query head).
+//                         one-launch kernel and sparf_logits_kernel do this
+//                         themselves when asked to and every KV head has a single
+//                         query head).
 #include <stdlib.h>
 
 #include <atomic>
