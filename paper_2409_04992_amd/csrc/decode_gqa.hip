@@ -1,5 +1,6 @@
 // Split pass of decode attention for grouped queries on the matrix cores
-// (head_dim 64 or 128, 2..16 query heads per KV head).
+// (head_dim 64 or 128; up to 16 query heads of a KV head per block, a larger group
+// takes one block per 16 of its heads).
 //
 // Paper: Sec. II-A/II-B give the operation; the paper's engine runs one query
 // head per K/V stream.  With G query heads sharing a KV head every fp16 loaded
