@@ -502,6 +502,30 @@ def test_drawn_configurations(cfg):
     full_check(wl, out_dtype=torch.float32 if f32 else torch.float16, fused=fused)
 
 
+def _drawn_wide(n, seed):
+    """Drawn over more of the argument space: groups beyond 16, page sizes, both pool
+    layouts, split lengths forced through the environment."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(n):
+        out.append(dict(i=i, D=int(rng.choice([64, 128])), G=int(rng.choice([1, 2, 5, 8, 16, 17, 24, 33, 48])),
+                        Hkv=int(rng.choice([1, 2, 3])), S=int(rng.integers(0, int(rng.choice([700, 3000, 9000])))),
+                        Bn=int(rng.integers(1, 5)), paged=bool(rng.integers(0, 2)), page=int(rng.choice([16, 32, 64])),
+                        adjacent=bool(rng.integers(0, 2)), f32=bool(rng.integers(0, 2)), fused=bool(rng.integers(0, 2)),
+                        chunk=int(rng.choice([0, 0, 128, 384, 1152]))))
+    return out
+
+
+@pytest.mark.parametrize("cfg", _drawn_wide(30, 20241127), ids=lambda c: "cfg%d" % c["i"])
+def test_drawn_configurations_wide(monkeypatch, cfg):
+    if cfg["chunk"]:
+        monkeypatch.setenv("INSTATTN_CHUNK", str(cfg["chunk"]))
+    wl = W.Workload("wide%d" % cfg["i"], cfg["Bn"], cfg["G"] * cfg["Hkv"], cfg["Hkv"], cfg["D"], cfg["S"],
+                    seq_len_min=cfg["S"] // 3, paged=cfg["paged"], page_size=cfg["page"],
+                    kv_adjacent=cfg["paged"] and cfg["adjacent"], seed=900 + cfg["i"])
+    full_check(wl, out_dtype=torch.float32 if cfg["f32"] else torch.float16, fused=cfg["fused"])
+
+
 @pytest.mark.parametrize("cfg", _drawn_configs(12, 20240919), ids=lambda c: "cfg%d" % c[0])
 def test_drawn_configurations_with_rotated_walks(monkeypatch, cfg):
     """INSTATTN_ROTATE=1: every unit starts at a tile of its own and wraps round (the
