@@ -1,20 +1,32 @@
 #!/usr/bin/env python3
 """Decode-attention benchmark on one MI355X.
 
-A step is one pass of the whole hot path for one layer's batch: the new token's
-k, v are appended to the cache and the query attends over it (split pass + LSE
-merge where the plan splits), through the C ABI (instattn_append_decode, or the
-two separate calls with --two-calls), with every input already resident in HBM.  The workload is the 13B-shaped MHA layer (batch 16,
-40 heads of 128, 4096 cached positions, fp16).  Steps rotate over several distinct
-layer caches so that no step starts with its KV in the last-level cache.
+A step is one pass of the whole hot path over one batch: for every layer of the
+workload the new token's k, v are appended to the cache and the query attends over
+it (split pass + LSE merge where the plan splits), through the C ABI
+(instattn_append_decode, or the two separate calls with --two-calls), with every
+input already resident in HBM.  Steps rotate over several distinct layer caches so
+that no step starts with its KV in the last-level cache.
 
-Prints ONE JSON line: whole-job KV GB/s (algorithmic K+V bytes / wall time of the
-timed steps), the roofline of the split-pass kernel measured live with HIP events,
-and the CPU oracle timed on the host cores as a baseline.
+With no --workload the ONE JSON line it prints has the largest single-GPU
+configuration as its headline (gqa70b_16k: 80 layers, 172 GB of KV resident, a step
+walks all 80) and carries the other timed configurations under "per_config"
+(mha13b_4k, mha13b_32k, ragged_paged; same fields) and the SparF path (Algorithm 1)
+at 1/8 of the dense bytes on those three shapes under "sparf".  --workload NAME times
+that configuration alone (the form the rocprofv3 summaries under profiles/ are made
+with).  --steps / --warmup apply to the headline; the per_config and sparf entries
+use fixed counts of their own, stated in each entry.
+
+Fields: whole-job KV GB/s (algorithmic K+V bytes / wall time of the timed steps),
+the roofline of the split-pass kernel timed live with HIP events on the launch
+stream (the split pass of the fused call the step makes), HBM traffic per launch
+as read from the matching rocprofv3 summary under profiles/, and the CPU oracle
+timed on the host cores as a baseline.
 """
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -22,15 +34,12 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
-# HBM bytes per launch of the split-pass kernel from rocprofv3 --pmc FETCH_SIZE and
-# WRITE_SIZE runs of this script, scaled by what the same counters read for the
-# 256 MiB copy kernel (FETCH_SIZE x 2.000, WRITE_SIZE x 1.000); see profiles/.
-MEASURED_TRAFFIC_BYTES = {"mha13b_4k": 1343993230, "mha13b_32k": 5374823655, "ragged_paged": 11332819755,
-                          "gqa70b_16k": 2151831655}
-# The same for all launches of a SparF step (fetched + written), keyed by workload and r,k,l.
-SPARF_MEASURED_TRAFFIC_BYTES = {("mha13b_4k", "16,256,16"): 172801109 + 4116672,
-                                ("mha13b_32k", "16,2048,16"): 820750144 + 48992272,
-                                ("ragged_paged", "16,1024,16"): 2077144320 + 24337384}
+HEADLINE = "gqa70b_16k"
+# name -> (steps, warmup, resident layer caches) of the per_config entries
+PER_CONFIG = {"mha13b_4k": (400, 40, 8), "mha13b_32k": (200, 20, 3), "ragged_paged": (100, 10, 2)}
+# name -> ("r,k,l", steps, warmup) of the sparf entries: r = d_h/8 columns, k = L/16 rows, i.e. 1/8 of the dense bytes
+SPARF = {"mha13b_4k": ("16,256,16", 300, 30), "mha13b_32k": ("16,2048,16", 200, 20),
+         "ragged_paged": ("16,1024,16", 100, 10)}
 
 
 def parse():
@@ -38,11 +47,14 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="mha13b_4k",
-                    help="one of the named configurations, or custom:{json fields of Workload} for sweeps")
-    ap.add_argument("--layers-resident", type=int, default=8,
-                    help="distinct layer caches the steps rotate over")
+    ap.add_argument("--workload", default=None,
+                    help="time this configuration alone: one of the named ones, or custom:{json fields of "
+                         "Workload} for sweeps (default: headline %s plus per_config and sparf entries)" % HEADLINE)
+    ap.add_argument("--layers-resident", type=int, default=None,
+                    help="distinct layer caches the steps rotate over (single-layer workloads)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="default run without the per_config and sparf entries")
     ap.add_argument("--kt-page", type=int, default=None,
                     help="with --sparf: positions per page of the component-major K copy "
                          "(0: contiguous; default 256 for a paged workload, else 0)")
@@ -62,6 +74,33 @@ def parse():
     return ap.parse_args()
 
 
+# ----------------------------------------------------------------------------- profiles/
+def profile_traffic(kernel, workload):
+    """HBM bytes per launch of `kernel` on `workload` from the rocprofv3 summary under
+    profiles/ named for that kernel and workload (FETCH_SIZE and WRITE_SIZE runs scaled by
+    what the same counters read for the 256 MiB copy kernel; the summary states the
+    factors), or None when there is no such summary."""
+    path = os.path.join(ROOT, "profiles", "%s__%s.txt" % (kernel, workload))
+    if not os.path.exists(path):
+        return None
+    m = re.search(r"total HBM traffic (\d+) B", open(path).read())
+    return int(m.group(1)) if m else None
+
+
+def sparf_profile_traffic(workload, rkl):
+    """The same for all launches of a SparF step (fetched + written), from the summary
+    profiles/sparf_step__<workload>.txt made with the same r,k,l."""
+    path = os.path.join(ROOT, "profiles", "sparf_step__%s.txt" % workload)
+    if not os.path.exists(path):
+        return None
+    text = open(path).read()
+    if "--sparf %s " % rkl not in text:
+        return None
+    m = re.search(r"all launches of a step: fetched (\d+) B.*?written (\d+) B", text)
+    return int(m.group(1)) + int(m.group(2)) if m else None
+
+
+# ----------------------------------------------------------------------------- CPU baseline
 def cpu_baseline(cases, kv_bytes_layer, positions_layer):
     """The C oracle as it stands, on the host cores, on a bounded sample: whole
     layers of the same workload (every (sequence, head) pair, or every n-th pair if
@@ -106,33 +145,26 @@ def cpu_baseline(cases, kv_bytes_layer, positions_layer):
     single = kv_bytes_layer * len(range(0, pairs, stride1)) / pairs / dt1 / 1e9
     return {
         "value": kv_bytes_layer * frac / dt / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
-        "sample": "%d (sequence, head) pairs = every %d-th pair of %d layer(s) of the same workload, "
-                  "fp64 C oracle, %d OpenMP threads, %.1f s wall" % (done, stride, layers, cores, dt),
+        "sample": "%d (sequence, head) pairs = every %d-th pair of %d layer(s) of workload %s, "
+                  "fp64 C oracle, %d OpenMP threads, %.1f s wall" % (done, stride, layers, wl.name, cores, dt),
         "single_core_value": single,
         "attended_tokens_per_s": positions_layer * frac / dt,
     }
 
 
-def bench_sparf(args):
-    """SparF step (sparf_append + sparf_decode) against the dense step on the same caches."""
+# ----------------------------------------------------------------------------- SparF
+def sparf_setup(cases, descs, kt_page, kt_capacity=None):
+    """Component-major K copy and V sum for every resident layer (instattn_sparf_build)."""
     import torch
     from paper_2409_04992_amd import binding as B
-    from paper_2409_04992_amd import workloads as W
-    dev = "cuda:0"
-    r, k, l = (int(x) for x in args.sparf.split(","))
-    wl = W.get_workload(args.workload)
-    kt_page = args.kt_page if args.kt_page is not None else (256 if wl.paged else 0)
-    R = max(1, args.layers_resident)
-    steps = args.steps or 200
-    warmup = args.warmup or 20
-    cases = [W.make_case(wl, dev, layer=i) for i in range(R)]
-    descs = [B.kv_desc(c.k_cache, c.v_cache, c.page_table) for c in cases]
-    auxs, keep = [], []
+    wl = cases[0].wl
+    dev = cases[0].q.device
+    auxs = []
     for c, d in zip(cases, descs):
         Bn, Hkv, cap, D = wl.batch, wl.num_kv_heads, c.capacity, wl.head_dim
         vsum = torch.zeros(Bn, Hkv, D, dtype=torch.float32, device=dev)
         if kt_page == 0:
-            kt, kt_table = torch.zeros(Bn, Hkv, D, max(cap, args.kt_capacity or 0), dtype=torch.float16, device=dev), None
+            kt, kt_table = torch.zeros(Bn, Hkv, D, max(cap, kt_capacity or 0), dtype=torch.float16, device=dev), None
         else:
             # the component-major copy in pages of its own size behind a shuffled table
             need = [(int(L) + kt_page - 1) // kt_page for L in c.seq_lens.cpu().tolist()]
@@ -148,7 +180,18 @@ def bench_sparf(args):
         a = B.sparf_aux(kt, vsum, kt_table)
         B.sparf_build(d, a, (c.seq_lens - 1).contiguous(), Hkv, D)
         auxs.append(a)
-        keep.append((kt, vsum, kt_table))
+    return auxs
+
+
+def time_sparf(cases, descs, rkl, steps, warmup, kt_page, two_calls=False, kt_capacity=None):
+    """SparF step (sparf_append_decode) and the dense step on the same caches."""
+    import torch
+    from paper_2409_04992_amd import binding as B
+    wl = cases[0].wl
+    dev = cases[0].q.device
+    r, k, l = (int(x) for x in rkl.split(","))
+    R = len(cases)
+    auxs = sparf_setup(cases, descs, kt_page, kt_capacity)
     max_len = int(cases[0].seq_lens.max().item())
     lens = cases[0].seq_lens.cpu().tolist()
     D, Hq = wl.head_dim, wl.num_q_heads
@@ -161,7 +204,7 @@ def bench_sparf(args):
 
     def sparf_step(i):
         c, d, a = cases[i % R], descs[i % R], auxs[i % R]
-        if args.two_calls:
+        if two_calls:
             B.sparf_append(d, a, c.k_new, c.v_new, c.seq_lens)
             B.sparf_decode(c.q, d, a, c.seq_lens, wl.num_kv_heads, c.scale, r, k, l, out, ws, max_len)
         else:
@@ -183,28 +226,26 @@ def bench_sparf(args):
         return (time.perf_counter() - t0) / steps
 
     t_sparf, t_dense = timed(sparf_step), timed(dense_step)
-    res = {
+    plan = B.sparf_plan(wl.batch, Hq, wl.num_kv_heads, D, max_len, k, with_append=not two_calls)
+    default_page = kt_page == (256 if wl.paged else 0)
+    return {
         "metric": "sparf_decode_attention_dense_equivalent_kv_bandwidth",
         "value": dense_bytes / t_sparf / 1e9, "unit": "GB/s", "n_gpus": 1, "steps": steps,
         "warmup": warmup, "ms_per_step": t_sparf * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f16", "data": "synthetic",
         "config": {"workload": wl.name, "r": r, "k": k, "l": l, "layers_resident": R,
-                   "kt_page": kt_page,
-                   "step": ("sparf_append + sparf_decode" if args.two_calls else "sparf_append_decode") +
+                   "kt_page": kt_page, "launches": plan["launches"],
+                   "step": ("sparf_append + sparf_decode" if two_calls else "sparf_append_decode") +
                            " (column scores, selection, gather attention)"},
         "dense_ms_per_step": t_dense * 1e3, "speedup_over_dense_step": t_dense / t_sparf,
         "bytes_read_algorithm1": sparf_bytes, "bytes_read_dense": dense_bytes,
         "compression": sparf_bytes / dense_bytes, "score_bytes_written_and_read": score_bytes,
-        "achieved_GBps_algorithm1_bytes": sparf_bytes / t_sparf / 1e9,
         # the whole step (one or several launches) against the bytes Algorithm 1 must read
         "roofline": {"bound": "hbm", "achieved": sparf_bytes / t_sparf / 1e9, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": sparf_bytes / t_sparf / 1e9 / HBM_PEAK_GBPS,
-                     "traffic": SPARF_MEASURED_TRAFFIC_BYTES.get((wl.name, args.sparf)) if kt_page == (256 if wl.paged else 0) else None,
+                     "traffic": sparf_profile_traffic(wl.name, rkl) if default_page and not two_calls else None,
                      "kernel": "whole SparF step", "algorithmic_bytes_per_launch": sparf_bytes},
     }
-    if not args.no_cpu_baseline:
-        res["cpu_baseline"] = sparf_cpu_baseline(cases, r, k, l)
-    print(json.dumps(res), flush=True)
 
 
 def sparf_cpu_baseline(cases, r, k, l, budget_s=10.0):
@@ -241,13 +282,30 @@ def sparf_cpu_baseline(cases, r, k, l, budget_s=10.0):
                       "metric" % (done, dt)}
 
 
+def bench_sparf(args):
+    from paper_2409_04992_amd import binding as B
+    from paper_2409_04992_amd import workloads as W
+    wl = W.get_workload(args.workload or "mha13b_4k")
+    kt_page = args.kt_page if args.kt_page is not None else (256 if wl.paged else 0)
+    R = max(1, args.layers_resident or 8)
+    cases = [W.make_case(wl, "cuda:0", layer=i) for i in range(R)]
+    descs = [B.kv_desc(c.k_cache, c.v_cache, c.page_table) for c in cases]
+    res = time_sparf(cases, descs, args.sparf, args.steps or 200, args.warmup or 20, kt_page,
+                     two_calls=args.two_calls, kt_capacity=args.kt_capacity)
+    if not args.no_cpu_baseline:
+        r, k, l = (int(x) for x in args.sparf.split(","))
+        res["cpu_baseline"] = sparf_cpu_baseline(cases, r, k, l)
+    print(json.dumps(res), flush=True)
+
+
+# ----------------------------------------------------------------------------- bulk write
 def bench_kv_write(args):
     """Bulk store of seq_len prompt rows per sequence into the cache (one layer)."""
     import torch
     from paper_2409_04992_amd import binding as B
     from paper_2409_04992_amd import workloads as W
     dev = "cuda:0"
-    wl = W.get_workload(args.workload)
+    wl = W.get_workload(args.workload or "mha13b_4k")
     steps, warmup = args.steps or 50, args.warmup or 5
     R = 3
     cases = [W.make_case(wl, dev, layer=i) for i in range(R)]
@@ -279,30 +337,15 @@ def bench_kv_write(args):
         "bytes_stored": nbytes, "pct_of_hbm_peak": 100.0 * 2 * nbytes / dt / 1e9 / HBM_PEAK_GBPS}), flush=True)
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
-              "use --gpus 1", file=sys.stderr)
-        sys.exit(2)
-    if args.sparf:
-        return bench_sparf(args)
-    if args.kv_write:
-        return bench_kv_write(args)
-
+# ----------------------------------------------------------------------------- dense path
+def time_dense(cases, descs, steps, warmup, two_calls=False, graph=False, probes=True):
+    """Times `steps` steps of the dense path over the given resident layer caches and the
+    split pass on its own; returns the fields of one bench entry."""
     import torch
     from paper_2409_04992_amd import binding as B
-    from paper_2409_04992_amd import workloads as W
-
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    B.lib()                                   # fail loudly if the HIP library is missing
-    dev = "cuda:0"
-    wl = W.get_workload(args.workload)
-    # a multi-layer workload keeps all its layers resident and a step walks them all
-    R = wl.layers if wl.layers > 1 else max(1, args.layers_resident)
-    lps = wl.layers
-    cases = [W.make_case(wl, dev, layer=i) for i in range(R)]
-    descs = [B.kv_desc(c.k_cache, c.v_cache, c.page_table) for c in cases]
+    wl = cases[0].wl
+    dev = cases[0].q.device
+    R, lps = len(cases), wl.layers
     max_len = int(cases[0].seq_lens.max().item())
     ws = B.alloc_workspace(wl.batch, wl.num_q_heads, wl.num_kv_heads, wl.head_dim, max_len, dev)
     out_dtype = torch.float32 if wl.out_dtype == "f32" else torch.float16
@@ -311,69 +354,113 @@ def main():
     kv_bytes = kv_bytes_layer * lps                      # per step
     positions = int(cases[0].seq_lens.sum().item()) * lps
     chunk, splits = B.decode_plan(wl.batch, wl.num_q_heads, wl.num_kv_heads, wl.head_dim, max_len)
+    launches = B.decode_launches(wl.batch, wl.num_q_heads, wl.num_kv_heads, wl.head_dim, max_len, not two_calls)
 
     def step(i):
         for j in range(lps):
             c, d = cases[(i * lps + j) % R], descs[(i * lps + j) % R]
-            if args.two_calls:
+            if two_calls:
                 B.kv_append(d, c.k_new, c.v_new, c.seq_lens)
                 B.decode(c.q, d, c.seq_lens, wl.num_kv_heads, c.scale, out, ws, max_len)
             else:
                 B.append_decode(c.q, c.k_new, c.v_new, d, c.seq_lens, wl.num_kv_heads, c.scale,
                                 out, ws, max_len)
 
-    if args.steps is None:
-        args.steps = 400 if lps == 1 else 20
-    if args.warmup is None:
-        args.warmup = 40 if lps == 1 else 2
-    if args.graph:
+    if graph:
         # One graph holds as many consecutive steps as it takes to come back to the first
         # resident layer cache; the timed loop replays it.
         per_graph = max(1, R // lps)
-        args.steps = max(per_graph, args.steps // per_graph * per_graph)
+        steps = max(per_graph, steps // per_graph * per_graph)
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(side):
             step(0)                                    # warm everything the capture touches
         torch.cuda.current_stream().wait_stream(side)
         torch.cuda.synchronize()
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
             for i in range(per_graph):
                 step(i)
 
         def run(n_steps):
             for _ in range(n_steps // per_graph):
-                graph.replay()
+                g.replay()
     else:
         def run(n_steps):
             for i in range(n_steps):
                 step(i)
-    run(args.warmup if not args.graph else max(1, args.warmup // max(1, R // lps)) * max(1, R // lps))
+    run(warmup if not graph else max(1, warmup // max(1, R // lps)) * max(1, R // lps))
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    run(args.steps)
+    run(steps)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    ms_per_step = wall / args.steps * 1e3
-    value = kv_bytes * args.steps / wall / 1e9
+    ms_per_step = wall / steps * 1e3
+    value = kv_bytes * steps / wall / 1e9
 
-    # Dominant kernel (the split pass) on its own, HIP events on the launch stream.
-    n_k = min(args.steps, 200)
+    # Dominant kernel on its own: the split pass of the call the step makes (the fused
+    # append included; where the plan lists the units first, that small launch too), HIP
+    # events on the launch stream.
+    n_k = min(steps * lps, 200)
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
           for _ in range(n_k)]
     for i in range(n_k):
         c, d = cases[i % R], descs[i % R]
         ev[i][0].record()
-        B.decode_partial(c.q, d, c.seq_lens, wl.num_kv_heads, c.scale, out, ws, max_len)
+        if two_calls:
+            B.decode_partial(c.q, d, c.seq_lens, wl.num_kv_heads, c.scale, out, ws, max_len)
+        else:
+            B.append_decode_partial(c.q, c.k_new, c.v_new, d, c.seq_lens, wl.num_kv_heads, c.scale, out, ws,
+                                    max_len)
         ev[i][1].record()
     torch.cuda.synchronize()
     k_ms = sorted(a.elapsed_time(b) for a, b in ev)
     k_avg_ms = sum(k_ms) / len(k_ms)
     achieved = kv_bytes_layer / (k_avg_ms * 1e-3) / 1e9
+    kernel = "decode_mha_kernel" if wl.group == 1 else "decode_gqa_kernel"
 
-    # Read ceiling: a plain streaming-read kernel over a buffer of the size one launch of
-    # the split pass reads (K and V of a layer), two buffers in turn so that none is warm.
+    res = {
+        "metric": "decode_attention_kv_bandwidth", "value": value, "unit": "GB/s",
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": wl.name, "batch": wl.batch, "num_q_heads": wl.num_q_heads,
+                   "num_kv_heads": wl.num_kv_heads, "head_dim": wl.head_dim,
+                   "seq_len": wl.seq_len, "kv_layout": "paged16" if wl.paged else "contiguous",
+                   "out_dtype": wl.out_dtype, "layers_resident": R, "layers_per_step": lps,
+                   "step": ("kv_append; decode" if two_calls else "append_decode (append fused into "
+                            "the split pass)") + (", LSE merge" if splits > 1 else ", single split: no merge")
+                           + (", unit list built on the device in front" if launches["unit_list"] else "")
+                           + ", for each layer of the step"
+                           + ("; launches replayed from a HIP graph" if graph else ""),
+                   "chunk_tokens": chunk, "num_splits": splits,
+                   "kv_bytes_per_step": kv_bytes},
+        "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBPS,
+        "attended_tokens_per_s": positions * steps / wall,
+        "attended_head_tokens_per_s": positions * wl.num_q_heads * steps / wall,
+        # a step that walks every layer produces one token per sequence (attention only)
+        "decode_tokens_per_s_attention_only": wl.batch * steps / wall if lps > 1 else None,
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS,
+                     "traffic": profile_traffic(kernel, wl.name),
+                     "kernel": kernel + (" (split pass of the step's call" +
+                                         ("; the unit-list launch in front of it is inside the events" if launches["unit_list"] else "") + ")"),
+                     "kernel_ms_avg": k_avg_ms, "kernel_ms_median": k_ms[len(k_ms) // 2],
+                     "kernel_ms_min": k_ms[0], "launches_timed": n_k,
+                     "algorithmic_bytes_per_launch": kv_bytes_layer},
+    }
+    if probes:
+        res.update(time_probes(kv_bytes_layer, dev))
+    return res
+
+
+def time_probes(kv_bytes_layer, dev):
+    """Read ceiling: a plain streaming-read kernel over a buffer of the size one launch of
+    the split pass reads (K and V of a layer), two buffers in turn so that none is warm.
+    And a plain copy of known size (256 MiB read + 256 MiB written per launch): the
+    reference kernel for scaling the hardware traffic counters."""
+    import torch
+    from paper_2409_04992_amd import binding as B
     sink = torch.zeros(4096, dtype=torch.int32, device=dev)
     n_probe = (kv_bytes_layer + 4095) // 4096 * 4096
     flat = [torch.empty(n_probe, dtype=torch.uint8, device=dev).random_(0, 255) for _ in range(2)]
@@ -388,9 +475,6 @@ def main():
     rd_ms = sorted(a.elapsed_time(b) for a, b in rd[2:])
     ceiling = n_probe / (sum(rd_ms) / len(rd_ms) * 1e-3) / 1e9
     del flat
-
-    # A plain copy of known size (256 MiB read + 256 MiB written per launch): the
-    # reference kernel for scaling the hardware traffic counters.
     csrc = torch.empty(256 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
     cdst = torch.empty_like(csrc)
     cp = []
@@ -403,37 +487,65 @@ def main():
     torch.cuda.synchronize()
     cp_ms = sorted(a.elapsed_time(b) for a, b in cp[1:])
     copy_gbps = 2 * csrc.numel() / (sum(cp_ms) / len(cp_ms) * 1e-3) / 1e9
+    return {"read_ceiling_GBps": ceiling, "copy_GBps_read_plus_write": copy_gbps}
 
-    res = {
-        "metric": "decode_attention_kv_bandwidth", "value": value, "unit": "GB/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f16", "data": "synthetic",
-        "config": {"workload": wl.name, "batch": wl.batch, "num_q_heads": wl.num_q_heads,
-                   "num_kv_heads": wl.num_kv_heads, "head_dim": wl.head_dim,
-                   "seq_len": wl.seq_len, "kv_layout": "paged16" if wl.paged else "contiguous",
-                   "out_dtype": wl.out_dtype, "layers_resident": R, "layers_per_step": lps,
-                   "step": ("kv_append; decode" if args.two_calls else "append_decode (append fused into "
-                            "the split pass)") + (", LSE merge" if splits > 1 else ", single split: no merge")
-                           + ", for each layer of the step"
-                           + ("; launches replayed from a HIP graph" if args.graph else ""),
-                   "chunk_tokens": chunk, "num_splits": splits,
-                   "kv_bytes_per_step": kv_bytes},
-        "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBPS,
-        "attended_tokens_per_s": positions * args.steps / wall,
-        "attended_head_tokens_per_s": positions * wl.num_q_heads * args.steps / wall,
-        # a step that walks every layer produces one token per sequence (attention only)
-        "decode_tokens_per_s_attention_only": wl.batch * args.steps / wall if lps > 1 else None,
-        "read_ceiling_GBps": ceiling, "copy_GBps_read_plus_write": copy_gbps,
-        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name),
-                     "kernel": "decode split pass", "kernel_ms_avg": k_avg_ms,
-                     "kernel_ms_min": k_ms[0], "launches_timed": n_k,
-                     "algorithmic_bytes_per_launch": kv_bytes_layer},
-    }
+
+def make_cases(wl, R):
+    from paper_2409_04992_amd import binding as B
+    from paper_2409_04992_amd import workloads as W
+    cases = [W.make_case(wl, "cuda:0", layer=i) for i in range(R)]
+    return cases, [B.kv_desc(c.k_cache, c.v_cache, c.page_table) for c in cases]
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2409_04992_amd import binding as B
+    from paper_2409_04992_amd import workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    B.lib()                                   # fail loudly if the HIP library is missing
+    if args.sparf:
+        return bench_sparf(args)
+    if args.kv_write:
+        return bench_kv_write(args)
+
+    extras = args.workload is None and not args.no_extras and not args.graph and not args.two_calls
+    per_config, sparf = {}, {}
+    if extras:
+        # the smaller configurations first, each freed before the next, then the headline
+        for name, (steps, warmup, R) in PER_CONFIG.items():
+            R_sparf = 8 if name == "mha13b_4k" else R          # the 4K SparF step touches 168 MB: 8 caches keep it out of the last-level cache
+            cases, descs = make_cases(W.get_workload(name), max(R, R_sparf))
+            e = time_dense(cases[:R], descs[:R], steps, warmup, probes=False)
+            per_config[name] = {k: e[k] for k in ("value", "unit", "steps", "warmup", "ms_per_step", "pct_of_hbm_peak",
+                                                  "attended_tokens_per_s", "config", "roofline")}
+            rkl, s_steps, s_warmup = SPARF[name]
+            e = time_sparf(cases, descs, rkl, s_steps, s_warmup, 256 if cases[0].wl.paged else 0)
+            sparf[name] = {k: e[k] for k in ("value", "unit", "steps", "warmup", "ms_per_step", "dense_ms_per_step",
+                                             "speedup_over_dense_step", "bytes_read_algorithm1", "compression",
+                                             "config", "roofline")}
+            del cases, descs, e
+            torch.cuda.empty_cache()
+
+    wl = W.get_workload(args.workload or HEADLINE)
+    # a multi-layer workload keeps all its layers resident and a step walks them all
+    R = wl.layers if wl.layers > 1 else max(1, args.layers_resident or 8)
+    cases, descs = make_cases(wl, R)
+    steps = args.steps if args.steps is not None else (400 if wl.layers == 1 else 20)
+    warmup = args.warmup if args.warmup is not None else (40 if wl.layers == 1 else 2)
+    res = time_dense(cases, descs, steps, warmup, two_calls=args.two_calls, graph=args.graph)
     if not args.no_cpu_baseline:
-        res["cpu_baseline"] = cpu_baseline(cases, kv_bytes_layer, positions // lps)
+        res["cpu_baseline"] = cpu_baseline(cases, cases[0].kv_read_bytes(),
+                                           int(cases[0].seq_lens.sum().item()))
+    if extras:
+        res["per_config"] = per_config
+        res["sparf"] = sparf
     print(json.dumps(res), flush=True)
 
 

@@ -92,6 +92,26 @@ int instattn_version(void);
 const char* instattn_status_string(int status);
 
 /*
+ * Implementation switches, for experiments and tests (host only; no effect on what is
+ * computed beyond the order of floating-point sums).  Each forces one choice the host
+ * otherwise makes from the sizes of a call; value < 0 hands the choice back to the host.
+ * They are process-wide: a call reads them once when it starts; setting one while calls
+ * run in other threads is safe and affects calls that start later.  On first use every
+ * switch takes the integer value of the environment variable of the same name, if set.
+ *   "INSTATTN_CHUNK"                n > 0: positions per unit of the dense split pass (rounded up to 128)
+ *   "INSTATTN_ROTATE"               1: every unit starts its walk over its rows at a tile of its own
+ *   "INSTATTN_COMPACT"              1 / 0: the dense split pass walks a device-built list of the units
+ *                                   that hold rows (one small launch in front), or never does
+ *   "INSTATTN_SPARF_DISTRIBUTED"    1 / 0: SparF selection spread over one block per 8192 scores, or never
+ *   "INSTATTN_SPARF_THREE_LAUNCHES" 1: SparF never takes its one-launch kernel
+ *   "INSTATTN_SPARF_WIDE"           1 / 0: the one-launch kernel's 512/1024-thread forms whenever they fit, or never
+ *   "INSTATTN_SPARF_SPLIT_TAIL"     1: SparF selection and gather never share a launch
+ * An unknown name (or a NULL pointer) is INSTATTN_ERR_INVALID_ARG.  name, value: host.
+ */
+int instattn_set_option(const char* name, int value);
+int instattn_get_option(const char* name, int* value);
+
+/*
  * Store the new token's key and value (Sec. IV-C "Batch Writing Requests").
  * For every sequence b and KV head hk, copies the head_dim fp16 values
  * k_new[b][hk][:] and v_new[b][hk][:] bit for bit into position seq_lens[b] - 1
@@ -125,11 +145,25 @@ int instattn_kv_write(const instattn_kv_desc* kv, const void* k_src, const void*
  * single long sequence still fills the chip; unit i of sequence b covers
  * positions [i*chunk, (i+1)*chunk) cut off at L_b, and num_splits =
  * ceil(max_seq_len / chunk).  The plan depends only on the arguments given here
- * (and the INSTATTN_CHUNK environment variable, which forces chunk_tokens for
- * experiments).  Either output pointer may be NULL.  host pointers.
+ * (and the "INSTATTN_CHUNK" switch, which forces chunk_tokens for experiments).
+ * Either output pointer may be NULL.  host pointers.  More than 65535 splits are
+ * INSTATTN_ERR_UNSUPPORTED (here and in every call that uses the plan).
  */
 int instattn_decode_plan(int batch, int num_q_heads, int num_kv_heads, int head_dim,
                          int max_seq_len, int* chunk_tokens, int* num_splits);
+
+/*
+ * Which kernels instattn_decode (with_append = 0) or instattn_append_decode
+ * (with_append = 1) launches for these sizes: host arithmetic only.  launches: host,
+ * 4 int32, each 0 or 1:
+ *   [0] the store of the new token as a launch of its own (groups of more than 16 query heads)
+ *   [1] the list of the units that hold rows (batches with at least 256 and at most 8192
+ *       (sequence, split) pairs, where a ragged batch leaves much of that grid empty)
+ *   [2] the split pass
+ *   [3] the merge (plans with more than one split)
+ */
+int instattn_decode_launches(int batch, int num_q_heads, int num_kv_heads, int head_dim, int max_seq_len,
+                             int with_append, int32_t* launches);
 
 /* Bytes of device workspace decode needs for these arguments (0 if they are invalid). */
 size_t instattn_decode_workspace_size(int batch, int num_q_heads, int num_kv_heads,
@@ -153,8 +187,10 @@ size_t instattn_decode_workspace_size(int batch, int num_q_heads, int num_kv_hea
  * Supported: head_dim 64 or 128; num_q_heads a multiple of num_kv_heads with a
  * ratio of 1 (vector-ALU path) or more (MFMA group path: up to 16 query heads of a
  * group share one pass over their KV head; a larger group, as in multi-query
- * models, takes one pass per 16 of its heads); both layouts; both output types.  Two kernel launches (partial pass, merge); the merge is skipped
- * when the plan has a single split.
+ * models, takes one pass per 16 of its heads); both layouts; both output types.
+ * One to three kernel launches (instattn_decode_launches tells which): the split pass,
+ * the merge unless the plan has a single split, and for batches with many (sequence,
+ * split) pairs a small launch in front that lists the units that hold rows.
  */
 int instattn_decode(const void* q, const instattn_kv_desc* kv, const int32_t* seq_lens,
                     int batch, int num_q_heads, int num_kv_heads, int head_dim, float scale,
@@ -183,12 +219,19 @@ int instattn_append_decode(const void* q, const void* k_new, const void* v_new,
  * leaving a normalised partial output row and its log-sum-exp in the workspace
  * (when the plan has one split it writes out/lse directly).  decode_merge
  * combines the units of each (b, h) by their log-sum-exp weights into out/lse;
- * with a single split it launches nothing.
+ * with a single split it launches nothing.  append_decode_partial is the split pass of
+ * instattn_append_decode: it stores the new token as well (calling it twice with the same
+ * arguments stores the same bits twice).
  */
 int instattn_decode_partial(const void* q, const instattn_kv_desc* kv, const int32_t* seq_lens,
                             int batch, int num_q_heads, int num_kv_heads, int head_dim,
                             float scale, void* out, int out_dtype, float* lse, void* workspace,
                             size_t workspace_bytes, int max_seq_len, void* stream);
+int instattn_append_decode_partial(const void* q, const void* k_new, const void* v_new,
+                                   const instattn_kv_desc* kv, const int32_t* seq_lens, int batch,
+                                   int num_q_heads, int num_kv_heads, int head_dim, float scale, void* out,
+                                   int out_dtype, float* lse, void* workspace, size_t workspace_bytes,
+                                   int max_seq_len, void* stream);
 int instattn_decode_merge(const int32_t* seq_lens, int batch, int num_q_heads, int num_kv_heads,
                           int head_dim, int capacity, void* out, int out_dtype, float* lse,
                           const void* workspace, size_t workspace_bytes, int max_seq_len,
@@ -275,8 +318,8 @@ int instattn_sparf_append(const instattn_kv_desc* kv, const instattn_sparf_aux* 
  * Which kernels instattn_sparf_decode (with_append = 0) or
  * instattn_sparf_append_decode (with_append = 1) launches for these sizes: host
  * arithmetic only, no device access (the choices are the implementation's, not
- * the paper's; they depend on the arguments and on the INSTATTN_SPARF_*
- * environment switches that force a form for tests).  plan: host, 6 int32:
+ * the paper's; they depend on the arguments and on the "INSTATTN_SPARF_*"
+ * switches that force a form for tests).  plan: host, 6 int32:
  *   [0] kernel launches in all
  *   [1] threads per block of the one-launch kernel (256, 512 or 1024), 0 if the
  *       pipeline runs instead

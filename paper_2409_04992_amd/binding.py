@@ -67,6 +67,12 @@ def lib() -> ctypes.CDLL:
         L.instattn_version.argtypes = []
         L.instattn_status_string.restype = ctypes.c_char_p
         L.instattn_status_string.argtypes = [i]
+        L.instattn_set_option.restype = i
+        L.instattn_set_option.argtypes = [ctypes.c_char_p, i]
+        L.instattn_get_option.restype = i
+        L.instattn_get_option.argtypes = [ctypes.c_char_p, ctypes.POINTER(i)]
+        L.instattn_decode_launches.restype = i
+        L.instattn_decode_launches.argtypes = [i, i, i, i, i, i, ctypes.POINTER(ctypes.c_int32)]
         L.instattn_kv_append.restype = i
         L.instattn_kv_append.argtypes = [ctypes.POINTER(KvDesc), vp, vp, vp, i, i, i, vp]
         L.instattn_kv_write.restype = i
@@ -82,6 +88,8 @@ def lib() -> ctypes.CDLL:
         L.instattn_decode_partial.argtypes = decode_args
         L.instattn_append_decode.restype = i
         L.instattn_append_decode.argtypes = [vp, vp, vp] + decode_args[1:]
+        L.instattn_append_decode_partial.restype = i
+        L.instattn_append_decode_partial.argtypes = [vp, vp, vp] + decode_args[1:]
         L.instattn_decode_merge.restype = i
         L.instattn_decode_merge.argtypes = [vp, i, i, i, i, i, vp, i, vp, vp, sz, i, vp]
         pk, pa = ctypes.POINTER(KvDesc), ctypes.POINTER(SparfAux)
@@ -115,6 +123,22 @@ def version() -> int:
 
 def status_string(status: int) -> str:
     return lib().instattn_status_string(int(status)).decode()
+
+
+OPTIONS = ("INSTATTN_CHUNK", "INSTATTN_ROTATE", "INSTATTN_COMPACT", "INSTATTN_SPARF_DISTRIBUTED",
+           "INSTATTN_SPARF_THREE_LAUNCHES", "INSTATTN_SPARF_WIDE", "INSTATTN_SPARF_SPLIT_TAIL")
+
+
+def set_option(name: str, value: Optional[int]) -> None:
+    """Force one of the host's choices (None or a negative value: hand it back)."""
+    _check(lib().instattn_set_option(name.encode(), -1 if value is None else int(value)),
+           "instattn_set_option")
+
+
+def get_option(name: str) -> int:
+    v = ctypes.c_int(0)
+    _check(lib().instattn_get_option(name.encode(), ctypes.byref(v)), "instattn_get_option")
+    return v.value
 
 
 def _check(status: int, where: str) -> None:
@@ -184,6 +208,15 @@ def decode_plan(batch: int, num_q_heads: int, num_kv_heads: int, head_dim: int,
     return chunk.value, splits.value
 
 
+def decode_launches(batch: int, num_q_heads: int, num_kv_heads: int, head_dim: int, max_seq_len: int,
+                    with_append: bool = False) -> dict:
+    """Which kernels a dense decode of these sizes launches (host arithmetic only)."""
+    out = (ctypes.c_int32 * 4)()
+    _check(lib().instattn_decode_launches(batch, num_q_heads, num_kv_heads, head_dim, max_seq_len,
+                                          int(with_append), out), "instattn_decode_launches")
+    return {"append": bool(out[0]), "unit_list": bool(out[1]), "split_pass": bool(out[2]), "merge": bool(out[3])}
+
+
 def decode_workspace_size(batch: int, num_q_heads: int, num_kv_heads: int, head_dim: int,
                           max_seq_len: int) -> int:
     return lib().instattn_decode_workspace_size(batch, num_q_heads, num_kv_heads, head_dim,
@@ -214,6 +247,15 @@ def append_decode(q, k_new, v_new, desc: KvDesc, seq_lens, num_kv_heads: int, sc
                         stream)
     _check(lib().instattn_append_decode(args[0], _p(k_new), _p(v_new), *args[1:]),
            "instattn_append_decode")
+
+
+def append_decode_partial(q, k_new, v_new, desc: KvDesc, seq_lens, num_kv_heads: int, scale: float, out,
+                          workspace, max_seq_len: int, lse=None, stream=None) -> None:
+    assert k_new.is_contiguous() and v_new.is_contiguous() and k_new.dtype == torch.float16
+    args = _decode_args(q, desc, seq_lens, num_kv_heads, scale, out, lse, workspace, max_seq_len,
+                        stream)
+    _check(lib().instattn_append_decode_partial(args[0], _p(k_new), _p(v_new), *args[1:]),
+           "instattn_append_decode_partial")
 
 
 def decode_partial(q, desc: KvDesc, seq_lens, num_kv_heads: int, scale: float, out, workspace,

@@ -5,15 +5,62 @@
 #include <math.h>
 #include <limits.h>
 #include <stdlib.h>
+#include <string.h>
+
+#include <atomic>
+#include <mutex>
 
 #include "common.h"
 #include "host_checks.h"
+#include "options.h"
 
 using namespace instattn;
 
+// ---------------------------------------------------------------------------
+// Implementation switches: process-wide atomics, first filled from the environment.
+namespace instattn {
 namespace {
 
-constexpr int kVersion = 100;          // 0.1.0
+const char* const kOptionNames[kNumOptions] = {
+    "INSTATTN_CHUNK", "INSTATTN_ROTATE", "INSTATTN_SPARF_DISTRIBUTED", "INSTATTN_SPARF_THREE_LAUNCHES",
+    "INSTATTN_SPARF_WIDE", "INSTATTN_SPARF_SPLIT_TAIL", "INSTATTN_COMPACT",
+};
+std::atomic<int> g_options[kNumOptions];
+std::once_flag g_options_once;
+
+void options_from_environment()
+{
+    for (int o = 0; o < kNumOptions; ++o) {
+        const char* e = getenv(kOptionNames[o]);
+        g_options[o].store(e && e[0] ? atoi(e) : -1, std::memory_order_relaxed);
+    }
+}
+
+}  // namespace
+
+Options options_snapshot()
+{
+    std::call_once(g_options_once, options_from_environment);
+    Options s;
+    for (int o = 0; o < kNumOptions; ++o) s.v[o] = g_options[o].load(std::memory_order_relaxed);
+    return s;
+}
+
+const char* option_name(int o) { return o >= 0 && o < kNumOptions ? kOptionNames[o] : nullptr; }
+
+}  // namespace instattn
+
+namespace {
+
+int option_index(const char* name)
+{
+    if (!name) return -1;
+    for (int o = 0; o < kNumOptions; ++o)
+        if (strcmp(name, kOptionNames[o]) == 0) return o;
+    return -1;
+}
+
+constexpr int kVersion = 200;          // 0.2.0
 constexpr int kChunkQuantum = 128;     // every kernel's block tile divides this
 constexpr int kMinChunk = 384;
 // Work units wanted per launch and largest unit, per kernel family.  The
@@ -26,17 +73,23 @@ constexpr int kTargetUnitsMha = 4096, kMaxChunkMha = 1408;
 constexpr int kTargetUnitsGqa = 192, kMaxChunkGqa = 5504;
 constexpr int kSingleSplitStreams = 512, kSingleSplitMaxLen = 8192 + kChunkQuantum;
 constexpr int kResidentUnits = 1280;   // five blocks of the vector-ALU kernel on each of 256 compute units
+// The compacted unit list: (sequence, split) pairs from which on the host expects a ragged
+// batch to be worth one small launch in front, and the most the one block of that launch sorts.
+constexpr int kCompactMinEntries = 256, kCompactMaxEntries = 8192;
 
 struct Plan {
     int chunk;
     int num_splits;
+    int group_blocks;     // MFMA kernel: blocks per KV head and unit (16 query heads each)
+    bool compact;         // the split pass walks a device-built list of the units that hold rows
+    bool rotate;
 };
 
 // Sequence split: units of `chunk` positions, enough of them to fill the chip
 // from host-known sizes alone.  The chunk is an ODD multiple of 128 rows: units
 // that start a large power of two apart walk the same HBM channels in lockstep
 // and lose up to a fifth of the bandwidth (measured), an odd multiple staggers them.
-Plan make_plan(int batch, int num_q_heads, int num_kv_heads, int max_seq_len)
+Plan make_plan(const Options& opt, int batch, int num_q_heads, int num_kv_heads, int max_seq_len)
 {
     const int group = num_q_heads / num_kv_heads;
     // the MFMA path walks a KV head once for its whole query group
@@ -66,14 +119,27 @@ Plan make_plan(int batch, int num_q_heads, int num_kv_heads, int max_seq_len)
         chunk = ((((long)max_seq_len + n - 1) / n + kChunkQuantum - 1) / kChunkQuantum | 1) * kChunkQuantum;
         if (chunk < kMinChunk) chunk = kMinChunk;
     }
-    const char* forced = getenv("INSTATTN_CHUNK");
-    if (forced && atoi(forced) > 0)
-        chunk = ((long)atoi(forced) + kChunkQuantum - 1) / kChunkQuantum * kChunkQuantum;
+    if (opt[kOptChunk] > 0)
+        chunk = ((long)opt[kOptChunk] + kChunkQuantum - 1) / kChunkQuantum * kChunkQuantum;
     const long whole = ((long)max_seq_len + kChunkQuantum - 1) / kChunkQuantum * kChunkQuantum;
     if (chunk > whole) chunk = whole;
     Plan p;
     p.chunk = (int)chunk;
     p.num_splits = (int)((max_seq_len + chunk - 1) / chunk);
+    p.group_blocks = (group + 15) / 16;
+    // Of a ragged batch's (sequence, split) grid a good part holds no rows, and its last
+    // units are as long as its first.  With many such pairs one block first lists the units
+    // that hold rows, the full ones in front and the partly filled ones behind them from
+    // long to short, and the split pass walks that list: no empty blocks, and the launch
+    // ends on its shortest units.  Below kCompactMinEntries pairs the launch in front
+    // (about 3 us) costs more than it brings.
+    const long entries = (long)batch * p.num_splits;
+    const bool can = p.num_splits > 1 && batch > 1 && entries <= kCompactMaxEntries && p.group_blocks == 1;
+    p.compact = can && (opt[kOptCompact] >= 0 ? opt[kOptCompact] == 1 : entries >= kCompactMinEntries);
+    // Streams whose strides walk the HBM channels in step (a contiguous cache of 2064
+    // rows per head does) lose a tenth to a half of the bandwidth; starting every unit
+    // at its own tile undoes most of that and costs about 1 % elsewhere: off by default.
+    p.rotate = opt[kOptRotate] == 1;
     return p;
 }
 
@@ -87,11 +153,34 @@ int check_shape(int batch, int num_q_heads, int num_kv_heads, int head_dim, int 
     return INSTATTN_OK;
 }
 
-size_t workspace_bytes_for(int batch, int num_q_heads, int head_dim, const Plan& p)
+// What the launch grids can hold, known once the plan is: the split index is a grid
+// dimension of its own, and a group of more than 16 query heads runs on a one-dimensional
+// grid of units x blocks per unit.
+int check_plan(const Plan& p, int batch, int num_kv_heads)
 {
-    size_t units = (size_t)batch * num_q_heads * p.num_splits;
-    size_t bytes = units * (size_t)(head_dim + 1) * sizeof(float);
-    return (bytes + 255) / 256 * 256;
+    if (p.num_splits > 65535) return INSTATTN_ERR_UNSUPPORTED;
+    if (p.group_blocks > 1 &&
+        ((int64_t)batch * num_kv_heads * p.num_splits + 8) * p.group_blocks > (int64_t)INT32_MAX)
+        return INSTATTN_ERR_UNSUPPORTED;
+    return INSTATTN_OK;
+}
+
+// The caller's workspace: partial rows, their log-sum-exp, the list of units.
+struct Carve {
+    size_t o_part, lse_part, unit_list, total;
+};
+
+Carve carve(int batch, int num_q_heads, int head_dim, const Plan& p)
+{
+    const size_t units = (size_t)batch * num_q_heads * p.num_splits;
+    const size_t entries = (size_t)batch * p.num_splits;
+    Carve c;
+    c.o_part = 0;
+    c.lse_part = c.o_part + units * (size_t)head_dim * sizeof(float);
+    c.unit_list = (c.lse_part + units * sizeof(float) + 255) / 256 * 256;
+    // room for the list whenever the plan could use it, so that the size does not depend on the switches
+    c.total = c.unit_list + (entries <= (size_t)kCompactMaxEntries ? (entries * sizeof(int32_t) + 255) / 256 * 256 : 0);
+    return c;
 }
 
 int check_out(void* out, int out_dtype, const void* workspace, size_t workspace_bytes, size_t need)
@@ -101,6 +190,143 @@ int check_out(void* out, int out_dtype, const void* workspace, size_t workspace_
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < need)
         return INSTATTN_ERR_WORKSPACE;
     return INSTATTN_OK;
+}
+
+// Every host check of a decode, in one place and in front of the first launch; leaves the plan.
+int check_decode(const void* q, const void* k_new, const void* v_new, bool fused,
+                 const instattn_kv_desc* kv, const int32_t* seq_lens, int batch, int num_q_heads,
+                 int num_kv_heads, int head_dim, float scale, void* out, int out_dtype,
+                 const void* workspace, size_t workspace_bytes, int max_seq_len, Plan* plan)
+{
+    int st = check_shape(batch, num_q_heads, num_kv_heads, head_dim, max_seq_len);
+    if (st != INSTATTN_OK) return st;
+    st = check_kv(kv, head_dim);
+    if (st != INSTATTN_OK) return st;
+    if (!q || !aligned16(q) || !seq_lens || !isfinite(scale)) return INSTATTN_ERR_INVALID_ARG;
+    if (max_seq_len > kv->capacity) return INSTATTN_ERR_INVALID_ARG;
+    if (fused && (!k_new || !v_new || !aligned16(k_new) || !aligned16(v_new)))
+        return INSTATTN_ERR_INVALID_ARG;
+    *plan = make_plan(options_snapshot(), batch, num_q_heads, num_kv_heads, max_seq_len);
+    st = check_plan(*plan, batch, num_kv_heads);
+    if (st != INSTATTN_OK) return st;
+    return check_out(out, out_dtype, workspace, workspace_bytes, carve(batch, num_q_heads, head_dim, *plan).total);
+}
+
+int status_of(hipError_t e) { return e == hipSuccess ? INSTATTN_OK : INSTATTN_ERR_RUNTIME; }
+
+AppendArgs append_args(const instattn_kv_desc* kv, const void* k_new, const void* v_new,
+                       const int32_t* seq_lens, int batch, int num_kv_heads, int head_dim)
+{
+    const KvView w = make_view(kv);
+    AppendArgs a;
+    a.k = (half_t*)kv->k;
+    a.v = (half_t*)kv->v;
+    a.page_table = w.page_table;
+    a.stride_b = w.stride_b;
+    a.stride_h = w.stride_h;
+    a.stride_t = w.stride_t;
+    a.capacity = w.capacity;
+    a.page_shift = w.page_shift;
+    a.page_mask = w.page_mask;
+    a.max_pages = w.max_pages;
+    a.last_page = w.last_page;
+    a.k_new = (const half_t*)k_new;
+    a.v_new = (const half_t*)v_new;
+    a.seq_lens = seq_lens;
+    a.batch = batch;
+    a.num_kv_heads = num_kv_heads;
+    a.head_dim = head_dim;
+    return a;
+}
+
+// The split pass of a checked decode (with the store of the new token when k_new is given).
+int enqueue_partial(const Plan& p, const void* q, const void* k_new, const void* v_new,
+                    const instattn_kv_desc* kv, const int32_t* seq_lens, int batch, int num_q_heads,
+                    int num_kv_heads, int head_dim, float scale, void* out, int out_dtype, float* lse,
+                    void* workspace, int max_seq_len, hipStream_t stream)
+{
+    // The split pass stores the new token itself where one block per KV head and unit reads
+    // it; a group of more than 16 query heads is shared out over several blocks, so there the
+    // store is a launch of its own in front.
+    if (k_new && p.group_blocks > 1) {
+        if (launch_kv_append(append_args(kv, k_new, v_new, seq_lens, batch, num_kv_heads, head_dim), stream) !=
+            hipSuccess)
+            return INSTATTN_ERR_RUNTIME;
+        k_new = v_new = nullptr;
+    }
+    const Carve c = carve(batch, num_q_heads, head_dim, p);
+    DecodeArgs a;
+    a.group_blocks = p.group_blocks;
+    a.units = 0;
+    a.k_new = (const half_t*)k_new;
+    a.v_new = (const half_t*)v_new;
+    a.rotate = p.rotate;
+    a.q = (const half_t*)q;
+    a.kv = make_view(kv);
+    a.seq_lens = seq_lens;
+    a.num_q_heads = num_q_heads;
+    a.num_kv_heads = num_kv_heads;
+    a.chunk = p.chunk;
+    a.num_splits = p.num_splits;
+    a.max_len = max_seq_len;
+    a.scale_log2 = scale * kLog2e;
+    a.o_part = (float*)((char*)workspace + c.o_part);
+    a.lse_part = (float*)((char*)workspace + c.lse_part);
+    a.unit_list = nullptr;
+    a.list_len = 0;
+    a.out = out;
+    a.lse = lse;
+    a.out_f32 = out_dtype == INSTATTN_F32;
+    if (p.compact) {
+        a.unit_list = (int32_t*)((char*)workspace + c.unit_list);
+        a.list_len = batch * p.num_splits;
+        if (launch_list_units(a, batch, stream) != hipSuccess) return INSTATTN_ERR_RUNTIME;
+    }
+    return status_of(num_q_heads == num_kv_heads ? launch_decode_mha(a, batch, head_dim, stream)
+                                                 : launch_decode_gqa(a, batch, head_dim, stream));
+}
+
+// The merge of a checked decode; nothing to do when the split pass wrote out/lse itself.
+int enqueue_merge(const Plan& p, const int32_t* seq_lens, int batch, int num_q_heads, int head_dim,
+                  void* out, int out_dtype, float* lse, const void* workspace, int max_seq_len,
+                  hipStream_t stream)
+{
+    if (p.num_splits == 1) return INSTATTN_OK;
+    const Carve c = carve(batch, num_q_heads, head_dim, p);
+    MergeArgs m;
+    m.seq_lens = seq_lens;
+    m.o_part = (const float*)((const char*)workspace + c.o_part);
+    m.lse_part = (const float*)((const char*)workspace + c.lse_part);
+    m.out = out;
+    m.lse = lse;
+    m.num_q_heads = num_q_heads;
+    m.chunk = p.chunk;
+    m.num_splits = p.num_splits;
+    m.max_len = max_seq_len;
+    m.out_f32 = out_dtype == INSTATTN_F32;
+    return status_of(launch_merge(m, batch, head_dim, stream));
+}
+
+// One call = one set of checks, one plan, then the launches.
+int run_decode(const void* q, const void* k_new, const void* v_new, bool fused, bool partial, bool merge,
+               const instattn_kv_desc* kv, const int32_t* seq_lens, int batch, int num_q_heads,
+               int num_kv_heads, int head_dim, float scale, void* out, int out_dtype, float* lse,
+               void* workspace, size_t workspace_bytes, int max_seq_len, void* stream)
+{
+    Plan p;
+    int st = check_decode(q, k_new, v_new, fused, kv, seq_lens, batch, num_q_heads, num_kv_heads, head_dim,
+                          scale, out, out_dtype, workspace, workspace_bytes, max_seq_len, &p);
+    if (st != INSTATTN_OK) return st;
+    if (partial) {
+        st = enqueue_partial(p, q, fused ? k_new : nullptr, fused ? v_new : nullptr, kv, seq_lens, batch,
+                             num_q_heads, num_kv_heads, head_dim, scale, out, out_dtype, lse, workspace,
+                             max_seq_len, (hipStream_t)stream);
+        if (st != INSTATTN_OK) return st;
+    }
+    if (merge)
+        st = enqueue_merge(p, seq_lens, batch, num_q_heads, head_dim, out, out_dtype, lse, workspace,
+                           max_seq_len, (hipStream_t)stream);
+    return st;
 }
 
 }  // namespace
@@ -121,6 +347,23 @@ const char* instattn_status_string(int status)
     }
 }
 
+int instattn_set_option(const char* name, int value)
+{
+    const int o = option_index(name);
+    if (o < 0) return INSTATTN_ERR_INVALID_ARG;
+    options_snapshot();                       // the environment first, so that it never overwrites this value
+    g_options[o].store(value < 0 ? -1 : value, std::memory_order_relaxed);
+    return INSTATTN_OK;
+}
+
+int instattn_get_option(const char* name, int* value)
+{
+    const int o = option_index(name);
+    if (o < 0 || !value) return INSTATTN_ERR_INVALID_ARG;
+    *value = options_snapshot()[(Option)o];
+    return INSTATTN_OK;
+}
+
 int instattn_kv_append(const instattn_kv_desc* kv, const void* k_new, const void* v_new,
                        const int32_t* seq_lens, int batch, int num_kv_heads, int head_dim,
                        void* stream)
@@ -130,26 +373,8 @@ int instattn_kv_append(const instattn_kv_desc* kv, const void* k_new, const void
     if (st != INSTATTN_OK) return st;
     if (!k_new || !v_new || !seq_lens || !aligned16(k_new) || !aligned16(v_new))
         return INSTATTN_ERR_INVALID_ARG;
-    const KvView w = make_view(kv);
-    AppendArgs a;
-    a.k = (half_t*)kv->k;
-    a.v = (half_t*)kv->v;
-    a.page_table = w.page_table;
-    a.stride_b = w.stride_b;
-    a.stride_h = w.stride_h;
-    a.stride_t = w.stride_t;
-    a.capacity = w.capacity;
-    a.page_shift = w.page_shift;
-    a.page_mask = w.page_mask;
-    a.max_pages = w.max_pages;
-    a.last_page = w.last_page;
-    a.k_new = (const half_t*)k_new;
-    a.v_new = (const half_t*)v_new;
-    a.seq_lens = seq_lens;
-    a.batch = batch;
-    a.num_kv_heads = num_kv_heads;
-    a.head_dim = head_dim;
-    return launch_kv_append(a, (hipStream_t)stream) == hipSuccess ? INSTATTN_OK : INSTATTN_ERR_RUNTIME;
+    return status_of(launch_kv_append(append_args(kv, k_new, v_new, seq_lens, batch, num_kv_heads, head_dim),
+                                      (hipStream_t)stream));
 }
 
 int instattn_kv_write(const instattn_kv_desc* kv, const void* k_src, const void* v_src,
@@ -173,7 +398,7 @@ int instattn_kv_write(const instattn_kv_desc* kv, const void* k_src, const void*
     a.num_kv_heads = num_kv_heads;
     a.head_dim = head_dim;
     a.max_new = max_new;
-    return launch_kv_write(a, (hipStream_t)stream) == hipSuccess ? INSTATTN_OK : INSTATTN_ERR_RUNTIME;
+    return status_of(launch_kv_write(a, (hipStream_t)stream));
 }
 
 int instattn_decode_plan(int batch, int num_q_heads, int num_kv_heads, int head_dim,
@@ -181,9 +406,27 @@ int instattn_decode_plan(int batch, int num_q_heads, int num_kv_heads, int head_
 {
     int st = check_shape(batch, num_q_heads, num_kv_heads, head_dim, max_seq_len);
     if (st != INSTATTN_OK) return st;
-    const Plan p = make_plan(batch, num_q_heads, num_kv_heads, max_seq_len);
+    const Plan p = make_plan(options_snapshot(), batch, num_q_heads, num_kv_heads, max_seq_len);
+    st = check_plan(p, batch, num_kv_heads);
+    if (st != INSTATTN_OK) return st;
     if (chunk_tokens) *chunk_tokens = p.chunk;
     if (num_splits) *num_splits = p.num_splits;
+    return INSTATTN_OK;
+}
+
+int instattn_decode_launches(int batch, int num_q_heads, int num_kv_heads, int head_dim, int max_seq_len,
+                             int with_append, int32_t* launches)
+{
+    int st = check_shape(batch, num_q_heads, num_kv_heads, head_dim, max_seq_len);
+    if (st != INSTATTN_OK) return st;
+    if (!launches) return INSTATTN_ERR_INVALID_ARG;
+    const Plan p = make_plan(options_snapshot(), batch, num_q_heads, num_kv_heads, max_seq_len);
+    st = check_plan(p, batch, num_kv_heads);
+    if (st != INSTATTN_OK) return st;
+    launches[0] = with_append && p.group_blocks > 1;   // the store of the new token as a launch of its own
+    launches[1] = p.compact;                           // the list of units
+    launches[2] = 1;                                   // the split pass
+    launches[3] = p.num_splits > 1;                    // the merge
     return INSTATTN_OK;
 }
 
@@ -191,72 +434,9 @@ size_t instattn_decode_workspace_size(int batch, int num_q_heads, int num_kv_hea
                                       int max_seq_len)
 {
     if (check_shape(batch, num_q_heads, num_kv_heads, head_dim, max_seq_len) != INSTATTN_OK) return 0;
-    return workspace_bytes_for(batch, num_q_heads, head_dim,
-                               make_plan(batch, num_q_heads, num_kv_heads, max_seq_len));
-}
-
-static int run_partial(const void* q, const void* k_new, const void* v_new, bool fused,
-                       const instattn_kv_desc* kv, const int32_t* seq_lens,
-                       int batch, int num_q_heads, int num_kv_heads, int head_dim,
-                       float scale, void* out, int out_dtype, float* lse, void* workspace,
-                       size_t workspace_bytes, int max_seq_len, void* stream)
-{
-    int st = check_shape(batch, num_q_heads, num_kv_heads, head_dim, max_seq_len);
-    if (st != INSTATTN_OK) return st;
-    st = check_kv(kv, head_dim);
-    if (st != INSTATTN_OK) return st;
-    if (!q || !aligned16(q) || !seq_lens || !isfinite(scale)) return INSTATTN_ERR_INVALID_ARG;
-    if (max_seq_len > kv->capacity) return INSTATTN_ERR_INVALID_ARG;
-    if (fused && (!k_new || !v_new || !aligned16(k_new) || !aligned16(v_new)))
-        return INSTATTN_ERR_INVALID_ARG;
-    const Plan p = make_plan(batch, num_q_heads, num_kv_heads, max_seq_len);
-    st = check_out(out, out_dtype, workspace, workspace_bytes,
-                   workspace_bytes_for(batch, num_q_heads, head_dim, p));
-    if (st != INSTATTN_OK) return st;
-
-    // The split pass stores the new token itself where one block per KV head and unit reads
-    // it; a group of more than 16 query heads is shared out over several blocks, so there the
-    // store is a launch of its own in front.
-    const int group = num_q_heads / num_kv_heads;
-    if (fused && group > 16) {
-        st = instattn_kv_append(kv, k_new, v_new, seq_lens, batch, num_kv_heads, head_dim, stream);
-        if (st != INSTATTN_OK) return st;
-        fused = false;
-    }
-    DecodeArgs a;
-    a.group_blocks = (group + 15) / 16;
-    a.units = 0;
-    // such a group runs on a one-dimensional grid of units x blocks per unit
-    if (a.group_blocks > 1 &&
-        ((int64_t)batch * num_kv_heads * p.num_splits + 8) * a.group_blocks > (int64_t)INT32_MAX)
-        return INSTATTN_ERR_UNSUPPORTED;
-    a.k_new = fused ? (const half_t*)k_new : nullptr;
-    a.v_new = fused ? (const half_t*)v_new : nullptr;
-    // Streams whose strides walk the HBM channels in step (a contiguous cache of 2064
-    // rows per head does) lose a tenth to a half of the bandwidth; starting every unit
-    // at its own tile undoes most of that and costs about 1 % elsewhere: off by default.
-    {
-        const char* e = getenv("INSTATTN_ROTATE");
-        a.rotate = e && e[0] == '1';
-    }
-    a.q = (const half_t*)q;
-    a.kv = make_view(kv);
-    a.seq_lens = seq_lens;
-    a.num_q_heads = num_q_heads;
-    a.num_kv_heads = num_kv_heads;
-    a.chunk = p.chunk;
-    a.num_splits = p.num_splits;
-    a.max_len = max_seq_len;
-    a.scale_log2 = scale * kLog2e;
-    a.o_part = (float*)workspace;
-    a.lse_part = a.o_part + (size_t)batch * num_q_heads * p.num_splits * head_dim;
-    a.out = out;
-    a.lse = lse;
-    a.out_f32 = out_dtype == INSTATTN_F32;
-    hipError_t e = num_q_heads == num_kv_heads
-                       ? launch_decode_mha(a, batch, head_dim, (hipStream_t)stream)
-                       : launch_decode_gqa(a, batch, head_dim, (hipStream_t)stream);
-    return e == hipSuccess ? INSTATTN_OK : INSTATTN_ERR_RUNTIME;
+    const Plan p = make_plan(options_snapshot(), batch, num_q_heads, num_kv_heads, max_seq_len);
+    if (check_plan(p, batch, num_kv_heads) != INSTATTN_OK) return 0;
+    return carve(batch, num_q_heads, head_dim, p).total;
 }
 
 int instattn_decode_partial(const void* q, const instattn_kv_desc* kv, const int32_t* seq_lens,
@@ -264,9 +444,18 @@ int instattn_decode_partial(const void* q, const instattn_kv_desc* kv, const int
                             float scale, void* out, int out_dtype, float* lse, void* workspace,
                             size_t workspace_bytes, int max_seq_len, void* stream)
 {
-    return run_partial(q, nullptr, nullptr, false, kv, seq_lens, batch, num_q_heads, num_kv_heads,
-                       head_dim, scale, out, out_dtype, lse, workspace, workspace_bytes, max_seq_len,
-                       stream);
+    return run_decode(q, nullptr, nullptr, false, true, false, kv, seq_lens, batch, num_q_heads, num_kv_heads,
+                      head_dim, scale, out, out_dtype, lse, workspace, workspace_bytes, max_seq_len, stream);
+}
+
+int instattn_append_decode_partial(const void* q, const void* k_new, const void* v_new,
+                                   const instattn_kv_desc* kv, const int32_t* seq_lens, int batch,
+                                   int num_q_heads, int num_kv_heads, int head_dim, float scale, void* out,
+                                   int out_dtype, float* lse, void* workspace, size_t workspace_bytes,
+                                   int max_seq_len, void* stream)
+{
+    return run_decode(q, k_new, v_new, true, true, false, kv, seq_lens, batch, num_q_heads, num_kv_heads,
+                      head_dim, scale, out, out_dtype, lse, workspace, workspace_bytes, max_seq_len, stream);
 }
 
 int instattn_append_decode(const void* q, const void* k_new, const void* v_new,
@@ -275,13 +464,8 @@ int instattn_append_decode(const void* q, const void* k_new, const void* v_new,
                            int out_dtype, float* lse, void* workspace, size_t workspace_bytes,
                            int max_seq_len, void* stream)
 {
-    int st = run_partial(q, k_new, v_new, true, kv, seq_lens, batch, num_q_heads, num_kv_heads,
-                         head_dim, scale, out, out_dtype, lse, workspace, workspace_bytes,
-                         max_seq_len, stream);
-    if (st != INSTATTN_OK) return st;
-    return instattn_decode_merge(seq_lens, batch, num_q_heads, num_kv_heads, head_dim,
-                                 kv->capacity, out, out_dtype, lse, workspace, workspace_bytes,
-                                 max_seq_len, stream);
+    return run_decode(q, k_new, v_new, true, true, true, kv, seq_lens, batch, num_q_heads, num_kv_heads,
+                      head_dim, scale, out, out_dtype, lse, workspace, workspace_bytes, max_seq_len, stream);
 }
 
 int instattn_decode_merge(const int32_t* seq_lens, int batch, int num_q_heads, int num_kv_heads,
@@ -292,25 +476,13 @@ int instattn_decode_merge(const int32_t* seq_lens, int batch, int num_q_heads, i
     int st = check_shape(batch, num_q_heads, num_kv_heads, head_dim, max_seq_len);
     if (st != INSTATTN_OK) return st;
     if (!seq_lens || capacity <= 0 || max_seq_len > capacity) return INSTATTN_ERR_INVALID_ARG;
-    const Plan p = make_plan(batch, num_q_heads, num_kv_heads, max_seq_len);
-    st = check_out(out, out_dtype, workspace, workspace_bytes,
-                   workspace_bytes_for(batch, num_q_heads, head_dim, p));
+    const Plan p = make_plan(options_snapshot(), batch, num_q_heads, num_kv_heads, max_seq_len);
+    st = check_plan(p, batch, num_kv_heads);
     if (st != INSTATTN_OK) return st;
-    if (p.num_splits == 1) return INSTATTN_OK;   // the split pass already wrote out/lse
-
-    MergeArgs m;
-    m.seq_lens = seq_lens;
-    m.o_part = (const float*)workspace;
-    m.lse_part = m.o_part + (size_t)batch * num_q_heads * p.num_splits * head_dim;
-    m.out = out;
-    m.lse = lse;
-    m.num_q_heads = num_q_heads;
-    m.chunk = p.chunk;
-    m.num_splits = p.num_splits;
-    m.max_len = max_seq_len;
-    m.out_f32 = out_dtype == INSTATTN_F32;
-    return launch_merge(m, batch, head_dim, (hipStream_t)stream) == hipSuccess ? INSTATTN_OK
-                                                                                : INSTATTN_ERR_RUNTIME;
+    st = check_out(out, out_dtype, workspace, workspace_bytes, carve(batch, num_q_heads, head_dim, p).total);
+    if (st != INSTATTN_OK) return st;
+    return enqueue_merge(p, seq_lens, batch, num_q_heads, head_dim, out, out_dtype, lse, workspace, max_seq_len,
+                         (hipStream_t)stream);
 }
 
 int instattn_decode(const void* q, const instattn_kv_desc* kv, const int32_t* seq_lens, int batch,
@@ -318,28 +490,21 @@ int instattn_decode(const void* q, const instattn_kv_desc* kv, const int32_t* se
                     int out_dtype, float* lse, void* workspace, size_t workspace_bytes,
                     int max_seq_len, void* stream)
 {
-    int st = instattn_decode_partial(q, kv, seq_lens, batch, num_q_heads, num_kv_heads, head_dim,
-                                     scale, out, out_dtype, lse, workspace, workspace_bytes,
-                                     max_seq_len, stream);
-    if (st != INSTATTN_OK) return st;
-    return instattn_decode_merge(seq_lens, batch, num_q_heads, num_kv_heads, head_dim,
-                                 kv->capacity, out, out_dtype, lse, workspace, workspace_bytes,
-                                 max_seq_len, stream);
+    return run_decode(q, nullptr, nullptr, false, true, true, kv, seq_lens, batch, num_q_heads, num_kv_heads,
+                      head_dim, scale, out, out_dtype, lse, workspace, workspace_bytes, max_seq_len, stream);
 }
 
 int instattn_probe_read(const void* src, size_t bytes, void* sink, void* stream)
 {
     if (!src || !sink || bytes == 0 || bytes % 16 || !aligned16(src)) return INSTATTN_ERR_INVALID_ARG;
-    return launch_probe_read(src, bytes, sink, (hipStream_t)stream) == hipSuccess ? INSTATTN_OK
-                                                                                    : INSTATTN_ERR_RUNTIME;
+    return status_of(launch_probe_read(src, bytes, sink, (hipStream_t)stream));
 }
 
 int instattn_probe_copy(const void* src, void* dst, size_t bytes, void* stream)
 {
     if (!src || !dst || bytes == 0 || bytes % 16 || !aligned16(src) || !aligned16(dst))
         return INSTATTN_ERR_INVALID_ARG;
-    return launch_probe_copy(src, dst, bytes, (hipStream_t)stream) == hipSuccess ? INSTATTN_OK
-                                                                                  : INSTATTN_ERR_RUNTIME;
+    return status_of(launch_probe_copy(src, dst, bytes, (hipStream_t)stream));
 }
 
 }  // extern "C"

@@ -5,6 +5,7 @@
 #include <stdlib.h>
 
 #include "host_checks.h"
+#include "options.h"
 #include "sparf.h"
 
 using namespace instattn;
@@ -31,6 +32,7 @@ struct Carve {
 Carve carve(int batch, int num_q_heads, int head_dim, int max_seq_len, int k)
 {
     Carve c;
+    if (k > max_seq_len) k = max_seq_len;       // no head keeps more rows than it has
     c.nchunk = (max_seq_len + kSparfChunk - 1) / kSparfChunk;
     c.lpad = c.nchunk * kSparfChunk;
     c.nstat = c.lpad / kSparfStatRun;
@@ -77,7 +79,8 @@ struct SparfPlan {
     int launches;
 };
 
-SparfPlan plan_sparf(int batch, int num_q_heads, int num_kv_heads, int max_seq_len, int k, bool append)
+SparfPlan plan_sparf(const Options& opt, int batch, int num_q_heads, int num_kv_heads, int max_seq_len, int k,
+                     bool append)
 {
     SparfPlan p = {};
     const int64_t heads = (int64_t)batch * num_q_heads;
@@ -91,8 +94,8 @@ SparfPlan plan_sparf(int batch, int num_q_heads, int num_kv_heads, int max_seq_l
     {
         const double one_block = max_seq_len / 1100.0 * (double)((heads + 255) / 256);
         const double spread = (24.0 + 0.015 * (double)heads * nchunk) * (heads <= 512 ? 1.0 : 1.3);
-        const char* e = getenv("INSTATTN_SPARF_DISTRIBUTED");
-        p.distributed = e ? (e[0] == '1') : (max_seq_len > 2 * kSparfChunk && spread < one_block);
+        const int forced = opt[kOptSparfDistributed];
+        p.distributed = forced >= 0 ? forced == 1 : (max_seq_len > 2 * kSparfChunk && spread < one_block);
     }
     // Slices of a head's kept rows for the attend kernel: enough blocks to fill the
     // chip when there are few heads, none smaller than 256 rows.
@@ -104,14 +107,12 @@ SparfPlan plan_sparf(int batch, int num_q_heads, int num_kv_heads, int max_seq_l
         p.nslices = ns;
         p.slice_rows = ((kept + ns - 1) / ns + 15) / 16 * 16;
     }
-    const char* force3 = getenv("INSTATTN_SPARF_THREE_LAUNCHES");
     // Rows behind the 256-thread form's limit take the one-launch kernel's 512-thread form
     // (up to 18432 positions; up to 36864 one of 1024 threads) when there are heads enough
     // for one block each.  Measured at 16K rows: 160 heads 52 us against the pipeline's 63,
     // 120 heads 48 against 55, 80 heads 46 against 48, 40 heads 44 against 40.
     // INSTATTN_SPARF_WIDE forces either way.
-    const char* wide_env = getenv("INSTATTN_SPARF_WIDE");
-    const bool force_wide = wide_env && wide_env[0] == '1', forbid_wide = wide_env && wide_env[0] == '0';
+    const bool force_wide = opt[kOptSparfWide] == 1, forbid_wide = opt[kOptSparfWide] == 0;
     p.fused_threads = 0;
     if (max_seq_len <= kSparfFusedMaxLen) p.fused_threads = 256;
     else if (max_seq_len <= kSparfFusedWideMaxLen && !forbid_wide && (force_wide || heads >= 80)) p.fused_threads = 512;
@@ -120,7 +121,7 @@ SparfPlan plan_sparf(int batch, int num_q_heads, int num_kv_heads, int max_seq_l
         p.fused_threads = 1024;   // one block per compute unit: pays when the heads fit in one round of those
                                   // (measured at 32K rows: 160 heads 94 us against the pipeline's 108;
                                   // 320 and 640 heads level; 40 heads 74 against 56)
-    if (force3 && force3[0] == '1') p.fused_threads = 0;
+    if (opt[kOptSparfThreeLaunches] == 1) p.fused_threads = 0;
     p.one_launch = p.fused_threads != 0;
     // The decode's first launch (the one-launch kernel, or the pipeline's score pass) stores
     // the new token itself when one block is the only reader of what it stores during that
@@ -128,9 +129,8 @@ SparfPlan plan_sparf(int batch, int num_q_heads, int num_kv_heads, int max_seq_l
     // its own.
     p.append_fused = append && num_q_heads == num_kv_heads;
     // One block per head and no slices: that block also gathers the rows it kept.
-    const char* split = getenv("INSTATTN_SPARF_SPLIT_TAIL");
     p.fused_tail = !p.one_launch && !p.distributed && p.nslices == 1 && max_seq_len < kSparfTailMaxLen &&
-                   !(split && split[0] == '1');
+                   opt[kOptSparfSplitTail] != 1;
     p.launches = (append && !p.append_fused) ? 1 : 0;
     if (p.one_launch) p.launches += 1;
     else if (p.fused_tail) p.launches += 2;
@@ -245,7 +245,7 @@ int instattn_sparf_plan(int batch, int num_q_heads, int num_kv_heads, int head_d
         return INSTATTN_ERR_INVALID_ARG;
     if (max_seq_len > kSparfMaxSeqLen) return INSTATTN_ERR_UNSUPPORTED;
     if (head_dim != 64 && head_dim != 128) return head_dim > 0 ? INSTATTN_ERR_UNSUPPORTED : INSTATTN_ERR_INVALID_ARG;
-    const SparfPlan p = plan_sparf(batch, num_q_heads, num_kv_heads, max_seq_len, k, with_append != 0);
+    const SparfPlan p = plan_sparf(options_snapshot(), batch, num_q_heads, num_kv_heads, max_seq_len, k, with_append != 0);
     plan[0] = p.launches;
     plan[1] = p.fused_threads;
     plan[2] = p.append_fused;
@@ -298,7 +298,9 @@ int run_sparf_decode(const void* q, const void* k_new, const void* v_new, bool a
     a.max_len = max_seq_len;
     a.scale_log2 = scale * kLog2e;
     a.r = r;
-    a.k = k;
+    // kept rows are stored k apart in the caller's sel_rows; the library's own list needs
+    // no more room per head than a row has positions
+    a.k = sel_rows || k < max_seq_len ? k : max_seq_len;
     a.l = l;
     char* ws = (char*)workspace;
     a.logits = (float*)(ws + c.logits);
@@ -318,7 +320,7 @@ int run_sparf_decode(const void* q, const void* k_new, const void* v_new, bool a
     a.nparts = c.nchunk < kSparfHistParts ? c.nchunk : kSparfHistParts;
     a.mass_part = (float*)(ws + c.mass_part);
     a.rowstat = (float*)(ws + c.rowstat);
-    const SparfPlan plan = plan_sparf(batch, num_q_heads, num_kv_heads, max_seq_len, k, append);
+    const SparfPlan plan = plan_sparf(options_snapshot(), batch, num_q_heads, num_kv_heads, max_seq_len, k, append);
     a.distributed = plan.distributed;
     a.nslices = plan.nslices;
     a.slice_rows = plan.slice_rows;

@@ -60,6 +60,11 @@ struct DecodeArgs {
     // query heads (1 for groups of at most 16).
     int32_t group_blocks;
     int32_t units;              // with group_blocks > 1: KV heads x splits x sequences (the grid is one-dimensional then)
+    // Compacted unit list (nullptr: the grid itself spans sequences x splits): entry j is
+    // (sequence << 16 | split) of the j-th unit that holds rows, -1 behind the last one;
+    // list_len = sequences x splits entries, filled by list_units_kernel in front of the pass.
+    int32_t* unit_list;
+    int32_t list_len;
 };
 
 // Arguments of the log-sum-exp merge.
@@ -98,6 +103,7 @@ struct WriteArgs {
 // Launchers (one per kernel family); each returns hipGetLastError() of its launch.
 hipError_t launch_decode_mha(const DecodeArgs& a, int batch, int head_dim, hipStream_t stream);
 hipError_t launch_decode_gqa(const DecodeArgs& a, int batch, int head_dim, hipStream_t stream);
+hipError_t launch_list_units(const DecodeArgs& a, int batch, hipStream_t stream);
 hipError_t launch_merge(const MergeArgs& a, int batch, int head_dim, hipStream_t stream);
 hipError_t launch_kv_append(const AppendArgs& a, hipStream_t stream);
 hipError_t launch_kv_write(const WriteArgs& a, hipStream_t stream);
@@ -107,6 +113,20 @@ hipError_t launch_probe_copy(const void* src, void* dst, size_t bytes, hipStream
 __device__ __forceinline__ int clamp_len(int L, int max_len) {
     L = L < 0 ? 0 : L;
     return L > max_len ? max_len : L;
+}
+
+// Which (sequence, split) a block of the split pass works on: its grid coordinates, or the
+// entry of the compacted unit list its blockIdx.y names.  False: no unit (the list's tail).
+__device__ __forceinline__ bool unit_of_block(const DecodeArgs& a, int& b, int& split) {
+    if (a.unit_list == nullptr) {
+        split = blockIdx.y;
+        b = blockIdx.z;
+        return true;
+    }
+    const int e = a.unit_list[blockIdx.y];
+    b = (int)((uint32_t)e >> 16);
+    split = e & 0xFFFF;
+    return e >= 0;
 }
 
 // A page id as read from a page table: the table lives on the device and cannot be

@@ -33,9 +33,6 @@
 #ifndef INSTATTN_MHA_LDS_PAD
 #define INSTATTN_MHA_LDS_PAD 0   // extra LDS bytes per block (experiments: caps blocks per CU)
 #endif
-#ifndef INSTATTN_MHA_HEAD_FAST
-#define INSTATTN_MHA_HEAD_FAST 1 // 1: blockIdx.x walks heads, blockIdx.y walks splits
-#endif
 
 namespace instattn {
 
@@ -67,11 +64,9 @@ __global__ __launch_bounds__(INSTATTN_MHA_WAVES * 64) void decode_mha_kernel(Dec
     constexpr int TILE = WAVES * WTILE;    // rows per block per iteration
     constexpr int NG = WAVES * RPW;        // independent softmax streams per block
 
-#if INSTATTN_MHA_HEAD_FAST
-    const int split = blockIdx.y, h = blockIdx.x, b = blockIdx.z;
-#else
-    const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-#endif
+    const int h = blockIdx.x;
+    int split, b;
+    if (!unit_of_block(a, b, split)) return;       // block-uniform
     const int G = a.num_q_heads / a.num_kv_heads;
     const int hk = h / G;
     const int L = clamp_len(a.seq_lens[b], a.max_len);
@@ -226,11 +221,9 @@ __global__ __launch_bounds__(INSTATTN_MHA_WAVES * 64) void decode_mha_kernel(Dec
 template <int D>
 static hipError_t launch_mha(const DecodeArgs& a, int batch, hipStream_t stream)
 {
-#if INSTATTN_MHA_HEAD_FAST
-    dim3 grid(a.num_q_heads, a.num_splits, batch);
-#else
-    dim3 grid(a.num_splits, a.num_q_heads, batch);
-#endif
+    // blockIdx.x walks the heads: consecutive blocks go round-robin over the XCDs, so every
+    // XCD gets the same mix of units whatever the sequence lengths are
+    const dim3 grid = a.unit_list ? dim3(a.num_q_heads, a.list_len, 1) : dim3(a.num_q_heads, a.num_splits, batch);
     if (a.kv.page_table)
         hipLaunchKernelGGL((decode_mha_kernel<D, true>), grid, dim3(INSTATTN_MHA_WAVES * 64), 0, stream, a);
     else

@@ -1,8 +1,68 @@
-// Log-sum-exp merge of the split pass's units, the KV append, and two
-// measurement kernels.
+// Log-sum-exp merge of the split pass's units, the list of units of a ragged batch, the
+// KV append, and two measurement kernels.
 #include "common.h"
 
 namespace instattn {
+
+// ---------------------------------------------------------------------------
+// List of the units that hold rows, for the split pass of a ragged batch: of the
+// sequences x splits grid only the pairs with rows, the full units first (in sequence
+// order), behind them the partly filled ones from long to short (in sixteenths of a
+// unit), -1 in the rest of the list.  The launch then has no empty blocks and ends on
+// its shortest units.  One block; wave w places class w in order (ballot + popcount),
+// so the same lengths give the same list.
+constexpr int kListClasses = 18;        // 0: full, 1..16: partly filled, long to short, 17: no rows
+constexpr int kListMaxBatch = 4096;     // sequences whose lengths the block keeps in LDS (at least two splits each)
+
+__global__ __launch_bounds__(1024) void list_units_kernel(DecodeArgs a, int batch)
+{
+    __shared__ int s_len[kListMaxBatch];
+    __shared__ int s_count[kListClasses];
+    __shared__ int s_base[kListClasses + 1];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, E = a.list_len;
+    for (int b = tid; b < batch; b += 1024) s_len[b] = clamp_len(a.seq_lens[b], a.max_len);
+    if (tid < kListClasses) s_count[tid] = 0;
+    __syncthreads();
+    auto klass = [&](int e, int& packed) {
+        const int b = e / a.num_splits, split = e - b * a.num_splits;
+        packed = b << 16 | split;
+        const int rows = min(s_len[b] - split * a.chunk, a.chunk);
+        if (rows <= 0) return kListClasses - 1;
+        if (rows == a.chunk) return 0;
+        return 16 - (int)((int64_t)rows * 16 / a.chunk);
+    };
+    int packed;
+    for (int e = tid; e < E; e += 1024) atomicAdd(&s_count[klass(e, packed)], 1);
+    __syncthreads();
+    if (tid == 0) {
+        int at = 0;
+        for (int c = 0; c < kListClasses; ++c) {
+            s_base[c] = at;
+            at += s_count[c];
+        }
+        s_base[kListClasses] = at;
+    }
+    __syncthreads();
+    for (int cls = wave; cls < kListClasses - 1; cls += 16) {
+        if (s_count[cls] == 0) continue;                        // wave-uniform
+        int pos = s_base[cls];
+        for (int e0 = 0; e0 < E; e0 += 64) {
+            const int e = e0 + lane;
+            const bool mine = e < E && klass(e, packed) == cls;
+            const uint64_t m = __ballot(mine);
+            if (mine) a.unit_list[pos + __popcll(m & ((1ull << lane) - 1))] = packed;
+            pos += __popcll(m);
+        }
+    }
+    for (int e = s_base[kListClasses - 1] + tid; e < E; e += 1024) a.unit_list[e] = -1;
+}
+
+hipError_t launch_list_units(const DecodeArgs& a, int batch, hipStream_t stream)
+{
+    if (batch > kListMaxBatch || a.num_splits < 2 || a.list_len != batch * a.num_splits) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(list_units_kernel, dim3(1), dim3(1024), 0, stream, a, batch);
+    return hipGetLastError();
+}
 
 // One block per (b, h).  Unit i of a row holds the attention over positions
 // [i*chunk, (i+1)*chunk) and 2^lse_i = sum of exp(score) there, so the whole row is

@@ -114,14 +114,20 @@ def draw_seq_lens(wl: Workload, device="cpu") -> torch.Tensor:
 
 
 def make_case(wl: Workload, device="cpu", layer: int = 0, poison: bool = False,
-              capacity: Optional[int] = None) -> Case:
+              capacity: Optional[int] = None, lens=None) -> Case:
     """Draw one layer's inputs.  `poison` fills every cache row at or behind
     position L_b - 1 (stale rows, slack in the last page, spare pages) with NaN so
-    that any read outside the valid range shows in the output."""
+    that any read outside the valid range shows in the output.  `lens` (a list of
+    wl.batch lengths between 0 and wl.seq_len + 1, the appended token counted) takes
+    the place of the drawn lengths; page tables and poison follow it."""
     dev = torch.device(device)
     B, Hq, Hkv, D = wl.batch, wl.num_q_heads, wl.num_kv_heads, wl.head_dim
     g = _gen(dev, wl.seed * 1000 + layer)
-    seq_lens = draw_seq_lens(wl, dev)
+    if lens is None:
+        seq_lens = draw_seq_lens(wl, dev)
+    else:
+        assert len(lens) == B and all(0 <= int(L) <= wl.seq_len + 1 for L in lens)
+        seq_lens = torch.tensor([int(L) for L in lens], dtype=torch.int32, device=dev)
     lens_cpu = seq_lens.cpu()
     q = _randn_f16((B, Hq, D), g, dev)
     k_new = _randn_f16((B, Hkv, D), g, dev)
@@ -143,8 +149,8 @@ def make_case(wl: Workload, device="cpu", layer: int = 0, poison: bool = False,
                     t[:, hk] = (t[:, hk].float() * sigma[hk]).half()
         if poison:
             for b in range(B):
-                k_cache[b, :, int(lens_cpu[b]) - 1:, :] = float("nan")
-                v_cache[b, :, int(lens_cpu[b]) - 1:, :] = float("nan")
+                k_cache[b, :, max(int(lens_cpu[b]) - 1, 0):, :] = float("nan")
+                v_cache[b, :, max(int(lens_cpu[b]) - 1, 0):, :] = float("nan")
         page_table = None
     else:
         ps = wl.page_size
@@ -172,6 +178,8 @@ def make_case(wl: Workload, device="cpu", layer: int = 0, poison: bool = False,
             v_cache[unused] = float("nan")
             for b in range(B):
                 L = int(lens_cpu[b])
+                if L < 1:
+                    continue                                   # no page of its own
                 last = int(table[b, (L - 1) // ps])
                 k_cache[last, :, (L - 1) % ps:, :] = float("nan")
                 v_cache[last, :, (L - 1) % ps:, :] = float("nan")

@@ -152,14 +152,91 @@ def test_plan_rejects_bad_shapes():
         B.decode_plan(1, 4, 3, 64, 100)
 
 
-def test_forced_chunk_env(monkeypatch):
-    monkeypatch.setenv("INSTATTN_CHUNK", "512")
+def test_forced_chunk_env(options):
+    options.setenv("INSTATTN_CHUNK", "512")
     assert B.decode_plan(16, 40, 40, 128, 4097) == (512, 9)
-    monkeypatch.setenv("INSTATTN_CHUNK", "500")      # rounded up to the tile quantum
+    options.setenv("INSTATTN_CHUNK", "500")      # rounded up to the tile quantum
     assert B.decode_plan(16, 40, 40, 128, 4097) == (512, 9)
-    monkeypatch.delenv("INSTATTN_CHUNK")
+    options.delenv("INSTATTN_CHUNK")
     assert B.decode_plan(16, 40, 40, 128, 4097) == (2176, 2)      # 640 streams in two halves
     assert B.decode_plan(32, 40, 40, 128, 4097) == (4224, 1)      # 1280 streams fill the chip: one unit each
+
+
+def test_switches_are_set_and_read_back(options):
+    for name in B.OPTIONS:
+        assert B.get_option(name) == -1
+        B.set_option(name, 1)
+        assert B.get_option(name) == 1
+        B.set_option(name, -7)                      # any negative value hands the choice back
+        assert B.get_option(name) == -1
+    L = B.lib()
+    assert L.instattn_set_option(b"INSTATTN_NO_SUCH_SWITCH", 1) == B.ERR_INVALID_ARG
+    assert L.instattn_set_option(None, 1) == B.ERR_INVALID_ARG
+    assert L.instattn_get_option(b"INSTATTN_CHUNK", None) == B.ERR_INVALID_ARG
+
+
+def test_switches_start_from_the_environment():
+    """Read once per process: a child that finds INSTATTN_CHUNK in its environment plans with it,
+    and a later change of the variable inside that process changes nothing."""
+    import subprocess
+    import sys
+    code = ("import os, sys; sys.path.insert(0, %r); from paper_2409_04992_amd import binding as B; "
+            "a = B.decode_plan(16, 40, 40, 128, 4097); os.environ['INSTATTN_CHUNK'] = '1024'; "
+            "print(a, B.decode_plan(16, 40, 40, 128, 4097), B.get_option('INSTATTN_CHUNK'))" % ROOT)
+    env = dict(os.environ, INSTATTN_CHUNK="512")
+    out = subprocess.run([sys.executable, "-c", code], check=True, capture_output=True, text=True, env=env).stdout
+    assert out.strip() == "(512, 9) (512, 9) 512"
+
+
+def test_decode_launches(options):
+    # the four timed shapes: only the ragged batch (64 x 12 pairs) lists its units first
+    assert B.decode_launches(16, 40, 40, 128, 4097, True) == \
+        {"append": False, "unit_list": False, "split_pass": True, "merge": True}
+    assert not B.decode_launches(8, 40, 40, 128, 32769, True)["unit_list"]       # 8 x 24 pairs
+    assert B.decode_launches(64, 40, 40, 128, 16385, True)["unit_list"]          # 64 x 12 pairs
+    assert not B.decode_launches(32, 64, 8, 128, 16385, True)["unit_list"]       # 32 x 3 pairs
+    assert B.decode_launches(32, 40, 40, 128, 4097) == \
+        {"append": False, "unit_list": False, "split_pass": True, "merge": False}  # whole sequences as units
+    # a group of more than 16 query heads: the append is a launch of its own, and no list
+    assert B.decode_launches(64, 48, 1, 128, 16385, True)["append"]
+    assert not B.decode_launches(64, 48, 1, 128, 16385, False)["append"]
+    options.setenv("INSTATTN_COMPACT", 1)
+    assert B.decode_launches(8, 40, 40, 128, 32769)["unit_list"]
+    assert not B.decode_launches(32, 40, 40, 128, 4097)["unit_list"]             # one split: nothing to list
+    assert not B.decode_launches(1, 40, 40, 128, 131072)["unit_list"]            # one sequence is never ragged
+    assert not B.decode_launches(64, 48, 1, 128, 16385)["unit_list"]
+    options.setenv("INSTATTN_COMPACT", 0)
+    assert not B.decode_launches(64, 40, 40, 128, 16385)["unit_list"]
+    # the workspace has room for the list whatever the switch says
+    sizes = set()
+    for v in (None, 0, 1):
+        options.setenv("INSTATTN_COMPACT", -1 if v is None else v)
+        sizes.add(B.decode_workspace_size(64, 40, 40, 128, 16385))
+    assert len(sizes) == 1 and sizes.pop() >= 64 * 40 * 12 * 129 * 4 + 64 * 12 * 4
+
+
+def test_limits_of_the_launch_grids_are_checked_before_anything_is_launched(options):
+    """More splits than a grid dimension holds, or more blocks than a one-dimensional grid:
+    unsupported, from the plan call and from the decode calls alike, and in front of the
+    separate append launch of a large group (on a box without a GPU a launch would come
+    back as a runtime error instead)."""
+    options.setenv("INSTATTN_CHUNK", 128)
+    long_len = 128 * 65536
+    assert B.lib().instattn_decode_plan(1, 8, 8, 128, long_len, None, None) == B.ERR_UNSUPPORTED
+    assert B.decode_workspace_size(1, 8, 8, 128, long_len) == 0
+    big = desc(capacity=long_len, stride_h=long_len * 128, stride_b=8 * long_len * 128)
+    assert decode_status(d=big, batch=1, hq=8, hkv=8, max_len=long_len) == B.ERR_UNSUPPORTED
+    assert B.decode_plan(1, 8, 8, 128, 128 * 65535) == (128, 65535)
+    options.delenv("INSTATTN_CHUNK")
+    # 65535 sequences x 1927 KV heads x 6 splits x 3 blocks per unit do not fit an int32
+    shape = dict(batch=65535, hq=1927 * 34, hkv=1927, max_len=27521)
+    assert B.lib().instattn_decode_plan(65535, 1927 * 34, 1927, 128, 27521, None, None) == B.ERR_UNSUPPORTED
+    assert decode_status(desc(capacity=27600), ws_bytes=1 << 50, **shape) == B.ERR_UNSUPPORTED
+    L = B.lib()
+    d = desc(capacity=27600)
+    st = L.instattn_append_decode(FAKE, FAKE, FAKE, ctypes.byref(d), FAKE, 65535, 1927 * 34, 1927, 128, 0.088,
+                                  FAKE, B.F16, None, FAKE & ~255, 1 << 50, 27521, None)
+    assert st == B.ERR_UNSUPPORTED
 
 
 # ------------------------------------------------------------------ SparF entry points
@@ -266,6 +343,8 @@ def test_sparf_build_and_append_reject():
                                    None) == B.ERR_INVALID_ARG
     assert B.sparf_workspace_size(16, 40, 128, 4097, 256) >= 16 * 40 * (6144 + 256 + 1) * 4
     assert B.sparf_workspace_size(16, 40, 100, 4097, 256) == 0
+    # a k beyond the row length (every row kept = the dense result) asks for no more room than k = row length
+    assert B.sparf_workspace_size(16, 40, 128, 4097, 1 << 30) == B.sparf_workspace_size(16, 40, 128, 4097, 4097)
 
 
 def test_kv_write_rejects():
@@ -288,10 +367,8 @@ SPARF_ENV = ("INSTATTN_SPARF_THREE_LAUNCHES", "INSTATTN_SPARF_WIDE", "INSTATTN_S
 
 
 @pytest.fixture
-def no_sparf_env(monkeypatch):
-    for name in SPARF_ENV:
-        monkeypatch.delenv(name, raising=False)
-    return monkeypatch
+def no_sparf_env(options):
+    return options
 
 
 def test_sparf_plan_of_the_measured_shapes(no_sparf_env):

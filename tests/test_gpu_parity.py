@@ -63,44 +63,29 @@ def sampled_check(wl, pairs, poison, layer=0, fused=False):
 
 
 @pytest.mark.parametrize("fused", [False, True])
-def test_config3_mha13b_32k_full_size_sampled(fused):
-    wl = W.WORKLOADS["mha13b_32k"]
-    pairs = [(0, 0), (0, 39), (3, 17), (7, 39), (5, 1), (2, 20)]
-    case, out, _ = sampled_check(wl, pairs, poison=True, fused=fused)
-    # append landed: row L-1 of sampled heads equals the new k, v bit for bit
-    L = int(case.seq_lens[0])
-    assert torch.equal(case.k_cache[:, :, L - 1].view(torch.int16), case.k_new.view(torch.int16))
-    assert torch.equal(case.v_cache[:, :, L - 1].view(torch.int16), case.v_new.view(torch.int16))
+def test_config3_mha13b_32k_full_size(fused):
+    """8 x 40 heads x 32K at full size (5.4 GB of KV): every output row and every byte of
+    the caches against the oracle, which works on host copies taken before the step."""
+    full_check(W.WORKLOADS["mha13b_32k"], fused=fused)
 
 
 @pytest.mark.parametrize("fused", [False, True])
-def test_config4_ragged_paged_full_size_sampled(fused):
+def test_config4_ragged_paged_full_size(fused):
+    """The ragged paged batch at full size (11.4 GB of KV in 16-token pages behind a
+    shuffled table), in the launch configuration the bench times (the split pass walks the
+    device-built list of units): every output row, every byte of both pools."""
     wl = W.WORKLOADS["ragged_paged"]
     lens = W.draw_seq_lens(wl)
-    order = torch.argsort(lens)
-    bs = [int(order[0]), int(order[-1]), int(order[len(order) // 2]), 0, 63]
-    pairs = [(b, h) for b in bs for h in (0, 39)] + [(11, 7), (42, 23)]
-    case, out, _ = sampled_check(wl, pairs, poison=True, fused=fused)
     assert lens.min() >= 1025 and lens.max() <= 16385 and len(set(lens.tolist())) > 32
-    # appended rows sit behind the page table
-    for b in bs:
-        L = int(case.seq_lens[b])
-        page = int(case.page_table[b, (L - 1) // 16])
-        assert torch.equal(case.k_cache[page, :, (L - 1) % 16].view(torch.int16),
-                           case.k_new[b].view(torch.int16))
-        assert torch.equal(case.v_cache[page, :, (L - 1) % 16].view(torch.int16),
-                           case.v_new[b].view(torch.int16))
+    assert B.decode_launches(wl.batch, wl.num_q_heads, wl.num_kv_heads, wl.head_dim, int(lens.max()), fused)["unit_list"]
+    full_check(wl, fused=fused)
 
 
 @pytest.mark.parametrize("fused", [False, True])
-def test_config5_gqa_layer_full_shape_sampled(fused):
-    """One layer of the 80-layer GQA step at its real shape (2.1 GB of KV)."""
+def test_config5_gqa_layer_full_shape(fused):
+    """One layer of the 80-layer GQA step at its real shape (2.1 GB of KV): whole tensors."""
     wl = dataclasses.replace(W.WORKLOADS["gqa70b_16k"], layers=1)
-    pairs = [(0, 0), (0, 7), (0, 8), (13, 31), (31, 63), (20, 40)]
-    case, out, _ = sampled_check(wl, pairs, poison=True, layer=3, fused=fused)
-    L = int(case.seq_lens[0])
-    assert torch.equal(case.k_cache[:, :, L - 1].view(torch.int16), case.k_new.view(torch.int16))
-    assert torch.equal(case.v_cache[:, :, L - 1].view(torch.int16), case.v_new.view(torch.int16))
+    full_check(wl, fused=fused)
 
 
 def test_config5_all_80_layers_resident():
@@ -305,11 +290,11 @@ def test_strided_cache_views():
 
 
 @pytest.mark.parametrize("chunk", [128, 256, 384, 1024, 100000])
-def test_result_does_not_depend_on_the_split(monkeypatch, chunk):
+def test_result_does_not_depend_on_the_split(options, chunk):
     wl = small("mha13b_4k", batch=2, num_q_heads=4, num_kv_heads=4, seq_len=2500)
     case = W.make_case(wl, DEV)
     want_out, want_lse, _, _ = H.oracle_step(case)
-    monkeypatch.setenv("INSTATTN_CHUNK", str(chunk))
+    options.setenv("INSTATTN_CHUNK", str(chunk))
     assert B.decode_plan(2, 4, 4, 128, 2501)[0] == min((chunk + 127) // 128 * 128, 2560)
     out, lse = H.gpu_step(case, out_dtype=torch.float32)
     H.assert_close(out, lse, want_out, want_lse, "chunk %d" % chunk)
@@ -328,6 +313,69 @@ def test_deterministic_and_heads_independent():
                                wl=dataclasses.replace(wl, num_q_heads=4, num_kv_heads=4))
     c, _ = H.gpu_step(half, append=False)
     assert (a[:, 4:].float() - c.float()).abs().max() <= 1e-3
+
+
+def test_head_sharded_equals_unsharded_bit_for_bit_under_one_plan(options):
+    """Head-level sharding (Sec. IV-D "Scale To CSD Array"): with the same unit length on
+    both sides a shard's rows are the unsharded rows bit for bit, for both kernels."""
+    options.setenv("INSTATTN_CHUNK", 384)
+    for hq, hkv in ((8, 8), (16, 4)):
+        wl = small("mha13b_4k", batch=3, num_q_heads=hq, num_kv_heads=hkv, seq_len=1500, seq_len_min=200)
+        case = W.make_case(wl, DEV)
+        assert B.decode_plan(3, hq, hkv, 128, 1501) == B.decode_plan(3, hq // 2, hkv // 2, 128, 1501) == (384, 4)
+        a, la = H.gpu_step(case)
+        half = dataclasses.replace(case, q=case.q[:, hq // 2:].contiguous(), k_cache=case.k_cache[:, hkv // 2:],
+                                   v_cache=case.v_cache[:, hkv // 2:], k_new=case.k_new[:, hkv // 2:].contiguous(),
+                                   v_new=case.v_new[:, hkv // 2:].contiguous(),
+                                   wl=dataclasses.replace(wl, num_q_heads=hq // 2, num_kv_heads=hkv // 2))
+        c, lc = H.gpu_step(half, append=False)
+        assert torch.equal(a[:, hq // 2:], c) and torch.equal(la[:, hq // 2:], lc)
+
+
+@pytest.mark.parametrize("shape", ["mha_paged", "mha_contiguous", "gqa_paged", "gqa_d64"])
+def test_compacted_unit_list_equals_the_grid_bit_for_bit(options, shape):
+    """A ragged batch through the device-built list of units and through the plain
+    (sequence, split) grid: same plan, same arithmetic per unit, so the same bits - and
+    both agree with the oracle.  Lengths include empty sequences, full units, single rows
+    behind a unit boundary and the longest length the cache holds."""
+    hq, hkv, dim, paged = {"mha_paged": (5, 5, 128, True), "mha_contiguous": (3, 3, 128, False),
+                           "gqa_paged": (8, 2, 128, True), "gqa_d64": (6, 3, 64, False)}[shape]
+    wl = small("ragged_paged", batch=9, num_q_heads=hq, num_kv_heads=hkv, head_dim=dim, seq_len=1700,
+               seq_len_min=100, paged=paged)
+    lens = [0, 384, 385, 1, 1701, 768, 1152, 1153, 700]
+    options.setenv("INSTATTN_CHUNK", 384)
+    res = []
+    for compact in (0, 1):
+        options.setenv("INSTATTN_COMPACT", compact)
+        assert B.decode_launches(9, hq, hkv, dim, 1701)["unit_list"] == bool(compact)
+        for fused in (False, True):
+            case = W.make_case(wl, DEV, poison=True, lens=lens)
+            want_out, want_lse, want_k, want_v = H.oracle_step(case)
+            out, lse = H.gpu_step(case, fused=fused, out_dtype=torch.float32, max_seq_len=1701)
+            H.assert_close(out, lse, want_out, want_lse, shape)
+            assert np.array_equal(H.host(case.k_cache).view(np.uint16), want_k.view(np.uint16))
+            assert np.array_equal(H.host(case.v_cache).view(np.uint16), want_v.view(np.uint16))
+            res.append((out, lse))
+    for out, lse in res[1:]:
+        assert torch.equal(out, res[0][0]) and torch.equal(lse, res[0][1])
+
+
+def test_compacted_unit_list_with_a_bound_below_the_lengths(options):
+    """max_seq_len below some lengths: those sequences are cut off there, the new token is
+    still stored at its own position (inside the capacity), and the list holds exactly the
+    units of the cut-off lengths."""
+    wl = small("ragged_paged", batch=6, num_q_heads=4, num_kv_heads=4, seq_len=1500, seq_len_min=300, paged=True)
+    options.setenv("INSTATTN_CHUNK", 256)
+    outs = []
+    for compact in (0, 1):
+        options.setenv("INSTATTN_COMPACT", compact)
+        case = W.make_case(wl, DEV)
+        k_before = case.k_cache.clone()
+        out, lse = H.gpu_step(case, fused=True, max_seq_len=900)
+        outs.append((out, lse, case.k_cache.clone()))
+        assert not torch.equal(case.k_cache, k_before)
+    assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
+    assert torch.equal(outs[0][2].view(torch.int16), outs[1][2].view(torch.int16))
 
 
 def test_dominant_score_large_values_fp16_rounding():
@@ -517,9 +565,9 @@ def _drawn_wide(n, seed):
 
 
 @pytest.mark.parametrize("cfg", _drawn_wide(30, 20241127), ids=lambda c: "cfg%d" % c["i"])
-def test_drawn_configurations_wide(monkeypatch, cfg):
+def test_drawn_configurations_wide(options, cfg):
     if cfg["chunk"]:
-        monkeypatch.setenv("INSTATTN_CHUNK", str(cfg["chunk"]))
+        options.setenv("INSTATTN_CHUNK", str(cfg["chunk"]))
     wl = W.Workload("wide%d" % cfg["i"], cfg["Bn"], cfg["G"] * cfg["Hkv"], cfg["Hkv"], cfg["D"], cfg["S"],
                     seq_len_min=cfg["S"] // 3, paged=cfg["paged"], page_size=cfg["page"],
                     kv_adjacent=cfg["paged"] and cfg["adjacent"], seed=900 + cfg["i"])
@@ -527,18 +575,18 @@ def test_drawn_configurations_wide(monkeypatch, cfg):
 
 
 @pytest.mark.parametrize("cfg", _drawn_configs(12, 20240919), ids=lambda c: "cfg%d" % c[0])
-def test_drawn_configurations_with_rotated_walks(monkeypatch, cfg):
+def test_drawn_configurations_with_rotated_walks(options, cfg):
     """INSTATTN_ROTATE=1: every unit starts at a tile of its own and wraps round (the
     remedy for cache strides that walk the HBM channels in step); same results."""
-    monkeypatch.setenv("INSTATTN_ROTATE", "1")
+    options.setenv("INSTATTN_ROTATE", "1")
     i, Bn, D, G, Hkv, S, paged, f32, fused = cfg
     wl = W.Workload("rot%d" % i, Bn, G * Hkv, Hkv, D, S, seq_len_min=S // 4, paged=paged, page_size=16,
                     seed=800 + i)
     full_check(wl, out_dtype=torch.float32 if f32 else torch.float16, fused=fused)
 
 
-def test_rotated_walk_on_the_13b_shape(monkeypatch):
-    monkeypatch.setenv("INSTATTN_ROTATE", "1")
+def test_rotated_walk_on_the_13b_shape(options):
+    options.setenv("INSTATTN_ROTATE", "1")
     full_check(W.WORKLOADS["mha13b_4k"], fused=True)
 
 

@@ -186,22 +186,22 @@ def sparf_step(wl, r, k, l, out_dtype=torch.float32, pairs=None, kt_page=None, f
 @pytest.mark.parametrize("r,k,l", [(16, 64, 8), (8, 128, 0), (128, 32, 4), (1, 16, 16), (32, 700, 3)])
 @pytest.mark.parametrize("out_dtype", [torch.float32, torch.float16])
 @pytest.mark.parametrize("three_launches", [False, True])
-def test_sparf_mha_small(monkeypatch, r, k, l, out_dtype, three_launches):
+def test_sparf_mha_small(options, r, k, l, out_dtype, three_launches):
     """Both forms of the path: the one-launch kernel and the three-launch pipeline
     that long rows take (forced here through the environment)."""
     if three_launches:
-        monkeypatch.setenv("INSTATTN_SPARF_THREE_LAUNCHES", "1")
+        options.setenv("INSTATTN_SPARF_THREE_LAUNCHES", "1")
     wl = W.Workload("sparf_mha", 3, 4, 4, 128, 1500, seq_len_min=300, seed=401)
     sparf_step(wl, r, k, l, out_dtype)
 
 
 @pytest.mark.parametrize("kv_paged,kt_page", [(True, 256), (True, 16), (True, None), (False, 64), (True, 8)])
 @pytest.mark.parametrize("three_launches", [False, True])
-def test_sparf_paged_layouts(monkeypatch, kv_paged, kt_page, three_launches):
+def test_sparf_paged_layouts(options, kv_paged, kt_page, three_launches):
     """The cache in 16-row pages and/or the component-major copy in pages of its own
     size, each behind its own shuffled page table, in every combination."""
     if three_launches:
-        monkeypatch.setenv("INSTATTN_SPARF_THREE_LAUNCHES", "1")
+        options.setenv("INSTATTN_SPARF_THREE_LAUNCHES", "1")
     wl = W.Workload("sparf_paged", 3, 4, 2, 128, 1700, seq_len_min=200, paged=kv_paged, page_size=16,
                     seed=410)
     sparf_step(wl, 16, 120, 9, torch.float32, kt_page=kt_page)
@@ -219,12 +219,12 @@ def test_sparf_paged_long_rows():
 
 
 @pytest.mark.parametrize("shape", ["mha", "mha64", "gqa", "paged", "long", "three"])
-def test_sparf_append_decode_in_one_call(monkeypatch, shape):
+def test_sparf_append_decode_in_one_call(options, shape):
     """The fused entry point against the oracle, in every form it takes: the new token
     stored by the one-launch kernel itself (one query head per KV head), or by a launch
     of its own in front (grouped queries, long rows, the three-launch pipeline)."""
     if shape == "three":
-        monkeypatch.setenv("INSTATTN_SPARF_THREE_LAUNCHES", "1")
+        options.setenv("INSTATTN_SPARF_THREE_LAUNCHES", "1")
     wl = {
         "mha": W.Workload("sparf_f1", 3, 4, 4, 128, 1500, seq_len_min=300, seed=420),
         "mha64": W.Workload("sparf_f2", 2, 4, 4, 64, 700, seq_len_min=1, seed=421),
@@ -253,12 +253,12 @@ def test_sparf_append_decode_equals_the_two_calls():
 @pytest.mark.parametrize("seq_len,k", [(20000, 1300), (8192, 100), (32767, 3000), (32768, 600), (40000, 2500),
                                        (65534, 700), (70000, 4400), (9000, 20000)])
 @pytest.mark.parametrize("distributed", ["0", "1"])
-def test_sparf_long_rows_take_the_three_launch_pipeline(monkeypatch, seq_len, k, distributed):
+def test_sparf_long_rows_take_the_three_launch_pipeline(options, seq_len, k, distributed):
     """Rows behind the one-launch limit.  One block per head: the selection keeps the
     scores in registers up to 32768 and up to 65535 positions and passes over the
     workspace beyond.  Distributed: one block per stretch of 8192 scores, three
     launches.  The attend kernel cuts the kept rows of a head into up to 8 slices."""
-    monkeypatch.setenv("INSTATTN_SPARF_DISTRIBUTED", distributed)
+    options.setenv("INSTATTN_SPARF_DISTRIBUTED", distributed)
     wl = W.Workload("sparf_long", 1, 2, 2, 128, seq_len, seed=408)
     sparf_step(wl, 16, k, 32, torch.float16)
 
@@ -267,24 +267,24 @@ def test_sparf_long_rows_take_the_three_launch_pipeline(monkeypatch, seq_len, k,
                                                 (20000, 511, 128), (32767, 500, 64), (40000, 300, 128),
                                                 (65534, 200, 128), (65534, 480, 64)])
 @pytest.mark.parametrize("split_tail", ["0", "1"])
-def test_sparf_long_rows_selected_and_gathered_by_one_block(monkeypatch, seq_len, k, head_dim, split_tail):
+def test_sparf_long_rows_selected_and_gathered_by_one_block(options, seq_len, k, head_dim, split_tail):
     """Few kept rows per head (no slices), one block per head: that block selects and
     then gathers (two launches in all), or, forced here, the selection and the gather
     stay kernels of their own.  Every block size of the selection."""
-    monkeypatch.setenv("INSTATTN_SPARF_DISTRIBUTED", "0")
-    monkeypatch.setenv("INSTATTN_SPARF_SPLIT_TAIL", split_tail)
+    options.setenv("INSTATTN_SPARF_DISTRIBUTED", "0")
+    options.setenv("INSTATTN_SPARF_SPLIT_TAIL", split_tail)
     wl = W.Workload("sparf_tail", 2, 3, 3, head_dim, seq_len, seq_len_min=seq_len // 2, seed=414)
     sparf_step(wl, head_dim // 8, k, 16, torch.float16)
 
 
-def test_sparf_one_block_tail_equals_the_two_kernels(monkeypatch):
+def test_sparf_one_block_tail_equals_the_two_kernels(options):
     wl = W.Workload("sparf_tail_eq", 3, 4, 2, 128, 12000, seq_len_min=0, paged=True, page_size=16, seed=415)
     case, desc, aux, kt, vsum, _ = setup(wl, kt_page=256)
     B.sparf_append(desc, aux, case.k_new, case.v_new, case.seq_lens)
-    monkeypatch.setenv("INSTATTN_SPARF_DISTRIBUTED", "0")
-    monkeypatch.setenv("INSTATTN_SPARF_SPLIT_TAIL", "1")
+    options.setenv("INSTATTN_SPARF_DISTRIBUTED", "0")
+    options.setenv("INSTATTN_SPARF_SPLIT_TAIL", "1")
     a = run_decode(case, desc, aux, 16, 300, 16, torch.float32)
-    monkeypatch.setenv("INSTATTN_SPARF_SPLIT_TAIL", "0")
+    options.setenv("INSTATTN_SPARF_SPLIT_TAIL", "0")
     b = run_decode(case, desc, aux, 16, 300, 16, torch.float32)
     assert torch.equal(a[1], b[1]) and torch.equal(a[2], b[2])       # same kept rows, same alpha
     assert (a[0] - b[0]).abs().max() <= 2e-6
@@ -296,47 +296,47 @@ def test_sparf_one_block_tail_equals_the_two_kernels(monkeypatch):
     (18430, 5000, 64, False, True),
     (18432, 700, 128, False, True), (25000, 26000, 64, True, True), (32768, 2048, 128, False, True),
     (36863, 100, 128, True, False), (36862, 30000, 64, False, True)])
-def test_sparf_one_launch_kernel_of_512_and_1024_threads(monkeypatch, seq_len, k, head_dim, paged, fused):
+def test_sparf_one_launch_kernel_of_512_and_1024_threads(options, seq_len, k, head_dim, paged, fused):
     """Rows between 8193 and 18432 positions in the one-launch kernel's form of 512
     threads, up to 36864 positions in that of 1024 (forced here: with few heads the host
     would pick the pipeline), with and without the append inside it, up to the longest row
     each takes; kept rows beyond the room for row ids in LDS go through in pieces."""
-    monkeypatch.setenv("INSTATTN_SPARF_WIDE", "1")
+    options.setenv("INSTATTN_SPARF_WIDE", "1")
     wl = W.Workload("sparf_wide", 2, 3, 3, head_dim, seq_len, seq_len_min=seq_len - 9000, paged=paged,
                     page_size=16, seed=416)
     sparf_step(wl, head_dim // 8, k, 16, torch.float32, kt_page=256 if paged else None, fused_append=fused)
 
 
-def test_sparf_wide_one_launch_equals_the_pipeline(monkeypatch):
+def test_sparf_wide_one_launch_equals_the_pipeline(options):
     wl = W.Workload("sparf_wide_eq", 2, 4, 2, 128, 15000, seq_len_min=9000, seed=417)
     case, desc, aux, kt, vsum, _ = setup(wl)
     B.sparf_append(desc, aux, case.k_new, case.v_new, case.seq_lens)
-    monkeypatch.setenv("INSTATTN_SPARF_WIDE", "1")
+    options.setenv("INSTATTN_SPARF_WIDE", "1")
     a = run_decode(case, desc, aux, 16, 900, 16, torch.float32)
-    monkeypatch.setenv("INSTATTN_SPARF_WIDE", "0")
+    options.setenv("INSTATTN_SPARF_WIDE", "0")
     b = run_decode(case, desc, aux, 16, 900, 16, torch.float32)
     assert torch.equal(a[1], b[1])                                   # same kept rows
     assert (a[0] - b[0]).abs().max() <= 2e-6 and (a[2] - b[2]).abs().max() <= 1e-6
 
 
 @pytest.mark.parametrize("distributed", ["0", "1"])
-def test_sparf_one_very_long_sequence(monkeypatch, distributed):
+def test_sparf_one_very_long_sequence(options, distributed):
     """A million positions per head, 65536 kept: 128 stretches per head in the
     distributed selection, the pass-over-memory selection in the one-block form, eight
     slices of 8192 kept rows each."""
-    monkeypatch.setenv("INSTATTN_SPARF_DISTRIBUTED", distributed)
+    options.setenv("INSTATTN_SPARF_DISTRIBUTED", distributed)
     wl = W.Workload("sparf_1m", 1, 2, 2, 128, 1 << 20, seed=418)
     sparf_step(wl, 16, 1 << 16, 16, torch.float16)
 
 
 @pytest.mark.parametrize("shape", ["short_mha", "short_gqa_fused"])
-def test_sparf_short_rows_forced_through_the_distributed_selection(monkeypatch, shape):
+def test_sparf_short_rows_forced_through_the_distributed_selection(options, shape):
     """Rows the one-launch kernel would take, sent through the pipeline with the
     selection spread over stretches (one stretch here): every switch combination must
     stay inside the workspace the library asked for (checked behind every decode of
     these tests by a guard band)."""
-    monkeypatch.setenv("INSTATTN_SPARF_THREE_LAUNCHES", "1")
-    monkeypatch.setenv("INSTATTN_SPARF_DISTRIBUTED", "1")
+    options.setenv("INSTATTN_SPARF_THREE_LAUNCHES", "1")
+    options.setenv("INSTATTN_SPARF_DISTRIBUTED", "1")
     if shape == "short_mha":
         wl = W.Workload("sparf_short_dist", 3, 4, 4, 128, 1500, seq_len_min=300, seed=442)
         sparf_step(wl, 16, 100, 7, torch.float32)
@@ -384,16 +384,16 @@ def test_sparf_build_with_and_without_scratch(shape):
             assert np.abs(got - want).max() <= 1e-5 * max(1.0, np.abs(V[b, :, :max(n, 1)]).astype(np.float64).sum(axis=1).max())
 
 
-def test_sparf_distributed_selection_equals_one_block_per_head(monkeypatch):
+def test_sparf_distributed_selection_equals_one_block_per_head(options):
     """Same kept rows bit for bit, alpha and out up to the order of the mass sum; ragged
     lengths so that heads use different numbers of stretches; repeated (the gathered
     members arrive in any order)."""
     wl = W.Workload("sparf_dist", 3, 4, 2, 128, 40000, seq_len_min=8300, paged=True, page_size=16, seed=414)
     case, desc, aux, kt, vsum, _ = setup(wl, kt_page=256)
     B.sparf_append(desc, aux, case.k_new, case.v_new, case.seq_lens)
-    monkeypatch.setenv("INSTATTN_SPARF_DISTRIBUTED", "0")
+    options.setenv("INSTATTN_SPARF_DISTRIBUTED", "0")
     ref = run_decode(case, desc, aux, 16, 3000, 16, torch.float32)
-    monkeypatch.setenv("INSTATTN_SPARF_DISTRIBUTED", "1")
+    options.setenv("INSTATTN_SPARF_DISTRIBUTED", "1")
     first = None
     for rep in range(3):
         got = run_decode(case, desc, aux, 16, 3000, 16, torch.float32)
@@ -404,11 +404,11 @@ def test_sparf_distributed_selection_equals_one_block_per_head(monkeypatch):
 
 
 @pytest.mark.parametrize("distributed", ["0", "1"])
-def test_sparf_long_rows_of_equal_scores(monkeypatch, distributed):
+def test_sparf_long_rows_of_equal_scores(options, distributed):
     """Identical keys on a long row: every score ties, the threshold bin holds the whole
     row (more than the distributed selection ranks directly: it falls back to the block
     of stretch 0).  Kept: the first k - l and the last l positions."""
-    monkeypatch.setenv("INSTATTN_SPARF_DISTRIBUTED", distributed)
+    options.setenv("INSTATTN_SPARF_DISTRIBUTED", distributed)
     wl = W.Workload("sparf_long_ties", 1, 2, 2, 128, 19999, seed=415)
     case, desc, aux, kt, vsum, _ = setup(wl)
     case.k_cache[:] = case.k_cache[:, :, :1]
@@ -422,20 +422,20 @@ def test_sparf_long_rows_of_equal_scores(monkeypatch, distributed):
 
 
 @pytest.mark.parametrize("seq_len,k", [(300_000, 20_000), (524_288, 1000)])
-def test_sparf_distributed_long_member_lists(monkeypatch, seq_len, k):
+def test_sparf_distributed_long_member_lists(options, seq_len, k):
     """Rows so long that the threshold bin holds more scores than go through LDS: the
     list is ranked from the workspace (finer buckets, then the one bucket directly)."""
-    monkeypatch.setenv("INSTATTN_SPARF_DISTRIBUTED", "1")
+    options.setenv("INSTATTN_SPARF_DISTRIBUTED", "1")
     wl = W.Workload("sparf_long_list", 1, 2, 1, 128, seq_len, seed=419)
     sparf_step(wl, 16, k, 16, torch.float32)
 
 
-def test_sparf_distributed_long_list_of_near_ties(monkeypatch):
+def test_sparf_distributed_long_list_of_near_ties(options):
     """A long row whose keys repeat 61 distinct rows: a few dozen distinct scores, each
     thousands of times.  The list of the threshold bin is long and its finer bucket still
     holds more than can be ranked directly: the block of stretch 0 selects the whole row.
     Ties go to the lower position either way."""
-    monkeypatch.setenv("INSTATTN_SPARF_DISTRIBUTED", "1")
+    options.setenv("INSTATTN_SPARF_DISTRIBUTED", "1")
     wl = W.Workload("sparf_near_ties", 1, 2, 2, 128, 280_000, seed=420)
     case, desc, aux, kt, vsum, _ = setup(wl)
     L = int(case.seq_lens[0])
@@ -448,9 +448,9 @@ def test_sparf_distributed_long_list_of_near_ties(monkeypatch):
     check_against_oracle(case, out, sel, alpha, 16, 30_000, 16)
 
 
-def test_sparf_distributed_edge_lengths(monkeypatch):
+def test_sparf_distributed_edge_lengths(options):
     """Lengths around the stretch edges, k below l, k above the length, an empty row."""
-    monkeypatch.setenv("INSTATTN_SPARF_DISTRIBUTED", "1")
+    options.setenv("INSTATTN_SPARF_DISTRIBUTED", "1")
     wl = W.Workload("sparf_dist_edges", 6, 2, 2, 64, 16500, seed=416)
     case, desc, aux, kt, vsum, _ = setup(wl)
     case.seq_lens = torch.tensor([8193, 16384, 16385, 0, 9000, 16500], dtype=torch.int32, device=DEV)
@@ -462,22 +462,22 @@ def test_sparf_distributed_edge_lengths(monkeypatch):
 
 
 @pytest.mark.parametrize("wide", ["0", "1"])
-def test_sparf_long_rows_many_heads_no_slices(monkeypatch, wide):
+def test_sparf_long_rows_many_heads_no_slices(options, wide):
     """1040 heads of up to 9001 positions: the pipeline (score pass, then one block per
     head that selects and gathers), or the one-launch kernel's 512-thread form (the
     host's choice for this shape)."""
-    monkeypatch.setenv("INSTATTN_SPARF_WIDE", wide)
+    options.setenv("INSTATTN_SPARF_WIDE", wide)
     wl = W.Workload("sparf_long_many", 26, 40, 40, 64, 9000, seq_len_min=100, seed=413)
     pairs = [(0, 0), (25, 39), (13, 7), (5, 20)]
     sparf_step(wl, 8, 300, 4, torch.float16, pairs=pairs)
 
 
-def test_sparf_one_launch_and_three_launches_agree(monkeypatch):
+def test_sparf_one_launch_and_three_launches_agree(options):
     wl = W.Workload("sparf_both", 2, 4, 2, 128, 4000, seq_len_min=1000, seed=409)
     case, desc, aux, kt, vsum, _ = setup(wl)
     B.sparf_append(desc, aux, case.k_new, case.v_new, case.seq_lens)
     a = run_decode(case, desc, aux, 16, 250, 16, torch.float32)
-    monkeypatch.setenv("INSTATTN_SPARF_THREE_LAUNCHES", "1")
+    options.setenv("INSTATTN_SPARF_THREE_LAUNCHES", "1")
     b = run_decode(case, desc, aux, 16, 250, 16, torch.float32)
     assert torch.equal(a[1], b[1])                                   # same kept rows
     assert (a[0] - b[0]).abs().max() <= 2e-6 and (a[2] - b[2]).abs().max() <= 1e-6
@@ -519,7 +519,7 @@ def test_sparf_empty_and_mixed_lengths():
     assert torch.equal(out[2].view(torch.int32), case.v_new[2].float().view(torch.int32))   # L = 1
 
 
-def test_sparf_13b_shape_one_eighth(monkeypatch):
+def test_sparf_13b_shape_one_eighth(options):
     """The 13B-shaped layer at the paper's 1/8 compression (r = 16 of 128 columns,
     k = 256 of 4097 rows, 16 most recent kept): sampled heads against the oracle."""
     wl = W.WORKLOADS["mha13b_4k"]
@@ -619,20 +619,20 @@ def _drawn_forms(n, seed):
 
 
 @pytest.mark.parametrize("cfg", _drawn_forms(30, 20240920), ids=lambda c: "cfg%d" % c[0])
-def test_sparf_drawn_configurations_in_forced_forms(monkeypatch, cfg):
+def test_sparf_drawn_configurations_in_forced_forms(options, cfg):
     i, D, G, Hkv, S, paged, kt_page, r, k, l, f16, fused, env = cfg
     for name, value in env.items():
-        monkeypatch.setenv(name, value)
+        options.setenv(name, value)
     wl = W.Workload("sparf_form%d" % i, 2, G * Hkv, Hkv, D, S, seq_len_min=int(S * 0.4), paged=paged,
                     page_size=16, seed=700 + i)
     sparf_step(wl, r, k, l, torch.float16 if f16 else torch.float32, kt_page=kt_page, fused_append=fused)
 
 
-def test_calls_on_two_streams_at_once_do_not_disturb_each_other(monkeypatch):
+def test_calls_on_two_streams_at_once_do_not_disturb_each_other(options):
     """The library keeps no state between calls: a dense decode and a SparF decode of long
     rows (six launches), each on a stream and a workspace of its own, issued alternately so
     that they overlap on the GPU, give the bits they give one after the other."""
-    monkeypatch.setenv("INSTATTN_SPARF_DISTRIBUTED", "1")
+    options.setenv("INSTATTN_SPARF_DISTRIBUTED", "1")
     wl_s = W.Workload("two_streams_sparf", 1, 4, 4, 128, 40000, seed=811)
     wl_d = W.Workload("two_streams_dense", 3, 16, 2, 128, 9000, seq_len_min=3000, seed=812)
     case, desc, aux, _, _, _ = setup(wl_s)
@@ -703,13 +703,13 @@ def test_sparf_page_ids_outside_the_pools_are_pulled_into_them(seq_len, k):
 
 @pytest.mark.parametrize("seq_len,k,distributed", [(3000, 200, None), (20000, 1500, "0"), (20000, 1500, "1"),
                                                    (70000, 3000, "0"), (70000, 3000, "1")])
-def test_sparf_scores_that_are_not_numbers_stay_inside_their_head(monkeypatch, seq_len, k, distributed):
+def test_sparf_scores_that_are_not_numbers_stay_inside_their_head(options, seq_len, k, distributed):
     """NaN and infinities in K, V or q make scores the selection cannot order sensibly.
     Every address that depends on a score is bounded all the same: nothing is written
     outside the outputs (guard band, untouched neighbours), the kept positions of the
     spoilt heads lie in the row, and the other heads give the bits of the clean run."""
     if distributed is not None:
-        monkeypatch.setenv("INSTATTN_SPARF_DISTRIBUTED", distributed)
+        options.setenv("INSTATTN_SPARF_DISTRIBUTED", distributed)
     wl = W.Workload("sparf_nonfinite", 2, 4, 4, 128, seq_len, seq_len_min=seq_len - 100, seed=977)
     res = {}
     for kind in ("clean", "spoilt"):
@@ -773,15 +773,15 @@ def test_sparf_ties_go_to_the_lower_position():
 
 # ------------------------------------------------------------------ HIP graph replay
 @pytest.mark.parametrize("form", ["one_launch", "one_launch_512", "pipeline_tail", "pipeline_distributed"])
-def test_sparf_decode_replayed_from_a_hip_graph(monkeypatch, form):
+def test_sparf_decode_replayed_from_a_hip_graph(options, form):
     """The launches of a SparF decode recorded into a HIP graph, in each form the host can
     pick: every replay — workspace overwritten and unrelated eager work in between —
     gives the oracle's result and bit for bit the eager one (nothing in the path
     allocates, synchronises or depends on what the workspace held before)."""
     seq_len, k = {"one_launch": (3000, 200), "one_launch_512": (12000, 700), "pipeline_tail": (12000, 200),
                   "pipeline_distributed": (20000, 1500)}[form]
-    monkeypatch.setenv("INSTATTN_SPARF_WIDE", "1" if form == "one_launch_512" else "0")
-    monkeypatch.setenv("INSTATTN_SPARF_DISTRIBUTED", "1" if form == "pipeline_distributed" else "0")
+    options.setenv("INSTATTN_SPARF_WIDE", "1" if form == "one_launch_512" else "0")
+    options.setenv("INSTATTN_SPARF_DISTRIBUTED", "1" if form == "pipeline_distributed" else "0")
     wl = W.Workload("sparf_graph", 2, 3, 3, 128, seq_len, seq_len_min=seq_len // 2, paged=True, page_size=16,
                     seed=440)
     case, desc, aux, kt, vsum, _ = setup(wl, kt_page=256)
