@@ -237,6 +237,26 @@ int instattn_decode_merge(const int32_t* seq_lens, int batch, int num_q_heads, i
                           const void* workspace, size_t workspace_bytes, int max_seq_len,
                           void* stream);
 
+/*
+ * instattn_decode for callers that cannot allocate device memory (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): same arguments minus
+ * the workspace, same checks, same kernels and bit for bit the same out/lse.  The
+ * partial rows of the split pass go to a scratch array of INSTATTN_STATIC_SCRATCH_BYTES
+ * that is part of the library's device code: every GPU the library runs on holds its
+ * own copy until the process ends.  The call allocates and frees nothing.  Its first
+ * call on a device looks up that device's copy (make that call before a graph capture).
+ * A shape whose instattn_decode_workspace_size exceeds INSTATTN_STATIC_SCRATCH_BYTES is
+ * rejected with INSTATTN_ERR_WORKSPACE and launches nothing (the five measured
+ * configurations need 0.5 KB to 16 MB).  All calls on one GPU share that GPU's array:
+ * calls that overlap there - on different streams, or from several threads - race;
+ * order them.  Nothing in the array has to start at zero (the merge reads only what
+ * the split pass of the same call wrote), so nothing is cleared.
+ */
+#define INSTATTN_STATIC_SCRATCH_BYTES (32u << 20)
+int instattn_decode_static(const void* q, const instattn_kv_desc* kv, const int32_t* seq_lens,
+                           int batch, int num_q_heads, int num_kv_heads, int head_dim, float scale,
+                           void* out, int out_dtype, float* lse, int max_seq_len, void* stream);
+
 /* ------------------------------------------------------------------------
  * SparF attention (Algorithm 1): decode attention from a fraction of the cache.
  *

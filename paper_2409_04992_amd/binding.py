@@ -90,6 +90,8 @@ def lib() -> ctypes.CDLL:
         L.instattn_append_decode.argtypes = [vp, vp, vp] + decode_args[1:]
         L.instattn_append_decode_partial.restype = i
         L.instattn_append_decode_partial.argtypes = [vp, vp, vp] + decode_args[1:]
+        L.instattn_decode_static.restype = i
+        L.instattn_decode_static.argtypes = [vp, ctypes.POINTER(KvDesc), vp, i, i, i, i, f, vp, i, vp, i, vp]
         L.instattn_decode_merge.restype = i
         L.instattn_decode_merge.argtypes = [vp, i, i, i, i, i, vp, i, vp, vp, sz, i, vp]
         pk, pa = ctypes.POINTER(KvDesc), ctypes.POINTER(SparfAux)
@@ -238,6 +240,16 @@ def decode(q, desc: KvDesc, seq_lens, num_kv_heads: int, scale: float, out, work
            max_seq_len: int, lse=None, stream=None) -> None:
     _check(lib().instattn_decode(*_decode_args(q, desc, seq_lens, num_kv_heads, scale, out, lse,
                                                workspace, max_seq_len, stream)), "instattn_decode")
+
+
+STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def decode_static(q, desc: KvDesc, seq_lens, num_kv_heads: int, scale: float, out, max_seq_len: int,
+                  lse=None, stream=None) -> None:
+    """instattn_decode on the library's own scratch: no workspace argument, nothing allocated."""
+    a = _decode_args(q, desc, seq_lens, num_kv_heads, scale, out, lse, out, max_seq_len, stream)
+    _check(lib().instattn_decode_static(*a[:11], a[13], a[14]), "instattn_decode_static")
 
 
 def append_decode(q, k_new, v_new, desc: KvDesc, seq_lens, num_kv_heads: int, scale: float, out,

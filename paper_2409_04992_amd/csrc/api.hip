@@ -494,6 +494,57 @@ int instattn_decode(const void* q, const instattn_kv_desc* kv, const int32_t* se
                       head_dim, scale, out, out_dtype, lse, workspace, workspace_bytes, max_seq_len, stream);
 }
 
+// ---------------------------------------------------------------------------
+// The entry point that allocates nothing: instattn_decode with the library's own scratch
+// as its workspace.  `scratch` is a host-side stand-in for the device array, not an address
+// a kernel can take; the device address is looked up once per device and kept.
+static __device__ __align__(256) unsigned char scratch[INSTATTN_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices];       // per device: its own copy of the array, at its own address
+std::mutex g_scratch_mutex;
+
+// Address of the current device's copy of `scratch`; nullptr (and *status set) on failure.
+void* scratch_of_current_device(int* status)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        *status = INSTATTN_ERR_RUNTIME;
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) {
+            *status = INSTATTN_ERR_RUNTIME;
+            return nullptr;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
+
+}  // namespace
+
+int instattn_decode_static(const void* q, const instattn_kv_desc* kv, const int32_t* seq_lens, int batch,
+                           int num_q_heads, int num_kv_heads, int head_dim, float scale, void* out,
+                           int out_dtype, float* lse, int max_seq_len, void* stream)
+{
+    // sizes first: a call that does not fit is rejected whatever the device says
+    if (check_shape(batch, num_q_heads, num_kv_heads, head_dim, max_seq_len) == INSTATTN_OK) {
+        const size_t need = instattn_decode_workspace_size(batch, num_q_heads, num_kv_heads, head_dim, max_seq_len);
+        if (need > (size_t)INSTATTN_STATIC_SCRATCH_BYTES) return INSTATTN_ERR_WORKSPACE;
+    }
+    int st = INSTATTN_OK;
+    void* ws = scratch_of_current_device(&st);
+    if (ws == nullptr) return st;
+    return run_decode(q, nullptr, nullptr, false, true, true, kv, seq_lens, batch, num_q_heads, num_kv_heads,
+                      head_dim, scale, out, out_dtype, lse, ws, (size_t)INSTATTN_STATIC_SCRATCH_BYTES, max_seq_len,
+                      stream);
+}
+
 int instattn_probe_read(const void* src, size_t bytes, void* sink, void* stream)
 {
     if (!src || !sink || bytes == 0 || bytes % 16 || !aligned16(src)) return INSTATTN_ERR_INVALID_ARG;
