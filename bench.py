@@ -354,7 +354,8 @@ def time_dense(cases, descs, steps, warmup, two_calls=False, graph=False, probes
     kv_bytes = kv_bytes_layer * lps                      # per step
     positions = int(cases[0].seq_lens.sum().item()) * lps
     chunk, splits = B.decode_plan(wl.batch, wl.num_q_heads, wl.num_kv_heads, wl.head_dim, max_len)
-    launches = B.decode_launches(wl.batch, wl.num_q_heads, wl.num_kv_heads, wl.head_dim, max_len, not two_calls)
+    launches = B.decode_launches(wl.batch, wl.num_q_heads, wl.num_kv_heads, wl.head_dim, max_len, not two_calls,
+                                 paged=wl.paged)
 
     def step(i):
         for j in range(lps):
@@ -516,13 +517,28 @@ def main():
         return bench_kv_write(args)
 
     extras = args.workload is None and not args.no_extras and not args.graph and not args.two_calls
-    per_config, sparf = {}, {}
+    wl = W.get_workload(args.workload or HEADLINE)
+    # a multi-layer workload keeps all its layers resident and a step walks them all
+    R = wl.layers if wl.layers > 1 else max(1, args.layers_resident or 8)
+    # The headline first, into device memory nothing has been freed from yet: caches allocated
+    # behind large frees land on scattered physical pages and read 2-4 % slower (measured on
+    # every shape, also across processes on one box).
+    cases, descs = make_cases(wl, R)
+    steps = args.steps if args.steps is not None else (400 if wl.layers == 1 else 20)
+    warmup = args.warmup if args.warmup is not None else (40 if wl.layers == 1 else 2)
+    res = time_dense(cases, descs, steps, warmup, two_calls=args.two_calls, graph=args.graph)
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(cases, cases[0].kv_read_bytes(),
+                                           int(cases[0].seq_lens.sum().item()))
     if extras:
-        # the smaller configurations first, each freed before the next, then the headline
-        for name, (steps, warmup, R) in PER_CONFIG.items():
-            R_sparf = 8 if name == "mha13b_4k" else R          # the 4K SparF step touches 168 MB: 8 caches keep it out of the last-level cache
-            cases, descs = make_cases(W.get_workload(name), max(R, R_sparf))
-            e = time_dense(cases[:R], descs[:R], steps, warmup, probes=False)
+        del cases, descs
+        torch.cuda.empty_cache()
+        per_config, sparf = {}, {}
+        # the smaller configurations, each freed before the next
+        for name, (c_steps, c_warmup, c_R) in PER_CONFIG.items():
+            R_sparf = 8 if name == "mha13b_4k" else c_R        # the 4K SparF step touches 168 MB: 8 caches keep it out of the last-level cache
+            cases, descs = make_cases(W.get_workload(name), max(c_R, R_sparf))
+            e = time_dense(cases[:c_R], descs[:c_R], c_steps, c_warmup, probes=False)
             per_config[name] = {k: e[k] for k in ("value", "unit", "steps", "warmup", "ms_per_step", "pct_of_hbm_peak",
                                                   "attended_tokens_per_s", "config", "roofline")}
             rkl, s_steps, s_warmup = SPARF[name]
@@ -532,18 +548,6 @@ def main():
                                              "config", "roofline")}
             del cases, descs, e
             torch.cuda.empty_cache()
-
-    wl = W.get_workload(args.workload or HEADLINE)
-    # a multi-layer workload keeps all its layers resident and a step walks them all
-    R = wl.layers if wl.layers > 1 else max(1, args.layers_resident or 8)
-    cases, descs = make_cases(wl, R)
-    steps = args.steps if args.steps is not None else (400 if wl.layers == 1 else 20)
-    warmup = args.warmup if args.warmup is not None else (40 if wl.layers == 1 else 2)
-    res = time_dense(cases, descs, steps, warmup, two_calls=args.two_calls, graph=args.graph)
-    if not args.no_cpu_baseline:
-        res["cpu_baseline"] = cpu_baseline(cases, cases[0].kv_read_bytes(),
-                                           int(cases[0].seq_lens.sum().item()))
-    if extras:
         res["per_config"] = per_config
         res["sparf"] = sparf
     print(json.dumps(res), flush=True)

@@ -101,7 +101,8 @@ const char* instattn_status_string(int status);
  *   "INSTATTN_CHUNK"                n > 0: positions per unit of the dense split pass (rounded up to 128)
  *   "INSTATTN_ROTATE"               1: every unit starts its walk over its rows at a tile of its own
  *   "INSTATTN_COMPACT"              1 / 0: the dense split pass walks a device-built list of the units
- *                                   that hold rows (one small launch in front), or never does
+ *                                   that hold rows (one small launch in front; the host's choice for
+ *                                   large paged caches), or never does
  *   "INSTATTN_SPARF_DISTRIBUTED"    1 / 0: SparF selection spread over one block per 8192 scores, or never
  *   "INSTATTN_SPARF_THREE_LAUNCHES" 1: SparF never takes its one-launch kernel
  *   "INSTATTN_SPARF_WIDE"           1 / 0: the one-launch kernel's 512/1024-thread forms whenever they fit, or never
@@ -154,16 +155,17 @@ int instattn_decode_plan(int batch, int num_q_heads, int num_kv_heads, int head_
 
 /*
  * Which kernels instattn_decode (with_append = 0) or instattn_append_decode
- * (with_append = 1) launches for these sizes: host arithmetic only.  launches: host,
- * 4 int32, each 0 or 1:
+ * (with_append = 1) launches for these sizes on a cache of the given layout
+ * (an instattn_kv_layout): host arithmetic only.  launches: host, 4 int32, each 0 or 1:
  *   [0] the store of the new token as a launch of its own (groups of more than 16 query heads)
- *   [1] the list of the units that hold rows (batches with at least 256 and at most 8192
- *       (sequence, split) pairs, where a ragged batch leaves much of that grid empty)
+ *   [1] the list of the units that hold rows: paged caches with 2 to 4096 sequences, at
+ *       most 8192 (sequence, split) pairs and max_seq_len x KV streams >= 2^21 rows; the
+ *       split pass then walks that list with the blocks of a unit on one XCD
  *   [2] the split pass
  *   [3] the merge (plans with more than one split)
  */
 int instattn_decode_launches(int batch, int num_q_heads, int num_kv_heads, int head_dim, int max_seq_len,
-                             int with_append, int32_t* launches);
+                             int kv_layout, int with_append, int32_t* launches);
 
 /* Bytes of device workspace decode needs for these arguments (0 if they are invalid). */
 size_t instattn_decode_workspace_size(int batch, int num_q_heads, int num_kv_heads,
@@ -189,8 +191,8 @@ size_t instattn_decode_workspace_size(int batch, int num_q_heads, int num_kv_hea
  * group share one pass over their KV head; a larger group, as in multi-query
  * models, takes one pass per 16 of its heads); both layouts; both output types.
  * One to three kernel launches (instattn_decode_launches tells which): the split pass,
- * the merge unless the plan has a single split, and for batches with many (sequence,
- * split) pairs a small launch in front that lists the units that hold rows.
+ * the merge unless the plan has a single split, and for large paged caches a small
+ * launch in front that lists the units that hold rows.
  */
 int instattn_decode(const void* q, const instattn_kv_desc* kv, const int32_t* seq_lens,
                     int batch, int num_q_heads, int num_kv_heads, int head_dim, float scale,
@@ -372,7 +374,7 @@ size_t instattn_sparf_workspace_size(int batch, int num_q_heads, int head_dim, i
  * attention over the kept rows, and a launch that combines the slices when a
  * head's kept rows are cut up.
  * A paged cache is limited to num_pages*page_size < 2^31 rows here, max_seq_len to
- * 2^30 (INSTATTN_ERR_UNSUPPORTED beyond).  max_seq_len must bound every L_b: a longer
+ * 65535 x 8192 (INSTATTN_ERR_UNSUPPORTED beyond).  max_seq_len must bound every L_b: a longer
  * sequence is cut off at max_seq_len as everywhere (memory-safe), but aux.vsum still
  * holds the sum of all its rows, so the mean of V that step 11 blends in is then not
  * the mean of the rows attended.

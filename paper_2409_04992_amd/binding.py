@@ -72,7 +72,7 @@ def lib() -> ctypes.CDLL:
         L.instattn_get_option.restype = i
         L.instattn_get_option.argtypes = [ctypes.c_char_p, ctypes.POINTER(i)]
         L.instattn_decode_launches.restype = i
-        L.instattn_decode_launches.argtypes = [i, i, i, i, i, i, ctypes.POINTER(ctypes.c_int32)]
+        L.instattn_decode_launches.argtypes = [i, i, i, i, i, i, i, ctypes.POINTER(ctypes.c_int32)]
         L.instattn_kv_append.restype = i
         L.instattn_kv_append.argtypes = [ctypes.POINTER(KvDesc), vp, vp, vp, i, i, i, vp]
         L.instattn_kv_write.restype = i
@@ -211,11 +211,12 @@ def decode_plan(batch: int, num_q_heads: int, num_kv_heads: int, head_dim: int,
 
 
 def decode_launches(batch: int, num_q_heads: int, num_kv_heads: int, head_dim: int, max_seq_len: int,
-                    with_append: bool = False) -> dict:
+                    with_append: bool = False, paged: bool = False) -> dict:
     """Which kernels a dense decode of these sizes launches (host arithmetic only)."""
     out = (ctypes.c_int32 * 4)()
     _check(lib().instattn_decode_launches(batch, num_q_heads, num_kv_heads, head_dim, max_seq_len,
-                                          int(with_append), out), "instattn_decode_launches")
+                                          KV_PAGED if paged else KV_CONTIGUOUS, int(with_append), out),
+           "instattn_decode_launches")
     return {"append": bool(out[0]), "unit_list": bool(out[1]), "split_pass": bool(out[2]), "merge": bool(out[3])}
 
 

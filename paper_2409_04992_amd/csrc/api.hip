@@ -63,19 +63,24 @@ int option_index(const char* name)
 constexpr int kVersion = 200;          // 0.2.0
 constexpr int kChunkQuantum = 128;     // every kernel's block tile divides this
 constexpr int kMinChunk = 384;
-// Work units wanted per launch and largest unit, per kernel family.  The
-// vector-ALU kernel runs 5 blocks per CU and is insensitive to the unit size, so
-// units stay small enough to balance ragged batches; the MFMA kernel runs 2
+// Work units wanted per launch and largest unit, per kernel family.  The vector-ALU
+// kernel runs one block per CU with a deep ring of tiles: units of about 3000 rows
+// amortise its prologue and epilogue, and some fourteen rounds of them over the 256
+// compute units still balance (8 x 40 heads x 32K: 2944 rows 88.2 % of peak, 1408 rows
+// 87.1 %, 3456 rows 87.9 %, 3712 rows 87.0 %; multiples 17 and 19 of 128 rows lose
+// 3 to 6 % there: units that walk the HBM channels in step).  The MFMA kernel runs 2
 // blocks per CU and pays more per unit (prologue, cross-wave epilogue), so it gets
 // fewer, larger units: about three per four compute units measured best from
 // 16 x 16K down to 128 x 1K rows in all.
-constexpr int kTargetUnitsMha = 4096, kMaxChunkMha = 1408;
+constexpr int kTargetUnitsMha = 3584, kMaxChunkMha = 2944;
 constexpr int kTargetUnitsGqa = 192, kMaxChunkGqa = 5504;
 constexpr int kSingleSplitStreams = 512, kSingleSplitMaxLen = 8192 + kChunkQuantum;
 constexpr int kResidentUnits = 1280;   // five blocks of the vector-ALU kernel on each of 256 compute units
-// The compacted unit list: (sequence, split) pairs from which on the host expects a ragged
-// batch to be worth one small launch in front, and the most the one block of that launch sorts.
-constexpr int kCompactMinEntries = 256, kCompactMaxEntries = 8192;
+// The unit list of a paged cache: rows (an upper bound: max_seq_len x KV streams) from
+// which on its small launch in front pays, and the most (sequence, split) pairs the one
+// block of that launch sorts.
+constexpr long kCompactMinRows = 2L << 20;
+constexpr int kCompactMaxEntries = 8192, kCompactMaxBatch = 4096;
 
 struct Plan {
     int chunk;
@@ -89,7 +94,7 @@ struct Plan {
 // from host-known sizes alone.  The chunk is an ODD multiple of 128 rows: units
 // that start a large power of two apart walk the same HBM channels in lockstep
 // and lose up to a fifth of the bandwidth (measured), an odd multiple staggers them.
-Plan make_plan(const Options& opt, int batch, int num_q_heads, int num_kv_heads, int max_seq_len)
+Plan make_plan(const Options& opt, int batch, int num_q_heads, int num_kv_heads, int max_seq_len, bool paged)
 {
     const int group = num_q_heads / num_kv_heads;
     // the MFMA path walks a KV head once for its whole query group
@@ -127,15 +132,20 @@ Plan make_plan(const Options& opt, int batch, int num_q_heads, int num_kv_heads,
     p.chunk = (int)chunk;
     p.num_splits = (int)((max_seq_len + chunk - 1) / chunk);
     p.group_blocks = (group + 15) / 16;
-    // Of a ragged batch's (sequence, split) grid a good part holds no rows, and its last
-    // units are as long as its first.  With many such pairs one block first lists the units
-    // that hold rows, the full ones in front and the partly filled ones behind them from
-    // long to short, and the split pass walks that list: no empty blocks, and the launch
-    // ends on its shortest units.  Below kCompactMinEntries pairs the launch in front
-    // (about 3 us) costs more than it brings.
+    // A paged cache is read in scattered pieces (4 KB per page and head), every one behind an
+    // address translation of its own.  There one block first lists the units that hold
+    // rows - the full ones in front, the partly filled ones behind them from long to short -
+    // and the split pass walks that list with the blocks of a unit (its heads) on ONE XCD:
+    // they read the same pages of the pool together, so a translation serves all of them,
+    // and the list's order deals the units out evenly over the XCDs and ends the launch on
+    // its shortest units.  Measured on the same caches: 64 ragged sequences of 1K..16K rows,
+    // 40 heads, 16-token pages 82.1 -> 84.8 % of peak (the same list without the XCD grouping:
+    // 81.8 %); 64 x 8.7K rows 81.9 -> 85.8 %.  A contiguous cache gains nothing from it (ragged
+    // 87.8 % without, 86.6 % with) and keeps the plain grid.
     const long entries = (long)batch * p.num_splits;
-    const bool can = p.num_splits > 1 && batch > 1 && entries <= kCompactMaxEntries && p.group_blocks == 1;
-    p.compact = can && (opt[kOptCompact] >= 0 ? opt[kOptCompact] == 1 : entries >= kCompactMinEntries);
+    const bool can = batch > 1 && batch <= kCompactMaxBatch && entries <= kCompactMaxEntries && p.group_blocks == 1;
+    p.compact = can && (opt[kOptCompact] >= 0 ? opt[kOptCompact] == 1
+                                               : paged && (long)max_seq_len * streams >= kCompactMinRows);
     // Streams whose strides walk the HBM channels in step (a contiguous cache of 2064
     // rows per head does) lose a tenth to a half of the bandwidth; starting every unit
     // at its own tile undoes most of that and costs about 1 % elsewhere: off by default.
@@ -180,6 +190,7 @@ Carve carve(int batch, int num_q_heads, int head_dim, const Plan& p)
     c.unit_list = (c.lse_part + units * sizeof(float) + 255) / 256 * 256;
     // room for the list whenever the plan could use it, so that the size does not depend on the switches
     c.total = c.unit_list + (entries <= (size_t)kCompactMaxEntries ? (entries * sizeof(int32_t) + 255) / 256 * 256 : 0);
+    // (the layout changes neither the units nor this size, only whether the list is used)
     return c;
 }
 
@@ -206,7 +217,8 @@ int check_decode(const void* q, const void* k_new, const void* v_new, bool fused
     if (max_seq_len > kv->capacity) return INSTATTN_ERR_INVALID_ARG;
     if (fused && (!k_new || !v_new || !aligned16(k_new) || !aligned16(v_new)))
         return INSTATTN_ERR_INVALID_ARG;
-    *plan = make_plan(options_snapshot(), batch, num_q_heads, num_kv_heads, max_seq_len);
+    *plan = make_plan(options_snapshot(), batch, num_q_heads, num_kv_heads, max_seq_len,
+                      kv->layout == INSTATTN_KV_PAGED);
     st = check_plan(*plan, batch, num_kv_heads);
     if (st != INSTATTN_OK) return st;
     return check_out(out, out_dtype, workspace, workspace_bytes, carve(batch, num_q_heads, head_dim, *plan).total);
@@ -406,7 +418,7 @@ int instattn_decode_plan(int batch, int num_q_heads, int num_kv_heads, int head_
 {
     int st = check_shape(batch, num_q_heads, num_kv_heads, head_dim, max_seq_len);
     if (st != INSTATTN_OK) return st;
-    const Plan p = make_plan(options_snapshot(), batch, num_q_heads, num_kv_heads, max_seq_len);
+    const Plan p = make_plan(options_snapshot(), batch, num_q_heads, num_kv_heads, max_seq_len, false);
     st = check_plan(p, batch, num_kv_heads);
     if (st != INSTATTN_OK) return st;
     if (chunk_tokens) *chunk_tokens = p.chunk;
@@ -415,12 +427,14 @@ int instattn_decode_plan(int batch, int num_q_heads, int num_kv_heads, int head_
 }
 
 int instattn_decode_launches(int batch, int num_q_heads, int num_kv_heads, int head_dim, int max_seq_len,
-                             int with_append, int32_t* launches)
+                             int kv_layout, int with_append, int32_t* launches)
 {
     int st = check_shape(batch, num_q_heads, num_kv_heads, head_dim, max_seq_len);
     if (st != INSTATTN_OK) return st;
-    if (!launches) return INSTATTN_ERR_INVALID_ARG;
-    const Plan p = make_plan(options_snapshot(), batch, num_q_heads, num_kv_heads, max_seq_len);
+    if (!launches || (kv_layout != INSTATTN_KV_CONTIGUOUS && kv_layout != INSTATTN_KV_PAGED))
+        return INSTATTN_ERR_INVALID_ARG;
+    const Plan p = make_plan(options_snapshot(), batch, num_q_heads, num_kv_heads, max_seq_len,
+                             kv_layout == INSTATTN_KV_PAGED);
     st = check_plan(p, batch, num_kv_heads);
     if (st != INSTATTN_OK) return st;
     launches[0] = with_append && p.group_blocks > 1;   // the store of the new token as a launch of its own
@@ -434,7 +448,7 @@ size_t instattn_decode_workspace_size(int batch, int num_q_heads, int num_kv_hea
                                       int max_seq_len)
 {
     if (check_shape(batch, num_q_heads, num_kv_heads, head_dim, max_seq_len) != INSTATTN_OK) return 0;
-    const Plan p = make_plan(options_snapshot(), batch, num_q_heads, num_kv_heads, max_seq_len);
+    const Plan p = make_plan(options_snapshot(), batch, num_q_heads, num_kv_heads, max_seq_len, false);
     if (check_plan(p, batch, num_kv_heads) != INSTATTN_OK) return 0;
     return carve(batch, num_q_heads, head_dim, p).total;
 }
@@ -476,7 +490,7 @@ int instattn_decode_merge(const int32_t* seq_lens, int batch, int num_q_heads, i
     int st = check_shape(batch, num_q_heads, num_kv_heads, head_dim, max_seq_len);
     if (st != INSTATTN_OK) return st;
     if (!seq_lens || capacity <= 0 || max_seq_len > capacity) return INSTATTN_ERR_INVALID_ARG;
-    const Plan p = make_plan(options_snapshot(), batch, num_q_heads, num_kv_heads, max_seq_len);
+    const Plan p = make_plan(options_snapshot(), batch, num_q_heads, num_kv_heads, max_seq_len, false);
     st = check_plan(p, batch, num_kv_heads);
     if (st != INSTATTN_OK) return st;
     st = check_out(out, out_dtype, workspace, workspace_bytes, carve(batch, num_q_heads, head_dim, p).total);

@@ -60,9 +60,10 @@ struct DecodeArgs {
     // query heads (1 for groups of at most 16).
     int32_t group_blocks;
     int32_t units;              // with group_blocks > 1: KV heads x splits x sequences (the grid is one-dimensional then)
-    // Compacted unit list (nullptr: the grid itself spans sequences x splits): entry j is
+    // Unit list (nullptr: the grid itself spans sequences x splits): entry j is
     // (sequence << 16 | split) of the j-th unit that holds rows, -1 behind the last one;
-    // list_len = sequences x splits entries, filled by list_units_kernel in front of the pass.
+    // list_len = sequences x splits entries, filled by list_units_kernel in front of the pass;
+    // the pass then runs on a one-dimensional grid (unit_of_block).
     int32_t* unit_list;
     int32_t list_len;
 };
@@ -115,15 +116,24 @@ __device__ __forceinline__ int clamp_len(int L, int max_len) {
     return L > max_len ? max_len : L;
 }
 
-// Which (sequence, split) a block of the split pass works on: its grid coordinates, or the
-// entry of the compacted unit list its blockIdx.y names.  False: no unit (the list's tail).
-__device__ __forceinline__ bool unit_of_block(const DecodeArgs& a, int& b, int& split) {
+// Which (sequence, split, head) a block of the split pass works on: its grid coordinates,
+// or, with the unit list, an entry of the list.  The list's grid is one-dimensional and a
+// unit's `heads` blocks are 8 apart in it: consecutive block ids go round-robin over the 8
+// XCDs, so the blocks of a unit run on one XCD and walk the same pages of a paged pool
+// together (one address translation serves all of them), while the list's order deals the
+// units out evenly over the XCDs.  False: no unit (the list's tail).
+__device__ __forceinline__ bool unit_of_block(const DecodeArgs& a, int heads, int& b, int& split, int& h) {
     if (a.unit_list == nullptr) {
+        h = blockIdx.x;
         split = blockIdx.y;
         b = blockIdx.z;
         return true;
     }
-    const int e = a.unit_list[blockIdx.y];
+    const uint32_t i = blockIdx.x, s = i >> 3, u = s / (uint32_t)heads;
+    const int j = (int)(u * 8 + (i & 7));
+    h = (int)(s - u * (uint32_t)heads);
+    if (j >= a.list_len) return false;
+    const int e = a.unit_list[j];
     b = (int)((uint32_t)e >> 16);
     split = e & 0xFFFF;
     return e >= 0;

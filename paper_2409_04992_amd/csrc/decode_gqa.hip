@@ -102,8 +102,8 @@ __global__ __launch_bounds__(256, 2) void decode_gqa_kernel(DecodeArgs a)
     // each (the last one the rest): every one of them streams the KV head again.
     // Those blocks of a unit are 8 apart in a one-dimensional grid: same XCD, dispatched
     // together, so that the passes behind the first find the rows in that XCD's L2.
-    int split, b, hk = blockIdx.x, sub = 0;
-    if (!unit_of_block(a, b, split)) return;                     // block-uniform
+    int split, b, hk, sub = 0;
+    if (!unit_of_block(a, a.num_kv_heads, b, split, hk)) return;   // block-uniform
     if (a.group_blocks > 1) {
         const int span = 8 * a.group_blocks;
         const int chunk = (int)blockIdx.x / span, within = (int)blockIdx.x - chunk * span;
@@ -327,7 +327,8 @@ template <int D>
 static hipError_t launch_gqa(const DecodeArgs& args, int batch, hipStream_t stream)
 {
     DecodeArgs a = args;
-    dim3 grid = a.unit_list ? dim3(a.num_kv_heads, a.list_len, 1) : dim3(a.num_kv_heads, a.num_splits, batch);
+    dim3 grid(a.num_kv_heads, a.num_splits, batch);
+    if (a.unit_list) grid = dim3((unsigned)((a.list_len + 7) / 8 * 8 * a.num_kv_heads), 1, 1);   // see unit_of_block
     if (a.group_blocks > 1) {
         a.units = a.num_kv_heads * a.num_splits * batch;
         grid = dim3((unsigned)((a.units + 7) / 8 * 8 * a.group_blocks), 1, 1);

@@ -5,14 +5,15 @@
 namespace instattn {
 
 // ---------------------------------------------------------------------------
-// List of the units that hold rows, for the split pass of a ragged batch: of the
+// List of the units that hold rows, for the split pass over a paged cache: of the
 // sequences x splits grid only the pairs with rows, the full units first (in sequence
 // order), behind them the partly filled ones from long to short (in sixteenths of a
-// unit), -1 in the rest of the list.  The launch then has no empty blocks and ends on
-// its shortest units.  One block; wave w places class w in order (ballot + popcount),
-// so the same lengths give the same list.
+// unit), -1 in the rest of the list (with a single split an empty sequence stays in the
+// list, at its end: the pass writes its zero row).  The pass deals the list out over the XCDs in this
+// order, has no empty blocks and ends on its shortest units.  One block; wave w places
+// class w in order (ballot + popcount), so the same lengths give the same list.
 constexpr int kListClasses = 18;        // 0: full, 1..16: partly filled, long to short, 17: no rows
-constexpr int kListMaxBatch = 4096;     // sequences whose lengths the block keeps in LDS (at least two splits each)
+constexpr int kListMaxBatch = 4096;     // sequences whose lengths the block keeps in LDS
 
 __global__ __launch_bounds__(1024) void list_units_kernel(DecodeArgs a, int batch)
 {
@@ -27,7 +28,8 @@ __global__ __launch_bounds__(1024) void list_units_kernel(DecodeArgs a, int batc
         const int b = e / a.num_splits, split = e - b * a.num_splits;
         packed = b << 16 | split;
         const int rows = min(s_len[b] - split * a.chunk, a.chunk);
-        if (rows <= 0) return kListClasses - 1;
+        // with a single split the pass itself writes the zero row of an empty sequence: listed, last
+        if (rows <= 0) return a.num_splits == 1 ? kListClasses - 2 : kListClasses - 1;
         if (rows == a.chunk) return 0;
         return 16 - (int)((int64_t)rows * 16 / a.chunk);
     };
@@ -59,7 +61,7 @@ __global__ __launch_bounds__(1024) void list_units_kernel(DecodeArgs a, int batc
 
 hipError_t launch_list_units(const DecodeArgs& a, int batch, hipStream_t stream)
 {
-    if (batch > kListMaxBatch || a.num_splits < 2 || a.list_len != batch * a.num_splits) return hipErrorInvalidValue;
+    if (batch > kListMaxBatch || a.list_len != batch * a.num_splits) return hipErrorInvalidValue;
     hipLaunchKernelGGL(list_units_kernel, dim3(1), dim3(1024), 0, stream, a, batch);
     return hipGetLastError();
 }

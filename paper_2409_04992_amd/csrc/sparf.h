@@ -6,7 +6,7 @@
 namespace instattn {
 
 constexpr int kSparfChunk = 8192;      // positions per block of the approximate-score pass
-constexpr int kSparfMaxSeqLen = 1 << 30;  // longest row accepted (the padded row length stays an int32)
+constexpr int kSparfMaxSeqLen = 65535 * kSparfChunk;   // longest row accepted: its stretches are a grid dimension (and the padded row length stays an int32)
 constexpr int kSparfStatRun = 512;     // scores per entry of the score statistics (a wave's share of a unit)
 constexpr int kSparfAttendWaves = 8;
 constexpr int kSparfMemberCap = 1024;  // members of the threshold bin the distributed selection ranks through LDS

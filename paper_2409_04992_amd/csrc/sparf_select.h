@@ -51,7 +51,6 @@ __device__ __forceinline__ void locate_bin(SelectScratch& S, uint32_t remaining,
     }
 }
 
-// All kept columns of one stretch of at most STEPS * NT * 8 positions, in groups
 // Level-1 bucket of a score: linear between the row's minimum and maximum,
 // monotone in the score, so every score in a higher bucket is >= every score in a
 // lower one.

@@ -189,30 +189,39 @@ def test_switches_start_from_the_environment():
 
 
 def test_decode_launches(options):
-    # the four timed shapes: only the ragged batch (64 x 12 pairs) lists its units first
+    # the four timed shapes: only the paged one lists its units first
     assert B.decode_launches(16, 40, 40, 128, 4097, True) == \
         {"append": False, "unit_list": False, "split_pass": True, "merge": True}
-    assert not B.decode_launches(8, 40, 40, 128, 32769, True)["unit_list"]       # 8 x 24 pairs
-    assert B.decode_launches(64, 40, 40, 128, 16385, True)["unit_list"]          # 64 x 12 pairs
-    assert not B.decode_launches(32, 64, 8, 128, 16385, True)["unit_list"]       # 32 x 3 pairs
+    assert not B.decode_launches(8, 40, 40, 128, 32769, True)["unit_list"]
+    assert B.decode_launches(64, 40, 40, 128, 16385, True, paged=True)["unit_list"]
+    assert not B.decode_launches(64, 40, 40, 128, 16385, True)["unit_list"]      # the same batch, contiguous
+    assert not B.decode_launches(32, 64, 8, 128, 16385, True)["unit_list"]
     assert B.decode_launches(32, 40, 40, 128, 4097) == \
         {"append": False, "unit_list": False, "split_pass": True, "merge": False}  # whole sequences as units
+    assert B.decode_launches(32, 40, 40, 128, 4097, paged=True)["unit_list"]     # ... listed all the same when paged
+    assert not B.decode_launches(2, 4, 4, 128, 4097, paged=True)["unit_list"]    # too little to pay for the launch
+    assert not B.decode_launches(1, 40, 40, 128, 131072, paged=True)["unit_list"]  # one sequence: nothing to order
     # a group of more than 16 query heads: the append is a launch of its own, and no list
-    assert B.decode_launches(64, 48, 1, 128, 16385, True)["append"]
+    assert B.decode_launches(64, 48, 1, 128, 16385, True, paged=True) == \
+        {"append": True, "unit_list": False, "split_pass": True, "merge": True}
     assert not B.decode_launches(64, 48, 1, 128, 16385, False)["append"]
     options.setenv("INSTATTN_COMPACT", 1)
     assert B.decode_launches(8, 40, 40, 128, 32769)["unit_list"]
-    assert not B.decode_launches(32, 40, 40, 128, 4097)["unit_list"]             # one split: nothing to list
-    assert not B.decode_launches(1, 40, 40, 128, 131072)["unit_list"]            # one sequence is never ragged
+    assert B.decode_launches(32, 40, 40, 128, 4097)["unit_list"]
+    assert not B.decode_launches(1, 40, 40, 128, 131072)["unit_list"]
     assert not B.decode_launches(64, 48, 1, 128, 16385)["unit_list"]
+    assert not B.decode_launches(5000, 8, 8, 128, 4097)["unit_list"]             # more sequences than the list's block holds
     options.setenv("INSTATTN_COMPACT", 0)
-    assert not B.decode_launches(64, 40, 40, 128, 16385)["unit_list"]
-    # the workspace has room for the list whatever the switch says
+    assert not B.decode_launches(64, 40, 40, 128, 16385, paged=True)["unit_list"]
+    # the workspace has room for the list whatever the switch and the layout say
     sizes = set()
     for v in (None, 0, 1):
         options.setenv("INSTATTN_COMPACT", -1 if v is None else v)
         sizes.add(B.decode_workspace_size(64, 40, 40, 128, 16385))
-    assert len(sizes) == 1 and sizes.pop() >= 64 * 40 * 12 * 129 * 4 + 64 * 12 * 4
+    assert len(sizes) == 1 and sizes.pop() >= 64 * 40 * 6 * 129 * 4 + 64 * 6 * 4
+    L = B.lib()
+    assert L.instattn_decode_launches(8, 40, 40, 128, 32769, 7, 0, (ctypes.c_int32 * 4)()) == B.ERR_INVALID_ARG
+    assert L.instattn_decode_launches(8, 40, 40, 128, 32769, 0, 0, None) == B.ERR_INVALID_ARG
 
 
 def test_limits_of_the_launch_grids_are_checked_before_anything_is_launched(options):
@@ -456,12 +465,13 @@ def test_sparf_plan_rejects():
         with pytest.raises(B.InstattnError) as e:
             B.sparf_plan(*args)
         assert e.value.status == B.ERR_INVALID_ARG
-    for args in [(1, 4, 4, 96, 100, 10), (1, 4, 4, 128, (1 << 30) + 1, 10)]:
+    longest = 65535 * 8192              # the stretches of a row are a grid dimension of the distributed selection
+    for args in [(1, 4, 4, 96, 100, 10), (1, 4, 4, 128, longest + 1, 10)]:
         with pytest.raises(B.InstattnError) as e:
             B.sparf_plan(*args)
         assert e.value.status == B.ERR_UNSUPPORTED
-    assert B.sparf_workspace_size(1, 4, 128, (1 << 30) + 1, 10) == 0
-    assert B.sparf_workspace_size(1, 4, 128, 1 << 30, 10) > (1 << 30) * 4 * 4
+    assert B.sparf_workspace_size(1, 4, 128, longest + 1, 10) == 0
+    assert B.sparf_workspace_size(1, 4, 128, longest, 10) > longest * 4 * 4
 
 
 # ------------------------------------------------------------------ the header as plain C

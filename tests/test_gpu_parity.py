@@ -77,7 +77,8 @@ def test_config4_ragged_paged_full_size(fused):
     wl = W.WORKLOADS["ragged_paged"]
     lens = W.draw_seq_lens(wl)
     assert lens.min() >= 1025 and lens.max() <= 16385 and len(set(lens.tolist())) > 32
-    assert B.decode_launches(wl.batch, wl.num_q_heads, wl.num_kv_heads, wl.head_dim, int(lens.max()), fused)["unit_list"]
+    assert B.decode_launches(wl.batch, wl.num_q_heads, wl.num_kv_heads, wl.head_dim, int(lens.max()), fused,
+                             paged=True)["unit_list"]
     full_check(wl, fused=fused)
 
 
@@ -332,22 +333,25 @@ def test_head_sharded_equals_unsharded_bit_for_bit_under_one_plan(options):
         assert torch.equal(a[:, hq // 2:], c) and torch.equal(la[:, hq // 2:], lc)
 
 
+@pytest.mark.parametrize("chunk", [384, 100000])
 @pytest.mark.parametrize("shape", ["mha_paged", "mha_contiguous", "gqa_paged", "gqa_d64"])
-def test_compacted_unit_list_equals_the_grid_bit_for_bit(options, shape):
+def test_compacted_unit_list_equals_the_grid_bit_for_bit(options, shape, chunk):
     """A ragged batch through the device-built list of units and through the plain
     (sequence, split) grid: same plan, same arithmetic per unit, so the same bits - and
     both agree with the oracle.  Lengths include empty sequences, full units, single rows
-    behind a unit boundary and the longest length the cache holds."""
+    behind a unit boundary and the longest length the cache holds; with units of 384 rows
+    and with whole sequences as units (the list then orders the sequences by length)."""
     hq, hkv, dim, paged = {"mha_paged": (5, 5, 128, True), "mha_contiguous": (3, 3, 128, False),
                            "gqa_paged": (8, 2, 128, True), "gqa_d64": (6, 3, 64, False)}[shape]
     wl = small("ragged_paged", batch=9, num_q_heads=hq, num_kv_heads=hkv, head_dim=dim, seq_len=1700,
                seq_len_min=100, paged=paged)
     lens = [0, 384, 385, 1, 1701, 768, 1152, 1153, 700]
-    options.setenv("INSTATTN_CHUNK", 384)
+    options.setenv("INSTATTN_CHUNK", chunk)
     res = []
     for compact in (0, 1):
         options.setenv("INSTATTN_COMPACT", compact)
-        assert B.decode_launches(9, hq, hkv, dim, 1701)["unit_list"] == bool(compact)
+        assert B.decode_launches(9, hq, hkv, dim, 1701, paged=paged) == \
+            {"append": False, "unit_list": bool(compact), "split_pass": True, "merge": chunk == 384}
         for fused in (False, True):
             case = W.make_case(wl, DEV, poison=True, lens=lens)
             want_out, want_lse, want_k, want_v = H.oracle_step(case)

@@ -139,8 +139,8 @@ def check_against_oracle(case, out, sel, alpha, r, k, l, pairs=None, rows_of=Non
         leff = min(l, keff)
         assert set(range(L - leff, L)) <= set(got_rows)            # step 5
         # step 6: a valid top-k of the oracle's scores up to fp32 rounding
-        want_rows = set(res["j_rows"].tolist())
-        lg = res["logits_hat"]
+        want_rows = set(res["kept_rows"].tolist())
+        lg = res["approx_logits"]
         cand = np.array(sorted(want_rows - set(range(L - leff, L))))
         if len(cand):
             thr = lg[cand].min()
@@ -149,8 +149,8 @@ def check_against_oracle(case, out, sel, alpha, r, k, l, pairs=None, rows_of=Non
             for t in want_rows - set(got_rows.tolist()):
                 assert lg[t] <= thr + SCORE_EPS, (b, h, t)
         # steps 7, 10, 11 on the kernel's own selection
-        want_out, want_alpha = sparf.finish_from_selection(q[b, h], Kr, Vr, case.scale, res["s_hat"],
-                                                           got_rows, res["vbar"])
+        want_out, want_alpha = sparf.finish_from_selection(q[b, h], Kr, Vr, case.scale, res["approx_weights"],
+                                                           got_rows, res["mean_v"])
         assert abs(float(alpha[b, h]) - want_alpha) <= 2e-5
         err = np.abs(out[b, h].double().cpu().numpy() - want_out).max()
         worst = max(worst, err)

@@ -30,16 +30,16 @@ def test_selecting_every_row_gives_dense_attention(r, l):
     res = sparf.sparf_one(q, K, V, 0.25, r=r, k=60, l=l)
     want, _, _ = dense.attend_one(q, K, V, 0.25)
     np.testing.assert_allclose(res["out"], want, rtol=0, atol=1e-13)
-    assert abs(res["alpha"] - 1.0) < 1e-13 and len(res["j_rows"]) == 60
+    assert abs(res["kept_mass"] - 1.0) < 1e-13 and len(res["kept_rows"]) == 60
 
 
 def test_all_components_give_exact_scores_and_exact_top_k():
     q, K, V = draw(2, S=80, D=8)
     res = sparf.sparf_one(q, K, V, 0.3, r=8, k=10, l=0)
     _, _, w = dense.attend_one(q, K, V, 0.3)
-    np.testing.assert_allclose(res["s_hat"], w, rtol=0, atol=1e-14)
-    assert set(res["j_rows"]) == set(np.argsort(-w)[:10])
-    assert abs(res["alpha"] - np.sort(w)[-10:].sum()) < 1e-14
+    np.testing.assert_allclose(res["approx_weights"], w, rtol=0, atol=1e-14)
+    assert set(res["kept_rows"]) == set(np.argsort(-w)[:10])
+    assert abs(res["kept_mass"] - np.sort(w)[-10:].sum()) < 1e-14
 
 
 # ---------------------------------------------------------------- brute force, written a second way
@@ -73,8 +73,8 @@ def test_brute_force_tiny(S, D, r, k, l, seed):
     q, K, V = draw(seed + 10, S, D)
     res = sparf.sparf_one(q, K, V, 0.5, r, k, l)
     out, rows, alpha, dims = brute(q, K, V, 0.5, r, k, l)
-    assert list(res["i_dims"]) == dims and list(res["j_rows"]) == rows
-    assert abs(res["alpha"] - alpha) < 1e-14
+    assert list(res["kept_dims"]) == dims and list(res["kept_rows"]) == rows
+    assert abs(res["kept_mass"] - alpha) < 1e-14
     np.testing.assert_allclose(res["out"], out, rtol=0, atol=1e-14)
 
 
@@ -87,16 +87,16 @@ def test_temperature_with_equal_magnitudes_is_sqrt_r():
     q = f16(r_.choice([-1.0, 1.0], size=D) * 0.5)
     K, V = f16(r_.normal(size=(S, D))), f16(r_.normal(size=(S, D)))
     res = sparf.sparf_one(q, K, V, 1.0 / math.sqrt(D), r, 5, 0)
-    dims = res["i_dims"]
+    dims = res["kept_dims"]
     assert list(dims) == [0, 1, 2, 3]                      # ties towards the lower index
     lg = K[:, dims].astype(np.float64) @ q[dims].astype(np.float64) / math.sqrt(r)
-    np.testing.assert_allclose(res["s_hat"], sparf.softmax(lg), rtol=0, atol=1e-7)
+    np.testing.assert_allclose(res["approx_weights"], sparf.softmax(lg), rtol=0, atol=1e-7)
 
 
 def test_components_are_chosen_by_magnitude_not_sign():
     q = f16([0.1, -5.0, 0.2, 3.0, -0.3, 0.05])
     K, V = f16(rng(6).normal(size=(9, 6))), f16(rng(7).normal(size=(9, 6)))
-    assert list(sparf.sparf_one(q, K, V, 0.4, 2, 3, 0)["i_dims"]) == [1, 3]
+    assert list(sparf.sparf_one(q, K, V, 0.4, 2, 3, 0)["kept_dims"]) == [1, 3]
 
 
 # ---------------------------------------------------------------- steps 5-7: selection
@@ -105,9 +105,9 @@ def test_most_recent_rows_are_always_selected(l):
     q, K, V = draw(8, S=50, D=8)
     K[-8:] = f16(-4.0 * q)                                   # make the recent rows the weakest
     res = sparf.sparf_one(q, K, V, 0.5, r=4, k=8, l=l)
-    assert set(range(50 - l, 50)) <= set(res["j_rows"]) and len(res["j_rows"]) == 8
+    assert set(range(50 - l, 50)) <= set(res["kept_rows"]) and len(res["kept_rows"]) == 8
     if l == 0:
-        assert not set(range(42, 50)) & set(res["j_rows"])
+        assert not set(range(42, 50)) & set(res["kept_rows"])
 
 
 def test_alpha_is_the_selected_mass_and_grows_with_k():
@@ -115,10 +115,10 @@ def test_alpha_is_the_selected_mass_and_grows_with_k():
     prev = 0.0
     for k in [1, 4, 16, 40, 64]:
         res = sparf.sparf_one(q, K, V, 0.3, r=6, k=k, l=1)
-        assert 0.0 < res["alpha"] <= 1.0 + 1e-15
-        assert res["alpha"] > prev - 1e-15
-        assert abs(res["alpha"] - res["s_hat"][res["j_rows"]].sum()) < 1e-15
-        prev = res["alpha"]
+        assert 0.0 < res["kept_mass"] <= 1.0 + 1e-15
+        assert res["kept_mass"] > prev - 1e-15
+        assert abs(res["kept_mass"] - res["approx_weights"][res["kept_rows"]].sum()) < 1e-15
+        prev = res["kept_mass"]
     assert abs(prev - 1.0) < 1e-13
 
 
@@ -128,11 +128,11 @@ def test_two_step_page_load_recovers_exactly_the_selection():
     q, K, V = draw(10, S=100, D=8)
     res = sparf.sparf_one(q, K, V, 0.5, r=3, k=12, l=2)
     for n in (4, 16):
-        pages = sparf.pages_touched(res["j_rows"], n)
+        pages = sparf.pages_touched(res["kept_rows"], n)
         fetched = np.concatenate([np.arange(p * n, min((p + 1) * n, 100)) for p in pages])
         keep = np.zeros(100, bool)
-        keep[res["j_rows"]] = True
-        assert list(fetched[keep[fetched]]) == list(res["j_rows"])
+        keep[res["kept_rows"]] = True
+        assert list(fetched[keep[fetched]]) == list(res["kept_rows"])
         assert len(pages) <= 12 and len(fetched) >= 12
 
 
@@ -150,8 +150,8 @@ def test_output_is_a_convex_combination():
     V64 = V.astype(np.float64)
     assert (res["out"] <= V64.max(axis=0) + 1e-12).all() and (res["out"] >= V64.min(axis=0) - 1e-12).all()
     # and exactly alpha * (attention over the selected rows alone) + (1 - alpha) * mean of V
-    sub, _, _ = dense.attend_one(q, K[res["j_rows"]], V[res["j_rows"]], 0.6)
-    want = res["alpha"] * sub + (1 - res["alpha"]) * V64.mean(axis=0)
+    sub, _, _ = dense.attend_one(q, K[res["kept_rows"]], V[res["kept_rows"]], 0.6)
+    want = res["kept_mass"] * sub + (1 - res["kept_mass"]) * V64.mean(axis=0)
     np.testing.assert_allclose(res["out"], want, rtol=0, atol=1e-13)
 
 
@@ -162,15 +162,38 @@ def test_dominant_key_is_found_through_the_kept_components():
     K, V = f16(0.3 * r_.normal(size=(S, D))), f16(r_.normal(size=(S, D)))
     K[77] = f16(6.0 * q)
     res = sparf.sparf_one(q, K, V, 1.0, r=8, k=4, l=1)
-    assert 77 in res["j_rows"] and res["alpha"] > 1 - 1e-6
+    assert 77 in res["kept_rows"] and res["kept_mass"] > 1 - 1e-6
     np.testing.assert_allclose(res["out"], V[77].astype(np.float64), rtol=0, atol=1e-4)
+
+
+def test_helpers_on_their_own():
+    """The pieces sparf_one is made of, each against a value worked out by hand."""
+    # magnitudes 5, 4, 3, 3: the tie between components 2 and 3 goes to the lower index
+    assert list(sparf.kept_components(np.array([3.0, -5.0, 3.0, 4.0, 0.5]), 3)) == [0, 1, 3]
+    # all components kept: plain softmax of scale * K q (the temperature correction is 1)
+    K = np.array([[1.0, 0.0], [0.0, 2.0], [1.0, 1.0]])
+    q = np.array([2.0, -1.0])
+    logits, w = sparf.approximate_weights(q, K, np.array([0, 1]), 0.5)
+    np.testing.assert_allclose(logits, [1.0, -1.0, 0.5], atol=1e-15)
+    np.testing.assert_allclose(w, np.exp([1.0, -1.0, 0.5]) / np.exp([1.0, -1.0, 0.5]).sum(), atol=1e-15)
+    # one of two components kept, |q_kept|_1 / |q|_1 = 2/3: logits = scale * sqrt(3/2) * K[:, 0] * q[0]
+    logits, _ = sparf.approximate_weights(q, K, np.array([0]), 0.5)
+    np.testing.assert_allclose(logits, 0.5 * math.sqrt(1.5) * np.array([2.0, 0.0, 2.0]), atol=1e-15)
+    # three of five positions kept, the most recent two forced in: the best of the other three joins them
+    assert list(sparf.kept_positions(np.array([0.1, 0.5, 0.3, 0.05, 0.05]), 3, 2)) == [1, 3, 4]
+    assert list(sparf.kept_positions(np.array([0.1, 0.5, 0.3, 0.05, 0.05]), 2, 0)) == [1, 2]
+    # kept mass 0.8, attention over the two kept rows with equal scores = their mean
+    V = np.array([[1.0, 1.0], [3.0, 5.0], [9.0, 9.0]])
+    out, mass, exact = sparf.blend(np.zeros(2), K, V, 1.0, np.array([0.5, 0.3, 0.2]), [0, 1], np.array([10.0, 20.0]))
+    assert mass == 0.8 and list(exact) == [0.5, 0.5]
+    np.testing.assert_allclose(out, 0.8 * np.array([2.0, 3.0]) + 0.2 * np.array([10.0, 20.0]), atol=1e-15)
 
 
 def test_finish_from_selection_matches_the_full_run():
     q, K, V = draw(14)
     res = sparf.sparf_one(q, K, V, 0.25, 5, 9, 2)
-    out, alpha = sparf.finish_from_selection(q, K, V, 0.25, res["s_hat"], res["j_rows"], res["vbar"])
-    assert np.array_equal(out, res["out"]) and alpha == res["alpha"]
+    out, alpha = sparf.finish_from_selection(q, K, V, 0.25, res["approx_weights"], res["kept_rows"], res["mean_v"])
+    assert np.array_equal(out, res["out"]) and alpha == res["kept_mass"]
 
 
 def test_batch_form_and_group_mapping():
@@ -183,7 +206,7 @@ def test_batch_form_and_group_mapping():
     assert np.array_equal(out[1], np.zeros((Hkv * G, D))) and (alpha[1] == 0).all()
     for h in range(Hkv * G):
         one = sparf.sparf_one(q[0, h], K[0, h // G, :33], V[0, h // G, :33], 0.4, 3, 6, 1)
-        assert np.array_equal(out[0, h], one["out"]) and list(sel[0][h]) == list(one["j_rows"])
+        assert np.array_equal(out[0, h], one["out"]) and list(sel[0][h]) == list(one["kept_rows"])
 
 
 def test_one_eighth_of_the_dense_bytes():
