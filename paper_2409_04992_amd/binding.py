@@ -127,7 +127,7 @@ def status_string(status: int) -> str:
     return lib().instattn_status_string(int(status)).decode()
 
 
-OPTIONS = ("INSTATTN_CHUNK", "INSTATTN_ROTATE", "INSTATTN_COMPACT", "INSTATTN_SPARF_DISTRIBUTED",
+OPTIONS = ("INSTATTN_CHUNK", "INSTATTN_ROTATE", "INSTATTN_COMPACT", "INSTATTN_MHA_RING", "INSTATTN_SPARF_DISTRIBUTED",
            "INSTATTN_SPARF_THREE_LAUNCHES", "INSTATTN_SPARF_WIDE", "INSTATTN_SPARF_SPLIT_TAIL")
 
 

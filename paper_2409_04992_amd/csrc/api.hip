@@ -23,7 +23,7 @@ namespace {
 
 const char* const kOptionNames[kNumOptions] = {
     "INSTATTN_CHUNK", "INSTATTN_ROTATE", "INSTATTN_SPARF_DISTRIBUTED", "INSTATTN_SPARF_THREE_LAUNCHES",
-    "INSTATTN_SPARF_WIDE", "INSTATTN_SPARF_SPLIT_TAIL", "INSTATTN_COMPACT",
+    "INSTATTN_SPARF_WIDE", "INSTATTN_SPARF_SPLIT_TAIL", "INSTATTN_COMPACT", "INSTATTN_MHA_RING",
 };
 std::atomic<int> g_options[kNumOptions];
 std::once_flag g_options_once;
@@ -63,16 +63,23 @@ int option_index(const char* name)
 constexpr int kVersion = 200;          // 0.2.0
 constexpr int kChunkQuantum = 128;     // every kernel's block tile divides this
 constexpr int kMinChunk = 384;
-// Work units wanted per launch and largest unit, per kernel family.  The vector-ALU
-// kernel runs one block per CU with a deep ring of tiles: units of about 3000 rows
-// amortise its prologue and epilogue, and some fourteen rounds of them over the 256
-// compute units still balance (8 x 40 heads x 32K: 2944 rows 88.2 % of peak, 1408 rows
-// 87.1 %, 3456 rows 87.9 %, 3712 rows 87.0 %; multiples 17 and 19 of 128 rows lose
-// 3 to 6 % there: units that walk the HBM channels in step).  The MFMA kernel runs 2
-// blocks per CU and pays more per unit (prologue, cross-wave epilogue), so it gets
-// fewer, larger units: about three per four compute units measured best from
-// 16 x 16K down to 128 x 1K rows in all.
+// Work units wanted per launch and largest unit, per kernel.  The vector-ALU kernel has
+// two forms.  Large launches stage their tiles through an LDS ring, one block per CU:
+// units of about 3000 rows amortise its prologue and epilogue, and some fourteen rounds of
+// them over the 256 compute units still balance (8 x 40 heads x 32K: 2944 rows 88.2 % of
+// peak, 1408 rows 87.1 %, 3456 rows 87.9 %, 3712 rows 87.0 %; multiples 17 and 19 of 128
+// rows lose 3 to 6 % there: units that walk the HBM channels in step).  Small launches
+// (below kRingMinRows rows in all, an upper bound: 0.5 GB at head_dim 128) hold two tiles
+// in registers, five blocks per CU, and take shorter units, so that 1280 block slots hide
+// each other's start and end (4 x 40 heads x 1.5K: 24.5 us against 27.3 us through the
+// ring); so do launches whose units come out shorter than kRingMinChunk rows (32 x 40 heads x
+// 1.5K as whole sequences: 83.0 % of peak against 81.3 %).  The MFMA kernel runs 2 blocks per CU and pays more per unit (prologue,
+// cross-wave epilogue), so it gets fewer, larger units: about three per four compute
+// units measured best from 16 x 16K down to 128 x 1K rows in all.
 constexpr int kTargetUnitsMha = 3584, kMaxChunkMha = 2944;
+constexpr int kTargetUnitsMhaSmall = 4096, kMaxChunkMhaSmall = 1408;
+constexpr long kRingMinRows = 1L << 20;
+constexpr int kRingMinChunk = 2048;
 constexpr int kTargetUnitsGqa = 192, kMaxChunkGqa = 5504;
 constexpr int kSingleSplitStreams = 512, kSingleSplitMaxLen = 8192 + kChunkQuantum;
 constexpr int kResidentUnits = 1280;   // five blocks of the vector-ALU kernel on each of 256 compute units
@@ -87,6 +94,7 @@ struct Plan {
     int num_splits;
     int group_blocks;     // MFMA kernel: blocks per KV head and unit (16 query heads each)
     bool compact;         // the split pass walks a device-built list of the units that hold rows
+    bool staged;          // vector-ALU kernel: tiles through the LDS ring (large launches)
     bool rotate;
 };
 
@@ -99,36 +107,51 @@ Plan make_plan(const Options& opt, int batch, int num_q_heads, int num_kv_heads,
     const int group = num_q_heads / num_kv_heads;
     // the MFMA path walks a KV head once for its whole query group
     const long streams = (long)batch * (group == 1 ? num_q_heads : num_kv_heads);
-    const long target = group == 1 ? kTargetUnitsMha : kTargetUnitsGqa;
-    const long cap = group == 1 ? kMaxChunkMha : kMaxChunkGqa;
-    long chunk = ((long)max_seq_len * streams + target - 1) / target;
-    if (chunk < kMinChunk) chunk = kMinChunk;
-    if (chunk > cap) chunk = cap;
-    chunk = (chunk / kChunkQuantum | 1) * kChunkQuantum;
-    // Enough short independent streams already fill the chip with whole sequences as
-    // units: one unit per stream (the split pass writes the result itself, no merge) when
-    // the streams fill every block slot of the chip, else the fewest equal splits that do
-    // (640 streams in two halves: +1 % on the step; 520 in three thirds: +10 %).
-    if (group == 1 && streams >= kSingleSplitStreams && max_seq_len <= kSingleSplitMaxLen) {
-        const long n = (kResidentUnits + streams - 1) / streams;       // 1 from 1280 streams on
-        chunk = ((((long)max_seq_len + n - 1) / n + kChunkQuantum - 1) / kChunkQuantum | 1) * kChunkQuantum;
-    }
-    // The MFMA kernel holds two blocks per compute unit.  With a stream or more per
-    // compute unit and short sequences, whole sequences are the best units when they
-    // come out even over the 256 compute units (256 or 512 streams: 84.5 % of peak
-    // against 79 % in two splits, and no merge); otherwise equal splits, three units or
-    // more per compute unit, dilute the uneven last round (384 streams of 8K rows in
-    // halves: 82 % against 78 % at the longest allowed unit).
-    if (group > 1 && streams >= 256 && max_seq_len <= kSingleSplitMaxLen) {
-        const long n = streams % 256 == 0 ? 1 : (3 * 256 + streams - 1) / streams;
-        chunk = ((((long)max_seq_len + n - 1) / n + kChunkQuantum - 1) / kChunkQuantum | 1) * kChunkQuantum;
+    auto odd_multiple = [](long rows) { return ((rows + kChunkQuantum - 1) / kChunkQuantum | 1) * kChunkQuantum; };
+    // unit length from the units wanted and the longest unit allowed
+    auto unit_length = [&](long target, long cap) {
+        long chunk = ((long)max_seq_len * streams + target - 1) / target;
         if (chunk < kMinChunk) chunk = kMinChunk;
+        if (chunk > cap) chunk = cap;
+        chunk = (chunk / kChunkQuantum | 1) * kChunkQuantum;
+        // Enough short independent streams already fill the chip with whole sequences as
+        // units: one unit per stream (the split pass writes the result itself, no merge) when
+        // the streams fill every block slot of the chip, else the fewest equal splits that do
+        // (640 streams in two halves: +1 % on the step; 520 in three thirds: +10 %).
+        if (group == 1 && streams >= kSingleSplitStreams && max_seq_len <= kSingleSplitMaxLen) {
+            const long n = (kResidentUnits + streams - 1) / streams;       // 1 from 1280 streams on
+            chunk = odd_multiple(((long)max_seq_len + n - 1) / n);
+        }
+        // The MFMA kernel holds two blocks per compute unit.  With a stream or more per
+        // compute unit and short sequences, whole sequences are the best units when they
+        // come out even over the 256 compute units (256 or 512 streams: 84.5 % of peak
+        // against 79 % in two splits, and no merge); otherwise equal splits, three units or
+        // more per compute unit, dilute the uneven last round (384 streams of 8K rows in
+        // halves: 82 % against 78 % at the longest allowed unit).
+        if (group > 1 && streams >= 256 && max_seq_len <= kSingleSplitMaxLen) {
+            const long n = streams % 256 == 0 ? 1 : (3 * 256 + streams - 1) / streams;
+            chunk = odd_multiple(((long)max_seq_len + n - 1) / n);
+            if (chunk < kMinChunk) chunk = kMinChunk;
+        }
+        return chunk;
+    };
+    long chunk;
+    bool staged = false;
+    if (group > 1) {
+        chunk = unit_length(kTargetUnitsGqa, kMaxChunkGqa);
+    } else {
+        // the ring form wants a large launch of long units; everything else takes the register form
+        chunk = unit_length(kTargetUnitsMha, kMaxChunkMha);
+        staged = opt[kOptMhaRing] >= 0 ? opt[kOptMhaRing] == 1
+                                       : (long)max_seq_len * streams >= kRingMinRows && chunk >= kRingMinChunk;
+        if (!staged) chunk = unit_length(kTargetUnitsMhaSmall, kMaxChunkMhaSmall);
     }
     if (opt[kOptChunk] > 0)
         chunk = ((long)opt[kOptChunk] + kChunkQuantum - 1) / kChunkQuantum * kChunkQuantum;
     const long whole = ((long)max_seq_len + kChunkQuantum - 1) / kChunkQuantum * kChunkQuantum;
     if (chunk > whole) chunk = whole;
     Plan p;
+    p.staged = staged;
     p.chunk = (int)chunk;
     p.num_splits = (int)((max_seq_len + chunk - 1) / chunk);
     p.group_blocks = (group + 15) / 16;
@@ -286,6 +309,7 @@ int enqueue_partial(const Plan& p, const void* q, const void* k_new, const void*
     a.lse_part = (float*)((char*)workspace + c.lse_part);
     a.unit_list = nullptr;
     a.list_len = 0;
+    a.staged = p.staged;
     a.out = out;
     a.lse = lse;
     a.out_f32 = out_dtype == INSTATTN_F32;

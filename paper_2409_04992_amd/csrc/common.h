@@ -66,6 +66,7 @@ struct DecodeArgs {
     // the pass then runs on a one-dimensional grid (unit_of_block).
     int32_t* unit_list;
     int32_t list_len;
+    int32_t staged;             // vector-ALU kernel: 1 = tiles through the LDS ring, 0 = two register tiles
 };
 
 // Arguments of the log-sum-exp merge.

@@ -15,10 +15,13 @@
 //     the stage it has just emptied, so STAGES tiles are always in flight behind
 //     the one being consumed.  A wave touches only its own ring: no barrier in the
 //     loop, only the wave's own load counter.  One block of four waves per compute
-//     unit; measured against two register tiles with five blocks per compute unit
-//     (INSTATTN_MHA_LDS_STAGES=0 builds that form): same caches, same process,
-//     +0.7 % on 16 x 40 heads x 4K, +1.3 % on 8 x 40 x 32K at equal unit length and
-//     +2.5 % with the longer units this form allows.
+//     unit.  The other form of the kernel (STAGES = 0) holds two tiles in registers
+//     instead and runs five blocks per compute unit; measured on the same caches in
+//     one process the ring is ahead on large launches (+0.7 % on 16 x 40 heads x 4K,
+//     +1.3 % on 8 x 40 x 32K at equal unit length and +2.5 % with the longer units it
+//     allows, +1 % at head_dim 64) and behind on small ones, where 256 block slots
+//     are too few for short units (4 x 40 heads x 1.5K: -10 %), so the host picks
+//     the form by the size of the launch.
 //   * q.K: four v_dot2_f32_f16 per lane, then a DPP butterfly inside the 8- or
 //     16-lane row group (no LDS).
 //   * Every row group runs its own online softmax (running max m, sum l, fp32
@@ -37,7 +40,7 @@
 
 // Compile-time knobs (defaults are the measured best).
 #ifndef INSTATTN_MHA_LDS_STAGES
-#define INSTATTN_MHA_LDS_STAGES 3   // tiles per wave in the LDS ring (2: -1 %, 4 and 5: level); 0: two register tiles instead
+#define INSTATTN_MHA_LDS_STAGES 3   // tiles per wave in the LDS ring (2: -1 %, 4 and 5: level)
 #endif
 #ifndef INSTATTN_MHA_NT
 #define INSTATTN_MHA_NT 1           // 1: KV loads carry the non-temporal hint (without it: -10 %)
@@ -67,7 +70,7 @@ __device__ __forceinline__ u32x4 load16(const char* base, uint32_t lane_off) {
 #endif
 }
 
-template <int D, bool PAGED>
+template <int D, bool PAGED, int STAGES>
 __global__ __launch_bounds__(INSTATTN_MHA_WAVES * 64) void decode_mha_kernel(DecodeArgs a)
 {
     constexpr int LPR = D / 8;             // lanes per row
@@ -82,7 +85,7 @@ __global__ __launch_bounds__(INSTATTN_MHA_WAVES * 64) void decode_mha_kernel(Dec
     // One LDS buffer: the staged form's ring of tiles while the unit is walked, then (both
     // forms) the partial sums of the block's streams.
     constexpr int kSumBytes = (NG * D + 2 * NG) * (int)sizeof(float);
-    constexpr int kRingBytes = WAVES * INSTATTN_MHA_LDS_STAGES * 2 * U * 1024;
+    constexpr int kRingBytes = WAVES * STAGES * 2 * U * 1024;
     __shared__ __align__(16) char s_lds[kRingBytes > kSumBytes ? kRingBytes : kSumBytes];
 
     int split, b, h;
@@ -116,10 +119,8 @@ __global__ __launch_bounds__(INSTATTN_MHA_WAVES * 64) void decode_mha_kernel(Dec
 
     // q stays in registers as fp16 pairs; the softmax scale is applied in fp32.
     half8_t q8 = *(const half8_t*)(a.q + row * D + c * 8);
-#if INSTATTN_MHA_LDS_STAGES > 0
     // q arrives before the first tile is requested: the wait for it then does not wait for the tiles
-    asm volatile("" : "+v"(q8));
-#endif
+    if constexpr (STAGES > 0) asm volatile("" : "+v"(q8));
 
     const char* kp = (const char*)a.kv.k;
     const char* vp = (const char*)a.kv.v;
@@ -165,12 +166,10 @@ __global__ __launch_bounds__(INSTATTN_MHA_WAVES * 64) void decode_mha_kernel(Dec
         }
     };
 
-#if INSTATTN_MHA_LDS_STAGES > 0
-    {
+    if constexpr (STAGES > 0) {
         // Stage s of a wave holds one tile: U wave loads of K (1 KB each, the 16 bytes of lane i
         // at byte 16 i) and U of V.  Every iteration issues one full stage (tiles behind the end
         // are pulled back to the last row), which keeps the count of loads in flight known.
-        constexpr int STAGES = INSTATTN_MHA_LDS_STAGES;
         constexpr int STAGE_BYTES = 2 * U * 1024;
         static_assert(U == 4 || U == 2 || U == 1, "the ds_read sequences below are written for 1, 2 or 4 loads per tensor");
         char (*s_ring)[STAGES][STAGE_BYTES] = (char (*)[STAGES][STAGE_BYTES])s_lds;
@@ -261,9 +260,7 @@ __global__ __launch_bounds__(INSTATTN_MHA_WAVES * 64) void decode_mha_kernel(Dec
         }
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // the stages still in flight land before the wave moves on
         __syncthreads();                                      // the ring is dead in every wave: its LDS takes the partial sums
-    }
-#else
-    {
+    } else {
     // Pool page (paged) of that row; fetched one iteration ahead of its use.
     auto page_of = [&](int tw) { return PAGED ? table[tw >> a.kv.page_shift] : b; };
 
@@ -300,7 +297,6 @@ __global__ __launch_bounds__(INSTATTN_MHA_WAVES * 64) void decode_mha_kernel(Dec
         if (it + 1 < n_it) consume(B, it + 1);
     }
     }
-#endif
 
     // Combine the NG streams of this block.
     float (*s_acc)[D] = (float (*)[D])s_lds;
@@ -346,10 +342,15 @@ static hipError_t launch_mha(const DecodeArgs& a, int batch, hipStream_t stream)
     // XCD gets the same mix of units whatever the sequence lengths are
     dim3 grid(a.num_q_heads, a.num_splits, batch);
     if (a.unit_list) grid = dim3((unsigned)((a.list_len + 7) / 8 * 8 * a.num_q_heads), 1, 1);   // see unit_of_block
-    if (a.kv.page_table)
-        hipLaunchKernelGGL((decode_mha_kernel<D, true>), grid, dim3(INSTATTN_MHA_WAVES * 64), 0, stream, a);
-    else
-        hipLaunchKernelGGL((decode_mha_kernel<D, false>), grid, dim3(INSTATTN_MHA_WAVES * 64), 0, stream, a);
+    const dim3 block(INSTATTN_MHA_WAVES * 64);
+    constexpr int S = INSTATTN_MHA_LDS_STAGES;
+    if (a.staged) {
+        if (a.kv.page_table) hipLaunchKernelGGL((decode_mha_kernel<D, true, S>), grid, block, 0, stream, a);
+        else hipLaunchKernelGGL((decode_mha_kernel<D, false, S>), grid, block, 0, stream, a);
+    } else {
+        if (a.kv.page_table) hipLaunchKernelGGL((decode_mha_kernel<D, true, 0>), grid, block, 0, stream, a);
+        else hipLaunchKernelGGL((decode_mha_kernel<D, false, 0>), grid, block, 0, stream, a);
+    }
     return hipGetLastError();
 }
 

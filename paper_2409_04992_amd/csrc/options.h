@@ -15,6 +15,7 @@ enum Option {
     kOptSparfWide,            // INSTATTN_SPARF_WIDE: 1 / 0 = the one-launch kernel's wide forms always, or never
     kOptSparfSplitTail,       // INSTATTN_SPARF_SPLIT_TAIL: 1 = selection and gather never share a launch
     kOptCompact,              // INSTATTN_COMPACT: 1 / 0 = dense split pass over the compacted unit list always, or never
+    kOptMhaRing,              // INSTATTN_MHA_RING: 1 / 0 = vector-ALU split pass through its LDS ring always, or never
     kNumOptions
 };
 

@@ -30,8 +30,9 @@ static void* dummy(size_t bytes)
     return p;
 }
 
-static void set_all(int chunk, int compact, int rotate, int dist, int three, int wide, int split_tail)
+static void set_all(int chunk, int compact, int rotate, int dist, int three, int wide, int split_tail, int ring = -1)
 {
+    CHECK(instattn_set_option("INSTATTN_MHA_RING", ring) == INSTATTN_OK);
     CHECK(instattn_set_option("INSTATTN_CHUNK", chunk) == INSTATTN_OK);
     CHECK(instattn_set_option("INSTATTN_COMPACT", compact) == INSTATTN_OK);
     CHECK(instattn_set_option("INSTATTN_ROTATE", rotate) == INSTATTN_OK);
@@ -92,7 +93,7 @@ int main()
                     for (int chunk : chunks)
                         for (int compact = -1; compact <= 1; ++compact)
                             for (int paged = 0; paged <= 1; ++paged) {
-                                set_all(chunk, compact, compact == 1, -1, -1, -1, -1);
+                                set_all(chunk, compact, compact == 1, -1, -1, -1, -1, (b + len + paged) % 3 - 1);
                                 const size_t need = instattn_decode_workspace_size(b, h[0], h[1], dim, len);
                                 CHECK(need > 0 && need % 256 == 0);
                                 if (need > kMostWorkspace) continue;

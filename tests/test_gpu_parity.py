@@ -382,6 +382,24 @@ def test_compacted_unit_list_with_a_bound_below_the_lengths(options):
     assert torch.equal(outs[0][2].view(torch.int16), outs[1][2].view(torch.int16))
 
 
+@pytest.mark.parametrize("ring", [0, 1])
+@pytest.mark.parametrize("shape", ["d128", "d64", "paged", "paged_d64", "one_long_row", "short_rows"])
+def test_both_forms_of_the_vector_alu_pass(options, shape, ring):
+    """The host picks the form of the vector-ALU split pass by the size of the launch (tiles
+    through an LDS ring for large ones, two register tiles for small ones); here every shape
+    goes through both, with the append fused in and not, against the oracle: ragged lengths,
+    both layouts and head dims, a row of many units, rows shorter than one tile."""
+    wl = {"d128": W.Workload("form_d128", 3, 5, 5, 128, 3000, seq_len_min=100, seed=301),
+          "d64": W.Workload("form_d64", 3, 5, 5, 64, 3000, seq_len_min=100, seed=302, out_dtype="f32"),
+          "paged": W.Workload("form_paged", 4, 3, 3, 128, 2500, seq_len_min=1, paged=True, seed=303),
+          "paged_d64": W.Workload("form_paged64", 4, 3, 3, 64, 2500, seq_len_min=1, paged=True, page_size=32, seed=304),
+          "one_long_row": W.Workload("form_long", 1, 2, 2, 128, 40000, seed=305),
+          "short_rows": W.Workload("form_short", 6, 4, 4, 128, 40, seq_len_min=1, seed=306)}[shape]
+    options.setenv("INSTATTN_MHA_RING", ring)
+    for fused in (False, True):
+        full_check(wl, fused=fused)
+
+
 def test_dominant_score_large_values_fp16_rounding():
     """One key far along q: the row equals that v row (values of a few units), and
     the fp16 output is within one fp16 ulp of the oracle rounded to fp16."""
