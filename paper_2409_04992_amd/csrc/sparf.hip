@@ -357,23 +357,24 @@ __global__ __launch_bounds__(256) void sparf_hist_kernel(SparfArgs a)
         rs[2] = Z;
     }
     if (idle) return;
-    const Level1 level1(M, xmin);
-    __shared__ uint32_t s_hist[256];
-    s_hist[tid] = 0;
+    const ScoreRange range(M, xmin);
+    const Level1 level1(range);
+    __shared__ uint32_t s_hist[257];                       // slot 0: places behind the last candidate
+    s_hist[1 + tid] = 0;
     __syncthreads();
     // this block's stretches: every nparts-th one (a very long row has more stretches than
     // histograms are kept for it)
     for (int t0 = v.t0; t0 < v.ncand; t0 += a.nparts * kSparfChunk) {
         float xr[STEPS][8];
         own_scores<NT, STEPS>(a.logits + row * a.lpad + t0, v.ncand - t0, xr);
+        mark_candidates<NT, STEPS>(xr, t0, v.ncand, range);
 #pragma unroll
         for (int i = 0; i < STEPS; ++i)
 #pragma unroll
-            for (int e = 0; e < 8; ++e)
-                if (t0 + (i * NT + tid) * 8 + e < v.ncand) atomicAdd(&s_hist[level1(xr[i][e])], 1u);
+            for (int e = 0; e < 8; ++e) atomicAdd(&s_hist[1 + level1(xr[i][e])], 1u);
     }
     __syncthreads();
-    a.hist[(row * a.nparts + part) * 256 + tid] = s_hist[tid];
+    a.hist[(row * a.nparts + part) * 256 + tid] = s_hist[1 + tid];
 }
 
 __global__ __launch_bounds__(256) void sparf_members_kernel(SparfArgs a)
@@ -386,7 +387,9 @@ __global__ __launch_bounds__(256) void sparf_members_kernel(SparfArgs a)
     float xr[STEPS][8];
     own_scores<NT, STEPS>(a.logits + row * a.lpad + v.t0, v.ncand - v.t0, xr);
     const float M = a.rowstat[row * 4], xmin = a.rowstat[row * 4 + 1];
-    const Level1 level1(M, xmin);
+    const ScoreRange range(M, xmin);
+    const Level1 level1(range);
+    mark_candidates<NT, STEPS>(xr, v.t0, v.ncand, range);
 
     __shared__ SelectScratch S;
     __shared__ uint32_t s_keys[kSparfMemberCap];
@@ -400,29 +403,28 @@ __global__ __launch_bounds__(256) void sparf_members_kernel(SparfArgs a)
         total += (h0 + h1) + (h2 + h3);
     }
     for (; c < np; ++c) total += hp[c * 256];
-    S.hist[tid] = total;
+    S.hist(tid) = total;
     if (tid == 0) s_n = s_above = 0;
     __syncthreads();
     if (tid < 64) locate_bin(S, (uint32_t)v.want, tid);
     __syncthreads();
-    const uint32_t bin1 = S.prefix;
+    const int bin1 = (int)S.prefix;
     if (chunk == 0 && tid == 0) {
-        a.state[row * 2] = bin1;
+        a.state[row * 2] = (uint32_t)bin1;
         a.state[row * 2 + 1] = S.remaining;
     }
     uint32_t above = 0;
 #pragma unroll
     for (int i = 0; i < STEPS; ++i)
 #pragma unroll
-        for (int e = 0; e < 8; ++e)
-            if (v.t0 + (i * NT + tid) * 8 + e < v.ncand) {
-                const uint32_t bin = level1(xr[i][e]);
-                above += bin > bin1;
-                if (bin == bin1) {
-                    const uint32_t j = atomicAdd(&s_n, 1u);
-                    if (j < (uint32_t)kSparfMemberCap) s_keys[j] = order_key(xr[i][e]);
-                }
+        for (int e = 0; e < 8; ++e) {                      // places without a candidate: bin -1
+            const int bin = level1(xr[i][e]);
+            above += bin > bin1;
+            if (bin == bin1) {
+                const uint32_t j = atomicAdd(&s_n, 1u);
+                if (j < (uint32_t)kSparfMemberCap) s_keys[j] = order_key(xr[i][e]);
             }
+        }
     above = (uint32_t)wave_sum((float)above);              // at most 32 per lane: exact in fp32
     if ((tid & 63) == 0) atomicAdd(&s_above, above);
     __syncthreads();
@@ -471,17 +473,18 @@ __global__ __launch_bounds__(256) void sparf_compact_kernel(SparfArgs a)
     __shared__ __align__(16) uint32_t s_mkey2[kSparfMemberCap];
     __shared__ uint16_t s_mchunk[kSparfMemberCap];
     __shared__ uint32_t s_gtb, s_eqb;
-    const Level1 level1(M, xmin);
+    const ScoreRange range(M, xmin);
+    const Level1 level1(range);
     const uint32_t rem1 = v.want > 0 ? a.state[row * 2 + 1] : 0u;
     bool one_block = v.want <= 0 || nmem > cap || a.counters[row * 2 + 1] != 0;
     const bool long_list = !one_block && nmem > (uint32_t)kSparfMemberCap;
     uint32_t rem2 = 0, nsub = 0;
     if (long_list) {
         // every block of the head takes the same decisions from the same list
-        S.hist[tid] = 0;
+        S.hist(tid) = 0;
         if (tid == 0) S.nsub = 0;
         __syncthreads();
-        for (uint32_t i = tid; i < nmem; i += NT) atomicAdd(&S.hist[level1.sub(key_score(mem[2 * i]))], 1u);
+        for (uint32_t i = tid; i < nmem; i += NT) atomicAdd(&S.hist((int)level1.sub(key_score(mem[2 * i]))), 1u);
         __syncthreads();
         if (tid < 64) locate_bin(S, rem1, tid);
         __syncthreads();
@@ -515,7 +518,7 @@ __global__ __launch_bounds__(256) void sparf_compact_kernel(SparfArgs a)
     }
     float xr[STEPS][8];
     own_scores<NT, STEPS>(x + v.t0, v.ncand - v.t0, xr);
-    const uint32_t bin1 = a.state[row * 2];
+    mark_candidates<NT, STEPS>(xr, v.t0, v.ncand, range);
 
     if (tid == 0) s_gtb = s_eqb = 0;
     uint32_t thr, rem_eq;
@@ -568,9 +571,8 @@ __global__ __launch_bounds__(256) void sparf_compact_kernel(SparfArgs a)
     uint32_t gt_base = s_gtb, eq_base = s_eqb;
 
     float mass = 0.f;
-    compact_tile<NT, STEPS>(
-        xr, [&](int i, int e) { return level1(xr[i][e]); }, v.t0, v.ncand, bin1, thr, rem_eq, gt_base, eq_base,
-        &S.wave_cnt[0][0], M, sel, (uint32_t)v.want, mass);
+    compact_tile<NT, STEPS>(xr, v.t0, v.ncand, thr, rem_eq, gt_base, eq_base, &S.wave_cnt[0][0], M, sel,
+                            (uint32_t)v.want, mass);
     if (chunk == 0) {
         // step 5: the l most recent positions are always kept
         for (int i = tid; i < v.leff; i += NT) {
@@ -699,7 +701,11 @@ __global__ __launch_bounds__(NT, INSTATTN_SPARF_WAVES_PER_SIMD) void sparf_fused
         if (tid == 0) a.alpha[row] = 0.f;
         return;
     }
-    column_passes<NT, STEPS>(a, b, hk, 0, L, factor, s_q, s_dim, xs);
+    // the new token's score comes from k_new below: when it is the row's last position the
+    // column pass stops in front of it (a row of 2^n + 1 positions then takes no step for
+    // that one position)
+    const int L_cols = fresh && t_new == L - 1 ? L - 1 : L;
+    if (L_cols > 0) column_passes<NT, STEPS>(a, b, hk, 0, L_cols, factor, s_q, s_dim, xs);
     if (fresh && t_new < L && tid == ((t_new >> 3) % NT)) {
         // the score of the new position, from k_new, by the thread that owns it and with
         // the arithmetic of the column pass

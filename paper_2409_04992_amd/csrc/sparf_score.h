@@ -226,10 +226,44 @@ __device__ __forceinline__ void own_scores(const float* x, int L, float (&xr)[ST
     }
 }
 
+// What the selection works on instead of a raw score: the score pulled into the range
+// of the row's numbers, [lo, hi] = [minimum, maximum] cut off at the largest finite
+// float.  A score that is not a number becomes lo, an infinite one the end of the
+// range: the selection then orders every candidate, whatever the inputs held, and a
+// place of a register tile that holds no candidate can be marked by a NaN.
+struct ScoreRange {
+    float lo, hi;
+    __device__ __forceinline__ ScoreRange(float M, float xmin) {
+        hi = fminf(M, 3.4028235e38f);
+        lo = fminf(fmaxf(xmin, -3.4028235e38f), hi);       // a row without a number: lo = hi
+    }
+    __device__ __forceinline__ float operator()(float x) const { return fminf(fmaxf(x, lo), hi); }
+};
+
+// Candidates of a register tile: xr[i][e], the score of position t_off + (i * NT + tid) * 8 + e,
+// is pulled into the range; a NaN marks the places at or behind ncand.
+template <int NT, int STEPS>
+__device__ __forceinline__ void mark_candidates(float (&xr)[STEPS][8], int t_off, int ncand, const ScoreRange& range)
+{
+    const int tid = threadIdx.x;
+#pragma unroll
+    for (int i = 0; i < STEPS; ++i) {
+        const int t = t_off + (i * NT + tid) * 8;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) xr[i][e] = range(xr[i][e]);
+        if (t + 8 > ncand) {                                   // few lanes: the row's end
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (t + e >= ncand) xr[i][e] = __builtin_nanf("");
+        }
+    }
+}
+
 // Softmax statistics of step 4 over the first L positions of such a register
 // tile: maximum, minimum and sum of 2^(x - maximum), to every thread.  Own max,
 // min and sum first, then one block reduction for all three (fixed order).  red
-// holds 48 floats.
+// holds 48 floats.  A step that lies wholly inside the row (block-uniform) takes no
+// per-position tests.
 template <int NT, int STEPS>
 __device__ __forceinline__ void block_stats(const float (&xr)[STEPS][8], int L, float* red, float& M, float& xmin,
                                             float& Z)
@@ -238,7 +272,13 @@ __device__ __forceinline__ void block_stats(const float (&xr)[STEPS][8], int L, 
     float mx = kNegBig, mn = -kNegBig;
 #pragma unroll
     for (int i = 0; i < STEPS; ++i) {
-        if (i * NT * 8 < L) {                                  // block-uniform
+        if ((i + 1) * NT * 8 <= L) {                           // block-uniform
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                mx = fmaxf(mx, xr[i][e]);
+                mn = fminf(mn, xr[i][e]);
+            }
+        } else if (i * NT * 8 < L) {
 #pragma unroll
             for (int e = 0; e < 8; ++e)
                 if ((i * NT + tid) * 8 + e < L) {
@@ -250,7 +290,10 @@ __device__ __forceinline__ void block_stats(const float (&xr)[STEPS][8], int L, 
     float zs = 0.f;
 #pragma unroll
     for (int i = 0; i < STEPS; ++i) {
-        if (i * NT * 8 < L) {
+        if ((i + 1) * NT * 8 <= L) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) zs += fast_exp2(xr[i][e] - mx);
+        } else if (i * NT * 8 < L) {
 #pragma unroll
             for (int e = 0; e < 8; ++e)
                 if ((i * NT + tid) * 8 + e < L) zs += fast_exp2(xr[i][e] - mx);

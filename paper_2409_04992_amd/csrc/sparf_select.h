@@ -13,12 +13,15 @@ namespace {
 constexpr int kSelMembers = 512;     // members of the threshold bin ranked directly
 
 struct SelectScratch {
-    uint32_t hist[256];
+    // level-1 histogram: slot 0 takes the scores that are no candidates (see Level1),
+    // slot 1 + b counts bin b
+    uint32_t slots[260];
     uint32_t prefix, remaining, nmem, nsub;
     alignas(16) uint32_t mem_key[kSelMembers];
     alignas(16) uint32_t mem_key2[kSelMembers];
     uint32_t wave_cnt[8][16];        // per round parity (or step) and wave: rows above the threshold | rows at it << 16
     float red[48];
+    __device__ __forceinline__ uint32_t& hist(int bin) { return slots[bin + 1]; }
 };
 
 // Executed by wave 0 after a histogram is complete: finds the bin that holds the
@@ -27,8 +30,8 @@ struct SelectScratch {
 // Lane i owns bins 4i .. 4i+3; suffix sums over the lanes locate the bin.
 __device__ __forceinline__ void locate_bin(SelectScratch& S, uint32_t remaining, int lane)
 {
-    const uint32_t c0 = S.hist[4 * lane], c1 = S.hist[4 * lane + 1];
-    const uint32_t c2 = S.hist[4 * lane + 2], c3 = S.hist[4 * lane + 3];
+    const uint32_t c0 = S.hist(4 * lane), c1 = S.hist(4 * lane + 1);
+    const uint32_t c2 = S.hist(4 * lane + 2), c3 = S.hist(4 * lane + 3);
     const uint32_t mine = c0 + c1 + c2 + c3;
     uint32_t suffix = mine;                       // inclusive, over lanes >= this one
 #pragma unroll
@@ -51,20 +54,28 @@ __device__ __forceinline__ void locate_bin(SelectScratch& S, uint32_t remaining,
     }
 }
 
-// Level-1 bucket of a score: linear between the row's minimum and maximum,
-// monotone in the score, so every score in a higher bucket is >= every score in a
-// lower one.
+// Level-1 bucket of a candidate (a score inside the row's range, see ScoreRange):
+// linear between the ends of the range, 0 .. 255, monotone in the score (a
+// subtraction, a product with a positive factor, a clamp and a truncation are each
+// monotone), so every score in a higher bucket is >= every score in a lower one.
+// The NaN that marks a place without a candidate gets bucket -1: it is counted
+// nowhere and is a member of no bucket.
 struct Level1 {
-    float M, binscale;
-    __device__ __forceinline__ Level1(float M_, float xmin) : M(M_), binscale(M_ > xmin ? 255.99f / (M_ - xmin) : 0.f) {}
-    __device__ __forceinline__ uint32_t operator()(float v) const {
-        return 255u - (uint32_t)min(255, max(0, (int)((M - v) * binscale)));
+    float lo, scale;
+    __device__ __forceinline__ Level1(const ScoreRange& r) : lo(r.lo) {
+        const float d = r.hi - r.lo;                       // >= 0, may overflow to infinity
+        scale = d > 0.f ? (d < __builtin_inff() ? 255.99f / d : 1e-36f) : 1.f;
     }
+    __device__ __forceinline__ float place(float v) const {
+        // the maximum first: it turns the NaN into -1
+        return fminf(fmaxf((v - lo) * scale, -1.f), 255.99f);
+    }
+    __device__ __forceinline__ int operator()(float v) const { return (int)place(v); }
     // 256 finer buckets inside a level-1 bucket, monotone in the score like the bucket
     __device__ __forceinline__ uint32_t sub(float v) const {
-        const float t = (M - v) * binscale;
-        const float f = t - (float)min(255, max(0, (int)t));
-        return 255u - (uint32_t)min(255, max(0, (int)(f * 256.f)));
+        const float t = place(v);
+        const float f = t - (float)(int)t;
+        return (uint32_t)min(255, max(0, (int)(f * 256.f)));
     }
 };
 
@@ -119,10 +130,10 @@ __device__ __forceinline__ void rank_members(uint32_t* keys, uint32_t* keys2, ui
         rank_directly<NT>(keys, n, remaining, S);
         return;
     }
-    if (tid < 256) S.hist[tid] = 0;
+    if (tid < 256) S.hist(tid) = 0;
     if (tid == 0) S.nsub = 0;
     __syncthreads();
-    for (uint32_t i = tid; i < n; i += NT) atomicAdd(&S.hist[level1.sub(key_score(keys[i]))], 1u);
+    for (uint32_t i = tid; i < n; i += NT) atomicAdd(&S.hist((int)level1.sub(key_score(keys[i]))), 1u);
     __syncthreads();
     if (tid < 64) locate_bin(S, remaining, tid);
     __syncthreads();
@@ -144,34 +155,33 @@ __device__ __forceinline__ void rank_members(uint32_t* keys, uint32_t* keys2, ui
 // holds the threshold: normally a few dozen, which are gathered and ranked against
 // each other directly; if there are more than kSelMembers (e.g. all scores equal)
 // a 4-pass radix select on order-preserving keys takes over.  The outcome: the
-// kept candidates are those in a bin above bin1, those in bin1 with a key above
-// `prefix`, and the first `remaining` (in position order) with exactly that key.
-// for_each(f) calls f(score, its level-1 bin) for every candidate of the calling
-// thread; it is called several times and must visit the same candidates each time.
+// kept candidates are those with a key above `prefix` and the first `remaining`
+// (in position order) with exactly that key.
+// for_each(f) calls f(score) for every place of the calling thread's register tiles
+// (candidates as mark_candidates leaves them: inside the row's range, NaN where a
+// place holds none); it is called several times and must visit the same scores each
+// time.
 template <int NT, class ForEach>
 __device__ __forceinline__ void find_threshold(ForEach&& for_each, int want, const Level1& level1,
-                                               SelectScratch& S, uint32_t& bin1, uint32_t& prefix,
-                                               uint32_t& remaining)
+                                               SelectScratch& S, uint32_t& prefix, uint32_t& remaining)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    bin1 = 0;
     prefix = 0;
     remaining = (uint32_t)want;
     if (want <= 0) return;
     // level 1
-    if (tid < 256) S.hist[tid] = 0;
+    if (tid < 256) S.hist(tid) = 0;
     if (tid == 0) S.nmem = 0;
     __syncthreads();
-    for_each([&](float, uint32_t bin) { atomicAdd(&S.hist[bin], 1u); });
+    for_each([&](float v) { atomicAdd(&S.hist(level1(v)), 1u); });
     __syncthreads();
     if (wave == 0) locate_bin(S, remaining, lane);
     __syncthreads();
-    bin1 = S.prefix;
+    const int b1 = (int)S.prefix;
     remaining = S.remaining;
-    // level 2: gather the members of bin1
-    const uint32_t b1 = bin1;
-    for_each([&](float v, uint32_t bin) {
-        if (bin == b1) {
+    // level 2: gather the members of that bin
+    for_each([&](float v) {
+        if (level1(v) == b1) {
             const uint32_t i = atomicAdd(&S.nmem, 1u);
             if (i < (uint32_t)kSelMembers) S.mem_key[i] = order_key(v);
         }
@@ -186,14 +196,14 @@ __device__ __forceinline__ void find_threshold(ForEach&& for_each, int want, con
     } else {
         for (int shift = 24; shift >= 0; shift -= 8) {
             __syncthreads();
-            if (tid < 256) S.hist[tid] = 0;
+            if (tid < 256) S.hist(tid) = 0;
             __syncthreads();
             const uint32_t hi_mask = shift == 24 ? 0u : (0xFFFFFFFFu << (shift + 8));
             const uint32_t pfx = prefix;
-            for_each([&](float v, uint32_t bin) {
+            for_each([&](float v) {
                 const uint32_t key = order_key(v);
-                if (bin == b1 && (key & hi_mask) == (pfx & hi_mask))
-                    atomicAdd(&S.hist[(key >> shift) & 255u], 1u);
+                if (level1(v) == b1 && (key & hi_mask) == (pfx & hi_mask))
+                    atomicAdd(&S.hist((int)((key >> shift) & 255u)), 1u);
             });
             __syncthreads();
             if (wave == 0) locate_bin(S, remaining, lane);
@@ -204,53 +214,71 @@ __device__ __forceinline__ void find_threshold(ForEach&& for_each, int want, con
     }
 }
 
-// Ordered compaction of one register tile: xr[i][e] is the score of position
-// t_off + (i * NT + tid) * 8 + e, candidates are the positions below ncand.  Writes
-// the kept positions of the tile to their slots of sel and adds their softmax mass.
-// Position order is (i, wave, lane, e): a shuffle scan over the lanes of a wave per
-// step i, the wave totals per step through LDS (step_cnt, STEPS * NT / 64 words),
-// one barrier.  The output slot of a row is (rows above the threshold before it) +
-// min(rows at the threshold before it, number of those still wanted), so ties go
-// to the lower position and the result is deterministic.  gt_base / eq_base count
-// the rows above / at the threshold in earlier tiles and are advanced.
-template <int NT, int STEPS, class BinOf>
-__device__ __forceinline__ void compact_tile(const float (&xr)[STEPS][8], BinOf&& bin_of, int t_off, int ncand,
-                                             uint32_t bin1, uint32_t prefix, uint32_t remaining,
-                                             uint32_t& gt_base, uint32_t& eq_base, uint32_t* step_cnt,
-                                             float M, int32_t* sel, uint32_t room, float& mass)
+// Number of set bits of a wave-wide mask in the lanes below the calling one, added to n.
+__device__ __forceinline__ uint32_t lanes_below(uint64_t mask, uint32_t n) {
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, n));
+}
+
+// Ordered compaction of one register tile: xr[i][e] is the candidate at position
+// t_off + (i * NT + tid) * 8 + e (inside the row's range), or NaN where that position
+// is no candidate.  Writes the kept positions of the tile to their slots of sel and adds
+// their softmax mass.  A score is kept when it lies above the threshold score (the one
+// whose key is `prefix`; comparing the scores orders them as comparing their keys
+// does: the sums the scores come from never give a negative zero), or equals it
+// and fewer than `remaining` such rows lie before it.  Position order is (i, wave,
+// lane, e): per step i and place e one wave-wide compare, whose mask gives every lane
+// the number of kept rows in the lanes below it; the wave totals per step go through
+// LDS (step_cnt, STEPS * NT / 64 words), one barrier.  The output slot of a row is
+// (rows above the threshold before it) + min(rows at the threshold before it, number
+// of those still wanted), so ties go to the lower position and the result is
+// deterministic.  gt_base / eq_base count the rows above / at the threshold in earlier
+// tiles and are advanced.
+template <int NT, int STEPS>
+__device__ __forceinline__ void compact_tile(const float (&xr)[STEPS][8], int t_off, int ncand, uint32_t prefix,
+                                             uint32_t remaining, uint32_t& gt_base, uint32_t& eq_base,
+                                             uint32_t* step_cnt, float M, int32_t* sel, uint32_t room, float& mass)
 {
     constexpr int NW = NT / 64;
     typedef typename std::conditional<(STEPS > 4), uint64_t, uint32_t>::type bits_t;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    // the score whose key is the threshold key (inverse of order_key)
-    const float mass_at_key = fast_exp2(key_score(prefix) - M);
+    const float thr = key_score(prefix);                   // the score whose key is the threshold key
+    const float mass_at_key = fast_exp2(thr - M);
     bits_t gtbits = 0, eqbits = 0;                         // bit 8i + e
-    uint32_t excl[STEPS];                                  // kept before this lane in its wave, per step
+    uint32_t excl[STEPS];                                  // kept in the lanes below this one, per step (halves)
 #pragma unroll
     for (int i = 0; i < STEPS; ++i) {
-        uint32_t c = 0;
+        uint32_t below = 0, total = 0;                     // halves: at most 512 each
         if (t_off + i * NT * 8 < ncand) {                  // block-uniform
+            uint32_t g8 = 0;
+            uint64_t any_eq = 0;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const bool valid = t_off + (i * NT + tid) * 8 + e < ncand;
-                const uint32_t b1 = bin_of(i, e);
-                const uint32_t key = order_key(xr[i][e]);
-                const bool gt = valid && (b1 > bin1 || (b1 == bin1 && key > prefix));
-                const bool eq = valid && b1 == bin1 && key == prefix;
-                gtbits |= (bits_t)gt << (8 * i + e);
-                eqbits |= (bits_t)eq << (8 * i + e);
-                c += (uint32_t)gt + ((uint32_t)eq << 16);
-                if (gt) mass += fast_exp2(xr[i][e] - M);   // here, where the score is at hand in a register
+                const bool gt = xr[i][e] > thr;
+                const uint64_t m = __ballot(gt);
+                below = lanes_below(m, below);
+                total += (uint32_t)__popcll(m);
+                g8 |= gt ? 1u << e : 0u;
+                mass += gt ? fast_exp2(xr[i][e] - M) : 0.f;
+                any_eq |= __ballot(xr[i][e] == thr);
+            }
+            gtbits |= (bits_t)g8 << (8 * i);
+            if (any_eq != 0) {                             // wave-uniform; few waves hold a row at the threshold
+                uint32_t e8 = 0, eq_below = 0, eq_total = 0;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const bool eq = xr[i][e] == thr;
+                    const uint64_t m = __ballot(eq);
+                    eq_below = lanes_below(m, eq_below);
+                    eq_total += (uint32_t)__popcll(m);
+                    e8 |= eq ? 1u << e : 0u;
+                }
+                eqbits |= (bits_t)e8 << (8 * i);
+                below |= eq_below << 16;
+                total |= eq_total << 16;
             }
         }
-        uint32_t incl = c;                                 // 16-bit halves: at most 512 each
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const uint32_t o = __shfl_up(incl, d, 64);
-            if (lane >= d) incl += o;
-        }
-        excl[i] = incl - c;
-        if (lane == 63) step_cnt[i * NW + wave] = incl;
+        excl[i] = below;
+        if (lane == 0) step_cnt[i * NW + wave] = total;
     }
     __syncthreads();
     uint32_t run = 0;                                      // halves: at most 65535 each in a tile
@@ -263,7 +291,7 @@ __device__ __forceinline__ void compact_tile(const float (&xr)[STEPS][8], BinOf&
             run += step_cnt[i * NW + w];
         }
         const uint32_t gb = gt_base + ((mine + excl[i]) & 0xFFFFu), eb = eq_base + ((mine + excl[i]) >> 16);
-        // the few flagged slots of this lane, in position order
+        // the few flagged places of this lane, in position order
         const uint32_t g8 = (uint32_t)(gtbits >> (8 * i)) & 0xFFu, e8 = (uint32_t)(eqbits >> (8 * i)) & 0xFFu;
         uint32_t todo = g8 | e8;
         while (todo) {
@@ -302,22 +330,26 @@ __device__ __forceinline__ float select_rows(const float* x, int L, int k, int l
     const int leff = min(l, keff);
     const int want = keff - leff;          // rows to pick among the candidates
     const int ncand = L - leff;            // candidates: positions [0, ncand)
-    const Level1 level1(M, xmin);
+    const ScoreRange range(M, xmin);
+    const Level1 level1(range);
 
-    uint32_t bin1, prefix, remaining;
+    uint32_t prefix, remaining;
     find_threshold<NT>(
         [&](auto&& f) {
             for (int t_off = 0; t_off < ncand; t_off += TILE) {
                 float xr[STEPS][8];
                 own_scores<NT, STEPS>(x + t_off, ncand - t_off, xr);
+                mark_candidates<NT, STEPS>(xr, t_off, ncand, range);
 #pragma unroll
-                for (int i = 0; i < STEPS; ++i)
+                for (int i = 0; i < STEPS; ++i) {
+                    if (t_off + i * NT * 8 < ncand) {          // block-uniform
 #pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        if (t_off + (i * NT + tid) * 8 + e < ncand) f(xr[i][e], level1(xr[i][e]));
+                        for (int e = 0; e < 8; ++e) f(xr[i][e]);
+                    }
+                }
             }
         },
-        want, level1, S, bin1, prefix, remaining);
+        want, level1, S, prefix, remaining);
 
     float mass = 0.f;
     uint32_t gt_base = 0, eq_base = 0;
@@ -325,9 +357,9 @@ __device__ __forceinline__ float select_rows(const float* x, int L, int k, int l
     for (int t_off = 0; want > 0 && t_off < ncand; t_off += TILE, parity ^= 1) {
         float xr[STEPS][8];
         own_scores<NT, STEPS>(x + t_off, ncand - t_off, xr);
-        compact_tile<NT, STEPS>(
-            xr, [&](int i, int e) { return level1(xr[i][e]); }, t_off, ncand, bin1, prefix, remaining, gt_base,
-            eq_base, &S.wave_cnt[parity * 4][0], M, sel, (uint32_t)want, mass);
+        mark_candidates<NT, STEPS>(xr, t_off, ncand, range);
+        compact_tile<NT, STEPS>(xr, t_off, ncand, prefix, remaining, gt_base, eq_base, &S.wave_cnt[parity * 4][0], M,
+                                sel, (uint32_t)want, mass);
     }
     // step 5: the l most recent positions are always kept
     for (int i = tid; i < leff; i += NT) {
@@ -340,11 +372,11 @@ __device__ __forceinline__ float select_rows(const float* x, int L, int k, int l
 
 // The same for a row of at most STEPS * NT * 8 positions whose scores the threads
 // hold in registers already: xr[i][e] is the score of position (i * NT + tid) * 8 + e
-// (what the column pass gave this thread); xs holds the same scores in memory.
+// (what the column pass gave this thread); xs holds the same scores in memory.  xr is
+// turned into candidates in place.
 template <int NT, int STEPS>
-__device__ __forceinline__ float select_rows_reg(const float (&xr)[STEPS][8], const float* xs, int L, int k,
-                                                 int l, float M, float xmin, float Z, int32_t* sel,
-                                                 SelectScratch& S)
+__device__ __forceinline__ float select_rows_reg(float (&xr)[STEPS][8], const float* xs, int L, int k, int l,
+                                                 float M, float xmin, float Z, int32_t* sel, SelectScratch& S)
 {
     static_assert(STEPS * (NT / 64) <= 128 && STEPS * 8 <= 64, "counts and flag words");
     const int tid = threadIdx.x;
@@ -352,46 +384,28 @@ __device__ __forceinline__ float select_rows_reg(const float (&xr)[STEPS][8], co
     const int leff = min(l, keff);
     const int want = keff - leff;
     const int ncand = L - leff;
-    const Level1 level1(M, xmin);
+    const ScoreRange range(M, xmin);
+    const Level1 level1(range);
+    mark_candidates<NT, STEPS>(xr, 0, ncand, range);
 
-    // level-1 bins of the own scores, one byte each, computed once (where the register
-    // budget allows: with 40 or 64 scores per thread they are recomputed instead)
-    constexpr bool kCacheBins = STEPS <= 4;
-    uint32_t bins[kCacheBins ? STEPS : 1][2];
-    if constexpr (kCacheBins) {
-#pragma unroll
-        for (int i = 0; i < STEPS; ++i) {
-            bins[i][0] = bins[i][1] = 0;
-            if (want > 0 && i * NT * 8 < ncand) {              // block-uniform
-#pragma unroll
-                for (int e = 0; e < 8; ++e) bins[i][e >> 2] |= level1(xr[i][e]) << (8 * (e & 3));
-            }
-        }
-    }
-    auto bin_of = [&](int i, int e) -> uint32_t {
-        if constexpr (kCacheBins) return (bins[i][e >> 2] >> (8 * (e & 3))) & 255u;
-        else return level1(xr[i][e]);
-    };
-
-    uint32_t bin1, prefix, remaining;
+    uint32_t prefix, remaining;
     find_threshold<NT>(
         [&](auto&& f) {
 #pragma unroll
             for (int i = 0; i < STEPS; ++i) {
                 if (i * NT * 8 < ncand) {
 #pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        if ((i * NT + tid) * 8 + e < ncand) f(xr[i][e], bin_of(i, e));
+                    for (int e = 0; e < 8; ++e) f(xr[i][e]);
                 }
             }
         },
-        want, level1, S, bin1, prefix, remaining);
+        want, level1, S, prefix, remaining);
 
     float mass = 0.f;
     if (want > 0) {
         uint32_t gt_base = 0, eq_base = 0;
-        compact_tile<NT, STEPS>(xr, bin_of, 0, ncand, bin1, prefix, remaining, gt_base, eq_base, &S.wave_cnt[0][0],
-                                M, sel, (uint32_t)want, mass);
+        compact_tile<NT, STEPS>(xr, 0, ncand, prefix, remaining, gt_base, eq_base, &S.wave_cnt[0][0], M, sel,
+                                (uint32_t)want, mass);
     }
     // step 5: the l most recent positions are always kept
     for (int i = tid; i < leff; i += NT) {
