@@ -84,18 +84,21 @@ SparfPlan plan_sparf(const Options& opt, int batch, int num_q_heads, int num_kv_
 {
     SparfPlan p = {};
     const int64_t heads = (int64_t)batch * num_q_heads;
-    const int nchunk = (max_seq_len + kSparfChunk - 1) / kSparfChunk;
-    // One block per head selects well when there are heads enough to fill the chip or
-    // the rows are short; few heads with long rows spread each head's selection over
-    // its stretches (three launches).  Measured: one block takes about max_len / 1100
-    // us per round of 256 heads, the distributed form 24 us + 0.015 us per block.  With
-    // many heads the two come close (640 heads x 128K: 1.31 ms against 1.48 ms for the
-    // step; 2560 heads x 32K: 1.30 against 1.28), so there the estimate must win clearly.
+    // One block per head, or the selection of a head spread over its stretches (three
+    // launches)?  From step times measured with either form forced (40 to 1280 heads, rows
+    // of 20K to 256K positions): up to 40K positions one block per head is ahead for any
+    // number of heads (by 2 to 15 %); from 96K on the spread form is (40 heads x 128K: 111
+    // against 205 us, 640 heads x 128K: 1.31 against 1.48 ms); in between the spread form
+    // wins with few heads, which leave most of the chip idle otherwise (80 heads x 64K:
+    // 104 against 111 us), and with many, whose blocks come in several rounds (640 heads x
+    // 64K: 616 against 623 us), but not with about one round of them (160 heads x 64K: 190
+    // against 182 us).
     {
-        const double one_block = max_seq_len / 1100.0 * (double)((heads + 255) / 256);
-        const double spread = (24.0 + 0.015 * (double)heads * nchunk) * (heads <= 512 ? 1.0 : 1.3);
+        const bool few = heads <= kSparfSpreadFewHeads, many = heads > kSparfSpreadManyHeads;
         const int forced = opt[kOptSparfDistributed];
-        p.distributed = forced >= 0 ? forced == 1 : (max_seq_len > 2 * kSparfChunk && spread < one_block);
+        p.distributed = forced >= 0 ? forced == 1
+                                    : max_seq_len >= kSparfSpreadAlwaysLen ||
+                                          (max_seq_len > kSparfSpreadMinLen && (few || many));
     }
     // Slices of a head's kept rows for the attend kernel: enough blocks to fill the
     // chip when there are few heads, none smaller than 256 rows.

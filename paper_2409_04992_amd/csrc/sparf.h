@@ -98,5 +98,12 @@ __host__ __device__ constexpr int sparf_fused_lds_floats(int max_len, int ng, in
     return scores > least ? scores : least;
 }
 constexpr int kSparfTailMaxLen = 65536;   // rows below this length can be selected and gathered by one block
+// Rows up to this length are selected by one block per head, rows from kSparfSpreadAlwaysLen on by one
+// block per stretch; in between by one block per stretch when there are at most kSparfSpreadFewHeads
+// heads or more than kSparfSpreadManyHeads.
+constexpr int kSparfSpreadMinLen = 5 * kSparfChunk;
+constexpr int kSparfSpreadAlwaysLen = 12 * kSparfChunk;
+constexpr int kSparfSpreadFewHeads = 128;
+constexpr int kSparfSpreadManyHeads = 512;
 
 }  // namespace instattn

@@ -391,20 +391,32 @@ def test_sparf_plan_of_the_measured_shapes(no_sparf_env):
     # 64 ragged sequences up to 16K: the 512-thread form
     p = B.sparf_plan(64, 40, 40, 128, 16385, 1024, with_append=True)
     assert p["launches"] == 1 and p["one_launch_threads"] == 512 and p["append_fused"]
-    # 8 x 40 heads x 32K: score pass (which stores the new token), selection spread over the
-    # stretches, sliced gather, merge
+    # 8 x 40 heads x 32K: score pass (which stores the new token), one block per head selects,
+    # sliced gather, merge
     p = B.sparf_plan(8, 40, 40, 128, 32769, 2048, with_append=True)
-    assert p == {"launches": 6, "one_launch_threads": 0, "append_fused": True, "selection": 2,
+    assert p == {"launches": 4, "one_launch_threads": 0, "append_fused": True, "selection": 1,
                  "select_and_gather": False, "slices": 4}
     # the same with grouped queries: the append is a launch of its own
     p = B.sparf_plan(8, 40, 8, 128, 32769, 2048, with_append=True)
-    assert p["launches"] == 7 and not p["append_fused"]
-    # 1 x 40 heads x 128K
+    assert p["launches"] == 5 and not p["append_fused"]
+    # 1 x 40 heads x 128K: selection spread over the stretches
     p = B.sparf_plan(1, 40, 40, 128, 131073, 8192)
     assert p["selection"] == 2 and p["slices"] == 8 and p["launches"] == 6
-    # many heads: spread when the estimate wins clearly (16 x 40 x 128K), else one block per head
-    assert B.sparf_plan(16, 40, 40, 128, 131073, 8192)["selection"] == 2
-    assert B.sparf_plan(16, 40, 40, 128, 32769, 2048)["selection"] == 1
+
+
+def test_sparf_plan_one_block_per_head_or_one_per_stretch(no_sparf_env):
+    sel = lambda batch, L: B.sparf_plan(batch, 40, 40, 128, L, L // 16)["selection"]
+    # up to 40K positions one block per head, whatever the number of heads
+    for batch in (1, 2, 8, 16, 32):
+        assert sel(batch, 32769) == 1 and sel(batch, 40960) == 1
+    # from 96K on one block per stretch
+    for batch in (1, 4, 16):
+        assert sel(batch, 98304) == 2 and sel(batch, 262145) == 2
+    assert sel(4, 98303) == 1
+    # in between: few heads (at most 128) and many (more than 512) spread, about one round of blocks does not
+    assert sel(1, 40961) == 2 and sel(2, 65537) == 2 and sel(3, 65537) == 2
+    assert sel(4, 65537) == 1 and sel(8, 65537) == 1 and sel(12, 65537) == 1
+    assert sel(13, 65537) == 2 and sel(16, 65537) == 2 and sel(32, 65537) == 2
 
 
 def test_sparf_plan_limits_of_the_one_launch_kernel(no_sparf_env):
