@@ -267,17 +267,17 @@ int instattn_decode_static(const void* q, const instattn_kv_desc* kv, const int3
  * SparF attention (Algorithm 1): decode attention from a fraction of the cache.
  *
  * Per query head: keep the r components of q with the largest magnitude, score
- * every position from those r columns of K alone (softmax with the temperature
- * of step 4), keep the k best-scored positions, the l most recent always among
- * them (steps 5-6), let alpha be their share of the approximate softmax (step 7),
- * run exact softmax attention over the kept rows (step 10) and return
- *     out = alpha * attention_over_kept_rows + (1 - alpha) * mean(V[0:L_b])   (step 11).
+ * every position from those r columns of K alone (softmax with the algorithm's
+ * temperature), keep the k best-scored positions, the l most recent always among
+ * them, let alpha be their share of the approximate softmax, run exact softmax
+ * attention over the kept rows and return
+ *     out = alpha * attention_over_kept_rows + (1 - alpha) * mean(V[0:L_b]).
  * 1/sqrt(d_h) enters through `scale` as in the dense path.  Ties in either top-k
  * go to the lower index.  k and l are cut off at L_b, l at k.  With k >= L_b the
  * result equals instattn_decode.  Both cache layouts, head_dim 64 or 128.
  *
  * The column reads need K stored a second time, component-major (the paper's
- * hidden-embedding-indexed copy, Sec. IV-C), and step 11 needs the running sum
+ * hidden-embedding-indexed copy, Sec. IV-C), and the blend needs the running sum
  * of V; both live in caller-owned device memory described by instattn_sparf_aux:
  *   kt   : fp16, 16-byte aligned, strides multiples of 8.
  *          contiguous (page_size 0, page_table NULL): element (b, hk, d, t) at
@@ -367,20 +367,21 @@ size_t instattn_sparf_workspace_size(int batch, int num_q_heads, int head_dim, i
  *   sel_rows  : device [batch][num_q_heads][k] int32 or NULL: receives the kept
  *               positions of every head in ascending order (min(k, L_b) entries
  *               are written per head)
- *   alpha     : device [batch][num_q_heads] fp32 or NULL: receives step 7's alpha
+ *   alpha     : device [batch][num_q_heads] fp32 or NULL: receives alpha, the kept share
  * L_b <= 0 gives a zero row (alpha 0).  One launch when max_seq_len <= 8192, or
  * <= 18432 with at least 80 (sequence, query head) pairs, or <= 36864 with 96 to
  * 256 of them (one block per query head keeps the scores in LDS; 256, 512 or 1024
  * threads), otherwise two to six: column
  * scores; then either one launch in which a block per head selects and gathers
  * (many heads, rows below 65536), or selection (one launch with a block per head,
- * or three with a block per 8192 scores when there are few heads with long rows),
+ * or three with a block per 8192 scores for rows of 96K positions or more and, from
+ * 40K on, for at most 128 or more than 512 heads),
  * attention over the kept rows, and a launch that combines the slices when a
  * head's kept rows are cut up.
  * A paged cache is limited to num_pages*page_size < 2^31 rows here, max_seq_len to
  * 65535 x 8192 (INSTATTN_ERR_UNSUPPORTED beyond).  max_seq_len must bound every L_b: a longer
  * sequence is cut off at max_seq_len as everywhere (memory-safe), but aux.vsum still
- * holds the sum of all its rows, so the mean of V that step 11 blends in is then not
+ * holds the sum of all its rows, so the mean of V that is blended in is then not
  * the mean of the rows attended.
  */
 int instattn_sparf_decode(const void* q, const instattn_kv_desc* kv, const instattn_sparf_aux* aux,

@@ -1,34 +1,33 @@
 // SparF attention (Algorithm 1 of the paper) on the HBM-resident cache.
 //
-// The algorithm reads r of the d_h columns of K to approximate every score
-// (steps 1-4), keeps the k best positions plus the l most recent ones (steps 5-7)
-// and runs exact attention over those rows only, blended with the mean of V
-// (steps 10-11).  On flash the loads are page-wise with a filter behind them
-// (steps 2-3, 8-9); in HBM a 256-byte row or a run of 8 positions of one column
+// The algorithm reads r of the d_h columns of K to approximate every score, keeps
+// the k best positions plus the l most recent ones and runs exact attention over
+// those rows only, blended with the mean of V.  On flash its loads are page-wise
+// with a filter behind them; in HBM a 256-byte row or a run of 8 positions of one column
 // is already an efficient access, so the loads are exact: only selected columns
 // and selected rows are read.
 //
-// Kernels (the device functions they are made of are in sparf_score.h, steps 1-4;
-// sparf_select.h, steps 5-7; sparf_gather.h, steps 10-11):
+// Kernels (the device functions they are made of are in sparf_score.h, approximate
+// scores; sparf_select.h, selection; sparf_gather.h, attention over the kept rows):
 //   sparf_fused_kernel    the whole algorithm in one launch, one block per query
 //                         head, scores kept in LDS: 256 threads for rows of at most
 //                         8192 positions, 512 up to 18432, 1024 up to 36864.
 // Longer rows (or too few heads for the wider forms):
-//   sparf_logits_kernel   steps 1-4 up to the softmax normaliser: blocks walk units
+//   sparf_logits_kernel   approximate scores up to the softmax normaliser: blocks walk units
 //                         of 2048 positions of one query head; reads the component-
 //                         major K copy, writes fp32 scores (log2 domain) and every
 //                         wave's max / sum / min.
-//   sparf_select_attend_kernel  steps 4 (normaliser) to 11: one block per query head
+//   sparf_select_attend_kernel  everything behind the scores: one block per query head
 //                         selects (scores in registers) and gathers the rows it
 //                         kept; taken when the kept rows of a head are not sliced.
-//   sparf_select_kernel   steps 4 (normaliser), 5-7: one block per query head; an
+//   sparf_select_kernel   normaliser and selection: one block per query head; an
 //                         exact two-level selection over the scores (held in
 //                         registers for rows below 65536), ordered compaction
 //                         (ties towards the lower position), alpha.
 //   sparf_hist_kernel,    the same selection for few heads with long rows, one block
 //   sparf_members_kernel, per stretch of 8192 scores in three launches (described
 //   sparf_compact_kernel  with the kernels).
-//   sparf_attend_kernel   steps 10-11: one block per query head (or per slice of its
+//   sparf_attend_kernel   attention and blend: one block per query head (or per slice of its
 //                         kept rows, then sparf_merge_kernel combines the slices)
 //                         gathers the selected rows of K and V (online softmax as in
 //                         the dense vector-ALU kernel) and blends with the mean of V.
@@ -55,7 +54,7 @@
 namespace instattn {
 
 // ---------------------------------------------------------------------------
-// Steps 1-4 (without the normaliser), long rows.  A block of 256 threads ranks the
+// Approximate scores (without the normaliser), long rows.  A block of 256 threads ranks the
 // query once and walks units of 2048 positions of its head, every gridDim.y-th one;
 // a thread owns 8 consecutive positions of a unit and adds up the kept columns in
 // rank order, 8 columns per step (the same sums, in the same order, as the column
@@ -276,7 +275,7 @@ __device__ __forceinline__ void row_stats(const SparfArgs& a, int64_t row, int L
     xmin = -wave_max(-mn);
 }
 
-// Steps 4 (normaliser) to 7, long rows: one block per head over the stored scores.
+// Normaliser and selection, long rows: one block per head over the stored scores.
 // STEPS > 0: the row has at most NT * 8 * STEPS positions, every thread reads its
 // scores once and keeps them in registers; STEPS == 0: the selection passes over
 // the workspace.
@@ -303,7 +302,7 @@ __global__ __launch_bounds__(NT) void sparf_select_kernel(SparfArgs a)
 }
 
 // ---------------------------------------------------------------------------
-// Steps 4 (normaliser) to 7 for few heads with long rows: the selection of a head
+// Normaliser and selection for few heads with long rows: the selection of a head
 // is spread over one block of 256 threads per stretch of 8192 scores (held in
 // registers), in three launches that pass small integers through the workspace:
 //   sparf_hist_kernel     level-1 histogram of every stretch;
@@ -574,7 +573,7 @@ __global__ __launch_bounds__(256) void sparf_compact_kernel(SparfArgs a)
     compact_tile<NT, STEPS>(xr, v.t0, v.ncand, thr, rem_eq, gt_base, eq_base, &S.wave_cnt[0][0], M, sel,
                             (uint32_t)v.want, mass);
     if (chunk == 0) {
-        // step 5: the l most recent positions are always kept
+        // the l most recent positions are always kept
         for (int i = tid; i < v.leff; i += NT) {
             const int t = v.ncand + i;
             sel[v.want + i] = t;
@@ -582,10 +581,10 @@ __global__ __launch_bounds__(256) void sparf_compact_kernel(SparfArgs a)
         }
     }
     mass = block_sum(mass, S.red);
-    if (tid == 0) share[chunk] = mass;                      // step 7 is finished by the attend kernel
+    if (tid == 0) share[chunk] = mass;                      // alpha is finished by the attend kernel
 }
 
-// Step 7 after the distributed selection: the stretches' shares in stretch order.
+// Alpha after the distributed selection: the stretches' shares in stretch order.
 __device__ __forceinline__ float distributed_alpha(const SparfArgs& a, int64_t row, int L)
 {
     const float Z = a.rowstat[row * 4 + 2];
@@ -594,7 +593,7 @@ __device__ __forceinline__ float distributed_alpha(const SparfArgs& a, int64_t r
     return kept / Z;
 }
 
-// Steps 10-11, long rows: one block per query head and slice of its kept rows.
+// Attention and blend, long rows: one block per query head and slice of its kept rows.
 // With one slice the block writes the output row; with more, each writes its
 // share and sparf_merge_kernel finishes (few heads with many kept rows would
 // otherwise leave most of the chip idle).
@@ -628,7 +627,7 @@ __global__ __launch_bounds__(kSparfAttendWaves * 64) void sparf_attend_kernel(Sp
                                       kSparfAttendIds, s_acc, s_m, s_l);
 }
 
-// Combines the slices of a head (steps 10-11 finished): one thread per output dim.
+// Combines the slices of a head (attention and blend finished): one thread per output dim.
 template <int D>
 __global__ __launch_bounds__(D) void sparf_merge_kernel(SparfArgs a)
 {
@@ -685,7 +684,7 @@ __global__ __launch_bounds__(NT, INSTATTN_SPARF_WAVES_PER_SIMD) void sparf_fused
     float* s_m = xs + ids_cap + NG * D;
     float* s_l = s_m + NG;
 
-    // steps 1-4; the length is not needed before the column pass, so its load and
+    // approximate scores; the length is not needed before the column pass, so its load and
     // the load of q are in flight together
     const int L_raw = a.seq_lens[b];
     // Fused append (one query head per KV head only: this block is the only reader
@@ -717,18 +716,18 @@ __global__ __launch_bounds__(NT, INSTATTN_SPARF_WAVES_PER_SIMD) void sparf_fused
         }
         xs[t_new] = x;
     }
-    // the thread's own scores stay in registers for the rest of steps 4-7
+    // the thread's own scores stay in registers for the statistics and the selection
     float xr[STEPS][8];
     own_scores<NT, STEPS>(xs, L, xr);
     float M, xmin, Z;
     block_stats<NT, STEPS>(xr, L, S.red, M, xmin, Z);
 
-    // steps 5-7
+    // selection
     int32_t* sel = a.sel + row * a.k;
     const float alpha = select_rows_reg<NT, STEPS>(xr, xs, L, a.k, a.l, M, xmin, Z, sel, S);
     if (tid == 0) a.alpha[row] = alpha;
 
-    // steps 10-11; the scores are dead, their LDS takes the row ids (the barrier
+    // attention and blend; the scores are dead, their LDS takes the row ids (the barrier
     // in front of that also makes the kept positions visible to the whole block)
     attend_rows<D, NT / 64>(a, b, h, L, 0, min(a.k, L), sel, alpha, nullptr, (int32_t*)xs, ids_cap, s_acc, s_m, s_l,
                             fresh, t_new);
@@ -736,7 +735,7 @@ __global__ __launch_bounds__(NT, INSTATTN_SPARF_WAVES_PER_SIMD) void sparf_fused
 }
 
 // ---------------------------------------------------------------------------
-// Steps 4 (normaliser) to 11, long rows, one block per head: the selection of
+// Everything behind the scores, long rows, one block per head: the selection of
 // sparf_select_kernel on register-resident scores, then the same block gathers the
 // rows it kept.  With many heads the blocks drift apart, and the latency-bound
 // selection of some overlaps the memory-bound gather of others.

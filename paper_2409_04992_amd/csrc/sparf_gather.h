@@ -1,4 +1,4 @@
-// SparF device code, steps 10-11 of Algorithm 1: attention over the kept rows, blend
+// SparF device code, the end of Algorithm 1: attention over the kept rows, blend
 // with the mean of V; and the store of a new token's components.
 #pragma once
 
@@ -9,7 +9,7 @@ namespace instattn {
 namespace {
 
 
-// Steps 10-11 for one head over the n kept rows listed in sel, by WAVES waves:
+// Attention and blend for one head over the n kept rows listed in sel, by WAVES waves:
 // 16 (or 8) lanes read a row, every row group runs its own online softmax, the
 // groups are combined in LDS, the result is blended with the mean of V.
 // The kept positions are first turned into row ids in LDS (`ids`, room for
@@ -146,7 +146,7 @@ __device__ __forceinline__ void attend_rows(const SparfArgs& a, int b, int h, in
             return;
         }
         o /= lsum;
-        // step 11: alpha * (attention over the kept rows) + (1 - alpha) * mean of V
+        // the blend: alpha * (attention over the kept rows) + (1 - alpha) * mean of V
         const int64_t vi = ((int64_t)b * a.num_kv_heads + hk) * D + tid;
         float vs = a.aux.vsum[vi];
         if (fresh) vs += (float)a.v_new[vi];

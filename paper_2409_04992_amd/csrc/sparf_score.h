@@ -1,4 +1,4 @@
-// SparF device code, steps 1-4 of Algorithm 1: reductions, ranking of the query's
+// SparF device code, the approximate scores of Algorithm 1: reductions, ranking of the query's
 // components, the column pass over the component-major K copy, softmax statistics.
 #pragma once
 
@@ -61,7 +61,7 @@ __device__ __forceinline__ uint32_t order_key(float x) {
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-// Step 1 and the temperature of step 4.  Leaves q (fp32) in s_q and the components
+// The kept components and the temperature of the approximate softmax.  Leaves q (fp32) in s_q and the components
 // ordered by decreasing |q| (ties towards the lower index) in s_dim; returns the
 // factor that turns a column dot product into a log2-domain score.  Needs at least
 // head_dim threads and is called by the whole block; `red` holds 32 floats and is
@@ -78,7 +78,7 @@ __device__ __forceinline__ float prepare_query(const SparfArgs& a, int64_t row, 
         const float qd = (float)qh;
         s_q[tid] = qd;
         mine = fabsf(qd);
-        // one integer per component that orders them as step 1 wants: by magnitude (the
+        // one integer per component that orders them as the algorithm wants: by magnitude (the
         // fp16 bit pattern without its sign is monotone in it), ties to the lower index
         key = ((uint32_t)(__builtin_bit_cast(uint16_t, qh) & 0x7FFFu) << 8) | (uint32_t)(255 - tid);
         s_key[tid] = key;
@@ -115,7 +115,7 @@ __device__ __forceinline__ float prepare_query(const SparfArgs& a, int64_t row, 
     return rho > 0.f ? a.scale_log2 / sqrtf(rho) : 0.f;
 }
 
-// Column pass of a whole row by one block (steps 2-4 without the softmax): adds
+// Column pass of a whole row by one block (the approximate scores, without the softmax): adds
 // to xs[t], t < L, the contribution of CG kept columns, the ones ranked
 // j0 .. j0+CG-1, for the L positions that start at t_base (a multiple of 8).  The columns' offsets and the q components are the same for
 // every lane and are kept in scalar registers; a thread takes 8 consecutive
@@ -259,7 +259,7 @@ __device__ __forceinline__ void mark_candidates(float (&xr)[STEPS][8], int t_off
     }
 }
 
-// Softmax statistics of step 4 over the first L positions of such a register
+// Statistics of the approximate softmax over the first L positions of such a register
 // tile: maximum, minimum and sum of 2^(x - maximum), to every thread.  Own max,
 // min and sum first, then one block reduction for all three (fixed order).  red
 // holds 48 floats.  A step that lies wholly inside the row (block-uniform) takes no

@@ -1,4 +1,4 @@
-// SparF device code, steps 5-7 of Algorithm 1: exact two-level selection of the k best
+// SparF device code, the selection of Algorithm 1: exact two-level selection of the k best
 // positions, ordered compaction, the kept share of the approximate softmax.
 #pragma once
 
@@ -314,7 +314,7 @@ __device__ __forceinline__ void compact_tile(const float (&xr)[STEPS][8], int t_
     eq_base += run >> 16;
 }
 
-// Steps 5-7 for one head of any length: x[0..L) are the log2-domain scores in
+// The selection for one head of any length: x[0..L) are the log2-domain scores in
 // global memory, M their maximum, xmin their minimum and Z the sum of 2^(x - M).
 // Writes the kept positions in ascending order to sel and returns alpha to every
 // thread.  The row goes through register tiles of NT * 32 positions (two 128-bit
@@ -361,13 +361,13 @@ __device__ __forceinline__ float select_rows(const float* x, int L, int k, int l
         compact_tile<NT, STEPS>(xr, t_off, ncand, prefix, remaining, gt_base, eq_base, &S.wave_cnt[parity * 4][0], M,
                                 sel, (uint32_t)want, mass);
     }
-    // step 5: the l most recent positions are always kept
+    // the l most recent positions are always kept
     for (int i = tid; i < leff; i += NT) {
         const int t = ncand + i;
         sel[want + i] = t;
         mass += fast_exp2(x[t] - M);
     }
-    return block_sum(mass, S.red) / Z;     // step 7
+    return block_sum(mass, S.red) / Z;     // alpha: the kept share of the approximate softmax
 }
 
 // The same for a row of at most STEPS * NT * 8 positions whose scores the threads
@@ -407,13 +407,13 @@ __device__ __forceinline__ float select_rows_reg(float (&xr)[STEPS][8], const fl
         compact_tile<NT, STEPS>(xr, 0, ncand, prefix, remaining, gt_base, eq_base, &S.wave_cnt[0][0], M, sel,
                                 (uint32_t)want, mass);
     }
-    // step 5: the l most recent positions are always kept
+    // the l most recent positions are always kept
     for (int i = tid; i < leff; i += NT) {
         const int t = ncand + i;
         sel[want + i] = t;
         mass += fast_exp2(xs[t] - M);
     }
-    return block_sum(mass, S.red) / Z;     // step 7
+    return block_sum(mass, S.red) / Z;     // alpha: the kept share of the approximate softmax
 }
 
 }  // namespace

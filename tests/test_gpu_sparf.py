@@ -1,12 +1,12 @@
 """GPU parity of the SparF path (Algorithm 1) against its fp64 oracle.
 
-The top-k of steps 1 and 6 is an integer decision taken on floating-point
-scores.  Step 1 compares exact fp16 magnitudes, so the kept components must be
-identical.  Step 6 is taken by the kernel on fp32 scores, the oracle's on fp64
+Both top-k of the algorithm are integer decisions taken on floating-point
+numbers.  The choice of components compares exact fp16 magnitudes, so the kept
+components must be identical.  The choice of rows is taken by the kernel on fp32 scores, the oracle's on fp64
 ones: the two selections may differ only in rows whose score is within the fp32
 rounding of the threshold, so the test checks that the kernel's selection is a
 valid top-k of the oracle's scores up to that rounding, and then compares the
-output with the oracle's steps 7, 10, 11 evaluated on the kernel's selection."""
+output with the oracle's kept mass, attention and blend evaluated on the kernel's selection."""
 import numpy as np
 import pytest
 import torch
@@ -137,8 +137,8 @@ def check_against_oracle(case, out, sel, alpha, r, k, l, pairs=None, rows_of=Non
         got_rows = sel[b, h, :keff].cpu().numpy().astype(np.int64)
         assert (np.diff(got_rows) > 0).all() and got_rows[0] >= 0 and got_rows[-1] < L
         leff = min(l, keff)
-        assert set(range(L - leff, L)) <= set(got_rows)            # step 5
-        # step 6: a valid top-k of the oracle's scores up to fp32 rounding
+        assert set(range(L - leff, L)) <= set(got_rows)            # the most recent rows are kept
+        # the kept rows: a valid top-k of the oracle's scores up to fp32 rounding
         want_rows = set(res["kept_rows"].tolist())
         lg = res["approx_logits"]
         cand = np.array(sorted(want_rows - set(range(L - leff, L))))
@@ -148,7 +148,7 @@ def check_against_oracle(case, out, sel, alpha, r, k, l, pairs=None, rows_of=Non
                 assert lg[t] >= thr - SCORE_EPS, (b, h, t)
             for t in want_rows - set(got_rows.tolist()):
                 assert lg[t] <= thr + SCORE_EPS, (b, h, t)
-        # steps 7, 10, 11 on the kernel's own selection
+        # kept mass, attention and blend on the kernel's own selection
         want_out, want_alpha = sparf.finish_from_selection(q[b, h], Kr, Vr, case.scale, res["approx_weights"],
                                                            got_rows, res["mean_v"])
         assert abs(float(alpha[b, h]) - want_alpha) <= 2e-5

@@ -78,7 +78,7 @@ def test_brute_force_tiny(S, D, r, k, l, seed):
     np.testing.assert_allclose(res["out"], out, rtol=0, atol=1e-14)
 
 
-# ---------------------------------------------------------------- step 4: temperature
+# ---------------------------------------------------------------- temperature of the approximate softmax
 def test_temperature_with_equal_magnitudes_is_sqrt_r():
     """|q| constant: the r kept components carry r/D of the 1-norm, so the
     temperature sqrt(d_h * r/D) equals sqrt(r), the usual one for an r-dim dot."""
@@ -99,7 +99,7 @@ def test_components_are_chosen_by_magnitude_not_sign():
     assert list(sparf.sparf_one(q, K, V, 0.4, 2, 3, 0)["kept_dims"]) == [1, 3]
 
 
-# ---------------------------------------------------------------- steps 5-7: selection
+# ---------------------------------------------------------------- selection and kept mass
 @pytest.mark.parametrize("l", [0, 1, 5, 8])
 def test_most_recent_rows_are_always_selected(l):
     q, K, V = draw(8, S=50, D=8)
@@ -123,7 +123,7 @@ def test_alpha_is_the_selected_mass_and_grows_with_k():
 
 
 def test_two_step_page_load_recovers_exactly_the_selection():
-    """Steps 8-9: fetching whole n-row pages that hold a selected row and then
+    """The algorithm's second page-wise load: fetching whole n-row pages that hold a selected row and then
     filtering inside the page yields the selected rows and nothing else."""
     q, K, V = draw(10, S=100, D=8)
     res = sparf.sparf_one(q, K, V, 0.5, r=3, k=12, l=2)
@@ -136,7 +136,7 @@ def test_two_step_page_load_recovers_exactly_the_selection():
         assert len(pages) <= 12 and len(fetched) >= 12
 
 
-# ---------------------------------------------------------------- step 11: output
+# ---------------------------------------------------------------- output: the blend
 def test_constant_v_passes_through():
     q, K, _ = draw(11)
     V = np.full((60, 16), 0.75, np.float16)
