@@ -369,7 +369,7 @@ size_t instattn_sparf_workspace_size(int batch, int num_q_heads, int head_dim, i
  *               are written per head)
  *   alpha     : device [batch][num_q_heads] fp32 or NULL: receives alpha, the kept share
  * L_b <= 0 gives a zero row (alpha 0).  One launch when max_seq_len <= 8192, or
- * <= 18432 with at least 80 (sequence, query head) pairs, or <= 36864 with 96 to
+ * <= 18432 with at least 96 (sequence, query head) pairs, or <= 36864 with 96 to
  * 256 of them (one block per query head keeps the scores in LDS; 256, 512 or 1024
  * threads), otherwise two to six: column
  * scores; then either one launch in which a block per head selects and gathers

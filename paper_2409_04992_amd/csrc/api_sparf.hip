@@ -112,18 +112,18 @@ SparfPlan plan_sparf(const Options& opt, int batch, int num_q_heads, int num_kv_
     }
     // Rows behind the 256-thread form's limit take the one-launch kernel's 512-thread form
     // (up to 18432 positions; up to 36864 one of 1024 threads) when there are heads enough
-    // for one block each.  Measured at 16K rows: 160 heads 52 us against the pipeline's 63,
-    // 120 heads 48 against 55, 80 heads 46 against 48, 40 heads 44 against 40.
-    // INSTATTN_SPARF_WIDE forces either way.
+    // for one block each.  Step times at 16K rows: 160 heads 48 us against the pipeline's 58,
+    // 80 heads 42 against 41, 40 heads 40 against 33; at 12K rows: 120 heads 37 against 42,
+    // 80 heads 35 against 34.  INSTATTN_SPARF_WIDE forces either way.
     const bool force_wide = opt[kOptSparfWide] == 1, forbid_wide = opt[kOptSparfWide] == 0;
     p.fused_threads = 0;
     if (max_seq_len <= kSparfFusedMaxLen) p.fused_threads = 256;
-    else if (max_seq_len <= kSparfFusedWideMaxLen && !forbid_wide && (force_wide || heads >= 80)) p.fused_threads = 512;
+    else if (max_seq_len <= kSparfFusedWideMaxLen && !forbid_wide && (force_wide || heads >= kSparfWideMinHeads)) p.fused_threads = 512;
     else if (max_seq_len > kSparfFusedWideMaxLen && max_seq_len <= kSparfFusedWidestMaxLen && !forbid_wide &&
-             (force_wide || (heads >= 96 && heads <= 256)))
+             (force_wide || (heads >= kSparfWideMinHeads && heads <= kSparfWidestMaxHeads)))
         p.fused_threads = 1024;   // one block per compute unit: pays when the heads fit in one round of those
-                                  // (measured at 32K rows: 160 heads 94 us against the pipeline's 108;
-                                  // 320 and 640 heads level; 40 heads 74 against 56)
+                                  // (step times at 32K rows: 120 heads 78 us against the pipeline's 81, 240
+                                  // heads 112 against 132; 80 heads 73 against 62, 280 heads 179 against 164)
     if (opt[kOptSparfThreeLaunches] == 1) p.fused_threads = 0;
     p.one_launch = p.fused_threads != 0;
     // The decode's first launch (the one-launch kernel, or the pipeline's score pass) stores

@@ -85,6 +85,10 @@ constexpr int kSparfFusedMaxLen = 8192;   // rows up to this length take the one
 constexpr int kSparfFusedWideMaxLen = 18432;
 // ... and up to this length its form with 1024 threads (one block of 144 KB + 8 KB per compute unit)
 constexpr int kSparfFusedWidestMaxLen = 36864;
+// The wide forms are taken from this many (sequence, query head) pairs on, the 1024-thread form
+// up to one block per compute unit.
+constexpr int kSparfWideMinHeads = 96;
+constexpr int kSparfWidestMaxHeads = 256;
 
 // Floats at the end of the one-launch kernel's dynamic LDS that take the partial
 // sums of the gather (NG row groups of D sums, a maximum and a weight each) ...
