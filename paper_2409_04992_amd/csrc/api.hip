@@ -64,22 +64,31 @@ constexpr int kVersion = 200;          // 0.2.0
 constexpr int kChunkQuantum = 128;     // every kernel's block tile divides this
 constexpr int kMinChunk = 384;
 // Work units wanted per launch and largest unit, per kernel.  The vector-ALU kernel has
-// two forms.  Large launches stage their tiles through an LDS ring, one block per CU:
-// units of about 3000 rows amortise its prologue and epilogue, and some fourteen rounds of
-// them over the 256 compute units still balance (8 x 40 heads x 32K: 2944 rows 88.2 % of
-// peak, 1408 rows 87.1 %, 3456 rows 87.9 %, 3712 rows 87.0 %; multiples 17 and 19 of 128
-// rows lose 3 to 6 % there: units that walk the HBM channels in step).  Small launches
-// (below kRingMinRows rows in all, an upper bound: 0.5 GB at head_dim 128) hold two tiles
-// in registers, five blocks per CU, and take shorter units, so that 1280 block slots hide
+// two forms.  Large launches stage their tiles through an LDS ring, one block per CU, in
+// long units that amortise its prologue and epilogue (below).  Small launches (below
+// kRingMinRows rows in all, an upper bound: 0.5 GB at head_dim 128) hold two tiles in
+// registers, five blocks per CU, and take shorter units, so that 1280 block slots hide
 // each other's start and end (4 x 40 heads x 1.5K: 24.5 us against 27.3 us through the
-// ring); so do launches whose units come out shorter than kRingMinChunk rows (32 x 40 heads x
-// 1.5K as whole sequences: 83.0 % of peak against 81.3 %).  The MFMA kernel runs 2 blocks per CU and pays more per unit (prologue,
-// cross-wave epilogue), so it gets fewer, larger units: about three per four compute
-// units measured best from 16 x 16K down to 128 x 1K rows in all.
-constexpr int kTargetUnitsMha = 3584, kMaxChunkMha = 2944;
+// ring); so do launches of sequences shorter than kRingMinChunk rows (32 x 40 heads x 1.5K
+// as whole sequences: 83.0 % of peak against 81.3 %).  The MFMA kernel runs 2 blocks per CU
+// and pays more per unit (prologue, cross-wave epilogue), so it gets fewer, larger units:
+// about three per four compute units measured best from 16 x 16K down to 128 x 1K rows in all.
 constexpr int kTargetUnitsMhaSmall = 4096, kMaxChunkMhaSmall = 1408;
+// The ring form of the vector-ALU kernel (one block per compute unit) takes launches of 2^20
+// rows or more in units of 2048 rows or more.  Its units are 2944 or 5504 rows long: lengths
+// whose byte size, taken modulo 512 KB, lies near the middle of that period - units of a
+// stream that start nearly a multiple of 512 KB apart (2176, 4224, 8320 rows of 256 bytes)
+// walk the HBM channels in step and lose 3 to 6 % (measured on every shape tried).  Between
+// the two the launch's rounds decide (units over 256 compute units, rounded up, times the
+// unit length); the longer unit must win by 3 % (8 x 40 heads x 32K: 88.5 % of peak with
+// 2944, 87.7 % with 5504, equal rounds; 6 x 40 x 32K: 86.9 against 87.3 %, 1 x 40 x 128K:
+// 86.6 against 87.8 %, 24 x 8 x 16K: 84.0 against 77.8 %, where 5504 leaves a quarter of the
+// last round empty).
 constexpr long kRingMinRows = 1L << 20;
 constexpr int kRingMinChunk = 2048;
+constexpr int kRingChunk = 2944, kRingLongChunk = 5504;
+constexpr long kRingMinFill = 88;      // per cent of the rounds' rows that the launch must hold
+constexpr int kComputeUnits = 256;
 constexpr int kTargetUnitsGqa = 192, kMaxChunkGqa = 5504;
 constexpr int kSingleSplitStreams = 512, kSingleSplitMaxLen = 8192 + kChunkQuantum;
 constexpr int kResidentUnits = 1280;   // five blocks of the vector-ALU kernel on each of 256 compute units
@@ -141,10 +150,34 @@ Plan make_plan(const Options& opt, int batch, int num_q_heads, int num_kv_heads,
         chunk = unit_length(kTargetUnitsGqa, kMaxChunkGqa);
     } else {
         // the ring form wants a large launch of long units; everything else takes the register form
-        chunk = unit_length(kTargetUnitsMha, kMaxChunkMha);
-        staged = opt[kOptMhaRing] >= 0 ? opt[kOptMhaRing] == 1
-                                       : (long)max_seq_len * streams >= kRingMinRows && chunk >= kRingMinChunk;
-        if (!staged) chunk = unit_length(kTargetUnitsMhaSmall, kMaxChunkMhaSmall);
+        chunk = unit_length(kTargetUnitsMhaSmall, kMaxChunkMhaSmall);
+        const bool whole_sequences = streams >= kSingleSplitStreams && max_seq_len <= kSingleSplitMaxLen;
+        const bool large = (long)max_seq_len * streams >= kRingMinRows;
+        if (whole_sequences) {
+            staged = large && chunk >= kRingMinChunk;
+        } else {
+            auto rounds_times_length = [&](long c) {
+                const long units = streams * (((long)max_seq_len + c - 1) / c);
+                return (units + kComputeUnits - 1) / kComputeUnits * c;
+            };
+            long ring_chunk = kRingChunk;
+            if (100 * rounds_times_length(kRingLongChunk) <= 97 * rounds_times_length(ring_chunk)) ring_chunk = kRingLongChunk;
+            // sequences of at most the longer unit (+ a tile): one unit each, and no merge (12 x 40
+            // heads x 3K: whole step 82.1 % of peak against 78.9 % in the register form's short units)
+            const long whole_rows = ((long)max_seq_len + kChunkQuantum - 1) / kChunkQuantum * kChunkQuantum;
+            if (whole_rows <= kRingLongChunk + kChunkQuantum &&
+                100 * rounds_times_length(whole_rows) <= 97 * rounds_times_length(ring_chunk))
+                ring_chunk = whole_rows;
+            // ... and the rounds must come out nearly full: with one block per compute unit a last
+            // round of few units, or of short ends of sequences, idles most of the chip (3 x 8 heads x
+            // 64K: 552 units of 2944 rows fill 72 % of three rounds and run at 72.5 % of peak, the
+            // register form's 4104 short units at 82.8 %)
+            const bool full_rounds =
+                100 * (long)max_seq_len * streams >= kRingMinFill * rounds_times_length(ring_chunk) * kComputeUnits;
+            staged = large && max_seq_len >= kRingMinChunk && full_rounds;
+            if (opt[kOptMhaRing] == 1 || (staged && opt[kOptMhaRing] != 0)) chunk = ring_chunk;
+        }
+        if (opt[kOptMhaRing] >= 0) staged = opt[kOptMhaRing] == 1;
     }
     if (opt[kOptChunk] > 0)
         chunk = ((long)opt[kOptChunk] + kChunkQuantum - 1) / kChunkQuantum * kChunkQuantum;

@@ -145,6 +145,34 @@ def test_plan_covers_the_sequence_and_fills_the_chip(shape):
     assert ws >= batch * hq * splits * (dim + 1) * 4 and ws % 256 == 0
 
 
+def test_plan_units_of_the_ring_form(options):
+    """Large launches of the vector-ALU kernel: units of 2944 or 5504 rows (or whole sequences up to
+    that length), whichever gives the fewest rounds over 256 compute units times the unit length
+    (the longer must win by 3 %), and only when those rounds come out at least 88 % full; else the
+    register form's short units."""
+    plan = lambda b, h, L: B.decode_plan(b, h, h, 128, L)
+    assert plan(8, 40, 32769) == (2944, 12)          # 15 rounds of 2944 against 8 of 5504: level, the shorter
+    assert plan(6, 40, 32769) == (5504, 6)           # 12 rounds of 2944 against 6 of 5504
+    assert plan(1, 40, 131073) == (5504, 24)
+    assert plan(64, 40, 16385) == (5504, 3)
+    assert plan(32, 8, 16385) == (5504, 3)           # 768 units: three full rounds
+    assert plan(2, 40, 16385) == (5504, 3)           # 240 units: one round
+    assert plan(12, 40, 3073) == (3200, 1)           # 480 whole sequences: two rounds, no merge
+    assert plan(1, 40, 1 << 20) == (2944, 357)
+    # rounds that would stay partly empty: the register form (1280 block slots) in short units
+    assert plan(24, 8, 16385) == (896, 19)           # 1152 units of 2944 rows fill 83 % of five rounds
+    assert plan(3, 8, 65537) == (384, 171)           # 552 units: 72 % of three rounds
+    assert plan(5, 40, 8193) == (384, 22)
+    assert plan(10, 40, 6145) == (640, 10)           # a third unit of 257 rows per sequence
+    # below 2^20 rows in all, or sequences shorter than 2048 rows: the register form
+    assert plan(1, 40, 16385) == (384, 43) and plan(64, 8, 1537)[0] < 2048
+    # forced either way
+    options.setenv("INSTATTN_MHA_RING", 1)
+    assert plan(3, 8, 65537) == (2944, 23) and plan(1, 4, 4000) == (2944, 2)
+    options.setenv("INSTATTN_MHA_RING", 0)
+    assert plan(6, 40, 32769)[0] <= 1408
+
+
 def test_plan_rejects_bad_shapes():
     assert B.decode_workspace_size(0, 4, 4, 64, 100) == 0
     assert B.decode_workspace_size(1, 4, 4, 80, 100) == 0
@@ -218,7 +246,7 @@ def test_decode_launches(options):
     for v in (None, 0, 1):
         options.setenv("INSTATTN_COMPACT", -1 if v is None else v)
         sizes.add(B.decode_workspace_size(64, 40, 40, 128, 16385))
-    assert len(sizes) == 1 and sizes.pop() >= 64 * 40 * 6 * 129 * 4 + 64 * 6 * 4
+    assert len(sizes) == 1 and sizes.pop() >= 64 * 40 * 3 * 129 * 4 + 64 * 3 * 4
     L = B.lib()
     assert L.instattn_decode_launches(8, 40, 40, 128, 32769, 7, 0, (ctypes.c_int32 * 4)()) == B.ERR_INVALID_ARG
     assert L.instattn_decode_launches(8, 40, 40, 128, 32769, 0, 0, None) == B.ERR_INVALID_ARG
