@@ -90,6 +90,7 @@ constexpr int kRingChunk = 2944, kRingLongChunk = 5504;
 constexpr long kRingMinFill = 88;      // per cent of the rounds' rows that the launch must hold
 constexpr int kComputeUnits = 256;
 constexpr int kTargetUnitsGqa = 192, kMaxChunkGqa = 5504;
+constexpr int kLongChunkGqa = 8832, kSlotsGqa = 512;   // both sizes, modulo 512 KB, sit near the middle (see the ring form's units)
 constexpr int kSingleSplitStreams = 512, kSingleSplitMaxLen = 8192 + kChunkQuantum;
 constexpr int kResidentUnits = 1280;   // five blocks of the vector-ALU kernel on each of 256 compute units
 // The unit list of a paged cache: rows (an upper bound: max_seq_len x KV streams) from
@@ -148,6 +149,18 @@ Plan make_plan(const Options& opt, int batch, int num_q_heads, int num_kv_heads,
     bool staged = false;
     if (group > 1) {
         chunk = unit_length(kTargetUnitsGqa, kMaxChunkGqa);
+        // Long sequences in a large launch: units of 8832 rows when they save rounds over the
+        // kernel's 512 block slots (8 x 8 KV heads x 64K: 512 units in one round, 85.2 % of peak,
+        // against 768 units of 5504 rows in a round and a half, 83.9 %; 16 x 8 x 32K 85.0 against
+        // 83.7 %).  Not for sequences of fewer than four such units: 32 x 8 x 16K is level
+        // either way, and more, shorter units spread a ragged batch better.
+        if (chunk == kMaxChunkGqa && max_seq_len > 3 * kLongChunkGqa) {
+            auto rounds_times_length = [&](long c) {
+                const long units = streams * (((long)max_seq_len + c - 1) / c);
+                return (units + kSlotsGqa - 1) / kSlotsGqa * c;
+            };
+            if (100 * rounds_times_length(kLongChunkGqa) <= 97 * rounds_times_length(kMaxChunkGqa)) chunk = kLongChunkGqa;
+        }
     } else {
         // the ring form wants a large launch of long units; everything else takes the register form
         chunk = unit_length(kTargetUnitsMhaSmall, kMaxChunkMhaSmall);

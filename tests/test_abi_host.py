@@ -173,6 +173,18 @@ def test_plan_units_of_the_ring_form(options):
     assert plan(6, 40, 32769)[0] <= 1408
 
 
+def test_plan_units_of_the_grouped_query_kernel():
+    """About three units per four compute units, at most 5504 rows; sequences of more than three
+    units of 8832 rows take that length when it saves rounds over the kernel's 512 block slots."""
+    plan = lambda b, L: B.decode_plan(b, 64, 8, 128, L)
+    assert plan(32, 16385) == (5504, 3)              # the 80-layer configuration: 768 units
+    assert plan(8, 65537) == (8832, 8)               # 512 units in one round instead of 768 in one and a half
+    assert plan(4, 131073) == (8832, 15) and plan(16, 32769) == (8832, 4)
+    assert plan(64, 32769) == (5504, 6)              # 3072 units: six full rounds either way
+    assert plan(16, 26496) == (5504, 5)              # three units of 8832 rows: too few
+    assert plan(2, 32769) == (2688, 13)              # few streams: short units for every compute unit
+
+
 def test_plan_rejects_bad_shapes():
     assert B.decode_workspace_size(0, 4, 4, 64, 100) == 0
     assert B.decode_workspace_size(1, 4, 4, 80, 100) == 0
