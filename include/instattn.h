@@ -104,9 +104,9 @@ const char* instattn_status_string(int status);
  *                                   that hold rows (one small launch in front; the host's choice for
  *                                   large paged caches), or never does
  *   "INSTATTN_MHA_RING"             1 / 0: the vector-ALU split pass stages its tiles through its LDS ring
- *                                   (the host's choice for launches of 2^20 rows or more in units of 2048
- *                                   rows or more), or holds two tiles in registers; the unit length
- *                                   follows the form
+ *                                   (the host's choice for launches of 2^20 rows or more of sequences of
+ *                                   2048 rows or more whose units fill their rounds over the compute
+ *                                   units), or holds two tiles in registers; the unit length follows the form
  *   "INSTATTN_SPARF_DISTRIBUTED"    1 / 0: SparF selection spread over one block per 8192 scores, or never
  *   "INSTATTN_SPARF_THREE_LAUNCHES" 1: SparF never takes its one-launch kernel
  *   "INSTATTN_SPARF_WIDE"           1 / 0: the one-launch kernel's 512/1024-thread forms whenever they fit, or never
