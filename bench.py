@@ -226,6 +226,25 @@ def time_sparf(cases, descs, rkl, steps, warmup, kt_page, two_calls=False, kt_ca
         return (time.perf_counter() - t0) / steps
 
     t_sparf, t_dense = timed(sparf_step), timed(dense_step)
+    # What the memory system gives on the addresses of the score pass: a bare read of r of
+    # the D columns of every head over the same copies (contiguous copies of equal lengths only).
+    column_read = None
+    if kt_page == 0 and len(set(lens)) == 1 and lens[0] >= 16:
+        sink = torch.zeros(4096, dtype=torch.int32, device=dev)
+        positions = lens[0] // 8 * 8
+        ev = []
+        for i in range(12):
+            a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a0.record()
+            B.probe_read_columns(auxs[i % R].tensors[0], r, positions, sink)
+            a1.record()
+            ev.append((a0, a1))
+        torch.cuda.synchronize()
+        ms = sorted(x.elapsed_time(y) for x, y in ev[2:])
+        col_bytes = wl.batch * wl.num_kv_heads * r * positions * 2
+        column_read = {"GBps": col_bytes / (ms[len(ms) // 2] * 1e-3) / 1e9, "bytes": col_bytes,
+                       "us": ms[len(ms) // 2] * 1e3,
+                       "what": "bare read of r of the D columns of every KV head's component-major copy (no arithmetic)"}
     plan = B.sparf_plan(wl.batch, Hq, wl.num_kv_heads, D, max_len, k, with_append=not two_calls)
     default_page = kt_page == (256 if wl.paged else 0)
     return {
@@ -240,6 +259,7 @@ def time_sparf(cases, descs, rkl, steps, warmup, kt_page, two_calls=False, kt_ca
         "dense_ms_per_step": t_dense * 1e3, "speedup_over_dense_step": t_dense / t_sparf,
         "bytes_read_algorithm1": sparf_bytes, "bytes_read_dense": dense_bytes,
         "compression": sparf_bytes / dense_bytes, "score_bytes_written_and_read": score_bytes,
+        "column_read_probe": column_read,
         # the whole step (one or several launches) against the bytes Algorithm 1 must read
         "roofline": {"bound": "hbm", "achieved": sparf_bytes / t_sparf / 1e9, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": sparf_bytes / t_sparf / 1e9 / HBM_PEAK_GBPS,
@@ -556,7 +576,7 @@ def main():
             e = time_sparf(cases, descs, rkl, s_steps, s_warmup, 256 if cases[0].wl.paged else 0)
             sparf[name] = {k: e[k] for k in ("value", "unit", "steps", "warmup", "ms_per_step", "dense_ms_per_step",
                                              "speedup_over_dense_step", "bytes_read_algorithm1", "compression",
-                                             "config", "roofline")}
+                                             "column_read_probe", "config", "roofline")}
             del cases, descs, e
             release()
         res["per_config"] = per_config

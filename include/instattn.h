@@ -411,9 +411,18 @@ int instattn_sparf_append_decode(const void* q, const void* k_new, const void* v
  * (a multiple of 16) from src with 128-bit loads and folds them into 4 bytes per
  * workgroup written to sink (device, >= 16 KiB): the read ceiling a streaming
  * kernel can reach.  probe_copy copies `bytes` from src to dst (device, disjoint):
- * a kernel of known traffic for scaling hardware counters.
+ * a kernel of known traffic for scaling hardware counters.  probe_read_columns reads
+ * what the SparF score pass (Algorithm 1, the approximate scores) reads of a contiguous
+ * component-major copy and nothing else: of each of `rows` rows (row n at
+ * base + n * row_stride bytes, 16-byte aligned) r of its `dims` columns (column d
+ * d * col_stride bytes further on), the first `positions` fp16 (a multiple of 8) of
+ * each; the columns are a fixed spread, the same for every call.  It gives the rate the
+ * memory system reaches on those addresses, the ceiling of that pass.  sink as for
+ * probe_read.  positions <= 65535 x 2048 (INSTATTN_ERR_UNSUPPORTED beyond).
  */
 int instattn_probe_read(const void* src, size_t bytes, void* sink, void* stream);
+int instattn_probe_read_columns(const void* base, size_t row_stride, size_t col_stride, int rows, int dims, int r,
+                                int positions, void* sink, void* stream);
 int instattn_probe_copy(const void* src, void* dst, size_t bytes, void* stream);
 
 #ifdef __cplusplus

@@ -115,6 +115,8 @@ def lib() -> ctypes.CDLL:
         L.instattn_probe_read.argtypes = [vp, sz, vp, vp]
         L.instattn_probe_copy.restype = i
         L.instattn_probe_copy.argtypes = [vp, vp, sz, vp]
+        L.instattn_probe_read_columns.restype = i
+        L.instattn_probe_read_columns.argtypes = [vp, sz, sz, i, i, i, i, vp, vp]
         _lib = L
     return _lib
 
@@ -299,6 +301,14 @@ def alloc_workspace(batch: int, num_q_heads: int, num_kv_heads: int, head_dim: i
 def probe_read(src: torch.Tensor, sink: torch.Tensor, stream=None) -> None:
     _check(lib().instattn_probe_read(_p(src), src.numel() * src.element_size(), _p(sink),
                                      _stream(stream)), "instattn_probe_read")
+
+
+def probe_read_columns(kt: torch.Tensor, r: int, positions: int, sink: torch.Tensor, stream=None) -> None:
+    """kt: contiguous component-major copy [B, Hkv, D, capacity] fp16."""
+    Bn, Hkv, D, cap = kt.shape
+    assert kt.dtype == torch.float16 and kt.is_contiguous()
+    _check(lib().instattn_probe_read_columns(_p(kt), D * cap * 2, cap * 2, Bn * Hkv, D, int(r), int(positions),
+                                             _p(sink), _stream(stream)), "instattn_probe_read_columns")
 
 
 def probe_copy(src: torch.Tensor, dst: torch.Tensor, stream=None) -> None:

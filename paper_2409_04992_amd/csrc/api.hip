@@ -635,6 +635,18 @@ int instattn_probe_read(const void* src, size_t bytes, void* sink, void* stream)
     return status_of(launch_probe_read(src, bytes, sink, (hipStream_t)stream));
 }
 
+int instattn_probe_read_columns(const void* base, size_t row_stride, size_t col_stride, int rows, int dims, int r,
+                                int positions, void* sink, void* stream)
+{
+    if (!base || !sink || !aligned16(base) || row_stride % 16 || col_stride % 16) return INSTATTN_ERR_INVALID_ARG;
+    if (rows < 1 || dims < 1 || r < 1 || r > dims) return INSTATTN_ERR_INVALID_ARG;
+    if (positions < 8 || positions % 8 || (size_t)positions * 2 > col_stride || (size_t)dims * col_stride > row_stride)
+        return INSTATTN_ERR_INVALID_ARG;
+    if ((positions + 2047) / 2048 > 65535) return INSTATTN_ERR_UNSUPPORTED;
+    return status_of(launch_probe_columns(base, row_stride, col_stride, rows, dims, r, positions, sink,
+                                          (hipStream_t)stream));
+}
+
 int instattn_probe_copy(const void* src, void* dst, size_t bytes, void* stream)
 {
     if (!src || !dst || bytes == 0 || bytes % 16 || !aligned16(src) || !aligned16(dst))

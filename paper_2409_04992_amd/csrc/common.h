@@ -111,6 +111,8 @@ hipError_t launch_kv_append(const AppendArgs& a, hipStream_t stream);
 hipError_t launch_kv_write(const WriteArgs& a, hipStream_t stream);
 hipError_t launch_probe_read(const void* src, size_t bytes, void* sink, hipStream_t stream);
 hipError_t launch_probe_copy(const void* src, void* dst, size_t bytes, hipStream_t stream);
+hipError_t launch_probe_columns(const void* base, size_t row_stride, size_t col_stride, int rows, int dims, int r,
+                                int positions, void* sink, hipStream_t stream);
 
 __device__ __forceinline__ int clamp_len(int L, int max_len) {
     L = L < 0 ? 0 : L;

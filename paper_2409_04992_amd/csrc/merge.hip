@@ -257,6 +257,56 @@ __global__ __launch_bounds__(256) void probe_copy_kernel(const u32x4* src, u32x4
         dst[i] = src[i];
 }
 
+// A bare read of the addresses the SparF score pass reads: r of the `dims` columns of every
+// row of a component-major array (row n at n * row_stride, column d of it d * col_stride
+// further on, strides in bytes), the first `positions` fp16 of each (a multiple of 8).  A block takes a row
+// and a unit of 2048 positions; a lane reads 16 bytes per column, 8 columns per step, the
+// next step's loads in flight while one is folded: the score pass without its arithmetic,
+// its ranking and its stores.  Which columns: (7 n + 5 j) mod dims, j < r - spread over the
+// row like the columns a query picks.
+__global__ __launch_bounds__(256) void probe_columns_kernel(const char* base, size_t row_stride, size_t col_stride,
+                                                            int dims, int r, int positions, uint32_t* sink)
+{
+    constexpr int CG = 8, UNIT = 2048;
+    const int n = blockIdx.x, tid = threadIdx.x;
+    const int t = min((int)blockIdx.y * UNIT + tid * 8, positions - 8);
+    const char* p = base + (size_t)n * row_stride + (size_t)t * 2;
+    const int groups = (r + CG - 1) / CG;
+    auto load = [&](u32x4 (&T)[CG], int g) {
+#pragma unroll
+        for (int j = 0; j < CG; ++j) {
+            const int col = (7 * n + 5 * min(g * CG + j, r - 1)) % dims;
+            T[j] = __builtin_nontemporal_load((const u32x4*)(p + (size_t)col * col_stride));
+        }
+    };
+    uint32_t x = 0;
+    u32x4 A[CG], B[CG];
+    load(A, 0);
+    for (int g = 0; g < groups; g += 2) {
+        if (g + 1 < groups) load(B, g + 1);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < CG; ++j) x ^= A[j].x ^ A[j].y ^ A[j].z ^ A[j].w;
+        if (g + 2 < groups) load(A, g + 2);
+        __builtin_amdgcn_sched_barrier(0);
+        if (g + 1 < groups) {
+#pragma unroll
+            for (int j = 0; j < CG; ++j) x ^= B[j].x ^ B[j].y ^ B[j].z ^ B[j].w;
+        }
+    }
+    for (int s = 32; s > 0; s >>= 1) x ^= __shfl_xor(x, s);
+    if ((tid & 63) == 0) atomicXor(&sink[(blockIdx.x + blockIdx.y) % kProbeBlocks], x);
+}
+
+hipError_t launch_probe_columns(const void* base, size_t row_stride, size_t col_stride, int rows, int dims, int r,
+                                int positions, void* sink, hipStream_t stream)
+{
+    const dim3 grid((unsigned)rows, (unsigned)((positions + 2047) / 2048));
+    hipLaunchKernelGGL(probe_columns_kernel, grid, dim3(256), 0, stream, (const char*)base, row_stride, col_stride,
+                       dims, r, positions, (uint32_t*)sink);
+    return hipGetLastError();
+}
+
 hipError_t launch_probe_read(const void* src, size_t bytes, void* sink, hipStream_t stream)
 {
     const size_t nseg = (bytes / 16 + kProbeSeg16 - 1) / kProbeSeg16;

@@ -120,6 +120,7 @@ hipError_t launch_kv_append(const AppendArgs&, hipStream_t) { ++g_launches; retu
 hipError_t launch_kv_write(const WriteArgs&, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_probe_read(const void*, size_t, void*, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_probe_copy(const void*, void*, size_t, hipStream_t) { ++g_launches; return hipSuccess; }
+hipError_t launch_probe_columns(const void*, size_t, size_t, int, int, int, int, void*, hipStream_t) { ++g_launches; return hipSuccess; }
 
 hipError_t launch_sparf_build(const SparfArgs& a, hipStream_t)
 {

@@ -28,7 +28,7 @@ def test_library_exports_every_declared_symbol():
             "instattn_sparf_build_workspace_size",
             "instattn_sparf_decode", "instattn_sparf_workspace_size", "instattn_sparf_append_decode",
             "instattn_sparf_plan",
-            "instattn_probe_copy"} <= set(names)
+            "instattn_probe_copy", "instattn_probe_read_columns"} <= set(names)
     lib = B.lib()
     for n in names:
         assert getattr(lib, n) is not None
@@ -120,6 +120,12 @@ def test_probe_rejects():
     assert L.instattn_probe_read(FAKE, 1000, FAKE, None) == B.ERR_INVALID_ARG
     assert L.instattn_probe_copy(FAKE, None, 1024, None) == B.ERR_INVALID_ARG
     assert L.instattn_probe_copy(FAKE, FAKE, 0, None) == B.ERR_INVALID_ARG
+    cols = lambda *a: L.instattn_probe_read_columns(*a)
+    assert cols(None, 128 * 4112 * 2, 4112 * 2, 640, 128, 16, 4096, FAKE, None) == B.ERR_INVALID_ARG
+    assert cols(FAKE, 128 * 4112 * 2, 4112 * 2, 640, 128, 129, 4096, FAKE, None) == B.ERR_INVALID_ARG   # r > dims
+    assert cols(FAKE, 128 * 4112 * 2, 4112 * 2, 640, 128, 16, 4100, FAKE, None) == B.ERR_INVALID_ARG    # not a multiple of 8
+    assert cols(FAKE, 128 * 4112 * 2, 4112 * 2, 640, 128, 16, 4120, FAKE, None) == B.ERR_INVALID_ARG    # behind the column
+    assert cols(FAKE, 100 * 4112 * 2, 4112 * 2, 640, 128, 16, 4096, FAKE, None) == B.ERR_INVALID_ARG    # columns overlap rows
 
 
 # ------------------------------------------------------------------ split plan (host arithmetic)

@@ -744,6 +744,21 @@ def test_sparf_paged_pool_with_k_and_v_of_a_page_adjacent(seq_len, k):
     sparf_step(wl, 16, k, 16, torch.float16, kt_page=256, fused_append=True)
 
 
+def test_probe_read_columns_runs_inside_the_copy():
+    """The measurement aid reads r columns of every row of a component-major copy: the
+    neighbours of the copy (NaN-filled guard rows in front and behind) stay what they are
+    and the call returns; its argument checks run on the host (tests/test_abi_host.py)."""
+    for D, cap, positions, r in [(64, 264, 256, 8), (128, 4112, 4096, 16), (128, 2056, 8, 128), (64, 40000, 39992, 3)]:
+        whole = torch.full((2 + 2, 3, D, cap), float("nan"), dtype=torch.float16, device=DEV)
+        kt = whole[1:3]
+        kt.normal_()
+        before = whole.clone()
+        sink = torch.zeros(4096, dtype=torch.int32, device=DEV)
+        B.probe_read_columns(kt, r, positions, sink)
+        torch.cuda.synchronize()
+        assert torch.equal(whole.view(torch.int16), before.view(torch.int16))
+
+
 def test_sparf_is_deterministic():
     wl = W.Workload("sparf_det", 2, 4, 4, 128, 3000, seed=406)
     case, desc, aux, kt, vsum, _ = setup(wl)
