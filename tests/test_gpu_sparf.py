@@ -250,6 +250,34 @@ def test_sparf_append_decode_equals_the_two_calls():
                            y.view(torch.int32) if y.dtype == torch.float32 else y.view(torch.int16))
 
 
+@pytest.mark.parametrize("three_launches", [False, True])
+def test_sparf_new_token_alone_in_its_unit(options, three_launches):
+    """Rows of a multiple of 2048 cached positions: the appended token is the only position of
+    the row's last unit of the score pass (and of a step of the one-launch kernel's column
+    pass).  Same bits as appending first and decoding after, whatever the form (short rows are
+    sent through the pipeline by the switch), and the oracle's result."""
+    if three_launches:
+        options.setenv("INSTATTN_SPARF_THREE_LAUNCHES", "1")
+    lens = [2049, 4097, 10241, 2048, 1, 12289, 6145, 2050]
+    wl = W.Workload("sparf_lone", len(lens), 3, 3, 128, 12288, seq_len_min=1, seed=427)
+    res = []
+    for fused in (False, True):
+        case = W.make_case(wl, DEV, poison=True, lens=lens)
+        Bn, Hkv, D, cap = wl.batch, wl.num_kv_heads, wl.head_dim, case.capacity
+        vsum = torch.zeros(Bn, Hkv, D, dtype=torch.float32, device=DEV)
+        kt = torch.full((Bn, Hkv, D, (cap + 7) // 8 * 8), float("nan"), dtype=torch.float16, device=DEV)
+        desc, aux = B.kv_desc(case.k_cache, case.v_cache), B.sparf_aux(kt, vsum)
+        B.sparf_build(desc, aux, (case.seq_lens - 1).contiguous(), Hkv, D)
+        if not fused:
+            B.sparf_append(desc, aux, case.k_new, case.v_new, case.seq_lens)
+        out = run_decode(case, desc, aux, 16, 300, 16, torch.float32, max_len=12289, fused_append=fused)
+        res.append(out + (kt.clone(), vsum.clone(), case.k_cache.clone(), case.v_cache.clone()))
+    for x, y in zip(*res):
+        assert torch.equal(x.view(torch.int32) if x.dtype == torch.float32 else x.view(torch.int16),
+                           y.view(torch.int32) if y.dtype == torch.float32 else y.view(torch.int16))
+    check_against_oracle(case, *res[1][:3], 16, 300, 16)
+
+
 @pytest.mark.parametrize("seq_len,k", [(20000, 1300), (8192, 100), (32767, 3000), (32768, 600), (40000, 2500),
                                        (65534, 700), (70000, 4400), (9000, 20000)])
 @pytest.mark.parametrize("distributed", ["0", "1"])
